@@ -1,0 +1,190 @@
+/*
+ * petals_span.h - C ABI of the MI355X block-span library.
+ *
+ * One Petals server holds a span of consecutive BLOOM-style Transformer blocks
+ * in GPU memory with 8-bit weights, keeps attention keys/values per client
+ * session, and runs hidden states through all of its blocks (Petals paper,
+ * Section 2.1 "Inference of billion-scale models"; Section 3.1 "Large model
+ * inference on consumer GPUs").  This header is the whole boundary of that
+ * server-side computation on one GPU.
+ *
+ * Conventions that hold for every call:
+ *  - "dev" pointers are HIP device pointers on the current device; "host"
+ *    pointers are ordinary host memory.  fp16 tensors are IEEE binary16 stored
+ *    as 16-bit words, row-major, innermost dimension contiguous.
+ *  - The CALLER owns all device memory (weight arena, workspace, KV memory,
+ *    hidden states).  The library owns only host-side handles and never
+ *    allocates or frees device memory.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls enqueue work on it and return without synchronizing; every buffer
+ *    must stay alive and unmodified until the stream has passed that work.
+ *    One span (and its workspace) may be used by one stream at a time.
+ *  - Return value: 0 on success, a negative PETALS_ERR_* otherwise; on error no
+ *    session length changes.  petals_last_error() gives a thread-local text.
+ *  - Non-finite inputs: behaviour unspecified.
+ */
+#ifndef PETALS_SPAN_H
+#define PETALS_SPAN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PETALS_OK                0
+#define PETALS_ERR_INVALID_ARG  (-1)  /* null pointer, bad shape, duplicate session */
+#define PETALS_ERR_CAPACITY     (-2)  /* KV cache full, too many rows or sessions in one call */
+#define PETALS_ERR_UNSUPPORTED  (-3)  /* shape outside what the kernels cover */
+#define PETALS_ERR_STATE        (-4)  /* a block of the span has not been loaded */
+#define PETALS_ERR_HIP          (-5)  /* a HIP call failed; text in petals_last_error() */
+
+#define PETALS_MAX_SESSIONS_PER_CALL 64
+
+#define PETALS_EPILOGUE_NONE     0
+#define PETALS_EPILOGUE_GELU     1
+#define PETALS_EPILOGUE_RESIDUAL 2
+
+typedef struct petals_span petals_span;       /* opaque host-side handle */
+typedef struct petals_session petals_session; /* opaque host-side handle */
+
+/*
+ * Shape of a span.  Supported: hidden % 64 == 0, ffn % 64 == 0,
+ * head_dim = hidden / n_heads in {16, 32, 64, 128}, ffn <= 65536 (keeps the
+ * int32 accumulators exact: 127*127*65536 < 2^31).
+ */
+typedef struct {
+    int32_t n_blocks;
+    int32_t hidden;             /* H */
+    int32_t n_heads;
+    int32_t ffn;                /* F, MLP width (4*H in BLOOM) */
+    float ln_eps;               /* 1e-5 in BLOOM */
+    float outlier_threshold;    /* 6.0; +INF: pure int8; 0: every column on the fp16 path */
+    int32_t max_rows_per_call;  /* upper bound on sessions * new tokens in one call */
+} petals_span_config;
+
+/*
+ * Parameters of one block, all DEVICE pointers.  Weights are fp32 masters in
+ * the layout y = x W^T (row n of W produces output feature n); they are read
+ * once by petals_span_load_block and may be freed after the stream passes it.
+ * The fused QKV projection orders its 3H output rows per head: row
+ * h*3d + p*d + j is component j of (p = 0 query, 1 key, 2 value) of head h.
+ */
+typedef struct {
+    const float *w_qkv;   /* [3H, H] */
+    const float *w_dense; /* [H, H]  */
+    const float *w_up;    /* [F, H]  */
+    const float *w_down;  /* [H, F]  */
+    const uint16_t *b_qkv, *b_dense, *b_up, *b_down; /* fp16 [3H], [H], [F], [H] */
+    const uint16_t *ln1_g, *ln1_b, *ln2_g, *ln2_b;   /* fp16 [H] each */
+} petals_block_params;
+
+/* Sizes the caller must allocate (device bytes).  256-byte alignment is required. */
+int petals_span_weight_bytes(const petals_span_config *cfg, size_t *bytes);
+int petals_span_workspace_bytes(const petals_span_config *cfg, size_t *bytes);
+/* Device bytes of one session's key/value memory for `max_len` cached tokens. */
+int petals_span_kv_bytes(const petals_span_config *cfg, int32_t max_len, size_t *bytes);
+
+/*
+ * Create a span over caller-owned device memory (Section 2.1: a server holds
+ * consecutive blocks sized to its GPU memory).  No device work is enqueued.
+ */
+int petals_span_create(const petals_span_config *cfg, void *dev_weight_mem,
+                       void *dev_workspace, petals_span **out);
+
+/*
+ * Quantize one block's fp32 weights to int8 with one scale per output row
+ * (Section 3.1 "Compressing model weights": weights are kept in 8 bits),
+ * store them in the streaming tile order the kernels read, and copy the fp16
+ * biases and LayerNorm parameters into the weight arena.
+ * code = clamp(rint(w * (127 / rowmax)), -127, 127), fp32, ties to even.
+ */
+int petals_span_load_block(petals_span *span, int32_t block,
+                           const petals_block_params *params, void *stream);
+
+/* Frees the host handle only.  Sessions of the span must be closed first. */
+int petals_span_destroy(petals_span *span);
+
+/*
+ * Open a session: per-client attention key/value memory kept while the client
+ * generates (Section 2.1: "servers store attention keys and values from past
+ * client inputs").  dev_kv_mem has petals_span_kv_bytes(cfg, max_len) bytes,
+ * laid out [block][key|value][head][max_len][head_dim] fp16.  Length starts at 0.
+ */
+int petals_session_open(petals_span *span, void *dev_kv_mem, int32_t max_len,
+                        petals_session **out);
+int petals_session_length(const petals_session *session, int32_t *len);
+int petals_session_close(petals_session *session);
+
+/*
+ * Run T new tokens of each of B sessions through all blocks of the span
+ * (Section 2.1: the server "runs inputs through all blocks and returns final
+ * representations"; Section 3.2: re-feeding stored inputs to a replacement
+ * server rebuilds its keys and values).
+ *   hidden_in, hidden_out: dev fp16 [B, T, H]; they may not alias.
+ * Per block: LayerNorm, fused QKV linear, ALiBi causal attention over the
+ * session's cached keys/values plus the new ones (which are appended), dense
+ * linear + residual, LayerNorm, up linear + tanh-GeLU, down linear + residual.
+ * Every linear uses the 8-bit mixed decomposition (Section 3.1): columns whose
+ * magnitude reaches outlier_threshold in any of the B*T rows go through fp16
+ * with weights dequantized from int8, the rest through int8 x int8 -> int32.
+ * Each session's length grows by T.  Errors: B > PETALS_MAX_SESSIONS_PER_CALL,
+ * B*T > max_rows_per_call or a full cache -> PETALS_ERR_CAPACITY; the same
+ * session twice -> PETALS_ERR_INVALID_ARG.
+ */
+int petals_span_prefill(petals_span *span, petals_session *const *sessions, int32_t B,
+                        int32_t T, const void *hidden_in, void *hidden_out, void *stream);
+
+/* One token per session: petals_span_prefill with T = 1; hidden_* are [B, H]. */
+int petals_span_decode_step(petals_span *span, petals_session *const *sessions, int32_t B,
+                            const void *hidden_in, void *hidden_out, void *stream);
+
+/*
+ * Dynamic blockwise 8-bit quantization of hidden states exchanged between
+ * servers (Section 3.1 "Compressing communication buffers").  The flat buffer
+ * of n fp16 values is cut into blocks of `block` consecutive elements (the last
+ * may be partial); each block stores its absolute maximum (fp32) and, per
+ * element, the index of the nearest entry of a 256-entry non-uniform table
+ * (ties to the lower index).  u8_out: dev [n]; absmax_out: dev [ceil(n/block)].
+ * block must be a positive multiple of 64 and at most 16384.
+ */
+int petals_hidden_quantize(const void *fp16_in, size_t n, int32_t block, void *u8_out,
+                           float *absmax_out, void *stream);
+/* Inverse: fp16_out[i] = fp16(table[u8_in[i]] * absmax_in[i / block]). */
+int petals_hidden_dequantize(const void *u8_in, const float *absmax_in, size_t n,
+                             int32_t block, void *fp16_out, void *stream);
+/* The 256 table entries, ascending (host pointer). */
+int petals_hidden_code_table(float *host_table256);
+
+const char *petals_last_error(void);
+
+/* ------------------------------------------------------------ test hooks */
+
+/*
+ * Run ONE linear of a loaded block on caller-supplied fp16 rows through the
+ * same kernels prefill/decode use for that row count, and expose the integer
+ * intermediates.  which: 0 qkv, 1 dense, 2 up, 3 down.  x: dev fp16 [M, K].
+ * epilogue: PETALS_EPILOGUE_*; resid: dev fp16 [M, N] (RESIDUAL only).
+ * Outputs, dev, each may be NULL: xq int8 [M, K] row-major; sx fp32 [M];
+ * outlier_mask uint8 [K] (1 = outlier column); acc int32 [M, N]; y fp16 [M, N]
+ * (plain row-major also for qkv).  M <= max_rows_per_call.
+ */
+int petals_debug_linear(petals_span *span, int32_t block, int32_t which, const void *x,
+                        int32_t M, int32_t epilogue, const void *resid, int8_t *xq, float *sx,
+                        uint8_t *outlier_mask, int32_t *acc, void *y, void *stream);
+
+/* Row-major int8 codes [N, K] and row scales [N] of a loaded linear (dev outputs). */
+int petals_debug_export_weight(petals_span *span, int32_t block, int32_t which, int8_t *wq,
+                               float *sw, void *stream);
+
+/* Cache of one block as dev fp16 [2, n_heads, len, head_dim] (keys then values). */
+int petals_debug_export_kv(const petals_session *session, int32_t block, void *out, void *stream);
+/* Overwrite one block's cache from dev fp16 [2, n_heads, len, head_dim]; sets length = len. */
+int petals_debug_import_kv(petals_session *session, int32_t block, const void *in, int32_t len,
+                           void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PETALS_SPAN_H */

@@ -1,0 +1,275 @@
+"""ctypes binding of libpetals_span.so: the same entry points as include/petals_span.h.
+
+Argument marshalling only.  PyTorch supplies device memory (tensors own every buffer the
+library touches) and the current stream; all computation happens in the HIP library.
+If the library is missing this module raises: there is no fallback path.
+"""
+import ctypes as C
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libpetals_span.so")
+
+EPILOGUE_NONE, EPILOGUE_GELU, EPILOGUE_RESIDUAL = 0, 1, 2
+MAX_SESSIONS_PER_CALL = 64
+
+
+class PetalsError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__("petals_span error %d: %s" % (code, text))
+        self.code = code
+
+
+class SpanConfig(C.Structure):
+    _fields_ = [("n_blocks", C.c_int32), ("hidden", C.c_int32), ("n_heads", C.c_int32), ("ffn", C.c_int32),
+                ("ln_eps", C.c_float), ("outlier_threshold", C.c_float), ("max_rows_per_call", C.c_int32)]
+
+
+class BlockParams(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("w_qkv", "w_dense", "w_up", "w_down", "b_qkv", "b_dense", "b_up",
+                                           "b_down", "ln1_g", "ln1_b", "ln2_g", "ln2_b")]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded shared library (raises if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libpetals_span.so is not built: run `python -m paper_2209_01188_amd.build` "
+                               "(or __graft_entry__.build()); there is no fallback implementation")
+        L = C.CDLL(LIB_PATH)
+        L.petals_last_error.restype = C.c_char_p
+        for name in EXPORTS:
+            if name != "petals_last_error":
+                getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+EXPORTS = ["petals_span_weight_bytes", "petals_span_workspace_bytes", "petals_span_kv_bytes", "petals_span_create",
+           "petals_span_load_block", "petals_span_destroy", "petals_session_open", "petals_session_length",
+           "petals_session_close", "petals_span_prefill", "petals_span_decode_step", "petals_hidden_quantize",
+           "petals_hidden_dequantize", "petals_hidden_code_table", "petals_last_error", "petals_debug_linear",
+           "petals_debug_export_weight", "petals_debug_export_kv", "petals_debug_import_kv"]
+
+
+def _check(rc):
+    if rc != 0:
+        raise PetalsError(rc, lib().petals_last_error().decode())
+
+
+def _ptr(t):
+    return C.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def make_config(n_blocks, hidden, n_heads, ffn, max_rows_per_call, ln_eps=1e-5, outlier_threshold=6.0):
+    return SpanConfig(n_blocks, hidden, n_heads, ffn, ln_eps, outlier_threshold, max_rows_per_call)
+
+
+def petals_span_weight_bytes(cfg):
+    n = C.c_size_t()
+    _check(lib().petals_span_weight_bytes(C.byref(cfg), C.byref(n)))
+    return n.value
+
+
+def petals_span_workspace_bytes(cfg):
+    n = C.c_size_t()
+    _check(lib().petals_span_workspace_bytes(C.byref(cfg), C.byref(n)))
+    return n.value
+
+
+def petals_span_kv_bytes(cfg, max_len):
+    n = C.c_size_t()
+    _check(lib().petals_span_kv_bytes(C.byref(cfg), C.c_int32(max_len), C.byref(n)))
+    return n.value
+
+
+def petals_span_create(cfg, weight_mem, workspace):
+    h = C.c_void_p()
+    _check(lib().petals_span_create(C.byref(cfg), _ptr(weight_mem), _ptr(workspace), C.byref(h)))
+    return h
+
+
+def petals_span_load_block(span, block, params):
+    """params: dict of device tensors (fp32 weights, fp16 biases / LayerNorm parameters)."""
+    bp = BlockParams()
+    for name, _ in BlockParams._fields_:
+        t = params[name]
+        want = torch.float32 if name.startswith("w_") else torch.float16
+        assert t.is_cuda and t.is_contiguous() and t.dtype == want, name
+        setattr(bp, name, t.data_ptr())
+    _check(lib().petals_span_load_block(span, C.c_int32(block), C.byref(bp), _stream()))
+
+
+def petals_span_destroy(span):
+    _check(lib().petals_span_destroy(span))
+
+
+def petals_session_open(span, kv_mem, max_len):
+    h = C.c_void_p()
+    _check(lib().petals_session_open(span, _ptr(kv_mem), C.c_int32(max_len), C.byref(h)))
+    return h
+
+
+def petals_session_length(session):
+    n = C.c_int32()
+    _check(lib().petals_session_length(session, C.byref(n)))
+    return n.value
+
+
+def petals_session_close(session):
+    _check(lib().petals_session_close(session))
+
+
+def _session_array(sessions):
+    return (C.c_void_p * len(sessions))(*[s.value for s in sessions])
+
+
+def petals_span_prefill(span, sessions, T, hidden_in, hidden_out):
+    _check(lib().petals_span_prefill(span, _session_array(sessions), C.c_int32(len(sessions)), C.c_int32(T),
+                                     _ptr(hidden_in), _ptr(hidden_out), _stream()))
+
+
+def petals_span_decode_step(span, sessions, hidden_in, hidden_out):
+    _check(lib().petals_span_decode_step(span, _session_array(sessions), C.c_int32(len(sessions)),
+                                         _ptr(hidden_in), _ptr(hidden_out), _stream()))
+
+
+def petals_hidden_quantize(x, block, q_out, absmax_out):
+    _check(lib().petals_hidden_quantize(_ptr(x), C.c_size_t(x.numel()), C.c_int32(block), _ptr(q_out),
+                                        _ptr(absmax_out), _stream()))
+
+
+def petals_hidden_dequantize(q, absmax, block, y_out):
+    _check(lib().petals_hidden_dequantize(_ptr(q), _ptr(absmax), C.c_size_t(q.numel()), C.c_int32(block),
+                                          _ptr(y_out), _stream()))
+
+
+def petals_hidden_code_table():
+    buf = (C.c_float * 256)()
+    _check(lib().petals_hidden_code_table(buf))
+    return list(buf)
+
+
+def petals_debug_linear(span, block, which, x, epilogue=EPILOGUE_NONE, resid=None, xq=None, sx=None,
+                        outlier_mask=None, acc=None, y=None):
+    _check(lib().petals_debug_linear(span, C.c_int32(block), C.c_int32(which), _ptr(x), C.c_int32(x.shape[0]),
+                                     C.c_int32(epilogue), _ptr(resid), _ptr(xq), _ptr(sx), _ptr(outlier_mask),
+                                     _ptr(acc), _ptr(y), _stream()))
+
+
+def petals_debug_export_weight(span, block, which, wq, sw):
+    _check(lib().petals_debug_export_weight(span, C.c_int32(block), C.c_int32(which), _ptr(wq), _ptr(sw), _stream()))
+
+
+def petals_debug_export_kv(session, block, out):
+    _check(lib().petals_debug_export_kv(session, C.c_int32(block), _ptr(out), _stream()))
+
+
+def petals_debug_import_kv(session, block, kv):
+    _check(lib().petals_debug_import_kv(session, C.c_int32(block), _ptr(kv), C.c_int32(kv.shape[2]), _stream()))
+
+
+# ------------------------------------------------------------------ conveniences
+# Thin owners of the device buffers the C API asks the caller to provide.
+
+class Span:
+    def __init__(self, n_blocks, hidden, n_heads, ffn, max_rows_per_call, ln_eps=1e-5, outlier_threshold=6.0,
+                 device="cuda:0"):
+        self.cfg = make_config(n_blocks, hidden, n_heads, ffn, max_rows_per_call, ln_eps, outlier_threshold)
+        self.device = torch.device(device)
+        self.n_blocks, self.hidden, self.n_heads, self.ffn = n_blocks, hidden, n_heads, ffn
+        self.weight_mem = torch.empty(petals_span_weight_bytes(self.cfg), dtype=torch.uint8, device=self.device)
+        self.workspace = torch.empty(petals_span_workspace_bytes(self.cfg), dtype=torch.uint8, device=self.device)
+        self.handle = petals_span_create(self.cfg, self.weight_mem, self.workspace)
+        self.sessions = []
+
+    def shapes(self, which):
+        H, F = self.hidden, self.ffn
+        return [(3 * H, H), (H, H), (F, H), (H, F)][which]
+
+    def load_block(self, block, params):
+        dev = {k: (v if isinstance(v, torch.Tensor) else torch.from_numpy(v)).to(self.device).contiguous()
+               for k, v in params.items()}
+        petals_span_load_block(self.handle, block, dev)
+        torch.cuda.current_stream().synchronize()   # the fp32 masters may be released after this
+
+    def open_session(self, max_len):
+        s = Session(self, max_len)
+        self.sessions.append(s)
+        return s
+
+    def prefill(self, sessions, hidden_in):
+        B, T, H = hidden_in.shape
+        out = torch.empty_like(hidden_in)
+        petals_span_prefill(self.handle, [s.handle for s in sessions], T, hidden_in, out)
+        return out
+
+    def decode_step(self, sessions, hidden_in, out=None):
+        out = torch.empty_like(hidden_in) if out is None else out
+        petals_span_decode_step(self.handle, [s.handle for s in sessions], hidden_in, out)
+        return out
+
+    def debug_linear(self, block, which, x, epilogue=EPILOGUE_NONE, resid=None):
+        N, K = self.shapes(which)
+        M = x.shape[0]
+        dev = self.device
+        out = dict(xq=torch.empty((M, K), dtype=torch.int8, device=dev), sx=torch.empty(M, dtype=torch.float32, device=dev),
+                   mask=torch.empty(K, dtype=torch.uint8, device=dev), acc=torch.empty((M, N), dtype=torch.int32, device=dev),
+                   y=torch.empty((M, N), dtype=torch.float16, device=dev))
+        petals_debug_linear(self.handle, block, which, x, epilogue, resid, out["xq"], out["sx"], out["mask"],
+                            out["acc"], out["y"])
+        return out
+
+    def export_weight(self, block, which):
+        N, K = self.shapes(which)
+        wq = torch.empty((N, K), dtype=torch.int8, device=self.device)
+        sw = torch.empty(N, dtype=torch.float32, device=self.device)
+        petals_debug_export_weight(self.handle, block, which, wq, sw)
+        return wq, sw
+
+    def close(self):
+        for s in list(self.sessions):
+            s.close()
+        if self.handle is not None:
+            torch.cuda.synchronize(self.device)
+            petals_span_destroy(self.handle)
+            self.handle = None
+
+
+class Session:
+    def __init__(self, span, max_len):
+        self.span, self.max_len = span, max_len
+        self.kv_mem = torch.zeros(petals_span_kv_bytes(span.cfg, max_len), dtype=torch.uint8, device=span.device)
+        self.handle = petals_session_open(span.handle, self.kv_mem, max_len)
+
+    @property
+    def length(self):
+        return petals_session_length(self.handle)
+
+    def export_kv(self, block):
+        s = self.span
+        out = torch.empty((2, s.n_heads, self.length, s.hidden // s.n_heads), dtype=torch.float16, device=s.device)
+        if out.numel():
+            petals_debug_export_kv(self.handle, block, out)
+        return out
+
+    def import_kv(self, block, kv):
+        petals_debug_import_kv(self.handle, block, kv.contiguous())
+
+    def close(self):
+        if self.handle is not None:
+            torch.cuda.synchronize(self.span.device)
+            petals_session_close(self.handle)
+            self.handle = None
+            if self in self.span.sessions:
+                self.span.sessions.remove(self)

@@ -1,0 +1,451 @@
+// Host side of the C ABI: handles, argument checks, memory partitioning and the order
+// in which the kernels of one block are enqueued.  No device memory is allocated here.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "../../include/petals_span.h"
+#include "common.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+int hip_fail(hipError_t e, const char *what) {
+    return fail(PETALS_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+#define HIP_TRY(expr)                                        \
+    do {                                                     \
+        hipError_t e_ = (expr);                              \
+        if (e_ != hipSuccess) return hip_fail(e_, #expr);    \
+    } while (0)
+
+size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
+
+struct BlockW {
+    LinearW lin[4];
+    __half *ln1g, *ln1b, *ln2g, *ln2b;
+    bool loaded;
+};
+
+void linear_dims(const petals_span_config &c, int which, int *N, int *K) {
+    const int H = c.hidden, F = c.ffn;
+    const int n[4] = {3 * H, H, F, H}, k[4] = {H, H, H, F};
+    *N = n[which];
+    *K = k[which];
+}
+
+size_t block_weight_bytes(const petals_span_config &c) {
+    size_t b = 0;
+    for (int i = 0; i < 4; i++) {
+        int N, K;
+        linear_dims(c, i, &N, &K);
+        b += align_up((size_t)N * K) + align_up((size_t)N * 4) + align_up((size_t)N * 2);
+    }
+    return b + 4 * align_up((size_t)c.hidden * 2);
+}
+
+struct Workspace {
+    SessTable *table;
+    __half *a, *q, *ctx, *x1, *xa, *xb, *g;
+    int8_t *xq;
+    float *sx;
+    uint32_t *masks;    // [n_blocks][4][mask_words]
+    float *partials;
+    size_t mask_words;
+    size_t total;
+};
+
+Workspace carve(const petals_span_config &c, uint8_t *base) {
+    Workspace w;
+    const size_t M = (size_t)c.max_rows_per_call, Mp = (M + 15) / 16 * 16, H = c.hidden, F = c.ffn;
+    const size_t Kmax = F > H ? F : H;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { uint8_t *p = base ? base + off : nullptr; off += align_up(bytes); return p; };
+    w.table = (SessTable *)take(sizeof(SessTable));
+    w.a = (__half *)take(M * H * 2);
+    w.q = (__half *)take(M * H * 2);
+    w.ctx = (__half *)take(M * H * 2);
+    w.x1 = (__half *)take(M * H * 2);
+    w.xa = (__half *)take(M * H * 2);
+    w.xb = (__half *)take(M * H * 2);
+    w.g = (__half *)take(M * F * 2);
+    w.xq = (int8_t *)take(Mp * Kmax);
+    w.sx = (float *)take(Mp * 4);
+    w.mask_words = (Kmax + 63) / 64 * 2;
+    w.masks = (uint32_t *)take((size_t)c.n_blocks * 4 * w.mask_words * 4);
+    w.partials = (float *)take((size_t)PS_ATTN_PARTIAL_SLOTS * (128 + 2) * 4);
+    w.total = off;
+    return w;
+}
+
+int check_config(const petals_span_config *c) {
+    if (!c) return fail(PETALS_ERR_INVALID_ARG, "config is null");
+    if (c->n_blocks < 1 || c->hidden < 1 || c->n_heads < 1 || c->ffn < 1 || c->max_rows_per_call < 1)
+        return fail(PETALS_ERR_INVALID_ARG, "config fields must be positive");
+    if (c->hidden % c->n_heads) return fail(PETALS_ERR_INVALID_ARG, "hidden not divisible by n_heads");
+    const int d = c->hidden / c->n_heads;
+    if (c->hidden % 64 || c->ffn % 64) return fail(PETALS_ERR_UNSUPPORTED, "hidden and ffn must be multiples of 64");
+    if (d != 16 && d != 32 && d != 64 && d != 128) return fail(PETALS_ERR_UNSUPPORTED, "head_dim must be 16, 32, 64 or 128");
+    if (c->hidden > 16384) return fail(PETALS_ERR_UNSUPPORTED, "hidden above 16384");
+    if (c->ffn > 65536) return fail(PETALS_ERR_UNSUPPORTED, "ffn above 65536 would overflow the int32 accumulators");
+    if (c->n_heads > PS_MAX_HEADS) return fail(PETALS_ERR_UNSUPPORTED, "more than %d heads", PS_MAX_HEADS);
+    if (c->max_rows_per_call > 65535) return fail(PETALS_ERR_UNSUPPORTED, "max_rows_per_call above 65535");
+    if (!(c->ln_eps > 0.0f) || c->outlier_threshold < 0.0f || c->outlier_threshold != c->outlier_threshold)
+        return fail(PETALS_ERR_INVALID_ARG, "ln_eps must be positive and outlier_threshold non-negative");
+    return PETALS_OK;
+}
+
+// The 256 entries of the 8-bit dynamic data type: per decade 10^-e (e = 0..6) the centres
+// of 2^(6-e) equal buckets spanning [0.1, 1.0], both signs, plus 0 and 1.0; ascending.
+const CodeTable &code_table() {
+    static CodeTable tab;
+    static bool ready = false;
+    if (!ready) {
+        static const double decade[7] = {1.0, 1e-1, 1e-2, 1e-3, 1e-4, 1e-5, 1e-6};
+        std::vector<float> pos;
+        for (int e = 6; e >= 0; e--) {
+            const int cnt = 64 >> e;
+            for (int j = 0; j < cnt; j++) pos.push_back((float)(decade[e] * (0.1 + 0.9 * (j + 0.5) / cnt)));
+        }
+        // pos ascends: decades from small to large, buckets ascending inside a decade
+        int k = 0;
+        for (int i = (int)pos.size() - 1; i >= 0; i--) tab.code[k++] = -pos[i];
+        tab.code[k++] = 0.0f;
+        for (size_t i = 0; i < pos.size(); i++) tab.code[k++] = pos[i];
+        tab.code[k++] = 1.0f;
+        ready = true;
+    }
+    return tab;
+}
+
+}  // namespace
+
+struct petals_span {
+    petals_span_config cfg;
+    uint8_t *wmem;
+    Workspace ws;
+    std::vector<BlockW> blocks;
+    float slopes[PS_MAX_HEADS];
+    int open_sessions;
+};
+
+struct petals_session {
+    petals_span *span;
+    __half *kv;
+    int cap, len;
+};
+
+namespace {
+
+// One linear on M rows already resident as fp16 X[M,K]; picks the one-row or the MFMA path.
+int run_linear(petals_span *sp, const LinearW &w, const __half *X, int M, uint32_t *mask, const OutDesc &o,
+               int8_t *xq_dbg, hipStream_t st, bool row_already_quantized) {
+    Workspace &ws = sp->ws;
+    const float theta = sp->cfg.outlier_threshold;
+    if (M == 1) {
+        if (!row_already_quantized) HIP_TRY(ps_rowquant_row(X, w.K, theta, ws.xq, mask, ws.sx, st));
+        if (xq_dbg) HIP_TRY(ps_copy_bytes(ws.xq, xq_dbg, (size_t)w.K, st));
+        HIP_TRY(ps_gemv_row(w, ws.xq, mask, X, ws.sx, o, ws.table, st));
+    } else {
+        HIP_TRY(ps_fill_u32(mask, ws.mask_words, 0u, st));
+        HIP_TRY(ps_colmask(X, M, w.K, theta, mask, st));
+        HIP_TRY(ps_rowquant_tiled(X, M, w.K, mask, ws.xq, ws.sx, xq_dbg, st));
+        HIP_TRY(ps_gemm(w, ws.xq, mask, X, ws.sx, M, o, ws.table, st));
+    }
+    return PETALS_OK;
+}
+
+OutDesc plain_out(__half *y, int epilogue, const __half *resid) {
+    OutDesc o;
+    memset(&o, 0, sizeof(o));
+    o.y = y;
+    o.epilogue = epilogue;
+    o.resid = resid;
+    o.T = 1;
+    return o;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *petals_last_error(void) { return g_err; }
+
+int petals_span_weight_bytes(const petals_span_config *cfg, size_t *bytes) {
+    if (int rc = check_config(cfg)) return rc;
+    if (!bytes) return fail(PETALS_ERR_INVALID_ARG, "bytes is null");
+    *bytes = block_weight_bytes(*cfg) * (size_t)cfg->n_blocks;
+    return PETALS_OK;
+}
+
+int petals_span_workspace_bytes(const petals_span_config *cfg, size_t *bytes) {
+    if (int rc = check_config(cfg)) return rc;
+    if (!bytes) return fail(PETALS_ERR_INVALID_ARG, "bytes is null");
+    *bytes = carve(*cfg, nullptr).total;
+    return PETALS_OK;
+}
+
+int petals_span_kv_bytes(const petals_span_config *cfg, int32_t max_len, size_t *bytes) {
+    if (int rc = check_config(cfg)) return rc;
+    if (!bytes || max_len < 1) return fail(PETALS_ERR_INVALID_ARG, "bytes is null or max_len < 1");
+    *bytes = (size_t)cfg->n_blocks * 2 * cfg->hidden * (size_t)max_len * 2;
+    return PETALS_OK;
+}
+
+int petals_span_create(const petals_span_config *cfg, void *dev_weight_mem, void *dev_workspace, petals_span **out) {
+    if (int rc = check_config(cfg)) return rc;
+    if (!dev_weight_mem || !dev_workspace || !out) return fail(PETALS_ERR_INVALID_ARG, "null pointer");
+    if (((uintptr_t)dev_weight_mem | (uintptr_t)dev_workspace) & 255)
+        return fail(PETALS_ERR_INVALID_ARG, "device memory must be 256-byte aligned");
+    petals_span *sp = new (std::nothrow) petals_span();
+    if (!sp) return fail(PETALS_ERR_INVALID_ARG, "out of host memory");
+    sp->cfg = *cfg;
+    sp->wmem = (uint8_t *)dev_weight_mem;
+    sp->ws = carve(*cfg, (uint8_t *)dev_workspace);
+    sp->open_sessions = 0;
+    sp->blocks.resize(cfg->n_blocks);
+    const size_t per_block = block_weight_bytes(*cfg);
+    for (int b = 0; b < cfg->n_blocks; b++) {
+        uint8_t *p = sp->wmem + per_block * b;
+        BlockW &B = sp->blocks[b];
+        for (int i = 0; i < 4; i++) {
+            int N, K;
+            linear_dims(*cfg, i, &N, &K);
+            B.lin[i].N = N;
+            B.lin[i].K = K;
+            B.lin[i].wt = (int8_t *)p;       p += align_up((size_t)N * K);
+            B.lin[i].sw = (float *)p;        p += align_up((size_t)N * 4);
+            B.lin[i].bias = (__half *)p;     p += align_up((size_t)N * 2);
+        }
+        B.ln1g = (__half *)p; p += align_up((size_t)cfg->hidden * 2);
+        B.ln1b = (__half *)p; p += align_up((size_t)cfg->hidden * 2);
+        B.ln2g = (__half *)p; p += align_up((size_t)cfg->hidden * 2);
+        B.ln2b = (__half *)p; p += align_up((size_t)cfg->hidden * 2);
+        B.loaded = false;
+    }
+    // ALiBi slopes: geometric sequence for the largest power of two n2 <= heads, the
+    // remaining heads take the odd terms of the 2*n2 sequence
+    int n2 = 1;
+    while (n2 * 2 <= cfg->n_heads) n2 *= 2;
+    for (int h = 0; h < PS_MAX_HEADS; h++) sp->slopes[h] = 0.0f;
+    for (int h = 0; h < cfg->n_heads; h++)
+        sp->slopes[h] = (float)(h < n2 ? exp2(-8.0 * (h + 1) / n2) : exp2(-4.0 * (2 * (h - n2) + 1) / n2));
+    *out = sp;
+    return PETALS_OK;
+}
+
+int petals_span_load_block(petals_span *sp, int32_t block, const petals_block_params *p, void *stream) {
+    if (!sp || !p) return fail(PETALS_ERR_INVALID_ARG, "null pointer");
+    if (block < 0 || block >= sp->cfg.n_blocks) return fail(PETALS_ERR_INVALID_ARG, "block %d out of range", block);
+    const float *w[4] = {p->w_qkv, p->w_dense, p->w_up, p->w_down};
+    const uint16_t *bias[4] = {p->b_qkv, p->b_dense, p->b_up, p->b_down};
+    const uint16_t *ln[4] = {p->ln1_g, p->ln1_b, p->ln2_g, p->ln2_b};
+    for (int i = 0; i < 4; i++)
+        if (!w[i] || !bias[i] || !ln[i]) return fail(PETALS_ERR_INVALID_ARG, "null parameter pointer");
+    hipStream_t st = (hipStream_t)stream;
+    BlockW &B = sp->blocks[block];
+    for (int i = 0; i < 4; i++) {
+        const LinearW &L = B.lin[i];
+        HIP_TRY(ps_quantize_weight(w[i], L.N, L.K, (int8_t *)L.wt, (float *)L.sw, st));
+        HIP_TRY(ps_copy_bytes(bias[i], (void *)L.bias, (size_t)L.N * 2, st));
+    }
+    __half *dst[4] = {B.ln1g, B.ln1b, B.ln2g, B.ln2b};
+    for (int i = 0; i < 4; i++) HIP_TRY(ps_copy_bytes(ln[i], dst[i], (size_t)sp->cfg.hidden * 2, st));
+    B.loaded = true;
+    return PETALS_OK;
+}
+
+int petals_span_destroy(petals_span *sp) {
+    if (!sp) return fail(PETALS_ERR_INVALID_ARG, "null span");
+    if (sp->open_sessions) return fail(PETALS_ERR_STATE, "%d sessions still open", sp->open_sessions);
+    delete sp;
+    return PETALS_OK;
+}
+
+int petals_session_open(petals_span *sp, void *dev_kv_mem, int32_t max_len, petals_session **out) {
+    if (!sp || !dev_kv_mem || !out) return fail(PETALS_ERR_INVALID_ARG, "null pointer");
+    if (max_len < 1) return fail(PETALS_ERR_INVALID_ARG, "max_len < 1");
+    if ((uintptr_t)dev_kv_mem & 255) return fail(PETALS_ERR_INVALID_ARG, "kv memory must be 256-byte aligned");
+    petals_session *se = new (std::nothrow) petals_session();
+    if (!se) return fail(PETALS_ERR_INVALID_ARG, "out of host memory");
+    se->span = sp;
+    se->kv = (__half *)dev_kv_mem;
+    se->cap = max_len;
+    se->len = 0;
+    sp->open_sessions++;
+    *out = se;
+    return PETALS_OK;
+}
+
+int petals_session_length(const petals_session *se, int32_t *len) {
+    if (!se || !len) return fail(PETALS_ERR_INVALID_ARG, "null pointer");
+    *len = se->len;
+    return PETALS_OK;
+}
+
+int petals_session_close(petals_session *se) {
+    if (!se) return fail(PETALS_ERR_INVALID_ARG, "null session");
+    se->span->open_sessions--;
+    delete se;
+    return PETALS_OK;
+}
+
+int petals_span_prefill(petals_span *sp, petals_session *const *sessions, int32_t B, int32_t T,
+                        const void *hidden_in, void *hidden_out, void *stream) {
+    if (!sp || !sessions || !hidden_in || !hidden_out) return fail(PETALS_ERR_INVALID_ARG, "null pointer");
+    if (B < 1 || T < 1) return fail(PETALS_ERR_INVALID_ARG, "B and T must be positive");
+    if (hidden_in == hidden_out) return fail(PETALS_ERR_INVALID_ARG, "hidden_in and hidden_out alias");
+    if (B > PETALS_MAX_SESSIONS_PER_CALL) return fail(PETALS_ERR_CAPACITY, "more than %d sessions in one call", PETALS_MAX_SESSIONS_PER_CALL);
+    if ((int64_t)B * T > sp->cfg.max_rows_per_call)
+        return fail(PETALS_ERR_CAPACITY, "%lld rows exceed max_rows_per_call %d", (long long)B * T, sp->cfg.max_rows_per_call);
+    const petals_span_config &c = sp->cfg;
+    SessTable tab;
+    memset(&tab, 0, sizeof(tab));
+    int max_keys = 0;
+    for (int s = 0; s < B; s++) {
+        petals_session *se = sessions[s];
+        if (!se || se->span != sp) return fail(PETALS_ERR_INVALID_ARG, "session %d is null or belongs to another span", s);
+        for (int r = 0; r < s; r++)
+            if (sessions[r] == se) return fail(PETALS_ERR_INVALID_ARG, "session listed twice");
+        if (se->len + T > se->cap) return fail(PETALS_ERR_CAPACITY, "session %d: %d cached + %d new > capacity %d", s, se->len, T, se->cap);
+        tab.kv[s] = se->kv;
+        tab.len[s] = se->len;
+        tab.cap[s] = se->cap;
+        if (se->len + T > max_keys) max_keys = se->len + T;
+    }
+    for (int b = 0; b < c.n_blocks; b++)
+        if (!sp->blocks[b].loaded) return fail(PETALS_ERR_STATE, "block %d has not been loaded", b);
+    memcpy(tab.slopes, sp->slopes, sizeof(tab.slopes));
+
+    hipStream_t st = (hipStream_t)stream;
+    Workspace &ws = sp->ws;
+    const int M = B * T, H = c.hidden, F = c.ffn, nh = c.n_heads, d = H / nh;
+    HIP_TRY(ps_set_table(tab, ws.table, st));
+    const __half *x = (const __half *)hidden_in;
+    for (int b = 0; b < c.n_blocks; b++) {
+        const BlockW &W = sp->blocks[b];
+        __half *xout = (b == c.n_blocks - 1) ? (__half *)hidden_out : ((b & 1) ? ws.xb : ws.xa);
+        uint32_t *mk = ws.masks + (size_t)b * 4 * ws.mask_words;
+        OutDesc oq = plain_out(ws.q, PETALS_EPILOGUE_NONE, nullptr);
+        oq.scatter = 1; oq.T = T; oq.nh = nh; oq.d = d; oq.blk = b;
+        // LayerNorm 1 -> fused QKV (queries to ws.q, keys/values appended to the caches)
+        if (M == 1) {
+            HIP_TRY(ps_ln_quant_row(x, W.ln1g, W.ln1b, c.ln_eps, H, c.outlier_threshold, ws.a, ws.xq, mk, ws.sx, st));
+        } else {
+            HIP_TRY(ps_layernorm(x, W.ln1g, W.ln1b, c.ln_eps, M, H, ws.a, st));
+        }
+        if (int rc = run_linear(sp, W.lin[0], ws.a, M, mk, oq, nullptr, st, M == 1)) return rc;
+        HIP_TRY(ps_attention(ws.q, ws.table, b, M, T, nh, d, max_keys, ws.partials, ws.ctx, st));
+        // dense + residual
+        if (int rc = run_linear(sp, W.lin[1], ws.ctx, M, mk + ws.mask_words,
+                                plain_out(ws.x1, PETALS_EPILOGUE_RESIDUAL, x), nullptr, st, false)) return rc;
+        // LayerNorm 2 -> up + GeLU -> down + residual
+        if (M == 1) {
+            HIP_TRY(ps_ln_quant_row(ws.x1, W.ln2g, W.ln2b, c.ln_eps, H, c.outlier_threshold, ws.a, ws.xq,
+                                    mk + 2 * ws.mask_words, ws.sx, st));
+        } else {
+            HIP_TRY(ps_layernorm(ws.x1, W.ln2g, W.ln2b, c.ln_eps, M, H, ws.a, st));
+        }
+        if (int rc = run_linear(sp, W.lin[2], ws.a, M, mk + 2 * ws.mask_words,
+                                plain_out(ws.g, PETALS_EPILOGUE_GELU, nullptr), nullptr, st, M == 1)) return rc;
+        if (int rc = run_linear(sp, W.lin[3], ws.g, M, mk + 3 * ws.mask_words,
+                                plain_out(xout, PETALS_EPILOGUE_RESIDUAL, ws.x1), nullptr, st, false)) return rc;
+        x = xout;
+    }
+    for (int s = 0; s < B; s++) sessions[s]->len += T;
+    return PETALS_OK;
+}
+
+int petals_span_decode_step(petals_span *sp, petals_session *const *sessions, int32_t B, const void *hidden_in,
+                            void *hidden_out, void *stream) {
+    return petals_span_prefill(sp, sessions, B, 1, hidden_in, hidden_out, stream);
+}
+
+int petals_hidden_code_table(float *host_table256) {
+    if (!host_table256) return fail(PETALS_ERR_INVALID_ARG, "null pointer");
+    memcpy(host_table256, code_table().code, sizeof(float) * 256);
+    return PETALS_OK;
+}
+
+int petals_hidden_quantize(const void *fp16_in, size_t n, int32_t block, void *u8_out, float *absmax_out, void *stream) {
+    if (!fp16_in || !u8_out || !absmax_out) return fail(PETALS_ERR_INVALID_ARG, "null pointer");
+    if (block < 64 || block % 64 || block > 16384) return fail(PETALS_ERR_INVALID_ARG, "block must be a multiple of 64 in [64, 16384]");
+    HIP_TRY(ps_hidden_quantize((const __half *)fp16_in, n, block, code_table(), (uint8_t *)u8_out, absmax_out, (hipStream_t)stream));
+    return PETALS_OK;
+}
+
+int petals_hidden_dequantize(const void *u8_in, const float *absmax_in, size_t n, int32_t block, void *fp16_out, void *stream) {
+    if (!u8_in || !absmax_in || !fp16_out) return fail(PETALS_ERR_INVALID_ARG, "null pointer");
+    if (block < 64 || block % 64 || block > 16384) return fail(PETALS_ERR_INVALID_ARG, "block must be a multiple of 64 in [64, 16384]");
+    HIP_TRY(ps_hidden_dequantize((const uint8_t *)u8_in, absmax_in, n, block, code_table(), (__half *)fp16_out, (hipStream_t)stream));
+    return PETALS_OK;
+}
+
+int petals_debug_linear(petals_span *sp, int32_t block, int32_t which, const void *x, int32_t M, int32_t epilogue,
+                        const void *resid, int8_t *xq, float *sx, uint8_t *outlier_mask, int32_t *acc, void *y,
+                        void *stream) {
+    if (!sp || !x) return fail(PETALS_ERR_INVALID_ARG, "null pointer");
+    if (block < 0 || block >= sp->cfg.n_blocks || which < 0 || which > 3) return fail(PETALS_ERR_INVALID_ARG, "block or linear index out of range");
+    if (!sp->blocks[block].loaded) return fail(PETALS_ERR_STATE, "block %d has not been loaded", block);
+    if (M < 1 || M > sp->cfg.max_rows_per_call) return fail(PETALS_ERR_CAPACITY, "M out of range");
+    if (epilogue < 0 || epilogue > 2 || (epilogue == PETALS_EPILOGUE_RESIDUAL && !resid)) return fail(PETALS_ERR_INVALID_ARG, "bad epilogue");
+    hipStream_t st = (hipStream_t)stream;
+    Workspace &ws = sp->ws;
+    const LinearW &L = sp->blocks[block].lin[which];
+    // the product path always writes y; without a caller buffer use the (large enough) g buffer
+    __half *yy = y ? (__half *)y : ws.g;
+    if (!y && (size_t)M * L.N > (size_t)sp->cfg.max_rows_per_call * sp->cfg.ffn) return fail(PETALS_ERR_INVALID_ARG, "y is required for this shape");
+    OutDesc o = plain_out(yy, epilogue, (const __half *)resid);
+    o.acc_out = acc;
+    uint32_t *mk = ws.masks;
+    if (int rc = run_linear(sp, L, (const __half *)x, M, mk, o, xq, st, false)) return rc;
+    if (sx) HIP_TRY(ps_copy_bytes(ws.sx, sx, (size_t)M * 4, st));
+    if (outlier_mask) HIP_TRY(ps_mask_to_bytes(mk, L.K, outlier_mask, st));
+    return PETALS_OK;
+}
+
+int petals_debug_export_weight(petals_span *sp, int32_t block, int32_t which, int8_t *wq, float *sw, void *stream) {
+    if (!sp) return fail(PETALS_ERR_INVALID_ARG, "null span");
+    if (block < 0 || block >= sp->cfg.n_blocks || which < 0 || which > 3) return fail(PETALS_ERR_INVALID_ARG, "block or linear index out of range");
+    if (!sp->blocks[block].loaded) return fail(PETALS_ERR_STATE, "block %d has not been loaded", block);
+    const LinearW &L = sp->blocks[block].lin[which];
+    if (wq) HIP_TRY(ps_untile_weight(L.wt, L.N, L.K, wq, (hipStream_t)stream));
+    if (sw) HIP_TRY(ps_copy_bytes(L.sw, sw, (size_t)L.N * 4, (hipStream_t)stream));
+    return PETALS_OK;
+}
+
+int petals_debug_export_kv(const petals_session *se, int32_t block, void *out, void *stream) {
+    if (!se || !out) return fail(PETALS_ERR_INVALID_ARG, "null pointer");
+    const petals_span_config &c = se->span->cfg;
+    if (block < 0 || block >= c.n_blocks) return fail(PETALS_ERR_INVALID_ARG, "block out of range");
+    const int d = c.hidden / c.n_heads;
+    const __half *kv = se->kv + (size_t)block * 2 * c.n_heads * se->cap * d;
+    HIP_TRY(ps_kv_export(kv, c.n_heads, se->cap, d, se->len, (__half *)out, (hipStream_t)stream));
+    return PETALS_OK;
+}
+
+int petals_debug_import_kv(petals_session *se, int32_t block, const void *in, int32_t len, void *stream) {
+    if (!se || !in) return fail(PETALS_ERR_INVALID_ARG, "null pointer");
+    const petals_span_config &c = se->span->cfg;
+    if (block < 0 || block >= c.n_blocks) return fail(PETALS_ERR_INVALID_ARG, "block out of range");
+    if (len < 0 || len > se->cap) return fail(PETALS_ERR_CAPACITY, "len %d exceeds capacity %d", len, se->cap);
+    const int d = c.hidden / c.n_heads;
+    __half *kv = se->kv + (size_t)block * 2 * c.n_heads * se->cap * d;
+    HIP_TRY(ps_kv_import(kv, c.n_heads, se->cap, d, len, (const __half *)in, (hipStream_t)stream));
+    se->len = len;
+    return PETALS_OK;
+}
+
+}  // extern "C"

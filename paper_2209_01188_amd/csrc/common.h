@@ -1,0 +1,134 @@
+// Shared declarations of the span library's kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef _Float16 v4h __attribute__((ext_vector_type(4)));
+
+#define PS_MAX_SESSIONS 64
+#define PS_MAX_HEADS 256
+
+// int8 weights of one linear in streaming tile order: tiles of 16 output rows x 64
+// input columns, 1024 bytes each; tile (nt, kt) starts at ((nt * K/64) + kt) * 1024;
+// inside a tile lane l (0..63) owns bytes [16 l, 16 l + 16): row nt*16 + l%16,
+// columns kt*64 + (l/16)*16 + 0..15.  This is exactly the per-lane operand of
+// v_mfma_i32_16x16x64_i8, and a wave reads one tile as 1 KB of consecutive bytes.
+struct LinearW {
+    const int8_t *wt;
+    const float *sw;      // [N] row scales (row absmax)
+    const __half *bias;   // [N]
+    int N, K;
+};
+
+// Per-call table in device memory: key/value memory of the sessions of the call and
+// the ALiBi slopes.  len[s]: tokens cached BEFORE this call.
+struct SessTable {
+    __half *kv[PS_MAX_SESSIONS];   // session base: [block][key|value][head][cap][d]
+    int len[PS_MAX_SESSIONS];
+    int cap[PS_MAX_SESSIONS];
+    float slopes[PS_MAX_HEADS];    // ALiBi slope per head
+};
+
+// Where a linear's result goes and what is fused before the fp16 rounding.
+struct OutDesc {
+    int scatter;          // 0: y is [M,N] row-major; 1: fused-QKV scatter (q -> y [M,H], k/v -> caches)
+    __half *y;
+    int epilogue;         // 0 none, 1 tanh-GeLU, 2 + resid
+    const __half *resid;  // [M,N]
+    int32_t *acc_out;     // optional int32 [M,N] copy of the integer accumulators
+    int T, nh, d, blk;    // scatter: row t belongs to session t / T at position len + t % T of block blk
+};
+
+struct CodeTable { float code[256]; };
+
+// --- launchers (all enqueue on `st` and return the launch status) ---------------
+hipError_t ps_quantize_weight(const float *W, int N, int K, int8_t *wt, float *sw, hipStream_t st);
+hipError_t ps_untile_weight(const int8_t *wt, int N, int K, int8_t *wq_rowmajor, hipStream_t st);
+hipError_t ps_fill_u32(uint32_t *p, size_t n, uint32_t v, hipStream_t st);
+hipError_t ps_copy_bytes(const void *src, void *dst, size_t n, hipStream_t st);
+hipError_t ps_layernorm(const __half *x, const __half *g, const __half *b, float eps, int M, int H,
+                        __half *y, hipStream_t st);
+// M == 1: LayerNorm, outlier detection and int8 quantization of the one row in one kernel
+hipError_t ps_ln_quant_row(const __half *x, const __half *g, const __half *b, float eps, int H, float theta,
+                           __half *y, int8_t *xq, uint32_t *mask, float *sx, hipStream_t st);
+hipError_t ps_colmask(const __half *X, int M, int K, float theta, uint32_t *mask, hipStream_t st);
+// M rows -> tiled int8 codes (rows padded to 16 with zeros), row scales; mask given
+hipError_t ps_rowquant_tiled(const __half *X, int M, int K, const uint32_t *mask, int8_t *xq_tiled, float *sx,
+                             int8_t *xq_rowmajor_dbg, hipStream_t st);
+// one row -> its own mask, row-major codes, scale
+hipError_t ps_rowquant_row(const __half *x, int K, float theta, int8_t *xq, uint32_t *mask, float *sx,
+                           hipStream_t st);
+hipError_t ps_mask_to_bytes(const uint32_t *mask, int K, uint8_t *out, hipStream_t st);
+
+// y = mixed int8/fp16 linear for one row (decode, batch 1)
+hipError_t ps_gemv_row(const LinearW &w, const int8_t *xq, const uint32_t *mask, const __half *x, const float *sx,
+                       const OutDesc &o, const SessTable *sess, hipStream_t st);
+// same for M >= 2 rows on int8 / fp16 MFMA; xq_tiled as written by ps_rowquant_tiled
+hipError_t ps_gemm(const LinearW &w, const int8_t *xq_tiled, const uint32_t *mask, const __half *X, const float *sx,
+                   int M, const OutDesc &o, const SessTable *sess, hipStream_t st);
+
+// attention of M = B*T query rows against the caches (new keys/values already appended)
+hipError_t ps_set_table(const SessTable &host_table, SessTable *dev_table, hipStream_t st);
+#define PS_ATTN_MAX_SPLITS 16
+#define PS_ATTN_PARTIAL_SLOTS 8192   // (row, head, split) triples that may need a partial result
+hipError_t ps_attention(const __half *q, const SessTable *sess, int blk, int M, int T, int nh, int d, int max_keys,
+                        float *partials, __half *ctx, hipStream_t st);
+
+hipError_t ps_hidden_quantize(const __half *x, size_t n, int block, const CodeTable &tab, uint8_t *q, float *absmax,
+                              hipStream_t st);
+hipError_t ps_hidden_dequantize(const uint8_t *q, const float *absmax, size_t n, int block, const CodeTable &tab,
+                                __half *y, hipStream_t st);
+hipError_t ps_kv_export(const __half *kv, int nh, int cap, int d, int len, __half *out, hipStream_t st);
+hipError_t ps_kv_import(__half *kv, int nh, int cap, int d, int len, const __half *in, hipStream_t st);
+
+// --- small device helpers ---------------------------------------------------------
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+// workgroup reductions over NW waves; sm: NW floats of LDS; sums are added in a fixed order
+template <int NW>
+__device__ __forceinline__ float block_max(float v, float *sm) {
+    v = wave_max(v);
+    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float r = sm[0];
+#pragma unroll
+    for (int i = 1; i < NW; i++) r = fmaxf(r, sm[i]);
+    __syncthreads();
+    return r;
+}
+template <int NW>
+__device__ __forceinline__ float block_sum(float v, float *sm) {
+    v = wave_sum(v);
+    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float r = sm[0];
+#pragma unroll
+    for (int i = 1; i < NW; i++) r += sm[i];
+    __syncthreads();
+    return r;
+}
+__device__ __forceinline__ float gelu_tanh(float v) {
+    return 0.5f * v * (1.0f + tanhf(0.7978845608028654f * (v + 0.044715f * v * v * v)));
+}
+// int8 code of one activation/weight: fp32 product, round half to even, clamp
+__device__ __forceinline__ int q8(float x, float r) {
+    float q = rintf(x * r);
+    q = fminf(fmaxf(q, -127.0f), 127.0f);
+    return (int)q;
+}
+__device__ __forceinline__ int pack4(int a, int b, int c, int d) {
+    return (a & 0xff) | ((b & 0xff) << 8) | ((c & 0xff) << 16) | ((d & 0xff) << 24);
+}

@@ -1,0 +1,31 @@
+// Shared tail of every linear: combine the exact int32 part, the fp16 outlier part and
+// the bias, apply the fused GeLU / residual, round to fp16 once, store.
+#pragma once
+#include "common.h"
+
+__device__ __forceinline__ void emit_output(const OutDesc &o, const SessTable *__restrict__ sess, int N, int t,
+                                            int n, int acc, float outl, float sxd, float swd, float bias) {
+    float v = (float)acc * sxd * swd + outl + bias;
+    if (o.epilogue == 1) v = gelu_tanh(v);
+    else if (o.epilogue == 2) v += __half2float(o.resid[(size_t)t * N + n]);
+    const __half hv = __float2half_rn(v);
+    if (o.acc_out) o.acc_out[(size_t)t * N + n] = acc;
+    if (!o.scatter) {
+        o.y[(size_t)t * N + n] = hv;
+    } else {
+        // fused QKV: output row n = h*3d + p*d + j ; queries to y[M,H], keys/values appended to the caches
+        const int d = o.d, h = n / (3 * d), rem = n - h * 3 * d, p = rem / d, j = rem - p * d;
+        if (p == 0) {
+            o.y[(size_t)t * (o.nh * d) + h * d + j] = hv;
+        } else {
+            const int s = t / o.T, cap = sess->cap[s], pos = sess->len[s] + (t - s * o.T);
+            __half *base = sess->kv[s] + ((size_t)o.blk * 2 + (p == 2 ? 1 : 0)) * o.nh * cap * d;
+            base[((size_t)h * cap + pos) * d + j] = hv;
+        }
+    }
+}
+
+// fp16 weight reconstructed from an int8 code: fp32 product rounded to fp16
+__device__ __forceinline__ float dequant_w16(int code, float swd) {
+    return __half2float(__float2half_rn((float)code * swd));
+}

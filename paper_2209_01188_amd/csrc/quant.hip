@@ -1,0 +1,364 @@
+// Elementwise / per-row kernels of the span library: weight quantization into the
+// streaming tile order, LayerNorm, outlier-column detection, row-wise int8
+// quantization of activations, the blockwise 8-bit hidden-state codec, cache copies.
+#include "common.h"
+
+namespace {
+
+// ---------------------------------------------------------------- weights
+
+// One workgroup per 16 output rows.  Vector-wise int8 quantization of the fp32 rows
+// (one scale per row = its absolute maximum) written straight into tile order.
+__global__ void __launch_bounds__(256) k_quantize_weight(const float *__restrict__ W, int K,
+                                                         int8_t *__restrict__ wt, float *__restrict__ sw) {
+    __shared__ float s_abs[16];
+    const int p = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (int rr = 0; rr < 4; rr++) {
+        const int row = wave * 4 + rr;
+        const float *w = W + (size_t)(p * 16 + row) * K;
+        float m = 0.0f;
+        for (int k = lane * 4; k < K; k += 256) {
+            float4 v = *(const float4 *)(w + k);
+            m = fmaxf(m, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+        }
+        m = wave_max(m);
+        if (lane == 0) { s_abs[row] = m; sw[p * 16 + row] = m; }
+    }
+    __syncthreads();
+    const int row = lane & 15, kg = lane >> 4, KT = K >> 6;
+    const float s = s_abs[row];
+    const float r = s > 0.0f ? 127.0f / s : 0.0f;
+    for (int kt = wave; kt < KT; kt += 4) {
+        const float4 *w = (const float4 *)(W + (size_t)(p * 16 + row) * K + kt * 64 + kg * 16);
+        v4i out;
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            float4 a = w[i];
+            out[i] = pack4(q8(a.x, r), q8(a.y, r), q8(a.z, r), q8(a.w, r));
+        }
+        *(v4i *)(wt + ((size_t)(p * KT + kt) * 64 + lane) * 16) = out;
+    }
+}
+
+__global__ void __launch_bounds__(256) k_untile_weight(const int8_t *__restrict__ wt, int K,
+                                                       int8_t *__restrict__ wq) {
+    const int p = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int row = lane & 15, kg = lane >> 4, KT = K >> 6;
+    for (int kt = wave; kt < KT; kt += 4) {
+        v4i v = *(const v4i *)(wt + ((size_t)(p * KT + kt) * 64 + lane) * 16);
+        *(v4i *)(wq + (size_t)(p * 16 + row) * K + kt * 64 + kg * 16) = v;
+    }
+}
+
+__global__ void k_fill_u32(uint32_t *p, size_t n, uint32_t v) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+__global__ void k_copy_bytes(const uint8_t *__restrict__ s, uint8_t *__restrict__ d, size_t n) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) d[i] = s[i];
+}
+
+// -------------------------------------------------------------- LayerNorm
+
+// One workgroup per row; fp32 moments (mean, then centred second moment).
+template <int NT>
+__device__ __forceinline__ void row_moments(const __half *x, int H, float *sm, float &mean, float &inv, float eps) {
+    float s = 0.0f;
+    for (int k = threadIdx.x * 2; k < H; k += NT * 2) {
+        float2 v = __half22float2(*(const __half2 *)(x + k));
+        s += v.x + v.y;
+    }
+    mean = block_sum<NT / 64>(s, sm) / (float)H;
+    float q = 0.0f;
+    for (int k = threadIdx.x * 2; k < H; k += NT * 2) {
+        float2 v = __half22float2(*(const __half2 *)(x + k));
+        float a = v.x - mean, b = v.y - mean;
+        q += a * a + b * b;
+    }
+    float var = block_sum<NT / 64>(q, sm) / (float)H;
+    inv = 1.0f / sqrtf(var + eps);
+}
+
+__global__ void __launch_bounds__(256) k_layernorm(const __half *__restrict__ x, const __half *__restrict__ g,
+                                                   const __half *__restrict__ b, float eps, int H,
+                                                   __half *__restrict__ y) {
+    __shared__ float sm[4];
+    const __half *xr = x + (size_t)blockIdx.x * H;
+    __half *yr = y + (size_t)blockIdx.x * H;
+    float mean, inv;
+    row_moments<256>(xr, H, sm, mean, inv, eps);
+    for (int k = threadIdx.x * 2; k < H; k += 512) {
+        float2 v = __half22float2(*(const __half2 *)(xr + k));
+        float2 gg = __half22float2(*(const __half2 *)(g + k));
+        float2 bb = __half22float2(*(const __half2 *)(b + k));
+        *(__half2 *)(yr + k) = __floats2half2_rn((v.x - mean) * inv * gg.x + bb.x, (v.y - mean) * inv * gg.y + bb.y);
+    }
+}
+
+// ------------------------------------------- one-row detect + quantize (decode)
+
+// The row sits in LDS as fp16.  Marks outlier columns (|y| >= theta), takes the
+// absolute maximum of the remaining columns, writes int8 codes (0 on outliers).
+// 1024 threads; H % 64 == 0.
+__device__ __forceinline__ void row_detect_quantize(const __half *ys, int H, float theta, uint32_t *mask_lds,
+                                                    float *sm, int8_t *xq, uint32_t *mask, float *sx) {
+    const int lane = threadIdx.x & 63;
+    float m = 0.0f;
+    for (int k0 = (threadIdx.x >> 6) * 64; k0 < H; k0 += 1024) {       // wave-uniform
+        float a = fabsf(__half2float(ys[k0 + lane]));
+        bool out = a >= theta;
+        unsigned long long bal = __ballot(out);
+        if (lane == 0) {
+            mask_lds[k0 >> 5] = (uint32_t)bal;
+            mask_lds[(k0 >> 5) + 1] = (uint32_t)(bal >> 32);
+            mask[k0 >> 5] = (uint32_t)bal;
+            mask[(k0 >> 5) + 1] = (uint32_t)(bal >> 32);
+        }
+        if (!out) m = fmaxf(m, a);
+    }
+    const float s = block_max<16>(m, sm);   // also orders the mask_lds writes before the reads below
+    if (threadIdx.x == 0) *sx = s;
+    const float r = s > 0.0f ? 127.0f / s : 0.0f;
+    for (int k = threadIdx.x * 4; k < H; k += 4096) {
+        uint32_t bits = (mask_lds[k >> 5] >> (k & 31)) & 0xfu;
+        int c[4];
+#pragma unroll
+        for (int j = 0; j < 4; j++) c[j] = ((bits >> j) & 1u) ? 0 : q8(__half2float(ys[k + j]), r);
+        *(int *)(xq + k) = pack4(c[0], c[1], c[2], c[3]);
+    }
+}
+
+__global__ void __launch_bounds__(1024) k_ln_quant_row(const __half *__restrict__ x, const __half *__restrict__ g,
+                                                       const __half *__restrict__ b, float eps, int H, float theta,
+                                                       __half *__restrict__ y, int8_t *__restrict__ xq,
+                                                       uint32_t *__restrict__ mask, float *__restrict__ sx) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    __half *ys = (__half *)lds;                            // H halves
+    uint32_t *mask_lds = (uint32_t *)(lds + (size_t)H * 2);   // H/32 words
+    __shared__ float sm[16];
+    float mean, inv;
+    row_moments<1024>(x, H, sm, mean, inv, eps);
+    for (int k = threadIdx.x * 2; k < H; k += 2048) {
+        float2 v = __half22float2(*(const __half2 *)(x + k));
+        float2 gg = __half22float2(*(const __half2 *)(g + k));
+        float2 bb = __half22float2(*(const __half2 *)(b + k));
+        __half2 o = __floats2half2_rn((v.x - mean) * inv * gg.x + bb.x, (v.y - mean) * inv * gg.y + bb.y);
+        *(__half2 *)(ys + k) = o;
+        *(__half2 *)(y + k) = o;
+    }
+    __syncthreads();
+    row_detect_quantize(ys, H, theta, mask_lds, sm, xq, mask, sx);
+}
+
+__global__ void __launch_bounds__(1024) k_rowquant_row(const __half *__restrict__ x, int K, float theta,
+                                                       int8_t *__restrict__ xq, uint32_t *__restrict__ mask,
+                                                       float *__restrict__ sx) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    uint32_t *mask_lds = (uint32_t *)lds;                  // K/32 words; the row itself is read from global
+    __shared__ float sm[16];
+    row_detect_quantize(x, K, theta, mask_lds, sm, xq, mask, sx);
+}
+
+// -------------------------------------------------- many rows: mask, then quantize
+
+// Column c is an outlier if any row reaches theta.  grid.x covers columns (64 per
+// wave), grid.y covers 64-row slabs; slabs combine with atomicOr (order-free).
+__global__ void __launch_bounds__(256) k_colmask(const __half *__restrict__ X, int M, int K, float theta,
+                                                 uint32_t *__restrict__ mask) {
+    const int k0 = blockIdx.x * 256 + (threadIdx.x >> 6) * 64;
+    if (k0 >= K) return;                                   // wave-uniform
+    const int lane = threadIdx.x & 63;
+    const int t0 = blockIdx.y * 64, t1 = min(M, t0 + 64);
+    float m = 0.0f;
+    for (int t = t0; t < t1; t++) m = fmaxf(m, fabsf(__half2float(X[(size_t)t * K + k0 + lane])));
+    unsigned long long bal = __ballot(m >= theta);
+    if (lane == 0) {
+        if ((uint32_t)bal) atomicOr(&mask[k0 >> 5], (uint32_t)bal);
+        if ((uint32_t)(bal >> 32)) atomicOr(&mask[(k0 >> 5) + 1], (uint32_t)(bal >> 32));
+    }
+}
+
+// One workgroup per row of the 16-padded row range.  Row scale = absolute maximum over
+// non-outlier columns; codes go to the MFMA operand tile order (same tiling as the
+// weights, rows = tokens); padding rows are written as zeros.
+__global__ void __launch_bounds__(256) k_rowquant_tiled(const __half *__restrict__ X, int M, int K,
+                                                        const uint32_t *__restrict__ mask,
+                                                        int8_t *__restrict__ xq_tiled, float *__restrict__ sx,
+                                                        int8_t *__restrict__ xq_dbg) {
+    __shared__ float sm[4];
+    const int t = blockIdx.x, KT = K >> 6, nchunk = K >> 4;
+    const uint16_t *mask16 = (const uint16_t *)mask;
+    const size_t tile_row = (size_t)(t >> 4) * KT;
+    if (t >= M) {
+        for (int c = threadIdx.x; c < nchunk; c += 256) {
+            v4i z = {0, 0, 0, 0};
+            *(v4i *)(xq_tiled + ((tile_row + (c >> 2)) * 64 + (c & 3) * 16 + (t & 15)) * 16) = z;
+        }
+        return;
+    }
+    const __half *xr = X + (size_t)t * K;
+    float m = 0.0f;
+    for (int c = threadIdx.x; c < nchunk; c += 256) {
+        const uint32_t bits = mask16[c];
+        v8h a = *(const v8h *)(xr + c * 16), b = *(const v8h *)(xr + c * 16 + 8);
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            if (!((bits >> j) & 1u)) m = fmaxf(m, fabsf((float)a[j]));
+            if (!((bits >> (j + 8)) & 1u)) m = fmaxf(m, fabsf((float)b[j]));
+        }
+    }
+    const float s = block_max<4>(m, sm);
+    if (threadIdx.x == 0) sx[t] = s;
+    const float r = s > 0.0f ? 127.0f / s : 0.0f;
+    for (int c = threadIdx.x; c < nchunk; c += 256) {
+        const uint32_t bits = mask16[c];
+        v8h a = *(const v8h *)(xr + c * 16), b = *(const v8h *)(xr + c * 16 + 8);
+        int q[16];
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            q[j] = ((bits >> j) & 1u) ? 0 : q8((float)a[j], r);
+            q[j + 8] = ((bits >> (j + 8)) & 1u) ? 0 : q8((float)b[j], r);
+        }
+        v4i o;
+#pragma unroll
+        for (int i = 0; i < 4; i++) o[i] = pack4(q[4 * i], q[4 * i + 1], q[4 * i + 2], q[4 * i + 3]);
+        *(v4i *)(xq_tiled + ((tile_row + (c >> 2)) * 64 + (c & 3) * 16 + (t & 15)) * 16) = o;
+        if (xq_dbg) *(v4i *)(xq_dbg + (size_t)t * K + c * 16) = o;
+    }
+}
+
+__global__ void k_mask_to_bytes(const uint32_t *__restrict__ mask, int K, uint8_t *__restrict__ out) {
+    int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k < K) out[k] = (mask[k >> 5] >> (k & 31)) & 1u;
+}
+
+// ------------------------------------------------------------------- codec
+
+// One workgroup per block of `block` elements (last block may be short).
+__global__ void __launch_bounds__(256) k_hidden_quantize(const __half *__restrict__ x, size_t n, int block,
+                                                         CodeTable tab, uint8_t *__restrict__ q,
+                                                         float *__restrict__ absmax) {
+    __shared__ float mids[256];
+    __shared__ float sm[4];
+    if (threadIdx.x < 255) mids[threadIdx.x] = (tab.code[threadIdx.x] + tab.code[threadIdx.x + 1]) * 0.5f;
+    const size_t b0 = (size_t)blockIdx.x * block;
+    const int len = (int)min((size_t)block, n - b0);
+    float m = 0.0f;
+    for (int i = threadIdx.x; i < len; i += 256) m = fmaxf(m, fabsf(__half2float(x[b0 + i])));
+    const float a = block_max<4>(m, sm);    // its barrier also publishes mids
+    if (threadIdx.x == 0) absmax[blockIdx.x] = a;
+    for (int i = threadIdx.x; i < len; i += 256) {
+        const float v = a > 0.0f ? __half2float(x[b0 + i]) / a : 0.0f;
+        int lo = 0, hi = 255;               // count of midpoints strictly below v
+        while (lo < hi) {
+            int mid = (lo + hi) >> 1;
+            if (mids[mid] < v) lo = mid + 1; else hi = mid;
+        }
+        q[b0 + i] = (uint8_t)lo;
+    }
+}
+
+__global__ void __launch_bounds__(256) k_hidden_dequantize(const uint8_t *__restrict__ q,
+                                                           const float *__restrict__ absmax, size_t n, int block,
+                                                           CodeTable tab, __half *__restrict__ y) {
+    __shared__ float code[256];
+    code[threadIdx.x] = tab.code[threadIdx.x];
+    __syncthreads();
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) y[i] = __float2half_rn(code[q[i]] * absmax[i / (size_t)block]);
+}
+
+// ------------------------------------------------------------- cache copies
+
+// cache [nh][cap][d] (keys) + [nh][cap][d] (values)  <->  packed [2][nh][len][d]
+__global__ void k_kv_copy(__half *cache, int nh, int cap, int d, int len, __half *packed, int to_cache) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t total = (size_t)2 * nh * len * d;
+    if (i >= total) return;
+    int c = (int)(i % d);
+    size_t r = i / d;
+    int pos = (int)(r % len);
+    size_t ph = r / len;     // p * nh + h
+    size_t ci = (ph * cap + pos) * d + c;
+    if (to_cache) cache[ci] = packed[i]; else packed[i] = cache[ci];
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ launchers
+
+hipError_t ps_quantize_weight(const float *W, int N, int K, int8_t *wt, float *sw, hipStream_t st) {
+    k_quantize_weight<<<N / 16, 256, 0, st>>>(W, K, wt, sw);
+    return hipGetLastError();
+}
+hipError_t ps_untile_weight(const int8_t *wt, int N, int K, int8_t *wq, hipStream_t st) {
+    k_untile_weight<<<N / 16, 256, 0, st>>>(wt, K, wq);
+    return hipGetLastError();
+}
+hipError_t ps_fill_u32(uint32_t *p, size_t n, uint32_t v, hipStream_t st) {
+    if (n == 0) return hipSuccess;
+    k_fill_u32<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(p, n, v);
+    return hipGetLastError();
+}
+hipError_t ps_copy_bytes(const void *src, void *dst, size_t n, hipStream_t st) {
+    if (n == 0) return hipSuccess;
+    k_copy_bytes<<<(unsigned)((n + 255) / 256), 256, 0, st>>>((const uint8_t *)src, (uint8_t *)dst, n);
+    return hipGetLastError();
+}
+hipError_t ps_layernorm(const __half *x, const __half *g, const __half *b, float eps, int M, int H, __half *y,
+                        hipStream_t st) {
+    k_layernorm<<<M, 256, 0, st>>>(x, g, b, eps, H, y);
+    return hipGetLastError();
+}
+hipError_t ps_ln_quant_row(const __half *x, const __half *g, const __half *b, float eps, int H, float theta,
+                           __half *y, int8_t *xq, uint32_t *mask, float *sx, hipStream_t st) {
+    size_t lds = (size_t)H * 2 + (size_t)H / 8 + 16;
+    k_ln_quant_row<<<1, 1024, lds, st>>>(x, g, b, eps, H, theta, y, xq, mask, sx);
+    return hipGetLastError();
+}
+hipError_t ps_rowquant_row(const __half *x, int K, float theta, int8_t *xq, uint32_t *mask, float *sx,
+                           hipStream_t st) {
+    size_t lds = (size_t)K / 8 + 16;
+    k_rowquant_row<<<1, 1024, lds, st>>>(x, K, theta, xq, mask, sx);
+    return hipGetLastError();
+}
+hipError_t ps_colmask(const __half *X, int M, int K, float theta, uint32_t *mask, hipStream_t st) {
+    dim3 grid((K + 255) / 256, (M + 63) / 64);
+    k_colmask<<<grid, 256, 0, st>>>(X, M, K, theta, mask);
+    return hipGetLastError();
+}
+hipError_t ps_rowquant_tiled(const __half *X, int M, int K, const uint32_t *mask, int8_t *xq_tiled, float *sx,
+                             int8_t *xq_dbg, hipStream_t st) {
+    k_rowquant_tiled<<<(M + 15) / 16 * 16, 256, 0, st>>>(X, M, K, mask, xq_tiled, sx, xq_dbg);
+    return hipGetLastError();
+}
+hipError_t ps_mask_to_bytes(const uint32_t *mask, int K, uint8_t *out, hipStream_t st) {
+    k_mask_to_bytes<<<(K + 255) / 256, 256, 0, st>>>(mask, K, out);
+    return hipGetLastError();
+}
+hipError_t ps_hidden_quantize(const __half *x, size_t n, int block, const CodeTable &tab, uint8_t *q, float *absmax,
+                              hipStream_t st) {
+    if (n == 0) return hipSuccess;
+    k_hidden_quantize<<<(unsigned)((n + block - 1) / block), 256, 0, st>>>(x, n, block, tab, q, absmax);
+    return hipGetLastError();
+}
+hipError_t ps_hidden_dequantize(const uint8_t *q, const float *absmax, size_t n, int block, const CodeTable &tab,
+                                __half *y, hipStream_t st) {
+    if (n == 0) return hipSuccess;
+    k_hidden_dequantize<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(q, absmax, n, block, tab, y);
+    return hipGetLastError();
+}
+hipError_t ps_kv_export(const __half *kv, int nh, int cap, int d, int len, __half *out, hipStream_t st) {
+    size_t total = (size_t)2 * nh * len * d;
+    if (total == 0) return hipSuccess;
+    k_kv_copy<<<(unsigned)((total + 255) / 256), 256, 0, st>>>((__half *)kv, nh, cap, d, len, out, 0);
+    return hipGetLastError();
+}
+hipError_t ps_kv_import(__half *kv, int nh, int cap, int d, int len, const __half *in, hipStream_t st) {
+    size_t total = (size_t)2 * nh * len * d;
+    if (total == 0) return hipSuccess;
+    k_kv_copy<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(kv, nh, cap, d, len, (__half *)in, 1);
+    return hipGetLastError();
+}

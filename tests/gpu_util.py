@@ -1,0 +1,44 @@
+"""Helpers shared by the GPU parity tests."""
+import numpy as np
+import torch
+
+import oracle
+from paper_2209_01188_amd import binding, synth
+
+DEV = "cuda:0"
+
+
+def to_dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def to_np(t):
+    return t.detach().cpu().numpy()
+
+
+def hidden_close(got, ref, what="", rel=3e-3, max_abs=2e-2):
+    """The benchmark's tolerance for fp16 hidden states against the oracle: relative L2 <= 3e-3 and, per element,
+    |diff| <= 2e-2 or one fp16 ulp of the oracle value (above |x| = 16 an ulp alone exceeds 2e-2)."""
+    g, r = got.astype(np.float64), ref.astype(np.float64)
+    relerr = np.linalg.norm(g - r) / max(np.linalg.norm(r), 1e-30)
+    diff = np.abs(g - r)
+    ulp = np.spacing(np.abs(ref).astype(np.float16)).astype(np.float64)
+    bad = diff > np.maximum(max_abs, ulp)
+    assert relerr <= rel, "%s rel-L2 %.3e" % (what, relerr)
+    assert not bad.any(), "%s max-abs %.3e at %s" % (what, diff.max(), np.argwhere(bad)[:4].tolist())
+    return relerr, diff.max()
+
+
+def build_pair(cfg, n_blocks=None, theta=6.0, max_rows=None):
+    """The same synthetic span loaded into the oracle and into the GPU library."""
+    nb = n_blocks or cfg.n_blocks
+    rows = max_rows or max(cfg.batch * max(cfg.prompt, 1), 1)
+    osp = oracle.Span(nb, cfg.hidden, cfg.n_heads, cfg.F, 1e-5, theta)
+    gsp = binding.Span(nb, cfg.hidden, cfg.n_heads, cfg.F, rows, 1e-5, theta, DEV)
+    params = []
+    for b in range(nb):
+        p = synth.block_params(cfg, b)
+        osp.load_block(b, p)
+        gsp.load_block(b, p)
+        params.append(p)
+    return osp, gsp, params

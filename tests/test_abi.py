@@ -1,0 +1,88 @@
+"""The C-ABI library loads without a GPU, exports what the header declares, and its host-side
+argument checks return error codes before any device work.  No GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def b():
+    from paper_2209_01188_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):
+        build.build(force=False)
+    return binding
+
+
+def test_library_exports_every_declared_symbol(b):
+    header = open(os.path.join(ROOT, "include", "petals_span.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(petals_[a-z0-9_]+)\s*\(", header))
+    assert len(declared) >= 19
+    L = b.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert declared == set(b.EXPORTS)
+
+
+def test_size_queries_match_the_layout_arithmetic(b):
+    cfg = b.make_config(12, 14336, 112, 57344, 1)
+    H = 14336
+    wb = b.petals_span_weight_bytes(cfg)
+    # int8 weights 12 H^2 per block dominate; scales, biases and LayerNorm add < 0.1 %
+    assert 12 * 12 * H * H <= wb <= 12 * 12 * H * H * 1.001
+    assert b.petals_span_kv_bytes(cfg, 2049) == 12 * 2 * H * 2049 * 2
+    assert b.petals_span_workspace_bytes(cfg) > 0
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(hidden=100), -3),           # not a multiple of 64
+    (dict(n_heads=7), -1),            # hidden % heads
+    (dict(hidden=64 * 24, n_heads=2), -3),   # head_dim 768
+    (dict(ffn=131072), -3),           # int32 accumulator overflow
+    (dict(n_blocks=0), -1),
+    (dict(max_rows_per_call=70000), -3),
+])
+def test_bad_configs_are_rejected(b, kw, code):
+    args = dict(n_blocks=2, hidden=64, n_heads=4, ffn=256, max_rows_per_call=8)
+    args.update(kw)
+    cfg = b.make_config(**args)
+    with pytest.raises(b.PetalsError) as e:
+        b.petals_span_weight_bytes(cfg)
+    assert e.value.code == code and str(e.value)
+
+
+def test_host_side_checks_need_no_device(b):
+    cfg = b.make_config(2, 64, 4, 256, 8)
+    fake = C.c_void_p(0x10000)        # aligned, never dereferenced: create enqueues nothing
+    L = b.lib()
+    span = C.c_void_p()
+    assert L.petals_span_create(C.byref(cfg), fake, C.c_void_p(0x10001), C.byref(span)) == -1   # misaligned
+    assert L.petals_span_create(C.byref(cfg), fake, fake, C.byref(span)) == 0
+    sess = C.c_void_p()
+    assert L.petals_session_open(span, fake, 4, C.byref(sess)) == 0
+    n = C.c_int32(-1)
+    assert L.petals_session_length(sess, C.byref(n)) == 0 and n.value == 0
+    arr = (C.c_void_p * 2)(sess.value, sess.value)
+    # every check below fails before a kernel would be launched
+    assert L.petals_span_prefill(span, arr, 1, 5, fake, C.c_void_p(0x20000), None) == -2      # 5 > capacity 4
+    assert L.petals_span_prefill(span, arr, 1, 9, fake, C.c_void_p(0x20000), None) == -2      # 9 > max rows
+    assert L.petals_span_prefill(span, arr, 2, 1, fake, C.c_void_p(0x20000), None) == -1      # duplicate
+    assert L.petals_span_prefill(span, arr, 1, 1, fake, fake, None) == -1                     # aliasing
+    assert L.petals_span_prefill(span, arr, 1, 1, fake, C.c_void_p(0x20000), None) == -4      # blocks not loaded
+    assert b"loaded" in L.petals_last_error()
+    assert L.petals_session_length(sess, C.byref(n)) == 0 and n.value == 0                    # nothing changed
+    assert L.petals_span_destroy(span) == -4                                                  # session still open
+    assert L.petals_session_close(sess) == 0
+    assert L.petals_span_destroy(span) == 0
+    assert L.petals_hidden_quantize(fake, C.c_size_t(10), 100, fake, fake, None) == -1        # block % 64
+
+
+def test_code_table_bits_equal_the_oracle_table(b):
+    import numpy as np
+    import oracle
+    t = np.array(b.petals_hidden_code_table(), np.float32)
+    assert np.array_equal(t.view(np.uint32), oracle.codebook().view(np.uint32))

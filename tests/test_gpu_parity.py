@@ -1,0 +1,282 @@
+"""GPU parity: the HIP library through its C ABI against the CPU oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2209_01188_amd import binding, synth
+from tests.gpu_util import DEV, build_pair, hidden_close, to_dev, to_np
+
+pytestmark = pytest.mark.gpu
+INF = float("inf")
+C1, C2, C3 = synth.CONFIGS["C1"], synth.CONFIGS["C2"], synth.CONFIGS["C3"]
+
+
+# ------------------------------------------------------------- weight load
+
+@pytest.mark.parametrize("N,K", [(16, 64), (48, 192), (192, 64), (1024, 4096), (4096, 1024)])
+def test_weight_quantization_bit_exact(N, K):
+    r = np.random.default_rng(N + K)
+    W = (r.standard_normal((N, K)) * 0.02).astype(np.float32)
+    W[3] = 0.0                                  # an all-zero row
+    W[5, 7] = W[5].max() * 2                    # a row whose maximum is an isolated spike
+    # drive the span API with a one-block span whose dense linear has this shape? shapes are tied to H,F:
+    # use H = K, F = N when they fit the (N,K) = (F,H) "up" linear
+    H, F = K, N
+    if H % 64 or F % 64:
+        pytest.skip("shape does not form a span")
+    nh = H // 64 if H >= 64 else 1
+    sp = binding.Span(1, H, nh, F, 4, device=DEV)
+    p = synth.block_params(synth.scaled(C1, hidden=H, n_heads=nh, ffn=F), 0)
+    p["w_up"] = W
+    sp.load_block(0, p)
+    wq, sw = sp.export_weight(0, 2)
+    rq, rs = oracle.quantize_weight(W)
+    assert np.array_equal(to_np(sw).view(np.uint32), rs.view(np.uint32))
+    assert np.array_equal(to_np(wq), rq)
+    # the other three linears of the block as well
+    for which, name in ((0, "w_qkv"), (1, "w_dense"), (3, "w_down")):
+        wq, sw = sp.export_weight(0, which)
+        rq, rs = oracle.quantize_weight(p[name])
+        assert np.array_equal(to_np(wq), rq) and np.array_equal(to_np(sw), rs)
+    sp.close()
+
+
+# --------------------------------------------------- teacher-forced linears
+
+def _linear_case(cfg, theta, M, which, epilogue, seed, outlier_cols=3):
+    """One linear of block 0 on random fp16 rows with a few outlier columns; integer parts bit-exact."""
+    osp, gsp, params = build_pair(cfg, n_blocks=1, theta=theta, max_rows=max(M, 1))
+    N, K = gsp.shapes(which)
+    r = np.random.default_rng(seed)
+    X = r.standard_normal((M, K))
+    cols = r.choice(K, size=min(outlier_cols, K), replace=False)
+    X[:, cols] = r.uniform(6.5, 40, size=(M, len(cols))) * r.choice([-1, 1], size=len(cols))
+    if M > 2:
+        X[1] = 0.0                               # a zero row
+        X[2, :] = 0.0
+        X[2, cols[0]] = 9.0                      # zero outside the outlier set
+    X = X.astype(np.float16)
+    resid = (r.standard_normal((M, N)) * 4).astype(np.float16) if epilogue == 2 else None
+    wq, sw = osp.get_weight(0, which)
+    bias = params[0][("b_qkv", "b_dense", "b_up", "b_down")[which]]
+    Y, dbg = oracle.linear(X, wq, sw, bias, theta, epilogue, resid, want_debug=True)
+    out = gsp.debug_linear(0, which, to_dev(X), epilogue, None if resid is None else to_dev(resid))
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(out["mask"]), dbg["mask"]), "outlier set"
+    assert np.array_equal(to_np(out["sx"]).view(np.uint32), dbg["sx"].view(np.uint32)), "row scales"
+    assert np.array_equal(to_np(out["xq"]), dbg["xq"]), "int8 codes"
+    assert np.array_equal(to_np(out["acc"]), dbg["acc"]), "int32 accumulators"
+    hidden_close(to_np(out["y"]), Y, "linear %d M=%d" % (which, M))
+    gsp.close(); osp.destroy()
+
+
+@pytest.mark.parametrize("M", [1, 2, 5, 16, 17, 33, 64, 65, 130, 200])
+@pytest.mark.parametrize("which,epilogue", [(0, 0), (1, 2), (2, 1), (3, 2)])
+def test_linear_c1_shapes(M, which, epilogue):
+    _linear_case(C1, 6.0, M, which, epilogue, seed=M * 10 + which)
+
+
+@pytest.mark.parametrize("theta", [0.0, INF])
+@pytest.mark.parametrize("M", [1, 7, 150])
+def test_linear_threshold_extremes(theta, M):
+    _linear_case(C1, theta, M, 2, 1, seed=M)
+    _linear_case(C1, theta, M, 3, 2, seed=M + 1)
+
+
+@pytest.mark.parametrize("M", [1, 3, 24, 48, 136])
+@pytest.mark.parametrize("which,epilogue", [(0, 0), (2, 1), (3, 2)])
+def test_linear_c2_shapes(M, which, epilogue):
+    # K = 1024 / 4096: several tiles per wave, ragged M
+    _linear_case(C2, 6.0, M, which, epilogue, seed=M + which, outlier_cols=5)
+
+
+def test_linear_dense_outlier_sets():
+    # every 64-column tile holds outliers, and one tile is all outliers
+    cfg = C2
+    osp, gsp, params = build_pair(cfg, n_blocks=1, max_rows=20)
+    for M in (1, 20):
+        r = np.random.default_rng(M)
+        X = r.standard_normal((M, cfg.hidden))
+        X[:, ::37] = 7.0
+        X[:, 128:192] = -8.0
+        X = X.astype(np.float16)
+        wq, sw = osp.get_weight(0, 2)
+        Y, dbg = oracle.linear(X, wq, sw, params[0]["b_up"], 6.0, 1, want_debug=True)
+        out = gsp.debug_linear(0, 2, to_dev(X), 1)
+        assert np.array_equal(to_np(out["mask"]), dbg["mask"]) and np.array_equal(to_np(out["xq"]), dbg["xq"])
+        assert np.array_equal(to_np(out["acc"]), dbg["acc"])
+        hidden_close(to_np(out["y"]), Y, "dense outliers M=%d" % M)
+    gsp.close(); osp.destroy()
+
+
+# --------------------------------------------------------------- end to end
+
+def _run_generation(cfg, nb, B, T, steps, theta=6.0, cap=None):
+    osp, gsp, _ = build_pair(cfg, n_blocks=nb, theta=theta, max_rows=B * T)
+    cap = cap or (T + steps)
+    oses = [osp.open_session(cap) for _ in range(B)]
+    gses = [gsp.open_session(cap) for _ in range(B)]
+    outs = []
+    X = synth.hidden_states(cfg, 0, B, T)
+    Yo = osp.step(oses, X)
+    Yg = to_np(gsp.prefill(gses, to_dev(X)))
+    outs.append((Yg, Yo))
+    for i in range(1, steps + 1):
+        x = synth.hidden_states(cfg, i, B, 1)
+        yo = osp.step(oses, x)
+        yg = to_np(gsp.decode_step(gses, to_dev(x[:, 0])))
+        outs.append((yg[:, None, :], yo))
+    return osp, gsp, oses, gses, outs
+
+
+def test_c1_prefill_then_decode_end_to_end():
+    osp, gsp, oses, gses, outs = _run_generation(C1, C1.n_blocks, 1, C1.prompt, C1.decode)
+    for i, (g, o) in enumerate(outs):
+        hidden_close(g, o, "C1 call %d" % i)
+    assert gses[0].length == oses[0].length == C1.prompt + C1.decode
+    for b in range(C1.n_blocks):
+        hidden_close(to_np(gses[0].export_kv(b)), oses[0].export_kv(b), "C1 kv block %d" % b)
+    gsp.close(); osp.destroy()
+
+
+def test_c2_shape_reduced_depth_end_to_end():
+    osp, gsp, oses, gses, outs = _run_generation(C2, 4, 1, 128, 6)
+    for i, (g, o) in enumerate(outs):
+        hidden_close(g, o, "C2 call %d" % i)
+    hidden_close(to_np(gses[0].export_kv(3)), oses[0].export_kv(3), "C2 kv")
+    gsp.close(); osp.destroy()
+
+
+def test_c3_shape_batched_sessions_with_codec_at_the_boundaries():
+    cfg = synth.scaled(C3, n_blocks=2, batch=3, prompt=40)
+    B, T = 3, 40
+    osp, gsp, _ = build_pair(cfg, n_blocks=2, max_rows=B * T)
+    oses = [osp.open_session(48) for _ in range(B)]
+    gses = [gsp.open_session(48) for _ in range(B)]
+    X = synth.hidden_states(cfg, 0, B, T)
+    # the span receives and returns 8-bit blockwise-quantized hidden states
+    q, am = oracle.hidden_quantize(X, 4096)
+    Xo = oracle.hidden_dequantize(q, am, 4096).reshape(B, T, -1)
+    Yo = osp.step(oses, Xo)
+    qo, amo = oracle.hidden_quantize(Yo, 4096)
+
+    xin = torch.empty((B, T, cfg.hidden), dtype=torch.float16, device=DEV)
+    binding.petals_hidden_dequantize(to_dev(q), to_dev(am), 4096, xin)
+    assert np.array_equal(to_np(xin).view(np.uint16), Xo.view(np.uint16))
+    Yg = gsp.prefill(gses, xin)
+    qg = torch.empty(Yg.numel(), dtype=torch.uint8, device=DEV)
+    amg = torch.empty((Yg.numel() + 4095) // 4096, dtype=torch.float32, device=DEV)
+    binding.petals_hidden_quantize(Yg, 4096, qg, amg)
+    hidden_close(to_np(Yg), Yo, "C3 prefill")
+    # decode steps with all sessions in one call
+    for i in (1, 2):
+        x = synth.hidden_states(cfg, i, B, 1)
+        hidden_close(to_np(gsp.decode_step(gses, to_dev(x[:, 0])))[:, None], osp.step(oses, x), "C3 decode %d" % i)
+    gsp.close(); osp.destroy()
+
+
+def test_sessions_with_different_lengths_and_replay_is_bitwise():
+    cfg = C1
+    osp, gsp, _ = build_pair(cfg, max_rows=16)
+    calls = [(synth.hidden_states(cfg, 0, 1, 5), [0]), (synth.hidden_states(cfg, 1, 1, 2), [1]),
+             (synth.hidden_states(cfg, 2, 2, 1), [0, 1]), (synth.hidden_states(cfg, 3, 2, 3), [1, 0])]
+
+    def run(span, is_gpu):
+        ses = [span.open_session(16) for _ in range(2)]
+        res = []
+        for X, who in calls:
+            if is_gpu:
+                res.append(to_np(span.prefill([ses[i] for i in who], to_dev(X))))
+            else:
+                res.append(span.step([ses[i] for i in who], X))
+        return ses, res
+    oses, ores = run(osp, False)
+    gses, gres = run(gsp, True)
+    for g, o in zip(gres, ores):
+        hidden_close(g, o, "ragged sessions")
+    assert [s.length for s in gses] == [s.length for s in oses] == [9, 6]
+    # failure recovery: the same calls into fresh sessions rebuild identical state, bit for bit
+    gses2, gres2 = run(gsp, True)
+    for a, b in zip(gres, gres2):
+        assert np.array_equal(a.view(np.uint16), b.view(np.uint16))
+    for b in range(cfg.n_blocks):
+        assert torch.equal(gses[0].export_kv(b), gses2[0].export_kv(b))
+    gsp.close(); osp.destroy()
+
+
+def test_cached_decode_matches_full_prefill_on_gpu():
+    # theta = inf: rows are independent, so token-by-token decode reproduces the prefill rows
+    osp, gsp, _ = build_pair(C1, theta=INF, max_rows=8)
+    X = synth.hidden_states(C1, 0, 1, 8)
+    s1, s2 = gsp.open_session(8), gsp.open_session(8)
+    full = to_np(gsp.prefill([s1], to_dev(X)))
+    inc = np.concatenate([to_np(gsp.decode_step([s2], to_dev(X[:, t]))) for t in range(8)])[None]
+    hidden_close(inc, full, "decode vs prefill", rel=1e-3)
+    gsp.close(); osp.destroy()
+
+
+def test_kv_import_then_decode_at_a_long_prefix():
+    # several key ranges per head (split attention) on a C2-shaped block
+    cfg = synth.scaled(C2, n_blocks=1)
+    osp, gsp, _ = build_pair(cfg, n_blocks=1, max_rows=2)
+    for L in (255, 256, 700):
+        ose, gse = osp.open_session(L + 2), gsp.open_session(L + 2)
+        kv = synth.kv_prefix(cfg, 0, 0, L, std=1.5)
+        ose.import_kv(0, kv); gse.import_kv(0, to_dev(kv))
+        for i in (1, 2):
+            x = synth.hidden_states(cfg, i, 1, 1)
+            hidden_close(to_np(gsp.decode_step([gse], to_dev(x[:, 0])))[:, None], osp.step([ose], x), "L=%d" % L)
+        assert gse.length == L + 2
+        gse.close(); ose.close()
+    gsp.close(); osp.destroy()
+
+
+# -------------------------------------------------------------------- codec
+
+@pytest.mark.parametrize("n", [64, 4095, 4096, 4097, 14336, 8 * 14336 + 5])
+def test_codec_bit_exact(n):
+    r = np.random.default_rng(n)
+    x = (r.standard_normal(n) * r.choice([0.01, 1.0, 30.0], size=n)).astype(np.float16)
+    x[: min(n, 64)] = 0
+    q, am = oracle.hidden_quantize(x, 4096)
+    qg = torch.empty(n, dtype=torch.uint8, device=DEV)
+    amg = torch.empty((n + 4095) // 4096, dtype=torch.float32, device=DEV)
+    binding.petals_hidden_quantize(to_dev(x), 4096, qg, amg)
+    assert np.array_equal(to_np(amg).view(np.uint32), am.view(np.uint32))
+    assert np.array_equal(to_np(qg), q)
+    y = torch.empty(n, dtype=torch.float16, device=DEV)
+    binding.petals_hidden_dequantize(qg, amg, 4096, y)
+    assert np.array_equal(to_np(y).view(np.uint16), oracle.hidden_dequantize(q, am, 4096).view(np.uint16))
+
+
+def test_codec_every_finite_fp16_value():
+    x = np.arange(65536, dtype=np.uint16).view(np.float16)
+    x = x[np.isfinite(x)]
+    x = np.concatenate([x, np.zeros((-len(x)) % 64, np.float16)])
+    for block in (len(x) // 64 * 64 if len(x) <= 16384 else 16384, 64):
+        q, am = oracle.hidden_quantize(x, block)
+        qg = torch.empty(len(x), dtype=torch.uint8, device=DEV)
+        amg = torch.empty((len(x) + block - 1) // block, dtype=torch.float32, device=DEV)
+        binding.petals_hidden_quantize(to_dev(x), block, qg, amg)
+        assert np.array_equal(to_np(qg), q) and np.array_equal(to_np(amg), am)
+
+
+# ------------------------------------------------------------------- errors
+
+def test_capacity_and_state_errors_leave_sessions_untouched():
+    sp = binding.Span(2, 64, 4, 256, 8, device=DEV)
+    se = sp.open_session(4)
+    x = torch.zeros((1, 3, 64), dtype=torch.float16, device=DEV)
+    with pytest.raises(binding.PetalsError) as e:
+        sp.prefill([se], x)
+    assert e.value.code == -4                      # blocks not loaded
+    for b in range(2):
+        sp.load_block(b, synth.block_params(C1, b))
+    sp.prefill([se], x)
+    with pytest.raises(binding.PetalsError) as e:
+        sp.prefill([se], x)                        # 3 + 3 > 4
+    assert e.value.code == -2 and se.length == 3
+    with pytest.raises(binding.PetalsError):
+        sp.prefill([se, se], x[:, :1].repeat(2, 1, 1))
+    sp.close()
