@@ -1,0 +1,197 @@
+"""Benchmark: batch-1 decode through a 12-block BLOOM-176B-shaped span on one MI355X.
+
+One step = one token through all 12 blocks (LayerNorm, int8 QKV / dense / MLP linears with
+fp16 outlier columns, ALiBi attention against the session's KV cache).  Weights, KV prefix and
+hidden states are seeded synthetic tensors of the real shapes, resident in HBM before timing.
+Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def gemv_bytes(N, K):
+    """Algorithmic HBM bytes of one one-row linear: int8 weights, fp32 row scales, fp16 biases."""
+    return N * K + 4 * N + 2 * N
+
+
+def step_bytes(cfg, L):
+    """Algorithmic bytes of one decode step: per block the int8 weights (12 H^2), the row scales (36 H),
+    biases (18 H) and LayerNorm parameters (8 H); per session the cached keys/values read (4 (L+1) H), the
+    new ones written (4 H) and the hidden state in/out (4 H)."""
+    H = cfg.hidden
+    per_block = 12 * H * H + 36 * H + 18 * H + 8 * H + 4 * (L + 1) * H + 4 * H
+    return cfg.n_blocks * per_block + 4 * H
+
+
+def traffic_from_profile():
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary, if present."""
+    path = os.path.join(ROOT, "profiles", "k_gemv_row_c4_decode_pmc.txt")
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
+    return float(m.group(1)) if m else None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--prefix", type=int, default=2048, help="KV-cache prefix length of the headline figure")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile-events", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (a span per GPU; see DESIGN.md for how spans chain); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2209_01188_amd import binding, synth
+
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS["C4"]
+    H, F, nh, NB = cfg.hidden, cfg.F, cfg.n_heads, cfg.n_blocks
+    K, W = args.steps, args.warmup
+    prefixes = sorted(set(cfg.prefixes) | {args.prefix})
+
+    t_setup = time.time()
+    span = binding.Span(NB, H, nh, F, 1, 1e-5, 6.0, dev)
+    block0_host = None
+    for b in range(NB):
+        p = synth.block_params_device(cfg, b, dev)
+        span.load_block(b, p)
+        if b == 0 and not args.no_cpu_baseline:
+            block0_host = {k: v.cpu().numpy() for k, v in p.items()}
+        del p
+    torch.cuda.synchronize()
+    print("[bench] %d blocks loaded (%.1f GB int8) in %.1f s" % (NB, span.weight_mem.numel() / 1e9, time.time() - t_setup),
+          file=sys.stderr, flush=True)
+
+    # hidden-state inputs of all steps, resident on the device
+    n_calls = W + K
+    xs = torch.from_numpy(np.concatenate([synth.hidden_states(cfg, 1 + i, 1, 1)[0] for i in range(n_calls)])).to(dev)
+    out = torch.empty((1, H), dtype=torch.float16, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def timed_decode(L, profile):
+        se = span.open_session(L + n_calls + 1)
+        for b in range(NB):
+            se.import_kv(b, synth.kv_prefix_device(cfg, b, 0, L, 2.4, dev))
+        for i in range(W):
+            span.decode_step([se], xs[i:i + 1], out)
+        torch.cuda.synchronize()
+        if profile:
+            binding.petals_span_profile_begin(span.handle, K * NB * 8)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record(stream)
+        for i in range(W, W + K):
+            span.decode_step([se], xs[i:i + 1], out)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3
+        ms = max(e0.elapsed_time(e1), 0.0)
+        prof = binding.petals_span_profile_end(span.handle) if profile else None
+        se.close()
+        return max(ms, 0.0), wall_ms, prof
+
+    results = {}
+    for L in prefixes:
+        ms, wall_ms, prof = timed_decode(L, profile=not args.no_profile_events)
+        total = max(ms, wall_ms) if abs(ms - wall_ms) > 0.2 * wall_ms else ms
+        results[L] = dict(ms_per_step=total / K, tok_s=K / (total / 1e3), gbs=step_bytes(cfg, L) / (total / K / 1e3) / 1e9,
+                          prof=prof)
+        print("[bench] prefix %d: %.3f ms/step, %.1f tok/s, %.0f GB/s algorithmic" %
+              (L, results[L]["ms_per_step"], results[L]["tok_s"], results[L]["gbs"]), file=sys.stderr, flush=True)
+
+    main_r = results[args.prefix]
+    # dominant kernel: the one-row int8 linear (4 launches per block), from the events of the headline run
+    roofline = {"bound": "hbm", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None,
+                "traffic": traffic_from_profile(), "kernel": "k_gemv_row"}
+    if main_r["prof"] is not None:
+        ms_cls, n_cls = main_r["prof"]
+        n_gemv = n_cls[binding.PROFILE_GEMV]
+        if n_gemv:
+            per_block = sum(gemv_bytes(*span.shapes(i)) for i in range(4))
+            total_bytes = per_block * (n_gemv / 4.0)
+            achieved = total_bytes / (ms_cls[binding.PROFILE_GEMV] / 1e3) / 1e9
+            roofline.update(achieved=round(achieved, 1), frac=round(achieved / HBM_PEAK_GBS, 4),
+                            avg_launch_us=round(ms_cls[binding.PROFILE_GEMV] * 1e3 / n_gemv, 2), launches=n_gemv,
+                            bytes_per_launch=round(per_block / 4.0),
+                            attention_ms_per_step=round(ms_cls[binding.PROFILE_ATTENTION] / K, 4))
+
+    cpu_baseline = None
+    if block0_host is not None:
+        cpu_baseline = run_cpu_baseline(cfg, block0_host, dev)
+
+    line = {
+        "metric": "decode tokens/s per 12-block BLOOM-176B span (batch 1); achieved HBM GB/s",
+        "value": round(main_r["tok_s"], 2), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(main_r["ms_per_step"], 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "C4: 12-block BLOOM-176B-shaped span (H=14336, 112 heads, F=57344), int8 weights + fp16 "
+                               "outlier columns, batch-1 decode, KV prefix %d" % args.prefix,
+                   "prefix": args.prefix, "achieved_hbm_gbs": round(main_r["gbs"], 1),
+                   "hbm_frac_whole_step": round(main_r["gbs"] / HBM_PEAK_GBS, 4),
+                   "by_prefix": {str(L): {"tokens_per_s": round(r["tok_s"], 2), "ms_per_step": round(r["ms_per_step"], 4),
+                                          "achieved_hbm_gbs": round(r["gbs"], 1)} for L, r in results.items()}},
+        "roofline": roofline, "cpu_baseline": cpu_baseline,
+    }
+    span.close()
+    print(json.dumps(line))
+
+
+def run_cpu_baseline(cfg, block0_host, dev):
+    """The CPU oracle, as it stands, on a bounded sample: ONE of the 12 blocks, one decode step at prefix 128,
+    on this machine's host cores; tokens/s extrapolated to 12 blocks.  The same block runs on the GPU and the two
+    outputs are compared."""
+    import numpy as np
+    import torch
+    import oracle
+    from paper_2209_01188_amd import binding, synth
+
+    H, F, nh = cfg.hidden, cfg.F, cfg.n_heads
+    L = 128
+    t0 = time.time()
+    osp = oracle.Span(1, H, nh, F, 1e-5, 6.0)
+    osp.load_block(0, block0_host)
+    ose = osp.open_session(L + 2)
+    kv = synth.kv_prefix_device(cfg, 0, 0, L, 2.4, dev)
+    ose.import_kv(0, kv.cpu().numpy())
+    x = synth.hidden_states(cfg, 1, 1, 1)
+    print("[bench] oracle block loaded in %.1f s" % (time.time() - t0), file=sys.stderr, flush=True)
+    t0 = time.perf_counter()
+    y_ref = osp.step([ose], x)
+    dt = time.perf_counter() - t0
+    # same block, same inputs on the GPU
+    gsp = binding.Span(1, H, nh, F, 1, 1e-5, 6.0, dev)
+    gsp.load_block(0, block0_host)
+    gse = gsp.open_session(L + 2)
+    gse.import_kv(0, kv)
+    y_gpu = gsp.decode_step([gse], torch.from_numpy(x[:, 0]).to(dev)).cpu().numpy()[:, None]
+    gsp.close()
+    osp.destroy()
+    g, r = y_gpu.astype(np.float64), y_ref.astype(np.float64)
+    rel = float(np.linalg.norm(g - r) / np.linalg.norm(r))
+    exact = float((y_gpu.view(np.uint16) == y_ref.view(np.uint16)).mean())
+    print("[bench] oracle: %.2f s per block-step on %d threads; GPU vs oracle rel-L2 %.2e, bit-identical %.4f" %
+          (dt, oracle.num_threads(), rel, exact), file=sys.stderr, flush=True)
+    return {"value": round(1.0 / (dt * cfg.n_blocks), 4), "unit": "tokens/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "sample": "1 of 12 blocks, one decode step at KV prefix 128 (%.2f s), extrapolated x12; "
+            "GPU output of the same block: rel-L2 %.1e vs oracle" % (dt, rel)}
+
+
+if __name__ == "__main__":
+    main()

@@ -159,6 +159,21 @@ int petals_hidden_code_table(float *host_table256);
 
 const char *petals_last_error(void);
 
+/*
+ * Per-launch timing of the heavy kernels, for roofline reports.  Between
+ * profile_begin and profile_end every launch of a class below is bracketed by
+ * HIP events recorded on the stream the launch uses (at most max_launches
+ * launches are timed, later ones run untimed).  profile_end waits for the
+ * recorded events and returns, per class, the summed kernel time in ms and the
+ * number of timed launches.  Arrays have PETALS_PROFILE_CLASSES entries (host).
+ */
+#define PETALS_PROFILE_GEMV      0  /* one-row int8 linear (decode, batch 1) */
+#define PETALS_PROFILE_GEMM      1  /* multi-row MFMA linear */
+#define PETALS_PROFILE_ATTENTION 2  /* attention incl. the merge of key ranges */
+#define PETALS_PROFILE_CLASSES   3
+int petals_span_profile_begin(petals_span *span, int32_t max_launches);
+int petals_span_profile_end(petals_span *span, double *ms_per_class, int64_t *launches_per_class);
+
 /* ------------------------------------------------------------ test hooks */
 
 /*

@@ -12,7 +12,7 @@ from .build_oracle import LIB, build
 
 __all__ = ["f16_to_f64", "f64_to_f16", "quantize_weight", "layernorm", "gelu", "linear",
            "alibi_slopes", "attention", "Span", "Session", "codebook", "hidden_quantize",
-           "hidden_dequantize", "EPI_NONE", "EPI_GELU", "EPI_RESIDUAL"]
+           "hidden_dequantize", "num_threads", "EPI_NONE", "EPI_GELU", "EPI_RESIDUAL"]
 
 EPI_NONE, EPI_GELU, EPI_RESIDUAL = 0, 1, 2
 
@@ -45,6 +45,10 @@ def _h(a):
     a = np.ascontiguousarray(a)
     assert a.dtype == np.float16, a.dtype
     return a
+
+
+def num_threads():
+    return lib().orc_num_threads()
 
 
 def f16_to_f64(x):

@@ -55,7 +55,9 @@ EXPORTS = ["petals_span_weight_bytes", "petals_span_workspace_bytes", "petals_sp
            "petals_span_load_block", "petals_span_destroy", "petals_session_open", "petals_session_length",
            "petals_session_close", "petals_span_prefill", "petals_span_decode_step", "petals_hidden_quantize",
            "petals_hidden_dequantize", "petals_hidden_code_table", "petals_last_error", "petals_debug_linear",
-           "petals_debug_export_weight", "petals_debug_export_kv", "petals_debug_import_kv"]
+           "petals_debug_export_weight", "petals_debug_export_kv", "petals_debug_import_kv",
+           "petals_span_profile_begin", "petals_span_profile_end"]
+PROFILE_GEMV, PROFILE_GEMM, PROFILE_ATTENTION, PROFILE_CLASSES = 0, 1, 2, 3
 
 
 def _check(rc):
@@ -158,6 +160,18 @@ def petals_hidden_code_table():
     buf = (C.c_float * 256)()
     _check(lib().petals_hidden_code_table(buf))
     return list(buf)
+
+
+def petals_span_profile_begin(span, max_launches):
+    _check(lib().petals_span_profile_begin(span, C.c_int32(max_launches)))
+
+
+def petals_span_profile_end(span):
+    """Returns (ms_per_class, launches_per_class)."""
+    ms = (C.c_double * PROFILE_CLASSES)()
+    n = (C.c_int64 * PROFILE_CLASSES)()
+    _check(lib().petals_span_profile_end(span, ms, n))
+    return list(ms), list(n)
 
 
 def petals_debug_linear(span, block, which, x, epilogue=EPILOGUE_NONE, resid=None, xq=None, sx=None,

@@ -9,10 +9,11 @@ LIB = os.path.join(HERE, "libpetals_span.so")
 OBJ = os.path.join(HERE, "_build")
 SOURCES = ["api.hip", "quant.hip", "gemv.hip", "gemm.hip", "attn.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-# -ffp-contract=off: the fp32 expressions that decide int8 codes must not be fused.
 # packed-fp32 ops are disabled on the test machines.
-FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-ffp-contract=off",
+FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
+# the quantizers' fp32 expressions decide int8 codes: never let the compiler fuse them
+EXTRA = {"quant.hip": ["-ffp-contract=off"]}
 
 
 def _stale(dst, deps):
@@ -27,7 +28,7 @@ def build(force=True, verbose=False):
     for s in SOURCES:
         src, obj = os.path.join(CSRC, s), os.path.join(OBJ, s.replace(".hip", ".o"))
         if force or _stale(obj, [src] + headers):
-            jobs.append([HIPCC] + FLAGS + ["-c", src, "-o", obj])
+            jobs.append([HIPCC] + FLAGS + EXTRA.get(s, []) + ["-c", src, "-o", obj])
 
     def run(cmd):
         r = subprocess.run(cmd, capture_output=True, text=True)

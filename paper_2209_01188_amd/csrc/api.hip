@@ -62,7 +62,7 @@ struct Workspace {
     int8_t *xq;
     float *sx;
     uint32_t *masks;    // [n_blocks][4][mask_words]
-    float *partials;
+    double *partials;
     size_t mask_words;
     size_t total;
 };
@@ -85,7 +85,7 @@ Workspace carve(const petals_span_config &c, uint8_t *base) {
     w.sx = (float *)take(Mp * 4);
     w.mask_words = (Kmax + 63) / 64 * 2;
     w.masks = (uint32_t *)take((size_t)c.n_blocks * 4 * w.mask_words * 4);
-    w.partials = (float *)take((size_t)PS_ATTN_PARTIAL_SLOTS * (128 + 2) * 4);
+    w.partials = (double *)take((size_t)PS_ATTN_PARTIAL_SLOTS * (128 + 2) * 8);
     w.total = off;
     return w;
 }
@@ -132,12 +132,31 @@ const CodeTable &code_table() {
 
 }  // namespace
 
+// Optional per-launch timing with HIP events recorded on the caller's stream.
+struct Profiler {
+    bool on = false;
+    std::vector<hipEvent_t> ev;        // pairs (start, stop)
+    std::vector<int> cls;              // kernel class of pair i
+    size_t used = 0;
+    bool begin(int kernel_class, hipStream_t st) {
+        if (!on || (used + 1) * 2 > ev.size()) return false;
+        cls[used] = kernel_class;
+        return hipEventRecord(ev[used * 2], st) == hipSuccess;
+    }
+    void end(bool started, hipStream_t st) {
+        if (!started) return;
+        hipEventRecord(ev[used * 2 + 1], st);
+        used++;
+    }
+};
+
 struct petals_span {
     petals_span_config cfg;
+    Profiler prof;
     uint8_t *wmem;
     Workspace ws;
     std::vector<BlockW> blocks;
-    float slopes[PS_MAX_HEADS];
+    double slopes[PS_MAX_HEADS];
     int open_sessions;
 };
 
@@ -157,12 +176,16 @@ int run_linear(petals_span *sp, const LinearW &w, const __half *X, int M, uint32
     if (M == 1) {
         if (!row_already_quantized) HIP_TRY(ps_rowquant_row(X, w.K, theta, ws.xq, mask, ws.sx, st));
         if (xq_dbg) HIP_TRY(ps_copy_bytes(ws.xq, xq_dbg, (size_t)w.K, st));
+        const bool pr = sp->prof.begin(PETALS_PROFILE_GEMV, st);
         HIP_TRY(ps_gemv_row(w, ws.xq, mask, X, ws.sx, o, ws.table, st));
+        sp->prof.end(pr, st);
     } else {
         HIP_TRY(ps_fill_u32(mask, ws.mask_words, 0u, st));
         HIP_TRY(ps_colmask(X, M, w.K, theta, mask, st));
         HIP_TRY(ps_rowquant_tiled(X, M, w.K, mask, ws.xq, ws.sx, xq_dbg, st));
+        const bool pr = sp->prof.begin(PETALS_PROFILE_GEMM, st);
         HIP_TRY(ps_gemm(w, ws.xq, mask, X, ws.sx, M, o, ws.table, st));
+        sp->prof.end(pr, st);
     }
     return PETALS_OK;
 }
@@ -239,9 +262,9 @@ int petals_span_create(const petals_span_config *cfg, void *dev_weight_mem, void
     // remaining heads take the odd terms of the 2*n2 sequence
     int n2 = 1;
     while (n2 * 2 <= cfg->n_heads) n2 *= 2;
-    for (int h = 0; h < PS_MAX_HEADS; h++) sp->slopes[h] = 0.0f;
+    for (int h = 0; h < PS_MAX_HEADS; h++) sp->slopes[h] = 0.0;
     for (int h = 0; h < cfg->n_heads; h++)
-        sp->slopes[h] = (float)(h < n2 ? exp2(-8.0 * (h + 1) / n2) : exp2(-4.0 * (2 * (h - n2) + 1) / n2));
+        sp->slopes[h] = h < n2 ? exp2(-8.0 * (h + 1) / n2) : exp2(-4.0 * (2 * (h - n2) + 1) / n2);
     *out = sp;
     return PETALS_OK;
 }
@@ -267,9 +290,40 @@ int petals_span_load_block(petals_span *sp, int32_t block, const petals_block_pa
     return PETALS_OK;
 }
 
+int petals_span_profile_begin(petals_span *sp, int32_t max_launches) {
+    if (!sp || max_launches < 1) return fail(PETALS_ERR_INVALID_ARG, "null span or max_launches < 1");
+    Profiler &P = sp->prof;
+    while (P.ev.size() < (size_t)max_launches * 2) {
+        hipEvent_t e;
+        HIP_TRY(hipEventCreate(&e));
+        P.ev.push_back(e);
+    }
+    P.cls.assign(P.ev.size() / 2, 0);
+    P.used = 0;
+    P.on = true;
+    return PETALS_OK;
+}
+
+int petals_span_profile_end(petals_span *sp, double *ms_per_class, int64_t *launches_per_class) {
+    if (!sp || !ms_per_class || !launches_per_class) return fail(PETALS_ERR_INVALID_ARG, "null pointer");
+    Profiler &P = sp->prof;
+    P.on = false;
+    for (int c = 0; c < PETALS_PROFILE_CLASSES; c++) { ms_per_class[c] = 0.0; launches_per_class[c] = 0; }
+    for (size_t i = 0; i < P.used; i++) {
+        float ms = 0.0f;
+        HIP_TRY(hipEventSynchronize(P.ev[i * 2 + 1]));
+        HIP_TRY(hipEventElapsedTime(&ms, P.ev[i * 2], P.ev[i * 2 + 1]));
+        ms_per_class[P.cls[i]] += ms;
+        launches_per_class[P.cls[i]]++;
+    }
+    P.used = 0;
+    return PETALS_OK;
+}
+
 int petals_span_destroy(petals_span *sp) {
     if (!sp) return fail(PETALS_ERR_INVALID_ARG, "null span");
     if (sp->open_sessions) return fail(PETALS_ERR_STATE, "%d sessions still open", sp->open_sessions);
+    for (hipEvent_t e : sp->prof.ev) hipEventDestroy(e);
     delete sp;
     return PETALS_OK;
 }
@@ -347,7 +401,11 @@ int petals_span_prefill(petals_span *sp, petals_session *const *sessions, int32_
             HIP_TRY(ps_layernorm(x, W.ln1g, W.ln1b, c.ln_eps, M, H, ws.a, st));
         }
         if (int rc = run_linear(sp, W.lin[0], ws.a, M, mk, oq, nullptr, st, M == 1)) return rc;
-        HIP_TRY(ps_attention(ws.q, ws.table, b, M, T, nh, d, max_keys, ws.partials, ws.ctx, st));
+        {
+            const bool pr = sp->prof.begin(PETALS_PROFILE_ATTENTION, st);
+            HIP_TRY(ps_attention(ws.q, ws.table, b, M, T, nh, d, max_keys, ws.partials, ws.ctx, st));
+            sp->prof.end(pr, st);
+        }
         // dense + residual
         if (int rc = run_linear(sp, W.lin[1], ws.ctx, M, mk + ws.mask_words,
                                 plain_out(ws.x1, PETALS_EPILOGUE_RESIDUAL, x), nullptr, st, false)) return rc;

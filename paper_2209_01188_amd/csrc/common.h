@@ -31,7 +31,7 @@ struct SessTable {
     __half *kv[PS_MAX_SESSIONS];   // session base: [block][key|value][head][cap][d]
     int len[PS_MAX_SESSIONS];
     int cap[PS_MAX_SESSIONS];
-    float slopes[PS_MAX_HEADS];    // ALiBi slope per head
+    double slopes[PS_MAX_HEADS];   // ALiBi slope per head
 };
 
 // Where a linear's result goes and what is fused before the fp16 rounding.
@@ -77,7 +77,7 @@ hipError_t ps_set_table(const SessTable &host_table, SessTable *dev_table, hipSt
 #define PS_ATTN_MAX_SPLITS 16
 #define PS_ATTN_PARTIAL_SLOTS 8192   // (row, head, split) triples that may need a partial result
 hipError_t ps_attention(const __half *q, const SessTable *sess, int blk, int M, int T, int nh, int d, int max_keys,
-                        float *partials, __half *ctx, hipStream_t st);
+                        double *partials, __half *ctx, hipStream_t st);
 
 hipError_t ps_hidden_quantize(const __half *x, size_t n, int block, const CodeTable &tab, uint8_t *q, float *absmax,
                               hipStream_t st);
@@ -110,6 +110,17 @@ __device__ __forceinline__ float block_max(float v, float *sm) {
     return r;
 }
 template <int NW>
+__device__ __forceinline__ double block_sum(double v, double *sm) {
+    v = wave_sum(v);
+    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = v;
+    __syncthreads();
+    double r = sm[0];
+#pragma unroll
+    for (int i = 1; i < NW; i++) r += sm[i];
+    __syncthreads();
+    return r;
+}
+template <int NW>
 __device__ __forceinline__ float block_sum(float v, float *sm) {
     v = wave_sum(v);
     if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = v;
@@ -120,8 +131,29 @@ __device__ __forceinline__ float block_sum(float v, float *sm) {
     __syncthreads();
     return r;
 }
-__device__ __forceinline__ float gelu_tanh(float v) {
-    return 0.5f * v * (1.0f + tanhf(0.7978845608028654f * (v + 0.044715f * v * v * v)));
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+// Keeps an fp32 value in a register as fp32: the compiler may otherwise fold "fp32 multiply,
+// then convert to fp16" into one mixed-precision instruction that rounds the exact product
+// once, which differs from the two-step result on double-rounding cases.
+__device__ __forceinline__ float keep_f32(float v) {
+    asm volatile("" : "+v"(v));
+    return v;
+}
+// tanh-form GeLU in fp64: 0.5 v (1 + tanh u) == v / (1 + exp(-2u))
+__device__ __forceinline__ double gelu_tanh(double v) {
+    const double u = 0.7978845608028654 * (v + 0.044715 * v * v * v);
+    return v / (1.0 + exp(-2.0 * u));
+}
+// double -> fp16 with ONE rounding (to nearest even): go through fp32 rounded to odd, which
+// keeps enough information for the final fp16 rounding to be exact
+__device__ __forceinline__ __half d2h_rn(double v) {
+    float f = __double2float_rz(v);
+    if ((double)f != v) f = __uint_as_float(__float_as_uint(f) | 1u);
+    return __float2half_rn(f);
 }
 // int8 code of one activation/weight: fp32 product, round half to even, clamp
 __device__ __forceinline__ int q8(float x, float r) {

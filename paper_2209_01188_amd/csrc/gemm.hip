@@ -12,8 +12,8 @@ __device__ __forceinline__ v8h dequant8(int w0, int w1, float swd) {
     v8h r;
 #pragma unroll
     for (int b = 0; b < 4; b++) {
-        r[b] = (_Float16)((float)(int8_t)((w0 >> (8 * b)) & 0xff) * swd);
-        r[b + 4] = (_Float16)((float)(int8_t)((w1 >> (8 * b)) & 0xff) * swd);
+        r[b] = (_Float16)keep_f32((float)(int8_t)((w0 >> (8 * b)) & 0xff) * swd);
+        r[b + 4] = (_Float16)keep_f32((float)(int8_t)((w1 >> (8 * b)) & 0xff) * swd);
     }
     return r;
 }
@@ -139,7 +139,7 @@ k_gemm(LinearW w, const int8_t *__restrict__ xq_tiled, const uint32_t *__restric
 #pragma unroll
             for (int r = 0; r < 4; r++) {
                 const int n = (nt0 + i) * 16 + 4 * kg + r;
-                emit_output(o, sess, N, t, n, acc[i][j][r], oac[i][j][r], sxd, w.sw[n] / 127.0f,
+                emit_output(o, sess, N, t, n, acc[i][j][r], (double)oac[i][j][r], sxd, w.sw[n] / 127.0f,
                             __half2float(w.bias[n]));
             }
         }

@@ -12,19 +12,19 @@ __device__ __forceinline__ int byte_of(const v4i &w, int j) {
 }
 
 // fp16 part of a 16-column group that contains outlier columns (rare path)
-__device__ __forceinline__ float outlier_group(const v4i &w, uint32_t bits, const __half *__restrict__ xp, float swd) {
-    float o = 0.0f;
+__device__ __forceinline__ double outlier_group(const v4i &w, uint32_t bits, const __half *__restrict__ xp, float swd) {
+    double o = 0.0;
     while (bits) {
         const int j = __ffs(bits) - 1;
         bits &= bits - 1;
-        o += __half2float(xp[j]) * dequant_w16(byte_of(w, j), swd);
+        o += (double)__half2float(xp[j]) * (double)dequant_w16(byte_of(w, j), swd);
     }
     return o;
 }
 
 __device__ __forceinline__ void tile_mac(const v4i &wv, const int8_t *xs, const uint16_t *ms,
                                          const __half *__restrict__ x, int kt, int kg, float swd, int &acc,
-                                         float &outl) {
+                                         double &outl) {
     const v4i xv = *(const v4i *)(xs + kt * 64 + kg * 16);
     acc = __builtin_amdgcn_sdot4(wv[0], xv[0], acc, false);
     acc = __builtin_amdgcn_sdot4(wv[1], xv[1], acc, false);
@@ -47,7 +47,7 @@ __global__ void __launch_bounds__(512) k_gemv_row(LinearW w, const int8_t *__res
     int8_t *xs = (int8_t *)lds;                               // K codes
     uint16_t *ms = (uint16_t *)(lds + K);                     // K/16 group masks
     int *red_i = (int *)(lds + K + K / 8);                    // [8][16]
-    float *red_f = (float *)(red_i + 128);                    // [8][16]
+    double *red_f = (double *)(red_i + 128);                  // [8][16]
     for (int i = threadIdx.x; i < K / 16; i += 512) ((v4i *)xs)[i] = ((const v4i *)xq)[i];
     for (int i = threadIdx.x; i < K / 32; i += 512) ((uint32_t *)ms)[i] = mask[i];
     __syncthreads();
@@ -57,7 +57,7 @@ __global__ void __launch_bounds__(512) k_gemv_row(LinearW w, const int8_t *__res
     const float swd = w.sw[n] / 127.0f;
     const v4i *wp = (const v4i *)(w.wt + (size_t)p * KT * 1024) + lane;
     int acc = 0;
-    float outl = 0.0f;
+    double outl = 0.0;
     const int nchunks = KT / U;
     for (int c = wave; c < nchunks; c += 8) {
         v4i wv[U];
@@ -78,7 +78,7 @@ __global__ void __launch_bounds__(512) k_gemv_row(LinearW w, const int8_t *__res
     __syncthreads();
     if (threadIdx.x < 16) {
         int a = 0;
-        float f = 0.0f;
+        double f = 0.0;
 #pragma unroll
         for (int i = 0; i < 8; i++) { a += red_i[i * 16 + threadIdx.x]; f += red_f[i * 16 + threadIdx.x]; }
         emit_output(o, sess, w.N, 0, n, a, f, sx[0] / 127.0f, swd, __half2float(w.bias[n]));
@@ -90,7 +90,7 @@ __global__ void __launch_bounds__(512) k_gemv_row(LinearW w, const int8_t *__res
 hipError_t ps_gemv_row(const LinearW &w, const int8_t *xq, const uint32_t *mask, const __half *x, const float *sx,
                        const OutDesc &o, const SessTable *sess, hipStream_t st) {
     const int KT = w.K / 64;
-    const size_t lds = (size_t)w.K + w.K / 8 + 128 * 8;
+    const size_t lds = (size_t)w.K + w.K / 8 + 128 * 12;
     const dim3 grid(w.N / 16), block(512);
     if (KT % 64 == 0) k_gemv_row<8><<<grid, block, lds, st>>>(w, xq, mask, x, sx, o, sess);
     else if (KT % 32 == 0) k_gemv_row<4><<<grid, block, lds, st>>>(w, xq, mask, x, sx, o, sess);

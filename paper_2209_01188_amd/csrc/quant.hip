@@ -62,39 +62,45 @@ __global__ void k_copy_bytes(const uint8_t *__restrict__ s, uint8_t *__restrict_
 
 // -------------------------------------------------------------- LayerNorm
 
-// One workgroup per row; fp32 moments (mean, then centred second moment).
+// One workgroup per row.  Moments and the affine map in fp64 (a row is a few thousand
+// elements; the cost is nil) so the fp16 result equals the exactly rounded one.
 template <int NT>
-__device__ __forceinline__ void row_moments(const __half *x, int H, float *sm, float &mean, float &inv, float eps) {
-    float s = 0.0f;
+__device__ __forceinline__ void row_moments(const __half *x, int H, double *sm, double &mean, double &inv, double eps) {
+    double s = 0.0;
     for (int k = threadIdx.x * 2; k < H; k += NT * 2) {
         float2 v = __half22float2(*(const __half2 *)(x + k));
-        s += v.x + v.y;
+        s += (double)v.x + (double)v.y;
     }
-    mean = block_sum<NT / 64>(s, sm) / (float)H;
-    float q = 0.0f;
+    mean = block_sum<NT / 64>(s, sm) / (double)H;
+    double q = 0.0;
     for (int k = threadIdx.x * 2; k < H; k += NT * 2) {
         float2 v = __half22float2(*(const __half2 *)(x + k));
-        float a = v.x - mean, b = v.y - mean;
+        double a = (double)v.x - mean, b = (double)v.y - mean;
         q += a * a + b * b;
     }
-    float var = block_sum<NT / 64>(q, sm) / (float)H;
-    inv = 1.0f / sqrtf(var + eps);
+    double var = block_sum<NT / 64>(q, sm) / (double)H;
+    inv = 1.0 / sqrt(var + eps);
+}
+
+__device__ __forceinline__ __half2 ln_affine(__half2 x, __half2 g, __half2 b, double mean, double inv) {
+    float2 v = __half22float2(x), gg = __half22float2(g), bb = __half22float2(b);
+    __half2 o;
+    o.x = d2h_rn(((double)v.x - mean) * inv * (double)gg.x + (double)bb.x);
+    o.y = d2h_rn(((double)v.y - mean) * inv * (double)gg.y + (double)bb.y);
+    return o;
 }
 
 __global__ void __launch_bounds__(256) k_layernorm(const __half *__restrict__ x, const __half *__restrict__ g,
                                                    const __half *__restrict__ b, float eps, int H,
                                                    __half *__restrict__ y) {
-    __shared__ float sm[4];
+    __shared__ double sm[4];
     const __half *xr = x + (size_t)blockIdx.x * H;
     __half *yr = y + (size_t)blockIdx.x * H;
-    float mean, inv;
-    row_moments<256>(xr, H, sm, mean, inv, eps);
-    for (int k = threadIdx.x * 2; k < H; k += 512) {
-        float2 v = __half22float2(*(const __half2 *)(xr + k));
-        float2 gg = __half22float2(*(const __half2 *)(g + k));
-        float2 bb = __half22float2(*(const __half2 *)(b + k));
-        *(__half2 *)(yr + k) = __floats2half2_rn((v.x - mean) * inv * gg.x + bb.x, (v.y - mean) * inv * gg.y + bb.y);
-    }
+    double mean, inv;
+    row_moments<256>(xr, H, sm, mean, inv, (double)eps);
+    for (int k = threadIdx.x * 2; k < H; k += 512)
+        *(__half2 *)(yr + k) = ln_affine(*(const __half2 *)(xr + k), *(const __half2 *)(g + k),
+                                         *(const __half2 *)(b + k), mean, inv);
 }
 
 // ------------------------------------------- one-row detect + quantize (decode)
@@ -138,13 +144,11 @@ __global__ void __launch_bounds__(1024) k_ln_quant_row(const __half *__restrict_
     __half *ys = (__half *)lds;                            // H halves
     uint32_t *mask_lds = (uint32_t *)(lds + (size_t)H * 2);   // H/32 words
     __shared__ float sm[16];
-    float mean, inv;
-    row_moments<1024>(x, H, sm, mean, inv, eps);
+    __shared__ double smd[16];
+    double mean, inv;
+    row_moments<1024>(x, H, smd, mean, inv, (double)eps);
     for (int k = threadIdx.x * 2; k < H; k += 2048) {
-        float2 v = __half22float2(*(const __half2 *)(x + k));
-        float2 gg = __half22float2(*(const __half2 *)(g + k));
-        float2 bb = __half22float2(*(const __half2 *)(b + k));
-        __half2 o = __floats2half2_rn((v.x - mean) * inv * gg.x + bb.x, (v.y - mean) * inv * gg.y + bb.y);
+        __half2 o = ln_affine(*(const __half2 *)(x + k), *(const __half2 *)(g + k), *(const __half2 *)(b + k), mean, inv);
         *(__half2 *)(ys + k) = o;
         *(__half2 *)(y + k) = o;
     }
@@ -267,7 +271,7 @@ __global__ void __launch_bounds__(256) k_hidden_dequantize(const uint8_t *__rest
     code[threadIdx.x] = tab.code[threadIdx.x];
     __syncthreads();
     size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < n) y[i] = __float2half_rn(code[q[i]] * absmax[i / (size_t)block]);
+    if (i < n) y[i] = __float2half_rn(keep_f32(code[q[i]] * absmax[i / (size_t)block]));
 }
 
 // ------------------------------------------------------------- cache copies

@@ -116,6 +116,16 @@ def kv_prefix(cfg, block, session, L, std=1.0):
     return (r.standard_normal((2, cfg.n_heads, L, cfg.head_dim), dtype=np.float32) * np.float32(std)).astype(np.float16)
 
 
+def kv_prefix_device(cfg, block, session, L, std=1.0, device="cuda:0"):
+    """Same recipe as kv_prefix, drawn on `device` with torch (different bits)."""
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(((cfg.seed * 1000003 + block) * 4099 + session) * 64 + 63)
+    kv = torch.empty((2, cfg.n_heads, L, cfg.head_dim), dtype=torch.float32, device=device)
+    kv.normal_(0.0, std, generator=g)
+    return kv.to(torch.float16)
+
+
 # ---------------------------------------------------------------- device side
 # Full-size weights (tens of GB) are drawn on the GPU with torch's seeded
 # generator; whoever needs them on the host copies the rows it wants.
