@@ -189,6 +189,13 @@ int petals_debug_linear(petals_span *span, int32_t block, int32_t which, const v
                         int32_t M, int32_t epilogue, const void *resid, int8_t *xq, float *sx,
                         uint8_t *outlier_mask, int32_t *acc, void *y, void *stream);
 
+/*
+ * One LayerNorm of a loaded block (which: 0 = before attention, 1 = before the MLP) on
+ * dev fp16 x [M, H] -> y [M, H], through the kernel prefill/decode use for that M.
+ */
+int petals_debug_layernorm(petals_span *span, int32_t block, int32_t which, const void *x,
+                           int32_t M, void *y, void *stream);
+
 /* Row-major int8 codes [N, K] and row scales [N] of a loaded linear (dev outputs). */
 int petals_debug_export_weight(petals_span *span, int32_t block, int32_t which, int8_t *wq,
                                float *sw, void *stream);

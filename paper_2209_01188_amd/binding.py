@@ -56,7 +56,7 @@ EXPORTS = ["petals_span_weight_bytes", "petals_span_workspace_bytes", "petals_sp
            "petals_session_close", "petals_span_prefill", "petals_span_decode_step", "petals_hidden_quantize",
            "petals_hidden_dequantize", "petals_hidden_code_table", "petals_last_error", "petals_debug_linear",
            "petals_debug_export_weight", "petals_debug_export_kv", "petals_debug_import_kv",
-           "petals_span_profile_begin", "petals_span_profile_end"]
+           "petals_span_profile_begin", "petals_span_profile_end", "petals_debug_layernorm"]
 PROFILE_GEMV, PROFILE_GEMM, PROFILE_ATTENTION, PROFILE_CLASSES = 0, 1, 2, 3
 
 
@@ -181,6 +181,11 @@ def petals_debug_linear(span, block, which, x, epilogue=EPILOGUE_NONE, resid=Non
                                      _ptr(acc), _ptr(y), _stream()))
 
 
+def petals_debug_layernorm(span, block, which, x, y):
+    _check(lib().petals_debug_layernorm(span, C.c_int32(block), C.c_int32(which), _ptr(x), C.c_int32(x.shape[0]),
+                                        _ptr(y), _stream()))
+
+
 def petals_debug_export_weight(span, block, which, wq, sw):
     _check(lib().petals_debug_export_weight(span, C.c_int32(block), C.c_int32(which), _ptr(wq), _ptr(sw), _stream()))
 
@@ -243,6 +248,11 @@ class Span:
         petals_debug_linear(self.handle, block, which, x, epilogue, resid, out["xq"], out["sx"], out["mask"],
                             out["acc"], out["y"])
         return out
+
+    def debug_layernorm(self, block, which, x):
+        y = torch.empty_like(x)
+        petals_debug_layernorm(self.handle, block, which, x, y)
+        return y
 
     def export_weight(self, block, which):
         N, K = self.shapes(which)

@@ -63,6 +63,8 @@ struct Workspace {
     float *sx;
     uint32_t *masks;    // [n_blocks][4][mask_words]
     double *partials;
+    int *ocount;
+    double *wd64, *x64;
     size_t mask_words;
     size_t total;
 };
@@ -86,6 +88,10 @@ Workspace carve(const petals_span_config &c, uint8_t *base) {
     w.mask_words = (Kmax + 63) / 64 * 2;
     w.masks = (uint32_t *)take((size_t)c.n_blocks * 4 * w.mask_words * 4);
     w.partials = (double *)take((size_t)PS_ATTN_PARTIAL_SLOTS * (128 + 2) * 8);
+    w.ocount = (int *)take(256);
+    const size_t Nmax = 3 * H > F ? 3 * H : F;
+    w.wd64 = (double *)take(Nmax / 16 * PS_OUTLIER_CHUNKS * 64 * 8);
+    w.x64 = (double *)take(Mp / 16 * PS_OUTLIER_CHUNKS * 64 * 8);
     w.total = off;
     return w;
 }
@@ -145,7 +151,7 @@ struct Profiler {
     }
     void end(bool started, hipStream_t st) {
         if (!started) return;
-        hipEventRecord(ev[used * 2 + 1], st);
+        (void)hipEventRecord(ev[used * 2 + 1], st);
         used++;
     }
 };
@@ -183,8 +189,10 @@ int run_linear(petals_span *sp, const LinearW &w, const __half *X, int M, uint32
         HIP_TRY(ps_fill_u32(mask, ws.mask_words, 0u, st));
         HIP_TRY(ps_colmask(X, M, w.K, theta, mask, st));
         HIP_TRY(ps_rowquant_tiled(X, M, w.K, mask, ws.xq, ws.sx, xq_dbg, st));
+        HIP_TRY(ps_outlier_prep(w, mask, X, M, ws.ocount, ws.wd64, ws.x64, st));
+        const OutlierSet os = {ws.ocount, ws.wd64, ws.x64};
         const bool pr = sp->prof.begin(PETALS_PROFILE_GEMM, st);
-        HIP_TRY(ps_gemm(w, ws.xq, mask, X, ws.sx, M, o, ws.table, st));
+        HIP_TRY(ps_gemm(w, ws.xq, mask, X, ws.sx, M, os, o, ws.table, st));
         sp->prof.end(pr, st);
     }
     return PETALS_OK;
@@ -323,7 +331,7 @@ int petals_span_profile_end(petals_span *sp, double *ms_per_class, int64_t *laun
 int petals_span_destroy(petals_span *sp) {
     if (!sp) return fail(PETALS_ERR_INVALID_ARG, "null span");
     if (sp->open_sessions) return fail(PETALS_ERR_STATE, "%d sessions still open", sp->open_sessions);
-    for (hipEvent_t e : sp->prof.ev) hipEventDestroy(e);
+    for (hipEvent_t e : sp->prof.ev) (void)hipEventDestroy(e);
     delete sp;
     return PETALS_OK;
 }
@@ -471,6 +479,24 @@ int petals_debug_linear(petals_span *sp, int32_t block, int32_t which, const voi
     if (int rc = run_linear(sp, L, (const __half *)x, M, mk, o, xq, st, false)) return rc;
     if (sx) HIP_TRY(ps_copy_bytes(ws.sx, sx, (size_t)M * 4, st));
     if (outlier_mask) HIP_TRY(ps_mask_to_bytes(mk, L.K, outlier_mask, st));
+    return PETALS_OK;
+}
+
+int petals_debug_layernorm(petals_span *sp, int32_t block, int32_t which, const void *x, int32_t M, void *y, void *stream) {
+    if (!sp || !x || !y) return fail(PETALS_ERR_INVALID_ARG, "null pointer");
+    if (block < 0 || block >= sp->cfg.n_blocks || which < 0 || which > 1) return fail(PETALS_ERR_INVALID_ARG, "block or LayerNorm index out of range");
+    if (!sp->blocks[block].loaded) return fail(PETALS_ERR_STATE, "block %d has not been loaded", block);
+    if (M < 1 || M > sp->cfg.max_rows_per_call) return fail(PETALS_ERR_CAPACITY, "M out of range");
+    const BlockW &W = sp->blocks[block];
+    const petals_span_config &c = sp->cfg;
+    hipStream_t st = (hipStream_t)stream;
+    if (M == 1) {   // the decode path's fused kernel; its quantizer outputs land in the workspace
+        HIP_TRY(ps_ln_quant_row((const __half *)x, which ? W.ln2g : W.ln1g, which ? W.ln2b : W.ln1b, c.ln_eps, c.hidden,
+                                c.outlier_threshold, (__half *)y, sp->ws.xq, sp->ws.masks, sp->ws.sx, st));
+    } else {
+        HIP_TRY(ps_layernorm((const __half *)x, which ? W.ln2g : W.ln1g, which ? W.ln2b : W.ln1b, c.ln_eps, M, c.hidden,
+                             (__half *)y, st));
+    }
     return PETALS_OK;
 }
 

@@ -147,7 +147,7 @@ hipError_t attn_launch(const __half *q, const SessTable *sess, int blk, int M, i
     if ((size_t)M * nh * nsplit > PS_ATTN_PARTIAL_SLOTS) nsplit = 1;
     int CH = ((max_keys + nsplit - 1) / nsplit + 255) / 256 * 256;
     if (nsplit == 1) CH = 1 << 30;
-    if (T == 1 || getenv("PS_ATTN_F64"))
+    if (T == 1 || !getenv("PS_ATTN_F32"))
         k_attn<D, double><<<dim3(nsplit, nh, M), 256, 0, st>>>(q, sess, blk, T, nh, CH, nsplit, partials, ctx);
     else
         k_attn<D, float><<<dim3(nsplit, nh, M), 256, 0, st>>>(q, sess, blk, T, nh, CH, nsplit, partials, ctx);

@@ -9,6 +9,7 @@ typedef int v2i __attribute__((ext_vector_type(2)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef _Float16 v4h __attribute__((ext_vector_type(4)));
+typedef double v4d __attribute__((ext_vector_type(4)));
 
 #define PS_MAX_SESSIONS 64
 #define PS_MAX_HEADS 256
@@ -46,6 +47,19 @@ struct OutDesc {
 
 struct CodeTable { float code[256]; };
 
+// Up to this many outlier columns the fp16 part of a multi-row linear is computed exactly
+// (fp64 matrix instructions on compacted operands); beyond it, on the fp16 matrix cores.
+#define PS_EXACT_OUTLIERS 64
+#define PS_OUTLIER_CHUNKS (PS_EXACT_OUTLIERS / 4)
+// Compacted outlier operands of one linear call, in v_mfma_f64_16x16x4_f64 lane order:
+// chunk c of tile r holds 64 doubles, lane l = column list[4c + l/16] of row 16r + l%16
+// (weight rows permuted inside a tile, see k_outlier_prep).
+struct OutlierSet {
+    const int *count;       // number of outlier columns of this call
+    const double *wd64;     // [N/16][PS_OUTLIER_CHUNKS][64] dequantized fp16 weights
+    const double *x64;      // [ceil(M/16)][PS_OUTLIER_CHUNKS][64] fp16 activations
+};
+
 // --- launchers (all enqueue on `st` and return the launch status) ---------------
 hipError_t ps_quantize_weight(const float *W, int N, int K, int8_t *wt, float *sw, hipStream_t st);
 hipError_t ps_untile_weight(const int8_t *wt, int N, int K, int8_t *wq_rowmajor, hipStream_t st);
@@ -68,9 +82,12 @@ hipError_t ps_mask_to_bytes(const uint32_t *mask, int K, uint8_t *out, hipStream
 // y = mixed int8/fp16 linear for one row (decode, batch 1)
 hipError_t ps_gemv_row(const LinearW &w, const int8_t *xq, const uint32_t *mask, const __half *x, const float *sx,
                        const OutDesc &o, const SessTable *sess, hipStream_t st);
-// same for M >= 2 rows on int8 / fp16 MFMA; xq_tiled as written by ps_rowquant_tiled
+// counts the outlier columns of a call and, if they are few, compacts their operands
+hipError_t ps_outlier_prep(const LinearW &w, const uint32_t *mask, const __half *X, int M, int *count, double *wd64,
+                           double *x64, hipStream_t st);
+// same for M >= 2 rows on int8 / fp16 / fp64 MFMA; xq_tiled as written by ps_rowquant_tiled
 hipError_t ps_gemm(const LinearW &w, const int8_t *xq_tiled, const uint32_t *mask, const __half *X, const float *sx,
-                   int M, const OutDesc &o, const SessTable *sess, hipStream_t st);
+                   int M, const OutlierSet &os, const OutDesc &o, const SessTable *sess, hipStream_t st);
 
 // attention of M = B*T query rows against the caches (new keys/values already appended)
 hipError_t ps_set_table(const SessTable &host_table, SessTable *dev_table, hipStream_t st);
@@ -93,6 +110,11 @@ __device__ __forceinline__ float wave_max(float v) {
     return v;
 }
 __device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+__device__ __forceinline__ double wave_sum(double v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
     return v;
@@ -131,11 +153,6 @@ __device__ __forceinline__ float block_sum(float v, float *sm) {
     __syncthreads();
     return r;
 }
-__device__ __forceinline__ double wave_sum(double v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    return v;
-}
 // Keeps an fp32 value in a register as fp32: the compiler may otherwise fold "fp32 multiply,
 // then convert to fp16" into one mixed-precision instruction that rounds the exact product
 // once, which differs from the two-step result on double-rounding cases.
@@ -149,10 +166,16 @@ __device__ __forceinline__ double gelu_tanh(double v) {
     return v / (1.0 + exp(-2.0 * u));
 }
 // double -> fp16 with ONE rounding (to nearest even): go through fp32 rounded to odd, which
-// keeps enough information for the final fp16 rounding to be exact
+// keeps enough information for the final fp16 rounding to be exact.  Round-to-odd is built
+// from the ordinary conversion: undo a rounding away from zero, then set the sticky bit.
 __device__ __forceinline__ __half d2h_rn(double v) {
-    float f = __double2float_rz(v);
-    if ((double)f != v) f = __uint_as_float(__float_as_uint(f) | 1u);
+    float f = (float)v;
+    const double fd = (double)f;
+    if (fd != v) {
+        uint32_t u = __float_as_uint(f);
+        if (fabs(fd) > fabs(v)) u -= 1u;
+        f = __uint_as_float(u | 1u);
+    }
     return __float2half_rn(f);
 }
 // int8 code of one activation/weight: fp32 product, round half to even, clamp

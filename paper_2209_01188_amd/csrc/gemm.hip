@@ -24,6 +24,64 @@ __device__ __forceinline__ v8h mask8(v8h v, uint32_t bits) {
     return v;
 }
 
+// Counts the outlier columns and, when there are at most PS_EXACT_OUTLIERS, gathers their
+// dequantized weights (one workgroup per 16 output rows) and activations (one per 16
+// tokens) as doubles in matrix-instruction lane order.  Every workgroup rebuilds the short
+// column list from the bit mask itself.
+__global__ void __launch_bounds__(64) k_outlier_prep(LinearW w, const uint32_t *__restrict__ mask,
+                                                     const __half *__restrict__ X, int M, int *__restrict__ count,
+                                                     double *__restrict__ wd64, double *__restrict__ x64) {
+    __shared__ int list[PS_EXACT_OUTLIERS];
+    const int K = w.K, KT = K >> 6, nwords = K >> 5, lane = threadIdx.x;
+    const int wpt = (nwords + 63) / 64, w0 = min(nwords, lane * wpt), w1 = min(nwords, w0 + wpt);
+    int cnt = 0;
+    for (int i = w0; i < w1; i++) cnt += __popc(mask[i]);
+    int incl = cnt;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int v = __shfl_up(incl, off);
+        if (lane >= off) incl += v;
+    }
+    const int total = __shfl(incl, 63);
+    if (blockIdx.x == 0 && lane == 0) *count = total;
+    if (total == 0 || total > PS_EXACT_OUTLIERS) return;
+    int pos = incl - cnt;
+    for (int i = w0; i < w1; i++) {
+        uint32_t b = mask[i];
+        while (b) {
+            const int j = __ffs(b) - 1;
+            b &= b - 1;
+            list[pos++] = i * 32 + j;
+        }
+    }
+    __syncthreads();
+    const int NT = w.N >> 4, row = lane & 15, kq = lane >> 4, nch = (total + 3) >> 2;
+    if ((int)blockIdx.x < NT) {
+        // the fp64 matrix instruction returns row 4r + g in register r of lane group g, the int8 one
+        // row 4g + r: store the weight rows permuted so both results line up in the same registers
+        const int nt = blockIdx.x, nrow = 4 * (row & 3) + (row >> 2);
+        const float swd = w.sw[nt * 16 + nrow] / 127.0f;
+        for (int c = 0; c < nch; c++) {
+            const int j = c * 4 + kq;
+            double v = 0.0;
+            if (j < total) {
+                const int k = list[j];
+                const int code = w.wt[((size_t)nt * KT + (k >> 6)) * 1024 + (((k & 63) >> 4) * 16 + nrow) * 16 + (k & 15)];
+                v = (double)dequant_w16(code, swd);
+            }
+            wd64[((size_t)nt * PS_OUTLIER_CHUNKS + c) * 64 + lane] = v;
+        }
+    } else {
+        const int mt = blockIdx.x - NT, t = mt * 16 + row;
+        for (int c = 0; c < nch; c++) {
+            const int j = c * 4 + kq;
+            double v = 0.0;
+            if (j < total && t < M) v = (double)__half2float(X[(size_t)t * K + list[j]]);
+            x64[((size_t)mt * PS_OUTLIER_CHUNKS + c) * 64 + lane] = v;
+        }
+    }
+}
+
 // Workgroup = WVN x WVM x WVK waves.  Wave (wn, wm, wk) owns WN weight tiles (16 output
 // rows each) x MT token tiles (16 rows each) and the K tiles kt = wk, wk + WVK, ...;
 // with WVK > 1 the partial sums meet in LDS and are added in a fixed order.
@@ -32,8 +90,10 @@ __device__ __forceinline__ v8h mask8(v8h v, uint32_t bits) {
 template <int WN, int MT, int WVN, int WVM, int WVK>
 __global__ void __launch_bounds__(64 * WVN * WVM * WVK)
 k_gemm(LinearW w, const int8_t *__restrict__ xq_tiled, const uint32_t *__restrict__ mask,
-       const __half *__restrict__ X, const float *__restrict__ sx, int M, OutDesc o,
+       const __half *__restrict__ X, const float *__restrict__ sx, int M, OutlierSet os, OutDesc o,
        const SessTable *__restrict__ sess) {
+    const int n_out = *os.count;
+    const bool exact = n_out <= PS_EXACT_OUTLIERS;     // few outliers: fp64 pass after the main loop
     const int K = w.K, KT = K >> 6, N = w.N, NT = N >> 4, MTT = (M + 15) >> 4;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, row = lane & 15, kg = lane >> 4;
     const int wk = wave % WVK, wm = (wave / WVK) % WVM, wn = wave / (WVK * WVM);
@@ -78,7 +138,7 @@ k_gemm(LinearW w, const int8_t *__restrict__ xq_tiled, const uint32_t *__restric
             for (int j = 0; j < MT; j++)
                 acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wv[i], xv[j], acc[i][j], 0, 0, 0);
         const uint64_t mbits = mask64[kt];                 // same for the whole wave
-        if (mbits) {
+        if (mbits && !exact) {
             const uint32_t gb = (uint32_t)(mbits >> (kg * 16)) & 0xffffu;
             v8h xlo[MT], xhi[MT];
 #pragma unroll
@@ -133,14 +193,23 @@ k_gemm(LinearW w, const int8_t *__restrict__ xq_tiled, const uint32_t *__restric
         if (nt0 + i >= NT) continue;
 #pragma unroll
         for (int j = 0; j < MT; j++) {
+            if (mt0 + j >= MTT) continue;                               // wave-uniform
+            v4d od = {(double)oac[i][j][0], (double)oac[i][j][1], (double)oac[i][j][2], (double)oac[i][j][3]};
+            if (exact && n_out > 0) {
+                // exact fp16 part: products of fp16 values are exact in fp64, sums round at 2^-53
+                const double *ap = os.wd64 + (size_t)(nt0 + i) * PS_OUTLIER_CHUNKS * 64 + lane;
+                const double *bp = os.x64 + (size_t)(mt0 + j) * PS_OUTLIER_CHUNKS * 64 + lane;
+                od = (v4d){0.0, 0.0, 0.0, 0.0};
+                for (int c = 0; c < (n_out + 3) >> 2; c++)
+                    od = __builtin_amdgcn_mfma_f64_16x16x4f64(ap[c * 64], bp[c * 64], od, 0, 0, 0);
+            }
             const int t = (mt0 + j) * 16 + row;
-            if (mt0 + j >= MTT || t >= M) continue;
+            if (t >= M) continue;
             const float sxd = sx[t] / 127.0f;
 #pragma unroll
             for (int r = 0; r < 4; r++) {
                 const int n = (nt0 + i) * 16 + 4 * kg + r;
-                emit_output(o, sess, N, t, n, acc[i][j][r], (double)oac[i][j][r], sxd, w.sw[n] / 127.0f,
-                            __half2float(w.bias[n]));
+                emit_output(o, sess, N, t, n, acc[i][j][r], od[r], sxd, w.sw[n] / 127.0f, __half2float(w.bias[n]));
             }
         }
     }
@@ -148,20 +217,26 @@ k_gemm(LinearW w, const int8_t *__restrict__ xq_tiled, const uint32_t *__restric
 
 template <int WN, int MT, int WVN, int WVM, int WVK>
 hipError_t launch(const LinearW &w, const int8_t *xq_tiled, const uint32_t *mask, const __half *X, const float *sx,
-                  int M, const OutDesc &o, const SessTable *sess, hipStream_t st) {
+                  int M, const OutlierSet &os, const OutDesc &o, const SessTable *sess, hipStream_t st) {
     const int NT = w.N / 16, MTT = (M + 15) / 16;
     dim3 grid((NT + WVN * WN - 1) / (WVN * WN), (MTT + WVM * MT - 1) / (WVM * MT));
     size_t lds = WVK > 1 ? (size_t)WVN * WVM * WVK * WN * MT * 64 * 32 : 0;
-    k_gemm<WN, MT, WVN, WVM, WVK><<<grid, 64 * WVN * WVM * WVK, lds, st>>>(w, xq_tiled, mask, X, sx, M, o, sess);
+    k_gemm<WN, MT, WVN, WVM, WVK><<<grid, 64 * WVN * WVM * WVK, lds, st>>>(w, xq_tiled, mask, X, sx, M, os, o, sess);
     return hipGetLastError();
 }
 
 }  // namespace
 
+hipError_t ps_outlier_prep(const LinearW &w, const uint32_t *mask, const __half *X, int M, int *count, double *wd64,
+                           double *x64, hipStream_t st) {
+    k_outlier_prep<<<w.N / 16 + (M + 15) / 16, 64, 0, st>>>(w, mask, X, M, count, wd64, x64);
+    return hipGetLastError();
+}
+
 hipError_t ps_gemm(const LinearW &w, const int8_t *xq_tiled, const uint32_t *mask, const __half *X, const float *sx,
-                   int M, const OutDesc &o, const SessTable *sess, hipStream_t st) {
-    if (M <= 16) return launch<1, 1, 1, 1, 8>(w, xq_tiled, mask, X, sx, M, o, sess, st);
-    if (M <= 32) return launch<1, 2, 1, 1, 8>(w, xq_tiled, mask, X, sx, M, o, sess, st);
-    if (M <= 64) return launch<1, 4, 1, 1, 8>(w, xq_tiled, mask, X, sx, M, o, sess, st);
-    return launch<4, 4, 2, 2, 1>(w, xq_tiled, mask, X, sx, M, o, sess, st);
+                   int M, const OutlierSet &os, const OutDesc &o, const SessTable *sess, hipStream_t st) {
+    if (M <= 16) return launch<1, 1, 1, 1, 8>(w, xq_tiled, mask, X, sx, M, os, o, sess, st);
+    if (M <= 32) return launch<1, 2, 1, 1, 8>(w, xq_tiled, mask, X, sx, M, os, o, sess, st);
+    if (M <= 64) return launch<1, 4, 1, 1, 8>(w, xq_tiled, mask, X, sx, M, os, o, sess, st);
+    return launch<4, 4, 2, 2, 1>(w, xq_tiled, mask, X, sx, M, os, o, sess, st);
 }
