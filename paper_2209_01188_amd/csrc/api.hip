@@ -82,7 +82,7 @@ Workspace carve(const petals_span_config &c, uint8_t *base) {
     w.x1 = (__half *)take(M * H * 2);
     w.xa = (__half *)take(M * H * 2);
     w.xb = (__half *)take(M * H * 2);
-    w.g = (__half *)take(M * F * 2);
+    w.g = (__half *)take(M * (F > 3 * H ? F : 3 * H) * 2);   // MLP activations; also scratch for a [M,3H] result
     w.xq = (int8_t *)take(Mp * Kmax);
     w.sx = (float *)take(Mp * 4);
     w.mask_words = (Kmax + 63) / 64 * 2;
@@ -174,18 +174,25 @@ struct petals_session {
 
 namespace {
 
-// One linear on M rows already resident as fp16 X[M,K]; picks the one-row or the MFMA path.
-int run_linear(petals_span *sp, const LinearW &w, const __half *X, int M, uint32_t *mask, const OutDesc &o,
-               int8_t *xq_dbg, hipStream_t st, bool row_already_quantized) {
+// One linear on M rows resident as fp16 X[M,K]; picks the one-row or the MFMA path.  ln_g/ln_b non-null:
+// X is the input of the LayerNorm that precedes the linear (fused on the one-row path, a kernel of its own
+// writing ws.a otherwise).  debug: copy the integer intermediates out (one-row path: into ws.xq/mask/ws.sx).
+int run_linear(petals_span *sp, const LinearW &w, const __half *X, const __half *ln_g, const __half *ln_b, int M,
+               uint32_t *mask, const OutDesc &o, int8_t *xq_dbg, bool debug, hipStream_t st) {
     Workspace &ws = sp->ws;
-    const float theta = sp->cfg.outlier_threshold;
+    const petals_span_config &c = sp->cfg;
+    const float theta = c.outlier_threshold;
     if (M == 1) {
-        if (!row_already_quantized) HIP_TRY(ps_rowquant_row(X, w.K, theta, ws.xq, mask, ws.sx, st));
-        if (xq_dbg) HIP_TRY(ps_copy_bytes(ws.xq, xq_dbg, (size_t)w.K, st));
+        RowDebug dbg = {nullptr, nullptr, nullptr, nullptr};
+        if (debug) dbg = RowDebug{ln_g ? ws.a : nullptr, xq_dbg, mask, ws.sx};
         const bool pr = sp->prof.begin(PETALS_PROFILE_GEMV, st);
-        HIP_TRY(ps_gemv_row(w, ws.xq, mask, X, ws.sx, o, ws.table, st));
+        HIP_TRY(ps_gemv_row(w, X, ln_g, ln_b, c.ln_eps, theta, dbg, o, ws.table, st));
         sp->prof.end(pr, st);
     } else {
+        if (ln_g) {
+            HIP_TRY(ps_layernorm(X, ln_g, ln_b, c.ln_eps, M, c.hidden, ws.a, st));
+            X = ws.a;
+        }
         HIP_TRY(ps_fill_u32(mask, ws.mask_words, 0u, st));
         HIP_TRY(ps_colmask(X, M, w.K, theta, mask, st));
         HIP_TRY(ps_rowquant_tiled(X, M, w.K, mask, ws.xq, ws.sx, xq_dbg, st));
@@ -403,31 +410,20 @@ int petals_span_prefill(petals_span *sp, petals_session *const *sessions, int32_
         OutDesc oq = plain_out(ws.q, PETALS_EPILOGUE_NONE, nullptr);
         oq.scatter = 1; oq.T = T; oq.nh = nh; oq.d = d; oq.blk = b;
         // LayerNorm 1 -> fused QKV (queries to ws.q, keys/values appended to the caches)
-        if (M == 1) {
-            HIP_TRY(ps_ln_quant_row(x, W.ln1g, W.ln1b, c.ln_eps, H, c.outlier_threshold, ws.a, ws.xq, mk, ws.sx, st));
-        } else {
-            HIP_TRY(ps_layernorm(x, W.ln1g, W.ln1b, c.ln_eps, M, H, ws.a, st));
-        }
-        if (int rc = run_linear(sp, W.lin[0], ws.a, M, mk, oq, nullptr, st, M == 1)) return rc;
+        if (int rc = run_linear(sp, W.lin[0], x, W.ln1g, W.ln1b, M, mk, oq, nullptr, false, st)) return rc;
         {
             const bool pr = sp->prof.begin(PETALS_PROFILE_ATTENTION, st);
             HIP_TRY(ps_attention(ws.q, ws.table, b, M, T, nh, d, max_keys, ws.partials, ws.ctx, st));
             sp->prof.end(pr, st);
         }
         // dense + residual
-        if (int rc = run_linear(sp, W.lin[1], ws.ctx, M, mk + ws.mask_words,
-                                plain_out(ws.x1, PETALS_EPILOGUE_RESIDUAL, x), nullptr, st, false)) return rc;
+        if (int rc = run_linear(sp, W.lin[1], ws.ctx, nullptr, nullptr, M, mk + ws.mask_words,
+                                plain_out(ws.x1, PETALS_EPILOGUE_RESIDUAL, x), nullptr, false, st)) return rc;
         // LayerNorm 2 -> up + GeLU -> down + residual
-        if (M == 1) {
-            HIP_TRY(ps_ln_quant_row(ws.x1, W.ln2g, W.ln2b, c.ln_eps, H, c.outlier_threshold, ws.a, ws.xq,
-                                    mk + 2 * ws.mask_words, ws.sx, st));
-        } else {
-            HIP_TRY(ps_layernorm(ws.x1, W.ln2g, W.ln2b, c.ln_eps, M, H, ws.a, st));
-        }
-        if (int rc = run_linear(sp, W.lin[2], ws.a, M, mk + 2 * ws.mask_words,
-                                plain_out(ws.g, PETALS_EPILOGUE_GELU, nullptr), nullptr, st, M == 1)) return rc;
-        if (int rc = run_linear(sp, W.lin[3], ws.g, M, mk + 3 * ws.mask_words,
-                                plain_out(xout, PETALS_EPILOGUE_RESIDUAL, ws.x1), nullptr, st, false)) return rc;
+        if (int rc = run_linear(sp, W.lin[2], ws.x1, W.ln2g, W.ln2b, M, mk + 2 * ws.mask_words,
+                                plain_out(ws.g, PETALS_EPILOGUE_GELU, nullptr), nullptr, false, st)) return rc;
+        if (int rc = run_linear(sp, W.lin[3], ws.g, nullptr, nullptr, M, mk + 3 * ws.mask_words,
+                                plain_out(xout, PETALS_EPILOGUE_RESIDUAL, ws.x1), nullptr, false, st)) return rc;
         x = xout;
     }
     for (int s = 0; s < B; s++) sessions[s]->len += T;
@@ -476,7 +472,7 @@ int petals_debug_linear(petals_span *sp, int32_t block, int32_t which, const voi
     OutDesc o = plain_out(yy, epilogue, (const __half *)resid);
     o.acc_out = acc;
     uint32_t *mk = ws.masks;
-    if (int rc = run_linear(sp, L, (const __half *)x, M, mk, o, xq, st, false)) return rc;
+    if (int rc = run_linear(sp, L, (const __half *)x, nullptr, nullptr, M, mk, o, xq, true, st)) return rc;
     if (sx) HIP_TRY(ps_copy_bytes(ws.sx, sx, (size_t)M * 4, st));
     if (outlier_mask) HIP_TRY(ps_mask_to_bytes(mk, L.K, outlier_mask, st));
     return PETALS_OK;
@@ -490,9 +486,14 @@ int petals_debug_layernorm(petals_span *sp, int32_t block, int32_t which, const 
     const BlockW &W = sp->blocks[block];
     const petals_span_config &c = sp->cfg;
     hipStream_t st = (hipStream_t)stream;
-    if (M == 1) {   // the decode path's fused kernel; its quantizer outputs land in the workspace
-        HIP_TRY(ps_ln_quant_row((const __half *)x, which ? W.ln2g : W.ln1g, which ? W.ln2b : W.ln1b, c.ln_eps, c.hidden,
-                                c.outlier_threshold, (__half *)y, sp->ws.xq, sp->ws.masks, sp->ws.sx, st));
+    if (M == 1) {
+        // the decode path normalises inside the linear that follows: run that kernel (QKV or up) and
+        // take its copy of the LayerNorm output; the linear's own result goes to scratch
+        Workspace &ws = sp->ws;
+        RowDebug dbg = {(__half *)y, nullptr, nullptr, nullptr};
+        HIP_TRY(ps_gemv_row(W.lin[which ? 2 : 0], (const __half *)x, which ? W.ln2g : W.ln1g, which ? W.ln2b : W.ln1b,
+                            c.ln_eps, c.outlier_threshold, dbg, plain_out(ws.g, PETALS_EPILOGUE_NONE, nullptr),
+                            ws.table, st));
     } else {
         HIP_TRY(ps_layernorm((const __half *)x, which ? W.ln2g : W.ln1g, which ? W.ln2b : W.ln1b, c.ln_eps, M, c.hidden,
                              (__half *)y, st));

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 #include <stdint.h>
+#include <string.h>
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v2i __attribute__((ext_vector_type(2)));
@@ -67,21 +68,23 @@ hipError_t ps_fill_u32(uint32_t *p, size_t n, uint32_t v, hipStream_t st);
 hipError_t ps_copy_bytes(const void *src, void *dst, size_t n, hipStream_t st);
 hipError_t ps_layernorm(const __half *x, const __half *g, const __half *b, float eps, int M, int H,
                         __half *y, hipStream_t st);
-// M == 1: LayerNorm, outlier detection and int8 quantization of the one row in one kernel
-hipError_t ps_ln_quant_row(const __half *x, const __half *g, const __half *b, float eps, int H, float theta,
-                           __half *y, int8_t *xq, uint32_t *mask, float *sx, hipStream_t st);
 hipError_t ps_colmask(const __half *X, int M, int K, float theta, uint32_t *mask, hipStream_t st);
 // M rows -> tiled int8 codes (rows padded to 16 with zeros), row scales; mask given
 hipError_t ps_rowquant_tiled(const __half *X, int M, int K, const uint32_t *mask, int8_t *xq_tiled, float *sx,
                              int8_t *xq_rowmajor_dbg, hipStream_t st);
-// one row -> its own mask, row-major codes, scale
-hipError_t ps_rowquant_row(const __half *x, int K, float theta, int8_t *xq, uint32_t *mask, float *sx,
-                           hipStream_t st);
 hipError_t ps_mask_to_bytes(const uint32_t *mask, int K, uint8_t *out, hipStream_t st);
 
-// y = mixed int8/fp16 linear for one row (decode, batch 1)
-hipError_t ps_gemv_row(const LinearW &w, const int8_t *xq, const uint32_t *mask, const __half *x, const float *sx,
-                       const OutDesc &o, const SessTable *sess, hipStream_t st);
+// optional copies of the one-row path's intermediates for tests (each may be null)
+struct RowDebug {
+    __half *a_out;       // LayerNorm output [K]
+    int8_t *xq_out;      // int8 codes [K]
+    uint32_t *mask_out;  // outlier bit mask [K/32]
+    float *sx_out;       // row scale
+};
+// y = mixed int8/fp16 linear of ONE fp16 row x[K] (decode, batch 1); with ln_g/ln_b non-null the row
+// first goes through LayerNorm.  Outlier detection and int8 quantization happen inside the kernel.
+hipError_t ps_gemv_row(const LinearW &w, const __half *x, const __half *ln_g, const __half *ln_b, float eps,
+                       float theta, const RowDebug &dbg, const OutDesc &o, const SessTable *sess, hipStream_t st);
 // counts the outlier columns of a call and, if they are few, compacts their operands
 hipError_t ps_outlier_prep(const LinearW &w, const uint32_t *mask, const __half *X, int M, int *count, double *wd64,
                            double *x64, hipStream_t st);

@@ -1,100 +1,286 @@
-// Decode-time linear for ONE row (batch-1 generation): streams the int8 weight tiles of
-// a 16-row panel from HBM once, 16 bytes per lane per load, and accumulates with
-// v_dot4_i32_i8.  HBM-bound: every weight byte is read exactly once per token.
+// Decode-time linear for ONE row (batch-1 generation).  Every workgroup first turns the
+// fp16 input row into int8 codes in LDS (optionally after a LayerNorm), then streams the
+// int8 weight tiles of its 16-row panel from HBM once, 16 bytes per lane per load, and
+// accumulates with v_dot4_i32_i8.  HBM-bound: every weight byte is read exactly once per
+// token; the input row (a few tens of KB) comes from L2.
+#include <stdlib.h>
+
 #include "common.h"
 #include "epilogue.h"
 
 namespace {
+
+typedef unsigned short us2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ int byte_of(const v4i &w, int j) {
     int word = (j < 8) ? ((j < 4) ? w[0] : w[1]) : ((j < 12) ? w[2] : w[3]);
     return (int)(int8_t)((word >> ((j & 3) * 8)) & 0xff);
 }
 
-// fp16 part of a 16-column group that contains outlier columns (rare path)
-__device__ __forceinline__ double outlier_group(const v4i &w, uint32_t bits, const __half *__restrict__ xp, float swd) {
+__device__ __forceinline__ uint32_t pk_max(uint32_t a, uint32_t b) {
+    us2 r = __builtin_elementwise_max(*(us2 *)&a, *(us2 *)&b);
+    return *(uint32_t *)&r;
+}
+
+struct RowIn {
+    const __half *x;            // the input row [K]
+    const __half *ln_g, *ln_b;  // LayerNorm gain/bias (used by the LN variant)
+    float eps;
+    uint32_t theta_bits;
+    // optional copies for tests, written by workgroup 0 (each may be null)
+    __half *a_out;              // LayerNorm output
+    int8_t *xq_out;
+    uint32_t *mask_out;
+    float *sx_out;
+};
+
+// The fp16 value of column k the linear sees: the input itself, or its LayerNorm.
+template <bool LN>
+__device__ __forceinline__ __half row_value(const RowIn &in, int k, double mean, double inv) {
+    if (!LN) return in.x[k];
+    return d2h_rn(((double)__half2float(in.x[k]) - mean) * inv * (double)__half2float(in.ln_g[k]) +
+                  (double)__half2float(in.ln_b[k]));
+}
+
+// fp16 part of a 16-column group that contains outlier columns (rare path), in fp64
+template <bool LN>
+__device__ __forceinline__ double outlier_group(const v4i &w, uint32_t bits, const RowIn &in, int k0, double mean,
+                                                double inv, float swd) {
     double o = 0.0;
     while (bits) {
         const int j = __ffs(bits) - 1;
         bits &= bits - 1;
-        o += (double)__half2float(xp[j]) * (double)dequant_w16(byte_of(w, j), swd);
+        o += (double)__half2float(row_value<LN>(in, k0 + j, mean, inv)) * (double)dequant_w16(byte_of(w, j), swd);
     }
     return o;
 }
 
-__device__ __forceinline__ void tile_mac(const v4i &wv, const int8_t *xs, const uint16_t *ms,
-                                         const __half *__restrict__ x, int kt, int kg, float swd, int &acc,
-                                         double &outl) {
-    const v4i xv = *(const v4i *)(xs + kt * 64 + kg * 16);
-    acc = __builtin_amdgcn_sdot4(wv[0], xv[0], acc, false);
-    acc = __builtin_amdgcn_sdot4(wv[1], xv[1], acc, false);
-    acc = __builtin_amdgcn_sdot4(wv[2], xv[2], acc, false);
-    acc = __builtin_amdgcn_sdot4(wv[3], xv[3], acc, false);
-    const uint32_t bits = ms[kt * 4 + kg];
-    if (bits) outl += outlier_group(wv, bits, x + kt * 64 + kg * 16, swd);
+constexpr int GEMV_THREADS = 512;    // 8 waves share one 16-row panel at a time
+
+// Persistent-style one-row linear.  The grid is sized so that every workgroup is resident at
+// once (up to two per compute unit) and owns a contiguous range of 16-row panels.  Each workgroup
+//  1. (LN variant) normalises the row in fp64,
+//  2. marks outlier columns (|v| >= threshold, compared as fp16 bit patterns, which order like
+//     the magnitudes), takes the absolute maximum of the rest, writes int8 codes to LDS;
+//     all of it from registers, once per workgroup,
+//  3. streams its panels one after the other: the 8 waves split a panel's K/64 tiles in chunks of U
+//     consecutive tiles; lane l holds row l%16 and the 16 columns of group l/16, so one wave
+//     load is 1 KB contiguous; v_dot4_i32_i8 accumulates exactly.
+template <int U, int MAXCH, bool LN>
+__global__ void __launch_bounds__(GEMV_THREADS) k_gemv_row(LinearW w, RowIn in, OutDesc o,
+                                                           const SessTable *__restrict__ sess, int panels_per_wg,
+                                                           int panels_extra) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    __shared__ double smd[8];
+    __shared__ int smi[8];
+    const int K = w.K, KT = K >> 6, nch8 = K >> 3;
+    int8_t *xs = (int8_t *)lds;                               // K codes
+    uint8_t *m8 = (uint8_t *)(lds + K);                       // K/8 mask bytes = K/16 group masks
+    int *red_i = (int *)(lds + K + K / 8);                    // [2 parities][8 waves][16]
+    double *red_f = (double *)(red_i + 256);                  // same shape
+    const uint16_t *ms = (const uint16_t *)m8;
+    const bool first = blockIdx.x == 0;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, kg = lane >> 4, tw = wave;
+    // this workgroup's panels: [p0, p0 + np)
+    const int g = blockIdx.x;
+    const int np = panels_per_wg + (g < panels_extra ? 1 : 0);
+    const int p0 = g * panels_per_wg + min(g, panels_extra);
+    const int nchunks = KT / U;
+
+    // start the first weight chunk now: HBM stays busy while the row is being quantized
+    v4i wv[U];
+    if (tw < nchunks) {
+        const v4i *wp = (const v4i *)(w.wt + (size_t)p0 * KT * 1024) + lane;
+#pragma unroll
+        for (int u = 0; u < U; u++) wv[u] = __builtin_nontemporal_load(wp + (size_t)(tw * U + u) * 64);
+    }
+
+    for (int i = threadIdx.x; i < K / 32; i += GEMV_THREADS) ((uint32_t *)m8)[i] = 0u;
+    double mean = 0.0, inv = 0.0;
+    if (LN) {
+        double s = 0.0;
+        for (int c = threadIdx.x; c < nch8; c += GEMV_THREADS) {
+            v8h v = *(const v8h *)(in.x + c * 8);
+#pragma unroll
+            for (int e = 0; e < 8; e++) s += (double)(float)v[e];
+        }
+        mean = block_sum<8>(s, smd) / (double)K;
+        double q = 0.0;
+        for (int c = threadIdx.x; c < nch8; c += GEMV_THREADS) {
+            v8h v = *(const v8h *)(in.x + c * 8);
+#pragma unroll
+            for (int e = 0; e < 8; e++) { const double a = (double)(float)v[e] - mean; q += a * a; }
+        }
+        inv = 1.0 / sqrt(block_sum<8>(q, smd) / (double)K + (double)in.eps);
+    } else {
+        __syncthreads();      // mask bytes cleared before anybody sets one
+    }
+
+    // detect + absolute maximum over regular columns, 8 columns per register quad
+    v4i vals[MAXCH];
+    uint32_t mreg = 0;
+#pragma unroll
+    for (int i = 0; i < MAXCH; i++) {
+        const int c = threadIdx.x + GEMV_THREADS * i;
+        if (c < nch8) {
+            if (LN) {
+                v8h v = *(const v8h *)(in.x + c * 8), gg = *(const v8h *)(in.ln_g + c * 8), bb = *(const v8h *)(in.ln_b + c * 8);
+                __half out[8];
+#pragma unroll
+                for (int e = 0; e < 8; e++)
+                    out[e] = d2h_rn(((double)(float)v[e] - mean) * inv * (double)(float)gg[e] + (double)(float)bb[e]);
+                vals[i] = *(const v4i *)out;
+                if (first && in.a_out) *(v4i *)(in.a_out + c * 8) = vals[i];
+            } else {
+                vals[i] = *(const v4i *)(in.x + c * 8);
+            }
+            const uint32_t a0 = vals[i][0] & 0x7fff7fffu, a1 = vals[i][1] & 0x7fff7fffu;
+            const uint32_t a2 = vals[i][2] & 0x7fff7fffu, a3 = vals[i][3] & 0x7fff7fffu;
+            const uint32_t cm = pk_max(pk_max(a0, a1), pk_max(a2, a3));
+            const uint32_t cmax = max(cm & 0xffffu, cm >> 16);
+            if (cmax >= in.theta_bits) {
+                uint32_t byte = 0;
+#pragma unroll
+                for (int e = 0; e < 8; e++) {
+                    const uint32_t a = ((uint32_t)vals[i][e >> 1] >> ((e & 1) * 16)) & 0x7fffu;
+                    if (a >= in.theta_bits) byte |= 1u << e; else mreg = max(mreg, a);
+                }
+                m8[c] = (uint8_t)byte;
+            } else {
+                mreg = max(mreg, cmax);
+            }
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mreg = max(mreg, (uint32_t)__shfl_xor((int)mreg, off));
+    if (lane == 0) smi[wave] = (int)mreg;
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 8; i++) mreg = max(mreg, (uint32_t)smi[i]);
+    const unsigned short sb = (unsigned short)mreg;
+    const float s_x = __half2float(*(const __half *)&sb);
+    const float r = s_x > 0.0f ? 127.0f / s_x : 0.0f;
+#pragma unroll
+    for (int i = 0; i < MAXCH; i++) {
+        const int c = threadIdx.x + GEMV_THREADS * i;
+        if (c < nch8) {
+            const uint32_t byte = m8[c];          // set above by this same thread (0 from the initial clear)
+            int q[8];
+#pragma unroll
+            for (int e = 0; e < 8; e++) {
+                const unsigned short hb = (unsigned short)((uint32_t)vals[i][e >> 1] >> ((e & 1) * 16));
+                q[e] = ((byte >> e) & 1u) ? 0 : q8(__half2float(*(const __half *)&hb), r);
+            }
+            v2i o2 = {pack4(q[0], q[1], q[2], q[3]), pack4(q[4], q[5], q[6], q[7])};
+            *(v2i *)(xs + c * 8) = o2;
+        }
+    }
+    __syncthreads();
+    if (first) {
+        if (in.sx_out && threadIdx.x == 0) *in.sx_out = s_x;
+        if (in.xq_out) for (int i = threadIdx.x; i < K / 16; i += GEMV_THREADS) ((v4i *)in.xq_out)[i] = ((const v4i *)xs)[i];
+        if (in.mask_out) for (int i = threadIdx.x; i < K / 32; i += GEMV_THREADS) in.mask_out[i] = ((const uint32_t *)m8)[i];
+    }
+
+    for (int it = 0; it < np; it++) {
+        const bool active = true;
+        const int p = p0 + it;
+        const v4i *wp = (const v4i *)(w.wt + (size_t)p * KT * 1024) + lane;
+        const int n = p * 16 + (lane & 15);
+        const float swd = w.sw[n] / 127.0f;
+        int acc = 0;
+        double outl = 0.0;
+        if (active) {
+            for (int c = tw; c < nchunks; c += 8) {
+                if (it > 0 || c > tw) {                // the very first chunk was loaded before the prologue
+#pragma unroll
+                    for (int u = 0; u < U; u++) wv[u] = __builtin_nontemporal_load(wp + (size_t)(c * U + u) * 64);
+                }
+#pragma unroll
+                for (int u = 0; u < U; u++) {
+                    const int kt = c * U + u;
+                    const v4i xv = *(const v4i *)(xs + kt * 64 + kg * 16);
+                    acc = __builtin_amdgcn_sdot4(wv[u][0], xv[0], acc, false);
+                    acc = __builtin_amdgcn_sdot4(wv[u][1], xv[1], acc, false);
+                    acc = __builtin_amdgcn_sdot4(wv[u][2], xv[2], acc, false);
+                    acc = __builtin_amdgcn_sdot4(wv[u][3], xv[3], acc, false);
+                    const uint32_t bits = ms[kt * 4 + kg];
+                    if (bits) outl += outlier_group<LN>(wv[u], bits, in, kt * 64 + kg * 16, mean, inv, swd);
+                }
+            }
+            for (int kt = nchunks * U + tw; kt < KT; kt += 8) {
+                const v4i w1 = __builtin_nontemporal_load(wp + (size_t)kt * 64);
+                const v4i xv = *(const v4i *)(xs + kt * 64 + kg * 16);
+                acc = __builtin_amdgcn_sdot4(w1[0], xv[0], acc, false);
+                acc = __builtin_amdgcn_sdot4(w1[1], xv[1], acc, false);
+                acc = __builtin_amdgcn_sdot4(w1[2], xv[2], acc, false);
+                acc = __builtin_amdgcn_sdot4(w1[3], xv[3], acc, false);
+                const uint32_t bits = ms[kt * 4 + kg];
+                if (bits) outl += outlier_group<LN>(w1, bits, in, kt * 64 + kg * 16, mean, inv, swd);
+            }
+        }
+        acc += __shfl_xor(acc, 16);
+        acc += __shfl_xor(acc, 32);
+        outl += __shfl_xor(outl, 16);
+        outl += __shfl_xor(outl, 32);
+        int *ri = red_i + (it & 1) * 128;
+        double *rf = red_f + (it & 1) * 128;
+        if (lane < 16) { ri[wave * 16 + lane] = acc; rf[wave * 16 + lane] = outl; }
+        __syncthreads();
+        if (tw == 0 && lane < 16) {                    // lanes 0..15 of the first wave finish the 16 rows
+            int a = 0;
+            double f = 0.0;
+#pragma unroll
+            for (int i = 0; i < 8; i++) { a += ri[i * 16 + lane]; f += rf[i * 16 + lane]; }
+            emit_output(o, sess, w.N, 0, n, a, f, s_x / 127.0f, swd, __half2float(w.bias[n]));
+        }
+    }
 }
 
-// One workgroup (8 waves) per 16-row panel; the waves split the panel's K/64 tiles in
-// chunks of U consecutive tiles (U KB in flight per wave).  Lane l holds row l%16 and
-// the 16 columns of column group l/16, so a wave's load of one tile is 1 KB contiguous.
-template <int U>
-__global__ void __launch_bounds__(512) k_gemv_row(LinearW w, const int8_t *__restrict__ xq,
-                                                  const uint32_t *__restrict__ mask, const __half *__restrict__ x,
-                                                  const float *__restrict__ sx, OutDesc o,
-                                                  const SessTable *__restrict__ sess) {
-    extern __shared__ __align__(16) unsigned char lds[];
-    const int K = w.K, KT = K >> 6;
-    int8_t *xs = (int8_t *)lds;                               // K codes
-    uint16_t *ms = (uint16_t *)(lds + K);                     // K/16 group masks
-    int *red_i = (int *)(lds + K + K / 8);                    // [8][16]
-    double *red_f = (double *)(red_i + 128);                  // [8][16]
-    for (int i = threadIdx.x; i < K / 16; i += 512) ((v4i *)xs)[i] = ((const v4i *)xq)[i];
-    for (int i = threadIdx.x; i < K / 32; i += 512) ((uint32_t *)ms)[i] = mask[i];
-    __syncthreads();
+template <int U, int MAXCH>
+hipError_t launch2(bool ln, const LinearW &w, const RowIn &in, const OutDesc &o, const SessTable *sess, hipStream_t st) {
+    const size_t lds = (size_t)w.K + w.K / 8 + 256 * 12;
+    // one resident round: at most 2 workgroups per compute unit; prefer a split without remainder
+    const int panels = w.N / 16, max_wg = 512;
+    int G = min(max_wg, panels);
+    for (int cand = G; cand >= max(1, (G * 3) / 4); cand--)
+        if (panels % cand == 0) { G = cand; break; }
+    const int per = panels / G, extra = panels % G;
+    if (ln) k_gemv_row<U, MAXCH, true><<<G, GEMV_THREADS, lds, st>>>(w, in, o, sess, per, extra);
+    else k_gemv_row<U, MAXCH, false><<<G, GEMV_THREADS, lds, st>>>(w, in, o, sess, per, extra);
+    return hipGetLastError();
+}
 
-    const int p = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63, kg = lane >> 4;
-    const int n = p * 16 + (lane & 15);
-    const float swd = w.sw[n] / 127.0f;
-    const v4i *wp = (const v4i *)(w.wt + (size_t)p * KT * 1024) + lane;
-    int acc = 0;
-    double outl = 0.0;
-    const int nchunks = KT / U;
-    for (int c = wave; c < nchunks; c += 8) {
-        v4i wv[U];
-#pragma unroll
-        for (int u = 0; u < U; u++) wv[u] = __builtin_nontemporal_load(wp + (size_t)(c * U + u) * 64);
-#pragma unroll
-        for (int u = 0; u < U; u++) tile_mac(wv[u], xs, ms, x, c * U + u, kg, swd, acc, outl);
-    }
-    for (int kt = nchunks * U + wave; kt < KT; kt += 8) {
-        v4i wv = __builtin_nontemporal_load(wp + (size_t)kt * 64);
-        tile_mac(wv, xs, ms, x, kt, kg, swd, acc, outl);
-    }
-    acc += __shfl_xor(acc, 16);
-    acc += __shfl_xor(acc, 32);
-    outl += __shfl_xor(outl, 16);
-    outl += __shfl_xor(outl, 32);
-    if (lane < 16) { red_i[wave * 16 + lane] = acc; red_f[wave * 16 + lane] = outl; }
-    __syncthreads();
-    if (threadIdx.x < 16) {
-        int a = 0;
-        double f = 0.0;
-#pragma unroll
-        for (int i = 0; i < 8; i++) { a += red_i[i * 16 + threadIdx.x]; f += red_f[i * 16 + threadIdx.x]; }
-        emit_output(o, sess, w.N, 0, n, a, f, sx[0] / 127.0f, swd, __half2float(w.bias[n]));
-    }
+template <int U>
+hipError_t launch1(bool ln, const LinearW &w, const RowIn &in, const OutDesc &o, const SessTable *sess, hipStream_t st) {
+    const int per_thread = (w.K / 8 + GEMV_THREADS - 1) / GEMV_THREADS;   // 8-column chunks a thread holds in registers
+    if (per_thread <= 1) return launch2<U, 1>(ln, w, in, o, sess, st);
+    if (per_thread <= 4) return launch2<U, 4>(ln, w, in, o, sess, st);
+    return launch2<U, 16>(ln, w, in, o, sess, st);
+}
+
+// smallest non-negative fp16 bit pattern whose value is >= theta
+uint32_t theta_to_bits(float theta) {
+    if (!(theta > 0.0f)) return 0u;
+    _Float16 h = (_Float16)theta;          // round to nearest
+    unsigned short b;
+    memcpy(&b, &h, 2);
+    if ((float)h < theta) b++;             // next pattern up (0x7bff + 1 = 0x7c00 = +inf)
+    return b;
 }
 
 }  // namespace
 
-hipError_t ps_gemv_row(const LinearW &w, const int8_t *xq, const uint32_t *mask, const __half *x, const float *sx,
-                       const OutDesc &o, const SessTable *sess, hipStream_t st) {
+hipError_t ps_gemv_row(const LinearW &w, const __half *x, const __half *ln_g, const __half *ln_b, float eps,
+                       float theta, const RowDebug &dbg, const OutDesc &o, const SessTable *sess, hipStream_t st) {
+    RowIn in;
+    in.x = x; in.ln_g = ln_g; in.ln_b = ln_b; in.eps = eps; in.theta_bits = theta_to_bits(theta);
+    in.a_out = dbg.a_out; in.xq_out = dbg.xq_out; in.mask_out = dbg.mask_out; in.sx_out = dbg.sx_out;
+    const bool ln = ln_g != nullptr;
     const int KT = w.K / 64;
-    const size_t lds = (size_t)w.K + w.K / 8 + 128 * 12;
-    const dim3 grid(w.N / 16), block(512);
-    if (KT % 64 == 0) k_gemv_row<8><<<grid, block, lds, st>>>(w, xq, mask, x, sx, o, sess);
-    else if (KT % 32 == 0) k_gemv_row<4><<<grid, block, lds, st>>>(w, xq, mask, x, sx, o, sess);
-    else if (KT % 16 == 0) k_gemv_row<2><<<grid, block, lds, st>>>(w, xq, mask, x, sx, o, sess);
-    else k_gemv_row<1><<<grid, block, lds, st>>>(w, xq, mask, x, sx, o, sess);
-    return hipGetLastError();
+    static const int umax = getenv("PS_GEMV_U") ? atoi(getenv("PS_GEMV_U")) : 4;   // tuning knob: tiles per chunk
+    if (KT % 64 == 0 && umax >= 8) return launch1<8>(ln, w, in, o, sess, st);
+    if (KT % 32 == 0 && umax >= 4) return launch1<4>(ln, w, in, o, sess, st);
+    if (KT % 16 == 0) return launch1<2>(ln, w, in, o, sess, st);
+    return launch1<1>(ln, w, in, o, sess, st);
 }

@@ -103,68 +103,6 @@ __global__ void __launch_bounds__(256) k_layernorm(const __half *__restrict__ x,
                                          *(const __half2 *)(b + k), mean, inv);
 }
 
-// ------------------------------------------- one-row detect + quantize (decode)
-
-// The row sits in LDS as fp16.  Marks outlier columns (|y| >= theta), takes the
-// absolute maximum of the remaining columns, writes int8 codes (0 on outliers).
-// 1024 threads; H % 64 == 0.
-__device__ __forceinline__ void row_detect_quantize(const __half *ys, int H, float theta, uint32_t *mask_lds,
-                                                    float *sm, int8_t *xq, uint32_t *mask, float *sx) {
-    const int lane = threadIdx.x & 63;
-    float m = 0.0f;
-    for (int k0 = (threadIdx.x >> 6) * 64; k0 < H; k0 += 1024) {       // wave-uniform
-        float a = fabsf(__half2float(ys[k0 + lane]));
-        bool out = a >= theta;
-        unsigned long long bal = __ballot(out);
-        if (lane == 0) {
-            mask_lds[k0 >> 5] = (uint32_t)bal;
-            mask_lds[(k0 >> 5) + 1] = (uint32_t)(bal >> 32);
-            mask[k0 >> 5] = (uint32_t)bal;
-            mask[(k0 >> 5) + 1] = (uint32_t)(bal >> 32);
-        }
-        if (!out) m = fmaxf(m, a);
-    }
-    const float s = block_max<16>(m, sm);   // also orders the mask_lds writes before the reads below
-    if (threadIdx.x == 0) *sx = s;
-    const float r = s > 0.0f ? 127.0f / s : 0.0f;
-    for (int k = threadIdx.x * 4; k < H; k += 4096) {
-        uint32_t bits = (mask_lds[k >> 5] >> (k & 31)) & 0xfu;
-        int c[4];
-#pragma unroll
-        for (int j = 0; j < 4; j++) c[j] = ((bits >> j) & 1u) ? 0 : q8(__half2float(ys[k + j]), r);
-        *(int *)(xq + k) = pack4(c[0], c[1], c[2], c[3]);
-    }
-}
-
-__global__ void __launch_bounds__(1024) k_ln_quant_row(const __half *__restrict__ x, const __half *__restrict__ g,
-                                                       const __half *__restrict__ b, float eps, int H, float theta,
-                                                       __half *__restrict__ y, int8_t *__restrict__ xq,
-                                                       uint32_t *__restrict__ mask, float *__restrict__ sx) {
-    extern __shared__ __align__(16) unsigned char lds[];
-    __half *ys = (__half *)lds;                            // H halves
-    uint32_t *mask_lds = (uint32_t *)(lds + (size_t)H * 2);   // H/32 words
-    __shared__ float sm[16];
-    __shared__ double smd[16];
-    double mean, inv;
-    row_moments<1024>(x, H, smd, mean, inv, (double)eps);
-    for (int k = threadIdx.x * 2; k < H; k += 2048) {
-        __half2 o = ln_affine(*(const __half2 *)(x + k), *(const __half2 *)(g + k), *(const __half2 *)(b + k), mean, inv);
-        *(__half2 *)(ys + k) = o;
-        *(__half2 *)(y + k) = o;
-    }
-    __syncthreads();
-    row_detect_quantize(ys, H, theta, mask_lds, sm, xq, mask, sx);
-}
-
-__global__ void __launch_bounds__(1024) k_rowquant_row(const __half *__restrict__ x, int K, float theta,
-                                                       int8_t *__restrict__ xq, uint32_t *__restrict__ mask,
-                                                       float *__restrict__ sx) {
-    extern __shared__ __align__(16) unsigned char lds[];
-    uint32_t *mask_lds = (uint32_t *)lds;                  // K/32 words; the row itself is read from global
-    __shared__ float sm[16];
-    row_detect_quantize(x, K, theta, mask_lds, sm, xq, mask, sx);
-}
-
 // -------------------------------------------------- many rows: mask, then quantize
 
 // Column c is an outlier if any row reaches theta.  grid.x covers columns (64 per
@@ -314,18 +252,6 @@ hipError_t ps_copy_bytes(const void *src, void *dst, size_t n, hipStream_t st) {
 hipError_t ps_layernorm(const __half *x, const __half *g, const __half *b, float eps, int M, int H, __half *y,
                         hipStream_t st) {
     k_layernorm<<<M, 256, 0, st>>>(x, g, b, eps, H, y);
-    return hipGetLastError();
-}
-hipError_t ps_ln_quant_row(const __half *x, const __half *g, const __half *b, float eps, int H, float theta,
-                           __half *y, int8_t *xq, uint32_t *mask, float *sx, hipStream_t st) {
-    size_t lds = (size_t)H * 2 + (size_t)H / 8 + 16;
-    k_ln_quant_row<<<1, 1024, lds, st>>>(x, g, b, eps, H, theta, y, xq, mask, sx);
-    return hipGetLastError();
-}
-hipError_t ps_rowquant_row(const __half *x, int K, float theta, int8_t *xq, uint32_t *mask, float *sx,
-                           hipStream_t st) {
-    size_t lds = (size_t)K / 8 + 16;
-    k_rowquant_row<<<1, 1024, lds, st>>>(x, K, theta, xq, mask, sx);
     return hipGetLastError();
 }
 hipError_t ps_colmask(const __half *X, int M, int K, float theta, uint32_t *mask, hipStream_t st) {
