@@ -109,7 +109,13 @@ def main():
 
     results = {}
     for L in prefixes:
-        ms, wall_ms, prof = timed_decode(L, profile=not args.no_profile_events)
+        # the throughput figure is timed with no instrumentation in the stream; a second pass over the same
+        # steps brackets every heavy launch with HIP events (they cost a few microseconds each) to get the
+        # dominant kernel's own duration
+        ms, wall_ms, _ = timed_decode(L, profile=False)
+        prof = None
+        if L == args.prefix and not args.no_profile_events:
+            _, _, prof = timed_decode(L, profile=True)
         total = max(ms, wall_ms) if abs(ms - wall_ms) > 0.2 * wall_ms else ms
         results[L] = dict(ms_per_step=total / K, tok_s=K / (total / 1e3), gbs=step_bytes(cfg, L) / (total / K / 1e3) / 1e9,
                           prof=prof)

@@ -118,6 +118,120 @@ __global__ void __launch_bounds__(256) k_attn(const __half *__restrict__ q, cons
     }
 }
 
+// softmax state of a set of keys: running maximum m, sum l of exp(z - m), weighted value sum o
+__device__ __forceinline__ void merge_state(double &m, double &l, double *o, double m2, double l2, const double *o2,
+                                            int n) {
+    const double mm = fmax(m, m2);
+    const double fa = (m == -INFINITY) ? 0.0 : exp(m - mm), fb = (m2 == -INFINITY) ? 0.0 : exp(m2 - mm);
+    l = l * fa + l2 * fb;
+    for (int e = 0; e < n; e++) o[e] = o[e] * fa + o2[e] * fb;
+    m = mm;
+}
+
+// Decode (one query per session): every wave owns a contiguous slice of the key range and runs
+// its own online softmax over 64-key blocks with no workgroup barrier in the loop.  Inside a
+// wave, head_dim/8 neighbouring lanes share a key (16 bytes of it each), so one load
+// instruction reads 1 KB of consecutive cache bytes; each lane group keeps its own softmax
+// state, the groups, then the 4 waves, then the key ranges are merged at the end.  fp64
+// throughout: the kernel waits on HBM anyway, and the fp16 context then equals the exactly
+// rounded one.
+template <int D>
+__global__ void __launch_bounds__(256) k_attn_decode(const __half *__restrict__ q, const SessTable *__restrict__ sess,
+                                                     int blk, int nh, int CH, int nsplit,
+                                                     double *__restrict__ partials, __half *__restrict__ ctx) {
+    constexpr int LPK = D / 8, KPI = 64 / LPK, NIT = LPK;
+    __shared__ double red_m[4], red_l[4], red_o[4][D];
+    const int c = blockIdx.x, h = blockIdx.y, s = blockIdx.z;
+    const int i = sess->len[s];                                // position of the query; keys 0..i
+    const int k_begin = c * CH, k_end = min(i + 1, k_begin + CH);
+    if (k_begin >= k_end) return;                              // whole workgroup leaves together
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, sub = lane % LPK, kslot = lane / LPK;
+    const int cap = sess->cap[s], H = nh * D;
+    const __half *Kc = sess->kv[s] + ((size_t)blk * 2 * nh + h) * cap * D;
+    const __half *Vc = Kc + (size_t)nh * cap * D;
+    const double slope = sess->slopes[h], rsd = sqrt((double)D);
+    const int per = (((k_end - k_begin + 3) >> 2) + 63) & ~63;
+    const int wb = k_begin + wave * per, we = min(k_end, wb + per);
+    double qf[8];
+    {
+        v8h qv = *(const v8h *)(q + (size_t)s * H + h * D + sub * 8);
+#pragma unroll
+        for (int e = 0; e < 8; e++) qf[e] = (double)(float)qv[e];
+    }
+    double m_run = -INFINITY, l_run = 0.0, o[8];
+#pragma unroll
+    for (int e = 0; e < 8; e++) o[e] = 0.0;
+
+    for (int base = wb; base < we; base += 64) {
+        double sc_mine = -INFINITY, mb = -INFINITY;
+#pragma unroll
+        for (int it = 0; it < NIT; it++) {
+            const int j = base + it * KPI + kslot;
+            double dot = 0.0;
+            if (j < we) {
+                v8h kv = *(const v8h *)(Kc + (size_t)j * D + sub * 8);
+#pragma unroll
+                for (int e = 0; e < 8; e++) dot += qf[e] * (double)(float)kv[e];
+            }
+#pragma unroll
+            for (int off = 1; off < LPK; off <<= 1) dot += __shfl_xor(dot, off);
+            const double sc = (j < we) ? dot / rsd - slope * (double)(i - j) : -INFINITY;
+            mb = fmax(mb, sc);
+            if (sub == it) sc_mine = sc;                       // lane `sub` of a group exponentiates key `it`
+        }
+        if (mb == -INFINITY) continue;                         // no key of this lane group in the block (uniform per group)
+        const double m_new = fmax(m_run, mb);
+        const double alpha = (m_run == -INFINITY) ? 0.0 : exp(m_run - m_new);
+        const double p_mine = exp(sc_mine - m_new);            // exp(-inf) = 0 for keys past the end
+        double psum = p_mine;
+#pragma unroll
+        for (int off = 1; off < LPK; off <<= 1) psum += __shfl_xor(psum, off);
+        l_run = l_run * alpha + psum;
+        m_run = m_new;
+#pragma unroll
+        for (int e = 0; e < 8; e++) o[e] *= alpha;
+#pragma unroll
+        for (int it = 0; it < NIT; it++) {
+            const int j = base + it * KPI + kslot;
+            const double p = __shfl(p_mine, kslot * LPK + it);
+            if (j < we) {
+                v8h vv = *(const v8h *)(Vc + (size_t)j * D + sub * 8);
+#pragma unroll
+                for (int e = 0; e < 8; e++) o[e] += p * (double)(float)vv[e];
+            }
+        }
+    }
+    // merge the lane groups of the wave (same dims, different keys)
+#pragma unroll
+    for (int off = LPK; off < 64; off <<= 1) {
+        const double m2 = __shfl_xor(m_run, off), l2 = __shfl_xor(l_run, off);
+        double o2[8];
+#pragma unroll
+        for (int e = 0; e < 8; e++) o2[e] = __shfl_xor(o[e], off);
+        merge_state(m_run, l_run, o, m2, l2, o2, 8);
+    }
+    if (kslot == 0) {
+        if (sub == 0) { red_m[wave] = m_run; red_l[wave] = l_run; }
+#pragma unroll
+        for (int e = 0; e < 8; e++) red_o[wave][sub * 8 + e] = o[e];
+    }
+    __syncthreads();
+    if (threadIdx.x < D) {
+        double m = red_m[0], l = red_l[0], ov = red_o[0][threadIdx.x];
+        for (int w2 = 1; w2 < 4; w2++) {
+            const double o2 = red_o[w2][threadIdx.x];
+            merge_state(m, l, &ov, red_m[w2], red_l[w2], &o2, 1);
+        }
+        if (nsplit == 1) {
+            ctx[(size_t)s * H + h * D + threadIdx.x] = d2h_rn(ov / l);
+        } else {
+            double *pp = partials + ((size_t)(s * nh + h) * nsplit + c) * (D + 2);
+            if (threadIdx.x == 0) { pp[0] = m; pp[1] = l; }
+            pp[2 + threadIdx.x] = ov;
+        }
+    }
+}
+
 // merges the per-range partial results of one (row, head) in a fixed order
 template <int D>
 __global__ void k_attn_combine(const SessTable *__restrict__ sess, int T, int nh, int CH, int nsplit,
@@ -147,7 +261,9 @@ hipError_t attn_launch(const __half *q, const SessTable *sess, int blk, int M, i
     if ((size_t)M * nh * nsplit > PS_ATTN_PARTIAL_SLOTS) nsplit = 1;
     int CH = ((max_keys + nsplit - 1) / nsplit + 255) / 256 * 256;
     if (nsplit == 1) CH = 1 << 30;
-    if (T == 1 || !getenv("PS_ATTN_F32"))
+    if (T == 1)
+        k_attn_decode<D><<<dim3(nsplit, nh, M), 256, 0, st>>>(q, sess, blk, nh, CH, nsplit, partials, ctx);
+    else if (!getenv("PS_ATTN_F32"))
         k_attn<D, double><<<dim3(nsplit, nh, M), 256, 0, st>>>(q, sess, blk, T, nh, CH, nsplit, partials, ctx);
     else
         k_attn<D, float><<<dim3(nsplit, nh, M), 256, 0, st>>>(q, sess, blk, T, nh, CH, nsplit, partials, ctx);
