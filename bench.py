@@ -49,6 +49,9 @@ def main():
     ap.add_argument("--prefix", type=int, default=2048, help="KV-cache prefix length of the headline figure")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile-events", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one 1 GiB device-to-device copy, the known-size kernel that scales rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (a span per GPU; see DESIGN.md for how spans chain); "
@@ -106,6 +109,13 @@ def main():
         prof = binding.petals_span_profile_end(span.handle) if profile else None
         se.close()
         return max(ms, 0.0), wall_ms, prof
+
+    if args.calibration_copy:
+        src = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     results = {}
     for L in prefixes:

@@ -163,42 +163,47 @@ __global__ void __launch_bounds__(256) k_attn_decode(const __half *__restrict__ 
     for (int e = 0; e < 8; e++) o[e] = 0.0;
 
     for (int base = wb; base < we; base += 64) {
+        // all loads of the block are issued unconditionally (index clamped into the slice) so they
+        // go out back to back; out-of-range keys are masked by their score
+        v8h kv[NIT];
+#pragma unroll
+        for (int it = 0; it < NIT; it++)
+            kv[it] = *(const v8h *)(Kc + (size_t)min(base + it * KPI + kslot, we - 1) * D + sub * 8);
         double sc_mine = -INFINITY, mb = -INFINITY;
 #pragma unroll
         for (int it = 0; it < NIT; it++) {
             const int j = base + it * KPI + kslot;
             double dot = 0.0;
-            if (j < we) {
-                v8h kv = *(const v8h *)(Kc + (size_t)j * D + sub * 8);
 #pragma unroll
-                for (int e = 0; e < 8; e++) dot += qf[e] * (double)(float)kv[e];
-            }
+            for (int e = 0; e < 8; e++) dot += qf[e] * (double)(float)kv[it][e];
 #pragma unroll
             for (int off = 1; off < LPK; off <<= 1) dot += __shfl_xor(dot, off);
             const double sc = (j < we) ? dot / rsd - slope * (double)(i - j) : -INFINITY;
             mb = fmax(mb, sc);
             if (sub == it) sc_mine = sc;                       // lane `sub` of a group exponentiates key `it`
         }
-        if (mb == -INFINITY) continue;                         // no key of this lane group in the block (uniform per group)
-        const double m_new = fmax(m_run, mb);
+        // values of the same keys: in flight while the exponentials are computed
+#pragma unroll
+        for (int it = 0; it < NIT; it++)
+            kv[it] = *(const v8h *)(Vc + (size_t)min(base + it * KPI + kslot, we - 1) * D + sub * 8);
+        const double m_new = fmax(m_run, mb);                  // mb = -inf: no key of this lane group in the block
+
         const double alpha = (m_run == -INFINITY) ? 0.0 : exp(m_run - m_new);
-        const double p_mine = exp(sc_mine - m_new);            // exp(-inf) = 0 for keys past the end
+        const double p_mine = (mb == -INFINITY) ? 0.0 : exp(sc_mine - m_new);   // exp(-inf) = 0 for keys past the end
         double psum = p_mine;
 #pragma unroll
         for (int off = 1; off < LPK; off <<= 1) psum += __shfl_xor(psum, off);
-        l_run = l_run * alpha + psum;
-        m_run = m_new;
+        if (mb != -INFINITY) {                                 // per lane group; no cross-lane traffic inside
+            l_run = l_run * alpha + psum;
+            m_run = m_new;
 #pragma unroll
-        for (int e = 0; e < 8; e++) o[e] *= alpha;
+            for (int e = 0; e < 8; e++) o[e] *= alpha;
+        }
 #pragma unroll
         for (int it = 0; it < NIT; it++) {
-            const int j = base + it * KPI + kslot;
-            const double p = __shfl(p_mine, kslot * LPK + it);
-            if (j < we) {
-                v8h vv = *(const v8h *)(Vc + (size_t)j * D + sub * 8);
+            const double p = __shfl(p_mine, kslot * LPK + it);  // 0 for keys past the end
 #pragma unroll
-                for (int e = 0; e < 8; e++) o[e] += p * (double)(float)vv[e];
-            }
+            for (int e = 0; e < 8; e++) o[e] += p * (double)(float)kv[it][e];
         }
     }
     // merge the lane groups of the wave (same dims, different keys)
