@@ -200,6 +200,7 @@ int run_linear(petals_span *sp, const LinearW &w, const __half *X, const __half 
         const OutlierSet os = {ws.ocount, ws.wd64, ws.x64};
         const bool pr = sp->prof.begin(PETALS_PROFILE_GEMM, st);
         HIP_TRY(ps_gemm(w, ws.xq, mask, X, ws.sx, M, os, o, ws.table, st));
+        if (M > 64) HIP_TRY(ps_gemm_lds(w, ws.xq, ws.sx, M, os, o, ws.table, st));
         sp->prof.end(pr, st);
     }
     return PETALS_OK;

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 #include <stdint.h>
+#include <stdlib.h>
 #include <string.h>
 
 typedef int v4i __attribute__((ext_vector_type(4)));
@@ -74,6 +75,10 @@ hipError_t ps_rowquant_tiled(const __half *X, int M, int K, const uint32_t *mask
                              int8_t *xq_rowmajor_dbg, hipStream_t st);
 hipError_t ps_mask_to_bytes(const uint32_t *mask, int K, uint8_t *out, hipStream_t st);
 
+// LDS-staged variant for M > 64; returns at once (on the device) if the call has more than
+// PS_EXACT_OUTLIERS outlier columns, and ps_gemm returns at once if it has at most that many
+hipError_t ps_gemm_lds(const LinearW &w, const int8_t *xq_tiled, const float *sx, int M, const OutlierSet &os,
+                       const OutDesc &o, const SessTable *sess, hipStream_t st);
 // optional copies of the one-row path's intermediates for tests (each may be null)
 struct RowDebug {
     __half *a_out;       // LayerNorm output [K]

@@ -94,6 +94,7 @@ k_gemm(LinearW w, const int8_t *__restrict__ xq_tiled, const uint32_t *__restric
        const SessTable *__restrict__ sess) {
     const int n_out = *os.count;
     const bool exact = n_out <= PS_EXACT_OUTLIERS;     // few outliers: fp64 pass after the main loop
+    if (exact && M > 64) return;                       // the LDS-staged kernel takes this call
     const int K = w.K, KT = K >> 6, N = w.N, NT = N >> 4, MTT = (M + 15) >> 4;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, row = lane & 15, kg = lane >> 4;
     const int wk = wave % WVK, wm = (wave / WVK) % WVM, wn = wave / (WVK * WVM);
