@@ -27,6 +27,41 @@ __device__ __forceinline__ void emit_output(const OutDesc &o, const SessTable *_
     }
 }
 
+// Same for 4 consecutive output features n0..n0+3 (n0 % 4 == 0) of one token: one 8-byte store.
+// In the fused-QKV layout 4 aligned consecutive rows always belong to the same head and the same
+// one of query / key / value, because head_dim is a multiple of 4.
+__device__ __forceinline__ void emit_output4(const OutDesc &o, const SessTable *__restrict__ sess, int N, int t,
+                                             int n0, const v4i &acc, const v4d &outl, float sxd,
+                                             const float *__restrict__ sw, const __half *__restrict__ bias) {
+    const float4 s4 = *(const float4 *)(sw + n0);
+    const v4h b4 = *(const v4h *)(bias + n0);
+    const float swv[4] = {s4.x, s4.y, s4.z, s4.w};
+    v4h r4 = {(_Float16)0, (_Float16)0, (_Float16)0, (_Float16)0};
+    if (o.epilogue == 2) r4 = *(const v4h *)(o.resid + (size_t)t * N + n0);
+    __half out[4];
+#pragma unroll
+    for (int r = 0; r < 4; r++) {
+        double v = (double)acc[r] * (double)sxd * (double)(swv[r] / 127.0f) + outl[r] + (double)(float)b4[r];
+        if (o.epilogue == 1) v = gelu_tanh(v);
+        else if (o.epilogue == 2) v += (double)(float)r4[r];
+        out[r] = d2h_rn(v);
+    }
+    if (o.acc_out) *(v4i *)(o.acc_out + (size_t)t * N + n0) = acc;
+    __half *dst;
+    if (!o.scatter) {
+        dst = o.y + (size_t)t * N + n0;
+    } else {
+        const int d = o.d, h = n0 / (3 * d), rem = n0 - h * 3 * d, p = rem / d, j = rem - p * d;
+        if (p == 0) {
+            dst = o.y + (size_t)t * (o.nh * d) + h * d + j;
+        } else {
+            const int s = t / o.T, cap = sess->cap[s], pos = sess->len[s] + (t - s * o.T);
+            dst = sess->kv[s] + (((size_t)o.blk * 2 + (p == 2 ? 1 : 0)) * o.nh * cap + (size_t)h * cap + pos) * d + j;
+        }
+    }
+    *(v2i *)dst = *(const v2i *)out;
+}
+
 // fp16 weight reconstructed from an int8 code: fp32 product rounded to fp16
 __device__ __forceinline__ float dequant_w16(int code, float swd) {
     return __half2float(__float2half_rn(keep_f32((float)code * swd)));

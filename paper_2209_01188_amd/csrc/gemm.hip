@@ -207,11 +207,7 @@ k_gemm(LinearW w, const int8_t *__restrict__ xq_tiled, const uint32_t *__restric
             const int t = (mt0 + j) * 16 + row;
             if (t >= M) continue;
             const float sxd = sx[t] / 127.0f;
-#pragma unroll
-            for (int r = 0; r < 4; r++) {
-                const int n = (nt0 + i) * 16 + 4 * kg + r;
-                emit_output(o, sess, N, t, n, acc[i][j][r], od[r], sxd, w.sw[n] / 127.0f, __half2float(w.bias[n]));
-            }
+            emit_output4(o, sess, N, t, (nt0 + i) * 16 + 4 * kg, acc[i][j], od, sxd, w.sw, w.bias);
         }
     }
 }

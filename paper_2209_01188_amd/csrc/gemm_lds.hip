@@ -2,7 +2,8 @@
 // Both operands already sit in HBM in 16x64 tiles whose 1024 bytes are in the lane order of
 // v_mfma_i32_16x16x64_i8, so a tile travels global -> LDS -> registers as plain 16-byte
 // per-lane copies (bank-conflict free, no transposition).  A workgroup computes a
-// (WVN*TN*16) x (WVM*TM*16) block of the output; k-tiles move through a 3-slot LDS ring.
+// (WVN*TN*16) x (WVM*TM*16) block of the output; k-tiles move through a 4-slot LDS ring filled by
+// asynchronous global->LDS copies.
 // Covers calls with at most PS_EXACT_OUTLIERS outlier columns (their exact fp64 product is
 // added in the epilogue); calls with more are left to the register-tiled kernel.
 #include "common.h"
@@ -57,58 +58,84 @@ k_gemm_lds(LinearW w, const int8_t *__restrict__ xq_tiled, const float *__restri
 #pragma unroll
         for (int j = 0; j < TM; j++) acc[i][j] = (v4i){0, 0, 0, 0};
 
-    // Software pipeline over k-tiles with a ring of 3 LDS slots: in iteration s the wave multiplies the
-    // fragments of stage s (already in registers), reads the fragments of stage s+1 from LDS into a second
-    // register set, and copies stage s+2 from global memory into the third slot.  One barrier per
-    // iteration; the matrix pipe never waits for an LDS or global load issued in the same iteration.
-    auto lds_store = [&](int slot, const v4i *st) {
+    // k-tiles travel global -> LDS with the asynchronous global_load_lds instruction (no staging
+    // registers): one instruction copies one 1 KB tile, lane l supplying the address of bytes
+    // [16 l, 16 l + 16) and the hardware writing them to tile base + 16 l.  A ring of NSLOT slots
+    // holds PD = NSLOT - 1 stages in flight ahead of the one being multiplied, which covers the
+    // latency of an L2 miss.  Per iteration: wait until this wave's copies of stage s have landed
+    // (they complete in order, so "at most LOADS * (stages issued after s)" outstanding), barrier
+    // (now every wave's part of stage s is visible, and every wave has finished reading stage
+    // s - 1), reuse the slot of stage s - 1 for stage s + PD, multiply stage s.
+#ifndef GEMM_NSLOT
+#define GEMM_NSLOT 4
+#endif
+    constexpr int NSLOT = GEMM_NSLOT, PD = NSLOT - 1;
+    static_assert(STAGE % NW == 0, "every wave copies the same number of tiles per stage");
+    auto dma_stage = [&](int s) {
+        unsigned char *slot = lds + (size_t)(s % NSLOT) * STAGE * 1024;
 #pragma unroll
         for (int j = 0; j < LOADS; j++)
-            if (wave + NW * j < STAGE) *(v4i *)(lds + ((size_t)slot * STAGE + wave + NW * j) * 1024 + lane * 16) = st[j];
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void *)(src[j] + (size_t)s * 1024),
+                (__attribute__((address_space(3))) void *)(slot + (size_t)(wave + NW * j) * 1024), 16, 0, 0);
     };
-    auto frag_load = [&](int slot, v4i *fa, v4i *fb) {
-        const unsigned char *base = lds + (size_t)slot * STAGE * 1024 + lane * 16;
-#pragma unroll
-        for (int i = 0; i < TN; i++) fa[i] = *(const v4i *)(base + (size_t)(wn * TN + i) * 1024);
+    for (int s = 0; s < PD && s < NS; s++) dma_stage(s);
+
+    auto wait_own = [&](int in_flight_after) {      // this wave's copies, all but the newest in_flight_after stages
+        if (in_flight_after >= 3) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS * 3) : "memory");
+        else if (in_flight_after == 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS * 2) : "memory");
+        else if (in_flight_after == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    };
+    auto frag_load = [&](int s, v4i *fa, v4i *fb) {
+        const unsigned char *base = lds + (size_t)(s % NSLOT) * STAGE * 1024 + lane * 16;
 #pragma unroll
         for (int j = 0; j < TM; j++) fb[j] = *(const v4i *)(base + (size_t)(BN + wm * TM + j) * 1024);
+#pragma unroll
+        for (int i = 0; i < TN; i++) fa[i] = *(const v4i *)(base + (size_t)(wn * TN + i) * 1024);
     };
-    v4i st[LOADS];
-#pragma unroll
-    for (int j = 0; j < LOADS; j++) st[j] = *(const v4i *)src[j];
-    lds_store(0, st);
-    if (NS > 1) {
-#pragma unroll
-        for (int j = 0; j < LOADS; j++) st[j] = *(const v4i *)(src[j] + 1024);
-        lds_store(1, st);
-    }
-    __syncthreads();
+    // Fragments are double buffered in registers: while stage s is multiplied, the fragments of stage
+    // s + 1 are read from LDS.  So at the barrier of iteration s, stage s + 1 must have landed.
     v4i fa0[TN], fb0[TM], fa1[TN], fb1[TM];
+    wait_own(min(NS - 1, PD - 1));                  // stage 0 of this wave
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
     frag_load(0, fa0, fb0);
-
     auto step = [&](int s, const v4i *ca, const v4i *cb, v4i *na, v4i *nb) {
-        const bool more2 = s + 2 < NS;
-        if (more2) {
-#pragma unroll
-            for (int j = 0; j < LOADS; j++) st[j] = *(const v4i *)(src[j] + (size_t)(s + 2) * 1024);
+        if (s + 1 < NS) {
+            wait_own(min(NS - s - 2, PD - 2));      // stage s + 1 of this wave (stages up to s + PD - 1 are issued)
+#ifndef GEMM_DBG_NOBARRIER
+            __builtin_amdgcn_s_barrier();           // everybody's stage s + 1 visible; everybody done reading stage s - 1
+#endif
+            asm volatile("" ::: "memory");
+#ifndef GEMM_DBG_NODMA
+            if (s + PD < NS) dma_stage(s + PD);      // into the slot of stage s - 1
+#endif
+            frag_load(s + 1, na, nb);
         }
-        if (s + 1 < NS) frag_load((s + 1) % 3, na, nb);
 #pragma unroll
         for (int i = 0; i < TN; i++)
 #pragma unroll
             for (int j = 0; j < TM; j++)
                 acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ca[i], cb[j], acc[i][j], 0, 0, 0);
-        if (more2) lds_store((s + 2) % 3, st);
-        __syncthreads();
     };
     for (int s = 0; s < NS; s += 2) {
         step(s, fa0, fb0, fa1, fb1);
         if (s + 1 < NS) step(s + 1, fa1, fb1, fa0, fb0);
     }
+    static_assert(PD <= 4, "wait_own distinguishes at most three stages in flight behind the awaited one");
+    // all copies have landed (vmcnt(0) in the last iteration); wait for every wave to finish reading
+    // the last stage before the slots are reused below
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
 
     // Epilogue.  D[lane][r] = output row 4*(l/16)+r of the weight tile, token l%16 of the token tile.
     // The accumulators go through LDS (each lane parks and re-reads only its own values, half of the
     // wave's tiles at a time) so that the tail below is ONE rolled loop instead of TN*TM inlined copies.
+#ifdef GEMM_DBG_NOEPI
+    if (n_out >= 0) { if (acc[0][0][0] == 0x7fffffff) o.y[0] = __float2half(1.0f); return; }
+#endif
     const int nch = (n_out + 3) >> 2;
     v4i *mine = (v4i *)lds + (size_t)wave * (TN / 2 * TM * 64) + lane;
 #pragma unroll
@@ -132,11 +159,7 @@ k_gemm_lds(LinearW w, const int8_t *__restrict__ xq_tiled, const float *__restri
             const int t = mt * 16 + row;
             if (t >= M) continue;
             const float sxd = sx[t] / 127.0f;
-#pragma unroll
-            for (int r = 0; r < 4; r++) {
-                const int n = nt * 16 + 4 * kg + r;
-                emit_output(o, sess, N, t, n, a4[r], od[r], sxd, w.sw[n] / 127.0f, __half2float(w.bias[n]));
-            }
+            emit_output4(o, sess, N, t, nt * 16 + 4 * kg, a4, od, sxd, w.sw, w.bias);
         }
     }
 }
@@ -148,7 +171,7 @@ hipError_t launch_lds(const LinearW &w, const int8_t *xq_tiled, const float *sx,
     const int NT = w.N / 16, MTT = (M + 15) / 16;
     const int nb_n = (NT + BN - 1) / BN, nb_m = (MTT + BM - 1) / BM;
     const int total = nb_n * nb_m;
-    const size_t lds_stage = (size_t)3 * (BN + BM) * KS * 1024, lds_epi = (size_t)WVN * WVM * (TN / 2) * TM * 1024;
+    const size_t lds_stage = (size_t)GEMM_NSLOT * (BN + BM) * KS * 1024, lds_epi = (size_t)WVN * WVM * (TN / 2) * TM * 1024;
     const size_t lds = lds_stage > lds_epi ? lds_stage : lds_epi;
     auto kern = k_gemm_lds<WVN, WVM, TN, TM, KS>;
     static bool attr_set = false;
