@@ -15,105 +15,100 @@ __global__ void k_set_table(SessTable t, SessTable *dst) {
     for (int i = threadIdx.x; i < (int)(sizeof(SessTable) / 4); i += blockDim.x) d[i] = s[i];
 }
 
-template <typename A, int NW>
-__device__ __forceinline__ A blk_max(A v, A *sm) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) { A w = __shfl_xor(v, o); v = v > w ? v : w; }
-    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = v;
-    __syncthreads();
-    A r = sm[0];
-#pragma unroll
-    for (int i = 1; i < NW; i++) r = r > sm[i] ? r : sm[i];
-    __syncthreads();
-    return r;
-}
-
-// A = float for prefill (many rows, ALU time matters), double for decode (T == 1): there the
-// kernel waits on HBM, and fp64 makes the fp16 context equal the exactly rounded one.
-template <int D, typename A>
-__global__ void __launch_bounds__(256) k_attn(const __half *__restrict__ q, const SessTable *__restrict__ sess,
-                                              int blk, int T, int nh, int CH, int nsplit,
-                                              double *__restrict__ partials, __half *__restrict__ ctx) {
-    constexpr int LPK = D / 8, KPI = 64 / LPK, NIT = 64 / KPI;
-    __shared__ A sc[256];
-    __shared__ A sm[4];
-    __shared__ A red[4][D];
-    const int c = blockIdx.x, h = blockIdx.y, t = blockIdx.z;
-    const int s = t / T, i = sess->len[s] + (t - s * T);      // absolute position of the query
-    const int k_begin = c * CH, k_end = min(i + 1, k_begin + CH);
-    if (k_begin >= k_end) return;                              // whole workgroup leaves together
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, sub = lane % LPK, kslot = lane / LPK;
-    const int cap = sess->cap[s], H = nh * D;
+// Prefill (T > 1 new tokens per session): exact attention on the fp64 matrix cores.
+// One wave owns 16 consecutive query rows of one (session, head) and walks the key tiles
+// (16 keys each) up to the causal limit with an online softmax.
+//   S^T = K Q^T   : v_mfma_f64_16x16x4_f64, A = keys (row = key), B = queries (column = query);
+//                   lane l feeds row/column l%16 and the dims [l/16 * D/4, +D/4) - any pairing of
+//                   the contraction index works as long as both operands use the same one, and
+//                   this one makes each lane read D/2 consecutive bytes of a key or query.
+//   the result registers hold S^T[key 4r + l/16][query l%16], which is exactly the B operand of
+//   O^T += V^T P^T (A = values with row i = output dims i*D/16 + blk), so the probabilities never
+//   change lanes.  Products of fp16 inputs are exact in fp64; the fp16 context equals the exactly
+//   rounded one (a different summation order moves the fp64 sum by ~1e-16 relative).
+template <int D>
+__global__ void __launch_bounds__(64) k_attn_prefill(const __half *__restrict__ q, const SessTable *__restrict__ sess,
+                                                     int blk, int T, int nh, __half *__restrict__ ctx) {
+    constexpr int DS = D / 4, NB = D / 16;           // dims per lane group; output blocks of 16 dims
+    const int qt = blockIdx.x, h = blockIdx.y, s = blockIdx.z;
+    const int lane = threadIdx.x, c = lane & 15, g = lane >> 4;
+    const int L = sess->len[s], cap = sess->cap[s], H = nh * D;
     const __half *Kc = sess->kv[s] + ((size_t)blk * 2 * nh + h) * cap * D;
     const __half *Vc = Kc + (size_t)nh * cap * D;
-    const A slope = (A)sess->slopes[h];
-    const A rsd = sqrt((A)D);
-    const A NEG_INF = -(A)INFINITY;
-    A qf[8];
-    {
-        v8h qv = *(const v8h *)(q + (size_t)t * H + h * D + sub * 8);
-#pragma unroll
-        for (int e = 0; e < 8; e++) qf[e] = (A)(float)qv[e];
-    }
-    A m_run = NEG_INF, l_run = 0, oacc[8];
-#pragma unroll
-    for (int e = 0; e < 8; e++) oacc[e] = 0;
+    const double slope = sess->slopes[h], rsd = sqrt((double)D);
+    const int last_key = L + T - 1;                   // newest key in the cache (already appended)
+    const int tq = qt * 16 + c;                       // this lane's query row inside the session
+    const int qpos = L + tq;                          // its absolute position
+    const size_t qrow = (size_t)s * T + min(tq, T - 1);
 
-    for (int base = k_begin; base < k_end; base += 256) {
-#pragma unroll 4
-        for (int it = 0; it < NIT; it++) {
-            const int jl = wave * 64 + it * KPI + kslot, j = base + jl;
-            A dot = 0;
-            if (j < k_end) {
-                v8h kv = *(const v8h *)(Kc + (size_t)j * D + sub * 8);
+    __half qh[DS];                                    // kept as fp16 (converted per use) to save registers
+    {
+        const __half *qp = q + qrow * H + h * D + g * DS;
 #pragma unroll
-                for (int e = 0; e < 8; e++) dot += qf[e] * (A)(float)kv[e];
-            }
+        for (int e = 0; e < DS; e++) qh[e] = qp[e];
+    }
+    v4d O[NB];
 #pragma unroll
-            for (int off = 1; off < LPK; off <<= 1) dot += __shfl_xor(dot, off);
-            if (sub == 0) sc[jl] = (j < k_end) ? dot / rsd - slope * (A)(i - j) : NEG_INF;
+    for (int b = 0; b < NB; b++) O[b] = (v4d){0.0, 0.0, 0.0, 0.0};
+    double m_run = -INFINITY, l_run = 0.0;
+
+    const int nkt = min(L + qt * 16 + 15, last_key) / 16 + 1;
+    for (int kt = 0; kt < nkt; kt++) {
+        // scores of 16 keys x 16 queries
+        v4d S = {0.0, 0.0, 0.0, 0.0};
+        {
+            const __half *kp = Kc + (size_t)min(kt * 16 + c, last_key) * D + g * DS;
+#pragma unroll
+            for (int e = 0; e < DS; e++)
+                S = __builtin_amdgcn_mfma_f64_16x16x4f64((double)__half2float(kp[e]), (double)__half2float(qh[e]), S, 0, 0, 0);
         }
-        __syncthreads();
-        const A sv = sc[threadIdx.x];
-        const A mc = blk_max<A, 4>(sv, sm);
-        const A m_new = m_run > mc ? m_run : mc;
-        const A pv = exp(sv - m_new);
-        sc[threadIdx.x] = pv;                                   // every thread overwrites only its own slot
-        const A lc = block_sum<4>(pv, sm);                      // barriers inside also publish sc
-        const A alpha = exp(m_run - m_new);
-        l_run = l_run * alpha + lc;
+        // values of the same keys, requested before the softmax arithmetic
+        __half vraw[4][NB];
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            const __half *vp = Vc + (size_t)min(kt * 16 + 4 * r + g, last_key) * D + c * NB;
+#pragma unroll
+            for (int b = 0; b < NB; b++) vraw[r][b] = vp[b];
+        }
+        double sc[4], mt = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            const int kpos = kt * 16 + 4 * r + g;
+            sc[r] = (kpos <= qpos && kpos <= last_key) ? S[r] / rsd - slope * (double)(qpos - kpos) : -INFINITY;
+            mt = fmax(mt, sc[r]);
+        }
+        mt = fmax(mt, __shfl_xor(mt, 16));
+        mt = fmax(mt, __shfl_xor(mt, 32));
+        const double m_new = fmax(m_run, mt);
+        const double alpha = (m_run == -INFINITY) ? 0.0 : exp(m_run - m_new);
+        double p[4], psum = 0.0;
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            p[r] = (sc[r] == -INFINITY) ? 0.0 : exp(sc[r] - m_new);
+            psum += p[r];
+        }
+        l_run = l_run * alpha + psum;                 // per lane group; the groups are added at the end
         m_run = m_new;
 #pragma unroll
-        for (int e = 0; e < 8; e++) oacc[e] *= alpha;
-#pragma unroll 4
-        for (int it = 0; it < NIT; it++) {
-            const int jl = wave * 64 + it * KPI + kslot, j = base + jl;
-            if (j < k_end) {
-                const A p = sc[jl];
-                v8h vv = *(const v8h *)(Vc + (size_t)j * D + sub * 8);
+        for (int b = 0; b < NB; b++) O[b] *= alpha;
 #pragma unroll
-                for (int e = 0; e < 8; e++) oacc[e] += p * (A)(float)vv[e];
-            }
-        }
-        __syncthreads();
+        for (int r = 0; r < 4; r++)
+#pragma unroll
+            for (int b = 0; b < NB; b++)
+                O[b] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)__half2float(vraw[r][b]), p[r], O[b], 0, 0, 0);
     }
+    l_run += __shfl_xor(l_run, 16);
+    l_run += __shfl_xor(l_run, 32);
+    if (tq < T) {
+        // O[b][r] = output dim (4r + g) * NB + b of query c: NB consecutive dims per (r, g)
+        __half *dst = ctx + qrow * H + h * D;
 #pragma unroll
-    for (int e = 0; e < 8; e++)
+        for (int r = 0; r < 4; r++) {
+            __half out[NB];
 #pragma unroll
-        for (int off = LPK; off < 64; off <<= 1) oacc[e] += __shfl_xor(oacc[e], off);
-    if (kslot == 0) {
+            for (int b = 0; b < NB; b++) out[b] = d2h_rn(O[b][r] / l_run);
 #pragma unroll
-        for (int e = 0; e < 8; e++) red[wave][sub * 8 + e] = oacc[e];
-    }
-    __syncthreads();
-    if (threadIdx.x < D) {
-        const A o = red[0][threadIdx.x] + red[1][threadIdx.x] + red[2][threadIdx.x] + red[3][threadIdx.x];
-        if (nsplit == 1) {
-            ctx[(size_t)t * H + h * D + threadIdx.x] = d2h_rn((double)o / (double)l_run);
-        } else {
-            double *pp = partials + ((size_t)(t * nh + h) * nsplit + c) * (D + 2);
-            if (threadIdx.x == 0) { pp[0] = (double)m_run; pp[1] = (double)l_run; }
-            pp[2 + threadIdx.x] = (double)o;
+            for (int b = 0; b < NB; b++) dst[(4 * r + g) * NB + b] = out[b];
         }
     }
 }
@@ -266,12 +261,11 @@ hipError_t attn_launch(const __half *q, const SessTable *sess, int blk, int M, i
     if ((size_t)M * nh * nsplit > PS_ATTN_PARTIAL_SLOTS) nsplit = 1;
     int CH = ((max_keys + nsplit - 1) / nsplit + 255) / 256 * 256;
     if (nsplit == 1) CH = 1 << 30;
-    if (T == 1)
-        k_attn_decode<D><<<dim3(nsplit, nh, M), 256, 0, st>>>(q, sess, blk, nh, CH, nsplit, partials, ctx);
-    else if (!getenv("PS_ATTN_F32"))
-        k_attn<D, double><<<dim3(nsplit, nh, M), 256, 0, st>>>(q, sess, blk, T, nh, CH, nsplit, partials, ctx);
-    else
-        k_attn<D, float><<<dim3(nsplit, nh, M), 256, 0, st>>>(q, sess, blk, T, nh, CH, nsplit, partials, ctx);
+    if (T > 1) {
+        k_attn_prefill<D><<<dim3((T + 15) / 16, nh, M / T), 64, 0, st>>>(q, sess, blk, T, nh, ctx);
+        return hipGetLastError();
+    }
+    k_attn_decode<D><<<dim3(nsplit, nh, M), 256, 0, st>>>(q, sess, blk, nh, CH, nsplit, partials, ctx);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || nsplit == 1) return e;
     k_attn_combine<D><<<dim3(nh, M), D, 0, st>>>(sess, T, nh, CH, nsplit, partials, ctx);
