@@ -280,3 +280,93 @@ def test_capacity_and_state_errors_leave_sessions_untouched():
     with pytest.raises(binding.PetalsError):
         sp.prefill([se, se], x[:, :1].repeat(2, 1, 1))
     sp.close()
+
+
+# ------------------------------------------------- full-size configurations
+
+def test_c2_full_configuration_prefill_128_then_128_decode_steps():
+    """BLOOM-560M-shaped span exactly as configured: 24 blocks, prompt 128, 128 decode steps."""
+    cfg = C2
+    osp, gsp, oses, gses, outs = _run_generation(cfg, cfg.n_blocks, 1, cfg.prompt, cfg.decode)
+    exact = []
+    for i, (g, o) in enumerate(outs):
+        hidden_close(g, o, "C2 full call %d" % i)
+        exact.append((g.view(np.uint16) == o.view(np.uint16)).mean())
+    assert gses[0].length == cfg.prompt + cfg.decode
+    # the fp64 epilogues make the GPU agree with the oracle far inside the tolerance
+    assert min(exact) > 0.999
+    gsp.close(); osp.destroy()
+
+
+def _c4_block_pair(theta=6.0, rows=1):
+    """One full-size BLOOM-176B-shaped block with weights drawn on the GPU, loaded into both sides."""
+    cfg = synth.CONFIGS["C4"]
+    p = synth.block_params_device(cfg, 0, DEV)
+    gsp = binding.Span(1, cfg.hidden, cfg.n_heads, cfg.F, rows, 1e-5, theta, DEV)
+    gsp.load_block(0, p)
+    host = {k: v.cpu().numpy() for k, v in p.items()}
+    del p
+    osp = oracle.Span(1, cfg.hidden, cfg.n_heads, cfg.F, 1e-5, theta)
+    osp.load_block(0, host)
+    return cfg, osp, gsp, host
+
+
+def test_c4_full_size_block_decode_at_the_benchmark_prefixes():
+    """The benchmark's launch configuration (batch 1, H = 14336, F = 57344) on one block, every output checked."""
+    cfg, osp, gsp, host = _c4_block_pair()
+    for L in (128, 2048):
+        kv = synth.kv_prefix_device(cfg, 0, 0, L, 2.4, DEV)
+        ose, gse = osp.open_session(L + 3), gsp.open_session(L + 3)
+        ose.import_kv(0, kv.cpu().numpy()); gse.import_kv(0, kv)
+        for i in (1, 2):
+            x = synth.hidden_states(cfg, i, 1, 1)
+            yo = osp.step([ose], x)
+            yg = to_np(gsp.decode_step([gse], to_dev(x[:, 0])))[:, None]
+            hidden_close(yg, yo, "C4 block L=%d step %d" % (L, i))
+        hidden_close(to_np(gse.export_kv(0))[:, :, L:], ose.export_kv(0)[:, :, L:], "C4 appended kv")
+        gse.close(); ose.close()
+    # teacher-forced integer parts of every linear at full size, one row
+    r = np.random.default_rng(0)
+    for which, name, bname in ((0, "w_qkv", "b_qkv"), (1, "w_dense", "b_dense"), (2, "w_up", "b_up"), (3, "w_down", "b_down")):
+        N, K = gsp.shapes(which)
+        X = r.standard_normal((1, K)) * 2.4
+        X[0, r.choice(K, 6, replace=False)] = r.uniform(20, 60, 6)
+        X = X.astype(np.float16)
+        wq, sw = osp.get_weight(0, which)
+        Y, dbg = oracle.linear(X, wq, sw, host[bname], 6.0, want_debug=True)
+        out = gsp.debug_linear(0, which, to_dev(X))
+        assert np.array_equal(to_np(out["mask"]), dbg["mask"]) and dbg["mask"].sum() >= 6
+        assert np.array_equal(to_np(out["xq"]), dbg["xq"]) and np.array_equal(to_np(out["sx"]), dbg["sx"])
+        assert np.array_equal(to_np(out["acc"]), dbg["acc"])
+        hidden_close(to_np(out["y"]), Y, "C4 linear %d" % which)
+    gsp.close(); osp.destroy()
+
+
+def test_c4_full_size_linears_with_several_rows_sampled_against_the_oracle():
+    """Batched decode (8 rows) and a prefill-size call (200 rows) on the full-size up linear: the oracle computes
+    a sample of output features one by one (the full product is too slow for a test)."""
+    cfg = synth.CONFIGS["C4"]
+    p = synth.block_params_device(cfg, 0, DEV)
+    gsp = binding.Span(1, cfg.hidden, cfg.n_heads, cfg.F, 200, 1e-5, 6.0, DEV)
+    gsp.load_block(0, p)
+    r = np.random.default_rng(5)
+    for which, wname, bname in ((2, "w_up", "b_up"), (1, "w_dense", "b_dense")):
+        N, K = gsp.shapes(which)
+        rows = np.sort(r.choice(N, 96, replace=False))
+        rows[:16] = np.arange(16)                      # one whole tile plus scattered rows, incl. the last
+        rows[-1] = N - 1
+        rows = np.unique(rows)
+        Wsub = p[wname][torch.as_tensor(rows, device=DEV)].cpu().numpy()
+        bsub = p[bname].cpu().numpy()[rows]
+        wq, sw = oracle.quantize_weight(Wsub)
+        for M in (8, 200):
+            X = r.standard_normal((M, K))
+            X[:, r.choice(K, 6, replace=False)] = r.uniform(20, 60, (M, 6))
+            X = X.astype(np.float16)
+            Y, dbg = oracle.linear(X, wq, sw, bsub, 6.0, want_debug=True)
+            out = gsp.debug_linear(0, which, to_dev(X))
+            assert np.array_equal(to_np(out["mask"]), dbg["mask"])
+            assert np.array_equal(to_np(out["xq"]), dbg["xq"]) and np.array_equal(to_np(out["sx"]), dbg["sx"])
+            assert np.array_equal(to_np(out["acc"])[:, rows], dbg["acc"])
+            hidden_close(to_np(out["y"])[:, rows], Y, "C4 linear %d M=%d" % (which, M))
+    gsp.close()
