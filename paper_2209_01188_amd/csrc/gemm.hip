@@ -127,12 +127,9 @@ k_gemm(LinearW w, const int8_t *__restrict__ xq_tiled, const uint32_t *__restric
     }
     const uint64_t *mask64 = (const uint64_t *)mask;
 
-    for (int kt = wk; kt < KT; kt += WVK) {
-        v4i wv[WN], xv[MT];
-#pragma unroll
-        for (int i = 0; i < WN; i++) wv[i] = *(const v4i *)(wbase[i] + (size_t)kt * 1024);
-#pragma unroll
-        for (int j = 0; j < MT; j++) xv[j] = *(const v4i *)(xbase[j] + (size_t)kt * 1024);
+    // One k-tile: int8 product, and on tiles that hold outlier columns (when they are too many for the
+    // exact pass) the fp16 product of the masked activations with weights dequantized in registers.
+    auto tile = [&](int kt, const v4i *wv, const v4i *xv) {
 #pragma unroll
         for (int i = 0; i < WN; i++)
 #pragma unroll
@@ -159,6 +156,30 @@ k_gemm(LinearW w, const int8_t *__restrict__ xq_tiled, const uint32_t *__restric
                 }
             }
         }
+    };
+    // Wave wk takes chunks of UK consecutive k-tiles (chunk c = wk, wk + WVK, ...) and requests all
+    // operand tiles of a chunk before using any, so several KB per wave are in flight.
+    constexpr int UK = (WN * MT <= 2) ? 4 : (WN * MT <= 4 ? 2 : 1);
+    const int nchunks = KT / UK;
+    for (int c = wk; c < nchunks; c += WVK) {
+        v4i wv[UK][WN], xv[UK][MT];
+#pragma unroll
+        for (int u = 0; u < UK; u++) {
+#pragma unroll
+            for (int i = 0; i < WN; i++) wv[u][i] = __builtin_nontemporal_load((const v4i *)(wbase[i] + (size_t)(c * UK + u) * 1024));
+#pragma unroll
+            for (int j = 0; j < MT; j++) xv[u][j] = *(const v4i *)(xbase[j] + (size_t)(c * UK + u) * 1024);
+        }
+#pragma unroll
+        for (int u = 0; u < UK; u++) tile(c * UK + u, wv[u], xv[u]);
+    }
+    for (int kt = nchunks * UK + wk; kt < KT; kt += WVK) {
+        v4i wv[WN], xv[MT];
+#pragma unroll
+        for (int i = 0; i < WN; i++) wv[i] = *(const v4i *)(wbase[i] + (size_t)kt * 1024);
+#pragma unroll
+        for (int j = 0; j < MT; j++) xv[j] = *(const v4i *)(xbase[j] + (size_t)kt * 1024);
+        tile(kt, wv, xv);
     }
 
     if (WVK > 1) {

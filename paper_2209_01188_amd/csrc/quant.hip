@@ -90,15 +90,16 @@ __device__ __forceinline__ __half2 ln_affine(__half2 x, __half2 g, __half2 b, do
     return o;
 }
 
-__global__ void __launch_bounds__(256) k_layernorm(const __half *__restrict__ x, const __half *__restrict__ g,
-                                                   const __half *__restrict__ b, float eps, int H,
-                                                   __half *__restrict__ y) {
-    __shared__ double sm[4];
+template <int NT>
+__global__ void __launch_bounds__(NT) k_layernorm(const __half *__restrict__ x, const __half *__restrict__ g,
+                                                  const __half *__restrict__ b, float eps, int H,
+                                                  __half *__restrict__ y) {
+    __shared__ double sm[NT / 64];
     const __half *xr = x + (size_t)blockIdx.x * H;
     __half *yr = y + (size_t)blockIdx.x * H;
     double mean, inv;
-    row_moments<256>(xr, H, sm, mean, inv, (double)eps);
-    for (int k = threadIdx.x * 2; k < H; k += 512)
+    row_moments<NT>(xr, H, sm, mean, inv, (double)eps);
+    for (int k = threadIdx.x * 2; k < H; k += NT * 2)
         *(__half2 *)(yr + k) = ln_affine(*(const __half2 *)(xr + k), *(const __half2 *)(g + k),
                                          *(const __half2 *)(b + k), mean, inv);
 }
@@ -251,7 +252,9 @@ hipError_t ps_copy_bytes(const void *src, void *dst, size_t n, hipStream_t st) {
 }
 hipError_t ps_layernorm(const __half *x, const __half *g, const __half *b, float eps, int M, int H, __half *y,
                         hipStream_t st) {
-    k_layernorm<<<M, 256, 0, st>>>(x, g, b, eps, H, y);
+    // few rows: more threads per row (latency), many rows: more rows in flight
+    if (M <= 256 && H >= 4096) k_layernorm<1024><<<M, 1024, 0, st>>>(x, g, b, eps, H, y);
+    else k_layernorm<256><<<M, 256, 0, st>>>(x, g, b, eps, H, y);
     return hipGetLastError();
 }
 hipError_t ps_colmask(const __half *X, int M, int K, float theta, uint32_t *mask, hipStream_t st) {
