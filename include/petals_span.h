@@ -170,7 +170,8 @@ const char *petals_last_error(void);
 #define PETALS_PROFILE_GEMV      0  /* one-row int8 linear (decode, batch 1) */
 #define PETALS_PROFILE_GEMM      1  /* multi-row MFMA linear */
 #define PETALS_PROFILE_ATTENTION 2  /* attention incl. the merge of key ranges */
-#define PETALS_PROFILE_CLASSES   3
+#define PETALS_PROFILE_LINEAR0   3  /* 3..6: the same linear launches again, by linear (qkv, dense, up, down) */
+#define PETALS_PROFILE_CLASSES   7
 int petals_span_profile_begin(petals_span *span, int32_t max_launches);
 int petals_span_profile_end(petals_span *span, double *ms_per_class, int64_t *launches_per_class);
 

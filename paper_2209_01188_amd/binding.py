@@ -57,7 +57,7 @@ EXPORTS = ["petals_span_weight_bytes", "petals_span_workspace_bytes", "petals_sp
            "petals_hidden_dequantize", "petals_hidden_code_table", "petals_last_error", "petals_debug_linear",
            "petals_debug_export_weight", "petals_debug_export_kv", "petals_debug_import_kv",
            "petals_span_profile_begin", "petals_span_profile_end", "petals_debug_layernorm"]
-PROFILE_GEMV, PROFILE_GEMM, PROFILE_ATTENTION, PROFILE_CLASSES = 0, 1, 2, 3
+PROFILE_GEMV, PROFILE_GEMM, PROFILE_ATTENTION, PROFILE_LINEAR0, PROFILE_CLASSES = 0, 1, 2, 3, 7
 
 
 def _check(rc):

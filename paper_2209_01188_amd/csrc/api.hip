@@ -142,11 +142,12 @@ const CodeTable &code_table() {
 struct Profiler {
     bool on = false;
     std::vector<hipEvent_t> ev;        // pairs (start, stop)
-    std::vector<int> cls;              // kernel class of pair i
+    std::vector<int> cls, kind;        // kernel class of pair i; which linear it was (-1: none)
     size_t used = 0;
-    bool begin(int kernel_class, hipStream_t st) {
+    bool begin(int kernel_class, int which, hipStream_t st) {
         if (!on || (used + 1) * 2 > ev.size()) return false;
         cls[used] = kernel_class;
+        kind[used] = which;
         return hipEventRecord(ev[used * 2], st) == hipSuccess;
     }
     void end(bool started, hipStream_t st) {
@@ -177,7 +178,7 @@ namespace {
 // One linear on M rows resident as fp16 X[M,K]; picks the one-row or the MFMA path.  ln_g/ln_b non-null:
 // X is the input of the LayerNorm that precedes the linear (fused on the one-row path, a kernel of its own
 // writing ws.a otherwise).  debug: copy the integer intermediates out (one-row path: into ws.xq/mask/ws.sx).
-int run_linear(petals_span *sp, const LinearW &w, const __half *X, const __half *ln_g, const __half *ln_b, int M,
+int run_linear(petals_span *sp, int which, const LinearW &w, const __half *X, const __half *ln_g, const __half *ln_b, int M,
                uint32_t *mask, const OutDesc &o, int8_t *xq_dbg, bool debug, hipStream_t st) {
     Workspace &ws = sp->ws;
     const petals_span_config &c = sp->cfg;
@@ -185,7 +186,7 @@ int run_linear(petals_span *sp, const LinearW &w, const __half *X, const __half 
     if (M == 1) {
         RowDebug dbg = {nullptr, nullptr, nullptr, nullptr};
         if (debug) dbg = RowDebug{ln_g ? ws.a : nullptr, xq_dbg, mask, ws.sx};
-        const bool pr = sp->prof.begin(PETALS_PROFILE_GEMV, st);
+        const bool pr = sp->prof.begin(PETALS_PROFILE_GEMV, which, st);
         HIP_TRY(ps_gemv_row(w, X, ln_g, ln_b, c.ln_eps, theta, dbg, o, ws.table, st));
         sp->prof.end(pr, st);
     } else {
@@ -198,7 +199,7 @@ int run_linear(petals_span *sp, const LinearW &w, const __half *X, const __half 
         HIP_TRY(ps_rowquant_tiled(X, M, w.K, mask, ws.xq, ws.sx, xq_dbg, st));
         HIP_TRY(ps_outlier_prep(w, mask, X, M, ws.ocount, ws.wd64, ws.x64, st));
         const OutlierSet os = {ws.ocount, ws.wd64, ws.x64};
-        const bool pr = sp->prof.begin(PETALS_PROFILE_GEMM, st);
+        const bool pr = sp->prof.begin(PETALS_PROFILE_GEMM, which, st);
         HIP_TRY(ps_gemm(w, ws.xq, mask, X, ws.sx, M, os, o, ws.table, st));
         if (M > 64) HIP_TRY(ps_gemm_lds(w, ws.xq, ws.sx, M, os, o, ws.table, st));
         sp->prof.end(pr, st);
@@ -315,6 +316,7 @@ int petals_span_profile_begin(petals_span *sp, int32_t max_launches) {
         P.ev.push_back(e);
     }
     P.cls.assign(P.ev.size() / 2, 0);
+    P.kind.assign(P.ev.size() / 2, -1);
     P.used = 0;
     P.on = true;
     return PETALS_OK;
@@ -331,6 +333,10 @@ int petals_span_profile_end(petals_span *sp, double *ms_per_class, int64_t *laun
         HIP_TRY(hipEventElapsedTime(&ms, P.ev[i * 2], P.ev[i * 2 + 1]));
         ms_per_class[P.cls[i]] += ms;
         launches_per_class[P.cls[i]]++;
+        if (P.kind[i] >= 0) {
+            ms_per_class[PETALS_PROFILE_LINEAR0 + P.kind[i]] += ms;
+            launches_per_class[PETALS_PROFILE_LINEAR0 + P.kind[i]]++;
+        }
     }
     P.used = 0;
     return PETALS_OK;
@@ -411,19 +417,19 @@ int petals_span_prefill(petals_span *sp, petals_session *const *sessions, int32_
         OutDesc oq = plain_out(ws.q, PETALS_EPILOGUE_NONE, nullptr);
         oq.scatter = 1; oq.T = T; oq.nh = nh; oq.d = d; oq.blk = b;
         // LayerNorm 1 -> fused QKV (queries to ws.q, keys/values appended to the caches)
-        if (int rc = run_linear(sp, W.lin[0], x, W.ln1g, W.ln1b, M, mk, oq, nullptr, false, st)) return rc;
+        if (int rc = run_linear(sp, 0, W.lin[0], x, W.ln1g, W.ln1b, M, mk, oq, nullptr, false, st)) return rc;
         {
-            const bool pr = sp->prof.begin(PETALS_PROFILE_ATTENTION, st);
+            const bool pr = sp->prof.begin(PETALS_PROFILE_ATTENTION, -1, st);
             HIP_TRY(ps_attention(ws.q, ws.table, b, M, T, nh, d, max_keys, ws.partials, ws.ctx, st));
             sp->prof.end(pr, st);
         }
         // dense + residual
-        if (int rc = run_linear(sp, W.lin[1], ws.ctx, nullptr, nullptr, M, mk + ws.mask_words,
+        if (int rc = run_linear(sp, 1, W.lin[1], ws.ctx, nullptr, nullptr, M, mk + ws.mask_words,
                                 plain_out(ws.x1, PETALS_EPILOGUE_RESIDUAL, x), nullptr, false, st)) return rc;
         // LayerNorm 2 -> up + GeLU -> down + residual
-        if (int rc = run_linear(sp, W.lin[2], ws.x1, W.ln2g, W.ln2b, M, mk + 2 * ws.mask_words,
+        if (int rc = run_linear(sp, 2, W.lin[2], ws.x1, W.ln2g, W.ln2b, M, mk + 2 * ws.mask_words,
                                 plain_out(ws.g, PETALS_EPILOGUE_GELU, nullptr), nullptr, false, st)) return rc;
-        if (int rc = run_linear(sp, W.lin[3], ws.g, nullptr, nullptr, M, mk + 3 * ws.mask_words,
+        if (int rc = run_linear(sp, 3, W.lin[3], ws.g, nullptr, nullptr, M, mk + 3 * ws.mask_words,
                                 plain_out(xout, PETALS_EPILOGUE_RESIDUAL, ws.x1), nullptr, false, st)) return rc;
         x = xout;
     }
@@ -473,7 +479,7 @@ int petals_debug_linear(petals_span *sp, int32_t block, int32_t which, const voi
     OutDesc o = plain_out(yy, epilogue, (const __half *)resid);
     o.acc_out = acc;
     uint32_t *mk = ws.masks;
-    if (int rc = run_linear(sp, L, (const __half *)x, nullptr, nullptr, M, mk, o, xq, true, st)) return rc;
+    if (int rc = run_linear(sp, which, L, (const __half *)x, nullptr, nullptr, M, mk, o, xq, true, st)) return rc;
     if (sx) HIP_TRY(ps_copy_bytes(ws.sx, sx, (size_t)M * 4, st));
     if (outlier_mask) HIP_TRY(ps_mask_to_bytes(mk, L.K, outlier_mask, st));
     return PETALS_OK;
