@@ -65,6 +65,7 @@ struct Workspace {
     double *partials;
     int *ocount;
     double *wd64, *x64;
+    ManyOutliers many;     // only carved when max_rows_per_call > 64
     size_t mask_words;
     size_t total;
 };
@@ -92,6 +93,14 @@ Workspace carve(const petals_span_config &c, uint8_t *base) {
     const size_t Nmax = 3 * H > F ? 3 * H : F;
     w.wd64 = (double *)take(Nmax / 16 * PS_OUTLIER_CHUNKS * 64 * 8);
     w.x64 = (double *)take(Mp / 16 * PS_OUTLIER_CHUNKS * 64 * 8);
+    w.many = ManyOutliers{nullptr, nullptr, nullptr, nullptr};
+    if (M > 64) {   // prefill-size calls: room for the case that most columns are outliers
+        const size_t NKmax = (size_t)(3 * H > F ? 3 * H : F) * H > H * F ? (size_t)(3 * H > F ? 3 * H : F) * H : H * F;
+        w.many.list = (int *)take((Kmax + 32) * 4);
+        w.many.xo = (__half *)take(Mp * (Kmax + 32) * 2);
+        w.many.wo = (__half *)take((NKmax + 32 * Nmax) * 2);
+        w.many.outl = (float *)take(Mp * Nmax * 4);
+    }
     w.total = off;
     return w;
 }
@@ -200,8 +209,8 @@ int run_linear(petals_span *sp, int which, const LinearW &w, const __half *X, co
         HIP_TRY(ps_outlier_prep(w, mask, X, M, ws.ocount, ws.wd64, ws.x64, st));
         const OutlierSet os = {ws.ocount, ws.wd64, ws.x64};
         const bool pr = sp->prof.begin(PETALS_PROFILE_GEMM, which, st);
-        HIP_TRY(ps_gemm(w, ws.xq, mask, X, ws.sx, M, os, o, ws.table, st));
-        if (M > 64) HIP_TRY(ps_gemm_lds(w, ws.xq, ws.sx, M, os, o, ws.table, st));
+        if (M <= 64) HIP_TRY(ps_gemm(w, ws.xq, mask, X, ws.sx, M, os, o, ws.table, st));
+        else HIP_TRY(ps_gemm_lds(w, ws.xq, mask, X, ws.sx, M, os, ws.many, o, ws.table, st));
         sp->prof.end(pr, st);
     }
     return PETALS_OK;

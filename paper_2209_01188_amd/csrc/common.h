@@ -6,6 +6,8 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <type_traits>
+
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v2i __attribute__((ext_vector_type(2)));
 typedef float v4f __attribute__((ext_vector_type(4)));
@@ -75,10 +77,17 @@ hipError_t ps_rowquant_tiled(const __half *X, int M, int K, const uint32_t *mask
                              int8_t *xq_rowmajor_dbg, hipStream_t st);
 hipError_t ps_mask_to_bytes(const uint32_t *mask, int K, uint8_t *out, hipStream_t st);
 
-// LDS-staged variant for M > 64; returns at once (on the device) if the call has more than
-// PS_EXACT_OUTLIERS outlier columns, and ps_gemm returns at once if it has at most that many
-hipError_t ps_gemm_lds(const LinearW &w, const int8_t *xq_tiled, const float *sx, int M, const OutlierSet &os,
-                       const OutDesc &o, const SessTable *sess, hipStream_t st);
+// Scratch of the outlier-heavy case of a prefill-size call (more than PS_EXACT_OUTLIERS columns)
+struct ManyOutliers {
+    int *list;      // [K] outlier column indices, ascending, padded with -1 to a multiple of 32
+    __half *xo;     // gathered fp16 activations, tiles [ceil(M/16)][ceil(n_out/32)][512 halves]
+    __half *wo;     // gathered dequantized fp16 weights, tiles [N/16][ceil(n_out/32)][512 halves]
+    float *outl;    // [M, N] fp32 outlier product
+};
+// LDS-staged linear for M > 64 rows (any number of outlier columns)
+hipError_t ps_gemm_lds(const LinearW &w, const int8_t *xq_tiled, const uint32_t *mask, const __half *X, const float *sx,
+                       int M, const OutlierSet &os, const ManyOutliers &mo, const OutDesc &o, const SessTable *sess,
+                       hipStream_t st);
 // optional copies of the one-row path's intermediates for tests (each may be null)
 struct RowDebug {
     __half *a_out;       // LayerNorm output [K]

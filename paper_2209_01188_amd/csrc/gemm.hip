@@ -94,7 +94,6 @@ k_gemm(LinearW w, const int8_t *__restrict__ xq_tiled, const uint32_t *__restric
        const SessTable *__restrict__ sess) {
     const int n_out = *os.count;
     const bool exact = n_out <= PS_EXACT_OUTLIERS;     // few outliers: fp64 pass after the main loop
-    if (exact && M > 64) return;                       // the LDS-staged kernel takes this call
     const int K = w.K, KT = K >> 6, N = w.N, NT = N >> 4, MTT = (M + 15) >> 4;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, row = lane & 15, kg = lane >> 4;
     const int wk = wave % WVK, wm = (wave / WVK) % WVM, wn = wave / (WVK * WVM);
@@ -256,5 +255,5 @@ hipError_t ps_gemm(const LinearW &w, const int8_t *xq_tiled, const uint32_t *mas
     if (M <= 16) return launch<1, 1, 1, 1, 8>(w, xq_tiled, mask, X, sx, M, os, o, sess, st);
     if (M <= 32) return launch<1, 2, 1, 1, 8>(w, xq_tiled, mask, X, sx, M, os, o, sess, st);
     if (M <= 64) return launch<1, 4, 1, 1, 8>(w, xq_tiled, mask, X, sx, M, os, o, sess, st);
-    return launch<4, 4, 2, 2, 1>(w, xq_tiled, mask, X, sx, M, os, o, sess, st);
+    return hipErrorInvalidValue;   // larger calls belong to ps_gemm_lds
 }

@@ -1,31 +1,134 @@
-// Prefill-size linear (M > 64 rows) on int8 MFMA with LDS-staged operand tiles.
-// Both operands already sit in HBM in 16x64 tiles whose 1024 bytes are in the lane order of
-// v_mfma_i32_16x16x64_i8, so a tile travels global -> LDS -> registers as plain 16-byte
-// per-lane copies (bank-conflict free, no transposition).  A workgroup computes a
-// (WVN*TN*16) x (WVM*TM*16) block of the output; k-tiles move through a 4-slot LDS ring filled by
-// asynchronous global->LDS copies.
-// Covers calls with at most PS_EXACT_OUTLIERS outlier columns (their exact fp64 product is
-// added in the epilogue); calls with more are left to the register-tiled kernel.
+// Prefill-size linear (M > 64 rows) on the matrix cores with LDS-staged operand tiles.
+//
+// Regular columns: int8 x int8 -> int32 with v_mfma_i32_16x16x64_i8.  Both operands already sit
+// in HBM in 16x64 tiles whose 1024 bytes are in the lane order of that instruction, so a tile
+// travels global -> LDS -> registers as plain 16-byte per-lane copies (bank-conflict free, no
+// transposition).  A workgroup computes a 256 x 256 block of the output; k-tiles move through a
+// 4-slot LDS ring filled by asynchronous global->LDS copies.
+//
+// Outlier columns: up to PS_EXACT_OUTLIERS of them are added exactly in the epilogue (fp64 matrix
+// instruction on compacted operands, see k_outlier_prep).  More than that: the outlier columns of
+// the activations and of the dequantized weights are gathered into dense fp16 tile arrays and
+// multiplied by the same pipeline with v_mfma_f32_16x16x32_f16 into an fp32 [M,N] buffer that the
+// int8 kernel's epilogue adds.
 #include "common.h"
 #include "epilogue.h"
 
 namespace {
 
-constexpr int STRIP = 4;   // m-blocks per rasterization strip
+constexpr int STRIP = 4;       // m-blocks per rasterization strip
+constexpr int NSLOT = 4;       // LDS ring slots
+constexpr int PD = NSLOT - 1;  // stages requested ahead
 
-template <int WVN, int WVM, int TN, int TM, int KS>
+// ---------------------------------------------------------------------------------------------
+// outlier column list and fp16 gathers (only do work when the call has > PS_EXACT_OUTLIERS)
+
+// One workgroup: ascending list of the set bits of mask[0 .. K/32); entries up to the next multiple
+// of 32 are -1.  count must already hold the number of set bits.
+__global__ void __launch_bounds__(1024) k_outlier_list(const uint32_t *__restrict__ mask, int K,
+                                                       const int *__restrict__ count, int *__restrict__ list) {
+    __shared__ int wave_tot[16];
+    const int n_out = *count;
+    if (n_out <= PS_EXACT_OUTLIERS) return;
+    const int nwords = K >> 5, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wpt = (nwords + 1023) / 1024, w0 = min(nwords, (int)threadIdx.x * wpt), w1 = min(nwords, w0 + wpt);
+    int cnt = 0;
+    for (int i = w0; i < w1; i++) cnt += __popc(mask[i]);
+    int incl = cnt;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int v = __shfl_up(incl, off);
+        if (lane >= off) incl += v;
+    }
+    if (lane == 63) wave_tot[wave] = incl;
+    __syncthreads();
+    int pos = incl - cnt;
+    for (int i = 0; i < wave; i++) pos += wave_tot[i];
+    for (int i = w0; i < w1; i++) {
+        uint32_t b = mask[i];
+        while (b) {
+            const int j = __ffs(b) - 1;
+            b &= b - 1;
+            list[pos++] = i * 32 + j;
+        }
+    }
+    const int padded = (n_out + 31) & ~31;
+    for (int i = n_out + threadIdx.x; i < padded; i += 1024) list[i] = -1;
+}
+
+// fp16 tiles for v_mfma_f32_16x16x32_f16: 16 rows x 32 (compacted) columns = 1024 bytes, lane l owns
+// row l%16 and columns (l/16)*8 .. +8.  Tile (r, c) at ((r * CT) + c) * 1024 with CT = ceil(n_out/32).
+// One wave per tile; the grid is fixed and strides over the tiles the call actually has.
+__global__ void __launch_bounds__(64) k_gather_x(const __half *__restrict__ X, int M, int K,
+                                                 const int *__restrict__ count, const int *__restrict__ list,
+                                                 __half *__restrict__ xo) {
+    const int n_out = *count;
+    if (n_out <= PS_EXACT_OUTLIERS) return;
+    const int CT = (n_out + 31) >> 5, MTT = (M + 15) >> 4, lane = threadIdx.x;
+    for (int item = blockIdx.x; item < MTT * CT; item += gridDim.x) {
+        const int mt = item / CT, ct = item - mt * CT, t = mt * 16 + (lane & 15), c0 = ct * 32 + (lane >> 4) * 8;
+        v8h v;
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+            const int idx = list[c0 + e];
+            v[e] = (t < M && idx >= 0) ? (_Float16)__half2float(X[(size_t)t * K + idx]) : (_Float16)0.0f;
+        }
+        *(v8h *)(xo + ((size_t)item * 64 + lane) * 8) = v;
+    }
+}
+
+__global__ void __launch_bounds__(64) k_gather_w(LinearW w, const int *__restrict__ count,
+                                                 const int *__restrict__ list, __half *__restrict__ wo) {
+    const int n_out = *count;
+    if (n_out <= PS_EXACT_OUTLIERS) return;
+    const int CT = (n_out + 31) >> 5, NT = w.N >> 4, KT = w.K >> 6, lane = threadIdx.x, row = lane & 15;
+    for (int item = blockIdx.x; item < NT * CT; item += gridDim.x) {
+        const int nt = item / CT, ct = item - nt * CT, c0 = ct * 32 + (lane >> 4) * 8;
+        const float swd = w.sw[nt * 16 + row] / 127.0f;
+        v8h v;
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+            const int k = list[c0 + e];
+            float f = 0.0f;
+            if (k >= 0) {
+                const int code = w.wt[((size_t)nt * KT + (k >> 6)) * 1024 + (((k & 63) >> 4) * 16 + row) * 16 + (k & 15)];
+                f = dequant_w16(code, swd);
+            }
+            v[e] = (_Float16)f;
+        }
+        *(v8h *)(wo + ((size_t)item * 64 + lane) * 8) = v;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// the tile pipeline
+
+struct GemmArgs {
+    const unsigned char *a_tiles;   // weight-side tiles: [N/16][KTILES][1024]
+    const unsigned char *b_tiles;   // token-side tiles:  [ceil(M/16)][KTILES][1024]
+    int ktiles;                     // int8: K/64.  fp16: unused (derived from the outlier count)
+    int M, N;
+    int nb_n, nb_m;
+};
+
+// F16 = false: int8 main product with the full epilogue.  F16 = true: fp16 outlier product into outl.
+template <bool F16, int WVN, int WVM, int TN, int TM>
 __global__ void __launch_bounds__(64 * WVN * WVM)
-k_gemm_lds(LinearW w, const int8_t *__restrict__ xq_tiled, const float *__restrict__ sx, int M, OutlierSet os,
-           OutDesc o, const SessTable *__restrict__ sess, int nb_n, int nb_m) {
-    constexpr int NW = WVN * WVM, BN = WVN * TN, BM = WVM * TM, STAGE = (BN + BM) * KS, LOADS = (STAGE + NW - 1) / NW;
+k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, float *__restrict__ outl, OutDesc o,
+           const SessTable *__restrict__ sess) {
+    constexpr int NW = WVN * WVM, BN = WVN * TN, BM = WVM * TM, STAGE = BN + BM, LOADS = STAGE / NW;
+    static_assert(STAGE % NW == 0, "every wave copies the same number of tiles per stage");
+    static_assert(TN % 2 == 0, "the epilogue parks half of the accumulators at a time");
     extern __shared__ __align__(16) unsigned char lds[];
     const int n_out = *os.count;
-    if (n_out > PS_EXACT_OUTLIERS) return;                      // the other kernel takes this call
+    const bool many = n_out > PS_EXACT_OUTLIERS;
+    if (F16 && !many) return;
+    const int NS = F16 ? (n_out + 31) >> 5 : ga.ktiles;          // k-tiles to walk (64 int8 or 32 fp16 columns each)
 
     // Workgroup -> output block.  Consecutive workgroup ids land on different XCDs (8 of them, each
     // with its own L2); give each XCD a contiguous run of blocks, ordered in strips of STRIP
     // m-blocks, so that the blocks an XCD works on at one time share weight and token tiles in its L2.
-    const int total = nb_n * nb_m, per_xcd = (total + 7) >> 3;
+    const int nb_n = ga.nb_n, nb_m = ga.nb_m, total = nb_n * nb_m, per_xcd = (total + 7) >> 3;
     const int ord = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if ((int)(blockIdx.x >> 3) >= per_xcd || ord >= total) return;
     const int nstrips = (nb_m + STRIP - 1) / STRIP;
@@ -33,44 +136,32 @@ k_gemm_lds(LinearW w, const int8_t *__restrict__ xq_tiled, const float *__restri
     const int rem = ord - strip * STRIP * nb_n, sw_this = min(STRIP, nb_m - strip * STRIP);
     const int bn = rem / sw_this, bm = strip * STRIP + rem % sw_this;
 
-    const int K = w.K, KT = K >> 6, N = w.N, NT = N >> 4, MTT = (M + 15) >> 4, NS = KT / KS;
+    const int M = ga.M, N = ga.N, NT = N >> 4, MTT = (M + 15) >> 4;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, row = lane & 15, kg = lane >> 4;
     const int wn = wave / WVM, wm = wave % WVM;
     const int nt0 = bn * BN, mt0 = bm * BM;
 
-    // the stage tiles this wave copies: s = wave + NW*j; s < BN*KS: weight tile, else token tile
-    const int8_t *src[LOADS];
+    // the stage tiles this wave copies: s = wave + NW*j; s < BN: weight tile, else token tile
+    const unsigned char *src[LOADS];
 #pragma unroll
     for (int j = 0; j < LOADS; j++) {
-        const int s = min(wave + NW * j, STAGE - 1);
-        if (s < BN * KS) {
-            const int nt = min(nt0 + s / KS, NT - 1);
-            src[j] = w.wt + ((size_t)nt * KT + s % KS) * 1024 + lane * 16;
-        } else {
-            const int s2 = s - BN * KS, mt = min(mt0 + s2 / KS, MTT - 1);
-            src[j] = xq_tiled + ((size_t)mt * KT + s2 % KS) * 1024 + lane * 16;
-        }
+        const int s = wave + NW * j;
+        if (s < BN) src[j] = ga.a_tiles + (size_t)min(nt0 + s, NT - 1) * NS * 1024 + lane * 16;
+        else src[j] = ga.b_tiles + (size_t)min(mt0 + s - BN, MTT - 1) * NS * 1024 + lane * 16;
     }
 
-    v4i acc[TN][TM];
+    typedef typename std::conditional<F16, v4f, v4i>::type acc_t;
+    acc_t acc[TN][TM];
 #pragma unroll
     for (int i = 0; i < TN; i++)
 #pragma unroll
-        for (int j = 0; j < TM; j++) acc[i][j] = (v4i){0, 0, 0, 0};
+        for (int j = 0; j < TM; j++) acc[i][j] = (acc_t){0, 0, 0, 0};
 
     // k-tiles travel global -> LDS with the asynchronous global_load_lds instruction (no staging
     // registers): one instruction copies one 1 KB tile, lane l supplying the address of bytes
-    // [16 l, 16 l + 16) and the hardware writing them to tile base + 16 l.  A ring of NSLOT slots
-    // holds PD = NSLOT - 1 stages in flight ahead of the one being multiplied, which covers the
-    // latency of an L2 miss.  Per iteration: wait until this wave's copies of stage s have landed
-    // (they complete in order, so "at most LOADS * (stages issued after s)" outstanding), barrier
-    // (now every wave's part of stage s is visible, and every wave has finished reading stage
-    // s - 1), reuse the slot of stage s - 1 for stage s + PD, multiply stage s.
-#ifndef GEMM_NSLOT
-#define GEMM_NSLOT 4
-#endif
-    constexpr int NSLOT = GEMM_NSLOT, PD = NSLOT - 1;
-    static_assert(STAGE % NW == 0, "every wave copies the same number of tiles per stage");
+    // [16 l, 16 l + 16) and the hardware writing them to tile base + 16 l.  The ring holds PD stages
+    // in flight, which covers the latency of an L2 miss.  Copies of one wave complete in order, so
+    // "stage s has landed" is "at most LOADS * (stages requested after s) copies outstanding".
     auto dma_stage = [&](int s) {
         unsigned char *slot = lds + (size_t)(s % NSLOT) * STAGE * 1024;
 #pragma unroll
@@ -79,14 +170,12 @@ k_gemm_lds(LinearW w, const int8_t *__restrict__ xq_tiled, const float *__restri
                 (const __attribute__((address_space(1))) void *)(src[j] + (size_t)s * 1024),
                 (__attribute__((address_space(3))) void *)(slot + (size_t)(wave + NW * j) * 1024), 16, 0, 0);
     };
-    for (int s = 0; s < PD && s < NS; s++) dma_stage(s);
-
-    auto wait_own = [&](int in_flight_after) {      // this wave's copies, all but the newest in_flight_after stages
-        if (in_flight_after >= 3) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS * 3) : "memory");
-        else if (in_flight_after == 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS * 2) : "memory");
+    auto wait_own = [&](int in_flight_after) {
+        if (in_flight_after >= 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS * 2) : "memory");
         else if (in_flight_after == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS) : "memory");
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     };
+    static_assert(PD == 3, "wait_own distinguishes at most two stages in flight behind the awaited one");
     auto frag_load = [&](int s, v4i *fa, v4i *fb) {
         const unsigned char *base = lds + (size_t)(s % NSLOT) * STAGE * 1024 + lane * 16;
 #pragma unroll
@@ -94,6 +183,8 @@ k_gemm_lds(LinearW w, const int8_t *__restrict__ xq_tiled, const float *__restri
 #pragma unroll
         for (int i = 0; i < TN; i++) fa[i] = *(const v4i *)(base + (size_t)(wn * TN + i) * 1024);
     };
+    for (int s = 0; s < PD && s < NS; s++) dma_stage(s);
+
     // Fragments are double buffered in registers: while stage s is multiplied, the fragments of stage
     // s + 1 are read from LDS.  So at the barrier of iteration s, stage s + 1 must have landed.
     v4i fa0[TN], fb0[TM], fa1[TN], fb1[TM];
@@ -103,29 +194,28 @@ k_gemm_lds(LinearW w, const int8_t *__restrict__ xq_tiled, const float *__restri
     frag_load(0, fa0, fb0);
     auto step = [&](int s, const v4i *ca, const v4i *cb, v4i *na, v4i *nb) {
         if (s + 1 < NS) {
-            wait_own(min(NS - s - 2, PD - 2));      // stage s + 1 of this wave (stages up to s + PD - 1 are issued)
-#ifndef GEMM_DBG_NOBARRIER
+            wait_own(min(NS - s - 2, PD - 2));      // stage s + 1 of this wave (stages up to s + PD - 1 are requested)
             __builtin_amdgcn_s_barrier();           // everybody's stage s + 1 visible; everybody done reading stage s - 1
-#endif
             asm volatile("" ::: "memory");
-#ifndef GEMM_DBG_NODMA
             if (s + PD < NS) dma_stage(s + PD);      // into the slot of stage s - 1
-#endif
             frag_load(s + 1, na, nb);
         }
 #pragma unroll
         for (int i = 0; i < TN; i++)
 #pragma unroll
-            for (int j = 0; j < TM; j++)
-                acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ca[i], cb[j], acc[i][j], 0, 0, 0);
+            for (int j = 0; j < TM; j++) {
+                if constexpr (F16)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(*(const v8h *)&ca[i], *(const v8h *)&cb[j], acc[i][j], 0, 0, 0);
+                else
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ca[i], cb[j], acc[i][j], 0, 0, 0);
+            }
     };
     for (int s = 0; s < NS; s += 2) {
         step(s, fa0, fb0, fa1, fb1);
         if (s + 1 < NS) step(s + 1, fa1, fb1, fa0, fb0);
     }
-    static_assert(PD <= 4, "wait_own distinguishes at most three stages in flight behind the awaited one");
-    // all copies have landed (vmcnt(0) in the last iteration); wait for every wave to finish reading
-    // the last stage before the slots are reused below
+    // all copies have landed (vmcnt(0) when the last stage was awaited); wait for every wave to finish
+    // reading the last stage before the slots are reused below
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
@@ -133,11 +223,8 @@ k_gemm_lds(LinearW w, const int8_t *__restrict__ xq_tiled, const float *__restri
     // Epilogue.  D[lane][r] = output row 4*(l/16)+r of the weight tile, token l%16 of the token tile.
     // The accumulators go through LDS (each lane parks and re-reads only its own values, half of the
     // wave's tiles at a time) so that the tail below is ONE rolled loop instead of TN*TM inlined copies.
-#ifdef GEMM_DBG_NOEPI
-    if (n_out >= 0) { if (acc[0][0][0] == 0x7fffffff) o.y[0] = __float2half(1.0f); return; }
-#endif
     const int nch = (n_out + 3) >> 2;
-    v4i *mine = (v4i *)lds + (size_t)wave * (TN / 2 * TM * 64) + lane;
+    acc_t *mine = (acc_t *)lds + (size_t)wave * (TN / 2 * TM * 64) + lane;
 #pragma unroll
     for (int p = 0; p < 2; p++) {
 #pragma unroll
@@ -148,47 +235,66 @@ k_gemm_lds(LinearW w, const int8_t *__restrict__ xq_tiled, const float *__restri
         for (int idx = 0; idx < TN / 2 * TM; idx++) {
             const int nt = nt0 + wn * TN + p * (TN / 2) + idx / TM, mt = mt0 + wm * TM + idx % TM;
             if (nt >= NT || mt >= MTT) continue;                        // wave-uniform
-            const v4i a4 = mine[idx * 64];
-            v4d od = {0.0, 0.0, 0.0, 0.0};
-            if (n_out > 0) {
-                const double *ap = os.wd64 + (size_t)nt * PS_OUTLIER_CHUNKS * 64 + lane;
-                const double *bp = os.x64 + (size_t)mt * PS_OUTLIER_CHUNKS * 64 + lane;
-                for (int c = 0; c < nch; c++)
-                    od = __builtin_amdgcn_mfma_f64_16x16x4f64(ap[c * 64], bp[c * 64], od, 0, 0, 0);
+            const acc_t a4 = mine[idx * 64];
+            const int t = mt * 16 + row, n0 = nt * 16 + 4 * kg;
+            if constexpr (F16) {
+                if (t < M) *(v4f *)(outl + (size_t)t * N + n0) = a4;
+            } else {
+                v4d od = {0.0, 0.0, 0.0, 0.0};
+                if (many) {
+                    if (t < M) {
+                        const v4f f = *(const v4f *)(outl + (size_t)t * N + n0);
+                        od = (v4d){(double)f[0], (double)f[1], (double)f[2], (double)f[3]};
+                    }
+                } else if (n_out > 0) {
+                    const double *ap = os.wd64 + (size_t)nt * PS_OUTLIER_CHUNKS * 64 + lane;
+                    const double *bp = os.x64 + (size_t)mt * PS_OUTLIER_CHUNKS * 64 + lane;
+                    for (int c = 0; c < nch; c++)
+                        od = __builtin_amdgcn_mfma_f64_16x16x4f64(ap[c * 64], bp[c * 64], od, 0, 0, 0);
+                }
+                if (t >= M) continue;
+                emit_output4(o, sess, N, t, n0, a4, od, sx[t] / 127.0f, w.sw, w.bias);
             }
-            const int t = mt * 16 + row;
-            if (t >= M) continue;
-            const float sxd = sx[t] / 127.0f;
-            emit_output4(o, sess, N, t, nt * 16 + 4 * kg, a4, od, sxd, w.sw, w.bias);
         }
     }
 }
 
-template <int WVN, int WVM, int TN, int TM, int KS>
-hipError_t launch_lds(const LinearW &w, const int8_t *xq_tiled, const float *sx, int M, const OutlierSet &os,
+template <bool F16>
+hipError_t launch_lds(const GemmArgs &ga0, const LinearW &w, const float *sx, const OutlierSet &os, float *outl,
                       const OutDesc &o, const SessTable *sess, hipStream_t st) {
-    constexpr int BN = WVN * TN, BM = WVM * TM;
-    const int NT = w.N / 16, MTT = (M + 15) / 16;
-    const int nb_n = (NT + BN - 1) / BN, nb_m = (MTT + BM - 1) / BM;
-    const int total = nb_n * nb_m;
-    const size_t lds_stage = (size_t)GEMM_NSLOT * (BN + BM) * KS * 1024, lds_epi = (size_t)WVN * WVM * (TN / 2) * TM * 1024;
+    constexpr int WVN = 2, WVM = 4, TN = 8, TM = 4, BN = WVN * TN, BM = WVM * TM;   // 8 waves, 128 x 64 per wave
+    GemmArgs ga = ga0;
+    const int NT = ga.N / 16, MTT = (ga.M + 15) / 16;
+    ga.nb_n = (NT + BN - 1) / BN;
+    ga.nb_m = (MTT + BM - 1) / BM;
+    const int total = ga.nb_n * ga.nb_m;
+    const size_t lds_stage = (size_t)NSLOT * (BN + BM) * 1024, lds_epi = (size_t)WVN * WVM * (TN / 2) * TM * 1024;
     const size_t lds = lds_stage > lds_epi ? lds_stage : lds_epi;
-    auto kern = k_gemm_lds<WVN, WVM, TN, TM, KS>;
+    auto kern = k_gemm_lds<F16, WVN, WVM, TN, TM>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    kern<<<((total + 7) / 8) * 8, 64 * WVN * WVM, lds, st>>>(w, xq_tiled, sx, M, os, o, sess, nb_n, nb_m);
+    kern<<<((total + 7) / 8) * 8, 64 * WVN * WVM, lds, st>>>(ga, w, sx, os, outl, o, sess);
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t ps_gemm_lds(const LinearW &w, const int8_t *xq_tiled, const float *sx, int M, const OutlierSet &os,
-                       const OutDesc &o, const SessTable *sess, hipStream_t st) {
-    static const int variant = getenv("PS_GEMM_VARIANT") ? atoi(getenv("PS_GEMM_VARIANT")) : 0;   // tuning knob
-    if (variant == 1) return launch_lds<2, 2, 8, 8, 1>(w, xq_tiled, sx, M, os, o, sess, st);   // 4 waves, 128x128 per wave
-    return launch_lds<2, 4, 8, 4, 1>(w, xq_tiled, sx, M, os, o, sess, st);                     // 8 waves, 128x64 per wave
+hipError_t ps_gemm_lds(const LinearW &w, const int8_t *xq_tiled, const uint32_t *mask, const __half *X, const float *sx,
+                       int M, const OutlierSet &os, const ManyOutliers &mo, const OutDesc &o, const SessTable *sess,
+                       hipStream_t st) {
+    // the outlier-heavy case first (all four kernels return at once when the call has few outlier columns)
+    k_outlier_list<<<1, 1024, 0, st>>>(mask, w.K, os.count, mo.list);
+    k_gather_x<<<2048, 64, 0, st>>>(X, M, w.K, os.count, mo.list, mo.xo);
+    k_gather_w<<<4096, 64, 0, st>>>(w, os.count, mo.list, mo.wo);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    GemmArgs gf = {(const unsigned char *)mo.wo, (const unsigned char *)mo.xo, 0, M, w.N, 0, 0};
+    e = launch_lds<true>(gf, w, sx, os, mo.outl, o, sess, st);
+    if (e != hipSuccess) return e;
+    GemmArgs gi = {(const unsigned char *)w.wt, (const unsigned char *)xq_tiled, w.K / 64, M, w.N, 0, 0};
+    return launch_lds<false>(gi, w, sx, os, mo.outl, o, sess, st);
 }
