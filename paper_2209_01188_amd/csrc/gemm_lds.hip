@@ -123,7 +123,9 @@ k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, 
     const int n_out = *os.count;
     const bool many = n_out > PS_EXACT_OUTLIERS;
     if (F16 && !many) return;
-    const int NS = F16 ? (n_out + 31) >> 5 : ga.ktiles;          // k-tiles to walk (64 int8 or 32 fp16 columns each)
+    // k-tiles to walk (64 int8 or 32 fp16 columns each).  If EVERY column is an outlier all int8 codes are
+    // zero: the int8 product is skipped and only the epilogue runs.
+    const int NS = F16 ? (n_out + 31) >> 5 : (n_out == ga.ktiles * 64 ? 0 : ga.ktiles);
 
     // Workgroup -> output block.  Consecutive workgroup ids land on different XCDs (8 of them, each
     // with its own L2); give each XCD a contiguous run of blocks, ordered in strips of STRIP
@@ -188,10 +190,12 @@ k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, 
     // Fragments are double buffered in registers: while stage s is multiplied, the fragments of stage
     // s + 1 are read from LDS.  So at the barrier of iteration s, stage s + 1 must have landed.
     v4i fa0[TN], fb0[TM], fa1[TN], fb1[TM];
-    wait_own(min(NS - 1, PD - 1));                  // stage 0 of this wave
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-    frag_load(0, fa0, fb0);
+    if (NS > 0) {
+        wait_own(min(NS - 1, PD - 1));              // stage 0 of this wave
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        frag_load(0, fa0, fb0);
+    }
     auto step = [&](int s, const v4i *ca, const v4i *cb, v4i *na, v4i *nb) {
         if (s + 1 < NS) {
             wait_own(min(NS - s - 2, PD - 2));      // stage s + 1 of this wave (stages up to s + PD - 1 are requested)
