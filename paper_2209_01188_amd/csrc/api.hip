@@ -60,6 +60,7 @@ struct Workspace {
     SessTable *table;
     __half *a, *q, *ctx, *x1, *xa, *xb, *g;
     int8_t *xq;
+    int8_t *xo;         // outlier values per (token, 16-column group) of calls of at most 64 rows
     float *sx;
     uint32_t *masks;    // [n_blocks][4][mask_words]
     double *partials;
@@ -85,6 +86,7 @@ Workspace carve(const petals_span_config &c, uint8_t *base) {
     w.xb = (__half *)take(M * H * 2);
     w.g = (__half *)take(M * (F > 3 * H ? F : 3 * H) * 2);   // MLP activations; also scratch for a [M,3H] result
     w.xq = (int8_t *)take(Mp * Kmax);
+    w.xo = (int8_t *)take((Mp < 64 ? Mp : 64) * Kmax);
     w.sx = (float *)take(Mp * 4);
     w.mask_words = (Kmax + 63) / 64 * 2;
     w.masks = (uint32_t *)take((size_t)c.n_blocks * 4 * w.mask_words * 4);
@@ -205,11 +207,11 @@ int run_linear(petals_span *sp, int which, const LinearW &w, const __half *X, co
         }
         HIP_TRY(ps_fill_u32(mask, ws.mask_words, 0u, st));
         HIP_TRY(ps_colmask(X, M, w.K, theta, mask, st));
-        HIP_TRY(ps_rowquant_tiled(X, M, w.K, mask, ws.xq, ws.sx, xq_dbg, st));
-        HIP_TRY(ps_outlier_prep(w, mask, X, M, ws.ocount, ws.wd64, ws.x64, st));
+        HIP_TRY(ps_rowquant_tiled(X, M, w.K, mask, ws.xq, M <= 64 ? ws.xo : nullptr, ws.sx, xq_dbg, st));
         const OutlierSet os = {ws.ocount, ws.wd64, ws.x64};
+        if (M > 64) HIP_TRY(ps_outlier_prep(w, mask, X, M, ws.ocount, ws.wd64, ws.x64, st));
         const bool pr = sp->prof.begin(PETALS_PROFILE_GEMM, which, st);
-        if (M <= 64) HIP_TRY(ps_gemm(w, ws.xq, mask, X, ws.sx, M, os, o, ws.table, st));
+        if (M <= 64) HIP_TRY(ps_gemm(w, ws.xq, ws.xo, mask, X, ws.sx, M, o, ws.table, st));
         else HIP_TRY(ps_gemm_lds(w, ws.xq, mask, X, ws.sx, M, os, ws.many, o, ws.table, st));
         sp->prof.end(pr, st);
     }

@@ -73,8 +73,10 @@ hipError_t ps_layernorm(const __half *x, const __half *g, const __half *b, float
                         __half *y, hipStream_t st);
 hipError_t ps_colmask(const __half *X, int M, int K, float theta, uint32_t *mask, hipStream_t st);
 // M rows -> tiled int8 codes (rows padded to 16 with zeros), row scales; mask given
-hipError_t ps_rowquant_tiled(const __half *X, int M, int K, const uint32_t *mask, int8_t *xq_tiled, float *sx,
-                             int8_t *xq_rowmajor_dbg, hipStream_t st);
+// xo_tiled (may be null): same tile order, 16 bytes per (token, 16-column group) = the fp16 values of the
+// group's first 8 outlier columns in ascending order; groups without outliers are not written
+hipError_t ps_rowquant_tiled(const __half *X, int M, int K, const uint32_t *mask, int8_t *xq_tiled, int8_t *xo_tiled,
+                             float *sx, int8_t *xq_rowmajor_dbg, hipStream_t st);
 hipError_t ps_mask_to_bytes(const uint32_t *mask, int K, uint8_t *out, hipStream_t st);
 
 // Scratch of the outlier-heavy case of a prefill-size call (more than PS_EXACT_OUTLIERS columns)
@@ -99,12 +101,13 @@ struct RowDebug {
 // first goes through LayerNorm.  Outlier detection and int8 quantization happen inside the kernel.
 hipError_t ps_gemv_row(const LinearW &w, const __half *x, const __half *ln_g, const __half *ln_b, float eps,
                        float theta, const RowDebug &dbg, const OutDesc &o, const SessTable *sess, hipStream_t st);
-// counts the outlier columns of a call and, if they are few, compacts their operands
+// counts the outlier columns of a prefill-size call and, if they are few, compacts their operands
 hipError_t ps_outlier_prep(const LinearW &w, const uint32_t *mask, const __half *X, int M, int *count, double *wd64,
                            double *x64, hipStream_t st);
-// same for M >= 2 rows on int8 / fp16 / fp64 MFMA; xq_tiled as written by ps_rowquant_tiled
-hipError_t ps_gemm(const LinearW &w, const int8_t *xq_tiled, const uint32_t *mask, const __half *X, const float *sx,
-                   int M, const OutlierSet &os, const OutDesc &o, const SessTable *sess, hipStream_t st);
+// batched-decode linear, 2 <= M <= 64 rows (int8 MFMA, outlier columns exactly on fp64 MFMA inside the
+// loop); xq_tiled and xo_tiled as written by ps_rowquant_tiled
+hipError_t ps_gemm(const LinearW &w, const int8_t *xq_tiled, const int8_t *xo_tiled, const uint32_t *mask,
+                   const __half *X, const float *sx, int M, const OutDesc &o, const SessTable *sess, hipStream_t st);
 
 // attention of M = B*T query rows against the caches (new keys/values already appended)
 hipError_t ps_set_table(const SessTable &host_table, SessTable *dev_table, hipStream_t st);

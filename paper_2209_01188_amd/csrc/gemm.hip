@@ -1,28 +1,13 @@
-// Linear for M >= 2 rows on the matrix cores: int8 x int8 -> int32 with
-// v_mfma_i32_16x16x64_i8 for the regular columns, and v_mfma_f32_16x16x32_f16 on the
-// 64-column tiles that contain outlier columns (weights dequantized in registers from the
-// same int8 tile, activations masked to the outlier columns).
+// Batched-decode linear (2 <= M <= 64 rows) on the matrix cores.  HBM bound: every weight tile is
+// streamed once.  Regular columns: int8 x int8 -> int32 with v_mfma_i32_16x16x64_i8.  Outlier
+// columns are added exactly, inside the loop, from the weight bytes already in registers: on a
+// 64-column tile that holds outliers, each of the four 16-column lane groups hands its next outlier
+// column to one k-slot of v_mfma_f64_16x16x4_f64 (products of fp16 values are exact in fp64).
+// Also here: the compaction kernel that prefill-size calls use for the same exact product.
 #include "common.h"
 #include "epilogue.h"
 
 namespace {
-
-// 8 int8 codes (two 32-bit words) -> 8 fp16 weights: fp32 product with the row's scale/127, RNE to fp16
-__device__ __forceinline__ v8h dequant8(int w0, int w1, float swd) {
-    v8h r;
-#pragma unroll
-    for (int b = 0; b < 4; b++) {
-        r[b] = (_Float16)keep_f32((float)(int8_t)((w0 >> (8 * b)) & 0xff) * swd);
-        r[b + 4] = (_Float16)keep_f32((float)(int8_t)((w1 >> (8 * b)) & 0xff) * swd);
-    }
-    return r;
-}
-
-__device__ __forceinline__ v8h mask8(v8h v, uint32_t bits) {
-#pragma unroll
-    for (int b = 0; b < 8; b++) v[b] = ((bits >> b) & 1u) ? v[b] : (_Float16)0.0f;
-    return v;
-}
 
 // Counts the outlier columns and, when there are at most PS_EXACT_OUTLIERS, gathers their
 // dequantized weights (one workgroup per 16 output rows) and activations (one per 16
@@ -82,163 +67,198 @@ __global__ void __launch_bounds__(64) k_outlier_prep(LinearW w, const uint32_t *
     }
 }
 
-// Workgroup = WVN x WVM x WVK waves.  Wave (wn, wm, wk) owns WN weight tiles (16 output
-// rows each) x MT token tiles (16 rows each) and the K tiles kt = wk, wk + WVK, ...;
-// with WVK > 1 the partial sums meet in LDS and are added in a fixed order.
-// Weights are the A operand (lane l: row l%16, 16 codes of column group l/16), tokens the
-// B operand in the same tile order, so D[lane][r] is output row 4*(l/16)+r of token l%16.
-template <int WN, int MT, int WVN, int WVM, int WVK>
-__global__ void __launch_bounds__(64 * WVN * WVM * WVK)
-k_gemm(LinearW w, const int8_t *__restrict__ xq_tiled, const uint32_t *__restrict__ mask,
-       const __half *__restrict__ X, const float *__restrict__ sx, int M, OutlierSet os, OutDesc o,
-       const SessTable *__restrict__ sess) {
-    const int n_out = *os.count;
-    const bool exact = n_out <= PS_EXACT_OUTLIERS;     // few outliers: fp64 pass after the main loop
-    const int K = w.K, KT = K >> 6, N = w.N, NT = N >> 4, MTT = (M + 15) >> 4;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, row = lane & 15, kg = lane >> 4;
-    const int wk = wave % WVK, wm = (wave / WVK) % WVM, wn = wave / (WVK * WVM);
-    const int nt0 = (blockIdx.x * WVN + wn) * WN, mt0 = (blockIdx.y * WVM + wm) * MT;
+__device__ __forceinline__ int byte_of16(const v4i &w, int j) {
+    const int word = (j < 8) ? ((j < 4) ? w[0] : w[1]) : ((j < 12) ? w[2] : w[3]);
+    return (int)(int8_t)((word >> ((j & 3) * 8)) & 0xff);
+}
+__device__ __forceinline__ float half_of8(const v4i &x, int r) {   // r-th of the 8 halves in x
+    const int word = (r < 4) ? ((r < 2) ? x[0] : x[1]) : ((r < 6) ? x[2] : x[3]);
+    return __half2float(__ushort_as_half((unsigned short)((word >> ((r & 1) * 16)) & 0xffff)));
+}
+
+// One workgroup = WVK waves on WN consecutive 16-row weight panels; wave wk takes chunks of UK
+// consecutive k-tiles (chunk c = wk, wk + WVK, ...) for MT token tiles of 16 rows, so a token tile
+// fetched once meets WN weight tiles.  Weights are the A operand (lane l: row l%16, 16 codes of
+// column group l/16), tokens the B operand in the same tile order: D[lane][r] is output row
+// 4*(l/16)+r of token l%16.  The next chunk's operands are requested before the current chunk is
+// multiplied.  xo: per token tile and k-tile, lane (token, column group) holds the values of the
+// group's first 8 outlier columns (written by ps_rowquant_tiled); a group with more takes the rest
+// from X.  The waves' partial sums meet in LDS as a tree.
+template <int WN, int MT, int UK, int WVK>
+__global__ void __launch_bounds__(64 * WVK)
+k_gemm(LinearW w, const int8_t *__restrict__ xq_tiled, const int8_t *__restrict__ xo_tiled,
+       const uint32_t *__restrict__ mask, const __half *__restrict__ X, const float *__restrict__ sx, int M,
+       OutDesc o, const SessTable *__restrict__ sess) {
+    const int K = w.K, KT = K >> 6, N = w.N, MTT = (M + 15) >> 4;
+    const int wk = threadIdx.x >> 6, lane = threadIdx.x & 63, row = lane & 15, kg = lane >> 4;
+    const int nt0 = blockIdx.x * WN;
 
     v4i acc[WN][MT];
-    v4f oac[WN][MT];
+    v4d od[WN][MT];
 #pragma unroll
-    for (int i = 0; i < WN; i++)
+    for (int p = 0; p < WN; p++)
 #pragma unroll
         for (int j = 0; j < MT; j++) {
-            acc[i][j] = (v4i){0, 0, 0, 0};
-            oac[i][j] = (v4f){0.f, 0.f, 0.f, 0.f};
+            acc[p][j] = (v4i){0, 0, 0, 0};
+            od[p][j] = (v4d){0.0, 0.0, 0.0, 0.0};
         }
-    const int8_t *wbase[WN];
+    const int8_t *wbase = w.wt + (size_t)nt0 * KT * 1024 + lane * 16;
     float swd[WN];
 #pragma unroll
-    for (int i = 0; i < WN; i++) {
-        const int nt = min(nt0 + i, NT - 1);
-        wbase[i] = w.wt + (size_t)nt * KT * 1024 + lane * 16;
-        swd[i] = w.sw[nt * 16 + row] / 127.0f;
-    }
-    const int8_t *xbase[MT];
+    for (int p = 0; p < WN; p++) swd[p] = w.sw[(nt0 + p) * 16 + row] / 127.0f;
+    size_t xoff[MT];
     const __half *xrow[MT];
 #pragma unroll
     for (int j = 0; j < MT; j++) {
-        const int mt = min(mt0 + j, MTT - 1);
-        xbase[j] = xq_tiled + (size_t)mt * KT * 1024 + lane * 16;
+        const int mt = min(j, MTT - 1);
+        xoff[j] = (size_t)mt * KT * 1024 + lane * 16;
         xrow[j] = X + (size_t)min(mt * 16 + row, M - 1) * K + kg * 16;
     }
     const uint64_t *mask64 = (const uint64_t *)mask;
+    const int nch = (KT + UK - 1) / UK;
 
-    // One k-tile: int8 product, and on tiles that hold outlier columns (when they are too many for the
-    // exact pass) the fp16 product of the masked activations with weights dequantized in registers.
-    auto tile = [&](int kt, const v4i *wv, const v4i *xv) {
+    struct Buf {
+        v4i w[UK][WN], x[UK][MT], xo[UK][MT];
+        uint64_t m[UK];
+    };
+    auto load = [&](Buf &b, int c) {
 #pragma unroll
-        for (int i = 0; i < WN; i++)
+        for (int u = 0; u < UK; u++) {
+            const int kt = min(c * UK + u, KT - 1);
 #pragma unroll
-            for (int j = 0; j < MT; j++)
-                acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wv[i], xv[j], acc[i][j], 0, 0, 0);
-        const uint64_t mbits = mask64[kt];                 // same for the whole wave
-        if (mbits && !exact) {
-            const uint32_t gb = (uint32_t)(mbits >> (kg * 16)) & 0xffffu;
-            v8h xlo[MT], xhi[MT];
+            for (int p = 0; p < WN; p++)
+                b.w[u][p] = __builtin_nontemporal_load((const v4i *)(wbase + ((size_t)p * KT + kt) * 1024));
 #pragma unroll
-            for (int j = 0; j < MT; j++) {
-                const __half *xp = xrow[j] + kt * 64;
-                xlo[j] = mask8(*(const v8h *)xp, gb);
-                xhi[j] = mask8(*(const v8h *)(xp + 8), gb >> 8);
+            for (int j = 0; j < MT; j++) b.x[u][j] = *(const v4i *)(xq_tiled + xoff[j] + (size_t)kt * 1024);
+        }
+#pragma unroll
+        for (int u = 0; u < UK; u++) {
+            const int kt = min(c * UK + u, KT - 1);
+            b.m[u] = mask64[kt];                              // same for the whole wave
+#pragma unroll
+            for (int j = 0; j < MT; j++) b.xo[u][j] = (v4i){0, 0, 0, 0};
+            if (b.m[u]) {
+#pragma unroll
+                for (int j = 0; j < MT; j++) b.xo[u][j] = *(const v4i *)(xo_tiled + xoff[j] + (size_t)kt * 1024);
             }
+        }
+    };
+    auto compute = [&](const Buf &b, int c) {
 #pragma unroll
-            for (int i = 0; i < WN; i++) {
-                const v8h wlo = dequant8(wv[i][0], wv[i][1], swd[i]);
-                const v8h whi = dequant8(wv[i][2], wv[i][3], swd[i]);
+        for (int u = 0; u < UK; u++) {
+            const int kt = c * UK + u;
+            if (kt >= KT) break;                              // ragged last chunk
 #pragma unroll
-                for (int j = 0; j < MT; j++) {
-                    oac[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wlo, xlo[j], oac[i][j], 0, 0, 0);
-                    oac[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(whi, xhi[j], oac[i][j], 0, 0, 0);
+            for (int p = 0; p < WN; p++)
+#pragma unroll
+                for (int j = 0; j < MT; j++)
+                    acc[p][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(b.w[u][p], b.x[u][j], acc[p][j], 0, 0, 0);
+            const uint64_t mbits = b.m[u];
+            if (mbits) {
+                // outlier columns of this tile, exactly: round r takes the r-th outlier column of each of
+                // the four 16-column groups into one k-slot of the fp64 instruction
+                uint32_t gb = (uint32_t)(mbits >> (kg * 16)) & 0xffffu;
+                const int rounds =
+                    max(max(__popc((uint32_t)mbits & 0xffffu), __popc((uint32_t)(mbits >> 16) & 0xffffu)),
+                        max(__popc((uint32_t)(mbits >> 32) & 0xffffu), __popc((uint32_t)(mbits >> 48))));
+                for (int r = 0; r < rounds; r++) {
+                    const bool have = gb != 0;
+                    const int jcol = have ? __ffs(gb) - 1 : 0;
+                    gb &= gb - 1;
+                    double a[WN];
+#pragma unroll
+                    for (int p = 0; p < WN; p++)
+                        a[p] = have ? (double)dequant_w16(byte_of16(b.w[u][p], jcol), swd[p]) : 0.0;
+#pragma unroll
+                    for (int j = 0; j < MT; j++) {
+                        float xv = r < 8 ? half_of8(b.xo[u][j], r) : __half2float(xrow[j][kt * 64 + jcol]);
+                        const double bx = have ? (double)xv : 0.0;
+#pragma unroll
+                        for (int p = 0; p < WN; p++)
+                            od[p][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[p], bx, od[p][j], 0, 0, 0);
+                    }
                 }
             }
         }
     };
-    // Wave wk takes chunks of UK consecutive k-tiles (chunk c = wk, wk + WVK, ...) and requests all
-    // operand tiles of a chunk before using any, so several KB per wave are in flight.
-    constexpr int UK = (WN * MT <= 2) ? 4 : (WN * MT <= 4 ? 2 : 1);
-    const int nchunks = KT / UK;
-    for (int c = wk; c < nchunks; c += WVK) {
-        v4i wv[UK][WN], xv[UK][MT];
+
+    Buf A, B;
+    int c = wk;
+    if (c < nch) load(A, c);
+    while (c < nch) {
+        const int c1 = c + WVK, c2 = c1 + WVK;
+        if (c1 < nch) load(B, c1);
+        compute(A, c);
+        if (c2 < nch) load(A, c2);
+        if (c1 < nch) compute(B, c1);
+        c = c2;
+    }
+
+    // tree over the waves, PP panels at a time: the upper half of the live waves writes, the lower
+    // half adds (integers in any order; the fp64 terms are exact products of fp16 values)
+    constexpr int PP = (4 / MT > WN) ? WN : (4 / MT > 0 ? 4 / MT : 1);
+    extern __shared__ __align__(16) unsigned char lds[];
+    v4i *ri = (v4i *)lds;                                                  // [WVK/2][PP*MT][64]
+    v4d *rf = (v4d *)(lds + (size_t)(WVK / 2) * PP * MT * 64 * 16);        // [WVK/2][PP*MT][64]
 #pragma unroll
-        for (int u = 0; u < UK; u++) {
+    for (int p0 = 0; p0 < WN; p0 += PP) {
 #pragma unroll
-            for (int i = 0; i < WN; i++) wv[u][i] = __builtin_nontemporal_load((const v4i *)(wbase[i] + (size_t)(c * UK + u) * 1024));
+        for (int half = WVK / 2; half >= 1; half >>= 1) {
+            if (wk >= half && wk < 2 * half) {
 #pragma unroll
-            for (int j = 0; j < MT; j++) xv[u][j] = *(const v4i *)(xbase[j] + (size_t)(c * UK + u) * 1024);
+                for (int pp = 0; pp < PP; pp++)
+#pragma unroll
+                    for (int j = 0; j < MT; j++) {
+                        ri[((wk - half) * PP * MT + pp * MT + j) * 64 + lane] = acc[p0 + pp][j];
+                        rf[((wk - half) * PP * MT + pp * MT + j) * 64 + lane] = od[p0 + pp][j];
+                    }
+            }
+            __syncthreads();
+            if (wk < half) {
+#pragma unroll
+                for (int pp = 0; pp < PP; pp++)
+#pragma unroll
+                    for (int j = 0; j < MT; j++) {
+                        acc[p0 + pp][j] += ri[(wk * PP * MT + pp * MT + j) * 64 + lane];
+                        od[p0 + pp][j] += rf[(wk * PP * MT + pp * MT + j) * 64 + lane];
+                    }
+            }
+            __syncthreads();
         }
-#pragma unroll
-        for (int u = 0; u < UK; u++) tile(c * UK + u, wv[u], xv[u]);
     }
-    for (int kt = nchunks * UK + wk; kt < KT; kt += WVK) {
-        v4i wv[WN], xv[MT];
+    if (wk != 0) return;
 #pragma unroll
-        for (int i = 0; i < WN; i++) wv[i] = *(const v4i *)(wbase[i] + (size_t)kt * 1024);
-#pragma unroll
-        for (int j = 0; j < MT; j++) xv[j] = *(const v4i *)(xbase[j] + (size_t)kt * 1024);
-        tile(kt, wv, xv);
-    }
-
-    if (WVK > 1) {
-        extern __shared__ __align__(16) unsigned char lds[];
-        v4i *ri = (v4i *)lds;                                           // [waves][WN*MT][64]
-        v4f *rf = (v4f *)(lds + (size_t)WVN * WVM * WVK * WN * MT * 64 * 16);
-#pragma unroll
-        for (int i = 0; i < WN; i++)
-#pragma unroll
-            for (int j = 0; j < MT; j++) {
-                ri[(wave * WN * MT + i * MT + j) * 64 + lane] = acc[i][j];
-                rf[(wave * WN * MT + i * MT + j) * 64 + lane] = oac[i][j];
-            }
-        __syncthreads();
-        if (wk != 0) return;
-#pragma unroll
-        for (int i = 0; i < WN; i++)
-#pragma unroll
-            for (int j = 0; j < MT; j++) {
-                v4i a = ri[(wave * WN * MT + i * MT + j) * 64 + lane];
-                v4f f = rf[(wave * WN * MT + i * MT + j) * 64 + lane];
-                for (int s = 1; s < WVK; s++) {
-                    a += ri[((wave + s) * WN * MT + i * MT + j) * 64 + lane];
-                    f += rf[((wave + s) * WN * MT + i * MT + j) * 64 + lane];
-                }
-                acc[i][j] = a;
-                oac[i][j] = f;
-            }
-    }
-
-#pragma unroll
-    for (int i = 0; i < WN; i++) {
-        if (nt0 + i >= NT) continue;
+    for (int p = 0; p < WN; p++)
 #pragma unroll
         for (int j = 0; j < MT; j++) {
-            if (mt0 + j >= MTT) continue;                               // wave-uniform
-            v4d od = {(double)oac[i][j][0], (double)oac[i][j][1], (double)oac[i][j][2], (double)oac[i][j][3]};
-            if (exact && n_out > 0) {
-                // exact fp16 part: products of fp16 values are exact in fp64, sums round at 2^-53
-                const double *ap = os.wd64 + (size_t)(nt0 + i) * PS_OUTLIER_CHUNKS * 64 + lane;
-                const double *bp = os.x64 + (size_t)(mt0 + j) * PS_OUTLIER_CHUNKS * 64 + lane;
-                od = (v4d){0.0, 0.0, 0.0, 0.0};
-                for (int c = 0; c < (n_out + 3) >> 2; c++)
-                    od = __builtin_amdgcn_mfma_f64_16x16x4f64(ap[c * 64], bp[c * 64], od, 0, 0, 0);
+            if (j >= MTT) continue;                                     // wave-uniform
+            const v4d f = od[p][j];
+            // the fp64 instruction returns row 4r + g in register r of lane group g, the int8 one row 4g + r:
+            // transpose the 4 x 4 (group, register) block among the four lanes that share a token
+            v4d ft;
+#pragma unroll
+            for (int r = 0; r < 4; r++) {
+                double v = 0.0;
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    const double t = __shfl(f[q], row + 16 * r);
+                    if (q == kg) v = t;
+                }
+                ft[r] = v;
             }
-            const int t = (mt0 + j) * 16 + row;
+            const int t = j * 16 + row;
             if (t >= M) continue;
-            const float sxd = sx[t] / 127.0f;
-            emit_output4(o, sess, N, t, (nt0 + i) * 16 + 4 * kg, acc[i][j], od, sxd, w.sw, w.bias);
+            emit_output4(o, sess, N, t, (nt0 + p) * 16 + 4 * kg, acc[p][j], ft, sx[t] / 127.0f, w.sw, w.bias);
         }
-    }
 }
 
-template <int WN, int MT, int WVN, int WVM, int WVK>
-hipError_t launch(const LinearW &w, const int8_t *xq_tiled, const uint32_t *mask, const __half *X, const float *sx,
-                  int M, const OutlierSet &os, const OutDesc &o, const SessTable *sess, hipStream_t st) {
-    const int NT = w.N / 16, MTT = (M + 15) / 16;
-    dim3 grid((NT + WVN * WN - 1) / (WVN * WN), (MTT + WVM * MT - 1) / (WVM * MT));
-    size_t lds = WVK > 1 ? (size_t)WVN * WVM * WVK * WN * MT * 64 * 32 : 0;
-    k_gemm<WN, MT, WVN, WVM, WVK><<<grid, 64 * WVN * WVM * WVK, lds, st>>>(w, xq_tiled, mask, X, sx, M, os, o, sess);
+template <int WN, int MT, int UK>
+hipError_t launch(const LinearW &w, const int8_t *xq_tiled, const int8_t *xo_tiled, const uint32_t *mask,
+                  const __half *X, const float *sx, int M, const OutDesc &o, const SessTable *sess, hipStream_t st) {
+    constexpr int WVK = 8;
+    constexpr int PP = (4 / MT > WN) ? WN : (4 / MT > 0 ? 4 / MT : 1);
+    const size_t lds = (size_t)(WVK / 2) * PP * MT * 64 * (16 + 32);   // 48 KB
+    k_gemm<WN, MT, UK, WVK><<<w.N / (16 * WN), 64 * WVK, lds, st>>>(w, xq_tiled, xo_tiled, mask, X, sx, M, o, sess);
     return hipGetLastError();
 }
 
@@ -250,10 +270,11 @@ hipError_t ps_outlier_prep(const LinearW &w, const uint32_t *mask, const __half 
     return hipGetLastError();
 }
 
-hipError_t ps_gemm(const LinearW &w, const int8_t *xq_tiled, const uint32_t *mask, const __half *X, const float *sx,
-                   int M, const OutlierSet &os, const OutDesc &o, const SessTable *sess, hipStream_t st) {
-    if (M <= 16) return launch<1, 1, 1, 1, 8>(w, xq_tiled, mask, X, sx, M, os, o, sess, st);
-    if (M <= 32) return launch<1, 2, 1, 1, 8>(w, xq_tiled, mask, X, sx, M, os, o, sess, st);
-    if (M <= 64) return launch<1, 4, 1, 1, 8>(w, xq_tiled, mask, X, sx, M, os, o, sess, st);
+hipError_t ps_gemm(const LinearW &w, const int8_t *xq_tiled, const int8_t *xo_tiled, const uint32_t *mask,
+                   const __half *X, const float *sx, int M, const OutDesc &o, const SessTable *sess, hipStream_t st) {
+    if (w.N % 64) return hipErrorInvalidValue;
+    if (M <= 16) return launch<4, 1, 2>(w, xq_tiled, xo_tiled, mask, X, sx, M, o, sess, st);
+    if (M <= 32) return launch<4, 2, 1>(w, xq_tiled, xo_tiled, mask, X, sx, M, o, sess, st);
+    if (M <= 64) return launch<2, 4, 1>(w, xq_tiled, xo_tiled, mask, X, sx, M, o, sess, st);
     return hipErrorInvalidValue;   // larger calls belong to ps_gemm_lds
 }

@@ -128,7 +128,8 @@ __global__ void __launch_bounds__(256) k_colmask(const __half *__restrict__ X, i
 // weights, rows = tokens); padding rows are written as zeros.
 __global__ void __launch_bounds__(256) k_rowquant_tiled(const __half *__restrict__ X, int M, int K,
                                                         const uint32_t *__restrict__ mask,
-                                                        int8_t *__restrict__ xq_tiled, float *__restrict__ sx,
+                                                        int8_t *__restrict__ xq_tiled,
+                                                        int8_t *__restrict__ xo_tiled, float *__restrict__ sx,
                                                         int8_t *__restrict__ xq_dbg) {
     __shared__ float sm[4];
     const int t = blockIdx.x, KT = K >> 6, nchunk = K >> 4;
@@ -167,8 +168,26 @@ __global__ void __launch_bounds__(256) k_rowquant_tiled(const __half *__restrict
         v4i o;
 #pragma unroll
         for (int i = 0; i < 4; i++) o[i] = pack4(q[4 * i], q[4 * i + 1], q[4 * i + 2], q[4 * i + 3]);
-        *(v4i *)(xq_tiled + ((tile_row + (c >> 2)) * 64 + (c & 3) * 16 + (t & 15)) * 16) = o;
+        const size_t slot = ((tile_row + (c >> 2)) * 64 + (c & 3) * 16 + (t & 15)) * 16;
+        *(v4i *)(xq_tiled + slot) = o;
         if (xq_dbg) *(v4i *)(xq_dbg + (size_t)t * K + c * 16) = o;
+        if (xo_tiled && bits) {   // the group's first 8 outlier values, ascending column order
+            v8h ov;
+            uint32_t rest = bits;
+#pragma unroll
+            for (int r = 0; r < 8; r++) {
+                const int j = rest ? __ffs(rest) - 1 : 0;
+                _Float16 v = (_Float16)0.0f;
+#pragma unroll
+                for (int i = 0; i < 8; i++) {
+                    if (j == i) v = a[i];
+                    if (j == i + 8) v = b[i];
+                }
+                ov[r] = rest ? v : (_Float16)0.0f;
+                rest &= rest - 1;
+            }
+            *(v8h *)(xo_tiled + slot) = ov;
+        }
     }
 }
 
@@ -262,9 +281,9 @@ hipError_t ps_colmask(const __half *X, int M, int K, float theta, uint32_t *mask
     k_colmask<<<grid, 256, 0, st>>>(X, M, K, theta, mask);
     return hipGetLastError();
 }
-hipError_t ps_rowquant_tiled(const __half *X, int M, int K, const uint32_t *mask, int8_t *xq_tiled, float *sx,
-                             int8_t *xq_dbg, hipStream_t st) {
-    k_rowquant_tiled<<<(M + 15) / 16 * 16, 256, 0, st>>>(X, M, K, mask, xq_tiled, sx, xq_dbg);
+hipError_t ps_rowquant_tiled(const __half *X, int M, int K, const uint32_t *mask, int8_t *xq_tiled, int8_t *xo_tiled,
+                             float *sx, int8_t *xq_dbg, hipStream_t st) {
+    k_rowquant_tiled<<<(M + 15) / 16 * 16, 256, 0, st>>>(X, M, K, mask, xq_tiled, xo_tiled, sx, xq_dbg);
     return hipGetLastError();
 }
 hipError_t ps_mask_to_bytes(const uint32_t *mask, int K, uint8_t *out, hipStream_t st) {
