@@ -189,8 +189,10 @@ namespace {
 // One linear on M rows resident as fp16 X[M,K]; picks the one-row or the MFMA path.  ln_g/ln_b non-null:
 // X is the input of the LayerNorm that precedes the linear (fused on the one-row path, a kernel of its own
 // writing ws.a otherwise).  debug: copy the integer intermediates out (one-row path: into ws.xq/mask/ws.sx).
+// mask_ready (multi-row calls without LayerNorm): the kernel that wrote X has already flagged the outlier
+// columns in mask; with a LayerNorm the mask must arrive cleared and the LayerNorm kernel flags them.
 int run_linear(petals_span *sp, int which, const LinearW &w, const __half *X, const __half *ln_g, const __half *ln_b, int M,
-               uint32_t *mask, const OutDesc &o, int8_t *xq_dbg, bool debug, hipStream_t st) {
+               uint32_t *mask, bool mask_ready, const OutDesc &o, int8_t *xq_dbg, bool debug, hipStream_t st) {
     Workspace &ws = sp->ws;
     const petals_span_config &c = sp->cfg;
     const float theta = c.outlier_threshold;
@@ -201,12 +203,13 @@ int run_linear(petals_span *sp, int which, const LinearW &w, const __half *X, co
         HIP_TRY(ps_gemv_row(w, X, ln_g, ln_b, c.ln_eps, theta, dbg, o, ws.table, st));
         sp->prof.end(pr, st);
     } else {
+        if (!mask_ready) HIP_TRY(ps_fill_u32(mask, ws.mask_words, 0u, st));
         if (ln_g) {
-            HIP_TRY(ps_layernorm(X, ln_g, ln_b, c.ln_eps, M, c.hidden, ws.a, st));
+            HIP_TRY(ps_layernorm(X, ln_g, ln_b, c.ln_eps, M, c.hidden, ws.a, mask, theta, st));
             X = ws.a;
+        } else if (!mask_ready) {
+            HIP_TRY(ps_colmask(X, M, w.K, theta, mask, st));
         }
-        HIP_TRY(ps_fill_u32(mask, ws.mask_words, 0u, st));
-        HIP_TRY(ps_colmask(X, M, w.K, theta, mask, st));
         HIP_TRY(ps_rowquant_tiled(X, M, w.K, mask, ws.xq, M <= 64 ? ws.xo : nullptr, ws.sx, xq_dbg, st));
         const OutlierSet os = {ws.ocount, ws.wd64, ws.x64};
         if (M > 64) HIP_TRY(ps_outlier_prep(w, mask, X, M, ws.ocount, ws.wd64, ws.x64, st));
@@ -420,6 +423,12 @@ int petals_span_prefill(petals_span *sp, petals_session *const *sessions, int32_
     Workspace &ws = sp->ws;
     const int M = B * T, H = c.hidden, F = c.ffn, nh = c.n_heads, d = H / nh;
     HIP_TRY(ps_set_table(tab, ws.table, st));
+    // Multi-row calls: the outlier-column masks of all linears are cleared once; the kernel that writes a
+    // linear's input (LayerNorm, attention, the GeLU epilogue) flags the columns.  One-row calls detect
+    // the outliers inside the fused kernel.
+    const bool multi = M > 1;
+    const float theta = c.outlier_threshold;
+    if (multi) HIP_TRY(ps_fill_u32(ws.masks, (size_t)c.n_blocks * 4 * ws.mask_words, 0u, st));
     const __half *x = (const __half *)hidden_in;
     for (int b = 0; b < c.n_blocks; b++) {
         const BlockW &W = sp->blocks[b];
@@ -428,19 +437,22 @@ int petals_span_prefill(petals_span *sp, petals_session *const *sessions, int32_
         OutDesc oq = plain_out(ws.q, PETALS_EPILOGUE_NONE, nullptr);
         oq.scatter = 1; oq.T = T; oq.nh = nh; oq.d = d; oq.blk = b;
         // LayerNorm 1 -> fused QKV (queries to ws.q, keys/values appended to the caches)
-        if (int rc = run_linear(sp, 0, W.lin[0], x, W.ln1g, W.ln1b, M, mk, oq, nullptr, false, st)) return rc;
+        if (int rc = run_linear(sp, 0, W.lin[0], x, W.ln1g, W.ln1b, M, mk, multi, oq, nullptr, false, st)) return rc;
         {
             const bool pr = sp->prof.begin(PETALS_PROFILE_ATTENTION, -1, st);
-            HIP_TRY(ps_attention(ws.q, ws.table, b, M, T, nh, d, max_keys, ws.partials, ws.ctx, st));
+            HIP_TRY(ps_attention(ws.q, ws.table, b, M, T, nh, d, max_keys, ws.partials, ws.ctx,
+                                 multi ? mk + ws.mask_words : nullptr, theta, st));
             sp->prof.end(pr, st);
         }
         // dense + residual
-        if (int rc = run_linear(sp, 1, W.lin[1], ws.ctx, nullptr, nullptr, M, mk + ws.mask_words,
+        if (int rc = run_linear(sp, 1, W.lin[1], ws.ctx, nullptr, nullptr, M, mk + ws.mask_words, multi,
                                 plain_out(ws.x1, PETALS_EPILOGUE_RESIDUAL, x), nullptr, false, st)) return rc;
         // LayerNorm 2 -> up + GeLU -> down + residual
-        if (int rc = run_linear(sp, 2, W.lin[2], ws.x1, W.ln2g, W.ln2b, M, mk + 2 * ws.mask_words,
-                                plain_out(ws.g, PETALS_EPILOGUE_GELU, nullptr), nullptr, false, st)) return rc;
-        if (int rc = run_linear(sp, 3, W.lin[3], ws.g, nullptr, nullptr, M, mk + 3 * ws.mask_words,
+        OutDesc ou = plain_out(ws.g, PETALS_EPILOGUE_GELU, nullptr);
+        if (multi) { ou.next_mask = mk + 3 * ws.mask_words; ou.next_theta = theta; }
+        if (int rc = run_linear(sp, 2, W.lin[2], ws.x1, W.ln2g, W.ln2b, M, mk + 2 * ws.mask_words, multi, ou, nullptr,
+                                false, st)) return rc;
+        if (int rc = run_linear(sp, 3, W.lin[3], ws.g, nullptr, nullptr, M, mk + 3 * ws.mask_words, multi,
                                 plain_out(xout, PETALS_EPILOGUE_RESIDUAL, ws.x1), nullptr, false, st)) return rc;
         x = xout;
     }
@@ -490,7 +502,7 @@ int petals_debug_linear(petals_span *sp, int32_t block, int32_t which, const voi
     OutDesc o = plain_out(yy, epilogue, (const __half *)resid);
     o.acc_out = acc;
     uint32_t *mk = ws.masks;
-    if (int rc = run_linear(sp, which, L, (const __half *)x, nullptr, nullptr, M, mk, o, xq, true, st)) return rc;
+    if (int rc = run_linear(sp, which, L, (const __half *)x, nullptr, nullptr, M, mk, false, o, xq, true, st)) return rc;
     if (sx) HIP_TRY(ps_copy_bytes(ws.sx, sx, (size_t)M * 4, st));
     if (outlier_mask) HIP_TRY(ps_mask_to_bytes(mk, L.K, outlier_mask, st));
     return PETALS_OK;
@@ -514,7 +526,7 @@ int petals_debug_layernorm(petals_span *sp, int32_t block, int32_t which, const 
                             ws.table, st));
     } else {
         HIP_TRY(ps_layernorm((const __half *)x, which ? W.ln2g : W.ln1g, which ? W.ln2b : W.ln1b, c.ln_eps, M, c.hidden,
-                             (__half *)y, st));
+                             (__half *)y, nullptr, 0.0f, st));
     }
     return PETALS_OK;
 }

@@ -28,7 +28,8 @@ __global__ void k_set_table(SessTable t, SessTable *dst) {
 //   rounded one (a different summation order moves the fp64 sum by ~1e-16 relative).
 template <int D>
 __global__ void __launch_bounds__(64) k_attn_prefill(const __half *__restrict__ q, const SessTable *__restrict__ sess,
-                                                     int blk, int T, int nh, __half *__restrict__ ctx) {
+                                                     int blk, int T, int nh, __half *__restrict__ ctx,
+                                                     uint32_t *__restrict__ mask, float theta) {
     constexpr int DS = D / 4, NB = D / 16;           // dims per lane group; output blocks of 16 dims
     const int qt = blockIdx.x, h = blockIdx.y, s = blockIdx.z;
     const int lane = threadIdx.x, c = lane & 15, g = lane >> 4;
@@ -108,7 +109,10 @@ __global__ void __launch_bounds__(64) k_attn_prefill(const __half *__restrict__ 
 #pragma unroll
             for (int b = 0; b < NB; b++) out[b] = d2h_rn(O[b][r] / l_run);
 #pragma unroll
-            for (int b = 0; b < NB; b++) dst[(4 * r + g) * NB + b] = out[b];
+            for (int b = 0; b < NB; b++) {
+                dst[(4 * r + g) * NB + b] = out[b];
+                flag_outlier(mask, theta, h * D + (4 * r + g) * NB + b, out[b]);
+            }
         }
     }
 }
@@ -133,7 +137,8 @@ __device__ __forceinline__ void merge_state(double &m, double &l, double *o, dou
 template <int D>
 __global__ void __launch_bounds__(256) k_attn_decode(const __half *__restrict__ q, const SessTable *__restrict__ sess,
                                                      int blk, int nh, int CH, int nsplit,
-                                                     double *__restrict__ partials, __half *__restrict__ ctx) {
+                                                     double *__restrict__ partials, __half *__restrict__ ctx,
+                                                     uint32_t *__restrict__ mask, float theta) {
     constexpr int LPK = D / 8, KPI = 64 / LPK, NIT = LPK;
     __shared__ double red_m[4], red_l[4], red_o[4][D];
     const int c = blockIdx.x, h = blockIdx.y, s = blockIdx.z;
@@ -223,7 +228,9 @@ __global__ void __launch_bounds__(256) k_attn_decode(const __half *__restrict__ 
             merge_state(m, l, &ov, red_m[w2], red_l[w2], &o2, 1);
         }
         if (nsplit == 1) {
-            ctx[(size_t)s * H + h * D + threadIdx.x] = d2h_rn(ov / l);
+            const __half hv = d2h_rn(ov / l);
+            ctx[(size_t)s * H + h * D + threadIdx.x] = hv;
+            flag_outlier(mask, theta, h * D + threadIdx.x, hv);
         } else {
             double *pp = partials + ((size_t)(s * nh + h) * nsplit + c) * (D + 2);
             if (threadIdx.x == 0) { pp[0] = m; pp[1] = l; }
@@ -235,7 +242,8 @@ __global__ void __launch_bounds__(256) k_attn_decode(const __half *__restrict__ 
 // merges the per-range partial results of one (row, head) in a fixed order
 template <int D>
 __global__ void k_attn_combine(const SessTable *__restrict__ sess, int T, int nh, int CH, int nsplit,
-                               const double *__restrict__ partials, __half *__restrict__ ctx) {
+                               const double *__restrict__ partials, __half *__restrict__ ctx,
+                               uint32_t *__restrict__ mask, float theta) {
     const int h = blockIdx.x, t = blockIdx.y;
     const int s = t / T, i = sess->len[s] + (t - s * T);
     const int nvalid = min(nsplit, (i + 1 + CH - 1) / CH);
@@ -248,12 +256,14 @@ __global__ void k_attn_combine(const SessTable *__restrict__ sess, int T, int nh
         l += wgt * pp[c * (D + 2) + 1];
         o += wgt * pp[c * (D + 2) + 2 + threadIdx.x];
     }
-    ctx[(size_t)t * nh * D + h * D + threadIdx.x] = d2h_rn(o / l);
+    const __half hv = d2h_rn(o / l);
+    ctx[(size_t)t * nh * D + h * D + threadIdx.x] = hv;
+    flag_outlier(mask, theta, h * D + threadIdx.x, hv);
 }
 
 template <int D>
 hipError_t attn_launch(const __half *q, const SessTable *sess, int blk, int M, int T, int nh, int max_keys,
-                       double *partials, __half *ctx, hipStream_t st) {
+                       double *partials, __half *ctx, uint32_t *mask, float theta, hipStream_t st) {
     // split the key range only when rows*heads alone cannot fill the GPU
     int nsplit = (max_keys + 255) / 256;
     nsplit = min(nsplit, PS_ATTN_MAX_SPLITS);
@@ -262,13 +272,13 @@ hipError_t attn_launch(const __half *q, const SessTable *sess, int blk, int M, i
     int CH = ((max_keys + nsplit - 1) / nsplit + 255) / 256 * 256;
     if (nsplit == 1) CH = 1 << 30;
     if (T > 1) {
-        k_attn_prefill<D><<<dim3((T + 15) / 16, nh, M / T), 64, 0, st>>>(q, sess, blk, T, nh, ctx);
+        k_attn_prefill<D><<<dim3((T + 15) / 16, nh, M / T), 64, 0, st>>>(q, sess, blk, T, nh, ctx, mask, theta);
         return hipGetLastError();
     }
-    k_attn_decode<D><<<dim3(nsplit, nh, M), 256, 0, st>>>(q, sess, blk, nh, CH, nsplit, partials, ctx);
+    k_attn_decode<D><<<dim3(nsplit, nh, M), 256, 0, st>>>(q, sess, blk, nh, CH, nsplit, partials, ctx, mask, theta);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || nsplit == 1) return e;
-    k_attn_combine<D><<<dim3(nh, M), D, 0, st>>>(sess, T, nh, CH, nsplit, partials, ctx);
+    k_attn_combine<D><<<dim3(nh, M), D, 0, st>>>(sess, T, nh, CH, nsplit, partials, ctx, mask, theta);
     return hipGetLastError();
 }
 
@@ -280,12 +290,12 @@ hipError_t ps_set_table(const SessTable &host_table, SessTable *dev_table, hipSt
 }
 
 hipError_t ps_attention(const __half *q, const SessTable *sess, int blk, int M, int T, int nh, int d, int max_keys,
-                        double *partials, __half *ctx, hipStream_t st) {
+                        double *partials, __half *ctx, uint32_t *mask, float theta, hipStream_t st) {
     switch (d) {
-        case 16: return attn_launch<16>(q, sess, blk, M, T, nh, max_keys, partials, ctx, st);
-        case 32: return attn_launch<32>(q, sess, blk, M, T, nh, max_keys, partials, ctx, st);
-        case 64: return attn_launch<64>(q, sess, blk, M, T, nh, max_keys, partials, ctx, st);
-        case 128: return attn_launch<128>(q, sess, blk, M, T, nh, max_keys, partials, ctx, st);
+        case 16: return attn_launch<16>(q, sess, blk, M, T, nh, max_keys, partials, ctx, mask, theta, st);
+        case 32: return attn_launch<32>(q, sess, blk, M, T, nh, max_keys, partials, ctx, mask, theta, st);
+        case 64: return attn_launch<64>(q, sess, blk, M, T, nh, max_keys, partials, ctx, mask, theta, st);
+        case 128: return attn_launch<128>(q, sess, blk, M, T, nh, max_keys, partials, ctx, mask, theta, st);
     }
     return hipErrorInvalidValue;
 }

@@ -47,6 +47,8 @@ struct OutDesc {
     const __half *resid;  // [M,N]
     int32_t *acc_out;     // optional int32 [M,N] copy of the integer accumulators
     int T, nh, d, blk;    // scatter: row t belongs to session t / T at position len + t % T of block blk
+    uint32_t *next_mask;  // optional (scatter == 0): outlier-column bit mask [N/32] of the linear that reads y
+    float next_theta;     // a column of y is flagged when any |y| >= next_theta
 };
 
 struct CodeTable { float code[256]; };
@@ -69,8 +71,9 @@ hipError_t ps_quantize_weight(const float *W, int N, int K, int8_t *wt, float *s
 hipError_t ps_untile_weight(const int8_t *wt, int N, int K, int8_t *wq_rowmajor, hipStream_t st);
 hipError_t ps_fill_u32(uint32_t *p, size_t n, uint32_t v, hipStream_t st);
 hipError_t ps_copy_bytes(const void *src, void *dst, size_t n, hipStream_t st);
+// mask (may be null): outlier-column bits of y are ORed into it (|y| >= theta)
 hipError_t ps_layernorm(const __half *x, const __half *g, const __half *b, float eps, int M, int H,
-                        __half *y, hipStream_t st);
+                        __half *y, uint32_t *mask, float theta, hipStream_t st);
 hipError_t ps_colmask(const __half *X, int M, int K, float theta, uint32_t *mask, hipStream_t st);
 // M rows -> tiled int8 codes (rows padded to 16 with zeros), row scales; mask given
 // xo_tiled (may be null): same tile order, 16 bytes per (token, 16-column group) = the fp16 values of the
@@ -113,8 +116,9 @@ hipError_t ps_gemm(const LinearW &w, const int8_t *xq_tiled, const int8_t *xo_ti
 hipError_t ps_set_table(const SessTable &host_table, SessTable *dev_table, hipStream_t st);
 #define PS_ATTN_MAX_SPLITS 16
 #define PS_ATTN_PARTIAL_SLOTS 8192   // (row, head, split) triples that may need a partial result
+// mask (may be null): outlier-column bits of ctx are ORed into it (|ctx| >= theta)
 hipError_t ps_attention(const __half *q, const SessTable *sess, int blk, int M, int T, int nh, int d, int max_keys,
-                        double *partials, __half *ctx, hipStream_t st);
+                        double *partials, __half *ctx, uint32_t *mask, float theta, hipStream_t st);
 
 hipError_t ps_hidden_quantize(const __half *x, size_t n, int block, const CodeTable &tab, uint8_t *q, float *absmax,
                               hipStream_t st);
@@ -124,6 +128,15 @@ hipError_t ps_kv_export(const __half *kv, int nh, int cap, int d, int len, __hal
 hipError_t ps_kv_import(__half *kv, int nh, int cap, int d, int len, const __half *in, hipStream_t st);
 
 // --- small device helpers ---------------------------------------------------------
+// Producer side of the outlier-column detection: ORs the bits of flagged columns into mask.
+// Bits are only ever set between two clears, so a stale read of the word can at worst cause a
+// redundant atomic.
+__device__ __forceinline__ void flag_outlier_bits(uint32_t *mask, int word, uint32_t bits) {
+    if (bits && (mask[word] & bits) != bits) atomicOr(&mask[word], bits);
+}
+__device__ __forceinline__ void flag_outlier(uint32_t *mask, float theta, int k, __half v) {
+    if (mask && fabsf(__half2float(v)) >= theta) flag_outlier_bits(mask, k >> 5, 1u << (k & 31));
+}
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));

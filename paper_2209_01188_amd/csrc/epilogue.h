@@ -14,6 +14,7 @@ __device__ __forceinline__ void emit_output(const OutDesc &o, const SessTable *_
     if (o.acc_out) o.acc_out[(size_t)t * N + n] = acc;
     if (!o.scatter) {
         o.y[(size_t)t * N + n] = hv;
+        flag_outlier(o.next_mask, o.next_theta, n, hv);
     } else {
         // fused QKV: output row n = h*3d + p*d + j ; queries to y[M,H], keys/values appended to the caches
         const int d = o.d, h = n / (3 * d), rem = n - h * 3 * d, p = rem / d, j = rem - p * d;
@@ -50,6 +51,13 @@ __device__ __forceinline__ void emit_output4(const OutDesc &o, const SessTable *
     __half *dst;
     if (!o.scatter) {
         dst = o.y + (size_t)t * N + n0;
+        if (o.next_mask) {
+            uint32_t bits = 0;
+#pragma unroll
+            for (int r = 0; r < 4; r++)
+                if (fabsf(__half2float(out[r])) >= o.next_theta) bits |= 1u << ((n0 + r) & 31);
+            flag_outlier_bits(o.next_mask, n0 >> 5, bits);
+        }
     } else {
         const int d = o.d, h = n0 / (3 * d), rem = n0 - h * 3 * d, p = rem / d, j = rem - p * d;
         if (p == 0) {

@@ -272,9 +272,24 @@ hipError_t ps_outlier_prep(const LinearW &w, const uint32_t *mask, const __half 
 
 hipError_t ps_gemm(const LinearW &w, const int8_t *xq_tiled, const int8_t *xo_tiled, const uint32_t *mask,
                    const __half *X, const float *sx, int M, const OutDesc &o, const SessTable *sess, hipStream_t st) {
-    if (w.N % 64) return hipErrorInvalidValue;
-    if (M <= 16) return launch<4, 1, 2>(w, xq_tiled, xo_tiled, mask, X, sx, M, o, sess, st);
-    if (M <= 32) return launch<4, 2, 1>(w, xq_tiled, xo_tiled, mask, X, sx, M, o, sess, st);
-    if (M <= 64) return launch<2, 4, 1>(w, xq_tiled, xo_tiled, mask, X, sx, M, o, sess, st);
+    // panels per workgroup: as many as still leave about one workgroup per compute unit
+    const int panels = w.N / 16;
+    const int wn = (panels % 4 == 0 && panels / 4 >= 224) ? 4 : (panels % 2 == 0 && panels / 2 >= 224) ? 2 : 1;
+#define PS_GEMM_CASE(WN_, MT_, UK_) return launch<WN_, MT_, UK_>(w, xq_tiled, xo_tiled, mask, X, sx, M, o, sess, st)
+    if (M <= 16) {
+        if (wn == 4) PS_GEMM_CASE(4, 1, 2);
+        if (wn == 2) PS_GEMM_CASE(2, 1, 2);
+        PS_GEMM_CASE(1, 1, 4);
+    }
+    if (M <= 32) {
+        if (wn == 4) PS_GEMM_CASE(4, 2, 1);
+        if (wn == 2) PS_GEMM_CASE(2, 2, 2);
+        PS_GEMM_CASE(1, 2, 2);
+    }
+    if (M <= 64) {
+        if (wn >= 2) PS_GEMM_CASE(2, 4, 1);
+        PS_GEMM_CASE(1, 4, 1);
+    }
+#undef PS_GEMM_CASE
     return hipErrorInvalidValue;   // larger calls belong to ps_gemm_lds
 }

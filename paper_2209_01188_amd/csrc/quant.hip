@@ -93,15 +93,22 @@ __device__ __forceinline__ __half2 ln_affine(__half2 x, __half2 g, __half2 b, do
 template <int NT>
 __global__ void __launch_bounds__(NT) k_layernorm(const __half *__restrict__ x, const __half *__restrict__ g,
                                                   const __half *__restrict__ b, float eps, int H,
-                                                  __half *__restrict__ y) {
+                                                  __half *__restrict__ y, uint32_t *__restrict__ mask,
+                                                  float theta) {
     __shared__ double sm[NT / 64];
     const __half *xr = x + (size_t)blockIdx.x * H;
     __half *yr = y + (size_t)blockIdx.x * H;
     double mean, inv;
     row_moments<NT>(xr, H, sm, mean, inv, (double)eps);
-    for (int k = threadIdx.x * 2; k < H; k += NT * 2)
-        *(__half2 *)(yr + k) = ln_affine(*(const __half2 *)(xr + k), *(const __half2 *)(g + k),
-                                         *(const __half2 *)(b + k), mean, inv);
+    for (int k = threadIdx.x * 2; k < H; k += NT * 2) {
+        const __half2 o = ln_affine(*(const __half2 *)(xr + k), *(const __half2 *)(g + k),
+                                    *(const __half2 *)(b + k), mean, inv);
+        *(__half2 *)(yr + k) = o;
+        if (mask) {
+            const uint32_t bits = (fabsf(__half2float(o.x)) >= theta ? 1u : 0u) | (fabsf(__half2float(o.y)) >= theta ? 2u : 0u);
+            flag_outlier_bits(mask, k >> 5, bits << (k & 31));
+        }
+    }
 }
 
 // -------------------------------------------------- many rows: mask, then quantize
@@ -191,6 +198,88 @@ __global__ void __launch_bounds__(256) k_rowquant_tiled(const __half *__restrict
     }
 }
 
+// The same for calls of few rows, where one row per workgroup leaves most of the chip idle and the
+// latency of the loads is the whole cost: 1024 threads, each keeps its (at most 4) chunks of 16
+// columns in registers between the absolute-maximum pass and the quantization.
+__global__ void __launch_bounds__(1024) k_rowquant_tiled_few(const __half *__restrict__ X, int M, int K,
+                                                             const uint32_t *__restrict__ mask,
+                                                             int8_t *__restrict__ xq_tiled,
+                                                             int8_t *__restrict__ xo_tiled, float *__restrict__ sx,
+                                                             int8_t *__restrict__ xq_dbg) {
+    __shared__ float sm[16];
+    const int t = blockIdx.x, KT = K >> 6, nchunk = K >> 4;
+    const uint16_t *mask16 = (const uint16_t *)mask;
+    const size_t tile_row = (size_t)(t >> 4) * KT;
+    if (t >= M) {
+        for (int c = threadIdx.x; c < nchunk; c += 1024) {
+            v4i z = {0, 0, 0, 0};
+            *(v4i *)(xq_tiled + ((tile_row + (c >> 2)) * 64 + (c & 3) * 16 + (t & 15)) * 16) = z;
+        }
+        return;
+    }
+    const __half *xr = X + (size_t)t * K;
+    v8h a[4], b[4];
+    uint32_t bits[4];
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        const int c = threadIdx.x + i * 1024;
+        if (c < nchunk) {
+            a[i] = *(const v8h *)(xr + c * 16);
+            b[i] = *(const v8h *)(xr + c * 16 + 8);
+            bits[i] = mask16[c];
+        }
+    }
+    float m = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        if (threadIdx.x + i * 1024 < nchunk) {
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                if (!((bits[i] >> j) & 1u)) m = fmaxf(m, fabsf((float)a[i][j]));
+                if (!((bits[i] >> (j + 8)) & 1u)) m = fmaxf(m, fabsf((float)b[i][j]));
+            }
+        }
+    }
+    const float s = block_max<16>(m, sm);
+    if (threadIdx.x == 0) sx[t] = s;
+    const float r = s > 0.0f ? 127.0f / s : 0.0f;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        const int c = threadIdx.x + i * 1024;
+        if (c < nchunk) {
+            int q[16];
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                q[j] = ((bits[i] >> j) & 1u) ? 0 : q8((float)a[i][j], r);
+                q[j + 8] = ((bits[i] >> (j + 8)) & 1u) ? 0 : q8((float)b[i][j], r);
+            }
+            v4i o;
+#pragma unroll
+            for (int k = 0; k < 4; k++) o[k] = pack4(q[4 * k], q[4 * k + 1], q[4 * k + 2], q[4 * k + 3]);
+            const size_t slot = ((tile_row + (c >> 2)) * 64 + (c & 3) * 16 + (t & 15)) * 16;
+            *(v4i *)(xq_tiled + slot) = o;
+            if (xq_dbg) *(v4i *)(xq_dbg + (size_t)t * K + c * 16) = o;
+            if (xo_tiled && bits[i]) {   // the group's first 8 outlier values, ascending column order
+                v8h ov;
+                uint32_t rest = bits[i];
+#pragma unroll
+                for (int rr = 0; rr < 8; rr++) {
+                    const int j = rest ? __ffs(rest) - 1 : 0;
+                    _Float16 v = (_Float16)0.0f;
+#pragma unroll
+                    for (int k = 0; k < 8; k++) {
+                        if (j == k) v = a[i][k];
+                        if (j == k + 8) v = b[i][k];
+                    }
+                    ov[rr] = rest ? v : (_Float16)0.0f;
+                    rest &= rest - 1;
+                }
+                *(v8h *)(xo_tiled + slot) = ov;
+            }
+        }
+    }
+}
+
 __global__ void k_mask_to_bytes(const uint32_t *__restrict__ mask, int K, uint8_t *__restrict__ out) {
     int k = blockIdx.x * blockDim.x + threadIdx.x;
     if (k < K) out[k] = (mask[k >> 5] >> (k & 31)) & 1u;
@@ -270,10 +359,10 @@ hipError_t ps_copy_bytes(const void *src, void *dst, size_t n, hipStream_t st) {
     return hipGetLastError();
 }
 hipError_t ps_layernorm(const __half *x, const __half *g, const __half *b, float eps, int M, int H, __half *y,
-                        hipStream_t st) {
+                        uint32_t *mask, float theta, hipStream_t st) {
     // few rows: more threads per row (latency), many rows: more rows in flight
-    if (M <= 256 && H >= 4096) k_layernorm<1024><<<M, 1024, 0, st>>>(x, g, b, eps, H, y);
-    else k_layernorm<256><<<M, 256, 0, st>>>(x, g, b, eps, H, y);
+    if (M <= 256 && H >= 4096) k_layernorm<1024><<<M, 1024, 0, st>>>(x, g, b, eps, H, y, mask, theta);
+    else k_layernorm<256><<<M, 256, 0, st>>>(x, g, b, eps, H, y, mask, theta);
     return hipGetLastError();
 }
 hipError_t ps_colmask(const __half *X, int M, int K, float theta, uint32_t *mask, hipStream_t st) {
@@ -283,7 +372,10 @@ hipError_t ps_colmask(const __half *X, int M, int K, float theta, uint32_t *mask
 }
 hipError_t ps_rowquant_tiled(const __half *X, int M, int K, const uint32_t *mask, int8_t *xq_tiled, int8_t *xo_tiled,
                              float *sx, int8_t *xq_dbg, hipStream_t st) {
-    k_rowquant_tiled<<<(M + 15) / 16 * 16, 256, 0, st>>>(X, M, K, mask, xq_tiled, xo_tiled, sx, xq_dbg);
+    if (M <= 64 && K >= 4096 && K <= 65536)
+        k_rowquant_tiled_few<<<(M + 15) / 16 * 16, 1024, 0, st>>>(X, M, K, mask, xq_tiled, xo_tiled, sx, xq_dbg);
+    else
+        k_rowquant_tiled<<<(M + 15) / 16 * 16, 256, 0, st>>>(X, M, K, mask, xq_tiled, xo_tiled, sx, xq_dbg);
     return hipGetLastError();
 }
 hipError_t ps_mask_to_bytes(const uint32_t *mask, int K, uint8_t *out, hipStream_t st) {
