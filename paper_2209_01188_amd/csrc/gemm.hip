@@ -194,70 +194,60 @@ k_gemm(LinearW w, const int8_t *__restrict__ xq_tiled, const int8_t *__restrict_
         c = c2;
     }
 
-    // tree over the waves, PP panels at a time: the upper half of the live waves writes, the lower
-    // half adds (integers in any order; the fp64 terms are exact products of fp16 values)
-    constexpr int PP = (4 / MT > WN) ? WN : (4 / MT > 0 ? 4 / MT : 1);
+    // The waves' partial sums meet in LDS, up to four (panel, token tile) pairs at a time; one wave per
+    // pair adds them in wave order (the fp64 terms are exact products of fp16 values) and finishes it.
+    constexpr int G = WN * MT, NPP = G < 4 ? G : 4;
     extern __shared__ __align__(16) unsigned char lds[];
-    v4i *ri = (v4i *)lds;                                                  // [WVK/2][PP*MT][64]
-    v4d *rf = (v4d *)(lds + (size_t)(WVK / 2) * PP * MT * 64 * 16);        // [WVK/2][PP*MT][64]
+    v4i *ri = (v4i *)lds;                                             // [WVK][NPP][64]
+    v4d *rf = (v4d *)(lds + (size_t)WVK * NPP * 64 * 16);             // [WVK][NPP][64]
 #pragma unroll
-    for (int p0 = 0; p0 < WN; p0 += PP) {
+    for (int g0 = 0; g0 < G; g0 += NPP) {
+        if (g0) __syncthreads();
 #pragma unroll
-        for (int half = WVK / 2; half >= 1; half >>= 1) {
-            if (wk >= half && wk < 2 * half) {
-#pragma unroll
-                for (int pp = 0; pp < PP; pp++)
-#pragma unroll
-                    for (int j = 0; j < MT; j++) {
-                        ri[((wk - half) * PP * MT + pp * MT + j) * 64 + lane] = acc[p0 + pp][j];
-                        rf[((wk - half) * PP * MT + pp * MT + j) * 64 + lane] = od[p0 + pp][j];
-                    }
-            }
-            __syncthreads();
-            if (wk < half) {
-#pragma unroll
-                for (int pp = 0; pp < PP; pp++)
-#pragma unroll
-                    for (int j = 0; j < MT; j++) {
-                        acc[p0 + pp][j] += ri[(wk * PP * MT + pp * MT + j) * 64 + lane];
-                        od[p0 + pp][j] += rf[(wk * PP * MT + pp * MT + j) * 64 + lane];
-                    }
-            }
-            __syncthreads();
+        for (int i = 0; i < NPP; i++) {
+            ri[(wk * NPP + i) * 64 + lane] = acc[(g0 + i) / MT][(g0 + i) % MT];
+            rf[(wk * NPP + i) * 64 + lane] = od[(g0 + i) / MT][(g0 + i) % MT];
         }
+        __syncthreads();
+        if (wk >= NPP) continue;
+        const int p = (g0 + wk) / MT, j = (g0 + wk) % MT;
+        if (j >= MTT) continue;                                         // wave-uniform
+        v4i a = ri[wk * 64 + lane];
+        v4d f = rf[wk * 64 + lane];
+        for (int s = 1; s < WVK; s++) {
+            a += ri[(s * NPP + wk) * 64 + lane];
+            f += rf[(s * NPP + wk) * 64 + lane];
+        }
+        // the fp64 instruction returns row 4r + g in register r of lane group g, the int8 one row 4g + r:
+        // transpose the 4 x 4 (group, register) block among the four lanes that share a token
+        v4d ft;
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            double v = 0.0;
+#pragma unroll
+            for (int q = 0; q < 4; q++) {
+                const double t = __shfl(f[q], row + 16 * r);
+                if (q == kg) v = t;
+            }
+            ft[r] = v;
+        }
+        const int t = j * 16 + row;
+        if (t < M) emit_output4(o, sess, N, t, (nt0 + p) * 16 + 4 * kg, a, ft, sx[t] / 127.0f, w.sw, w.bias);
     }
-    if (wk != 0) return;
-#pragma unroll
-    for (int p = 0; p < WN; p++)
-#pragma unroll
-        for (int j = 0; j < MT; j++) {
-            if (j >= MTT) continue;                                     // wave-uniform
-            const v4d f = od[p][j];
-            // the fp64 instruction returns row 4r + g in register r of lane group g, the int8 one row 4g + r:
-            // transpose the 4 x 4 (group, register) block among the four lanes that share a token
-            v4d ft;
-#pragma unroll
-            for (int r = 0; r < 4; r++) {
-                double v = 0.0;
-#pragma unroll
-                for (int q = 0; q < 4; q++) {
-                    const double t = __shfl(f[q], row + 16 * r);
-                    if (q == kg) v = t;
-                }
-                ft[r] = v;
-            }
-            const int t = j * 16 + row;
-            if (t >= M) continue;
-            emit_output4(o, sess, N, t, (nt0 + p) * 16 + 4 * kg, acc[p][j], ft, sx[t] / 127.0f, w.sw, w.bias);
-        }
 }
 
 template <int WN, int MT, int UK>
 hipError_t launch(const LinearW &w, const int8_t *xq_tiled, const int8_t *xo_tiled, const uint32_t *mask,
                   const __half *X, const float *sx, int M, const OutDesc &o, const SessTable *sess, hipStream_t st) {
-    constexpr int WVK = 8;
-    constexpr int PP = (4 / MT > WN) ? WN : (4 / MT > 0 ? 4 / MT : 1);
-    const size_t lds = (size_t)(WVK / 2) * PP * MT * 64 * (16 + 32);   // 48 KB
+    constexpr int WVK = 8, G = WN * MT, NPP = G < 4 ? G : 4;
+    const size_t lds = (size_t)WVK * NPP * 64 * (16 + 32);   // up to 96 KB
+    auto kern = k_gemm<WN, MT, UK, WVK>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
     k_gemm<WN, MT, UK, WVK><<<w.N / (16 * WN), 64 * WVK, lds, st>>>(w, xq_tiled, xo_tiled, mask, X, sx, M, o, sess);
     return hipGetLastError();
 }
