@@ -16,8 +16,17 @@
 
 namespace {
 
+#ifndef PS_WVN
+#define PS_WVN 2
+#define PS_WVM 4
+#define PS_TN 8
+#define PS_TM 4
+#endif
 constexpr int STRIP = 4;       // m-blocks per rasterization strip
-constexpr int NSLOT = 4;       // LDS ring slots
+#ifndef PS_NSLOT
+#define PS_NSLOT 4
+#endif
+constexpr int NSLOT = PS_NSLOT;       // LDS ring slots
 constexpr int PD = NSLOT - 1;  // stages requested ahead
 
 // ---------------------------------------------------------------------------------------------
@@ -113,12 +122,11 @@ struct GemmArgs {
 
 // F16 = false: int8 main product with the full epilogue.  F16 = true: fp16 outlier product into outl.
 template <bool F16, int WVN, int WVM, int TN, int TM>
-__global__ void __launch_bounds__(64 * WVN * WVM)
+__global__ void __launch_bounds__(64 * WVN * WVM, 2)   // two waves per SIMD: at most 256 registers
 k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, float *__restrict__ outl, OutDesc o,
            const SessTable *__restrict__ sess) {
     constexpr int NW = WVN * WVM, BN = WVN * TN, BM = WVM * TM, STAGE = BN + BM, LOADS = STAGE / NW;
     static_assert(STAGE % NW == 0, "every wave copies the same number of tiles per stage");
-    static_assert(TN % 2 == 0, "the epilogue parks half of the accumulators at a time");
     extern __shared__ __align__(16) unsigned char lds[];
     const int n_out = *os.count;
     const bool many = n_out > PS_EXACT_OUTLIERS;
@@ -177,13 +185,22 @@ k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, 
         else if (in_flight_after == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS) : "memory");
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     };
-    static_assert(PD == 3, "wait_own distinguishes at most two stages in flight behind the awaited one");
+    static_assert(PD <= 3 && PD >= 2, "wait_own distinguishes at most two stages in flight behind the awaited one");
     auto frag_load = [&](int s, v4i *fa, v4i *fb) {
         const unsigned char *base = lds + (size_t)(s % NSLOT) * STAGE * 1024 + lane * 16;
 #pragma unroll
-        for (int j = 0; j < TM; j++) fb[j] = *(const v4i *)(base + (size_t)(BN + wm * TM + j) * 1024);
-#pragma unroll
         for (int i = 0; i < TN; i++) fa[i] = *(const v4i *)(base + (size_t)(wn * TN + i) * 1024);
+#ifdef PS_EXP_FEWER_LDS
+#pragma unroll
+        for (int j = 0; j < TM; j++) fb[j] = fa[j];
+#elif defined(PS_EXP_FEWEST_LDS)
+        fa[1] = fa[0]; fa[3] = fa[2]; fa[5] = fa[4]; fa[7] = fa[6];
+#pragma unroll
+        for (int j = 0; j < TM; j++) fb[j] = fa[2 * (j & 1)];
+#else
+#pragma unroll
+        for (int j = 0; j < TM; j++) fb[j] = *(const v4i *)(base + (size_t)(BN + wm * TM + j) * 1024);
+#endif
     };
     for (int s = 0; s < PD && s < NS; s++) dma_stage(s);
 
@@ -225,39 +242,149 @@ k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, 
     asm volatile("" ::: "memory");
 
     // Epilogue.  D[lane][r] = output row 4*(l/16)+r of the weight tile, token l%16 of the token tile.
-    // The accumulators go through LDS (each lane parks and re-reads only its own values, half of the
-    // wave's tiles at a time) so that the tail below is ONE rolled loop instead of TN*TM inlined copies.
-    const int nch = (n_out + 3) >> 2;
-    acc_t *mine = (acc_t *)lds + (size_t)wave * (TN / 2 * TM * 64) + lane;
+    // The accumulators go through LDS (each lane parks and re-reads only its own values, half of
+    // the wave's tiles at a time) so that the tail is a rolled loop over weight panels instead of
+    // TN*TM inlined copies.  What depends only on the output column (weight scale / 127, bias, where a
+    // fused-QKV column goes) is tabulated in LDS once per block; what depends only on the token (row
+    // scale / 127, row addresses) sits in registers: the loop body has no division left.
+    constexpr int QN = TN / 2, NPARK = 2;                                // weight panels per parked half
+    static_assert(TN % 2 == 0, "the epilogue parks half of the accumulators at a time");
+    acc_t *mine = (acc_t *)lds + (size_t)wave * (QN * TM * 64) + lane;
+    if constexpr (F16) {
 #pragma unroll
-    for (int p = 0; p < 2; p++) {
+        for (int p = 0; p < NPARK; p++) {
 #pragma unroll
-        for (int i = 0; i < TN / 2; i++)
+            for (int i = 0; i < QN; i++)
 #pragma unroll
-            for (int j = 0; j < TM; j++) mine[(i * TM + j) * 64] = acc[p * (TN / 2) + i][j];
+                for (int j = 0; j < TM; j++) mine[(i * TM + j) * 64] = acc[p * QN + i][j];
 #pragma unroll 1
-        for (int idx = 0; idx < TN / 2 * TM; idx++) {
-            const int nt = nt0 + wn * TN + p * (TN / 2) + idx / TM, mt = mt0 + wm * TM + idx % TM;
-            if (nt >= NT || mt >= MTT) continue;                        // wave-uniform
-            const acc_t a4 = mine[idx * 64];
-            const int t = mt * 16 + row, n0 = nt * 16 + 4 * kg;
-            if constexpr (F16) {
-                if (t < M) *(v4f *)(outl + (size_t)t * N + n0) = a4;
+            for (int idx = 0; idx < QN * TM; idx++) {
+                const int nt = nt0 + wn * TN + p * QN + idx / TM, mt = mt0 + wm * TM + idx % TM;
+                if (nt >= NT || mt >= MTT) continue;                    // wave-uniform
+                const int t = mt * 16 + row;
+                if (t < M) *(v4f *)(outl + (size_t)t * N + nt * 16 + 4 * kg) = mine[idx * 64];
+            }
+        }
+    } else {
+        constexpr size_t PARK = (size_t)NW * QN * TM * 1024;
+        double *col_swd = (double *)(lds + PARK);                        // [BN * 16] weight scale / 127
+        double *col_bias = col_swd + BN * 16;                            // [BN * 16]
+        int2 *col_sc = (int2 *)(col_bias + BN * 16);                     // [BN * 4] fused-QKV: where 4 columns go
+        for (int i = threadIdx.x; i < BN * 16; i += 64 * NW) {
+            const int n = nt0 * 16 + i;
+            col_swd[i] = n < N ? (double)(w.sw[n] / 127.0f) : 0.0;
+            col_bias[i] = n < N ? (double)__half2float(w.bias[n]) : 0.0;
+        }
+        if (o.scatter) {
+            for (int i = threadIdx.x; i < BN * 4; i += 64 * NW) {
+                // output row n = h*3d + p*d + j: queries to y[M, nh*d], keys/values into the caches
+                const int n0 = nt0 * 16 + 4 * i, d = o.d, h = n0 / (3 * d), rem = n0 - h * 3 * d, p = rem / d, j = rem - p * d;
+                col_sc[i] = p == 0 ? make_int2(-1, h * d + j) : make_int2((o.blk * 2 + (p == 2 ? 1 : 0)) * o.nh + h, j);
+            }
+        }
+        // per token row of this lane (TM token tiles)
+        double sxd[TM];
+        __half *yrow[TM];            // plain: y row; fused QKV: query row
+        __half *kvrow[TM];           // fused QKV: session cache + position * d
+        int capd[TM];
+        const __half *rrow[TM];
+        int trow[TM];
+#pragma unroll
+        for (int j = 0; j < TM; j++) {
+            const int mt = mt0 + wm * TM + j, t = mt * 16 + row;
+            const bool ok = mt < MTT && t < M;
+            trow[j] = ok ? t : -1;
+            const int tc = ok ? t : 0;
+            sxd[j] = (double)(sx[tc] / 127.0f);
+            rrow[j] = o.epilogue == 2 ? o.resid + (size_t)tc * N : nullptr;
+            kvrow[j] = nullptr;
+            capd[j] = 0;
+            if (!o.scatter) {
+                yrow[j] = o.y + (size_t)tc * N;
             } else {
-                v4d od = {0.0, 0.0, 0.0, 0.0};
-                if (many) {
-                    if (t < M) {
-                        const v4f f = *(const v4f *)(outl + (size_t)t * N + n0);
-                        od = (v4d){(double)f[0], (double)f[1], (double)f[2], (double)f[3]};
+                const int sidx = tc / o.T, cap = sess->cap[sidx], pos = sess->len[sidx] + (tc - sidx * o.T);
+                yrow[j] = o.y + (size_t)tc * (o.nh * o.d);
+                kvrow[j] = sess->kv[sidx] + (size_t)pos * o.d;
+                capd[j] = cap * o.d;
+            }
+        }
+        // exact outlier part: the token-side operands of the first XC chunks stay in registers
+        constexpr int XC = 2;
+        const int nch = many ? 0 : (n_out + 3) >> 2;
+        double xw[TM][XC];
+#pragma unroll
+        for (int j = 0; j < TM; j++)
+#pragma unroll
+            for (int c = 0; c < XC; c++)
+                xw[j][c] = c < nch ? os.x64[((size_t)min(mt0 + wm * TM + j, MTT - 1) * PS_OUTLIER_CHUNKS + c) * 64 + lane] : 0.0;
+        __syncthreads();                                                 // tables visible
+
+#pragma unroll
+        for (int p = 0; p < NPARK; p++) {
+#pragma unroll
+            for (int i = 0; i < QN; i++)
+#pragma unroll
+                for (int j = 0; j < TM; j++) mine[(i * TM + j) * 64] = acc[p * QN + i][j];
+#pragma unroll 1
+            for (int i = 0; i < QN; i++) {
+                const int ntl = wn * TN + p * QN + i, nt = nt0 + ntl;
+                if (nt >= NT) continue;                                  // wave-uniform
+                const int n0 = nt * 16 + 4 * kg;
+                const v4d swd4 = *(const v4d *)(col_swd + ntl * 16 + 4 * kg);
+                const v4d bias4 = *(const v4d *)(col_bias + ntl * 16 + 4 * kg);
+                const int2 sc = o.scatter ? col_sc[ntl * 4 + kg] : make_int2(-1, n0);
+                double aw[XC];
+#pragma unroll
+                for (int c = 0; c < XC; c++)
+                    aw[c] = c < nch ? os.wd64[((size_t)nt * PS_OUTLIER_CHUNKS + c) * 64 + lane] : 0.0;
+#pragma unroll
+                for (int j = 0; j < TM; j++) {
+                    const v4i a4 = mine[(i * TM + j) * 64];
+                    const int t = trow[j];
+                    v4d od = {0.0, 0.0, 0.0, 0.0};
+                    if (many) {
+                        if (t >= 0) {
+                            const v4f f = *(const v4f *)(outl + (size_t)t * N + n0);
+                            od = (v4d){(double)f[0], (double)f[1], (double)f[2], (double)f[3]};
+                        }
+                    } else if (nch > 0) {
+#pragma unroll
+                        for (int c = 0; c < XC; c++)
+                            if (c < nch) od = __builtin_amdgcn_mfma_f64_16x16x4f64(aw[c], xw[j][c], od, 0, 0, 0);
+                        if (nch > XC) {
+                            const double *ap = os.wd64 + (size_t)nt * PS_OUTLIER_CHUNKS * 64 + lane;
+                            const double *bp = os.x64 + (size_t)min(mt0 + wm * TM + j, MTT - 1) * PS_OUTLIER_CHUNKS * 64 + lane;
+                            for (int c = XC; c < nch; c++)
+                                od = __builtin_amdgcn_mfma_f64_16x16x4f64(ap[c * 64], bp[c * 64], od, 0, 0, 0);
+                        }
                     }
-                } else if (n_out > 0) {
-                    const double *ap = os.wd64 + (size_t)nt * PS_OUTLIER_CHUNKS * 64 + lane;
-                    const double *bp = os.x64 + (size_t)mt * PS_OUTLIER_CHUNKS * 64 + lane;
-                    for (int c = 0; c < nch; c++)
-                        od = __builtin_amdgcn_mfma_f64_16x16x4f64(ap[c * 64], bp[c * 64], od, 0, 0, 0);
+                    if (t < 0) continue;
+                    v4h r4 = {(_Float16)0, (_Float16)0, (_Float16)0, (_Float16)0};
+                    if (o.epilogue == 2) r4 = *(const v4h *)(rrow[j] + n0);
+                    __half out[4];
+#pragma unroll
+                    for (int r = 0; r < 4; r++) {
+                        double v = (double)a4[r] * sxd[j] * swd4[r] + od[r] + bias4[r];
+                        if (o.epilogue == 1) v = gelu_tanh(v);
+                        else if (o.epilogue == 2) v += (double)(float)r4[r];
+                        out[r] = d2h_rn(v);
+                    }
+                    if (o.acc_out) *(v4i *)(o.acc_out + (size_t)t * N + n0) = a4;
+                    __half *dst;
+                    if (sc.x < 0) {
+                        dst = yrow[j] + sc.y;
+                        if (o.next_mask) {
+                            uint32_t bits = 0;
+#pragma unroll
+                            for (int r = 0; r < 4; r++)
+                                if (fabsf(__half2float(out[r])) >= o.next_theta) bits |= 1u << ((n0 + r) & 31);
+                            flag_outlier_bits(o.next_mask, n0 >> 5, bits);
+                        }
+                    } else {
+                        dst = kvrow[j] + (size_t)sc.x * capd[j] + sc.y;
+                    }
+                    *(v2i *)dst = *(const v2i *)out;
                 }
-                if (t >= M) continue;
-                emit_output4(o, sess, N, t, n0, a4, od, sx[t] / 127.0f, w.sw, w.bias);
             }
         }
     }
@@ -266,13 +393,14 @@ k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, 
 template <bool F16>
 hipError_t launch_lds(const GemmArgs &ga0, const LinearW &w, const float *sx, const OutlierSet &os, float *outl,
                       const OutDesc &o, const SessTable *sess, hipStream_t st) {
-    constexpr int WVN = 2, WVM = 4, TN = 8, TM = 4, BN = WVN * TN, BM = WVM * TM;   // 8 waves, 128 x 64 per wave
+    constexpr int WVN = PS_WVN, WVM = PS_WVM, TN = PS_TN, TM = PS_TM, BN = WVN * TN, BM = WVM * TM;
     GemmArgs ga = ga0;
     const int NT = ga.N / 16, MTT = (ga.M + 15) / 16;
     ga.nb_n = (NT + BN - 1) / BN;
     ga.nb_m = (MTT + BM - 1) / BM;
     const int total = ga.nb_n * ga.nb_m;
-    const size_t lds_stage = (size_t)NSLOT * (BN + BM) * 1024, lds_epi = (size_t)WVN * WVM * (TN / 2) * TM * 1024;
+    const size_t lds_stage = (size_t)NSLOT * (BN + BM) * 1024;
+    const size_t lds_epi = (size_t)WVN * WVM * (TN / 2) * TM * 1024 + (size_t)BN * 16 * 16 + (size_t)BN * 4 * 8;
     const size_t lds = lds_stage > lds_epi ? lds_stage : lds_epi;
     auto kern = k_gemm_lds<F16, WVN, WVM, TN, TM>;
     static bool attr_set = false;
