@@ -213,16 +213,9 @@ k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, 
         asm volatile("" ::: "memory");
         frag_load(0, fa0, fb0);
     }
-    auto step = [&](int s, const v4i *ca, const v4i *cb, v4i *na, v4i *nb) {
-        if (s + 1 < NS) {
-            wait_own(min(NS - s - 2, PD - 2));      // stage s + 1 of this wave (stages up to s + PD - 1 are requested)
-            __builtin_amdgcn_s_barrier();           // everybody's stage s + 1 visible; everybody done reading stage s - 1
-            asm volatile("" ::: "memory");
-            if (s + PD < NS) dma_stage(s + PD);      // into the slot of stage s - 1
-            frag_load(s + 1, na, nb);
-        }
+    auto multiply = [&](const v4i *ca, const v4i *cb, int i0, int i1) {
 #pragma unroll
-        for (int i = 0; i < TN; i++)
+        for (int i = i0; i < i1; i++)
 #pragma unroll
             for (int j = 0; j < TM; j++) {
                 if constexpr (F16)
@@ -230,6 +223,22 @@ k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, 
                 else
                     acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ca[i], cb[j], acc[i][j], 0, 0, 0);
             }
+    };
+    // The fragment reads of stage s + 1 are issued in the middle of the multiplications of stage s, so they
+    // have half a stage to complete before the wait that precedes their first use.  No branch may separate
+    // them from the multiplications: where two paths with different numbers of LDS reads in flight meet, the
+    // compiler waits for all of them.  So the last stage goes through the same motions (its barrier is one
+    // too many, its fragment reads fetch its own stage again).
+    auto step = [&](int s, const v4i *ca, const v4i *cb, v4i *na, v4i *nb) {
+        wait_own(max(0, min(NS - s - 2, PD - 2)));  // stage s + 1 of this wave (stages up to s + PD - 1 are requested)
+        __builtin_amdgcn_s_barrier();               // everybody's stage s + 1 visible; everybody done reading stage s - 1
+        asm volatile("" ::: "memory");
+        if (s + PD < NS) dma_stage(s + PD);          // into the slot of stage s - 1
+        multiply(ca, cb, 0, TN / 2);
+        __builtin_amdgcn_sched_barrier(0);          // keep the reads between the two halves
+        frag_load(min(s + 1, NS - 1), na, nb);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(ca, cb, TN / 2, TN);
     };
     for (int s = 0; s < NS; s += 2) {
         step(s, fa0, fb0, fa1, fb1);
@@ -270,6 +279,8 @@ k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, 
         double *col_swd = (double *)(lds + PARK);                        // [BN * 16] weight scale / 127
         double *col_bias = col_swd + BN * 16;                            // [BN * 16]
         int2 *col_sc = (int2 *)(col_bias + BN * 16);                     // [BN * 4] fused-QKV: where 4 columns go
+        uint32_t *col_flag = (uint32_t *)(col_sc + BN * 4);              // [BN / 2] outlier bits of this block's columns
+        if (threadIdx.x < BN / 2) col_flag[threadIdx.x] = 0u;
         for (int i = threadIdx.x; i < BN * 16; i += 64 * NW) {
             const int n = nt0 * 16 + i;
             col_swd[i] = n < N ? (double)(w.sw[n] / 127.0f) : 0.0;
@@ -373,12 +384,12 @@ k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, 
                     __half *dst;
                     if (sc.x < 0) {
                         dst = yrow[j] + sc.y;
-                        if (o.next_mask) {
+                        if (o.next_mask) {               // collected per block in LDS, sent once below
                             uint32_t bits = 0;
 #pragma unroll
                             for (int r = 0; r < 4; r++)
                                 if (fabsf(__half2float(out[r])) >= o.next_theta) bits |= 1u << ((n0 + r) & 31);
-                            flag_outlier_bits(o.next_mask, n0 >> 5, bits);
+                            if (bits) atomicOr(&col_flag[(ntl * 16 + 4 * kg) >> 5], bits);
                         }
                     } else {
                         dst = kvrow[j] + (size_t)sc.x * capd[j] + sc.y;
@@ -386,6 +397,12 @@ k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, 
                     *(v2i *)dst = *(const v2i *)out;
                 }
             }
+        }
+        if (o.next_mask && !o.scatter) {
+            __syncthreads();
+            const int word = (nt0 * 16 >> 5) + threadIdx.x;
+            if (threadIdx.x < BN / 2 && word < (N >> 5) && col_flag[threadIdx.x])
+                atomicOr(&o.next_mask[word], col_flag[threadIdx.x]);
         }
     }
 }
@@ -400,7 +417,7 @@ hipError_t launch_lds(const GemmArgs &ga0, const LinearW &w, const float *sx, co
     ga.nb_m = (MTT + BM - 1) / BM;
     const int total = ga.nb_n * ga.nb_m;
     const size_t lds_stage = (size_t)NSLOT * (BN + BM) * 1024;
-    const size_t lds_epi = (size_t)WVN * WVM * (TN / 2) * TM * 1024 + (size_t)BN * 16 * 16 + (size_t)BN * 4 * 8;
+    const size_t lds_epi = (size_t)WVN * WVM * (TN / 2) * TM * 1024 + (size_t)BN * 16 * 16 + (size_t)BN * 4 * 8 + (size_t)BN / 2 * 4;
     const size_t lds = lds_stage > lds_epi ? lds_stage : lds_epi;
     auto kern = k_gemm_lds<F16, WVN, WVM, TN, TM>;
     static bool attr_set = false;
