@@ -229,16 +229,56 @@ k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, 
     // them from the multiplications: where two paths with different numbers of LDS reads in flight meet, the
     // compiler waits for all of them.  So the last stage goes through the same motions (its barrier is one
     // too many, its fragment reads fetch its own stage again).
+    // pieces of the next stage's traffic, to be spread between the multiplications
+    auto dma_part = [&](int s, int j0, int j1) {
+        unsigned char *slot = lds + (size_t)(s % NSLOT) * STAGE * 1024;
+#pragma unroll
+        for (int j = j0; j < j1; j++)
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void *)(src[j] + (size_t)s * 1024),
+                (__attribute__((address_space(3))) void *)(slot + (size_t)(wave + NW * j) * 1024), 16, 0, 0);
+    };
+    auto frag_part = [&](int s, v4i *fa, v4i *fb, int part) {           // part 0: token side, 1 / 2: halves of the weight side
+        const unsigned char *base = lds + (size_t)(s % NSLOT) * STAGE * 1024 + lane * 16;
+        if (part == 0) {
+#pragma unroll
+            for (int j = 0; j < TM; j++) fb[j] = *(const v4i *)(base + (size_t)(BN + wm * TM + j) * 1024);
+        } else {
+#pragma unroll
+            for (int i = (part - 1) * (TN / 2); i < part * (TN / 2); i++)
+                fa[i] = *(const v4i *)(base + (size_t)(wn * TN + i) * 1024);
+        }
+    };
     auto step = [&](int s, const v4i *ca, const v4i *cb, v4i *na, v4i *nb) {
         wait_own(max(0, min(NS - s - 2, PD - 2)));  // stage s + 1 of this wave (stages up to s + PD - 1 are requested)
         __builtin_amdgcn_s_barrier();               // everybody's stage s + 1 visible; everybody done reading stage s - 1
         asm volatile("" ::: "memory");
-        if (s + PD < NS) dma_stage(s + PD);          // into the slot of stage s - 1
-        multiply(ca, cb, 0, TN / 2);
-        __builtin_amdgcn_sched_barrier(0);          // keep the reads between the two halves
-        frag_load(min(s + 1, NS - 1), na, nb);
+        // the copy requests (into the slot of stage s - 1) and the fragment reads are issued a few at a time
+        // while the matrix pipe is busy, not in front of it
+        const bool more = s + PD < NS;
+        const int sn = min(s + 1, NS - 1);
+        constexpr int E = TN / 8 > 0 ? TN / 8 : 1;   // weight fragments per eighth of a stage
+        multiply(ca, cb, 0, E);
         __builtin_amdgcn_sched_barrier(0);
-        multiply(ca, cb, TN / 2, TN);
+        if (more) dma_part(s + PD, 0, LOADS / 2);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(ca, cb, E, 2 * E);
+        __builtin_amdgcn_sched_barrier(0);
+        if (more) dma_part(s + PD, LOADS / 2, LOADS);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(ca, cb, 2 * E, 3 * E);
+        __builtin_amdgcn_sched_barrier(0);
+        frag_part(sn, na, nb, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(ca, cb, 3 * E, 4 * E);
+        __builtin_amdgcn_sched_barrier(0);
+        frag_part(sn, na, nb, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(ca, cb, 4 * E, 5 * E);
+        __builtin_amdgcn_sched_barrier(0);
+        frag_part(sn, na, nb, 2);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(ca, cb, 5 * E, TN);
     };
     for (int s = 0; s < NS; s += 2) {
         step(s, fa0, fb0, fa1, fb1);
@@ -257,7 +297,7 @@ k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, 
     // fused-QKV column goes) is tabulated in LDS once per block; what depends only on the token (row
     // scale / 127, row addresses) sits in registers: the loop body has no division left.
     constexpr int QN = TN / 2, NPARK = 2;                                // weight panels per parked half
-    static_assert(TN % 2 == 0, "the epilogue parks half of the accumulators at a time");
+    static_assert(TN % 8 == 0 && LOADS % 2 == 0, "a stage is multiplied in eighths; the epilogue parks half of the accumulators at a time");
     acc_t *mine = (acc_t *)lds + (size_t)wave * (QN * TM * 64) + lane;
     if constexpr (F16) {
 #pragma unroll
