@@ -343,7 +343,7 @@ def test_c4_full_size_block_decode_at_the_benchmark_prefixes():
 
 
 def test_c4_full_size_linears_with_several_rows_sampled_against_the_oracle():
-    """Batched decode (8 rows) and a prefill-size call (200 rows) on the full-size up linear: the oracle computes
+    """Batched decode (8 to 50 rows) and a prefill-size call (200 rows) on full-size linears: the oracle computes
     a sample of output features one by one (the full product is too slow for a test)."""
     cfg = synth.CONFIGS["C4"]
     p = synth.block_params_device(cfg, 0, DEV)
@@ -359,7 +359,7 @@ def test_c4_full_size_linears_with_several_rows_sampled_against_the_oracle():
         Wsub = p[wname][torch.as_tensor(rows, device=DEV)].cpu().numpy()
         bsub = p[bname].cpu().numpy()[rows]
         wq, sw = oracle.quantize_weight(Wsub)
-        for M in (8, 200):
+        for M in (8, 24, 50, 200):                     # 1, 2 and 4 token tiles of the batched-decode kernel, then prefill
             X = r.standard_normal((M, K))
             X[:, r.choice(K, 6, replace=False)] = r.uniform(20, 60, (M, 6))
             X = X.astype(np.float16)
@@ -370,3 +370,34 @@ def test_c4_full_size_linears_with_several_rows_sampled_against_the_oracle():
             assert np.array_equal(to_np(out["acc"])[:, rows], dbg["acc"])
             hidden_close(to_np(out["y"])[:, rows], Y, "C4 linear %d M=%d" % (which, M))
     gsp.close()
+
+
+def test_c4_full_size_down_linear_with_many_outlier_columns():
+    """Batched decode on the widest linear (K = 57344) when about 5% of its input columns are outliers, as the
+    GeLU output of this configuration has them; one 16-column group is all outliers (more than the 8 values
+    per group that travel with the quantized rows)."""
+    cfg = synth.CONFIGS["C4"]
+    p = synth.block_params_device(cfg, 0, DEV)
+    gsp = binding.Span(1, cfg.hidden, cfg.n_heads, cfg.F, 64, 1e-5, 6.0, DEV)
+    gsp.load_block(0, p)
+    r = np.random.default_rng(11)
+    N, K = gsp.shapes(3)
+    rows = np.unique(np.concatenate([np.arange(16), r.choice(N, 64, replace=False), [N - 1]]))
+    Wsub = p["w_down"][torch.as_tensor(rows, device=DEV)].cpu().numpy()
+    bsub = p["b_down"].cpu().numpy()[rows]
+    wq, sw = oracle.quantize_weight(Wsub)
+    for M in (8, 24, 50):
+        X = np.abs(r.standard_normal((M, K))) * 0.7
+        cols = r.choice(K, K // 20, replace=False)
+        X[r.integers(0, M, cols.size), cols] = r.uniform(6, 12, cols.size)      # one row each reaches the threshold
+        X[:, 4096 + 32:4096 + 48] = r.uniform(6, 9, (M, 16))
+        X = X.astype(np.float16)
+        R = (r.standard_normal((M, N)) * 0.5).astype(np.float16)
+        Y, dbg = oracle.linear(X, wq, sw, bsub, 6.0, 2, resid=R[:, rows], want_debug=True)
+        out = gsp.debug_linear(0, 3, to_dev(X), 2, to_dev(R))
+        assert np.array_equal(to_np(out["mask"]), dbg["mask"]) and dbg["mask"].sum() > K // 25
+        assert np.array_equal(to_np(out["xq"]), dbg["xq"]) and np.array_equal(to_np(out["sx"]), dbg["sx"])
+        assert np.array_equal(to_np(out["acc"])[:, rows], dbg["acc"])
+        hidden_close(to_np(out["y"])[:, rows], Y, "C4 down, many outliers, M=%d" % M)
+    gsp.close()
+
