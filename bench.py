@@ -49,8 +49,12 @@ def main():
     ap.add_argument("--prefix", type=int, default=2048, help="KV-cache prefix length of the headline figure")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile-events", action="store_true")
-    ap.add_argument("--mode", choices=["decode", "prefill"], default="decode",
-                    help="decode: the headline batch-1 decode benchmark; prefill: secondary, int8 MFMA GEMM regime")
+    ap.add_argument("--mode", choices=["decode", "prefill", "batched"], default="decode",
+                    help="decode: the headline batch-1 decode benchmark; prefill: secondary, int8 MFMA GEMM regime; "
+                         "batched: secondary, several sessions per decode step")
+    ap.add_argument("--batched-config", choices=["C3", "C5span"], default="C3",
+                    help="batched mode: C3 = 30 BLOOM-7B1-shaped blocks, 8 sessions; C5span = one 12-block span of the "
+                         "70-block BLOOM-176B-shaped stack, 32 sessions")
     ap.add_argument("--prefill-batch", type=int, default=8, help="sessions in the prefill call (512 tokens each)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy, the known-size kernel that scales rocprofv3's "
@@ -69,6 +73,8 @@ def main():
     torch.cuda.set_device(0)
     if args.mode == "prefill":
         return prefill_main(args, dev)
+    if args.mode == "batched":
+        return batched_main(args, dev)
     cfg = synth.CONFIGS["C4"]
     H, F, nh, NB = cfg.hidden, cfg.F, cfg.n_heads, cfg.n_blocks
     K, W = args.steps, args.warmup
@@ -239,6 +245,102 @@ def prefill_main(args, dev):
                                         enumerate(("qkv", "dense", "up", "down"))}},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 1), "peak": 5000.0, "unit": "TOP/s",
                      "frac": round(achieved / 5000.0, 4), "traffic": None, "kernel": "k_gemm_lds (qkv and up linears)"},
+        "cpu_baseline": None,
+    }
+    span.close()
+    print(json.dumps(line))
+
+
+def batched_main(args, dev):
+    """Secondary benchmark: decode steps with several sessions in one call (one new token per session), hidden
+    states crossing the span boundary as blockwise 8-bit codes.  The prompts (512 tokens per session) go through
+    the library's own prefill first.  One step = dequantize the incoming codes, one decode step for all sessions,
+    quantize the result.  Reports aggregate tokens/s and, for the dominant kernel (the batched-decode int8
+    linear), weight bytes streamed per second against the HBM peak."""
+    import numpy as np
+    import torch
+    from paper_2209_01188_amd import binding, synth
+
+    if args.batched_config == "C3":
+        cfg, NB, B = synth.CONFIGS["C3"], synth.CONFIGS["C3"].n_blocks, synth.CONFIGS["C3"].batch
+        name = "C3: 30-block BLOOM-7B1-shaped span (H=4096, 32 heads, F=16384), %d sessions" % B
+    else:
+        cfg, NB, B = synth.CONFIGS["C4"], 12, 32
+        name = "one 12-block span of C5 (H=14336, 112 heads, F=57344), %d sessions" % B
+    H, F, nh, T = cfg.hidden, cfg.F, cfg.n_heads, 512
+    K, W = args.steps, args.warmup
+    chunk = max(1, min(B, 4096 // T))                      # sessions per prefill call
+    span = binding.Span(NB, H, nh, F, max(B, chunk * T), 1e-5, 6.0, dev)
+    for b in range(NB):
+        span.load_block(b, synth.block_params_device(cfg, b, dev))
+    ses = [span.open_session(T + W + K + 1) for _ in range(B)]
+    Xp = synth.hidden_states(cfg, 0, B, T)
+    for s0 in range(0, B, chunk):
+        span.prefill(ses[s0:s0 + chunk], torch.from_numpy(Xp[s0:s0 + chunk]).to(dev))
+    torch.cuda.synchronize()
+    print("[bench] %d blocks loaded, %d x %d prompt tokens prefilled" % (NB, B, T), file=sys.stderr, flush=True)
+
+    CB = 4096                                              # codec block
+    nblk = (B * H + CB - 1) // CB
+    codes, absmax = [], []
+    for i in range(W + K):                                 # the incoming codes of every step, resident on the device
+        x = torch.from_numpy(synth.hidden_states(cfg, 1 + i, B, 1)[:, 0]).to(dev)
+        q = torch.empty(B * H, dtype=torch.uint8, device=dev)
+        a = torch.empty(nblk, dtype=torch.float32, device=dev)
+        binding.petals_hidden_quantize(x, CB, q, a)
+        codes.append(q); absmax.append(a)
+    xin = torch.empty((B, H), dtype=torch.float16, device=dev)
+    out = torch.empty((B, H), dtype=torch.float16, device=dev)
+    qo = torch.empty(B * H, dtype=torch.uint8, device=dev)
+    ao = torch.empty(nblk, dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step(i):
+        binding.petals_hidden_dequantize(codes[i], absmax[i], CB, xin)
+        span.decode_step(ses, xin, out)
+        binding.petals_hidden_quantize(out, CB, qo, ao)
+
+    for i in range(W):
+        step(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for i in range(W, W + K):
+        step(i)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / K
+    # a second pass over one step with the heavy launches bracketed by events (sessions are one token longer)
+    for s in ses:
+        s.close()
+    ses = [span.open_session(T + 2) for _ in range(B)]
+    for s0 in range(0, B, chunk):
+        span.prefill(ses[s0:s0 + chunk], torch.from_numpy(Xp[s0:s0 + chunk]).to(dev))
+    torch.cuda.synchronize()
+    binding.petals_span_profile_begin(span.handle, NB * 8)
+    step(W)
+    torch.cuda.synchronize()
+    pm, pn = binding.petals_span_profile_end(span.handle)
+    L = T + W + K // 2                                     # mean cached length over the timed steps
+    wbytes = NB * sum(gemv_bytes(*span.shapes(i)) for i in range(4))
+    total_bytes = NB * (12 * H * H + 62 * H) + B * NB * (4 * (L + 1) * H + 4 * H) + 2 * B * H * 3
+    gemm_ms, n_gemm = pm[binding.PROFILE_GEMM], pn[binding.PROFILE_GEMM]
+    achieved = wbytes / (gemm_ms * 1e-3) / 1e9 if n_gemm else None
+    line = {
+        "metric": "decode tokens/s per span, all sessions of the call together; achieved HBM GB/s",
+        "value": round(B / (ms * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "data": "synthetic",
+        "config": {"workload": name + ", 512-token prompts, one token per session per step, 8-bit codec at the span "
+                               "boundary", "sessions": B,
+                   "achieved_hbm_gbs": round(total_bytes / (ms * 1e-3) / 1e9, 1),
+                   "hbm_frac_whole_step": round(total_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                   "linears_ms_per_step": round(gemm_ms, 4), "attention_ms_per_step": round(pm[binding.PROFILE_ATTENTION], 4),
+                   "per_linear_gbs": {n: round(NB * gemv_bytes(*span.shapes(i)) / (pm[binding.PROFILE_LINEAR0 + i] * 1e-3) / 1e9, 1)
+                                      for i, n in enumerate(("qkv", "dense", "up", "down")) if pm[binding.PROFILE_LINEAR0 + i] > 0}},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1) if achieved else None, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4) if achieved else None, "traffic": None,
+                     "kernel": "k_gemm (batched-decode int8 linear)", "launches": n_gemm},
         "cpu_baseline": None,
     }
     span.close()
