@@ -16,23 +16,28 @@ __global__ void k_set_table(SessTable t, SessTable *dst) {
 }
 
 // Prefill (T > 1 new tokens per session): exact attention on the fp64 matrix cores.
-// One wave owns 16 consecutive query rows of one (session, head) and walks the key tiles
-// (16 keys each) up to the causal limit with an online softmax.
+// A workgroup of four waves owns 64 consecutive query rows of one (session, head), 16 per wave, and
+// walks the key tiles (16 keys each) up to the causal limit with an online softmax per wave.
 //   S^T = K Q^T   : v_mfma_f64_16x16x4_f64, A = keys (row = key), B = queries (column = query);
 //                   lane l feeds row/column l%16 and the dims [l/16 * D/4, +D/4) - any pairing of
-//                   the contraction index works as long as both operands use the same one, and
-//                   this one makes each lane read D/2 consecutive bytes of a key or query.
+//                   the contraction index works as long as both operands use the same one.
 //   the result registers hold S^T[key 4r + l/16][query l%16], which is exactly the B operand of
 //   O^T += V^T P^T (A = values with row i = output dims i*D/16 + blk), so the probabilities never
 //   change lanes.  Products of fp16 inputs are exact in fp64; the fp16 context equals the exactly
 //   rounded one (a different summation order moves the fp64 sum by ~1e-16 relative).
+// The fp16 -> fp64 conversions of a key / value tile cost about as much vector-ALU time as its
+// matrix instructions take, so they are done once per workgroup: the four waves convert the next
+// tile together into LDS, already in A-operand order (one 8-byte read per lane and instruction),
+// while the current one is multiplied.  Queries are converted once per wave and stay in registers.
 template <int D>
-__global__ void __launch_bounds__(64) k_attn_prefill(const __half *__restrict__ q, const SessTable *__restrict__ sess,
-                                                     int blk, int T, int nh, __half *__restrict__ ctx,
-                                                     uint32_t *__restrict__ mask, float theta) {
+__global__ void __launch_bounds__(256, 2) k_attn_prefill(const __half *__restrict__ q, const SessTable *__restrict__ sess,
+                                                         int blk, int T, int nh, __half *__restrict__ ctx,
+                                                         uint32_t *__restrict__ mask, float theta) {
     constexpr int DS = D / 4, NB = D / 16;           // dims per lane group; output blocks of 16 dims
-    const int qt = blockIdx.x, h = blockIdx.y, s = blockIdx.z;
-    const int lane = threadIdx.x, c = lane & 15, g = lane >> 4;
+    constexpr int TILE = 16 * D;                     // fp64 values of one key or value tile
+    extern __shared__ __align__(16) double kvd[];    // [2 buffers][keys | values][TILE]
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, c = lane & 15, g = lane >> 4;
+    const int qt = blockIdx.x * 4 + wave, h = blockIdx.y, s = blockIdx.z;
     const int L = sess->len[s], cap = sess->cap[s], H = nh * D;
     const __half *Kc = sess->kv[s] + ((size_t)blk * 2 * nh + h) * cap * D;
     const __half *Vc = Kc + (size_t)nh * cap * D;
@@ -42,61 +47,92 @@ __global__ void __launch_bounds__(64) k_attn_prefill(const __half *__restrict__ 
     const int qpos = L + tq;                          // its absolute position
     const size_t qrow = (size_t)s * T + min(tq, T - 1);
 
-    __half qh[DS];                                    // kept as fp16 (converted per use) to save registers
+    double qd[DS];
     {
         const __half *qp = q + qrow * H + h * D + g * DS;
 #pragma unroll
-        for (int e = 0; e < DS; e++) qh[e] = qp[e];
+        for (int e = 0; e < DS; e++) qd[e] = (double)__half2float(qp[e]);
     }
     v4d O[NB];
 #pragma unroll
     for (int b = 0; b < NB; b++) O[b] = (v4d){0.0, 0.0, 0.0, 0.0};
     double m_run = -INFINITY, l_run = 0.0;
 
-    const int nkt = min(L + qt * 16 + 15, last_key) / 16 + 1;
+    // key tiles this wave needs (none if its queries lie beyond T) and the workgroup's last wave needs
+    const int nkt_w = qt * 16 < T ? min(L + qt * 16 + 15, last_key) / 16 + 1 : 0;
+    const int nkt = min(L + (blockIdx.x * 4 + 3) * 16 + 15, last_key) / 16 + 1;
+
+    // conversion duty of this thread: NB consecutive dims of one key of the tile, keys and values alike
+    const int fk = threadIdx.x >> 4, fd = (threadIdx.x & 15) * NB;
+    __half kraw[NB], vraw[NB];
+    auto fetch = [&](int kt) {
+        const size_t off = (size_t)min(kt * 16 + fk, last_key) * D + fd;
+#pragma unroll
+        for (int i = 0; i < NB; i++) {
+            kraw[i] = Kc[off + i];
+            vraw[i] = Vc[off + i];
+        }
+    };
+    auto stash = [&](int buf) {
+        double *kd = kvd + (size_t)buf * 2 * TILE, *vd = kd + TILE;
+#pragma unroll
+        for (int i = 0; i < NB; i++) {
+            const int d = fd + i;
+            // keys: A operand of step e is K[key][g * DS + e] at lane (g, key)
+            kd[(d % DS) * 64 + (d / DS) * 16 + fk] = (double)__half2float(kraw[i]);
+            // values: A operand of step (r, b) is V[key 4r + g][c * NB + b] at lane (g, c)
+            vd[((fk >> 2) * NB + i) * 64 + (fk & 3) * 16 + (threadIdx.x & 15)] = (double)__half2float(vraw[i]);
+        }
+    };
+    fetch(0);
+    stash(0);
+    __syncthreads();
     for (int kt = 0; kt < nkt; kt++) {
-        // scores of 16 keys x 16 queries
-        v4d S = {0.0, 0.0, 0.0, 0.0};
-        {
-            const __half *kp = Kc + (size_t)min(kt * 16 + c, last_key) * D + g * DS;
+        if (kt + 1 < nkt) fetch(kt + 1);              // in flight during the multiplications below
+        if (kt < nkt_w) {
+            const double *kd = kvd + (size_t)(kt & 1) * 2 * TILE + lane, *vd = kd + TILE;
+            // scores of 16 keys x 16 queries
+            // (a dependent fp64 matrix instruction issues at about half the rate of independent ones:
+            // up to four partial sums run side by side)
+            constexpr int NCH = DS >= 16 ? 4 : (DS >= 8 ? 2 : 1);
+            v4d Sp[NCH];
+#pragma unroll
+            for (int i = 0; i < NCH; i++) Sp[i] = (v4d){0.0, 0.0, 0.0, 0.0};
 #pragma unroll
             for (int e = 0; e < DS; e++)
-                S = __builtin_amdgcn_mfma_f64_16x16x4f64((double)__half2float(kp[e]), (double)__half2float(qh[e]), S, 0, 0, 0);
+                Sp[e % NCH] = __builtin_amdgcn_mfma_f64_16x16x4f64(kd[e * 64], qd[e], Sp[e % NCH], 0, 0, 0);
+            v4d S = Sp[0];
+#pragma unroll
+            for (int i = 1; i < NCH; i++) S += Sp[i];
+            double sc[4], mt = -INFINITY;
+#pragma unroll
+            for (int r = 0; r < 4; r++) {
+                const int kpos = kt * 16 + 4 * r + g;
+                sc[r] = (kpos <= qpos && kpos <= last_key) ? S[r] / rsd - slope * (double)(qpos - kpos) : -INFINITY;
+                mt = fmax(mt, sc[r]);
+            }
+            mt = fmax(mt, __shfl_xor(mt, 16));
+            mt = fmax(mt, __shfl_xor(mt, 32));
+            const double m_new = fmax(m_run, mt);
+            const double alpha = (m_run == -INFINITY) ? 0.0 : exp(m_run - m_new);
+            double p[4], psum = 0.0;
+#pragma unroll
+            for (int r = 0; r < 4; r++) {
+                p[r] = (sc[r] == -INFINITY) ? 0.0 : exp(sc[r] - m_new);
+                psum += p[r];
+            }
+            l_run = l_run * alpha + psum;             // per lane group; the groups are added at the end
+            m_run = m_new;
+#pragma unroll
+            for (int b = 0; b < NB; b++) O[b] *= alpha;
+#pragma unroll
+            for (int r = 0; r < 4; r++)
+#pragma unroll
+                for (int b = 0; b < NB; b++)
+                    O[b] = __builtin_amdgcn_mfma_f64_16x16x4f64(vd[(r * NB + b) * 64], p[r], O[b], 0, 0, 0);
         }
-        // values of the same keys, requested before the softmax arithmetic
-        __half vraw[4][NB];
-#pragma unroll
-        for (int r = 0; r < 4; r++) {
-            const __half *vp = Vc + (size_t)min(kt * 16 + 4 * r + g, last_key) * D + c * NB;
-#pragma unroll
-            for (int b = 0; b < NB; b++) vraw[r][b] = vp[b];
-        }
-        double sc[4], mt = -INFINITY;
-#pragma unroll
-        for (int r = 0; r < 4; r++) {
-            const int kpos = kt * 16 + 4 * r + g;
-            sc[r] = (kpos <= qpos && kpos <= last_key) ? S[r] / rsd - slope * (double)(qpos - kpos) : -INFINITY;
-            mt = fmax(mt, sc[r]);
-        }
-        mt = fmax(mt, __shfl_xor(mt, 16));
-        mt = fmax(mt, __shfl_xor(mt, 32));
-        const double m_new = fmax(m_run, mt);
-        const double alpha = (m_run == -INFINITY) ? 0.0 : exp(m_run - m_new);
-        double p[4], psum = 0.0;
-#pragma unroll
-        for (int r = 0; r < 4; r++) {
-            p[r] = (sc[r] == -INFINITY) ? 0.0 : exp(sc[r] - m_new);
-            psum += p[r];
-        }
-        l_run = l_run * alpha + psum;                 // per lane group; the groups are added at the end
-        m_run = m_new;
-#pragma unroll
-        for (int b = 0; b < NB; b++) O[b] *= alpha;
-#pragma unroll
-        for (int r = 0; r < 4; r++)
-#pragma unroll
-            for (int b = 0; b < NB; b++)
-                O[b] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)__half2float(vraw[r][b]), p[r], O[b], 0, 0, 0);
+        if (kt + 1 < nkt) stash((kt + 1) & 1);        // that buffer was last read before the previous barrier
+        __syncthreads();
     }
     l_run += __shfl_xor(l_run, 16);
     l_run += __shfl_xor(l_run, 32);
@@ -272,7 +308,7 @@ hipError_t attn_launch(const __half *q, const SessTable *sess, int blk, int M, i
     int CH = ((max_keys + nsplit - 1) / nsplit + 255) / 256 * 256;
     if (nsplit == 1) CH = 1 << 30;
     if (T > 1) {
-        k_attn_prefill<D><<<dim3((T + 15) / 16, nh, M / T), 64, 0, st>>>(q, sess, blk, T, nh, ctx, mask, theta);
+        k_attn_prefill<D><<<dim3((T + 63) / 64, nh, M / T), 256, (size_t)2 * 2 * 16 * D * 8, st>>>(q, sess, blk, T, nh, ctx, mask, theta);
         return hipGetLastError();
     }
     k_attn_decode<D><<<dim3(nsplit, nh, M), 256, 0, st>>>(q, sess, blk, nh, CH, nsplit, partials, ctx, mask, theta);
