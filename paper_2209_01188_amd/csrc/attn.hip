@@ -4,6 +4,7 @@
 // 1 KB of consecutive cache bytes; softmax runs online across 256-key tiles whose
 // scores and probabilities are staged in LDS.
 #include "common.h"
+#include <cstdlib>
 #include <stdlib.h>
 
 namespace {
@@ -300,12 +301,14 @@ __global__ void k_attn_combine(const SessTable *__restrict__ sess, int T, int nh
 template <int D>
 hipError_t attn_launch(const __half *q, const SessTable *sess, int blk, int M, int T, int nh, int max_keys,
                        double *partials, __half *ctx, uint32_t *mask, float theta, hipStream_t st) {
-    // split the key range only when rows*heads alone cannot fill the GPU
-    int nsplit = (max_keys + 255) / 256;
+    // Split the key range only as far as rows*heads alone leave the GPU short of about two workgroups per
+    // compute unit (the kernel is bound by its fp64 arithmetic and by latency, not by the number of workgroups:
+    // measured on 112 heads and 2048 keys, 4 ranges beat 9 and 16), at least 128 keys per range.
+    int nsplit = max(1, 512 / (M * nh));
+    nsplit = min(nsplit, max(1, max_keys / 128));
     nsplit = min(nsplit, PS_ATTN_MAX_SPLITS);
-    nsplit = min(nsplit, max(1, PS_ATTN_PARTIAL_SLOTS / 2 / max(1, M * nh)));
     if ((size_t)M * nh * nsplit > PS_ATTN_PARTIAL_SLOTS) nsplit = 1;
-    int CH = ((max_keys + nsplit - 1) / nsplit + 255) / 256 * 256;
+    int CH = ((max_keys + nsplit - 1) / nsplit + 63) / 64 * 64;
     if (nsplit == 1) CH = 1 << 30;
     if (T > 1) {
         k_attn_prefill<D><<<dim3((T + 63) / 64, nh, M / T), 256, (size_t)2 * 2 * 16 * D * 8, st>>>(q, sess, blk, T, nh, ctx, mask, theta);
