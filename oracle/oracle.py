@@ -12,7 +12,7 @@ from .build_oracle import LIB, build
 
 __all__ = ["f16_to_f64", "f64_to_f16", "quantize_weight", "layernorm", "gelu", "linear",
            "alibi_slopes", "attention", "Span", "Session", "codebook", "hidden_quantize",
-           "hidden_dequantize", "num_threads", "EPI_NONE", "EPI_GELU", "EPI_RESIDUAL"]
+           "hidden_dequantize", "num_threads", "embed", "lm_head", "EPI_NONE", "EPI_GELU", "EPI_RESIDUAL"]
 
 EPI_NONE, EPI_GELU, EPI_RESIDUAL = 0, 1, 2
 
@@ -107,6 +107,30 @@ def linear(X, wq, sw, bias, theta, epilogue=EPI_NONE, resid=None, want_debug=Fal
                      _p(dbg["xq"]) if dbg else None, _p(dbg["sx"]) if dbg else None,
                      _p(dbg["mask"]) if dbg else None, _p(dbg["acc"]) if dbg else None, _p(Y))
     return (Y, dbg) if want_debug else Y
+
+
+def embed(ids, E, g, b, eps=1e-5):
+    """fp16 [M, H]: LayerNorm of the embedding rows of the token ids."""
+    ids = np.ascontiguousarray(ids, np.int32)
+    E, g, b = _h(E), _h(g), _h(b)
+    V, H = E.shape
+    assert ids.min() >= 0 and ids.max() < V
+    y = np.empty((ids.size, H), np.float16)
+    lib().orc_embed(_p(ids), C.c_int(ids.size), _p(E), C.c_int(H), _p(g), _p(b), C.c_double(eps), _p(y))
+    return y
+
+
+def lm_head(x, E, g, b, eps=1e-5, want_logits=False):
+    """Greedy next tokens int32 [M] (and the fp64 logits [M, V]) of final hidden states x fp16 [M, H]."""
+    x, E, g, b = _h(x), _h(E), _h(g), _h(b)
+    M, H = x.shape
+    V = E.shape[0]
+    assert E.shape == (V, H)
+    nxt = np.empty(M, np.int32)
+    logits = np.empty((M, V), np.float64) if want_logits else None
+    lib().orc_lm_head(_p(x), C.c_int(M), _p(E), C.c_int(V), C.c_int(H), _p(g), _p(b), C.c_double(eps),
+                      _p(logits), _p(nxt))
+    return (nxt, logits) if want_logits else nxt
 
 
 def alibi_slopes(nh):

@@ -10,8 +10,10 @@
  * Section 3.1 "Compressing model weights": 8-bit mixed matrix decomposition,
  * int8 regular part plus 16-bit outlier part; Section 3.1 "Compressing
  * communication buffers": dynamic blockwise 8-bit quantization of hidden
- * states).  The paper names these methods without printing equations, so the
- * numerical details follow the readings listed at each function.
+ * states; Section 2.1 / Figure 2: the client's embedding lookup and LM head
+ * around the spans).  The paper names these methods without printing
+ * equations, so the numerical details follow the readings listed at each
+ * function.
  *
  * Conventions: fp16 values travel as uint16_t bit patterns.  Storage points
  * are fp16; between storage points arithmetic is exact integer or fp64,
@@ -501,6 +503,56 @@ int orc_span_step(orc_span *s, orc_session *const *sess, int B, int T,
     for (int i = 0; i < B; i++) sess[i]->len += T;
     free(x); free(a); free(qkv); free(ctx); free(x1); free(g);
     return 0;
+}
+
+/* ------------------------------------------- client side of a generation step */
+
+/*
+ * What the client computes around the server spans (Section 2.1: the client
+ * keeps the token embeddings locally, looks up embedding vectors, and from the
+ * outputs of the final block "computes next token probabilities"; Figure 2:
+ * word_embeddings, lm_head, sample_next_token).  BLOOM-style reading: the
+ * embedding row goes through a LayerNorm, the final hidden state goes through
+ * a LayerNorm and is multiplied with the SAME embedding matrix (tied weights).
+ *
+ * Embedding: y[t] = LayerNorm(E[ids[t]]), stored fp16.
+ */
+void orc_embed(const int32_t *ids, int M, const uint16_t *E, int H,
+               const uint16_t *g, const uint16_t *b, double eps, uint16_t *y)
+{
+    for (int t = 0; t < M; t++)
+        orc_layernorm(E + (size_t)ids[t] * H, g, b, 1, H, eps, y + (size_t)t * H);
+}
+
+/*
+ * LM head: a = LayerNorm(x) (stored fp16), logits[t][v] = sum_k a[t][k] * E[v][k]
+ * in fp64 (every product of two fp16 values is exact), greedy next token =
+ * the first index of the largest logit.  logits (may be NULL) is [M][V] fp64.
+ */
+void orc_lm_head(const uint16_t *x, int M, const uint16_t *E, int V, int H,
+                 const uint16_t *g, const uint16_t *b, double eps,
+                 double *logits, int32_t *next)
+{
+    uint16_t *a = (uint16_t *)malloc((size_t)H * 2);
+    double *ad = (double *)malloc((size_t)H * 8);
+    double *row = (double *)malloc((size_t)V * 8);
+    for (int t = 0; t < M; t++) {
+        orc_layernorm(x + (size_t)t * H, g, b, 1, H, eps, a);
+        for (int k = 0; k < H; k++) ad[k] = h2d(a[k]);
+#pragma omp parallel for schedule(static)
+        for (int v = 0; v < V; v++) {
+            const uint16_t *e = E + (size_t)v * H;
+            double acc = 0.0;
+            for (int k = 0; k < H; k++) acc += ad[k] * h2d(e[k]);
+            row[v] = acc;
+        }
+        int best = 0;
+        for (int v = 1; v < V; v++)
+            if (row[v] > row[best]) best = v;
+        next[t] = best;
+        if (logits) memcpy(logits + (size_t)t * V, row, (size_t)V * 8);
+    }
+    free(a); free(ad); free(row);
 }
 
 /* ---------------------------------------------------------------- codec */
