@@ -44,7 +44,7 @@ def lib():
                                "(or __graft_entry__.build()); there is no fallback implementation")
         L = C.CDLL(LIB_PATH)
         L.petals_last_error.restype = C.c_char_p
-        for name in EXPORTS:
+        for name in EXPORTS + CLIENT_EXPORTS:
             if name != "petals_last_error":
                 getattr(L, name).restype = C.c_int
         _lib = L
@@ -57,6 +57,8 @@ EXPORTS = ["petals_span_weight_bytes", "petals_span_workspace_bytes", "petals_sp
            "petals_hidden_dequantize", "petals_hidden_code_table", "petals_last_error", "petals_debug_linear",
            "petals_debug_export_weight", "petals_debug_export_kv", "petals_debug_import_kv",
            "petals_span_profile_begin", "petals_span_profile_end", "petals_debug_layernorm"]
+CLIENT_EXPORTS = ["petals_client_workspace_bytes", "petals_client_create", "petals_client_destroy",
+                  "petals_client_embed", "petals_client_lm_head"]
 PROFILE_GEMV, PROFILE_GEMM, PROFILE_ATTENTION, PROFILE_LINEAR0, PROFILE_CLASSES = 0, 1, 2, 3, 7
 
 
@@ -297,3 +299,71 @@ class Session:
             self.handle = None
             if self in self.span.sessions:
                 self.span.sessions.remove(self)
+
+
+# ----------------------------------------------------------------- client-side ends (petals_client.h)
+
+class ClientConfig(C.Structure):
+    _fields_ = [("vocab", C.c_int32), ("hidden", C.c_int32), ("ln_eps", C.c_float), ("max_rows_per_call", C.c_int32)]
+
+
+class ClientParams(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("embeddings", "emb_ln_g", "emb_ln_b", "final_ln_g", "final_ln_b")]
+
+
+def petals_client_workspace_bytes(cfg):
+    n = C.c_size_t()
+    _check(lib().petals_client_workspace_bytes(C.byref(cfg), C.byref(n)))
+    return n.value
+
+
+def petals_client_create(cfg, params, workspace):
+    h = C.c_void_p()
+    _check(lib().petals_client_create(C.byref(cfg), C.byref(params), _ptr(workspace), C.byref(h)))
+    return h
+
+
+def petals_client_destroy(client):
+    _check(lib().petals_client_destroy(client))
+
+
+def petals_client_embed(client, token_ids, hidden_out):
+    _check(lib().petals_client_embed(client, _ptr(token_ids), C.c_int32(token_ids.numel()), _ptr(hidden_out), _stream()))
+
+
+def petals_client_lm_head(client, hidden_in, logits_out, next_token_out):
+    _check(lib().petals_client_lm_head(client, _ptr(hidden_in), C.c_int32(hidden_in.shape[0]), _ptr(logits_out),
+                                       _ptr(next_token_out), _stream()))
+
+
+class Client:
+    """Embedding lookup and LM head over one fp16 embedding matrix that stays where the caller put it."""
+
+    def __init__(self, embeddings, emb_ln_g, emb_ln_b, final_ln_g, final_ln_b, max_rows, ln_eps=1e-5):
+        self.device = embeddings.device
+        self.vocab, self.hidden = embeddings.shape
+        self.tensors = [t.contiguous() for t in (embeddings, emb_ln_g, emb_ln_b, final_ln_g, final_ln_b)]
+        assert all(t.dtype == torch.float16 for t in self.tensors)
+        self.cfg = ClientConfig(self.vocab, self.hidden, ln_eps, max_rows)
+        self.workspace = torch.empty(petals_client_workspace_bytes(self.cfg), dtype=torch.uint8, device=self.device)
+        self.params = ClientParams(*[t.data_ptr() for t in self.tensors])
+        self.handle = petals_client_create(self.cfg, self.params, self.workspace)
+
+    def embed(self, token_ids, out=None):
+        token_ids = token_ids.to(torch.int32).contiguous()
+        out = torch.empty((token_ids.numel(), self.hidden), dtype=torch.float16, device=self.device) if out is None else out
+        petals_client_embed(self.handle, token_ids, out)
+        return out
+
+    def lm_head(self, hidden, want_logits=False, next_out=None):
+        M = hidden.shape[0]
+        logits = torch.empty((M, self.vocab), dtype=torch.float32, device=self.device) if want_logits else None
+        nxt = torch.empty(M, dtype=torch.int32, device=self.device) if next_out is None else next_out
+        petals_client_lm_head(self.handle, hidden.contiguous(), logits, nxt)
+        return (nxt, logits) if want_logits else nxt
+
+    def close(self):
+        if self.handle is not None:
+            torch.cuda.synchronize(self.device)
+            petals_client_destroy(self.handle)
+            self.handle = None

@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpetals_span.so")
 OBJ = os.path.join(HERE, "_build")
-SOURCES = ["api.hip", "quant.hip", "gemv.hip", "gemm.hip", "gemm_lds.hip", "attn.hip"]
+SOURCES = ["api.hip", "quant.hip", "gemv.hip", "gemm.hip", "gemm_lds.hip", "attn.hip", "client.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 ops are disabled on the test machines.
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17",
@@ -24,6 +24,7 @@ def build(force=True, verbose=False):
     os.makedirs(OBJ, exist_ok=True)
     headers = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
     headers.append(os.path.join(os.path.dirname(HERE), "include", "petals_span.h"))
+    headers.append(os.path.join(os.path.dirname(HERE), "include", "petals_client.h"))
     jobs = []
     for s in SOURCES:
         src, obj = os.path.join(CSRC, s), os.path.join(OBJ, s.replace(".hip", ".o"))

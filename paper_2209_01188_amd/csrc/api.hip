@@ -11,25 +11,26 @@
 #include "../../include/petals_span.h"
 #include "common.h"
 
+#include "host_util.h"
+
 namespace {
-
 thread_local char g_err[512] = "";
+}
 
-int fail(int code, const char *fmt, ...) {
+int ps_fail(int code, const char *fmt, ...) {
     va_list ap;
     va_start(ap, fmt);
     vsnprintf(g_err, sizeof(g_err), fmt, ap);
     va_end(ap);
     return code;
 }
-int hip_fail(hipError_t e, const char *what) {
-    return fail(PETALS_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+int ps_hip_fail(hipError_t e, const char *what) {
+    return ps_fail(PETALS_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
 }
-#define HIP_TRY(expr)                                        \
-    do {                                                     \
-        hipError_t e_ = (expr);                              \
-        if (e_ != hipSuccess) return hip_fail(e_, #expr);    \
-    } while (0)
+
+namespace {
+
+#define fail ps_fail
 
 size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 

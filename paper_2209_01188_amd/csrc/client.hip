@@ -1,0 +1,243 @@
+// Client-side ends of a generation step: embedding lookup with its LayerNorm, final
+// LayerNorm + LM head over the tied embedding matrix + greedy choice.  The LM head is a
+// matrix-vector product over V x H fp16 weights read once: HBM bound.
+#include <stdarg.h>
+#include <string.h>
+
+#include <new>
+
+#include "../../include/petals_client.h"
+#include "../../include/petals_span.h"
+#include "common.h"
+#include "host_util.h"
+#include "rowops.h"
+
+namespace {
+
+constexpr int LM_THREADS = 1024;           // 16 waves: enough 16-byte loads in flight for one workgroup per compute unit
+constexpr int LM_WAVES = LM_THREADS / 64;
+constexpr int LM_GROUPS = 256;             // workgroups of the LM head = partial results per row
+constexpr int LM_MAX_ROWS = 4;             // rows of hidden states multiplied per pass over the matrix
+constexpr size_t LM_LDS_BUDGET = 128 * 1024;
+
+// One workgroup per token: gather the embedding row, LayerNorm in fp64, store fp16.
+template <int NT>
+__global__ void __launch_bounds__(NT) k_embed_ln(const int32_t *__restrict__ ids, const __half *__restrict__ E, int V,
+                                                 int H, const __half *__restrict__ g, const __half *__restrict__ b,
+                                                 float eps, __half *__restrict__ y) {
+    __shared__ double sm[NT / 64];
+    const int id = min(max(ids[blockIdx.x], 0), V - 1);
+    const __half *xr = E + (size_t)id * H;
+    __half *yr = y + (size_t)blockIdx.x * H;
+    double mean, inv;
+    row_moments<NT>(xr, H, sm, mean, inv, (double)eps);
+    for (int k = threadIdx.x * 2; k < H; k += NT * 2)
+        *(__half2 *)(yr + k) = ln_affine(*(const __half2 *)(xr + k), *(const __half2 *)(g + k),
+                                         *(const __half2 *)(b + k), mean, inv);
+}
+
+struct Best {
+    double v;
+    int i;
+};
+__device__ __forceinline__ void take_better(Best &a, double v, int i) {   // larger value, then smaller index
+    if (v > a.v || (v == a.v && i < a.i)) {
+        a.v = v;
+        a.i = i;
+    }
+}
+
+// logits of RM rows of fp16 hidden states a[RM][H] against all V rows of E.  The hidden rows sit in
+// LDS as fp64 (converted once); wave w of workgroup g takes the matrix rows (g * 16 + w) + i * 16 * gridDim.x, one row
+// at a time: 64 lanes x 16 bytes per load instruction, four instructions in flight, a wave-wide fp64
+// sum at the end of the row.  Each workgroup leaves its best (value, index) per hidden row.
+template <int RM>
+__global__ void __launch_bounds__(LM_THREADS) k_lm_head(const __half *__restrict__ a, int rows, const __half *__restrict__ E,
+                                                        int V, int H, float *__restrict__ logits,
+                                                        Best *__restrict__ partial) {
+    // element k = 8 c + j of row m at [m][j][c]: the lanes of a wave hold consecutive chunks c, so their
+    // 8-byte reads of one j are consecutive in LDS (no bank conflicts)
+    extern __shared__ __align__(16) double ad[];       // [RM][8][H / 8]
+    __shared__ Best wbest[LM_WAVES][RM];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nchunk = H >> 3;
+    for (int i = threadIdx.x; i < RM * H; i += LM_THREADS) {
+        const int m = i / H, k = i - m * H;
+        ad[(size_t)m * H + (k & 7) * nchunk + (k >> 3)] = m < rows ? (double)__half2float(a[i]) : 0.0;
+    }
+    __syncthreads();
+    Best best[RM];
+#pragma unroll
+    for (int m = 0; m < RM; m++) best[m] = Best{-INFINITY, 0x7fffffff};
+    for (int v = blockIdx.x * LM_WAVES + wave; v < V; v += gridDim.x * LM_WAVES) {
+        const __half *er = E + (size_t)v * H;
+        double acc[RM];
+#pragma unroll
+        for (int m = 0; m < RM; m++) acc[m] = 0.0;
+        for (int c0 = lane; c0 < nchunk; c0 += 256) {
+            v8h e[4];
+#pragma unroll
+            for (int u = 0; u < 4; u++)             // index clamped: every lane issues all four loads
+                e[u] = __builtin_nontemporal_load((const v8h *)(er + (size_t)min(c0 + u * 64, nchunk - 1) * 8));
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                const int c = c0 + u * 64;
+                if (c < nchunk) {
+#pragma unroll
+                    for (int j = 0; j < 8; j++) {
+                        const double ed = (double)(float)e[u][j];
+#pragma unroll
+                        for (int m = 0; m < RM; m++) acc[m] += ed * ad[m * H + j * nchunk + c];
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int m = 0; m < RM; m++) {
+            const double s = wave_sum(acc[m]);
+            if (m < rows) {
+                if (lane == 0 && logits) logits[(size_t)m * V + v] = (float)s;
+                take_better(best[m], s, v);
+            }
+        }
+    }
+    if (lane == 0) {
+#pragma unroll
+        for (int m = 0; m < RM; m++) wbest[wave][m] = best[m];
+    }
+    __syncthreads();
+    if (threadIdx.x < RM) {
+        Best r = wbest[0][threadIdx.x];
+        for (int w = 1; w < LM_WAVES; w++) take_better(r, wbest[w][threadIdx.x].v, wbest[w][threadIdx.x].i);
+        partial[threadIdx.x * LM_GROUPS + blockIdx.x] = r;
+    }
+}
+
+// the best of the workgroups' candidates of each hidden row
+__global__ void __launch_bounds__(64) k_lm_pick(const Best *__restrict__ partial, int ngroups, int32_t *__restrict__ next) {
+    const Best *p = partial + (size_t)blockIdx.x * LM_GROUPS;
+    Best r = Best{-INFINITY, 0x7fffffff};
+    for (int i = threadIdx.x; i < ngroups; i += 64) take_better(r, p[i].v, p[i].i);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const double v = __shfl_xor(r.v, off);
+        const int i = __shfl_xor(r.i, off);
+        take_better(r, v, i);
+    }
+    if (threadIdx.x == 0) next[blockIdx.x] = r.i;
+}
+
+size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
+
+int rows_per_pass(int H) {
+    int rm = (int)(LM_LDS_BUDGET / ((size_t)H * 8));
+    return rm >= 4 ? 4 : (rm >= 2 ? 2 : 1);
+}
+
+}  // namespace
+
+struct petals_client {
+    petals_client_config cfg;
+    petals_client_params p;
+    __half *a;          // LayerNorm output of the rows of one lm_head call
+    Best *partial;      // [LM_MAX_ROWS][LM_GROUPS]
+    bool lds_attr_set[3];
+};
+
+namespace {
+int check_client_config(const petals_client_config *c) {
+    if (!c) return ps_fail(PETALS_ERR_INVALID_ARG, "config is null");
+    if (c->vocab < 1 || c->hidden < 1 || c->max_rows_per_call < 1)
+        return ps_fail(PETALS_ERR_INVALID_ARG, "config fields must be positive");
+    if (c->hidden % 64 || c->hidden > 16384) return ps_fail(PETALS_ERR_UNSUPPORTED, "hidden must be a multiple of 64, at most 16384");
+    if (!(c->ln_eps > 0.0f)) return ps_fail(PETALS_ERR_INVALID_ARG, "ln_eps must be positive");
+    return PETALS_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int petals_client_workspace_bytes(const petals_client_config *cfg, size_t *bytes) {
+    if (!bytes) return ps_fail(PETALS_ERR_INVALID_ARG, "null pointer");
+    if (int rc = check_client_config(cfg)) return rc;
+    *bytes = align_up((size_t)cfg->max_rows_per_call * cfg->hidden * 2) + align_up(sizeof(Best) * LM_MAX_ROWS * LM_GROUPS);
+    return PETALS_OK;
+}
+
+int petals_client_create(const petals_client_config *cfg, const petals_client_params *params, void *dev_workspace,
+                         petals_client **out) {
+    if (!params || !dev_workspace || !out) return ps_fail(PETALS_ERR_INVALID_ARG, "null pointer");
+    if (int rc = check_client_config(cfg)) return rc;
+    if (!params->embeddings || !params->emb_ln_g || !params->emb_ln_b || !params->final_ln_g || !params->final_ln_b)
+        return ps_fail(PETALS_ERR_INVALID_ARG, "a parameter pointer is null");
+    if ((uintptr_t)dev_workspace & 255) return ps_fail(PETALS_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+    if ((uintptr_t)params->embeddings & 15) return ps_fail(PETALS_ERR_INVALID_ARG, "embeddings must be 16-byte aligned");
+    petals_client *c = new (std::nothrow) petals_client;
+    if (!c) return ps_fail(PETALS_ERR_INVALID_ARG, "out of host memory");
+    c->cfg = *cfg;
+    c->p = *params;
+    c->a = (__half *)dev_workspace;
+    c->partial = (Best *)((uint8_t *)dev_workspace + align_up((size_t)cfg->max_rows_per_call * cfg->hidden * 2));
+    c->lds_attr_set[0] = c->lds_attr_set[1] = c->lds_attr_set[2] = false;
+    *out = c;
+    return PETALS_OK;
+}
+
+int petals_client_destroy(petals_client *client) {
+    if (!client) return ps_fail(PETALS_ERR_INVALID_ARG, "null pointer");
+    delete client;
+    return PETALS_OK;
+}
+
+int petals_client_embed(petals_client *c, const int32_t *token_ids, int32_t M, void *hidden_out, void *stream) {
+    if (!c || !token_ids || !hidden_out) return ps_fail(PETALS_ERR_INVALID_ARG, "null pointer");
+    if (M < 1) return ps_fail(PETALS_ERR_INVALID_ARG, "M must be positive");
+    if (M > c->cfg.max_rows_per_call) return ps_fail(PETALS_ERR_CAPACITY, "%d rows exceed max_rows_per_call %d", M, c->cfg.max_rows_per_call);
+    hipStream_t st = (hipStream_t)stream;
+    const __half *E = (const __half *)c->p.embeddings;
+    if (c->cfg.hidden >= 4096)
+        k_embed_ln<1024><<<M, 1024, 0, st>>>(token_ids, E, c->cfg.vocab, c->cfg.hidden, (const __half *)c->p.emb_ln_g,
+                                             (const __half *)c->p.emb_ln_b, c->cfg.ln_eps, (__half *)hidden_out);
+    else
+        k_embed_ln<256><<<M, 256, 0, st>>>(token_ids, E, c->cfg.vocab, c->cfg.hidden, (const __half *)c->p.emb_ln_g,
+                                           (const __half *)c->p.emb_ln_b, c->cfg.ln_eps, (__half *)hidden_out);
+    HIP_TRY(hipGetLastError());
+    return PETALS_OK;
+}
+
+int petals_client_lm_head(petals_client *c, const void *hidden_in, int32_t M, float *logits_out, int32_t *next_token_out,
+                          void *stream) {
+    if (!c || !hidden_in) return ps_fail(PETALS_ERR_INVALID_ARG, "null pointer");
+    if (!logits_out && !next_token_out) return ps_fail(PETALS_ERR_INVALID_ARG, "neither logits nor next tokens requested");
+    if (M < 1) return ps_fail(PETALS_ERR_INVALID_ARG, "M must be positive");
+    if (M > c->cfg.max_rows_per_call) return ps_fail(PETALS_ERR_CAPACITY, "%d rows exceed max_rows_per_call %d", M, c->cfg.max_rows_per_call);
+    hipStream_t st = (hipStream_t)stream;
+    const int H = c->cfg.hidden, V = c->cfg.vocab;
+    HIP_TRY(ps_layernorm((const __half *)hidden_in, (const __half *)c->p.final_ln_g, (const __half *)c->p.final_ln_b,
+                         c->cfg.ln_eps, M, H, c->a, nullptr, 0.0f, st));
+    const int rm = rows_per_pass(H);
+    const int groups = min(LM_GROUPS, (V + LM_WAVES - 1) / LM_WAVES);
+    const size_t lds = (size_t)rm * H * 8;
+    const int slot = rm == 4 ? 2 : (rm == 2 ? 1 : 0);
+    if (!c->lds_attr_set[slot]) {
+        const void *fn = rm == 4 ? (const void *)k_lm_head<4> : (rm == 2 ? (const void *)k_lm_head<2> : (const void *)k_lm_head<1>);
+        HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        c->lds_attr_set[slot] = true;
+    }
+    const __half *E = (const __half *)c->p.embeddings;
+    for (int m0 = 0; m0 < M; m0 += rm) {
+        const int rows = min(rm, M - m0);
+        const __half *a = c->a + (size_t)m0 * H;
+        float *lg = logits_out ? logits_out + (size_t)m0 * V : nullptr;
+        if (rm == 4) k_lm_head<4><<<groups, LM_THREADS, lds, st>>>(a, rows, E, V, H, lg, c->partial);
+        else if (rm == 2) k_lm_head<2><<<groups, LM_THREADS, lds, st>>>(a, rows, E, V, H, lg, c->partial);
+        else k_lm_head<1><<<groups, LM_THREADS, lds, st>>>(a, rows, E, V, H, lg, c->partial);
+        HIP_TRY(hipGetLastError());
+        if (next_token_out) {
+            k_lm_pick<<<rows, 64, 0, st>>>(c->partial, groups, next_token_out + m0);
+            HIP_TRY(hipGetLastError());
+        }
+    }
+    return PETALS_OK;
+}
+
+}  // extern "C"

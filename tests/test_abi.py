@@ -28,6 +28,22 @@ def test_library_exports_every_declared_symbol(b):
     assert declared == set(b.EXPORTS)
 
 
+def test_library_exports_every_symbol_of_the_client_header(b):
+    header = open(os.path.join(ROOT, "include", "petals_client.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(petals_[a-z0-9_]+)\s*\(", header))
+    assert len(declared) == 5
+    L = b.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert declared == set(b.CLIENT_EXPORTS)
+    # host-side checks that need no GPU
+    cfg = b.ClientConfig(250880, 14336, 1e-5, 4)
+    assert b.petals_client_workspace_bytes(cfg) >= 4 * 14336 * 2
+    with pytest.raises(b.PetalsError):
+        b.petals_client_workspace_bytes(b.ClientConfig(100, 100, 1e-5, 1))     # hidden not a multiple of 64
+
+
 def test_size_queries_match_the_layout_arithmetic(b):
     cfg = b.make_config(12, 14336, 112, 57344, 1)
     H = 14336

@@ -1,0 +1,110 @@
+"""GPU parity of the client-side ends of a generation step (embedding lookup + LayerNorm, final LayerNorm +
+tied LM head + greedy choice) against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2209_01188_amd import binding
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def h(x):
+    return np.asarray(x, dtype=np.float16)
+
+
+def to_dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def _model(seed, V, H):
+    r = np.random.default_rng(seed)
+    E = h(r.standard_normal((V, H)) * 0.05)
+    lg = [h(1.0 + 0.1 * r.standard_normal(H)), h(0.1 * r.standard_normal(H)),
+          h(1.0 + 0.1 * r.standard_normal(H)), h(0.1 * r.standard_normal(H))]
+    return r, E, lg
+
+
+# V: not a multiple of the 16 waves x 256 workgroups, more rows than one pass of workgroups covers;
+# H: 1 (H = 14336), 2 and 4 hidden rows per pass over the matrix, ragged last pass
+@pytest.mark.parametrize("V,H,M", [(1000, 64, 1), (5003, 1024, 5), (4099, 4096, 3), (9001, 8192, 3), (777, 14336, 2)])
+def test_embed_and_lm_head_match_the_oracle(V, H, M):
+    r, E, (eg, eb, fg, fb) = _model(V + H, V, H)
+    cl = binding.Client(to_dev(E), to_dev(eg), to_dev(eb), to_dev(fg), to_dev(fb), max_rows=M)
+    ids = r.integers(0, V, M).astype(np.int32)
+    ids[0], ids[-1] = V - 1, 0
+    got = cl.embed(to_dev(ids)).cpu().numpy()
+    ref = oracle.embed(ids, E, eg, eb)
+    assert np.array_equal(got.view(np.uint16), ref.view(np.uint16))
+
+    x = h(r.standard_normal((M, H)) * 2.0)
+    nxt, logits = cl.lm_head(to_dev(x), want_logits=True)
+    ref_next, ref_logits = oracle.lm_head(x, E, fg, fb, want_logits=True)
+    # greedy choice: decided on fp64 sums on both sides
+    assert np.array_equal(nxt.cpu().numpy(), ref_next)
+    # logits: fp64 sums rounded once to fp32 (different summation order: a few 1e-16 relative before the rounding)
+    lg = logits.cpu().numpy().astype(np.float64)
+    scale = np.abs(ref_logits).max()
+    assert np.abs(lg - ref_logits).max() <= 1.5e-7 * scale
+    assert (lg.astype(np.float32) == ref_logits.astype(np.float32)).mean() > 0.999
+    # next tokens alone (no logits buffer) give the same answer
+    assert np.array_equal(cl.lm_head(to_dev(x)).cpu().numpy(), ref_next)
+    cl.close()
+
+
+def test_equal_logits_resolve_to_the_lowest_token_id_and_ids_are_clamped():
+    V, H = 3000, 256
+    r, E, (eg, eb, fg, fb) = _model(9, V, H)
+    x = h(r.standard_normal((2, H)))
+    first = oracle.lm_head(x, E, fg, fb)
+    # duplicates of the winning rows far away in the matrix (another wave, another workgroup)
+    E2 = E.copy()
+    for t in range(2):
+        E2[(int(first[t]) + 1777) % V] = E[int(first[t])]
+    ref = oracle.lm_head(x, E2, fg, fb)
+    cl = binding.Client(to_dev(E2), to_dev(eg), to_dev(eb), to_dev(fg), to_dev(fb), max_rows=4)
+    assert np.array_equal(cl.lm_head(to_dev(x)).cpu().numpy(), ref)
+    assert all(int(ref[t]) == min(int(first[t]), (int(first[t]) + 1777) % V) for t in range(2))
+    # ids outside the table are clamped, not dereferenced
+    got = cl.embed(to_dev(np.array([-5, V + 100], np.int32))).cpu().numpy()
+    ref_e = oracle.embed(np.array([0, V - 1], np.int32), E2, eg, eb)
+    assert np.array_equal(got.view(np.uint16), ref_e.view(np.uint16))
+    with pytest.raises(binding.PetalsError):
+        cl.embed(to_dev(np.zeros(5, np.int32)))            # more rows than max_rows_per_call
+    cl.close()
+
+
+def test_greedy_generation_loop_stays_on_the_device_and_matches_the_oracle():
+    """embed -> span (2 small blocks) -> lm_head -> feed the chosen token back, 6 steps, token ids never leave
+    the GPU inside the loop; the oracle runs the same loop on the CPU."""
+    from paper_2209_01188_amd import synth
+    from tests.gpu_util import build_pair
+    cfg = synth.scaled(synth.CONFIGS["C2"], n_blocks=2)
+    V, H = 2000, cfg.hidden
+    r, E, (eg, eb, fg, fb) = _model(21, V, H)
+    E = h(E.astype(np.float64) * 20.0)                     # embedding rows of unit scale like hidden states
+    osp, gsp, _ = build_pair(cfg, n_blocks=2, max_rows=8)
+    cl = binding.Client(to_dev(E), to_dev(eg), to_dev(eb), to_dev(fg), to_dev(fb), max_rows=8)
+    prompt = r.integers(0, V, 8).astype(np.int32)
+    steps = 6
+    # oracle
+    ose = osp.open_session(8 + steps)
+    y = osp.step([ose], oracle.embed(prompt, E, eg, eb)[None])
+    tok = oracle.lm_head(y[0, -1:], E, fg, fb)
+    ref = [int(tok[0])]
+    for _ in range(steps - 1):
+        y = osp.step([ose], oracle.embed(tok, E, eg, eb)[None])
+        tok = oracle.lm_head(y[0], E, fg, fb)
+        ref.append(int(tok[0]))
+    # GPU
+    gse = gsp.open_session(8 + steps)
+    yg = gsp.prefill([gse], cl.embed(to_dev(prompt))[None])
+    out = torch.empty(steps, dtype=torch.int32, device=DEV)
+    cl.lm_head(yg[0, -1:], next_out=out[0:1])
+    for i in range(1, steps):
+        yg = gsp.decode_step([gse], cl.embed(out[i - 1:i]))
+        cl.lm_head(yg, next_out=out[i:i + 1])
+    assert out.cpu().tolist() == ref
+    cl.close(); gsp.close(); osp.destroy()
