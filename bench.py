@@ -49,9 +49,11 @@ def main():
     ap.add_argument("--prefix", type=int, default=2048, help="KV-cache prefix length of the headline figure")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile-events", action="store_true")
-    ap.add_argument("--mode", choices=["decode", "prefill", "batched"], default="decode",
+    ap.add_argument("--mode", choices=["decode", "prefill", "batched", "generate"], default="decode",
                     help="decode: the headline batch-1 decode benchmark; prefill: secondary, int8 MFMA GEMM regime; "
-                         "batched: secondary, several sessions per decode step")
+                         "batched: secondary, several sessions per decode step; generate: secondary, greedy "
+                         "generation loop with the client-side embedding and LM head on the same GPU")
+    ap.add_argument("--vocab", type=int, default=250880, help="generate mode: rows of the embedding matrix (BLOOM: 250880)")
     ap.add_argument("--batched-config", choices=["C3", "C5span"], default="C3",
                     help="batched mode: C3 = 30 BLOOM-7B1-shaped blocks, 8 sessions; C5span = one 12-block span of the "
                          "70-block BLOOM-176B-shaped stack, 32 sessions")
@@ -75,6 +77,8 @@ def main():
         return prefill_main(args, dev)
     if args.mode == "batched":
         return batched_main(args, dev)
+    if args.mode == "generate":
+        return generate_main(args, dev)
     cfg = synth.CONFIGS["C4"]
     H, F, nh, NB = cfg.hidden, cfg.F, cfg.n_heads, cfg.n_blocks
     K, W = args.steps, args.warmup
@@ -343,6 +347,97 @@ def batched_main(args, dev):
                      "kernel": "k_gemm (batched-decode int8 linear)", "launches": n_gemm},
         "cpu_baseline": None,
     }
+    span.close()
+    print(json.dumps(line))
+
+
+def generate_main(args, dev):
+    """Secondary benchmark: the greedy generation loop of the paper's Figure 2 on one GPU - embedding lookup,
+    one decode step through the 12-block BLOOM-176B-shaped span (KV prefix args.prefix), LM head over the tied
+    250880 x 14336 fp16 embedding matrix, and the chosen token fed back without leaving the device.  Reports
+    tokens/s of the whole loop and, for the LM-head kernel, streamed bytes per second against the HBM peak."""
+    import numpy as np
+    import torch
+    from paper_2209_01188_amd import binding, synth
+
+    cfg = synth.CONFIGS["C4"]
+    H, F, nh, NB, V = cfg.hidden, cfg.F, cfg.n_heads, cfg.n_blocks, args.vocab
+    K, W, L = args.steps, args.warmup, args.prefix
+    span = binding.Span(NB, H, nh, F, 1, 1e-5, 6.0, dev)
+    for b in range(NB):
+        span.load_block(b, synth.block_params_device(cfg, b, dev))
+    g = torch.Generator(device=dev)
+    g.manual_seed(1234)
+    E = torch.empty((V, H), dtype=torch.float16, device=dev)
+    for v0 in range(0, V, 16384):                         # unit-scale rows so the embedded vectors look like hidden states
+        E[v0:v0 + 16384] = torch.randn((min(16384, V - v0), H), generator=g, device=dev, dtype=torch.float32).to(torch.float16)
+    ln = [(1.0 + 0.02 * torch.randn(H, generator=g, device=dev)).to(torch.float16) if i % 2 == 0 else
+          (0.02 * torch.randn(H, generator=g, device=dev)).to(torch.float16) for i in range(4)]
+    cl = binding.Client(E, ln[0], ln[1], ln[2], ln[3], max_rows=1)
+    se = span.open_session(L + W + K + 2)
+    for b in range(NB):
+        se.import_kv(b, synth.kv_prefix_device(cfg, b, 0, L, 2.4, dev))
+    tok = torch.zeros(W + K + 1, dtype=torch.int32, device=dev)
+    tok[0] = 12345 % V
+    hid = torch.empty((1, H), dtype=torch.float16, device=dev)
+    out = torch.empty((1, H), dtype=torch.float16, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step(i):
+        cl.embed(tok[i:i + 1], out=hid)
+        span.decode_step([se], hid, out)
+        cl.lm_head(out, next_out=tok[i + 1:i + 2])
+
+    for i in range(W):
+        step(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for i in range(W, W + K):
+        step(i)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / K
+    # the LM head alone, bracketed by events on the same stream
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(8)]
+    nxt = torch.empty(1, dtype=torch.int32, device=dev)
+    for a, b_ in ev:
+        a.record(stream)
+        cl.lm_head(out, next_out=nxt)
+        b_.record(stream)
+    torch.cuda.synchronize()
+    lm_ms = sorted(a.elapsed_time(b_) for a, b_ in ev)[len(ev) // 2]
+    lm_bytes = V * H * 2
+    distinct = len(set(tok[W + 1:].cpu().tolist()))
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        sample = min(V, 32768)
+        Eh = E[:sample].cpu().numpy()
+        xh = out.cpu().numpy()
+        t0 = time.perf_counter()
+        ref = oracle.lm_head(xh, Eh, ln[2].cpu().numpy(), ln[3].cpu().numpy())
+        dt = time.perf_counter() - t0
+        sub = binding.Client(E[:sample], ln[0], ln[1], ln[2], ln[3], max_rows=1)
+        same = int(sub.lm_head(out).cpu()[0]) == int(ref[0])
+        sub.close()
+        cpu = {"value": round(1.0 / (dt * V / sample), 3), "unit": "LM-head evaluations/s", "cores": oracle.num_threads(),
+               "kind": "oracle", "sample": "LM head over the first %d of %d embedding rows (%.2f s), extrapolated; "
+               "GPU choice on the same rows %s the oracle's" % (sample, V, dt, "equals" if same else "DIFFERS FROM")}
+    line = {
+        "metric": "greedy generation tokens/s, client ends + 12-block BLOOM-176B span on one GPU (batch 1)",
+        "value": round(1e3 / ms, 2), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8 span, fp16 embeddings", "data": "synthetic",
+        "config": {"workload": "embedding lookup + LayerNorm, 12-block BLOOM-176B-shaped span decode step at KV prefix %d, "
+                               "final LayerNorm + tied LM head (%d x %d fp16) + greedy choice, token fed back on the device"
+                               % (L, V, H), "lm_head_ms": round(lm_ms, 4), "distinct_tokens_generated": distinct},
+        "roofline": {"bound": "hbm", "achieved": round(lm_bytes / (lm_ms * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(lm_bytes / (lm_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
+                     "kernel": "k_lm_head (LayerNorm and the final pick included in the timed call)"},
+        "cpu_baseline": cpu,
+    }
+    cl.close()
     span.close()
     print(json.dumps(line))
 
