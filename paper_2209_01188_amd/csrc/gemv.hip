@@ -55,7 +55,7 @@ __device__ __forceinline__ double outlier_group(const v4i &w, uint32_t bits, con
     return o;
 }
 
-constexpr int GEMV_THREADS = 512;    // 8 waves share one 16-row panel at a time
+constexpr int GEMV_GROUP = 512;      // 8 waves share one 16-row panel at a time
 
 // Persistent-style one-row linear.  The grid is sized so that every workgroup is resident at
 // once (up to two per compute unit) and owns a contiguous range of 16-row panels.  Each workgroup
@@ -66,21 +66,25 @@ constexpr int GEMV_THREADS = 512;    // 8 waves share one 16-row panel at a time
 //  3. streams its panels one after the other: the 8 waves split a panel's K/64 tiles in chunks of U
 //     consecutive tiles; lane l holds row l%16 and the 16 columns of group l/16, so one wave
 //     load is 1 KB contiguous; v_dot4_i32_i8 accumulates exactly.
-template <int U, int MAXCH, bool LN>
-__global__ void __launch_bounds__(GEMV_THREADS) k_gemv_row(LinearW w, RowIn in, OutDesc o,
-                                                           const SessTable *__restrict__ sess, int panels_per_wg,
-                                                           int panels_extra) {
+// NG = 2: one workgroup of 16 waves per compute unit, two groups of 8 waves working on two panels at a
+// time - the row is then prepared once per compute unit instead of twice, by twice the threads.
+template <int U, int MAXCH, bool LN, int NG>
+__global__ void __launch_bounds__(GEMV_GROUP * NG) k_gemv_row(LinearW w, RowIn in, OutDesc o,
+                                                             const SessTable *__restrict__ sess, int panels_per_wg,
+                                                             int panels_extra) {
+    constexpr int GEMV_THREADS = GEMV_GROUP * NG, NWV = GEMV_THREADS / 64;
     extern __shared__ __align__(16) unsigned char lds[];
-    __shared__ double smd[8];
-    __shared__ int smi[8];
+    __shared__ double smd[NWV];
+    __shared__ int smi[NWV];
     const int K = w.K, KT = K >> 6, nch8 = K >> 3;
     int8_t *xs = (int8_t *)lds;                               // K codes
     uint8_t *m8 = (uint8_t *)(lds + K);                       // K/8 mask bytes = K/16 group masks
-    int *red_i = (int *)(lds + K + K / 8);                    // [2 parities][8 waves][16]
-    double *red_f = (double *)(red_i + 256);                  // same shape
+    int *red_i = (int *)(lds + K + K / 8);                    // [2 parities][NG groups][8 waves][16]
+    double *red_f = (double *)(red_i + 256 * NG);             // same shape
     const uint16_t *ms = (const uint16_t *)m8;
     const bool first = blockIdx.x == 0;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, kg = lane >> 4, tw = wave;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, kg = lane >> 4;
+    const int grp = wave >> 3, tw = wave & 7;                 // group of 8 waves, wave inside the group
     // this workgroup's panels: [p0, p0 + np)
     const int g = blockIdx.x;
     const int np = panels_per_wg + (g < panels_extra ? 1 : 0);
@@ -89,8 +93,8 @@ __global__ void __launch_bounds__(GEMV_THREADS) k_gemv_row(LinearW w, RowIn in, 
 
     // start the first weight chunk now: HBM stays busy while the row is being quantized
     v4i wv[U];
-    if (tw < nchunks) {
-        const v4i *wp = (const v4i *)(w.wt + (size_t)p0 * KT * 1024) + lane;
+    if (tw < nchunks && grp < np) {
+        const v4i *wp = (const v4i *)(w.wt + (size_t)(p0 + grp) * KT * 1024) + lane;
 #pragma unroll
         for (int u = 0; u < U; u++) wv[u] = __builtin_nontemporal_load(wp + (size_t)(tw * U + u) * 64);
     }
@@ -104,14 +108,14 @@ __global__ void __launch_bounds__(GEMV_THREADS) k_gemv_row(LinearW w, RowIn in, 
 #pragma unroll
             for (int e = 0; e < 8; e++) s += (double)(float)v[e];
         }
-        mean = block_sum<8>(s, smd) / (double)K;
+        mean = block_sum<NWV>(s, smd) / (double)K;
         double q = 0.0;
         for (int c = threadIdx.x; c < nch8; c += GEMV_THREADS) {
             v8h v = *(const v8h *)(in.x + c * 8);
 #pragma unroll
             for (int e = 0; e < 8; e++) { const double a = (double)(float)v[e] - mean; q += a * a; }
         }
-        inv = 1.0 / sqrt(block_sum<8>(q, smd) / (double)K + (double)in.eps);
+        inv = 1.0 / sqrt(block_sum<NWV>(q, smd) / (double)K + (double)in.eps);
     } else {
         __syncthreads();      // mask bytes cleared before anybody sets one
     }
@@ -156,7 +160,7 @@ __global__ void __launch_bounds__(GEMV_THREADS) k_gemv_row(LinearW w, RowIn in, 
     if (lane == 0) smi[wave] = (int)mreg;
     __syncthreads();
 #pragma unroll
-    for (int i = 0; i < 8; i++) mreg = max(mreg, (uint32_t)smi[i]);
+    for (int i = 0; i < NWV; i++) mreg = max(mreg, (uint32_t)smi[i]);
     const unsigned short sb = (unsigned short)mreg;
     const float s_x = __half2float(*(const __half *)&sb);
     const float r = s_x > 0.0f ? 127.0f / s_x : 0.0f;
@@ -182,9 +186,9 @@ __global__ void __launch_bounds__(GEMV_THREADS) k_gemv_row(LinearW w, RowIn in, 
         if (in.mask_out) for (int i = threadIdx.x; i < K / 32; i += GEMV_THREADS) in.mask_out[i] = ((const uint32_t *)m8)[i];
     }
 
-    for (int it = 0; it < np; it++) {
-        const bool active = true;
-        const int p = p0 + it;
+    for (int it = 0; it * NG < np; it++) {
+        const bool active = it * NG + grp < np;        // the last round of an odd count leaves one group idle
+        const int p = p0 + min(it * NG + grp, np - 1);
         const v4i *wp = (const v4i *)(w.wt + (size_t)p * KT * 1024) + lane;
         const int n = p * 16 + (lane & 15);
         const float swd = w.sw[n] / 127.0f;
@@ -223,11 +227,11 @@ __global__ void __launch_bounds__(GEMV_THREADS) k_gemv_row(LinearW w, RowIn in, 
         acc += __shfl_xor(acc, 32);
         outl += __shfl_xor(outl, 16);
         outl += __shfl_xor(outl, 32);
-        int *ri = red_i + (it & 1) * 128;
-        double *rf = red_f + (it & 1) * 128;
-        if (lane < 16) { ri[wave * 16 + lane] = acc; rf[wave * 16 + lane] = outl; }
+        int *ri = red_i + ((it & 1) * NG + grp) * 128;
+        double *rf = red_f + ((it & 1) * NG + grp) * 128;
+        if (lane < 16) { ri[tw * 16 + lane] = acc; rf[tw * 16 + lane] = outl; }
         __syncthreads();
-        if (tw == 0 && lane < 16) {                    // lanes 0..15 of the first wave finish the 16 rows
+        if (active && tw == 0 && lane < 16) {          // lanes 0..15 of a group's first wave finish the 16 rows
             int a = 0;
             double f = 0.0;
 #pragma unroll
@@ -237,23 +241,42 @@ __global__ void __launch_bounds__(GEMV_THREADS) k_gemv_row(LinearW w, RowIn in, 
     }
 }
 
+template <int U, int MAXCH, int NG>
+hipError_t launch3(bool ln, const LinearW &w, const RowIn &in, const OutDesc &o, const SessTable *sess, hipStream_t st) {
+    const size_t lds = (size_t)w.K + w.K / 8 + 256 * 12 * NG;
+    // one resident round: at most 1024 threads' worth of workgroups per compute unit twice over (512 groups of
+    // 8 waves); prefer a split of the panels without remainder
+    const int panels = w.N / 16, units = panels / NG, max_wg = 512 / NG;
+    int G = min(max_wg, units);
+    for (int cand = G; cand >= max(1, (G * 3) / 4); cand--)
+        if (units % cand == 0) { G = cand; break; }
+    const int per = panels / G, extra = panels % G;
+    auto kern = ln ? k_gemv_row<U, MAXCH, true, NG> : k_gemv_row<U, MAXCH, false, NG>;
+    if (lds > 96 * 1024) return hipErrorInvalidValue;   // K <= 65536: at most 86 KB
+    if (lds > 64 * 1024) {
+        static bool attr_set[2] = {false, false};
+        if (!attr_set[ln]) {
+            hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+            if (e != hipSuccess) return e;
+            attr_set[ln] = true;
+        }
+    }
+    kern<<<G, GEMV_GROUP * NG, lds, st>>>(w, in, o, sess, per, extra);
+    return hipGetLastError();
+}
+
 template <int U, int MAXCH>
 hipError_t launch2(bool ln, const LinearW &w, const RowIn &in, const OutDesc &o, const SessTable *sess, hipStream_t st) {
-    const size_t lds = (size_t)w.K + w.K / 8 + 256 * 12;
-    // one resident round: at most 2 workgroups per compute unit; prefer a split without remainder
-    const int panels = w.N / 16, max_wg = 512;
-    int G = min(max_wg, panels);
-    for (int cand = G; cand >= max(1, (G * 3) / 4); cand--)
-        if (panels % cand == 0) { G = cand; break; }
-    const int per = panels / G, extra = panels % G;
-    if (ln) k_gemv_row<U, MAXCH, true><<<G, GEMV_THREADS, lds, st>>>(w, in, o, sess, per, extra);
-    else k_gemv_row<U, MAXCH, false><<<G, GEMV_THREADS, lds, st>>>(w, in, o, sess, per, extra);
-    return hipGetLastError();
+    // large linears: one 16-wave workgroup per compute unit (the row is prepared once per unit)
+    static const int ng_knob = getenv("PS_GEMV_NG") ? atoi(getenv("PS_GEMV_NG")) : 2;
+    const int panels = w.N / 16;
+    if (ng_knob == 2 && panels % 2 == 0 && panels >= 448 && MAXCH >= 4) return launch3<U, (MAXCH + 1) / 2, 2>(ln, w, in, o, sess, st);
+    return launch3<U, MAXCH, 1>(ln, w, in, o, sess, st);
 }
 
 template <int U>
 hipError_t launch1(bool ln, const LinearW &w, const RowIn &in, const OutDesc &o, const SessTable *sess, hipStream_t st) {
-    const int per_thread = (w.K / 8 + GEMV_THREADS - 1) / GEMV_THREADS;   // 8-column chunks a thread holds in registers
+    const int per_thread = (w.K / 8 + GEMV_GROUP - 1) / GEMV_GROUP;   // 8-column chunks a thread of an 8-wave workgroup holds in registers
     if (per_thread <= 1) return launch2<U, 1>(ln, w, in, o, sess, st);
     if (per_thread <= 4) return launch2<U, 4>(ln, w, in, o, sess, st);
     return launch2<U, 16>(ln, w, in, o, sess, st);
