@@ -42,7 +42,7 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(const __half *__restric
     const int L = sess->len[s], cap = sess->cap[s], H = nh * D;
     const __half *Kc = sess->kv[s] + ((size_t)blk * 2 * nh + h) * cap * D;
     const __half *Vc = Kc + (size_t)nh * cap * D;
-    const double slope = sess->slopes[h], rsd = sqrt((double)D);
+    const double slope = sess->slopes[h], inv_rsd = 1.0 / sqrt((double)D);
     const int last_key = L + T - 1;                   // newest key in the cache (already appended)
     const int tq = qt * 16 + c;                       // this lane's query row inside the session
     const int qpos = L + tq;                          // its absolute position
@@ -52,7 +52,7 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(const __half *__restric
     {
         const __half *qp = q + qrow * H + h * D + g * DS;
 #pragma unroll
-        for (int e = 0; e < DS; e++) qd[e] = (double)__half2float(qp[e]);
+        for (int e = 0; e < DS; e++) qd[e] = (double)__half2float(qp[e]) * inv_rsd;   // 1/sqrt(d) folded into the query
     }
     v4d O[NB];
 #pragma unroll
@@ -109,7 +109,7 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(const __half *__restric
 #pragma unroll
             for (int r = 0; r < 4; r++) {
                 const int kpos = kt * 16 + 4 * r + g;
-                sc[r] = (kpos <= qpos && kpos <= last_key) ? S[r] / rsd - slope * (double)(qpos - kpos) : -INFINITY;
+                sc[r] = (kpos <= qpos && kpos <= last_key) ? S[r] - slope * (double)(qpos - kpos) : -INFINITY;
                 mt = fmax(mt, sc[r]);
             }
             mt = fmax(mt, __shfl_xor(mt, 16));
@@ -186,14 +186,16 @@ __global__ void __launch_bounds__(256) k_attn_decode(const __half *__restrict__ 
     const int cap = sess->cap[s], H = nh * D;
     const __half *Kc = sess->kv[s] + ((size_t)blk * 2 * nh + h) * cap * D;
     const __half *Vc = Kc + (size_t)nh * cap * D;
-    const double slope = sess->slopes[h], rsd = sqrt((double)D);
+    // (q . k) / sqrt(d) is computed as (q / sqrt(d)) . k: one division per query element instead of one per key;
+    // the fp64 result moves by a few 1e-16 relative, far below the final fp16 rounding
+    const double slope = sess->slopes[h], inv_rsd = 1.0 / sqrt((double)D);
     const int per = (((k_end - k_begin + 3) >> 2) + 63) & ~63;
     const int wb = k_begin + wave * per, we = min(k_end, wb + per);
     double qf[8];
     {
         v8h qv = *(const v8h *)(q + (size_t)s * H + h * D + sub * 8);
 #pragma unroll
-        for (int e = 0; e < 8; e++) qf[e] = (double)(float)qv[e];
+        for (int e = 0; e < 8; e++) qf[e] = (double)(float)qv[e] * inv_rsd;   // 1/sqrt(d) folded into the query
     }
     double m_run = -INFINITY, l_run = 0.0, o[8];
 #pragma unroll
@@ -215,7 +217,7 @@ __global__ void __launch_bounds__(256) k_attn_decode(const __half *__restrict__ 
             for (int e = 0; e < 8; e++) dot += qf[e] * (double)(float)kv[it][e];
 #pragma unroll
             for (int off = 1; off < LPK; off <<= 1) dot += __shfl_xor(dot, off);
-            const double sc = (j < we) ? dot / rsd - slope * (double)(i - j) : -INFINITY;
+            const double sc = (j < we) ? dot - slope * (double)(i - j) : -INFINITY;
             mb = fmax(mb, sc);
             if (sub == it) sc_mine = sc;                       // lane `sub` of a group exponentiates key `it`
         }
