@@ -54,9 +54,10 @@ def main():
                          "batched: secondary, several sessions per decode step; generate: secondary, greedy "
                          "generation loop with the client-side embedding and LM head on the same GPU")
     ap.add_argument("--vocab", type=int, default=250880, help="generate mode: rows of the embedding matrix (BLOOM: 250880)")
-    ap.add_argument("--batched-config", choices=["C3", "C5span"], default="C3",
+    ap.add_argument("--batched-config", choices=["C3", "C5span", "C5"], default="C3",
                     help="batched mode: C3 = 30 BLOOM-7B1-shaped blocks, 8 sessions; C5span = one 12-block span of the "
-                         "70-block BLOOM-176B-shaped stack, 32 sessions")
+                         "70-block BLOOM-176B-shaped stack, 32 sessions; C5 = the whole 70-block stack (six chained "
+                         "spans, about 250 GB of HBM), 32 sessions")
     ap.add_argument("--prefill-batch", type=int, default=8, help="sessions in the prefill call (512 tokens each)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy, the known-size kernel that scales rocprofv3's "
@@ -266,6 +267,8 @@ def batched_main(args, dev):
     import torch
     from paper_2209_01188_amd import binding, synth
 
+    if args.batched_config == "C5":
+        return c5_main(args, dev)
     if args.batched_config == "C3":
         cfg, NB, B = synth.CONFIGS["C3"], synth.CONFIGS["C3"].n_blocks, synth.CONFIGS["C3"].batch
         name = "C3: 30-block BLOOM-7B1-shaped span (H=4096, 32 heads, F=16384), %d sessions" % B
@@ -349,6 +352,117 @@ def batched_main(args, dev):
         "cpu_baseline": None,
     }
     span.close()
+    print(json.dumps(line))
+
+
+def c5_main(args, dev):
+    """The whole 70-block BLOOM-176B-shaped stack on one GPU: six chained spans (12+12+12+12+12+10 blocks,
+    172.6 GB of int8 weights), 32 sessions, 512-token prompts (prefilled 8 sessions at a time), then decode steps;
+    the hidden states cross every span boundary, and the stack's input and output, as blockwise 8-bit codes."""
+    import numpy as np
+    import torch
+    from paper_2209_01188_amd import binding, synth
+
+    cfg = synth.CONFIGS["C5"]
+    H, F, nh, B, T = cfg.hidden, cfg.F, cfg.n_heads, cfg.batch, cfg.prompt
+    K, W = min(args.steps, cfg.decode), min(args.warmup, 4)
+    sizes = [12, 12, 12, 12, 12, 10]
+    chunk = 4096 // T
+    CB = 4096
+    t0 = time.time()
+    ws_cfg = binding.make_config(12, H, nh, F, chunk * T)
+    shared_ws = torch.empty(binding.petals_span_workspace_bytes(ws_cfg), dtype=torch.uint8, device=dev)
+    spans, blk = [], 0
+    for n in sizes:
+        sp = binding.Span(n, H, nh, F, chunk * T, 1e-5, 6.0, dev, workspace=shared_ws)
+        for b in range(n):
+            p = synth.block_params_device(cfg, blk, dev)
+            sp.load_block(b, p)
+            del p
+            blk += 1
+        torch.cuda.empty_cache()
+        spans.append(sp)
+        print("[bench] span %d: %d blocks loaded (%d so far, %.0f s, %.1f GB allocated)" %
+              (len(spans), n, blk, time.time() - t0, torch.cuda.memory_allocated() / 1e9), file=sys.stderr, flush=True)
+    cap = T + W + K + 2
+    ses = [[sp.open_session(cap) for _ in range(B)] for sp in spans]
+    print("[bench] KV caches for %d sessions x %d tokens: %.1f GB allocated" % (B, cap, torch.cuda.memory_allocated() / 1e9),
+          file=sys.stderr, flush=True)
+
+    def codec_buffers(rows):
+        n = rows * H
+        return (torch.empty(n, dtype=torch.uint8, device=dev), torch.empty((n + CB - 1) // CB, dtype=torch.float32, device=dev))
+
+    def through_stack(x_codes, x_absmax, rows_shape, sess_lists, scratch):
+        """codes in -> every span (dequantize, run, quantize) -> codes out"""
+        q, a = x_codes, x_absmax
+        hin, hout, qo, ao = scratch
+        for sp, ss in zip(spans, sess_lists):
+            binding.petals_hidden_dequantize(q, a, CB, hin)
+            if len(rows_shape) == 3:
+                binding.petals_span_prefill(sp.handle, [s.handle for s in ss], rows_shape[1], hin, hout)
+            else:
+                sp.decode_step(ss, hin, hout)
+            binding.petals_hidden_quantize(hout, CB, qo, ao)
+            q, a = qo, ao
+        return qo, ao
+
+    stream = torch.cuda.current_stream()
+    # prefill, 8 sessions per call
+    pre_scratch = (torch.empty((chunk, T, H), dtype=torch.float16, device=dev), torch.empty((chunk, T, H), dtype=torch.float16, device=dev),
+                   *codec_buffers(chunk * T))
+    qin, ain = codec_buffers(chunk * T)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    pre_ms = 0.0
+    Xall = synth.hidden_states(cfg, 0, B, T)
+    for s0 in range(0, B, chunk):
+        X = torch.from_numpy(Xall[s0:s0 + chunk]).to(dev)
+        binding.petals_hidden_quantize(X, CB, qin, ain)
+        torch.cuda.synchronize()
+        e0.record(stream)
+        through_stack(qin, ain, (chunk, T, H), [ss[s0:s0 + chunk] for ss in ses], pre_scratch)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        pre_ms += e0.elapsed_time(e1)
+    del pre_scratch, X, Xall
+    print("[bench] prefill of %d x %d tokens through 70 blocks: %.2f s" % (B, T, pre_ms / 1e3), file=sys.stderr, flush=True)
+    # decode
+    dec_scratch = (torch.empty((B, H), dtype=torch.float16, device=dev), torch.empty((B, H), dtype=torch.float16, device=dev),
+                   *codec_buffers(B))
+    codes = []
+    for i in range(W + K):
+        x = torch.from_numpy(synth.hidden_states(cfg, 1 + i, B, 1)[:, 0]).to(dev)
+        q, a = codec_buffers(B)
+        binding.petals_hidden_quantize(x, CB, q, a)
+        codes.append((q, a))
+    for i in range(W):
+        through_stack(codes[i][0], codes[i][1], (B, H), ses, dec_scratch)
+    torch.cuda.synchronize()
+    e0.record(stream)
+    for i in range(W, W + K):
+        through_stack(codes[i][0], codes[i][1], (B, H), ses, dec_scratch)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / K
+    L = T + W + K // 2
+    total_bytes = 70 * (12 * H * H + 62 * H) + B * 70 * (4 * (L + 1) * H + 4 * H) + 6 * 2 * B * H * 3
+    line = {
+        "metric": "decode tokens/s of the whole 70-block stack, all sessions together; achieved HBM GB/s",
+        "value": round(B / (ms * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "C5: 70 BLOOM-176B-shaped blocks as six chained spans (12+12+12+12+12+10) on one GPU, %d sessions, "
+                               "512-token prompts, one token per session per step, 8-bit codec at every span boundary" % B,
+                   "sessions": B, "hbm_gb_allocated": round(torch.cuda.max_memory_allocated() / 1e9, 1),
+                   "prefill_s": round(pre_ms / 1e3, 3), "prefill_tokens_per_s": round(B * T / (pre_ms / 1e3), 1),
+                   "achieved_hbm_gbs": round(total_bytes / (ms * 1e-3) / 1e9, 1),
+                   "hbm_frac_whole_step": round(total_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+        "roofline": {"bound": "hbm", "achieved": round(total_bytes / (ms * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(total_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
+                     "kernel": "whole decode step (weights + KV + codec bytes over its duration)"},
+        "cpu_baseline": None,
+    }
+    for sp in spans:
+        sp.close()
     print(json.dumps(line))
 
 

@@ -205,12 +205,18 @@ def petals_debug_import_kv(session, block, kv):
 
 class Span:
     def __init__(self, n_blocks, hidden, n_heads, ffn, max_rows_per_call, ln_eps=1e-5, outlier_threshold=6.0,
-                 device="cuda:0"):
+                 device="cuda:0", workspace=None):
+        """workspace: a uint8 tensor to use instead of a private one (spans that never run at the same time
+        may share it; nothing in it outlives a call)."""
         self.cfg = make_config(n_blocks, hidden, n_heads, ffn, max_rows_per_call, ln_eps, outlier_threshold)
         self.device = torch.device(device)
         self.n_blocks, self.hidden, self.n_heads, self.ffn = n_blocks, hidden, n_heads, ffn
         self.weight_mem = torch.empty(petals_span_weight_bytes(self.cfg), dtype=torch.uint8, device=self.device)
-        self.workspace = torch.empty(petals_span_workspace_bytes(self.cfg), dtype=torch.uint8, device=self.device)
+        need = petals_span_workspace_bytes(self.cfg)
+        if workspace is None:
+            workspace = torch.empty(need, dtype=torch.uint8, device=self.device)
+        assert workspace.numel() >= need and workspace.dtype == torch.uint8
+        self.workspace = workspace
         self.handle = petals_span_create(self.cfg, self.weight_mem, self.workspace)
         self.sessions = []
 
