@@ -16,17 +16,8 @@
 
 namespace {
 
-#ifndef PS_WVN
-#define PS_WVN 2
-#define PS_WVM 4
-#define PS_TN 8
-#define PS_TM 4
-#endif
 constexpr int STRIP = 4;       // m-blocks per rasterization strip
-#ifndef PS_NSLOT
-#define PS_NSLOT 4
-#endif
-constexpr int NSLOT = PS_NSLOT;       // LDS ring slots
+constexpr int NSLOT = 4;       // LDS ring slots
 constexpr int PD = NSLOT - 1;  // stages requested ahead
 
 // ---------------------------------------------------------------------------------------------
@@ -190,17 +181,8 @@ k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, 
         const unsigned char *base = lds + (size_t)(s % NSLOT) * STAGE * 1024 + lane * 16;
 #pragma unroll
         for (int i = 0; i < TN; i++) fa[i] = *(const v4i *)(base + (size_t)(wn * TN + i) * 1024);
-#ifdef PS_EXP_FEWER_LDS
-#pragma unroll
-        for (int j = 0; j < TM; j++) fb[j] = fa[j];
-#elif defined(PS_EXP_FEWEST_LDS)
-        fa[1] = fa[0]; fa[3] = fa[2]; fa[5] = fa[4]; fa[7] = fa[6];
-#pragma unroll
-        for (int j = 0; j < TM; j++) fb[j] = fa[2 * (j & 1)];
-#else
 #pragma unroll
         for (int j = 0; j < TM; j++) fb[j] = *(const v4i *)(base + (size_t)(BN + wm * TM + j) * 1024);
-#endif
     };
     for (int s = 0; s < PD && s < NS; s++) dma_stage(s);
 
@@ -450,7 +432,7 @@ k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, 
 template <bool F16>
 hipError_t launch_lds(const GemmArgs &ga0, const LinearW &w, const float *sx, const OutlierSet &os, float *outl,
                       const OutDesc &o, const SessTable *sess, hipStream_t st) {
-    constexpr int WVN = PS_WVN, WVM = PS_WVM, TN = PS_TN, TM = PS_TM, BN = WVN * TN, BM = WVM * TM;
+    constexpr int WVN = 2, WVM = 4, TN = 8, TM = 4, BN = WVN * TN, BM = WVM * TM;   // 8 waves, 128 x 64 per wave
     GemmArgs ga = ga0;
     const int NT = ga.N / 16, MTT = (ga.M + 15) / 16;
     ga.nb_n = (NT + BN - 1) / BN;

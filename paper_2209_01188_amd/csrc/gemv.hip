@@ -268,9 +268,8 @@ hipError_t launch3(bool ln, const LinearW &w, const RowIn &in, const OutDesc &o,
 template <int U, int MAXCH>
 hipError_t launch2(bool ln, const LinearW &w, const RowIn &in, const OutDesc &o, const SessTable *sess, hipStream_t st) {
     // large linears: one 16-wave workgroup per compute unit (the row is prepared once per unit)
-    static const int ng_knob = getenv("PS_GEMV_NG") ? atoi(getenv("PS_GEMV_NG")) : 2;
     const int panels = w.N / 16;
-    if (ng_knob == 2 && panels % 2 == 0 && panels >= 448 && MAXCH >= 4) return launch3<U, (MAXCH + 1) / 2, 2>(ln, w, in, o, sess, st);
+    if (panels % 2 == 0 && panels >= 448 && MAXCH >= 4) return launch3<U, (MAXCH + 1) / 2, 2>(ln, w, in, o, sess, st);
     return launch3<U, MAXCH, 1>(ln, w, in, o, sess, st);
 }
 
@@ -301,9 +300,8 @@ hipError_t ps_gemv_row(const LinearW &w, const __half *x, const __half *ln_g, co
     in.a_out = dbg.a_out; in.xq_out = dbg.xq_out; in.mask_out = dbg.mask_out; in.sx_out = dbg.sx_out;
     const bool ln = ln_g != nullptr;
     const int KT = w.K / 64;
-    static const int umax = getenv("PS_GEMV_U") ? atoi(getenv("PS_GEMV_U")) : 4;   // tuning knob: tiles per chunk
-    if (KT % 64 == 0 && umax >= 8) return launch1<8>(ln, w, in, o, sess, st);
-    if (KT % 32 == 0 && umax >= 4) return launch1<4>(ln, w, in, o, sess, st);
+    // tiles per chunk: 4 where the tile count allows (8 measured no faster and costs registers)
+    if (KT % 32 == 0) return launch1<4>(ln, w, in, o, sess, st);
     if (KT % 16 == 0) return launch1<2>(ln, w, in, o, sess, st);
     return launch1<1>(ln, w, in, o, sess, st);
 }
