@@ -232,6 +232,28 @@ def test_kv_import_then_decode_at_a_long_prefix():
     gsp.close(); osp.destroy()
 
 
+@pytest.mark.parametrize("hidden,heads", [(1024, 16), (512, 4), (256, 8)])      # head_dim 64, 128, 32
+def test_prefill_onto_a_filled_cache_and_ragged_batched_decode(hidden, heads):
+    """A prompt chunk of 150 tokens (three 64-query workgroups, ragged) appended to caches that already hold 37
+    and 101 tokens, then a decode step for three sessions of very different lengths (split key ranges)."""
+    cfg = synth.scaled(C2, n_blocks=1, hidden=hidden, n_heads=heads)
+    osp, gsp, _ = build_pair(cfg, n_blocks=1, max_rows=300)
+    lens = (37, 101, 900)
+    oses = [osp.open_session(1100) for _ in lens]
+    gses = [gsp.open_session(1100) for _ in lens]
+    for i, L in enumerate(lens):
+        kv = synth.kv_prefix(cfg, 0, i, L, std=1.5)
+        oses[i].import_kv(0, kv); gses[i].import_kv(0, to_dev(kv))
+    X = synth.hidden_states(cfg, 5, 2, 150)
+    hidden_close(to_np(gsp.prefill(gses[:2], to_dev(X))), osp.step(oses[:2], X), "prefill onto a filled cache")
+    assert [s.length for s in gses] == [187, 251, 900]
+    for b in range(1):
+        assert np.array_equal(to_np(gses[1].export_kv(b)).view(np.uint16), oses[1].export_kv(b).view(np.uint16))
+    x = synth.hidden_states(cfg, 6, 3, 1)
+    hidden_close(to_np(gsp.decode_step(gses, to_dev(x[:, 0])))[:, None], osp.step(oses, x), "ragged batched decode")
+    gsp.close(); osp.destroy()
+
+
 # -------------------------------------------------------------------- codec
 
 @pytest.mark.parametrize("n", [64, 4095, 4096, 4097, 14336, 8 * 14336 + 5])
