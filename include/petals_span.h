@@ -141,6 +141,22 @@ int petals_span_decode_step(petals_span *span, petals_session *const *sessions, 
                             const void *hidden_in, void *hidden_out, void *stream);
 
 /*
+ * Failure recovery (Section 2.1: clients "store past inputs to each server so that if any server
+ * fails ... another one can quickly take its place"; Section 3.2: "the client sends all previous
+ * inputs to the replacement server, so that it has the same attention keys and values").  Feeds the
+ * recorded inputs of ONE session into this span again, call by call: call_tokens[i] (HOST array,
+ * n_calls entries, each >= 1 and <= max_rows_per_call) is the number of tokens the i-th original call
+ * carried for this session, hidden_log (dev fp16 [sum of call_tokens, H]) their inputs in order.
+ * Keeping the call boundaries matters: the outlier columns of a linear are chosen per call, so only
+ * the same calls rebuild the same cache bit for bit (for sessions that were alone in their calls).
+ * scratch_out: dev fp16 [max over call_tokens, H], receives the outputs of the last replayed call.
+ * The session must be empty (length 0) and have room for all tokens.  On error the session may hold
+ * the calls replayed so far.
+ */
+int petals_session_replay(petals_span *span, petals_session *session, const void *hidden_log,
+                          const int32_t *call_tokens, int32_t n_calls, void *scratch_out, void *stream);
+
+/*
  * Dynamic blockwise 8-bit quantization of hidden states exchanged between
  * servers (Section 3.1 "Compressing communication buffers").  The flat buffer
  * of n fp16 values is cut into blocks of `block` consecutive elements (the last

@@ -56,7 +56,7 @@ EXPORTS = ["petals_span_weight_bytes", "petals_span_workspace_bytes", "petals_sp
            "petals_session_close", "petals_span_prefill", "petals_span_decode_step", "petals_hidden_quantize",
            "petals_hidden_dequantize", "petals_hidden_code_table", "petals_last_error", "petals_debug_linear",
            "petals_debug_export_weight", "petals_debug_export_kv", "petals_debug_import_kv",
-           "petals_span_profile_begin", "petals_span_profile_end", "petals_debug_layernorm"]
+           "petals_span_profile_begin", "petals_span_profile_end", "petals_debug_layernorm", "petals_session_replay"]
 CLIENT_EXPORTS = ["petals_client_workspace_bytes", "petals_client_create", "petals_client_destroy",
                   "petals_client_embed", "petals_client_lm_head"]
 PROFILE_GEMV, PROFILE_GEMM, PROFILE_ATTENTION, PROFILE_LINEAR0, PROFILE_CLASSES = 0, 1, 2, 3, 7
@@ -146,6 +146,12 @@ def petals_span_prefill(span, sessions, T, hidden_in, hidden_out):
 def petals_span_decode_step(span, sessions, hidden_in, hidden_out):
     _check(lib().petals_span_decode_step(span, _session_array(sessions), C.c_int32(len(sessions)),
                                          _ptr(hidden_in), _ptr(hidden_out), _stream()))
+
+
+def petals_session_replay(span, session, hidden_log, call_tokens, scratch_out):
+    arr = (C.c_int32 * len(call_tokens))(*call_tokens)
+    _check(lib().petals_session_replay(span, session, _ptr(hidden_log), arr, C.c_int32(len(call_tokens)),
+                                       _ptr(scratch_out), _stream()))
 
 
 def petals_hidden_quantize(x, block, q_out, absmax_out):

@@ -466,6 +466,28 @@ int petals_span_decode_step(petals_span *sp, petals_session *const *sessions, in
     return petals_span_prefill(sp, sessions, B, 1, hidden_in, hidden_out, stream);
 }
 
+int petals_session_replay(petals_span *sp, petals_session *se, const void *hidden_log, const int32_t *call_tokens,
+                          int32_t n_calls, void *scratch_out, void *stream) {
+    if (!sp || !se || !hidden_log || !call_tokens || !scratch_out) return fail(PETALS_ERR_INVALID_ARG, "null pointer");
+    if (se->span != sp) return fail(PETALS_ERR_INVALID_ARG, "session belongs to another span");
+    if (n_calls < 1) return fail(PETALS_ERR_INVALID_ARG, "n_calls must be positive");
+    if (se->len != 0) return fail(PETALS_ERR_STATE, "replay needs an empty session (length is %d)", se->len);
+    int64_t total = 0;
+    for (int i = 0; i < n_calls; i++) {
+        if (call_tokens[i] < 1 || call_tokens[i] > sp->cfg.max_rows_per_call)
+            return fail(PETALS_ERR_CAPACITY, "call %d carries %d tokens (allowed: 1..%d)", i, call_tokens[i], sp->cfg.max_rows_per_call);
+        total += call_tokens[i];
+    }
+    if (total > se->cap) return fail(PETALS_ERR_CAPACITY, "%lld recorded tokens > session capacity %d", (long long)total, se->cap);
+    const uint16_t *x = (const uint16_t *)hidden_log;
+    for (int i = 0; i < n_calls; i++) {
+        petals_session *one = se;
+        if (int rc = petals_span_prefill(sp, &one, 1, call_tokens[i], x, scratch_out, stream)) return rc;
+        x += (size_t)call_tokens[i] * sp->cfg.hidden;
+    }
+    return PETALS_OK;
+}
+
 int petals_hidden_code_table(float *host_table256) {
     if (!host_table256) return fail(PETALS_ERR_INVALID_ARG, "null pointer");
     memcpy(host_table256, code_table().code, sizeof(float) * 256);

@@ -254,6 +254,46 @@ def test_prefill_onto_a_filled_cache_and_ragged_batched_decode(hidden, heads):
     gsp.close(); osp.destroy()
 
 
+def test_replay_of_recorded_inputs_rebuilds_the_cache_bit_for_bit():
+    """Failure recovery (paper Section 3.2): the recorded inputs of a session, replayed call by call into a fresh
+    session, give the same keys and values and the same next output as the original."""
+    cfg = synth.scaled(C2, n_blocks=2)
+    osp, gsp, _ = build_pair(cfg, n_blocks=2, max_rows=16)
+    calls = [9, 1, 1, 4, 1]
+    log = np.concatenate([synth.hidden_states(cfg, i, 1, T)[0] for i, T in enumerate(calls)])
+    orig = gsp.open_session(32)
+    off, outs = 0, []
+    for T in calls:
+        outs.append(gsp.prefill([orig], to_dev(log[None, off:off + T])))
+        off += T
+    fresh = gsp.open_session(32)
+    scratch = torch.empty((max(calls), cfg.hidden), dtype=torch.float16, device=DEV)
+    binding.petals_session_replay(gsp.handle, fresh.handle, to_dev(log), calls, scratch)
+    assert fresh.length == orig.length == sum(calls)
+    for b in range(2):
+        assert torch.equal(fresh.export_kv(b), orig.export_kv(b))
+    assert torch.equal(scratch[:calls[-1]], outs[-1][0])
+    x = to_dev(synth.hidden_states(cfg, 9, 1, 1)[:, 0])
+    assert torch.equal(gsp.decode_step([fresh], x), gsp.decode_step([orig], x))
+    # against the oracle too (its sessions are fed the same calls)
+    ose = osp.open_session(32)
+    off = 0
+    for T in calls:
+        yo = osp.step([ose], log[None, off:off + T])
+        off += T
+    hidden_close(to_np(scratch[:calls[-1]])[None], yo, "replayed last call")
+    # argument checks: a used session, an oversized call, too many tokens
+    with pytest.raises(binding.PetalsError):
+        binding.petals_session_replay(gsp.handle, fresh.handle, to_dev(log), calls, scratch)
+    empty = gsp.open_session(8)
+    with pytest.raises(binding.PetalsError):
+        binding.petals_session_replay(gsp.handle, empty.handle, to_dev(log), [17], scratch)
+    with pytest.raises(binding.PetalsError):
+        binding.petals_session_replay(gsp.handle, empty.handle, to_dev(log), calls, scratch)
+    assert empty.length == 0
+    gsp.close(); osp.destroy()
+
+
 # -------------------------------------------------------------------- codec
 
 @pytest.mark.parametrize("n", [64, 4095, 4096, 4097, 14336, 8 * 14336 + 5])
