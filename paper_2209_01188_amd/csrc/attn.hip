@@ -1,11 +1,9 @@
-// ALiBi causal attention of query rows against the per-session key/value caches.
-// One workgroup per (key range, head, query row).  A key's head_dim values are spread
-// over head_dim/8 neighbouring lanes (16 bytes each), so one wave instruction reads
-// 1 KB of consecutive cache bytes; softmax runs online across 256-key tiles whose
-// scores and probabilities are staged in LDS.
+// ALiBi causal attention of query rows against the per-session key/value caches, fp64 throughout
+// (products of fp16 values are exact; the fp16 context equals the exactly rounded one).
+// Decode (one query per session): k_attn_decode, one workgroup per (key range, head, query row),
+// wave-local online softmax, k_attn_combine merges the key ranges.  Prefill (several queries per
+// session): k_attn_prefill on the fp64 matrix instruction.
 #include "common.h"
-#include <cstdlib>
-#include <stdlib.h>
 
 namespace {
 

@@ -83,7 +83,8 @@ __device__ __forceinline__ float half_of8(const v4i &x, int r) {   // r-th of th
 // 4*(l/16)+r of token l%16.  The next chunk's operands are requested before the current chunk is
 // multiplied.  xo: per token tile and k-tile, lane (token, column group) holds the values of the
 // group's first 8 outlier columns (written by ps_rowquant_tiled); a group with more takes the rest
-// from X.  The waves' partial sums meet in LDS as a tree.
+// from X.  The waves' partial sums meet in LDS once; up to four waves finish the (panel, token tile)
+// pairs.
 template <int WN, int MT, int UK, int WVK>
 __global__ void __launch_bounds__(64 * WVK)
 k_gemm(LinearW w, const int8_t *__restrict__ xq_tiled, const int8_t *__restrict__ xo_tiled,
