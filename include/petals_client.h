@@ -10,7 +10,8 @@
  * with the same embedding matrix (tied weights) on the way out.  These calls put
  * the two ends next to petals_span_* so a whole generation loop can stay on the
  * GPU; the conventions of petals_span.h (device pointers, caller-owned memory,
- * stream, error codes, petals_last_error) hold here too.
+ * stream, error codes, petals_last_error) hold here too.  One client handle (and its
+ * workspace) may be used by one stream at a time.
  */
 #ifndef PETALS_CLIENT_H
 #define PETALS_CLIENT_H
