@@ -68,7 +68,8 @@ int petals_client_embed(petals_client *client, const int32_t *token_ids, int32_t
  * logits_out: dev fp32 [M, V], may be NULL.  next_token_out: dev int32 [M], the first index
  * of the largest logit (greedy decoding), decided on the fp64 values; may be NULL if
  * logits_out is given.  hidden_in: dev fp16 [M, H].  The embedding matrix is streamed once
- * per group of rows that fits the compute units' local memory (1 row at H = 14336).
+ * per group of rows: 1 to 4 rows (what fits the compute units' local memory as fp64; 1 at
+ * H = 14336) for small M, 32 rows on the fp64 matrix instruction otherwise.
  */
 int petals_client_lm_head(petals_client *client, const void *hidden_in, int32_t M,
                           float *logits_out, int32_t *next_token_out, void *stream);

@@ -17,7 +17,7 @@ namespace {
 constexpr int LM_THREADS = 1024;           // 16 waves: enough 16-byte loads in flight for one workgroup per compute unit
 constexpr int LM_WAVES = LM_THREADS / 64;
 constexpr int LM_GROUPS = 256;             // workgroups of the LM head = partial results per row
-constexpr int LM_MAX_ROWS = 4;             // rows of hidden states multiplied per pass over the matrix
+constexpr int LM_MAX_ROWS = 32;            // rows of hidden states multiplied per pass over the matrix (matrix-core form)
 constexpr size_t LM_LDS_BUDGET = 128 * 1024;
 
 // One workgroup per token: gather the embedding row, LayerNorm in fp64, store fp16.
@@ -108,6 +108,85 @@ __global__ void __launch_bounds__(LM_THREADS) k_lm_head(const __half *__restrict
     if (threadIdx.x < RM) {
         Best r = wbest[0][threadIdx.x];
         for (int w = 1; w < LM_WAVES; w++) take_better(r, wbest[w][threadIdx.x].v, wbest[w][threadIdx.x].i);
+        partial[threadIdx.x * LM_GROUPS + blockIdx.x] = r;
+    }
+}
+
+// Several rows of hidden states at once: the same product on the fp64 matrix instruction (products of fp16
+// values are exact, sums in fp64 as in the one-row form).  A wave takes 16 matrix rows at a time as the A operand
+// and MT tiles of 16 hidden rows as the B operand; lane (row l%16, group l/16) loads 8 consecutive fp16 values
+// (16 bytes) of its matrix row and of its hidden row and feeds them to 8 instructions - any pairing of the
+// contraction index works as long as both operands use the same one.  Result register r of lane (g, c) is matrix
+// row 4r + g, hidden row c.  The matrix is streamed from HBM once per pass; the hidden rows come from L2.
+template <int MT>
+__global__ void __launch_bounds__(256) k_lm_head_mfma(const __half *__restrict__ a, int rows, const __half *__restrict__ E,
+                                                      int V, int H, float *__restrict__ logits, Best *__restrict__ partial) {
+    __shared__ Best wbest[4][MT * 16];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, c = lane & 15, g = lane >> 4;
+    const int ntiles = (V + 15) >> 4, nchunk = H >> 5;
+    const __half *ar[MT];
+#pragma unroll
+    for (int j = 0; j < MT; j++) ar[j] = a + (size_t)min(j * 16 + c, rows - 1) * H + g * 8;
+    Best best[MT];
+#pragma unroll
+    for (int j = 0; j < MT; j++) best[j] = Best{-INFINITY, 0x7fffffff};
+    for (int vt = blockIdx.x * 4 + wave; vt < ntiles; vt += gridDim.x * 4) {
+        const __half *er = E + (size_t)min(vt * 16 + c, V - 1) * H + g * 8;
+        v4d acc[MT];
+#pragma unroll
+        for (int j = 0; j < MT; j++) acc[j] = (v4d){0.0, 0.0, 0.0, 0.0};
+        for (int ch = 0; ch < nchunk; ch += 2) {          // H is a multiple of 64: two 32-column chunks per round
+            v8h e0 = __builtin_nontemporal_load((const v8h *)(er + (size_t)ch * 32));
+            v8h e1 = __builtin_nontemporal_load((const v8h *)(er + (size_t)(ch + 1) * 32));
+            v8h b0[MT], b1[MT];
+#pragma unroll
+            for (int j = 0; j < MT; j++) {
+                b0[j] = *(const v8h *)(ar[j] + (size_t)ch * 32);
+                b1[j] = *(const v8h *)(ar[j] + (size_t)(ch + 1) * 32);
+            }
+#pragma unroll
+            for (int q = 0; q < 8; q++) {
+                const double ea = (double)(float)e0[q];
+#pragma unroll
+                for (int j = 0; j < MT; j++)
+                    acc[j] = __builtin_amdgcn_mfma_f64_16x16x4f64(ea, (double)(float)b0[j][q], acc[j], 0, 0, 0);
+            }
+#pragma unroll
+            for (int q = 0; q < 8; q++) {
+                const double ea = (double)(float)e1[q];
+#pragma unroll
+                for (int j = 0; j < MT; j++)
+                    acc[j] = __builtin_amdgcn_mfma_f64_16x16x4f64(ea, (double)(float)b1[j][q], acc[j], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < MT; j++) {
+            const int t = j * 16 + c;
+#pragma unroll
+            for (int r = 0; r < 4; r++) {
+                const int v = vt * 16 + 4 * r + g;
+                if (t < rows && v < V) {
+                    if (logits) logits[(size_t)t * V + v] = (float)acc[j][r];
+                    take_better(best[j], acc[j][r], v);
+                }
+            }
+        }
+    }
+    // the four lane groups of a wave hold candidates of the same hidden rows, then the four waves
+#pragma unroll
+    for (int j = 0; j < MT; j++) {
+#pragma unroll
+        for (int off = 16; off < 64; off <<= 1) {
+            const double v2 = __shfl_xor(best[j].v, off);
+            const int i2 = __shfl_xor(best[j].i, off);
+            take_better(best[j], v2, i2);
+        }
+        if (g == 0) wbest[wave][j * 16 + c] = best[j];
+    }
+    __syncthreads();
+    if (threadIdx.x < MT * 16 && (int)threadIdx.x < rows) {
+        Best r = wbest[0][threadIdx.x];
+        for (int w2 = 1; w2 < 4; w2++) take_better(r, wbest[w2][threadIdx.x].v, wbest[w2][threadIdx.x].i);
         partial[threadIdx.x * LM_GROUPS + blockIdx.x] = r;
     }
 }
@@ -215,6 +294,25 @@ int petals_client_lm_head(petals_client *c, const void *hidden_in, int32_t M, fl
     HIP_TRY(ps_layernorm((const __half *)hidden_in, (const __half *)c->p.final_ln_g, (const __half *)c->p.final_ln_b,
                          c->cfg.ln_eps, M, H, c->a, nullptr, 0.0f, st));
     const int rm = rows_per_pass(H);
+    const __half *E = (const __half *)c->p.embeddings;
+    if (M > 4 * rm) {
+        // more rows than four passes of the one-row form cover (one matrix-core pass over 250880 x 14336 takes
+        // about as long as four of those): matrix-core form, up to 32 rows per pass
+        const int groups = min(LM_GROUPS, ((V + 15) / 16 + 3) / 4);
+        for (int m0 = 0; m0 < M; m0 += 32) {
+            const int rows = min(32, M - m0);
+            const __half *a = c->a + (size_t)m0 * H;
+            float *lg = logits_out ? logits_out + (size_t)m0 * V : nullptr;
+            if (rows > 16) k_lm_head_mfma<2><<<groups, 256, 0, st>>>(a, rows, E, V, H, lg, c->partial);
+            else k_lm_head_mfma<1><<<groups, 256, 0, st>>>(a, rows, E, V, H, lg, c->partial);
+            HIP_TRY(hipGetLastError());
+            if (next_token_out) {
+                k_lm_pick<<<rows, 64, 0, st>>>(c->partial, groups, next_token_out + m0);
+                HIP_TRY(hipGetLastError());
+            }
+        }
+        return PETALS_OK;
+    }
     const int groups = min(LM_GROUPS, (V + LM_WAVES - 1) / LM_WAVES);
     const size_t lds = (size_t)rm * H * 8;
     const int slot = rm == 4 ? 2 : (rm == 2 ? 1 : 0);
@@ -223,7 +321,6 @@ int petals_client_lm_head(petals_client *c, const void *hidden_in, int32_t M, fl
         HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         c->lds_attr_set[slot] = true;
     }
-    const __half *E = (const __half *)c->p.embeddings;
     for (int m0 = 0; m0 < M; m0 += rm) {
         const int rows = min(rm, M - m0);
         const __half *a = c->a + (size_t)m0 * H;

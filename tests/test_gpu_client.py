@@ -29,7 +29,9 @@ def _model(seed, V, H):
 
 # V: not a multiple of the 16 waves x 256 workgroups, more rows than one pass of workgroups covers;
 # H: 1 (H = 14336), 2 and 4 hidden rows per pass over the matrix, ragged last pass
-@pytest.mark.parametrize("V,H,M", [(1000, 64, 1), (5003, 1024, 5), (4099, 4096, 3), (9001, 8192, 3), (777, 14336, 2)])
+# more rows than four one-row passes cover go to the matrix-core form: 1 and 2 tiles of 16 hidden rows, two passes of 32
+@pytest.mark.parametrize("V,H,M", [(1000, 64, 1), (5003, 1024, 5), (4099, 4096, 3), (9001, 8192, 3), (777, 14336, 2),
+                                   (5003, 1024, 17), (4099, 1024, 20), (2001, 512, 40), (777, 14336, 5), (1501, 14336, 18)])
 def test_embed_and_lm_head_match_the_oracle(V, H, M):
     r, E, (eg, eb, fg, fb) = _model(V + H, V, H)
     cl = binding.Client(to_dev(E), to_dev(eg), to_dev(eb), to_dev(fg), to_dev(fb), max_rows=M)
