@@ -77,8 +77,11 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(const __half *__restric
 #pragma unroll
         for (int i = 0; i < NB; i++) {
             const int d = fd + i;
-            // keys: A operand of step e is K[key][g * DS + e] at lane (g, key)
-            kd[(d % DS) * 64 + (d / DS) * 16 + fk] = (double)__half2float(kraw[i]);
+            // keys: A operand of step e is K[key][g * DS + e] at lane (g, key); the 64 values of a step are
+            // rotated by 4 * (e / 8) positions so that the 64 threads of a wave, which write 4 steps, 4 lane
+            // groups and 4 keys at a time, spread over all LDS banks (reads stay 64 consecutive values)
+            const int e = d % DS;
+            kd[e * 64 + (((d / DS) * 16 + fk + 4 * (e >> 3)) & 63)] = (double)__half2float(kraw[i]);
             // values: A operand of step (r, b) is V[key 4r + g][c * NB + b] at lane (g, c)
             vd[((fk >> 2) * NB + i) * 64 + (fk & 3) * 16 + (threadIdx.x & 15)] = (double)__half2float(vraw[i]);
         }
@@ -89,7 +92,7 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(const __half *__restric
     for (int kt = 0; kt < nkt; kt++) {
         if (kt + 1 < nkt) fetch(kt + 1);              // in flight during the multiplications below
         if (kt < nkt_w) {
-            const double *kd = kvd + (size_t)(kt & 1) * 2 * TILE + lane, *vd = kd + TILE;
+            const double *kd0 = kvd + (size_t)(kt & 1) * 2 * TILE, *vd = kd0 + TILE + lane;
             // scores of 16 keys x 16 queries
             // (a dependent fp64 matrix instruction issues at about half the rate of independent ones:
             // up to four partial sums run side by side)
@@ -99,7 +102,7 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(const __half *__restric
             for (int i = 0; i < NCH; i++) Sp[i] = (v4d){0.0, 0.0, 0.0, 0.0};
 #pragma unroll
             for (int e = 0; e < DS; e++)
-                Sp[e % NCH] = __builtin_amdgcn_mfma_f64_16x16x4f64(kd[e * 64], qd[e], Sp[e % NCH], 0, 0, 0);
+                Sp[e % NCH] = __builtin_amdgcn_mfma_f64_16x16x4f64(kd0[e * 64 + ((lane + 4 * (e >> 3)) & 63)], qd[e], Sp[e % NCH], 0, 0, 0);
             v4d S = Sp[0];
 #pragma unroll
             for (int i = 1; i < NCH; i++) S += Sp[i];
