@@ -171,10 +171,10 @@ __global__ void __launch_bounds__(256) k_rowquant_tiled(const __half *__restrict
     }
 }
 
-// The same for calls of few rows, where one row per workgroup leaves most of the chip idle and the
-// latency of the loads is the whole cost: 1024 threads, each keeps its (at most 4) chunks of 16
-// columns in registers between the absolute-maximum pass and the quantization.
-__global__ void __launch_bounds__(1024) k_rowquant_tiled_few(const __half *__restrict__ X, int M, int K,
+// The same for wide rows (4096 <= K <= 65536): 1024 threads, each keeps its (at most 4) chunks of 16
+// columns in registers between the absolute-maximum pass and the quantization, so X is read once;
+// for calls of few rows, where the latency of the loads is the whole cost, this halves it.
+__global__ void __launch_bounds__(1024) k_rowquant_tiled_wide(const __half *__restrict__ X, int M, int K,
                                                              const uint32_t *__restrict__ mask,
                                                              int8_t *__restrict__ xq_tiled,
                                                              int8_t *__restrict__ xo_tiled, float *__restrict__ sx,
@@ -345,8 +345,8 @@ hipError_t ps_colmask(const __half *X, int M, int K, float theta, uint32_t *mask
 }
 hipError_t ps_rowquant_tiled(const __half *X, int M, int K, const uint32_t *mask, int8_t *xq_tiled, int8_t *xo_tiled,
                              float *sx, int8_t *xq_dbg, hipStream_t st) {
-    if (M <= 64 && K >= 4096 && K <= 65536)
-        k_rowquant_tiled_few<<<(M + 15) / 16 * 16, 1024, 0, st>>>(X, M, K, mask, xq_tiled, xo_tiled, sx, xq_dbg);
+    if (K >= 4096 && K <= 65536)   // wide rows: 1024 threads keep the row in registers, one pass over X
+        k_rowquant_tiled_wide<<<(M + 15) / 16 * 16, 1024, 0, st>>>(X, M, K, mask, xq_tiled, xo_tiled, sx, xq_dbg);
     else
         k_rowquant_tiled<<<(M + 15) / 16 * 16, 256, 0, st>>>(X, M, K, mask, xq_tiled, xo_tiled, sx, xq_dbg);
     return hipGetLastError();
