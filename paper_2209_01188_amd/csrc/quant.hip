@@ -84,6 +84,53 @@ __global__ void __launch_bounds__(NT) k_layernorm(const __half *__restrict__ x, 
     }
 }
 
+// The same with the row held in registers (4096 <= H <= 16384: at most 8 pairs per thread of 1024), so the
+// row is read from memory once instead of three times.  Same assignment of elements to threads and same
+// reduction order as k_layernorm: identical results.
+__global__ void __launch_bounds__(1024) k_layernorm_wide(const __half *__restrict__ x, const __half *__restrict__ g,
+                                                         const __half *__restrict__ b, float eps, int H,
+                                                         __half *__restrict__ y, uint32_t *__restrict__ mask,
+                                                         float theta) {
+    constexpr int NT = 1024, PER = 8;
+    __shared__ double sm[NT / 64];
+    const __half *xr = x + (size_t)blockIdx.x * H;
+    __half *yr = y + (size_t)blockIdx.x * H;
+    __half2 v[PER];
+    double s = 0.0;
+#pragma unroll
+    for (int i = 0; i < PER; i++) {
+        const int k = (threadIdx.x + i * NT) * 2;
+        if (k < H) {
+            v[i] = *(const __half2 *)(xr + k);
+            const float2 f = __half22float2(v[i]);
+            s += (double)f.x + (double)f.y;
+        }
+    }
+    const double mean = block_sum<NT / 64>(s, sm) / (double)H;
+    double q = 0.0;
+#pragma unroll
+    for (int i = 0; i < PER; i++) {
+        if ((threadIdx.x + i * NT) * 2 < H) {
+            const float2 f = __half22float2(v[i]);
+            const double a = (double)f.x - mean, c = (double)f.y - mean;
+            q += a * a + c * c;
+        }
+    }
+    const double inv = 1.0 / sqrt(block_sum<NT / 64>(q, sm) / (double)H + (double)eps);
+#pragma unroll
+    for (int i = 0; i < PER; i++) {
+        const int k = (threadIdx.x + i * NT) * 2;
+        if (k < H) {
+            const __half2 o = ln_affine(v[i], *(const __half2 *)(g + k), *(const __half2 *)(b + k), mean, inv);
+            *(__half2 *)(yr + k) = o;
+            if (mask) {
+                const uint32_t bits = (fabsf(__half2float(o.x)) >= theta ? 1u : 0u) | (fabsf(__half2float(o.y)) >= theta ? 2u : 0u);
+                flag_outlier_bits(mask, k >> 5, bits << (k & 31));
+            }
+        }
+    }
+}
+
 // -------------------------------------------------- many rows: mask, then quantize
 
 // Column c is an outlier if any row reaches theta.  grid.x covers columns (64 per
@@ -334,7 +381,8 @@ hipError_t ps_copy_bytes(const void *src, void *dst, size_t n, hipStream_t st) {
 hipError_t ps_layernorm(const __half *x, const __half *g, const __half *b, float eps, int M, int H, __half *y,
                         uint32_t *mask, float theta, hipStream_t st) {
     // few rows: more threads per row (latency), many rows: more rows in flight
-    if (M <= 256 && H >= 4096) k_layernorm<1024><<<M, 1024, 0, st>>>(x, g, b, eps, H, y, mask, theta);
+    if (H >= 4096 && H <= 16384) k_layernorm_wide<<<M, 1024, 0, st>>>(x, g, b, eps, H, y, mask, theta);
+    else if (M <= 256 && H >= 4096) k_layernorm<1024><<<M, 1024, 0, st>>>(x, g, b, eps, H, y, mask, theta);
     else k_layernorm<256><<<M, 256, 0, st>>>(x, g, b, eps, H, y, mask, theta);
     return hipGetLastError();
 }
