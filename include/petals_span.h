@@ -187,9 +187,37 @@ const char *petals_last_error(void);
 #define PETALS_PROFILE_GEMM      1  /* multi-row MFMA linear */
 #define PETALS_PROFILE_ATTENTION 2  /* attention incl. the merge of key ranges */
 #define PETALS_PROFILE_LINEAR0   3  /* 3..6: the same linear launches again, by linear (qkv, dense, up, down) */
-#define PETALS_PROFILE_CLASSES   7
+#define PETALS_PROFILE_BWD_GEMM       7  /* backward pass: fp16 product of a linear */
+#define PETALS_PROFILE_BWD_ATTENTION  8  /* backward pass: attention (transposed copies + both kernels) */
+#define PETALS_PROFILE_CLASSES   9
 int petals_span_profile_begin(petals_span *span, int32_t max_launches);
 int petals_span_profile_end(petals_span *span, double *ms_per_class, int64_t *launches_per_class);
+
+/* ------------------------------------------------------- backward pass */
+
+/*
+ * Backward pass through the frozen span (Section 2.2, "Distributed fine-tuning": servers "run
+ * backpropagation through their layers and return gradients with respect to activations", and never
+ * update their own parameters).  B sequences of T tokens each, every sequence attending only to itself
+ * (no session, no earlier cache).  The call runs the forward pass on hidden_in, keeping what the
+ * backward pass needs in dev_store, then backpropagates grad_out:
+ *   hidden_in  dev fp16 [B, T, H]  inputs of the span
+ *   grad_out   dev fp16 [B, T, H]  gradient of the loss w.r.t. the span's outputs
+ *   hidden_out dev fp16 [B, T, H]  the span's outputs (may be NULL)
+ *   grad_in    dev fp16 [B, T, H]  gradient w.r.t. hidden_in
+ * Arithmetic: the forward pass is petals_span_prefill's.  The derivative treats roundings and the int8
+ * quantization of activations as the identity; a linear's backward product uses the weights
+ * dequantized from int8 to fp16 (fp16 matrix instructions, fp32 accumulation); LayerNorm, softmax
+ * attention and GeLU are differentiated exactly; gradients of the GeLU input, of the attention context,
+ * of the fused query/key/value tensor and of the two residual streams are stored as fp16.  No loss
+ * scaling is applied: gradients far below 1e-4 in magnitude lose precision in fp16.
+ * dev_store: 256-byte aligned device memory of petals_span_backward_bytes(cfg, B, T) bytes, contents
+ * unspecified before and after.  B <= PETALS_MAX_SESSIONS_PER_CALL and B*T <= max_rows_per_call, else
+ * PETALS_ERR_CAPACITY.  The four tensors must not overlap.  Uses the span's workspace like any call.
+ */
+int petals_span_backward_bytes(const petals_span_config *cfg, int32_t B, int32_t T, size_t *bytes);
+int petals_span_backward(petals_span *span, void *dev_store, int32_t B, int32_t T, const void *hidden_in,
+                         const void *grad_out, void *hidden_out, void *grad_in, void *stream);
 
 /* ------------------------------------------------------------ test hooks */
 

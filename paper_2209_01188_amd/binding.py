@@ -56,10 +56,12 @@ EXPORTS = ["petals_span_weight_bytes", "petals_span_workspace_bytes", "petals_sp
            "petals_session_close", "petals_span_prefill", "petals_span_decode_step", "petals_hidden_quantize",
            "petals_hidden_dequantize", "petals_hidden_code_table", "petals_last_error", "petals_debug_linear",
            "petals_debug_export_weight", "petals_debug_export_kv", "petals_debug_import_kv",
-           "petals_span_profile_begin", "petals_span_profile_end", "petals_debug_layernorm", "petals_session_replay"]
+           "petals_span_profile_begin", "petals_span_profile_end", "petals_debug_layernorm", "petals_session_replay",
+           "petals_span_backward_bytes", "petals_span_backward"]
 CLIENT_EXPORTS = ["petals_client_workspace_bytes", "petals_client_create", "petals_client_destroy",
                   "petals_client_embed", "petals_client_lm_head"]
-PROFILE_GEMV, PROFILE_GEMM, PROFILE_ATTENTION, PROFILE_LINEAR0, PROFILE_CLASSES = 0, 1, 2, 3, 7
+PROFILE_GEMV, PROFILE_GEMM, PROFILE_ATTENTION, PROFILE_LINEAR0 = 0, 1, 2, 3
+PROFILE_BWD_GEMM, PROFILE_BWD_ATTENTION, PROFILE_CLASSES = 7, 8, 9
 
 
 def _check(rc):
@@ -194,6 +196,21 @@ def petals_debug_layernorm(span, block, which, x, y):
                                         _ptr(y), _stream()))
 
 
+def petals_span_backward_bytes(cfg, B, T):
+    n = C.c_size_t()
+    _check(lib().petals_span_backward_bytes(C.byref(cfg), C.c_int32(B), C.c_int32(T), C.byref(n)))
+    return n.value
+
+
+def petals_span_backward(span, store, hidden_in, grad_out, hidden_out, grad_in):
+    B, T, _ = hidden_in.shape
+    for t in (hidden_in, grad_out, grad_in) + (() if hidden_out is None else (hidden_out,)):
+        assert t.is_cuda and t.is_contiguous() and t.dtype == torch.float16 and t.shape == hidden_in.shape
+    assert store.is_cuda and store.dtype == torch.uint8
+    _check(lib().petals_span_backward(span, _ptr(store), C.c_int32(B), C.c_int32(T), _ptr(hidden_in), _ptr(grad_out),
+                                      _ptr(hidden_out), _ptr(grad_in), _stream()))
+
+
 def petals_debug_export_weight(span, block, which, wq, sw):
     _check(lib().petals_debug_export_weight(span, C.c_int32(block), C.c_int32(which), _ptr(wq), _ptr(sw), _stream()))
 
@@ -251,6 +268,19 @@ class Span:
         out = torch.empty_like(hidden_in) if out is None else out
         petals_span_decode_step(self.handle, [s.handle for s in sessions], hidden_in, out)
         return out
+
+    def backward(self, hidden_in, grad_out, store=None, want_output=True):
+        """Forward + backward of B sequences (hidden_in, grad_out fp16 [B,T,H]); returns (hidden_out, grad_in).
+        store: a uint8 tensor of at least petals_span_backward_bytes to reuse between calls."""
+        B, T, _ = hidden_in.shape
+        need = petals_span_backward_bytes(self.cfg, B, T)
+        if store is None:
+            store = torch.empty(need, dtype=torch.uint8, device=self.device)
+        assert store.numel() >= need
+        out = torch.empty_like(hidden_in) if want_output else None
+        grad_in = torch.empty_like(hidden_in)
+        petals_span_backward(self.handle, store, hidden_in, grad_out, out, grad_in)
+        return out, grad_in
 
     def debug_linear(self, block, which, x, epilogue=EPILOGUE_NONE, resid=None):
         N, K = self.shapes(which)

@@ -222,6 +222,14 @@ int run_linear(petals_span *sp, int which, const LinearW &w, const __half *X, co
     return PETALS_OK;
 }
 
+// What a forward pass keeps for the backward pass, per block: the block's input x[b] (x[n_blocks] is the
+// span's output), queries, the attention context before its fp16 rounding, x1 = x + attention branch, the sum
+// fed to GeLU, and the log of the softmax denominators.  Keys and values stay in the (internal) caches.
+struct SaveSet {
+    std::vector<__half *> x, q, x1, pre;
+    std::vector<float *> lse, ctx32;
+};
+
 OutDesc plain_out(__half *y, int epilogue, const __half *resid) {
     OutDesc o;
     memset(&o, 0, sizeof(o));
@@ -230,6 +238,124 @@ OutDesc plain_out(__half *y, int epilogue, const __half *resid) {
     o.resid = resid;
     o.T = 1;
     return o;
+}
+
+// The blocks of the span on M = B*T rows whose session table already sits in the workspace.
+// save == nullptr: intermediates live in the workspace.  Otherwise they are written where save says and
+// the up linear also stores the sum it feeds to GeLU.
+int forward_blocks(petals_span *sp, int M, int T, int max_keys, const __half *hidden_in, __half *hidden_out,
+                   const SaveSet *save, hipStream_t st) {
+    const petals_span_config &c = sp->cfg;
+    Workspace &ws = sp->ws;
+    const int H = c.hidden, nh = c.n_heads, d = H / nh;
+    // Multi-row calls: the outlier-column masks of all linears are cleared once; the kernel that writes a
+    // linear's input (LayerNorm, attention, the GeLU epilogue) flags the columns.  One-row calls detect
+    // the outliers inside the fused kernel.
+    const bool multi = M > 1;
+    const float theta = c.outlier_threshold;
+    if (multi) HIP_TRY(ps_fill_u32(ws.masks, (size_t)c.n_blocks * 4 * ws.mask_words, 0u, st));
+    const __half *x = hidden_in;
+    for (int b = 0; b < c.n_blocks; b++) {
+        const BlockW &W = sp->blocks[b];
+        __half *xout = (b == c.n_blocks - 1) ? hidden_out : (save ? save->x[b + 1] : ((b & 1) ? ws.xb : ws.xa));
+        __half *qb = save ? save->q[b] : ws.q, *ctxb = ws.ctx, *x1b = save ? save->x1[b] : ws.x1;
+        uint32_t *mk = ws.masks + (size_t)b * 4 * ws.mask_words;
+        OutDesc oq = plain_out(qb, PETALS_EPILOGUE_NONE, nullptr);
+        oq.scatter = 1; oq.T = T; oq.nh = nh; oq.d = d; oq.blk = b;
+        // LayerNorm 1 -> fused QKV (queries to qb, keys/values appended to the caches)
+        if (int rc = run_linear(sp, 0, W.lin[0], x, W.ln1g, W.ln1b, M, mk, multi, oq, nullptr, false, st)) return rc;
+        {
+            const bool pr = sp->prof.begin(PETALS_PROFILE_ATTENTION, -1, st);
+            HIP_TRY(ps_attention(qb, ws.table, b, M, T, nh, d, max_keys, ws.partials, ctxb,
+                                 multi ? mk + ws.mask_words : nullptr, theta, save ? save->lse[b] : nullptr,
+                                 save ? save->ctx32[b] : nullptr, st));
+            sp->prof.end(pr, st);
+        }
+        // dense + residual
+        if (int rc = run_linear(sp, 1, W.lin[1], ctxb, nullptr, nullptr, M, mk + ws.mask_words, multi,
+                                plain_out(x1b, PETALS_EPILOGUE_RESIDUAL, x), nullptr, false, st)) return rc;
+        // LayerNorm 2 -> up + GeLU -> down + residual
+        OutDesc ou = plain_out(ws.g, PETALS_EPILOGUE_GELU, nullptr);
+        if (multi) { ou.next_mask = mk + 3 * ws.mask_words; ou.next_theta = theta; }
+        if (save) ou.pre_out = save->pre[b];
+        if (int rc = run_linear(sp, 2, W.lin[2], x1b, W.ln2g, W.ln2b, M, mk + 2 * ws.mask_words, multi, ou, nullptr,
+                                false, st)) return rc;
+        if (int rc = run_linear(sp, 3, W.lin[3], ws.g, nullptr, nullptr, M, mk + 3 * ws.mask_words, multi,
+                                plain_out(xout, PETALS_EPILOGUE_RESIDUAL, x1b), nullptr, false, st)) return rc;
+        x = xout;
+    }
+    return PETALS_OK;
+}
+
+// Device memory of one backward call: what the forward pass keeps, the internal key/value memory of the
+// B sequences, and the scratch of the backward kernels.
+struct BackwardStore {
+    SaveSet save;
+    __half *kv;          // B sequences x [n_blocks][key|value][head][T][d]
+    size_t kv_per_seq;   // halves
+    __half *y_last;      // the span's output when the caller does not ask for it
+    __half *gy[2];       // gradient w.r.t. a block's input, alternating between blocks
+    __half *gx1;         // gradient w.r.t. x1
+    __half *tiles;       // gradient rows in matrix-instruction tile order, up to [ceil16(M), max(F, 3H)]
+    __half *wt16;        // transposed dequantized weights of one linear
+    float *out32;        // one backward product, up to [M, max(F, H)]
+    __half *dO, *dqkv, *QT, *KT, *dOT;
+    float *Dv;
+    size_t total;
+};
+
+BackwardStore carve_backward(const petals_span_config &c, int B, int T, uint8_t *base) {
+    BackwardStore s;
+    const size_t M = (size_t)B * T, Mp = (M + 15) / 16 * 16, Tp = ((size_t)T + 31) / 32 * 32, H = c.hidden, F = c.ffn;
+    const size_t Nmax = 3 * H > F ? 3 * H : F;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { uint8_t *p = base ? base + off : nullptr; off += align_up(bytes); return p; };
+    const int nb = c.n_blocks;
+    s.save.x.assign(nb + 1, nullptr);
+    s.save.q.resize(nb); s.save.ctx32.resize(nb); s.save.x1.resize(nb); s.save.pre.resize(nb); s.save.lse.resize(nb);
+    for (int b = 0; b < nb; b++) {
+        if (b > 0) s.save.x[b] = (__half *)take(M * H * 2);
+        s.save.q[b] = (__half *)take(M * H * 2);
+        s.save.ctx32[b] = (float *)take(M * H * 4);
+        s.save.x1[b] = (__half *)take(M * H * 2);
+        s.save.pre[b] = (__half *)take(M * F * 2);
+        s.save.lse[b] = (float *)take((size_t)c.n_heads * M * 4);
+    }
+    s.kv_per_seq = (size_t)nb * 2 * H * T;
+    s.kv = (__half *)take((size_t)B * s.kv_per_seq * 2);
+    s.y_last = (__half *)take(M * H * 2);
+    s.gy[0] = (__half *)take(M * H * 2);
+    s.gy[1] = (__half *)take(M * H * 2);
+    s.gx1 = (__half *)take(M * H * 2);
+    s.tiles = (__half *)take(Mp * Nmax * 2);
+    s.wt16 = (__half *)take(Nmax * H * 2);
+    s.out32 = (float *)take(M * (F > H ? F : H) * 4);
+    s.dO = (__half *)take(M * H * 2);
+    s.dqkv = (__half *)take(M * 3 * H * 2);
+    s.QT = (__half *)take((size_t)B * H * Tp * 2);
+    s.KT = (__half *)take((size_t)B * H * Tp * 2);
+    s.dOT = (__half *)take((size_t)B * H * Tp * 2);
+    s.Dv = (float *)take((size_t)c.n_heads * M * 4);
+    s.total = off;
+    return s;
+}
+
+int check_backward_shape(const petals_span_config &c, int32_t B, int32_t T) {
+    if (B < 1 || T < 1) return fail(PETALS_ERR_INVALID_ARG, "B and T must be positive");
+    if (B > PETALS_MAX_SESSIONS_PER_CALL) return fail(PETALS_ERR_CAPACITY, "more than %d sequences in one call", PETALS_MAX_SESSIONS_PER_CALL);
+    if ((int64_t)B * T > c.max_rows_per_call)
+        return fail(PETALS_ERR_CAPACITY, "%lld rows exceed max_rows_per_call %d", (long long)B * T, c.max_rows_per_call);
+    return PETALS_OK;
+}
+
+// dX[M, K] (fp32, into out32) = rows (already in tile order) x dequantized weights of linear w
+int backward_product(petals_span *sp, int which, const LinearW &w, const __half *row_tiles, int M, BackwardStore &bs,
+                     hipStream_t st) {
+    HIP_TRY(ps_transpose_w(w, bs.wt16, st));
+    const bool pr = sp->prof.begin(PETALS_PROFILE_BWD_GEMM, which, st);
+    HIP_TRY(ps_gemm_f16_tiles(bs.wt16, row_tiles, w.N / 32, M, w.K, bs.out32, st));
+    sp->prof.end(pr, st);
+    return PETALS_OK;
 }
 
 }  // namespace
@@ -422,41 +548,9 @@ int petals_span_prefill(petals_span *sp, petals_session *const *sessions, int32_
 
     hipStream_t st = (hipStream_t)stream;
     Workspace &ws = sp->ws;
-    const int M = B * T, H = c.hidden, F = c.ffn, nh = c.n_heads, d = H / nh;
+    const int M = B * T;
     HIP_TRY(ps_set_table(tab, ws.table, st));
-    // Multi-row calls: the outlier-column masks of all linears are cleared once; the kernel that writes a
-    // linear's input (LayerNorm, attention, the GeLU epilogue) flags the columns.  One-row calls detect
-    // the outliers inside the fused kernel.
-    const bool multi = M > 1;
-    const float theta = c.outlier_threshold;
-    if (multi) HIP_TRY(ps_fill_u32(ws.masks, (size_t)c.n_blocks * 4 * ws.mask_words, 0u, st));
-    const __half *x = (const __half *)hidden_in;
-    for (int b = 0; b < c.n_blocks; b++) {
-        const BlockW &W = sp->blocks[b];
-        __half *xout = (b == c.n_blocks - 1) ? (__half *)hidden_out : ((b & 1) ? ws.xb : ws.xa);
-        uint32_t *mk = ws.masks + (size_t)b * 4 * ws.mask_words;
-        OutDesc oq = plain_out(ws.q, PETALS_EPILOGUE_NONE, nullptr);
-        oq.scatter = 1; oq.T = T; oq.nh = nh; oq.d = d; oq.blk = b;
-        // LayerNorm 1 -> fused QKV (queries to ws.q, keys/values appended to the caches)
-        if (int rc = run_linear(sp, 0, W.lin[0], x, W.ln1g, W.ln1b, M, mk, multi, oq, nullptr, false, st)) return rc;
-        {
-            const bool pr = sp->prof.begin(PETALS_PROFILE_ATTENTION, -1, st);
-            HIP_TRY(ps_attention(ws.q, ws.table, b, M, T, nh, d, max_keys, ws.partials, ws.ctx,
-                                 multi ? mk + ws.mask_words : nullptr, theta, st));
-            sp->prof.end(pr, st);
-        }
-        // dense + residual
-        if (int rc = run_linear(sp, 1, W.lin[1], ws.ctx, nullptr, nullptr, M, mk + ws.mask_words, multi,
-                                plain_out(ws.x1, PETALS_EPILOGUE_RESIDUAL, x), nullptr, false, st)) return rc;
-        // LayerNorm 2 -> up + GeLU -> down + residual
-        OutDesc ou = plain_out(ws.g, PETALS_EPILOGUE_GELU, nullptr);
-        if (multi) { ou.next_mask = mk + 3 * ws.mask_words; ou.next_theta = theta; }
-        if (int rc = run_linear(sp, 2, W.lin[2], ws.x1, W.ln2g, W.ln2b, M, mk + 2 * ws.mask_words, multi, ou, nullptr,
-                                false, st)) return rc;
-        if (int rc = run_linear(sp, 3, W.lin[3], ws.g, nullptr, nullptr, M, mk + 3 * ws.mask_words, multi,
-                                plain_out(xout, PETALS_EPILOGUE_RESIDUAL, ws.x1), nullptr, false, st)) return rc;
-        x = xout;
-    }
+    if (int rc = forward_blocks(sp, M, T, max_keys, (const __half *)hidden_in, (__half *)hidden_out, nullptr, st)) return rc;
     for (int s = 0; s < B; s++) sessions[s]->len += T;
     return PETALS_OK;
 }
@@ -484,6 +578,75 @@ int petals_session_replay(petals_span *sp, petals_session *se, const void *hidde
         petals_session *one = se;
         if (int rc = petals_span_prefill(sp, &one, 1, call_tokens[i], x, scratch_out, stream)) return rc;
         x += (size_t)call_tokens[i] * sp->cfg.hidden;
+    }
+    return PETALS_OK;
+}
+
+int petals_span_backward_bytes(const petals_span_config *cfg, int32_t B, int32_t T, size_t *bytes) {
+    if (int rc = check_config(cfg)) return rc;
+    if (!bytes) return fail(PETALS_ERR_INVALID_ARG, "bytes is null");
+    if (int rc = check_backward_shape(*cfg, B, T)) return rc;
+    *bytes = carve_backward(*cfg, B, T, nullptr).total;
+    return PETALS_OK;
+}
+
+int petals_span_backward(petals_span *sp, void *dev_store, int32_t B, int32_t T, const void *hidden_in,
+                         const void *grad_out, void *hidden_out, void *grad_in, void *stream) {
+    if (!sp || !dev_store || !hidden_in || !grad_out || !grad_in) return fail(PETALS_ERR_INVALID_ARG, "null pointer");
+    if ((uintptr_t)dev_store & 255) return fail(PETALS_ERR_INVALID_ARG, "store memory must be 256-byte aligned");
+    if (grad_in == grad_out || grad_in == hidden_in || (hidden_out && (hidden_out == hidden_in || hidden_out == grad_in || hidden_out == grad_out)))
+        return fail(PETALS_ERR_INVALID_ARG, "buffers alias");
+    const petals_span_config &c = sp->cfg;
+    if (int rc = check_backward_shape(c, B, T)) return rc;
+    for (int b = 0; b < c.n_blocks; b++)
+        if (!sp->blocks[b].loaded) return fail(PETALS_ERR_STATE, "block %d has not been loaded", b);
+    BackwardStore bs = carve_backward(c, B, T, (uint8_t *)dev_store);
+    bs.save.x[0] = (__half *)hidden_in;      // read only
+    __half *y = hidden_out ? (__half *)hidden_out : bs.y_last;
+    bs.save.x[c.n_blocks] = y;
+
+    // forward pass on fresh internal sequences of exactly T positions
+    SessTable tab;
+    memset(&tab, 0, sizeof(tab));
+    for (int s = 0; s < B; s++) {
+        tab.kv[s] = bs.kv + (size_t)s * bs.kv_per_seq;
+        tab.len[s] = 0;
+        tab.cap[s] = T;
+    }
+    memcpy(tab.slopes, sp->slopes, sizeof(tab.slopes));
+    hipStream_t st = (hipStream_t)stream;
+    Workspace &ws = sp->ws;
+    const int M = B * T, H = c.hidden, F = c.ffn, nh = c.n_heads, d = H / nh;
+    HIP_TRY(ps_set_table(tab, ws.table, st));
+    if (int rc = forward_blocks(sp, M, T, T, (const __half *)hidden_in, y, &bs.save, st)) return rc;
+
+    // backward, last block first; gy: gradient w.r.t. the output of the block at hand
+    const __half *gy = (const __half *)grad_out;
+    for (int b = c.n_blocks - 1; b >= 0; b--) {
+        const BlockW &W = sp->blocks[b];
+        // x2 = x1 + down(GeLU(pre)):  dpre = (gy Wd_down) * GeLU'(pre), written in tile order
+        HIP_TRY(ps_tile_rows(gy, M, H, bs.tiles, st));
+        if (int rc = backward_product(sp, 3, W.lin[3], bs.tiles, M, bs, st)) return rc;
+        HIP_TRY(ps_gelu_bwd(bs.out32, bs.save.pre[b], M, F, bs.tiles, st));
+        // pre = up(LayerNorm2(x1)):  dx1 = gy + LayerNorm2'(dpre Wd_up)
+        if (int rc = backward_product(sp, 2, W.lin[2], bs.tiles, M, bs, st)) return rc;
+        HIP_TRY(ps_ln_bwd(bs.out32, bs.save.x1[b], W.ln2g, gy, c.ln_eps, M, H, bs.gx1, st));
+        // x1 = x + dense(ctx):  dctx = dx1 Wd_dense
+        HIP_TRY(ps_tile_rows(bs.gx1, M, H, bs.tiles, st));
+        if (int rc = backward_product(sp, 1, W.lin[1], bs.tiles, M, bs, st)) return rc;
+        HIP_TRY(ps_attn_bwd_prep(bs.out32, bs.save.ctx32[b], M, nh, d, bs.dO, bs.Dv, st));
+        {
+            const bool pr = sp->prof.begin(PETALS_PROFILE_BWD_ATTENTION, -1, st);
+            HIP_TRY(ps_attention_bwd(bs.save.q[b], ws.table, b, B, T, nh, d, bs.dO, bs.QT, bs.KT, bs.dOT, bs.save.lse[b],
+                                     bs.Dv, bs.dqkv, st));
+            sp->prof.end(pr, st);
+        }
+        // qkv = Lin(LayerNorm1(x)):  dx = dx1 + LayerNorm1'(dqkv Wd_qkv)
+        HIP_TRY(ps_tile_rows(bs.dqkv, M, 3 * H, bs.tiles, st));
+        if (int rc = backward_product(sp, 0, W.lin[0], bs.tiles, M, bs, st)) return rc;
+        __half *gx = b == 0 ? (__half *)grad_in : bs.gy[b & 1];
+        HIP_TRY(ps_ln_bwd(bs.out32, bs.save.x[b], W.ln1g, bs.gx1, c.ln_eps, M, H, gx, st));
+        gy = gx;
     }
     return PETALS_OK;
 }

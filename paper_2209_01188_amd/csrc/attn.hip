@@ -31,7 +31,8 @@ __global__ void k_set_table(SessTable t, SessTable *dst) {
 template <int D>
 __global__ void __launch_bounds__(256, 2) k_attn_prefill(const __half *__restrict__ q, const SessTable *__restrict__ sess,
                                                          int blk, int T, int nh, __half *__restrict__ ctx,
-                                                         uint32_t *__restrict__ mask, float theta) {
+                                                         uint32_t *__restrict__ mask, float theta,
+                                                         float *__restrict__ lse, float *__restrict__ ctx32) {
     constexpr int DS = D / 4, NB = D / 16;           // dims per lane group; output blocks of 16 dims
     constexpr int TILE = 16 * D;                     // fp64 values of one key or value tile
     extern __shared__ __align__(16) double kvd[];    // [2 buffers][keys | values][TILE]
@@ -138,6 +139,8 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(const __half *__restric
     }
     l_run += __shfl_xor(l_run, 16);
     l_run += __shfl_xor(l_run, 32);
+    // log of the softmax denominator, kept for the backward pass: [head][row of the call]
+    if (lse && tq < T && g == 0) lse[(size_t)h * gridDim.z * T + qrow] = (float)(m_run + log(l_run));
     if (tq < T) {
         // O[b][r] = output dim (4r + g) * NB + b of query c: NB consecutive dims per (r, g)
         __half *dst = ctx + qrow * H + h * D;
@@ -150,6 +153,10 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(const __half *__restric
             for (int b = 0; b < NB; b++) {
                 dst[(4 * r + g) * NB + b] = out[b];
                 flag_outlier(mask, theta, h * D + (4 * r + g) * NB + b, out[b]);
+            }
+            if (ctx32) {   // the context before its fp16 rounding, for the backward pass
+#pragma unroll
+                for (int b = 0; b < NB; b++) ctx32[qrow * H + h * D + (4 * r + g) * NB + b] = (float)(O[b][r] / l_run);
             }
         }
     }
@@ -303,7 +310,7 @@ __global__ void k_attn_combine(const SessTable *__restrict__ sess, int T, int nh
 
 template <int D>
 hipError_t attn_launch(const __half *q, const SessTable *sess, int blk, int M, int T, int nh, int max_keys,
-                       double *partials, __half *ctx, uint32_t *mask, float theta, hipStream_t st) {
+                       double *partials, __half *ctx, uint32_t *mask, float theta, float *lse, float *ctx32, hipStream_t st) {
     // Split the key range only as far as rows*heads alone leave the GPU short of about two workgroups per
     // compute unit (the kernel is bound by its fp64 arithmetic and by latency, not by the number of workgroups:
     // measured on 112 heads and 2048 keys, 4 ranges beat 9 and 16), at least 128 keys per range.
@@ -313,8 +320,8 @@ hipError_t attn_launch(const __half *q, const SessTable *sess, int blk, int M, i
     if ((size_t)M * nh * nsplit > PS_ATTN_PARTIAL_SLOTS) nsplit = 1;
     int CH = ((max_keys + nsplit - 1) / nsplit + 63) / 64 * 64;
     if (nsplit == 1) CH = 1 << 30;
-    if (T > 1) {
-        k_attn_prefill<D><<<dim3((T + 63) / 64, nh, M / T), 256, (size_t)2 * 2 * 16 * D * 8, st>>>(q, sess, blk, T, nh, ctx, mask, theta);
+    if (T > 1 || lse) {   // the matrix-core kernel also covers T = 1; it is the one that can report the denominators
+        k_attn_prefill<D><<<dim3((T + 63) / 64, nh, M / T), 256, (size_t)2 * 2 * 16 * D * 8, st>>>(q, sess, blk, T, nh, ctx, mask, theta, lse, ctx32);
         return hipGetLastError();
     }
     k_attn_decode<D><<<dim3(nsplit, nh, M), 256, 0, st>>>(q, sess, blk, nh, CH, nsplit, partials, ctx, mask, theta);
@@ -332,12 +339,13 @@ hipError_t ps_set_table(const SessTable &host_table, SessTable *dev_table, hipSt
 }
 
 hipError_t ps_attention(const __half *q, const SessTable *sess, int blk, int M, int T, int nh, int d, int max_keys,
-                        double *partials, __half *ctx, uint32_t *mask, float theta, hipStream_t st) {
+                        double *partials, __half *ctx, uint32_t *mask, float theta, float *lse, float *ctx32,
+                        hipStream_t st) {
     switch (d) {
-        case 16: return attn_launch<16>(q, sess, blk, M, T, nh, max_keys, partials, ctx, mask, theta, st);
-        case 32: return attn_launch<32>(q, sess, blk, M, T, nh, max_keys, partials, ctx, mask, theta, st);
-        case 64: return attn_launch<64>(q, sess, blk, M, T, nh, max_keys, partials, ctx, mask, theta, st);
-        case 128: return attn_launch<128>(q, sess, blk, M, T, nh, max_keys, partials, ctx, mask, theta, st);
+        case 16: return attn_launch<16>(q, sess, blk, M, T, nh, max_keys, partials, ctx, mask, theta, lse, ctx32, st);
+        case 32: return attn_launch<32>(q, sess, blk, M, T, nh, max_keys, partials, ctx, mask, theta, lse, ctx32, st);
+        case 64: return attn_launch<64>(q, sess, blk, M, T, nh, max_keys, partials, ctx, mask, theta, lse, ctx32, st);
+        case 128: return attn_launch<128>(q, sess, blk, M, T, nh, max_keys, partials, ctx, mask, theta, lse, ctx32, st);
     }
     return hipErrorInvalidValue;
 }

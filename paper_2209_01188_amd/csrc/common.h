@@ -49,6 +49,7 @@ struct OutDesc {
     int T, nh, d, blk;    // scatter: row t belongs to session t / T at position len + t % T of block blk
     uint32_t *next_mask;  // optional (scatter == 0): outlier-column bit mask [N/32] of the linear that reads y
     float next_theta;     // a column of y is flagged when any |y| >= next_theta
+    __half *pre_out;      // optional (scatter == 0): [M,N] copy of the sum BEFORE the fused GeLU / residual
 };
 
 struct CodeTable { float code[256]; };
@@ -117,8 +118,29 @@ hipError_t ps_set_table(const SessTable &host_table, SessTable *dev_table, hipSt
 #define PS_ATTN_MAX_SPLITS 16
 #define PS_ATTN_PARTIAL_SLOTS 8192   // (row, head, split) triples that may need a partial result
 // mask (may be null): outlier-column bits of ctx are ORed into it (|ctx| >= theta)
+// lse, ctx32 (both null, or both given): for the backward pass, fp32 [nh][M] log of the softmax denominator of
+// every (head, row) and fp32 [M, nh*d] context before its fp16 rounding
 hipError_t ps_attention(const __half *q, const SessTable *sess, int blk, int M, int T, int nh, int d, int max_keys,
-                        double *partials, __half *ctx, uint32_t *mask, float theta, hipStream_t st);
+                        double *partials, __half *ctx, uint32_t *mask, float theta, float *lse, float *ctx32,
+                        hipStream_t st);
+
+// --- backward pass (gradients w.r.t. activations) ---
+// fp16 [M,N] row-major -> 16 x 32 tiles in v_mfma_f32_16x16x32_f16 operand order, rows padded to 16 with zeros
+hipError_t ps_tile_rows(const __half *X, int M, int N, __half *tiles, hipStream_t st);
+// the linear's dequantized fp16 weights, transposed, in the same tile order: [K/16][N/32][512 halves]
+hipError_t ps_transpose_w(const LinearW &w, __half *wt16, hipStream_t st);
+// out[M, n_feat] (fp32) = token tiles [ceil(M/16)][ktiles] x feature tiles [n_feat/16][ktiles], contraction 32 * ktiles
+hipError_t ps_gemm_f16_tiles(const __half *feat_tiles, const __half *tok_tiles, int ktiles, int M, int n_feat,
+                             float *out, hipStream_t st);
+hipError_t ps_gelu_bwd(const float *dg, const __half *pre, int M, int N, __half *tiles, hipStream_t st);
+hipError_t ps_ln_bwd(const float *dz, const __half *x, const __half *g, const __half *dres, float eps, int M, int H,
+                     __half *dx, hipStream_t st);
+hipError_t ps_attn_bwd_prep(const float *dctx, const float *ctx32, int M, int nh, int d, __half *dO, float *Dv,
+                            hipStream_t st);
+// QT, KT, dOT: scratch [B][nh][d][ceil(T/32)*32] halves each; dqkv [B*T, 3*nh*d] in the fused-QKV column order
+hipError_t ps_attention_bwd(const __half *q, const SessTable *sess, int blk, int B, int T, int nh, int d, const __half *dO,
+                            __half *QT, __half *KT, __half *dOT, const float *lse, const float *Dv, __half *dqkv,
+                            hipStream_t st);
 
 hipError_t ps_hidden_quantize(const __half *x, size_t n, int block, const CodeTable &tab, uint8_t *q, float *absmax,
                               hipStream_t st);

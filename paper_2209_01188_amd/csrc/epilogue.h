@@ -8,6 +8,7 @@ __device__ __forceinline__ void emit_output(const OutDesc &o, const SessTable *_
     // fp64 here costs nothing next to the weight stream and makes the single fp16 rounding land on
     // the same value as an exact evaluation except in ~1e-12 of the cases
     double v = (double)acc * (double)sxd * (double)swd + outl + (double)bias;
+    if (o.pre_out) o.pre_out[(size_t)t * N + n] = d2h_rn(v);
     if (o.epilogue == 1) v = gelu_tanh(v);
     else if (o.epilogue == 2) v += (double)__half2float(o.resid[(size_t)t * N + n]);
     const __half hv = d2h_rn(v);
@@ -39,15 +40,17 @@ __device__ __forceinline__ void emit_output4(const OutDesc &o, const SessTable *
     const float swv[4] = {s4.x, s4.y, s4.z, s4.w};
     v4h r4 = {(_Float16)0, (_Float16)0, (_Float16)0, (_Float16)0};
     if (o.epilogue == 2) r4 = *(const v4h *)(o.resid + (size_t)t * N + n0);
-    __half out[4];
+    __half out[4], pre[4];
 #pragma unroll
     for (int r = 0; r < 4; r++) {
         double v = (double)acc[r] * (double)sxd * (double)(swv[r] / 127.0f) + outl[r] + (double)(float)b4[r];
+        if (o.pre_out) pre[r] = d2h_rn(v);
         if (o.epilogue == 1) v = gelu_tanh(v);
         else if (o.epilogue == 2) v += (double)(float)r4[r];
         out[r] = d2h_rn(v);
     }
     if (o.acc_out) *(v4i *)(o.acc_out + (size_t)t * N + n0) = acc;
+    if (o.pre_out) *(v2i *)(o.pre_out + (size_t)t * N + n0) = *(const v2i *)pre;
     __half *dst;
     if (!o.scatter) {
         dst = o.y + (size_t)t * N + n0;

@@ -106,7 +106,7 @@ __global__ void __launch_bounds__(64) k_gather_w(LinearW w, const int *__restric
 struct GemmArgs {
     const unsigned char *a_tiles;   // weight-side tiles: [N/16][KTILES][1024]
     const unsigned char *b_tiles;   // token-side tiles:  [ceil(M/16)][KTILES][1024]
-    int ktiles;                     // int8: K/64.  fp16: unused (derived from the outlier count)
+    int ktiles;                     // int8: K/64.  fp16: 0 = derived from the outlier count, else the plain product's tile count
     int M, N;
     int nb_n, nb_m;
 };
@@ -119,8 +119,10 @@ k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, 
     constexpr int NW = WVN * WVM, BN = WVN * TN, BM = WVM * TM, STAGE = BN + BM, LOADS = STAGE / NW;
     static_assert(STAGE % NW == 0, "every wave copies the same number of tiles per stage");
     extern __shared__ __align__(16) unsigned char lds[];
-    const int n_out = *os.count;
-    const bool many = n_out > PS_EXACT_OUTLIERS;
+    // F16 with a tile count given: a plain fp16 product over ga.ktiles tiles (backward pass), no outlier set
+    const bool plain16 = F16 && ga.ktiles > 0;
+    const int n_out = plain16 ? ga.ktiles * 32 : *os.count;
+    const bool many = plain16 || n_out > PS_EXACT_OUTLIERS;
     if (F16 && !many) return;
     // k-tiles to walk (64 int8 or 32 fp16 columns each).  If EVERY column is an outlier all int8 codes are
     // zero: the int8 product is skipped and only the epilogue runs.
@@ -394,15 +396,17 @@ k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, 
                     if (t < 0) continue;
                     v4h r4 = {(_Float16)0, (_Float16)0, (_Float16)0, (_Float16)0};
                     if (o.epilogue == 2) r4 = *(const v4h *)(rrow[j] + n0);
-                    __half out[4];
+                    __half out[4], pre[4];
 #pragma unroll
                     for (int r = 0; r < 4; r++) {
                         double v = (double)a4[r] * sxd[j] * swd4[r] + od[r] + bias4[r];
+                        if (o.pre_out) pre[r] = d2h_rn(v);
                         if (o.epilogue == 1) v = gelu_tanh(v);
                         else if (o.epilogue == 2) v += (double)(float)r4[r];
                         out[r] = d2h_rn(v);
                     }
                     if (o.acc_out) *(v4i *)(o.acc_out + (size_t)t * N + n0) = a4;
+                    if (o.pre_out) *(v2i *)(o.pre_out + (size_t)t * N + n0) = *(const v2i *)pre;
                     __half *dst;
                     if (sc.x < 0) {
                         dst = yrow[j] + sc.y;
@@ -453,6 +457,19 @@ hipError_t launch_lds(const GemmArgs &ga0, const LinearW &w, const float *sx, co
 }
 
 }  // namespace
+
+hipError_t ps_gemm_f16_tiles(const __half *feat_tiles, const __half *tok_tiles, int ktiles, int M, int n_feat,
+                             float *out, hipStream_t st) {
+    if (ktiles < 1 || M < 1 || n_feat < 16 || n_feat % 16) return hipErrorInvalidValue;
+    GemmArgs ga = {(const unsigned char *)feat_tiles, (const unsigned char *)tok_tiles, ktiles, M, n_feat, 0, 0};
+    LinearW w;
+    OutlierSet os;
+    OutDesc o;
+    memset(&w, 0, sizeof(w));
+    memset(&os, 0, sizeof(os));
+    memset(&o, 0, sizeof(o));
+    return launch_lds<true>(ga, w, nullptr, os, out, o, nullptr, st);
+}
 
 hipError_t ps_gemm_lds(const LinearW &w, const int8_t *xq_tiled, const uint32_t *mask, const __half *X, const float *sx,
                        int M, const OutlierSet &os, const ManyOutliers &mo, const OutDesc &o, const SessTable *sess,
