@@ -49,10 +49,11 @@ def main():
     ap.add_argument("--prefix", type=int, default=2048, help="KV-cache prefix length of the headline figure")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile-events", action="store_true")
-    ap.add_argument("--mode", choices=["decode", "prefill", "batched", "generate"], default="decode",
+    ap.add_argument("--mode", choices=["decode", "prefill", "batched", "generate", "backward"], default="decode",
                     help="decode: the headline batch-1 decode benchmark; prefill: secondary, int8 MFMA GEMM regime; "
                          "batched: secondary, several sessions per decode step; generate: secondary, greedy "
-                         "generation loop with the client-side embedding and LM head on the same GPU")
+                         "generation loop with the client-side embedding and LM head on the same GPU; backward: secondary, "
+                         "forward + backward (gradients w.r.t. activations) of a fine-tuning batch")
     ap.add_argument("--vocab", type=int, default=250880, help="generate mode: rows of the embedding matrix (BLOOM: 250880)")
     ap.add_argument("--batched-config", choices=["C3", "C5span", "C5"], default="C3",
                     help="batched mode: C3 = 30 BLOOM-7B1-shaped blocks, 8 sessions; C5span = one 12-block span of the "
@@ -80,6 +81,8 @@ def main():
         return batched_main(args, dev)
     if args.mode == "generate":
         return generate_main(args, dev)
+    if args.mode == "backward":
+        return backward_main(args, dev)
     cfg = synth.CONFIGS["C4"]
     H, F, nh, NB = cfg.hidden, cfg.F, cfg.n_heads, cfg.n_blocks
     K, W = args.steps, args.warmup
@@ -251,6 +254,69 @@ def prefill_main(args, dev):
                                         enumerate(("qkv", "dense", "up", "down"))}},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 1), "peak": 5000.0, "unit": "TOP/s",
                      "frac": round(achieved / 5000.0, 4), "traffic": None, "kernel": "k_gemm_lds (qkv and up linears)"},
+        "cpu_baseline": None,
+    }
+    span.close()
+    print(json.dumps(line))
+
+
+def backward_main(args, dev):
+    """Secondary benchmark: one fine-tuning call (forward + backward w.r.t. activations) of sessions x 512 tokens
+    through a 12-block BLOOM-176B-shaped span.  One step = one petals_span_backward call.  Reports tokens/s and,
+    for the dominant kernel of the backward half (the fp16 MFMA product dY Wd of the four linears), TFLOP/s
+    against the 2.5 PFLOP/s dense fp16 peak."""
+    import torch
+    from paper_2209_01188_amd import binding, synth
+
+    cfg = synth.CONFIGS["C4"]
+    H, F, nh, NB = cfg.hidden, cfg.F, cfg.n_heads, cfg.n_blocks
+    B, T = args.prefill_batch, 512
+    M = B * T
+    K_steps, W = max(1, min(args.steps, 3)), max(1, min(args.warmup, 1))
+    span = binding.Span(NB, H, nh, F, M, 1e-5, 6.0, dev)
+    for b in range(NB):
+        span.load_block(b, synth.block_params_device(cfg, b, dev))
+    X = torch.from_numpy(synth.hidden_states(cfg, 0, B, T)).to(dev)
+    g = torch.Generator(device=dev)
+    g.manual_seed(1234)
+    dY = torch.empty(X.shape, dtype=torch.float32, device=dev).normal_(0.0, 1.0, generator=g).to(torch.float16)
+    store = torch.empty(binding.petals_span_backward_bytes(span.cfg, B, T), dtype=torch.uint8, device=dev)
+    out, gin = torch.empty_like(X), torch.empty_like(X)
+    stream = torch.cuda.current_stream()
+    for _ in range(W):
+        binding.petals_span_backward(span.handle, store, X, dY, out, gin)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(K_steps):
+        binding.petals_span_backward(span.handle, store, X, dY, out, gin)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / K_steps
+    binding.petals_span_profile_begin(span.handle, NB * 16)
+    binding.petals_span_backward(span.handle, store, X, dY, out, gin)
+    torch.cuda.synchronize()
+    pm, pn = binding.petals_span_profile_end(span.handle)
+    flops = sum(2.0 * M * n * k for n, k in (span.shapes(i) for i in range(4))) * NB
+    bwd_gemm_ms = pm[binding.PROFILE_BWD_GEMM]
+    achieved = flops / (bwd_gemm_ms * 1e-3) / 1e12
+    fwd_ms = pm[binding.PROFILE_GEMM] + pm[binding.PROFILE_ATTENTION]
+    line = {
+        "metric": "fine-tuning tokens/s (forward + backward w.r.t. activations) per 12-block BLOOM-176B span",
+        "value": round(M / (ms * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": K_steps, "warmup": W,
+        "ms_per_step": round(ms, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
+        "data": "synthetic",
+        "config": {"workload": "12-block BLOOM-176B-shaped span (H=14336, F=57344), %d sequences x 512 tokens "
+                               "(%d rows per linear), forward then backward" % (B, M),
+                   "store_gb": round(store.numel() / 1e9, 2),
+                   "per_call_ms": {"forward_linears_and_attention": round(fwd_ms, 2),
+                                   "backward_products": round(bwd_gemm_ms, 2),
+                                   "backward_attention": round(pm[binding.PROFILE_BWD_ATTENTION], 2)}},
+        "roofline": {"bound": "mfma", "achieved": round(achieved, 1), "peak": 2500.0, "unit": "TFLOP/s",
+                     "frac": round(achieved / 2500.0, 4), "traffic": None,
+                     "kernel": "k_gemm_lds<fp16> (backward products of the four linears)",
+                     "avg_launch_us": round(bwd_gemm_ms * 1e3 / max(pn[binding.PROFILE_BWD_GEMM], 1), 1),
+                     "launches": pn[binding.PROFILE_BWD_GEMM]},
         "cpu_baseline": None,
     }
     span.close()
