@@ -251,6 +251,15 @@ int petals_debug_export_kv(const petals_session *session, int32_t block, void *o
 int petals_debug_import_kv(petals_session *session, int32_t block, const void *in, int32_t len,
                            void *stream);
 
+/*
+ * The backward product of ONE linear of a loaded block (Section 2.2), through the kernels
+ * petals_span_backward uses for B*T rows: dx [B*T, K] fp32 = dy [B*T, N] fp16 times the linear's
+ * weights dequantized from int8 to fp16 ([N, K]; which as in petals_debug_linear).  dev_store: as for
+ * petals_span_backward with the same B and T (used as scratch).
+ */
+int petals_debug_backward_product(petals_span *span, void *dev_store, int32_t B, int32_t T, int32_t block,
+                                  int32_t which, const void *dy, float *dx, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -57,7 +57,7 @@ EXPORTS = ["petals_span_weight_bytes", "petals_span_workspace_bytes", "petals_sp
            "petals_hidden_dequantize", "petals_hidden_code_table", "petals_last_error", "petals_debug_linear",
            "petals_debug_export_weight", "petals_debug_export_kv", "petals_debug_import_kv",
            "petals_span_profile_begin", "petals_span_profile_end", "petals_debug_layernorm", "petals_session_replay",
-           "petals_span_backward_bytes", "petals_span_backward"]
+           "petals_span_backward_bytes", "petals_span_backward", "petals_debug_backward_product"]
 CLIENT_EXPORTS = ["petals_client_workspace_bytes", "petals_client_create", "petals_client_destroy",
                   "petals_client_embed", "petals_client_lm_head"]
 PROFILE_GEMV, PROFILE_GEMM, PROFILE_ATTENTION, PROFILE_LINEAR0 = 0, 1, 2, 3
@@ -209,6 +209,13 @@ def petals_span_backward(span, store, hidden_in, grad_out, hidden_out, grad_in):
     assert store.is_cuda and store.dtype == torch.uint8
     _check(lib().petals_span_backward(span, _ptr(store), C.c_int32(B), C.c_int32(T), _ptr(hidden_in), _ptr(grad_out),
                                       _ptr(hidden_out), _ptr(grad_in), _stream()))
+
+
+def petals_debug_backward_product(span, store, B, T, block, which, dy, dx):
+    assert dy.is_cuda and dy.is_contiguous() and dy.dtype == torch.float16 and dy.shape[0] == B * T
+    assert dx.is_cuda and dx.is_contiguous() and dx.dtype == torch.float32 and dx.shape[0] == B * T
+    _check(lib().petals_debug_backward_product(span, _ptr(store), C.c_int32(B), C.c_int32(T), C.c_int32(block),
+                                               C.c_int32(which), _ptr(dy), _ptr(dx), _stream()))
 
 
 def petals_debug_export_weight(span, block, which, wq, sw):

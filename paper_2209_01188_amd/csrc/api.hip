@@ -694,6 +694,23 @@ int petals_debug_linear(petals_span *sp, int32_t block, int32_t which, const voi
     return PETALS_OK;
 }
 
+int petals_debug_backward_product(petals_span *sp, void *dev_store, int32_t B, int32_t T, int32_t block, int32_t which,
+                                  const void *dy, float *dx, void *stream) {
+    if (!sp || !dev_store || !dy || !dx) return fail(PETALS_ERR_INVALID_ARG, "null pointer");
+    if ((uintptr_t)dev_store & 255) return fail(PETALS_ERR_INVALID_ARG, "store memory must be 256-byte aligned");
+    if (block < 0 || block >= sp->cfg.n_blocks || which < 0 || which > 3) return fail(PETALS_ERR_INVALID_ARG, "block or linear index out of range");
+    if (!sp->blocks[block].loaded) return fail(PETALS_ERR_STATE, "block %d has not been loaded", block);
+    if (int rc = check_backward_shape(sp->cfg, B, T)) return rc;
+    BackwardStore bs = carve_backward(sp->cfg, B, T, (uint8_t *)dev_store);
+    const LinearW &L = sp->blocks[block].lin[which];
+    const int M = B * T;
+    hipStream_t st = (hipStream_t)stream;
+    HIP_TRY(ps_tile_rows((const __half *)dy, M, L.N, bs.tiles, st));
+    if (int rc = backward_product(sp, which, L, bs.tiles, M, bs, st)) return rc;
+    HIP_TRY(ps_copy_bytes(bs.out32, dx, (size_t)M * L.K * 4, st));
+    return PETALS_OK;
+}
+
 int petals_debug_layernorm(petals_span *sp, int32_t block, int32_t which, const void *x, int32_t M, void *y, void *stream) {
     if (!sp || !x || !y) return fail(PETALS_ERR_INVALID_ARG, "null pointer");
     if (block < 0 || block >= sp->cfg.n_blocks || which < 0 || which > 1) return fail(PETALS_ERR_INVALID_ARG, "block or LayerNorm index out of range");

@@ -171,3 +171,74 @@ def test_backward_c4_width_one_block_ragged_rows(wscale, strict):
     tolerance applies."""
     cfg = synth.CONFIGS["C4"]
     _check(cfg, 1, 2, 40, wscale=wscale, seed=9, min_branch=0.2, strict=strict)
+
+
+def test_backward_products_at_full_size_sampled_against_the_oracle():
+    """The four backward products of a BLOOM-176B-shaped block at the benchmark's 4096 rows (8 x 512), in the launch
+    configuration bench.py times: the oracle's definition dX = dY Wd evaluated for a sample of rows and columns
+    (first and last tiles included)."""
+    cfg = synth.CONFIGS["C4"]
+    B, T = 8, 512
+    M = B * T
+    p = synth.block_params_device(cfg, 0, DEV)
+    gsp = binding.Span(1, cfg.hidden, cfg.n_heads, cfg.F, M, 1e-5, 6.0, DEV)
+    gsp.load_block(0, p)
+    store = torch.empty(binding.petals_span_backward_bytes(gsp.cfg, B, T), dtype=torch.uint8, device=DEV)
+    r = np.random.default_rng(21)
+    gen = torch.Generator(device=DEV)
+    try:
+        for which, wname in ((3, "w_down"), (2, "w_up"), (0, "w_qkv"), (1, "w_dense")):
+            N, K = gsp.shapes(which)
+            wq, sw = oracle.quantize_weight(p[wname].cpu().numpy())
+            gen.manual_seed(100 + which)
+            dY = torch.empty((M, N), dtype=torch.float32, device=DEV).normal_(0.0, 1.0, generator=gen).to(torch.float16)
+            dX = torch.empty((M, K), dtype=torch.float32, device=DEV)
+            print("backward product of linear %d: [%d, %d] x [%d, %d]" % (which, M, N, N, K), flush=True)
+            binding.petals_debug_backward_product(gsp.handle, store, B, T, 0, which, dY, dX)
+            torch.cuda.synchronize()
+            rows = np.unique(np.concatenate([[0, 15, 16, 255, 256, M - 1], r.choice(M, 18, replace=False)]))
+            cols = np.unique(np.concatenate([np.arange(16), [K - 16, K - 1], r.choice(K, 40, replace=False)]))
+            Wd = ob.dequantized_weight(wq[:, cols], sw)                       # [N, len(cols)]
+            ref = to_np(dY[torch.as_tensor(rows, device=DEV)]).astype(np.float64) @ Wd
+            got = to_np(dX[torch.as_tensor(rows, device=DEV)][:, torch.as_tensor(cols, device=DEV)]).astype(np.float64)
+            rel = np.linalg.norm(got - ref) / np.linalg.norm(ref)
+            assert rel < 2e-6, (which, rel)                                   # fp32 accumulation of exact products
+            assert np.abs(got - ref).max() < 1e-4 * np.sqrt((ref ** 2).mean()) * 10, (which, np.abs(got - ref).max())
+            del wq, dY, dX
+    finally:
+        gsp.close()
+
+
+def test_backward_full_size_call_is_deterministic_linear_and_keeps_the_prefill_output():
+    """Properties that hold at any size, on 4096 rows (8 x 512) of two BLOOM-176B-shaped blocks: the same call twice
+    gives the same bits, a zero gradient stays zero, doubling the incoming gradient doubles the result up to fp16
+    rounding, and the forward output is the prefill output bit for bit."""
+    cfg = synth.CONFIGS["C4"]
+    B, T, nb = 8, 512, 2
+    gsp = binding.Span(nb, cfg.hidden, cfg.n_heads, cfg.F, B * T, 1e-5, 6.0, DEV)
+    try:
+        for b in range(nb):
+            gsp.load_block(b, synth.block_params_device(cfg, b, DEV))
+        X = to_dev(synth.hidden_states(cfg, 0, B, T))
+        gen = torch.Generator(device=DEV)
+        gen.manual_seed(7)
+        # the recipe's weights multiply the gradient by about 15 per block: keep it inside the fp16 range
+        g = (torch.empty(X.shape, dtype=torch.float32, device=DEV).normal_(0.0, 1.0, generator=gen) * 0.05).to(torch.float16)
+        store = torch.empty(binding.petals_span_backward_bytes(gsp.cfg, B, T), dtype=torch.uint8, device=DEV)
+        print("full-size backward calls", flush=True)
+        Y, d1 = gsp.backward(X, g, store=store)
+        d1 = d1.clone()
+        _, d1b = gsp.backward(X, g, store=store)
+        _, d0 = gsp.backward(X, torch.zeros_like(g), store=store)
+        _, d2 = gsp.backward(X, g * 2, store=store)
+        sessions = [gsp.open_session(T) for _ in range(B)]
+        Y2 = gsp.prefill(sessions, X)
+        torch.cuda.synchronize()
+        assert torch.isfinite(d1.float()).all() and torch.count_nonzero(d1) > d1.numel() // 2
+        assert torch.equal(d1.view(torch.int16), d1b.view(torch.int16))
+        assert torch.count_nonzero(d0) == 0
+        rel = torch.linalg.norm(d2.double() - 2 * d1.double()) / torch.linalg.norm(d2.double())
+        assert rel < 2e-3, float(rel)
+        assert torch.equal(Y.view(torch.int16), Y2.view(torch.int16))
+    finally:
+        gsp.close()
