@@ -307,20 +307,21 @@ __global__ void k_mask_to_bytes(const uint32_t *__restrict__ mask, int K, uint8_
 
 // ------------------------------------------------------------------- codec
 
-// One workgroup per block of `block` elements (last block may be short).
-__global__ void __launch_bounds__(256) k_hidden_quantize(const __half *__restrict__ x, size_t n, int block,
+// One workgroup per block of `block` elements (last block may be short).  A decode step has few blocks, so the
+// kernel is latency bound: 1024 threads keep the chain of dependent table look-ups per thread short.
+__global__ void __launch_bounds__(1024) k_hidden_quantize(const __half *__restrict__ x, size_t n, int block,
                                                          CodeTable tab, uint8_t *__restrict__ q,
                                                          float *__restrict__ absmax) {
     __shared__ float mids[256];
-    __shared__ float sm[4];
+    __shared__ float sm[16];
     if (threadIdx.x < 255) mids[threadIdx.x] = (tab.code[threadIdx.x] + tab.code[threadIdx.x + 1]) * 0.5f;
     const size_t b0 = (size_t)blockIdx.x * block;
     const int len = (int)min((size_t)block, n - b0);
     float m = 0.0f;
-    for (int i = threadIdx.x; i < len; i += 256) m = fmaxf(m, fabsf(__half2float(x[b0 + i])));
-    const float a = block_max<4>(m, sm);    // its barrier also publishes mids
+    for (int i = threadIdx.x; i < len; i += 1024) m = fmaxf(m, fabsf(__half2float(x[b0 + i])));
+    const float a = block_max<16>(m, sm);   // its barrier also publishes mids
     if (threadIdx.x == 0) absmax[blockIdx.x] = a;
-    for (int i = threadIdx.x; i < len; i += 256) {
+    for (int i = threadIdx.x; i < len; i += 1024) {
         const float v = a > 0.0f ? __half2float(x[b0 + i]) / a : 0.0f;
         int lo = 0, hi = 255;               // count of midpoints strictly below v
         while (lo < hi) {
@@ -406,7 +407,7 @@ hipError_t ps_mask_to_bytes(const uint32_t *mask, int K, uint8_t *out, hipStream
 hipError_t ps_hidden_quantize(const __half *x, size_t n, int block, const CodeTable &tab, uint8_t *q, float *absmax,
                               hipStream_t st) {
     if (n == 0) return hipSuccess;
-    k_hidden_quantize<<<(unsigned)((n + block - 1) / block), 256, 0, st>>>(x, n, block, tab, q, absmax);
+    k_hidden_quantize<<<(unsigned)((n + block - 1) / block), 1024, 0, st>>>(x, n, block, tab, q, absmax);
     return hipGetLastError();
 }
 hipError_t ps_hidden_dequantize(const uint8_t *q, const float *absmax, size_t n, int block, const CodeTable &tab,
