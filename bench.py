@@ -287,12 +287,20 @@ def backward_main(args, dev):
         binding.petals_span_backward(span.handle, store, X, dY, out, gin)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record(stream)
-    for _ in range(K_steps):
-        binding.petals_span_backward(span.handle, store, X, dY, out, gin)
-    e1.record(stream)
+
+    def timed():
+        e0.record(stream)
+        for _ in range(K_steps):
+            binding.petals_span_backward(span.handle, store, X, dY, out, gin)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / K_steps
+
+    ms_rebuild = timed()            # the transposed fp16 weights are rebuilt from int8 in every call
+    span.attach_backward_cache()    # ... or kept between calls (2 bytes per weight): the configuration reported
+    binding.petals_span_backward(span.handle, store, X, dY, out, gin)
     torch.cuda.synchronize()
-    ms = e0.elapsed_time(e1) / K_steps
+    ms = timed()
     binding.petals_span_profile_begin(span.handle, NB * 16)
     binding.petals_span_backward(span.handle, store, X, dY, out, gin)
     torch.cuda.synchronize()
@@ -309,6 +317,8 @@ def backward_main(args, dev):
         "config": {"workload": "12-block BLOOM-176B-shaped span (H=14336, F=57344), %d sequences x 512 tokens "
                                "(%d rows per linear), forward then backward" % (B, M),
                    "store_gb": round(store.numel() / 1e9, 2),
+                   "transposed_weight_cache_gb": round(span.backward_cache.numel() / 1e9, 2),
+                   "ms_per_step_without_the_cache": round(ms_rebuild, 3),
                    "per_call_ms": {"forward_linears_and_attention": round(fwd_ms, 2),
                                    "backward_products": round(bwd_gemm_ms, 2),
                                    "backward_attention": round(pm[binding.PROFILE_BWD_ATTENTION], 2)}},

@@ -219,6 +219,16 @@ int petals_span_backward_bytes(const petals_span_config *cfg, int32_t B, int32_t
 int petals_span_backward(petals_span *span, void *dev_store, int32_t B, int32_t T, const void *hidden_in,
                          const void *grad_out, void *hidden_out, void *grad_in, void *stream);
 
+/*
+ * Optional: keep the fp16 transposed dequantized weights that the backward products read (2 bytes per
+ * weight, petals_span_backward_cache_bytes in total) in caller-owned device memory, so that only the
+ * first backward call after a block is loaded builds them; without a cache every call rebuilds them
+ * from the int8 weights into its store.  Results are bit-identical either way.  dev_cache: 256-byte
+ * aligned, or NULL to detach; must stay alive while attached.  Loading a block invalidates its entries.
+ */
+int petals_span_backward_cache_bytes(const petals_span_config *cfg, size_t *bytes);
+int petals_span_backward_attach_cache(petals_span *span, void *dev_cache);
+
 /* ------------------------------------------------------------ test hooks */
 
 /*

@@ -57,7 +57,8 @@ EXPORTS = ["petals_span_weight_bytes", "petals_span_workspace_bytes", "petals_sp
            "petals_hidden_dequantize", "petals_hidden_code_table", "petals_last_error", "petals_debug_linear",
            "petals_debug_export_weight", "petals_debug_export_kv", "petals_debug_import_kv",
            "petals_span_profile_begin", "petals_span_profile_end", "petals_debug_layernorm", "petals_session_replay",
-           "petals_span_backward_bytes", "petals_span_backward", "petals_debug_backward_product"]
+           "petals_span_backward_bytes", "petals_span_backward", "petals_debug_backward_product",
+           "petals_span_backward_cache_bytes", "petals_span_backward_attach_cache"]
 CLIENT_EXPORTS = ["petals_client_workspace_bytes", "petals_client_create", "petals_client_destroy",
                   "petals_client_embed", "petals_client_lm_head"]
 PROFILE_GEMV, PROFILE_GEMM, PROFILE_ATTENTION, PROFILE_LINEAR0 = 0, 1, 2, 3
@@ -202,6 +203,16 @@ def petals_span_backward_bytes(cfg, B, T):
     return n.value
 
 
+def petals_span_backward_cache_bytes(cfg):
+    n = C.c_size_t()
+    _check(lib().petals_span_backward_cache_bytes(C.byref(cfg), C.byref(n)))
+    return n.value
+
+
+def petals_span_backward_attach_cache(span, cache):
+    _check(lib().petals_span_backward_attach_cache(span, _ptr(cache)))
+
+
 def petals_span_backward(span, store, hidden_in, grad_out, hidden_out, grad_in):
     B, T, _ = hidden_in.shape
     for t in (hidden_in, grad_out, grad_in) + (() if hidden_out is None else (hidden_out,)):
@@ -275,6 +286,12 @@ class Span:
         out = torch.empty_like(hidden_in) if out is None else out
         petals_span_decode_step(self.handle, [s.handle for s in sessions], hidden_in, out)
         return out
+
+    def attach_backward_cache(self, on=True):
+        """Keep the transposed fp16 weights of the backward products between calls (2 bytes per weight)."""
+        self.backward_cache = torch.empty(petals_span_backward_cache_bytes(self.cfg), dtype=torch.uint8,
+                                          device=self.device) if on else None
+        petals_span_backward_attach_cache(self.handle, self.backward_cache)
 
     def backward(self, hidden_in, grad_out, store=None, want_output=True):
         """Forward + backward of B sequences (hidden_in, grad_out fp16 [B,T,H]); returns (hidden_out, grad_in).

@@ -177,6 +177,9 @@ struct petals_span {
     std::vector<BlockW> blocks;
     double slopes[PS_MAX_HEADS];
     int open_sessions;
+    // optional cache of the transposed dequantized weights for the backward pass: [block][linear]
+    __half *bwd_cache = nullptr;
+    std::vector<uint8_t> bwd_cached;     // 1: the tiles of (block, linear) are in the cache
 };
 
 struct petals_session {
@@ -348,12 +351,32 @@ int check_backward_shape(const petals_span_config &c, int32_t B, int32_t T) {
     return PETALS_OK;
 }
 
-// dX[M, K] (fp32, into out32) = rows (already in tile order) x dequantized weights of linear w
-int backward_product(petals_span *sp, int which, const LinearW &w, const __half *row_tiles, int M, BackwardStore &bs,
+size_t backward_cache_block_halves(const petals_span_config &c) {
+    size_t h = 0;
+    for (int i = 0; i < 4; i++) {
+        int N, K;
+        linear_dims(c, i, &N, &K);
+        h += align_up((size_t)N * K * 2) / 2;
+    }
+    return h;
+}
+
+// dX[M, K] (fp32, into out32) = rows (already in tile order) x dequantized weights of linear `which` of block b.
+// The transposed fp16 tiles of the weights are built per call, or once if the span has a cache attached.
+int backward_product(petals_span *sp, int b, int which, const __half *row_tiles, int M, BackwardStore &bs,
                      hipStream_t st) {
-    HIP_TRY(ps_transpose_w(w, bs.wt16, st));
+    const LinearW &w = sp->blocks[b].lin[which];
+    __half *wt16 = bs.wt16;
+    if (sp->bwd_cache) {
+        wt16 = sp->bwd_cache + (size_t)b * backward_cache_block_halves(sp->cfg);
+        for (int i = 0; i < which; i++) wt16 += align_up((size_t)sp->blocks[b].lin[i].N * sp->blocks[b].lin[i].K * 2) / 2;
+    }
+    if (!sp->bwd_cache || !sp->bwd_cached[b * 4 + which]) {
+        HIP_TRY(ps_transpose_w(w, wt16, st));
+        if (sp->bwd_cache) sp->bwd_cached[b * 4 + which] = 1;
+    }
     const bool pr = sp->prof.begin(PETALS_PROFILE_BWD_GEMM, which, st);
-    HIP_TRY(ps_gemm_f16_tiles(bs.wt16, row_tiles, w.N / 32, M, w.K, bs.out32, st));
+    HIP_TRY(ps_gemm_f16_tiles(wt16, row_tiles, w.N / 32, M, w.K, bs.out32, st));
     sp->prof.end(pr, st);
     return PETALS_OK;
 }
@@ -397,6 +420,7 @@ int petals_span_create(const petals_span_config *cfg, void *dev_weight_mem, void
     sp->ws = carve(*cfg, (uint8_t *)dev_workspace);
     sp->open_sessions = 0;
     sp->blocks.resize(cfg->n_blocks);
+    sp->bwd_cached.assign((size_t)cfg->n_blocks * 4, 0);
     const size_t per_block = block_weight_bytes(*cfg);
     for (int b = 0; b < cfg->n_blocks; b++) {
         uint8_t *p = sp->wmem + per_block * b;
@@ -444,6 +468,7 @@ int petals_span_load_block(petals_span *sp, int32_t block, const petals_block_pa
     }
     __half *dst[4] = {B.ln1g, B.ln1b, B.ln2g, B.ln2b};
     for (int i = 0; i < 4; i++) HIP_TRY(ps_copy_bytes(ln[i], dst[i], (size_t)sp->cfg.hidden * 2, st));
+    for (int i = 0; i < 4; i++) sp->bwd_cached[block * 4 + i] = 0;
     B.loaded = true;
     return PETALS_OK;
 }
@@ -590,6 +615,21 @@ int petals_span_backward_bytes(const petals_span_config *cfg, int32_t B, int32_t
     return PETALS_OK;
 }
 
+int petals_span_backward_cache_bytes(const petals_span_config *cfg, size_t *bytes) {
+    if (int rc = check_config(cfg)) return rc;
+    if (!bytes) return fail(PETALS_ERR_INVALID_ARG, "bytes is null");
+    *bytes = backward_cache_block_halves(*cfg) * 2 * (size_t)cfg->n_blocks;
+    return PETALS_OK;
+}
+
+int petals_span_backward_attach_cache(petals_span *sp, void *dev_cache) {
+    if (!sp) return fail(PETALS_ERR_INVALID_ARG, "null span");
+    if ((uintptr_t)dev_cache & 255) return fail(PETALS_ERR_INVALID_ARG, "cache memory must be 256-byte aligned");
+    sp->bwd_cache = (__half *)dev_cache;
+    sp->bwd_cached.assign(sp->bwd_cached.size(), 0);
+    return PETALS_OK;
+}
+
 int petals_span_backward(petals_span *sp, void *dev_store, int32_t B, int32_t T, const void *hidden_in,
                          const void *grad_out, void *hidden_out, void *grad_in, void *stream) {
     if (!sp || !dev_store || !hidden_in || !grad_out || !grad_in) return fail(PETALS_ERR_INVALID_ARG, "null pointer");
@@ -626,14 +666,14 @@ int petals_span_backward(petals_span *sp, void *dev_store, int32_t B, int32_t T,
         const BlockW &W = sp->blocks[b];
         // x2 = x1 + down(GeLU(pre)):  dpre = (gy Wd_down) * GeLU'(pre), written in tile order
         HIP_TRY(ps_tile_rows(gy, M, H, bs.tiles, st));
-        if (int rc = backward_product(sp, 3, W.lin[3], bs.tiles, M, bs, st)) return rc;
+        if (int rc = backward_product(sp, b, 3, bs.tiles, M, bs, st)) return rc;
         HIP_TRY(ps_gelu_bwd(bs.out32, bs.save.pre[b], M, F, bs.tiles, st));
         // pre = up(LayerNorm2(x1)):  dx1 = gy + LayerNorm2'(dpre Wd_up)
-        if (int rc = backward_product(sp, 2, W.lin[2], bs.tiles, M, bs, st)) return rc;
+        if (int rc = backward_product(sp, b, 2, bs.tiles, M, bs, st)) return rc;
         HIP_TRY(ps_ln_bwd(bs.out32, bs.save.x1[b], W.ln2g, gy, c.ln_eps, M, H, bs.gx1, st));
         // x1 = x + dense(ctx):  dctx = dx1 Wd_dense
         HIP_TRY(ps_tile_rows(bs.gx1, M, H, bs.tiles, st));
-        if (int rc = backward_product(sp, 1, W.lin[1], bs.tiles, M, bs, st)) return rc;
+        if (int rc = backward_product(sp, b, 1, bs.tiles, M, bs, st)) return rc;
         HIP_TRY(ps_attn_bwd_prep(bs.out32, bs.save.ctx32[b], M, nh, d, bs.dO, bs.Dv, st));
         {
             const bool pr = sp->prof.begin(PETALS_PROFILE_BWD_ATTENTION, -1, st);
@@ -643,7 +683,7 @@ int petals_span_backward(petals_span *sp, void *dev_store, int32_t B, int32_t T,
         }
         // qkv = Lin(LayerNorm1(x)):  dx = dx1 + LayerNorm1'(dqkv Wd_qkv)
         HIP_TRY(ps_tile_rows(bs.dqkv, M, 3 * H, bs.tiles, st));
-        if (int rc = backward_product(sp, 0, W.lin[0], bs.tiles, M, bs, st)) return rc;
+        if (int rc = backward_product(sp, b, 0, bs.tiles, M, bs, st)) return rc;
         __half *gx = b == 0 ? (__half *)grad_in : bs.gy[b & 1];
         HIP_TRY(ps_ln_bwd(bs.out32, bs.save.x[b], W.ln1g, bs.gx1, c.ln_eps, M, H, gx, st));
         gy = gx;
@@ -706,7 +746,7 @@ int petals_debug_backward_product(petals_span *sp, void *dev_store, int32_t B, i
     const int M = B * T;
     hipStream_t st = (hipStream_t)stream;
     HIP_TRY(ps_tile_rows((const __half *)dy, M, L.N, bs.tiles, st));
-    if (int rc = backward_product(sp, which, L, bs.tiles, M, bs, st)) return rc;
+    if (int rc = backward_product(sp, block, which, bs.tiles, M, bs, st)) return rc;
     HIP_TRY(ps_copy_bytes(bs.out32, dx, (size_t)M * L.K * 4, st));
     return PETALS_OK;
 }

@@ -122,6 +122,39 @@ def test_backward_forward_output_is_the_prefill_output_bit_for_bit():
         osp.destroy()
 
 
+def test_backward_weight_cache_gives_the_same_bits_and_follows_a_reloaded_block():
+    cfg = synth.scaled(synth.CONFIGS["C2"], hidden=512, n_heads=8)
+    osp, gsp, params = _pair(cfg, 2, 2 * 40, 3.0)
+    try:
+        X = to_dev(synth.hidden_states(cfg, 0, 2, 40))
+        g = to_dev(_grad(cfg, 2, 40, 3))
+        _, plain = gsp.backward(X, g)
+        gsp.attach_backward_cache()
+        _, first = gsp.backward(X, g)          # fills the cache
+        _, second = gsp.backward(X, g)         # reads it
+        torch.cuda.synchronize()
+        assert torch.equal(plain.view(torch.int16), first.view(torch.int16))
+        assert torch.equal(plain.view(torch.int16), second.view(torch.int16))
+        # new weights in block 1: the cached tiles of that block must not be used any more
+        p = dict(params[1])
+        p["w_up"] = p["w_up"] * np.float32(0.5)
+        gsp.load_block(1, p)
+        osp.load_block(1, p)
+        params[1] = p
+        _, third = gsp.backward(X, g)
+        torch.cuda.synchronize()
+        _, ref = ob.span_backward(osp, params, to_np(X), to_np(g))
+        grad_close(to_np(third), ref)
+        assert not torch.equal(third.view(torch.int16), plain.view(torch.int16))
+        gsp.attach_backward_cache(False)
+        _, fourth = gsp.backward(X, g)
+        torch.cuda.synchronize()
+        assert torch.equal(third.view(torch.int16), fourth.view(torch.int16))
+    finally:
+        gsp.close()
+        osp.destroy()
+
+
 def test_backward_is_linear_in_the_incoming_gradient_and_zero_for_zero():
     cfg = synth.CONFIGS["C1"]
     osp, gsp, _ = _pair(cfg, 2, 24, 8.0)
