@@ -202,28 +202,37 @@ __global__ void __launch_bounds__(256) k_head_transpose(const __half *__restrict
 //   dS = P (dP - Dv_i),  dQ = dS K / sqrt(d),  dK = dS^T Q / sqrt(d),  dV = P^T dO.
 // KV = false: a workgroup owns 64 queries (16 per wave) and walks the key tiles (32 keys) up to the causal
 // limit, accumulating dQ.  KV = true: it owns 64 keys and walks the query tiles from its first key on,
-// accumulating dK and dV.  Either way the own rows are the A operand (fragments in registers), a tile of
-// the other side goes through LDS once per workgroup, in natural order (B operand of the score products)
-// and transposed (B operand of the accumulating products, read from the per-head transposed copies);
-// P and dS pass through a wave-private LDS patch to change from result layout to A-operand layout.
+// accumulating dK and dV.  A tile of the other side goes through LDS once per workgroup, in natural order
+// and transposed (from the per-head transposed copies).  All products are v_mfma_f32_16x16x32_f16:
+//   scores, transposed:  S^T = other x own^T   A = tile rows (LDS), B = the wave's own rows (registers);
+//     result register r of lane (c, g) = (other row 16 u + 4 g + r, own row c) for the tile's halves u = 0, 1;
+//   accumulation, transposed:  acc^T += other^T x dS^T   B = the 8 values a lane already holds (u, r),
+//     taken as contraction positions 8 g + 4 u + r; A = the transposed tile read with the same assignment
+//     (rows 4 g .. +4 and 16 + 4 g .. +4 of the tile).  P and dS never leave their lanes.
+// Grid: one dimension.  Consecutive workgroup ids land on different XCDs (8 of them, each with its own L2);
+// the id is decoded so that all workgroups of one (sequence, head) run on the same XCD and share its tiles there.
 template <int D, bool KV>
 __global__ void __launch_bounds__(256) k_attn_bwd(const __half *__restrict__ q, const SessTable *__restrict__ sess, int blk,
-                                                  int T, int Tp, int nh, const __half *__restrict__ dO,
+                                                  int B, int T, int Tp, int nh, const __half *__restrict__ dO,
                                                   const __half *__restrict__ QT, const __half *__restrict__ KT,
                                                   const __half *__restrict__ dOT, const float *__restrict__ lse,
                                                   const float *__restrict__ Dv, __half *__restrict__ dqkv) {
     constexpr int NC = (D + 31) / 32, NB = D / 16, PN = D + 8, PT = 40;
     constexpr int NCH = 4 * D;                                  // 16-byte chunks of one staged matrix
     constexpr int CN = (NCH + 255) / 256;
+    constexpr float LOG2E = 1.4426950408889634f;
     __shared__ __align__(16) __half y1[32 * PN], y2[32 * PN], y1t[D * PT], y2t[KV ? D * PT : 8];
-    __shared__ __align__(16) __half pbuf[4][KV ? 2 : 1][16 * PT];
+    __shared__ __align__(16) float st_l[32], st_d[32];          // KV: lse * log2(e) and Dv of the tile's query rows
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, c = lane & 15, g = lane >> 4;
-    const int own0 = blockIdx.x * 64, h = blockIdx.y, s = blockIdx.z, M = gridDim.z * T, H = nh * D;
+    const int nbx = (T + 63) / 64, grp = blockIdx.x / (8 * nbx), rem = blockIdx.x - grp * 8 * nbx;
+    const int pair = grp * 8 + (rem & 7);                       // (sequence, head) index; same XCD for all its blocks
+    if (pair >= B * nh) return;                                 // the whole workgroup
+    const int own0 = (rem >> 3) * 64, s = pair / nh, h = pair - s * nh, M = B * T, H = nh * D;
     const int cap = sess->cap[s];
     const __half *Qn = q + (size_t)s * T * H + h * D, *dOn = dO + (size_t)s * T * H + h * D;
     const __half *Kn = sess->kv[s] + ((size_t)blk * 2 * nh + h) * cap * D, *Vn = Kn + (size_t)nh * cap * D;
     const size_t th = ((size_t)(s * nh + h) * D) * Tp;
-    const float slope = (float)sess->slopes[h], rs = 1.0f / sqrtf((float)D);
+    const float rs = 1.0f / sqrtf((float)D), c1 = rs * LOG2E, slope2 = (float)sess->slopes[h] * LOG2E;
     const float *lse_h = lse + (size_t)h * M + (size_t)s * T, *dv_h = Dv + (size_t)h * M + (size_t)s * T;
 
     const __half *own1 = KV ? Kn : Qn, *own2 = KV ? Vn : dOn;
@@ -232,11 +241,11 @@ __global__ void __launch_bounds__(256) k_attn_bwd(const __half *__restrict__ q, 
     const size_t oth_stride = KV ? H : D;
     const __half *oth1t = (KV ? QT : KT) + th, *oth2t = dOT + th;
 
-    const int ro0 = own0 + wave * 16;
+    const int ro0 = own0 + wave * 16, own = ro0 + c;            // this lane's own row (query or key)
     const bool dims_ok = (D >= 32) || (g * 8 < D);              // head_dim 16: the upper half of the contraction is zero
     v8h a1[NC], a2[NC];
     {
-        const size_t r = (size_t)min(ro0 + c, T - 1) * own_stride;
+        const size_t r = (size_t)min(own, T - 1) * own_stride;
 #pragma unroll
         for (int cc = 0; cc < NC; cc++) {
             a1[cc] = a2[cc] = (v8h){0, 0, 0, 0, 0, 0, 0, 0};
@@ -246,14 +255,13 @@ __global__ void __launch_bounds__(256) k_attn_bwd(const __half *__restrict__ q, 
             }
         }
     }
-    float lse_r[4], dv_r[4];                                    // KV = false: statistics of the own (query) rows
-#pragma unroll
-    for (int r = 0; r < 4; r++) {
-        const int i = min(ro0 + 4 * g + r, T - 1);
-        lse_r[r] = lse_h[i];
-        dv_r[r] = dv_h[i];
+    // exponent in base 2: z = S c1 - slope2 (i - j) - lse_i log2(e)
+    float own_l2 = 0.0f, own_dv = 0.0f;                         // KV = false: statistics of the own (query) row
+    if (!KV) {
+        own_l2 = lse_h[min(own, T - 1)] * LOG2E;
+        own_dv = dv_h[min(own, T - 1)];
     }
-    v4f acc1[NB], acc2[KV ? NB : 1];
+    v4f acc1[NB], acc2[KV ? NB : 1];                            // transposed: register r = head dim 16 b + 4 g + r of own row c
 #pragma unroll
     for (int b = 0; b < NB; b++) acc1[b] = (v4f){0, 0, 0, 0};
 #pragma unroll
@@ -262,8 +270,15 @@ __global__ void __launch_bounds__(256) k_attn_bwd(const __half *__restrict__ q, 
     const int t_first = KV ? own0 / 32 : 0;
     const int t_end = KV ? (T + 31) / 32 : (min(T, own0 + 64) + 31) / 32;
 
-    v4i n1[CN], n2[CN], t1[CN], t2[CN];
-    auto fetch = [&](int t) {
+    // Tiles of the other side are fetched two iterations ahead into two alternating register sets, so that a
+    // global load has the time of two tiles to arrive; the waits are the compiler's (per register) and the
+    // workgroup barriers are bare s_barrier instructions: a fence would wait for the loads in flight as well.
+    struct TileRegs {
+        v4i n1[CN], n2[CN], t1[CN], t2[CN];
+        float ls, dv;                                           // KV: statistics of query row (thread id) of the tile
+    };
+    TileRegs RA, RB;
+    auto fetch = [&](int t, TileRegs &R) {
         const int o0 = t * 32;
 #pragma unroll
         for (int k = 0; k < CN; k++) {
@@ -271,99 +286,112 @@ __global__ void __launch_bounds__(256) k_attn_bwd(const __half *__restrict__ q, 
             if (ci < NCH) {
                 const int rr = ci / (D / 8), cc = ci - rr * (D / 8);
                 const size_t off = (size_t)min(o0 + rr, T - 1) * oth_stride + cc * 8;
-                n1[k] = *(const v4i *)(oth1 + off);
-                n2[k] = *(const v4i *)(oth2 + off);
+                R.n1[k] = *(const v4i *)(oth1 + off);
+                R.n2[k] = *(const v4i *)(oth2 + off);
                 const int dim = ci >> 2, part = ci & 3;
-                t1[k] = *(const v4i *)(oth1t + (size_t)dim * Tp + o0 + part * 8);
-                if (KV) t2[k] = *(const v4i *)(oth2t + (size_t)dim * Tp + o0 + part * 8);
+                R.t1[k] = *(const v4i *)(oth1t + (size_t)dim * Tp + o0 + part * 8);
+                if (KV) R.t2[k] = *(const v4i *)(oth2t + (size_t)dim * Tp + o0 + part * 8);
             }
         }
+        R.ls = R.dv = 0.0f;
+        if (KV && threadIdx.x < 32) {
+            R.ls = lse_h[min(o0 + (int)threadIdx.x, T - 1)] * LOG2E;
+            R.dv = dv_h[min(o0 + (int)threadIdx.x, T - 1)];
+        }
     };
-    auto stash = [&]() {
+    auto stash = [&](const TileRegs &R) {
 #pragma unroll
         for (int k = 0; k < CN; k++) {
             const int ci = threadIdx.x + 256 * k;
             if (ci < NCH) {
                 const int rr = ci / (D / 8), cc = ci - rr * (D / 8);
-                *(v4i *)(y1 + rr * PN + cc * 8) = n1[k];
-                *(v4i *)(y2 + rr * PN + cc * 8) = n2[k];
+                *(v4i *)(y1 + rr * PN + cc * 8) = R.n1[k];
+                *(v4i *)(y2 + rr * PN + cc * 8) = R.n2[k];
                 const int dim = ci >> 2, part = ci & 3;
-                *(v4i *)(y1t + dim * PT + part * 8) = t1[k];
-                if (KV) *(v4i *)(y2t + dim * PT + part * 8) = t2[k];
+                *(v4i *)(y1t + dim * PT + part * 8) = R.t1[k];
+                if (KV) *(v4i *)(y2t + dim * PT + part * 8) = R.t2[k];
             }
         }
+        if (KV && threadIdx.x < 32) {
+            st_l[threadIdx.x] = R.ls;
+            st_d[threadIdx.x] = R.dv;
+        }
     };
-    if (t_first < t_end) fetch(t_first);
-    for (int t = t_first; t < t_end; t++) {
-        __syncthreads();                                        // everybody done with the previous tile
-        stash();
-        __syncthreads();
-        if (t + 1 < t_end) fetch(t + 1);                        // in flight during the products below
+    auto wg_barrier = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
+    auto tile = [&](int t, TileRegs &R) {
+        wg_barrier();                                           // everybody done with the previous tile
+        stash(R);
+        wg_barrier();
+        if (t + 2 < t_end) fetch(t + 2, R);                     // the set is free again
         const int o0 = t * 32;
         const bool active = ro0 < T && (KV ? o0 + 31 >= ro0 : o0 <= ro0 + 15);   // wave-uniform
-        if (!active) continue;
-        __half *ds_buf = pbuf[wave][0], *p_buf = pbuf[wave][KV ? 1 : 0];
+        if (!active) return;
+        v8h b_ds, b_p;
 #pragma unroll
         for (int u = 0; u < 2; u++) {
             v4f sacc = {0, 0, 0, 0}, pacc = {0, 0, 0, 0};
 #pragma unroll
             for (int cc = 0; cc < NC; cc++) {
-                v8h b1 = {0, 0, 0, 0, 0, 0, 0, 0}, b2 = {0, 0, 0, 0, 0, 0, 0, 0};
+                v8h o1 = {0, 0, 0, 0, 0, 0, 0, 0}, o2 = {0, 0, 0, 0, 0, 0, 0, 0};
                 if (dims_ok) {
-                    b1 = *(const v8h *)(y1 + (16 * u + c) * PN + g * 8 + 32 * cc);
-                    b2 = *(const v8h *)(y2 + (16 * u + c) * PN + g * 8 + 32 * cc);
+                    o1 = *(const v8h *)(y1 + (16 * u + c) * PN + g * 8 + 32 * cc);
+                    o2 = *(const v8h *)(y2 + (16 * u + c) * PN + g * 8 + 32 * cc);
                 }
-                sacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1[cc], b1, sacc, 0, 0, 0);
-                pacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a2[cc], b2, pacc, 0, 0, 0);
+                sacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(o1, a1[cc], sacc, 0, 0, 0);
+                pacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(o2, a2[cc], pacc, 0, 0, 0);
             }
-            // result register r: own row 4 g + r, other row 16 u + c
-            const int co = o0 + 16 * u + c;
-            float lse_c = 0.0f, dv_c = 0.0f;
+            // result register r: other row o0 + 16 u + 4 g + r, own row c
+            const int ob = o0 + 16 * u + 4 * g;
+            v4f ls4 = {0, 0, 0, 0}, dv4 = {own_dv, own_dv, own_dv, own_dv};
             if (KV) {
-                lse_c = lse_h[min(co, T - 1)];
-                dv_c = dv_h[min(co, T - 1)];
+                ls4 = *(const v4f *)(st_l + 16 * u + 4 * g);
+                dv4 = *(const v4f *)(st_d + 16 * u + 4 * g);
             }
 #pragma unroll
             for (int r = 0; r < 4; r++) {
-                const int ro = ro0 + 4 * g + r;
-                const int i = KV ? co : ro, j = KV ? ro : co;
-                const bool valid = i < T && j <= i;
-                const float z = sacc[r] * rs - slope * (float)(i - j) - (KV ? lse_c : lse_r[r]);
-                const float p = valid ? expf(z) : 0.0f;
-                const float ds = p * (pacc[r] - (KV ? dv_c : dv_r[r])) * rs;
-                ds_buf[(4 * g + r) * PT + 16 * u + c] = __float2half_rn(ds);
-                if (KV) p_buf[(4 * g + r) * PT + 16 * u + c] = __float2half_rn(p);
+                const int o = ob + r;
+                // KV: query i = o, key j = own;  else: query i = own, key j = o
+                const bool valid = KV ? (o < T && o >= own) : (own < T && o <= own);
+                const float dist = (float)(KV ? o - own : own - o);
+                const float z = fmaf(-slope2, dist, fmaf(sacc[r], c1, -(KV ? ls4[r] : own_l2)));
+                const float p = valid ? __builtin_amdgcn_exp2f(z) : 0.0f;
+                const float ds = p * (pacc[r] - dv4[r]) * rs;
+                b_ds[4 * u + r] = (_Float16)ds;
+                b_p[4 * u + r] = (_Float16)p;
             }
         }
-        // the patch is private to the wave: order its writes before its reads
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        const v8h a_ds = *(const v8h *)(ds_buf + c * PT + g * 8);
-        v8h a_p = a_ds;
-        if (KV) a_p = *(const v8h *)(p_buf + c * PT + g * 8);
 #pragma unroll
         for (int b = 0; b < NB; b++) {
-            const v8h bt = *(const v8h *)(y1t + (16 * b + c) * PT + g * 8);
-            acc1[b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_ds, bt, acc1[b], 0, 0, 0);
+            // transposed tile rows (head dims) 16 b + c, contraction positions 8 g + e <-> tile rows 16 (e / 4) + 4 g + e % 4
+            const __half *r1 = y1t + (16 * b + c) * PT + 4 * g;
+            const v4h lo = *(const v4h *)r1, hi = *(const v4h *)(r1 + 16);
+            const v8h at = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            acc1[b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(at, b_ds, acc1[b], 0, 0, 0);
             if (KV) {
-                const v8h bt2 = *(const v8h *)(y2t + (16 * b + c) * PT + g * 8);
-                acc2[b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_p, bt2, acc2[b], 0, 0, 0);
+                const __half *r2 = y2t + (16 * b + c) * PT + 4 * g;
+                const v4h lo2 = *(const v4h *)r2, hi2 = *(const v4h *)(r2 + 16);
+                const v8h at2 = {lo2[0], lo2[1], lo2[2], lo2[3], hi2[0], hi2[1], hi2[2], hi2[3]};
+                acc2[b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(at2, b_p, acc2[b], 0, 0, 0);
             }
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
+    };
+    if (t_first < t_end) fetch(t_first, RA);
+    if (t_first + 1 < t_end) fetch(t_first + 1, RB);
+    for (int t = t_first; t < t_end; t += 2) {
+        tile(t, RA);
+        if (t + 1 < t_end) tile(t + 1, RB);
     }
-    // result register r: own row 4 g + r, head dim 16 b + c
-#pragma unroll
-    for (int r = 0; r < 4; r++) {
-        const int ro = ro0 + 4 * g + r;
-        if (ro >= T) continue;
-        __half *dst = dqkv + ((size_t)s * T + ro) * 3 * H + (size_t)h * 3 * D + c;
+    // result register r of block b: head dim 16 b + 4 g + r of own row c: one 8-byte store per block
+    if (own < T) {
+        __half *dst = dqkv + ((size_t)s * T + own) * 3 * H + (size_t)h * 3 * D + 4 * g;
 #pragma unroll
         for (int b = 0; b < NB; b++) {
-            dst[(KV ? D : 0) + 16 * b] = __float2half_rn(acc1[b][r]);
-            if (KV) dst[2 * D + 16 * b] = __float2half_rn(acc2[b][r]);
+            const v4h o1 = {(_Float16)acc1[b][0], (_Float16)acc1[b][1], (_Float16)acc1[b][2], (_Float16)acc1[b][3]};
+            *(v4h *)(dst + (KV ? D : 0) + 16 * b) = o1;
+            if (KV) {
+                const v4h o2 = {(_Float16)acc2[b][0], (_Float16)acc2[b][1], (_Float16)acc2[b][2], (_Float16)acc2[b][3]};
+                *(v4h *)(dst + 2 * D + 16 * b) = o2;
+            }
         }
     }
 }
@@ -376,9 +404,9 @@ hipError_t attn_bwd_launch(const __half *q, const SessTable *sess, int blk, int 
     k_head_transpose<D><<<gt, 256, 0, st>>>(q, sess, 0, blk, T, Tp, nh, QT);
     k_head_transpose<D><<<gt, 256, 0, st>>>(nullptr, sess, 1, blk, T, Tp, nh, KT);
     k_head_transpose<D><<<gt, 256, 0, st>>>(dO, sess, 0, blk, T, Tp, nh, dOT);
-    const dim3 grid((T + 63) / 64, nh, B);
-    k_attn_bwd<D, false><<<grid, 256, 0, st>>>(q, sess, blk, T, Tp, nh, dO, QT, KT, dOT, lse, Dv, dqkv);
-    k_attn_bwd<D, true><<<grid, 256, 0, st>>>(q, sess, blk, T, Tp, nh, dO, QT, KT, dOT, lse, Dv, dqkv);
+    const int grid = (B * nh + 7) / 8 * 8 * ((T + 63) / 64);
+    k_attn_bwd<D, false><<<grid, 256, 0, st>>>(q, sess, blk, B, T, Tp, nh, dO, QT, KT, dOT, lse, Dv, dqkv);
+    k_attn_bwd<D, true><<<grid, 256, 0, st>>>(q, sess, blk, B, T, Tp, nh, dO, QT, KT, dOT, lse, Dv, dqkv);
     return hipGetLastError();
 }
 
