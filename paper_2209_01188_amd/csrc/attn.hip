@@ -30,14 +30,20 @@ __global__ void k_set_table(SessTable t, SessTable *dst) {
 // while the current one is multiplied.  Queries are converted once per wave and stay in registers.
 template <int D>
 __global__ void __launch_bounds__(256, 2) k_attn_prefill(const __half *__restrict__ q, const SessTable *__restrict__ sess,
-                                                         int blk, int T, int nh, __half *__restrict__ ctx,
+                                                         int blk, int B, int T, int nh, __half *__restrict__ ctx,
                                                          uint32_t *__restrict__ mask, float theta,
                                                          float *__restrict__ lse, float *__restrict__ ctx32) {
     constexpr int DS = D / 4, NB = D / 16;           // dims per lane group; output blocks of 16 dims
     constexpr int TILE = 16 * D;                     // fp64 values of one key or value tile
     extern __shared__ __align__(16) double kvd[];    // [2 buffers][keys | values][TILE]
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, c = lane & 15, g = lane >> 4;
-    const int qt = blockIdx.x * 4 + wave, h = blockIdx.y, s = blockIdx.z;
+    // One-dimensional grid.  Consecutive workgroup ids land on different XCDs (8, each with its own L2): the id
+    // is decoded so that all query blocks of one (session, head) run on the same XCD and share its keys/values.
+    const int nbx = (T + 63) / 64, grp = blockIdx.x / (8 * nbx), rem = blockIdx.x - grp * 8 * nbx;
+    const int pair = grp * 8 + (rem & 7);
+    if (pair >= B * nh) return;                       // the whole workgroup
+    const int qb = rem >> 3, s = pair / nh, h = pair - s * nh;
+    const int qt = qb * 4 + wave;
     const int L = sess->len[s], cap = sess->cap[s], H = nh * D;
     const __half *Kc = sess->kv[s] + ((size_t)blk * 2 * nh + h) * cap * D;
     const __half *Vc = Kc + (size_t)nh * cap * D;
@@ -60,7 +66,7 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(const __half *__restric
 
     // key tiles this wave needs (none if its queries lie beyond T) and the workgroup's last wave needs
     const int nkt_w = qt * 16 < T ? min(L + qt * 16 + 15, last_key) / 16 + 1 : 0;
-    const int nkt = min(L + (blockIdx.x * 4 + 3) * 16 + 15, last_key) / 16 + 1;
+    const int nkt = min(L + (qb * 4 + 3) * 16 + 15, last_key) / 16 + 1;
 
     // conversion duty of this thread: NB consecutive dims of one key of the tile, keys and values alike
     const int fk = threadIdx.x >> 4, fd = (threadIdx.x & 15) * NB;
@@ -140,7 +146,7 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(const __half *__restric
     l_run += __shfl_xor(l_run, 16);
     l_run += __shfl_xor(l_run, 32);
     // log of the softmax denominator, kept for the backward pass: [head][row of the call]
-    if (lse && tq < T && g == 0) lse[(size_t)h * gridDim.z * T + qrow] = (float)(m_run + log(l_run));
+    if (lse && tq < T && g == 0) lse[(size_t)h * B * T + qrow] = (float)(m_run + log(l_run));
     if (tq < T) {
         // O[b][r] = output dim (4r + g) * NB + b of query c: NB consecutive dims per (r, g)
         __half *dst = ctx + qrow * H + h * D;
@@ -321,7 +327,8 @@ hipError_t attn_launch(const __half *q, const SessTable *sess, int blk, int M, i
     int CH = ((max_keys + nsplit - 1) / nsplit + 63) / 64 * 64;
     if (nsplit == 1) CH = 1 << 30;
     if (T > 1 || lse) {   // the matrix-core kernel also covers T = 1; it is the one that can report the denominators
-        k_attn_prefill<D><<<dim3((T + 63) / 64, nh, M / T), 256, (size_t)2 * 2 * 16 * D * 8, st>>>(q, sess, blk, T, nh, ctx, mask, theta, lse, ctx32);
+        const int B = M / T;
+        k_attn_prefill<D><<<(B * nh + 7) / 8 * 8 * ((T + 63) / 64), 256, (size_t)2 * 2 * 16 * D * 8, st>>>(q, sess, blk, B, T, nh, ctx, mask, theta, lse, ctx32);
         return hipGetLastError();
     }
     k_attn_decode<D><<<dim3(nsplit, nh, M), 256, 0, st>>>(q, sess, blk, nh, CH, nsplit, partials, ctx, mask, theta);
