@@ -6,12 +6,8 @@
 #include <string.h>
 
 #include <new>
-#include <vector>
 
-#include "../../include/petals_span.h"
-#include "common.h"
-
-#include "host_util.h"
+#include "span_internal.h"
 
 namespace {
 thread_local char g_err[512] = "";
@@ -32,14 +28,6 @@ namespace {
 
 #define fail ps_fail
 
-size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
-
-struct BlockW {
-    LinearW lin[4];
-    __half *ln1g, *ln1b, *ln2g, *ln2b;
-    bool loaded;
-};
-
 void linear_dims(const petals_span_config &c, int which, int *N, int *K) {
     const int H = c.hidden, F = c.ffn;
     const int n[4] = {3 * H, H, F, H}, k[4] = {H, H, H, F};
@@ -52,32 +40,17 @@ size_t block_weight_bytes(const petals_span_config &c) {
     for (int i = 0; i < 4; i++) {
         int N, K;
         linear_dims(c, i, &N, &K);
-        b += align_up((size_t)N * K) + align_up((size_t)N * 4) + align_up((size_t)N * 2);
+        b += ps_align_up((size_t)N * K) + ps_align_up((size_t)N * 4) + ps_align_up((size_t)N * 2);
     }
-    return b + 4 * align_up((size_t)c.hidden * 2);
+    return b + 4 * ps_align_up((size_t)c.hidden * 2);
 }
-
-struct Workspace {
-    SessTable *table;
-    __half *a, *q, *ctx, *x1, *xa, *xb, *g;
-    int8_t *xq;
-    int8_t *xo;         // outlier values per (token, 16-column group) of calls of at most 64 rows
-    float *sx;
-    uint32_t *masks;    // [n_blocks][4][mask_words]
-    double *partials;
-    int *ocount;
-    double *wd64, *x64;
-    ManyOutliers many;     // only carved when max_rows_per_call > 64
-    size_t mask_words;
-    size_t total;
-};
 
 Workspace carve(const petals_span_config &c, uint8_t *base) {
     Workspace w;
     const size_t M = (size_t)c.max_rows_per_call, Mp = (M + 15) / 16 * 16, H = c.hidden, F = c.ffn;
     const size_t Kmax = F > H ? F : H;
     size_t off = 0;
-    auto take = [&](size_t bytes) { uint8_t *p = base ? base + off : nullptr; off += align_up(bytes); return p; };
+    auto take = [&](size_t bytes) { uint8_t *p = base ? base + off : nullptr; off += ps_align_up(bytes); return p; };
     w.table = (SessTable *)take(sizeof(SessTable));
     w.a = (__half *)take(M * H * 2);
     w.q = (__half *)take(M * H * 2);
@@ -150,44 +123,6 @@ const CodeTable &code_table() {
 
 }  // namespace
 
-// Optional per-launch timing with HIP events recorded on the caller's stream.
-struct Profiler {
-    bool on = false;
-    std::vector<hipEvent_t> ev;        // pairs (start, stop)
-    std::vector<int> cls, kind;        // kernel class of pair i; which linear it was (-1: none)
-    size_t used = 0;
-    bool begin(int kernel_class, int which, hipStream_t st) {
-        if (!on || (used + 1) * 2 > ev.size()) return false;
-        cls[used] = kernel_class;
-        kind[used] = which;
-        return hipEventRecord(ev[used * 2], st) == hipSuccess;
-    }
-    void end(bool started, hipStream_t st) {
-        if (!started) return;
-        (void)hipEventRecord(ev[used * 2 + 1], st);
-        used++;
-    }
-};
-
-struct petals_span {
-    petals_span_config cfg;
-    Profiler prof;
-    uint8_t *wmem;
-    Workspace ws;
-    std::vector<BlockW> blocks;
-    double slopes[PS_MAX_HEADS];
-    int open_sessions;
-    // optional cache of the transposed dequantized weights for the backward pass: [block][linear]
-    __half *bwd_cache = nullptr;
-    std::vector<uint8_t> bwd_cached;     // 1: the tiles of (block, linear) are in the cache
-};
-
-struct petals_session {
-    petals_span *span;
-    __half *kv;
-    int cap, len;
-};
-
 namespace {
 
 // One linear on M rows resident as fp16 X[M,K]; picks the one-row or the MFMA path.  ln_g/ln_b non-null:
@@ -224,14 +159,6 @@ int run_linear(petals_span *sp, int which, const LinearW &w, const __half *X, co
     }
     return PETALS_OK;
 }
-
-// What a forward pass keeps for the backward pass, per block: the block's input x[b] (x[n_blocks] is the
-// span's output), queries, the attention context before its fp16 rounding, x1 = x + attention branch, the sum
-// fed to GeLU, and the log of the softmax denominators.  Keys and values stay in the (internal) caches.
-struct SaveSet {
-    std::vector<__half *> x, q, x1, pre;
-    std::vector<float *> lse, ctx32;
-};
 
 OutDesc plain_out(__half *y, int epilogue, const __half *resid) {
     OutDesc o;
@@ -290,98 +217,14 @@ int forward_blocks(petals_span *sp, int M, int T, int max_keys, const __half *hi
     return PETALS_OK;
 }
 
-// Device memory of one backward call: what the forward pass keeps, the internal key/value memory of the
-// B sequences, and the scratch of the backward kernels.
-struct BackwardStore {
-    SaveSet save;
-    __half *kv;          // B sequences x [n_blocks][key|value][head][T][d]
-    size_t kv_per_seq;   // halves
-    __half *y_last;      // the span's output when the caller does not ask for it
-    __half *gy[2];       // gradient w.r.t. a block's input, alternating between blocks
-    __half *gx1;         // gradient w.r.t. x1
-    __half *tiles;       // gradient rows in matrix-instruction tile order, up to [ceil16(M), max(F, 3H)]
-    __half *wt16;        // transposed dequantized weights of one linear
-    float *out32;        // one backward product, up to [M, max(F, H)]
-    __half *dO, *dqkv, *QT, *KT, *dOT;
-    float *Dv;
-    size_t total;
-};
-
-BackwardStore carve_backward(const petals_span_config &c, int B, int T, uint8_t *base) {
-    BackwardStore s;
-    const size_t M = (size_t)B * T, Mp = (M + 15) / 16 * 16, Tp = ((size_t)T + 31) / 32 * 32, H = c.hidden, F = c.ffn;
-    const size_t Nmax = 3 * H > F ? 3 * H : F;
-    size_t off = 0;
-    auto take = [&](size_t bytes) { uint8_t *p = base ? base + off : nullptr; off += align_up(bytes); return p; };
-    const int nb = c.n_blocks;
-    s.save.x.assign(nb + 1, nullptr);
-    s.save.q.resize(nb); s.save.ctx32.resize(nb); s.save.x1.resize(nb); s.save.pre.resize(nb); s.save.lse.resize(nb);
-    for (int b = 0; b < nb; b++) {
-        if (b > 0) s.save.x[b] = (__half *)take(M * H * 2);
-        s.save.q[b] = (__half *)take(M * H * 2);
-        s.save.ctx32[b] = (float *)take(M * H * 4);
-        s.save.x1[b] = (__half *)take(M * H * 2);
-        s.save.pre[b] = (__half *)take(M * F * 2);
-        s.save.lse[b] = (float *)take((size_t)c.n_heads * M * 4);
-    }
-    s.kv_per_seq = (size_t)nb * 2 * H * T;
-    s.kv = (__half *)take((size_t)B * s.kv_per_seq * 2);
-    s.y_last = (__half *)take(M * H * 2);
-    s.gy[0] = (__half *)take(M * H * 2);
-    s.gy[1] = (__half *)take(M * H * 2);
-    s.gx1 = (__half *)take(M * H * 2);
-    s.tiles = (__half *)take(Mp * Nmax * 2);
-    s.wt16 = (__half *)take(Nmax * H * 2);
-    s.out32 = (float *)take(M * (F > H ? F : H) * 4);
-    s.dO = (__half *)take(M * H * 2);
-    s.dqkv = (__half *)take(M * 3 * H * 2);
-    s.QT = (__half *)take((size_t)B * H * Tp * 2);
-    s.KT = (__half *)take((size_t)B * H * Tp * 2);
-    s.dOT = (__half *)take((size_t)B * H * Tp * 2);
-    s.Dv = (float *)take((size_t)c.n_heads * M * 4);
-    s.total = off;
-    return s;
-}
-
-int check_backward_shape(const petals_span_config &c, int32_t B, int32_t T) {
-    if (B < 1 || T < 1) return fail(PETALS_ERR_INVALID_ARG, "B and T must be positive");
-    if (B > PETALS_MAX_SESSIONS_PER_CALL) return fail(PETALS_ERR_CAPACITY, "more than %d sequences in one call", PETALS_MAX_SESSIONS_PER_CALL);
-    if ((int64_t)B * T > c.max_rows_per_call)
-        return fail(PETALS_ERR_CAPACITY, "%lld rows exceed max_rows_per_call %d", (long long)B * T, c.max_rows_per_call);
-    return PETALS_OK;
-}
-
-size_t backward_cache_block_halves(const petals_span_config &c) {
-    size_t h = 0;
-    for (int i = 0; i < 4; i++) {
-        int N, K;
-        linear_dims(c, i, &N, &K);
-        h += align_up((size_t)N * K * 2) / 2;
-    }
-    return h;
-}
-
-// dX[M, K] (fp32, into out32) = rows (already in tile order) x dequantized weights of linear `which` of block b.
-// The transposed fp16 tiles of the weights are built per call, or once if the span has a cache attached.
-int backward_product(petals_span *sp, int b, int which, const __half *row_tiles, int M, BackwardStore &bs,
-                     hipStream_t st) {
-    const LinearW &w = sp->blocks[b].lin[which];
-    __half *wt16 = bs.wt16;
-    if (sp->bwd_cache) {
-        wt16 = sp->bwd_cache + (size_t)b * backward_cache_block_halves(sp->cfg);
-        for (int i = 0; i < which; i++) wt16 += align_up((size_t)sp->blocks[b].lin[i].N * sp->blocks[b].lin[i].K * 2) / 2;
-    }
-    if (!sp->bwd_cache || !sp->bwd_cached[b * 4 + which]) {
-        HIP_TRY(ps_transpose_w(w, wt16, st));
-        if (sp->bwd_cache) sp->bwd_cached[b * 4 + which] = 1;
-    }
-    const bool pr = sp->prof.begin(PETALS_PROFILE_BWD_GEMM, which, st);
-    HIP_TRY(ps_gemm_f16_tiles(wt16, row_tiles, w.N / 32, M, w.K, bs.out32, st));
-    sp->prof.end(pr, st);
-    return PETALS_OK;
-}
-
 }  // namespace
+
+void ps_linear_dims(const petals_span_config &c, int which, int *N, int *K) { linear_dims(c, which, N, K); }
+int ps_check_config(const petals_span_config *c) { return check_config(c); }
+int ps_forward_blocks(petals_span *sp, int M, int T, int max_keys, const __half *hidden_in, __half *hidden_out,
+                      const SaveSet *save, hipStream_t st) {
+    return forward_blocks(sp, M, T, max_keys, hidden_in, hidden_out, save, st);
+}
 
 extern "C" {
 
@@ -430,14 +273,14 @@ int petals_span_create(const petals_span_config *cfg, void *dev_weight_mem, void
             linear_dims(*cfg, i, &N, &K);
             B.lin[i].N = N;
             B.lin[i].K = K;
-            B.lin[i].wt = (int8_t *)p;       p += align_up((size_t)N * K);
-            B.lin[i].sw = (float *)p;        p += align_up((size_t)N * 4);
-            B.lin[i].bias = (__half *)p;     p += align_up((size_t)N * 2);
+            B.lin[i].wt = (int8_t *)p;       p += ps_align_up((size_t)N * K);
+            B.lin[i].sw = (float *)p;        p += ps_align_up((size_t)N * 4);
+            B.lin[i].bias = (__half *)p;     p += ps_align_up((size_t)N * 2);
         }
-        B.ln1g = (__half *)p; p += align_up((size_t)cfg->hidden * 2);
-        B.ln1b = (__half *)p; p += align_up((size_t)cfg->hidden * 2);
-        B.ln2g = (__half *)p; p += align_up((size_t)cfg->hidden * 2);
-        B.ln2b = (__half *)p; p += align_up((size_t)cfg->hidden * 2);
+        B.ln1g = (__half *)p; p += ps_align_up((size_t)cfg->hidden * 2);
+        B.ln1b = (__half *)p; p += ps_align_up((size_t)cfg->hidden * 2);
+        B.ln2g = (__half *)p; p += ps_align_up((size_t)cfg->hidden * 2);
+        B.ln2b = (__half *)p; p += ps_align_up((size_t)cfg->hidden * 2);
         B.loaded = false;
     }
     // ALiBi slopes: geometric sequence for the largest power of two n2 <= heads, the
@@ -607,90 +450,6 @@ int petals_session_replay(petals_span *sp, petals_session *se, const void *hidde
     return PETALS_OK;
 }
 
-int petals_span_backward_bytes(const petals_span_config *cfg, int32_t B, int32_t T, size_t *bytes) {
-    if (int rc = check_config(cfg)) return rc;
-    if (!bytes) return fail(PETALS_ERR_INVALID_ARG, "bytes is null");
-    if (int rc = check_backward_shape(*cfg, B, T)) return rc;
-    *bytes = carve_backward(*cfg, B, T, nullptr).total;
-    return PETALS_OK;
-}
-
-int petals_span_backward_cache_bytes(const petals_span_config *cfg, size_t *bytes) {
-    if (int rc = check_config(cfg)) return rc;
-    if (!bytes) return fail(PETALS_ERR_INVALID_ARG, "bytes is null");
-    *bytes = backward_cache_block_halves(*cfg) * 2 * (size_t)cfg->n_blocks;
-    return PETALS_OK;
-}
-
-int petals_span_backward_attach_cache(petals_span *sp, void *dev_cache) {
-    if (!sp) return fail(PETALS_ERR_INVALID_ARG, "null span");
-    if ((uintptr_t)dev_cache & 255) return fail(PETALS_ERR_INVALID_ARG, "cache memory must be 256-byte aligned");
-    sp->bwd_cache = (__half *)dev_cache;
-    sp->bwd_cached.assign(sp->bwd_cached.size(), 0);
-    return PETALS_OK;
-}
-
-int petals_span_backward(petals_span *sp, void *dev_store, int32_t B, int32_t T, const void *hidden_in,
-                         const void *grad_out, void *hidden_out, void *grad_in, void *stream) {
-    if (!sp || !dev_store || !hidden_in || !grad_out || !grad_in) return fail(PETALS_ERR_INVALID_ARG, "null pointer");
-    if ((uintptr_t)dev_store & 255) return fail(PETALS_ERR_INVALID_ARG, "store memory must be 256-byte aligned");
-    if (grad_in == grad_out || grad_in == hidden_in || (hidden_out && (hidden_out == hidden_in || hidden_out == grad_in || hidden_out == grad_out)))
-        return fail(PETALS_ERR_INVALID_ARG, "buffers alias");
-    const petals_span_config &c = sp->cfg;
-    if (int rc = check_backward_shape(c, B, T)) return rc;
-    for (int b = 0; b < c.n_blocks; b++)
-        if (!sp->blocks[b].loaded) return fail(PETALS_ERR_STATE, "block %d has not been loaded", b);
-    BackwardStore bs = carve_backward(c, B, T, (uint8_t *)dev_store);
-    bs.save.x[0] = (__half *)hidden_in;      // read only
-    __half *y = hidden_out ? (__half *)hidden_out : bs.y_last;
-    bs.save.x[c.n_blocks] = y;
-
-    // forward pass on fresh internal sequences of exactly T positions
-    SessTable tab;
-    memset(&tab, 0, sizeof(tab));
-    for (int s = 0; s < B; s++) {
-        tab.kv[s] = bs.kv + (size_t)s * bs.kv_per_seq;
-        tab.len[s] = 0;
-        tab.cap[s] = T;
-    }
-    memcpy(tab.slopes, sp->slopes, sizeof(tab.slopes));
-    hipStream_t st = (hipStream_t)stream;
-    Workspace &ws = sp->ws;
-    const int M = B * T, H = c.hidden, F = c.ffn, nh = c.n_heads, d = H / nh;
-    HIP_TRY(ps_set_table(tab, ws.table, st));
-    if (int rc = forward_blocks(sp, M, T, T, (const __half *)hidden_in, y, &bs.save, st)) return rc;
-
-    // backward, last block first; gy: gradient w.r.t. the output of the block at hand
-    const __half *gy = (const __half *)grad_out;
-    for (int b = c.n_blocks - 1; b >= 0; b--) {
-        const BlockW &W = sp->blocks[b];
-        // x2 = x1 + down(GeLU(pre)):  dpre = (gy Wd_down) * GeLU'(pre), written in tile order
-        HIP_TRY(ps_tile_rows(gy, M, H, bs.tiles, st));
-        if (int rc = backward_product(sp, b, 3, bs.tiles, M, bs, st)) return rc;
-        HIP_TRY(ps_gelu_bwd(bs.out32, bs.save.pre[b], M, F, bs.tiles, st));
-        // pre = up(LayerNorm2(x1)):  dx1 = gy + LayerNorm2'(dpre Wd_up)
-        if (int rc = backward_product(sp, b, 2, bs.tiles, M, bs, st)) return rc;
-        HIP_TRY(ps_ln_bwd(bs.out32, bs.save.x1[b], W.ln2g, gy, c.ln_eps, M, H, bs.gx1, st));
-        // x1 = x + dense(ctx):  dctx = dx1 Wd_dense
-        HIP_TRY(ps_tile_rows(bs.gx1, M, H, bs.tiles, st));
-        if (int rc = backward_product(sp, b, 1, bs.tiles, M, bs, st)) return rc;
-        HIP_TRY(ps_attn_bwd_prep(bs.out32, bs.save.ctx32[b], M, nh, d, bs.dO, bs.Dv, st));
-        {
-            const bool pr = sp->prof.begin(PETALS_PROFILE_BWD_ATTENTION, -1, st);
-            HIP_TRY(ps_attention_bwd(bs.save.q[b], ws.table, b, B, T, nh, d, bs.dO, bs.QT, bs.KT, bs.dOT, bs.save.lse[b],
-                                     bs.Dv, bs.dqkv, st));
-            sp->prof.end(pr, st);
-        }
-        // qkv = Lin(LayerNorm1(x)):  dx = dx1 + LayerNorm1'(dqkv Wd_qkv)
-        HIP_TRY(ps_tile_rows(bs.dqkv, M, 3 * H, bs.tiles, st));
-        if (int rc = backward_product(sp, b, 0, bs.tiles, M, bs, st)) return rc;
-        __half *gx = b == 0 ? (__half *)grad_in : bs.gy[b & 1];
-        HIP_TRY(ps_ln_bwd(bs.out32, bs.save.x[b], W.ln1g, bs.gx1, c.ln_eps, M, H, gx, st));
-        gy = gx;
-    }
-    return PETALS_OK;
-}
-
 int petals_hidden_code_table(float *host_table256) {
     if (!host_table256) return fail(PETALS_ERR_INVALID_ARG, "null pointer");
     memcpy(host_table256, code_table().code, sizeof(float) * 256);
@@ -731,23 +490,6 @@ int petals_debug_linear(petals_span *sp, int32_t block, int32_t which, const voi
     if (int rc = run_linear(sp, which, L, (const __half *)x, nullptr, nullptr, M, mk, false, o, xq, true, st)) return rc;
     if (sx) HIP_TRY(ps_copy_bytes(ws.sx, sx, (size_t)M * 4, st));
     if (outlier_mask) HIP_TRY(ps_mask_to_bytes(mk, L.K, outlier_mask, st));
-    return PETALS_OK;
-}
-
-int petals_debug_backward_product(petals_span *sp, void *dev_store, int32_t B, int32_t T, int32_t block, int32_t which,
-                                  const void *dy, float *dx, void *stream) {
-    if (!sp || !dev_store || !dy || !dx) return fail(PETALS_ERR_INVALID_ARG, "null pointer");
-    if ((uintptr_t)dev_store & 255) return fail(PETALS_ERR_INVALID_ARG, "store memory must be 256-byte aligned");
-    if (block < 0 || block >= sp->cfg.n_blocks || which < 0 || which > 3) return fail(PETALS_ERR_INVALID_ARG, "block or linear index out of range");
-    if (!sp->blocks[block].loaded) return fail(PETALS_ERR_STATE, "block %d has not been loaded", block);
-    if (int rc = check_backward_shape(sp->cfg, B, T)) return rc;
-    BackwardStore bs = carve_backward(sp->cfg, B, T, (uint8_t *)dev_store);
-    const LinearW &L = sp->blocks[block].lin[which];
-    const int M = B * T;
-    hipStream_t st = (hipStream_t)stream;
-    HIP_TRY(ps_tile_rows((const __half *)dy, M, L.N, bs.tiles, st));
-    if (int rc = backward_product(sp, block, which, bs.tiles, M, bs, st)) return rc;
-    HIP_TRY(ps_copy_bytes(bs.out32, dx, (size_t)M * L.K * 4, st));
     return PETALS_OK;
 }
 
