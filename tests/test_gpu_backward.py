@@ -85,7 +85,7 @@ def _check(cfg, nb, B, T, wscale, seed=0, min_branch=0.05, strict=True):
         osp.destroy()
 
 
-@pytest.mark.parametrize("B,T", [(1, 1), (1, 7), (2, 16), (3, 33), (1, 70), (2, 100)])
+@pytest.mark.parametrize("B,T", [(1, 1), (1, 7), (2, 16), (3, 33), (1, 70), (2, 100), (64, 2), (5, 1), (1, 128)])
 def test_backward_c1_shape(B, T):
     _check(synth.CONFIGS["C1"], 2, B, T, wscale=8.0, seed=B * 100 + T)
 
