@@ -17,7 +17,8 @@ struct BackwardStore {
     __half *y_last;      // the span's output when the caller does not ask for it
     __half *gy[2];       // gradient w.r.t. a block's input, alternating between blocks
     __half *gx1;         // gradient w.r.t. x1
-    __half *tiles;       // gradient rows in matrix-instruction tile order, up to [ceil16(M), max(F, 3H)]
+    __half *tiles;       // gradient rows in matrix-instruction tile order, up to [ceil16(M), 3H]
+    __half *tiles2;      // gradient of the GeLU input in tile order [ceil16(M), F] (written by the product before it)
     __half *wt16;        // transposed dequantized weights of one linear
     float *out32;        // one backward product, up to [M, max(F, H)]
     __half *dO, *dqkv, *QT, *KT, *dOT;
@@ -49,6 +50,7 @@ BackwardStore carve_backward(const petals_span_config &c, int B, int T, uint8_t 
     s.gy[1] = (__half *)take(M * H * 2);
     s.gx1 = (__half *)take(M * H * 2);
     s.tiles = (__half *)take(Mp * Nmax * 2);
+    s.tiles2 = (__half *)take(Mp * F * 2);
     s.wt16 = (__half *)take(Nmax * H * 2);
     s.out32 = (float *)take(M * (F > H ? F : H) * 4);
     s.dO = (__half *)take(M * H * 2);
@@ -81,8 +83,9 @@ size_t backward_cache_block_halves(const petals_span_config &c) {
 
 // dX[M, K] (fp32, into out32) = rows (already in tile order) x dequantized weights of linear `which` of block b.
 // The transposed fp16 tiles of the weights are built per call, or once if the span has a cache attached.
+// gelu_pre / tile_out: see ps_gemm_f16_tiles (the product of the down linear, fused with GeLU').
 int backward_product(petals_span *sp, int b, int which, const __half *row_tiles, int M, BackwardStore &bs,
-                     hipStream_t st) {
+                     const __half *gelu_pre, __half *tile_out, hipStream_t st) {
     const LinearW &w = sp->blocks[b].lin[which];
     __half *wt16 = bs.wt16;
     if (sp->bwd_cache) {
@@ -94,7 +97,7 @@ int backward_product(petals_span *sp, int b, int which, const __half *row_tiles,
         if (sp->bwd_cache) sp->bwd_cached[b * 4 + which] = 1;
     }
     const bool pr = sp->prof.begin(PETALS_PROFILE_BWD_GEMM, which, st);
-    HIP_TRY(ps_gemm_f16_tiles(wt16, row_tiles, w.N / 32, M, w.K, bs.out32, st));
+    HIP_TRY(ps_gemm_f16_tiles(wt16, row_tiles, w.N / 32, M, w.K, bs.out32, gelu_pre, tile_out, st));
     sp->prof.end(pr, st);
     return PETALS_OK;
 }
@@ -160,16 +163,15 @@ int petals_span_backward(petals_span *sp, void *dev_store, int32_t B, int32_t T,
     const __half *gy = (const __half *)grad_out;
     for (int b = c.n_blocks - 1; b >= 0; b--) {
         const BlockW &W = sp->blocks[b];
-        // x2 = x1 + down(GeLU(pre)):  dpre = (gy Wd_down) * GeLU'(pre), written in tile order
+        // x2 = x1 + down(GeLU(pre)):  dpre = (gy Wd_down) * GeLU'(pre), written in tile order by the product's epilogue
         HIP_TRY(ps_tile_rows(gy, M, H, bs.tiles, st));
-        if (int rc = backward_product(sp, b, 3, bs.tiles, M, bs, st)) return rc;
-        HIP_TRY(ps_gelu_bwd(bs.out32, bs.save.pre[b], M, F, bs.tiles, st));
+        if (int rc = backward_product(sp, b, 3, bs.tiles, M, bs, bs.save.pre[b], bs.tiles2, st)) return rc;
         // pre = up(LayerNorm2(x1)):  dx1 = gy + LayerNorm2'(dpre Wd_up)
-        if (int rc = backward_product(sp, b, 2, bs.tiles, M, bs, st)) return rc;
+        if (int rc = backward_product(sp, b, 2, bs.tiles2, M, bs, nullptr, nullptr, st)) return rc;
         HIP_TRY(ps_ln_bwd(bs.out32, bs.save.x1[b], W.ln2g, gy, c.ln_eps, M, H, bs.gx1, st));
         // x1 = x + dense(ctx):  dctx = dx1 Wd_dense
         HIP_TRY(ps_tile_rows(bs.gx1, M, H, bs.tiles, st));
-        if (int rc = backward_product(sp, b, 1, bs.tiles, M, bs, st)) return rc;
+        if (int rc = backward_product(sp, b, 1, bs.tiles, M, bs, nullptr, nullptr, st)) return rc;
         HIP_TRY(ps_attn_bwd_prep(bs.out32, bs.save.ctx32[b], M, nh, d, bs.dO, bs.Dv, st));
         {
             const bool pr = sp->prof.begin(PETALS_PROFILE_BWD_ATTENTION, -1, st);
@@ -179,7 +181,7 @@ int petals_span_backward(petals_span *sp, void *dev_store, int32_t B, int32_t T,
         }
         // qkv = Lin(LayerNorm1(x)):  dx = dx1 + LayerNorm1'(dqkv Wd_qkv)
         HIP_TRY(ps_tile_rows(bs.dqkv, M, 3 * H, bs.tiles, st));
-        if (int rc = backward_product(sp, b, 0, bs.tiles, M, bs, st)) return rc;
+        if (int rc = backward_product(sp, b, 0, bs.tiles, M, bs, nullptr, nullptr, st)) return rc;
         __half *gx = b == 0 ? (__half *)grad_in : bs.gy[b & 1];
         HIP_TRY(ps_ln_bwd(bs.out32, bs.save.x[b], W.ln1g, bs.gx1, c.ln_eps, M, H, gx, st));
         gy = gx;
@@ -199,7 +201,7 @@ int petals_debug_backward_product(petals_span *sp, void *dev_store, int32_t B, i
     const int M = B * T;
     hipStream_t st = (hipStream_t)stream;
     HIP_TRY(ps_tile_rows((const __half *)dy, M, L.N, bs.tiles, st));
-    if (int rc = backward_product(sp, block, which, bs.tiles, M, bs, st)) return rc;
+    if (int rc = backward_product(sp, block, which, bs.tiles, M, bs, nullptr, nullptr, st)) return rc;
     HIP_TRY(ps_copy_bytes(bs.out32, dx, (size_t)M * L.K * 4, st));
     return PETALS_OK;
 }

@@ -59,31 +59,6 @@ __global__ void __launch_bounds__(256) k_transpose_w(LinearW w, __half *__restri
     }
 }
 
-// derivative of the tanh-form GeLU
-__device__ __forceinline__ float gelu_tanh_grad(float p) {
-    const float c0 = 0.7978845608028654f, c1 = 0.044715f;
-    const float t = tanhf(c0 * (p + c1 * p * p * p));
-    return 0.5f * (1.0f + t) + 0.5f * p * (1.0f - t * t) * c0 * (1.0f + 3.0f * c1 * p * p);
-}
-
-// du = dg * GeLU'(pre), stored as fp16 straight into the tile order of the next backward product.
-// dg [M,N] fp32 (backward product of the down linear), pre [M,N] fp16 (what the forward pass fed to GeLU).
-__global__ void __launch_bounds__(64) k_gelu_bwd(const float *__restrict__ dg, const __half *__restrict__ pre, int M,
-                                                 int N, __half *__restrict__ tiles) {
-    const int CT = N >> 5, MTT = (M + 15) >> 4, lane = threadIdx.x;
-    for (int item = blockIdx.x; item < MTT * CT; item += gridDim.x) {
-        const int mt = item / CT, ct = item - mt * CT, t = mt * 16 + (lane & 15), c0 = ct * 32 + (lane >> 4) * 8;
-        v8h out = {0, 0, 0, 0, 0, 0, 0, 0};
-        if (t < M) {
-            const v8h p8 = *(const v8h *)(pre + (size_t)t * N + c0);
-            const v4f a = *(const v4f *)(dg + (size_t)t * N + c0), b = *(const v4f *)(dg + (size_t)t * N + c0 + 4);
-#pragma unroll
-            for (int e = 0; e < 8; e++) out[e] = (_Float16)((e < 4 ? a[e] : b[e - 4]) * gelu_tanh_grad((float)p8[e]));
-        }
-        *(v8h *)(tiles + ((size_t)item * 64 + lane) * 8) = out;
-    }
-}
-
 // dx = dres + LayerNorm'(x)^T (dz * gain): one workgroup per row, the row in registers (H <= 16384).
 // dz [M,H] fp32 is the backward product of the linear that read the LayerNorm output.
 __global__ void __launch_bounds__(1024) k_ln_bwd(const float *__restrict__ dz, const __half *__restrict__ x,
@@ -419,11 +394,6 @@ hipError_t ps_tile_rows(const __half *X, int M, int N, __half *tiles, hipStream_
 
 hipError_t ps_transpose_w(const LinearW &w, __half *wt16, hipStream_t st) {
     k_transpose_w<<<2048, 256, 0, st>>>(w, wt16);
-    return hipGetLastError();
-}
-
-hipError_t ps_gelu_bwd(const float *dg, const __half *pre, int M, int N, __half *tiles, hipStream_t st) {
-    k_gelu_bwd<<<8192, 64, 0, st>>>(dg, pre, M, N, tiles);
     return hipGetLastError();
 }
 

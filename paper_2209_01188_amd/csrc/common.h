@@ -129,10 +129,11 @@ hipError_t ps_attention(const __half *q, const SessTable *sess, int blk, int M, 
 hipError_t ps_tile_rows(const __half *X, int M, int N, __half *tiles, hipStream_t st);
 // the linear's dequantized fp16 weights, transposed, in the same tile order: [K/16][N/32][512 halves]
 hipError_t ps_transpose_w(const LinearW &w, __half *wt16, hipStream_t st);
-// out[M, n_feat] (fp32) = token tiles [ceil(M/16)][ktiles] x feature tiles [n_feat/16][ktiles], contraction 32 * ktiles
+// out[M, n_feat] (fp32) = token tiles [ceil(M/16)][ktiles] x feature tiles [n_feat/16][ktiles], contraction 32 * ktiles.
+// With gelu_pre ([M, n_feat] fp16, n_feat % 32 == 0) the result is not stored as fp32: fp16(result * GeLU'(gelu_pre))
+// goes to tile_out in token-tile order [ceil(M/16)][n_feat/32][512 halves], rows beyond M zero (out is unused).
 hipError_t ps_gemm_f16_tiles(const __half *feat_tiles, const __half *tok_tiles, int ktiles, int M, int n_feat,
-                             float *out, hipStream_t st);
-hipError_t ps_gelu_bwd(const float *dg, const __half *pre, int M, int N, __half *tiles, hipStream_t st);
+                             float *out, const __half *gelu_pre, __half *tile_out, hipStream_t st);
 hipError_t ps_ln_bwd(const float *dz, const __half *x, const __half *g, const __half *dres, float eps, int M, int H,
                      __half *dx, hipStream_t st);
 hipError_t ps_attn_bwd_prep(const float *dctx, const float *ctx32, int M, int nh, int d, __half *dO, float *Dv,

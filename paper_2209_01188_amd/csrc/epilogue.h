@@ -73,6 +73,13 @@ __device__ __forceinline__ void emit_output4(const OutDesc &o, const SessTable *
     *(v2i *)dst = *(const v2i *)out;
 }
 
+// derivative of the tanh-form GeLU (backward pass)
+__device__ __forceinline__ float gelu_tanh_grad(float p) {
+    const float c0 = 0.7978845608028654f, c1 = 0.044715f;
+    const float t = tanhf(c0 * (p + c1 * p * p * p));
+    return 0.5f * (1.0f + t) + 0.5f * p * (1.0f - t * t) * c0 * (1.0f + 3.0f * c1 * p * p);
+}
+
 // fp16 weight reconstructed from an int8 code: fp32 product rounded to fp16
 __device__ __forceinline__ float dequant_w16(int code, float swd) {
     return __half2float(__float2half_rn(keep_f32((float)code * swd)));

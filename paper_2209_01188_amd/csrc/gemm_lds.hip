@@ -109,6 +109,10 @@ struct GemmArgs {
     int ktiles;                     // int8: K/64.  fp16: 0 = derived from the outlier count, else the plain product's tile count
     int M, N;
     int nb_n, nb_m;
+    // plain fp16 product only: instead of the fp32 result, store fp16(result * GeLU'(gelu_pre)) in the tile order
+    // of the next product's token-side operand (16 x 32 tiles, rows beyond M zero)
+    const __half *gelu_pre;   // [M, N] fp16, or null
+    __half *tile_out;
 };
 
 // F16 = false: int8 main product with the full epilogue.  F16 = true: fp16 outlier product into outl.
@@ -294,8 +298,19 @@ k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, 
             for (int idx = 0; idx < QN * TM; idx++) {
                 const int nt = nt0 + wn * TN + p * QN + idx / TM, mt = mt0 + wm * TM + idx % TM;
                 if (nt >= NT || mt >= MTT) continue;                    // wave-uniform
-                const int t = mt * 16 + row;
-                if (t < M) *(v4f *)(outl + (size_t)t * N + nt * 16 + 4 * kg) = mine[idx * 64];
+                const int t = mt * 16 + row, n0 = nt * 16 + 4 * kg;
+                if (ga.gelu_pre) {
+                    v4h du = {(_Float16)0, (_Float16)0, (_Float16)0, (_Float16)0};
+                    if (t < M) {
+                        const v4f a = mine[idx * 64];
+                        const v4h pre = *(const v4h *)(ga.gelu_pre + (size_t)t * N + n0);
+#pragma unroll
+                        for (int r = 0; r < 4; r++) du[r] = (_Float16)(a[r] * gelu_tanh_grad((float)pre[r]));
+                    }
+                    *(v4h *)(ga.tile_out + (((size_t)mt * (N >> 5) + (n0 >> 5)) * 64 + row + 16 * ((n0 & 31) >> 3)) * 8 + (n0 & 7)) = du;
+                } else if (t < M) {
+                    *(v4f *)(outl + (size_t)t * N + n0) = mine[idx * 64];
+                }
             }
         }
     } else {
@@ -459,9 +474,11 @@ hipError_t launch_lds(const GemmArgs &ga0, const LinearW &w, const float *sx, co
 }  // namespace
 
 hipError_t ps_gemm_f16_tiles(const __half *feat_tiles, const __half *tok_tiles, int ktiles, int M, int n_feat,
-                             float *out, hipStream_t st) {
+                             float *out, const __half *gelu_pre, __half *tile_out, hipStream_t st) {
     if (ktiles < 1 || M < 1 || n_feat < 16 || n_feat % 16) return hipErrorInvalidValue;
-    GemmArgs ga = {(const unsigned char *)feat_tiles, (const unsigned char *)tok_tiles, ktiles, M, n_feat, 0, 0};
+    if (gelu_pre && (!tile_out || n_feat % 32)) return hipErrorInvalidValue;
+    GemmArgs ga = {(const unsigned char *)feat_tiles, (const unsigned char *)tok_tiles, ktiles, M, n_feat, 0, 0,
+                   gelu_pre, tile_out};
     LinearW w;
     OutlierSet os;
     OutDesc o;
@@ -480,9 +497,9 @@ hipError_t ps_gemm_lds(const LinearW &w, const int8_t *xq_tiled, const uint32_t 
     k_gather_w<<<4096, 64, 0, st>>>(w, os.count, mo.list, mo.wo);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    GemmArgs gf = {(const unsigned char *)mo.wo, (const unsigned char *)mo.xo, 0, M, w.N, 0, 0};
+    GemmArgs gf = {(const unsigned char *)mo.wo, (const unsigned char *)mo.xo, 0, M, w.N, 0, 0, nullptr, nullptr};
     e = launch_lds<true>(gf, w, sx, os, mo.outl, o, sess, st);
     if (e != hipSuccess) return e;
-    GemmArgs gi = {(const unsigned char *)w.wt, (const unsigned char *)xq_tiled, w.K / 64, M, w.N, 0, 0};
+    GemmArgs gi = {(const unsigned char *)w.wt, (const unsigned char *)xq_tiled, w.K / 64, M, w.N, 0, 0, nullptr, nullptr};
     return launch_lds<false>(gi, w, sx, os, mo.outl, o, sess, st);
 }
