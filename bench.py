@@ -281,28 +281,28 @@ def backward_main(args, dev):
     g.manual_seed(1234)
     dY = torch.empty(X.shape, dtype=torch.float32, device=dev).normal_(0.0, 1.0, generator=g).to(torch.float16)
     store = torch.empty(binding.petals_span_backward_bytes(span.cfg, B, T), dtype=torch.uint8, device=dev)
-    out, gin = torch.empty_like(X), torch.empty_like(X)
+    gin = torch.empty_like(X)      # the forward output is not asked for: the client has it when it sends the gradient
     stream = torch.cuda.current_stream()
     for _ in range(W):
-        binding.petals_span_backward(span.handle, store, X, dY, out, gin)
+        binding.petals_span_backward(span.handle, store, X, dY, None, gin)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
 
     def timed():
         e0.record(stream)
         for _ in range(K_steps):
-            binding.petals_span_backward(span.handle, store, X, dY, out, gin)
+            binding.petals_span_backward(span.handle, store, X, dY, None, gin)
         e1.record(stream)
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / K_steps
 
     ms_rebuild = timed()            # the transposed fp16 weights are rebuilt from int8 in every call
     span.attach_backward_cache()    # ... or kept between calls (2 bytes per weight): the configuration reported
-    binding.petals_span_backward(span.handle, store, X, dY, out, gin)
+    binding.petals_span_backward(span.handle, store, X, dY, None, gin)
     torch.cuda.synchronize()
     ms = timed()
     binding.petals_span_profile_begin(span.handle, NB * 16)
-    binding.petals_span_backward(span.handle, store, X, dY, out, gin)
+    binding.petals_span_backward(span.handle, store, X, dY, None, gin)
     torch.cuda.synchronize()
     pm, pn = binding.petals_span_profile_end(span.handle)
     flops = sum(2.0 * M * n * k for n, k in (span.shapes(i) for i in range(4))) * NB

@@ -203,7 +203,8 @@ int petals_span_profile_end(petals_span *span, double *ms_per_class, int64_t *la
  * backward pass needs in dev_store, then backpropagates grad_out:
  *   hidden_in  dev fp16 [B, T, H]  inputs of the span
  *   grad_out   dev fp16 [B, T, H]  gradient of the loss w.r.t. the span's outputs
- *   hidden_out dev fp16 [B, T, H]  the span's outputs (may be NULL)
+ *   hidden_out dev fp16 [B, T, H]  the span's outputs (may be NULL: then the last block's down linear,
+ *                                  which nothing else reads, is not run; grad_in is the same bits either way)
  *   grad_in    dev fp16 [B, T, H]  gradient w.r.t. hidden_in
  * Arithmetic: the forward pass is petals_span_prefill's.  The derivative treats roundings and the int8
  * quantization of activations as the identity; a linear's backward product uses the weights

@@ -210,6 +210,7 @@ int forward_blocks(petals_span *sp, int M, int T, int max_keys, const __half *hi
         if (save) ou.pre_out = save->pre[b];
         if (int rc = run_linear(sp, 2, W.lin[2], x1b, W.ln2g, W.ln2b, M, mk + 2 * ws.mask_words, multi, ou, nullptr,
                                 false, st)) return rc;
+        if (!xout) break;    // backward pass without a caller for the output: nothing reads the last block's result
         if (int rc = run_linear(sp, 3, W.lin[3], ws.g, nullptr, nullptr, M, mk + 3 * ws.mask_words, multi,
                                 plain_out(xout, PETALS_EPILOGUE_RESIDUAL, x1b), nullptr, false, st)) return rc;
         x = xout;

@@ -14,7 +14,6 @@ struct BackwardStore {
     SaveSet save;
     __half *kv;          // B sequences x [n_blocks][key|value][head][T][d]
     size_t kv_per_seq;   // halves
-    __half *y_last;      // the span's output when the caller does not ask for it
     __half *gy[2];       // gradient w.r.t. a block's input, alternating between blocks
     __half *gx1;         // gradient w.r.t. x1
     __half *tiles;       // gradient rows in matrix-instruction tile order, up to [ceil16(M), 3H]
@@ -45,7 +44,6 @@ BackwardStore carve_backward(const petals_span_config &c, int B, int T, uint8_t 
     }
     s.kv_per_seq = (size_t)nb * 2 * H * T;
     s.kv = (__half *)take((size_t)B * s.kv_per_seq * 2);
-    s.y_last = (__half *)take(M * H * 2);
     s.gy[0] = (__half *)take(M * H * 2);
     s.gy[1] = (__half *)take(M * H * 2);
     s.gx1 = (__half *)take(M * H * 2);
@@ -141,7 +139,7 @@ int petals_span_backward(petals_span *sp, void *dev_store, int32_t B, int32_t T,
         if (!sp->blocks[b].loaded) return fail(PETALS_ERR_STATE, "block %d has not been loaded", b);
     BackwardStore bs = carve_backward(c, B, T, (uint8_t *)dev_store);
     bs.save.x[0] = (__half *)hidden_in;      // read only
-    __half *y = hidden_out ? (__half *)hidden_out : bs.y_last;
+    __half *y = (__half *)hidden_out;      // null: the last block's down linear is not run
     bs.save.x[c.n_blocks] = y;
 
     // forward pass on fresh internal sequences of exactly T positions

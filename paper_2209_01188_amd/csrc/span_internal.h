@@ -80,6 +80,7 @@ void ps_linear_dims(const petals_span_config &c, int which, int *N, int *K);
 int ps_check_config(const petals_span_config *c);
 // The blocks of the span on M = B*T rows whose session table already sits in the workspace.
 // save == nullptr: intermediates live in the workspace.  Otherwise they are written where save says and
-// the up linear also stores the sum it feeds to GeLU.
+// the up linear also stores the sum it feeds to GeLU; then hidden_out may be null, and the down linear of the
+// last block (whose result only hidden_out would receive) is skipped.
 int ps_forward_blocks(petals_span *sp, int M, int T, int max_keys, const __half *hidden_in, __half *hidden_out,
                       const SaveSet *save, hipStream_t st);

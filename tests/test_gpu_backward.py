@@ -111,6 +111,10 @@ def test_backward_forward_output_is_the_prefill_output_bit_for_bit():
         Y2 = gsp.prefill(sessions, X)
         torch.cuda.synchronize()
         assert torch.equal(Y.view(torch.int16), Y2.view(torch.int16))
+        # without a buffer for the forward output the gradient is the same bits
+        none, dX_only = gsp.backward(X, dY, want_output=False)
+        torch.cuda.synchronize()
+        assert none is None and torch.equal(dX_only.view(torch.int16), dX.view(torch.int16))
         # a second call on the same store gives the same bits (nothing carried over between calls)
         store = torch.empty(binding.petals_span_backward_bytes(gsp.cfg, 2, 50), dtype=torch.uint8, device=DEV)
         a = gsp.backward(X, dY, store=store)[1].clone()
