@@ -2,7 +2,8 @@
 // (products of fp16 values are exact; the fp16 context equals the exactly rounded one).
 // Decode (one query per session): k_attn_decode, one workgroup per (key range, head, query row),
 // wave-local online softmax, k_attn_combine merges the key ranges.  Prefill (several queries per
-// session): k_attn_prefill on the fp64 matrix instruction.
+// session): k_attn_prefill on the fp64 matrix instruction; for the backward pass it can also store the
+// log of the softmax denominators and the context before its fp16 rounding.
 #include "common.h"
 
 namespace {

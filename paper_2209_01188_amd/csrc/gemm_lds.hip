@@ -11,6 +11,10 @@
 // the activations and of the dequantized weights are gathered into dense fp16 tile arrays and
 // multiplied by the same pipeline with v_mfma_f32_16x16x32_f16 into an fp32 [M,N] buffer that the
 // int8 kernel's epilogue adds.
+//
+// The fp16 form of the pipeline also serves the backward pass as a plain product of two tile arrays
+// (ps_gemm_f16_tiles): fp32 result, or for the down linear fp16(result * GeLU') in the tile order of the
+// next product.
 #include "common.h"
 #include "epilogue.h"
 
