@@ -21,8 +21,6 @@
 namespace {
 
 constexpr int STRIP = 4;       // m-blocks per rasterization strip
-constexpr int NSLOT = 4;       // LDS ring slots
-constexpr int PD = NSLOT - 1;  // stages requested ahead
 
 // ---------------------------------------------------------------------------------------------
 // outlier column list and fp16 gathers (only do work when the call has > PS_EXACT_OUTLIERS)
@@ -112,7 +110,8 @@ struct GemmArgs {
     const unsigned char *b_tiles;   // token-side tiles:  [ceil(M/16)][KTILES][1024]
     int ktiles;                     // int8: K/64.  fp16: 0 = derived from the outlier count, else the plain product's tile count
     int M, N;
-    int nb_n, nb_m;
+    int nb_n, nb_m;                 // output blocks of this launch along the features and along the tokens
+    int nb_n0;                      // first feature block of this launch (a linear may be split over two launches)
     // plain fp16 product only: instead of the fp32 result, store fp16(result * GeLU'(gelu_pre)) in the tile order
     // of the next product's token-side operand (16 x 32 tiles, rows beyond M zero)
     const __half *gelu_pre;   // [M, N] fp16, or null
@@ -120,11 +119,13 @@ struct GemmArgs {
 };
 
 // F16 = false: int8 main product with the full epilogue.  F16 = true: fp16 outlier product into outl.
-template <bool F16, int WVN, int WVM, int TN, int TM>
+// NSLOT: LDS ring slots (NSLOT - 1 stages are requested ahead).
+template <bool F16, int WVN, int WVM, int TN, int TM, int NSLOT>
 __global__ void __launch_bounds__(64 * WVN * WVM, 2)   // two waves per SIMD: at most 256 registers
 k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, float *__restrict__ outl, OutDesc o,
            const SessTable *__restrict__ sess) {
     constexpr int NW = WVN * WVM, BN = WVN * TN, BM = WVM * TM, STAGE = BN + BM, LOADS = STAGE / NW;
+    constexpr int PD = NSLOT - 1;                    // stages requested ahead
     static_assert(STAGE % NW == 0, "every wave copies the same number of tiles per stage");
     extern __shared__ __align__(16) unsigned char lds[];
     // F16 with a tile count given: a plain fp16 product over ga.ktiles tiles (backward pass), no outlier set
@@ -150,7 +151,7 @@ k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, 
     const int M = ga.M, N = ga.N, NT = N >> 4, MTT = (M + 15) >> 4;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, row = lane & 15, kg = lane >> 4;
     const int wn = wave / WVM, wm = wave % WVM;
-    const int nt0 = bn * BN, mt0 = bm * BM;
+    const int nt0 = (ga.nb_n0 + bn) * BN, mt0 = bm * BM;
 
     // the stage tiles this wave copies: s = wave + NW*j; s < BN: weight tile, else token tile
     const unsigned char *src[LOADS];
@@ -289,7 +290,7 @@ k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, 
     // fused-QKV column goes) is tabulated in LDS once per block; what depends only on the token (row
     // scale / 127, row addresses) sits in registers: the loop body has no division left.
     constexpr int QN = TN / 2, NPARK = 2;                                // weight panels per parked half
-    static_assert(TN % 8 == 0 && LOADS % 2 == 0, "a stage is multiplied in eighths; the epilogue parks half of the accumulators at a time");
+    static_assert(TN % 8 == 0, "a stage is multiplied in eighths; the epilogue parks half of the accumulators at a time");
     acc_t *mine = (acc_t *)lds + (size_t)wave * (QN * TM * 64) + lane;
     if constexpr (F16) {
 #pragma unroll
@@ -452,19 +453,15 @@ k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, 
     }
 }
 
-template <bool F16>
-hipError_t launch_lds(const GemmArgs &ga0, const LinearW &w, const float *sx, const OutlierSet &os, float *outl,
+template <bool F16, int TM>
+hipError_t launch_one(const GemmArgs &ga, const LinearW &w, const float *sx, const OutlierSet &os, float *outl,
                       const OutDesc &o, const SessTable *sess, hipStream_t st) {
-    constexpr int WVN = 2, WVM = 4, TN = 8, TM = 4, BN = WVN * TN, BM = WVM * TM;   // 8 waves, 128 x 64 per wave
-    GemmArgs ga = ga0;
-    const int NT = ga.N / 16, MTT = (ga.M + 15) / 16;
-    ga.nb_n = (NT + BN - 1) / BN;
-    ga.nb_m = (MTT + BM - 1) / BM;
+    constexpr int WVN = 2, WVM = 4, TN = 8, NSLOT = 4, BN = WVN * TN, BM = WVM * TM;   // 8 waves, 128 x (16 TM) per wave
     const int total = ga.nb_n * ga.nb_m;
     const size_t lds_stage = (size_t)NSLOT * (BN + BM) * 1024;
     const size_t lds_epi = (size_t)WVN * WVM * (TN / 2) * TM * 1024 + (size_t)BN * 16 * 16 + (size_t)BN * 4 * 8 + (size_t)BN / 2 * 4;
     const size_t lds = lds_stage > lds_epi ? lds_stage : lds_epi;
-    auto kern = k_gemm_lds<F16, WVN, WVM, TN, TM>;
+    auto kern = k_gemm_lds<F16, WVN, WVM, TN, TM, NSLOT>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -475,13 +472,41 @@ hipError_t launch_lds(const GemmArgs &ga0, const LinearW &w, const float *sx, co
     return hipGetLastError();
 }
 
+// One workgroup per compute unit (128 KB of LDS): a launch of 256 x 256 blocks takes ceil(blocks / 256) rounds of
+// equal length, and a last round that fills half of the units or less costs as much as a full one (896 blocks: 4
+// rounds for the work of 3.5).  In that case the feature blocks of the last round go to a second launch with
+// blocks of half the token height (256 x 128, 128 x 32 per wave), which fills all units for a shorter round
+// (measured: 2 to 4 % of the linear's time; 4-wave workgroups with a 3-slot ring, two per unit, were slower).
+template <bool F16>
+hipError_t launch_lds(const GemmArgs &ga0, const LinearW &w, const float *sx, const OutlierSet &os, float *outl,
+                      const OutDesc &o, const SessTable *sess, hipStream_t st) {
+    constexpr int BN = 16, BM = 16, UNITS = 256;
+    GemmArgs ga = ga0;
+    const int NT = ga.N / 16, MTT = (ga.M + 15) / 16;
+    ga.nb_n = (NT + BN - 1) / BN;
+    ga.nb_m = (MTT + BM - 1) / BM;
+    ga.nb_n0 = 0;
+    const int total = ga.nb_n * ga.nb_m, rest = total % UNITS;
+    if (total > UNITS && rest > 0 && rest <= UNITS / 2 && rest % ga.nb_m == 0) {
+        GemmArgs gb = ga;
+        gb.nb_n = rest / ga.nb_m;
+        ga.nb_n -= gb.nb_n;
+        gb.nb_n0 = ga.nb_n;
+        gb.nb_m = (MTT + BM / 2 - 1) / (BM / 2);
+        hipError_t e = launch_one<F16, 4>(ga, w, sx, os, outl, o, sess, st);
+        if (e != hipSuccess) return e;
+        return launch_one<F16, 2>(gb, w, sx, os, outl, o, sess, st);
+    }
+    return launch_one<F16, 4>(ga, w, sx, os, outl, o, sess, st);
+}
+
 }  // namespace
 
 hipError_t ps_gemm_f16_tiles(const __half *feat_tiles, const __half *tok_tiles, int ktiles, int M, int n_feat,
                              float *out, const __half *gelu_pre, __half *tile_out, hipStream_t st) {
     if (ktiles < 1 || M < 1 || n_feat < 16 || n_feat % 16) return hipErrorInvalidValue;
     if (gelu_pre && (!tile_out || n_feat % 32)) return hipErrorInvalidValue;
-    GemmArgs ga = {(const unsigned char *)feat_tiles, (const unsigned char *)tok_tiles, ktiles, M, n_feat, 0, 0,
+    GemmArgs ga = {(const unsigned char *)feat_tiles, (const unsigned char *)tok_tiles, ktiles, M, n_feat, 0, 0, 0,
                    gelu_pre, tile_out};
     LinearW w;
     OutlierSet os;
@@ -501,9 +526,9 @@ hipError_t ps_gemm_lds(const LinearW &w, const int8_t *xq_tiled, const uint32_t 
     k_gather_w<<<4096, 64, 0, st>>>(w, os.count, mo.list, mo.wo);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    GemmArgs gf = {(const unsigned char *)mo.wo, (const unsigned char *)mo.xo, 0, M, w.N, 0, 0, nullptr, nullptr};
+    GemmArgs gf = {(const unsigned char *)mo.wo, (const unsigned char *)mo.xo, 0, M, w.N, 0, 0, 0, nullptr, nullptr};
     e = launch_lds<true>(gf, w, sx, os, mo.outl, o, sess, st);
     if (e != hipSuccess) return e;
-    GemmArgs gi = {(const unsigned char *)w.wt, (const unsigned char *)xq_tiled, w.K / 64, M, w.N, 0, 0, nullptr, nullptr};
+    GemmArgs gi = {(const unsigned char *)w.wt, (const unsigned char *)xq_tiled, w.K / 64, M, w.N, 0, 0, 0, nullptr, nullptr};
     return launch_lds<false>(gi, w, sx, os, mo.outl, o, sess, st);
 }

@@ -434,6 +434,41 @@ def test_c4_full_size_linears_with_several_rows_sampled_against_the_oracle():
     gsp.close()
 
 
+def test_c4_full_size_linears_at_the_benchmark_row_count_sampled_against_the_oracle():
+    """4096 rows (the prefill benchmark's call) on full-size linears, in the launch configuration bench.py times:
+    the dense linear (14336 output features: 896 output blocks, whose last partial round goes to a second launch
+    with half-height blocks) and the fused QKV linear; the oracle computes a sample of output features, taken from
+    the first, the middle and the last feature blocks."""
+    cfg = synth.CONFIGS["C4"]
+    M = 4096
+    p = synth.block_params_device(cfg, 0, DEV)
+    gsp = binding.Span(1, cfg.hidden, cfg.n_heads, cfg.F, M, 1e-5, 6.0, DEV)
+    gsp.load_block(0, p)
+    r = np.random.default_rng(17)
+    try:
+        for which, wname, bname in ((1, "w_dense", "b_dense"), (0, "w_qkv", "b_qkv")):
+            N, K = gsp.shapes(which)
+            rows = np.unique(np.concatenate([np.arange(16), r.choice(N, 40, replace=False),
+                                             np.arange(N - 2048, N - 2048 + 8), np.arange(N - 8, N)]))
+            Wsub = p[wname][torch.as_tensor(rows, device=DEV)].cpu().numpy()
+            bsub = p[bname].cpu().numpy()[rows]
+            wq, sw = oracle.quantize_weight(Wsub)
+            X = r.standard_normal((M, K))
+            X[:, r.choice(K, 6, replace=False)] = r.uniform(20, 60, (M, 6))
+            X = X.astype(np.float16)
+            Y, dbg = oracle.linear(X, wq, sw, bsub, 6.0, want_debug=True)
+            print("C4 linear %d at %d rows" % (which, M), flush=True)
+            out = gsp.debug_linear(0, which, to_dev(X))
+            torch.cuda.synchronize()
+            assert np.array_equal(to_np(out["mask"]), dbg["mask"])
+            assert np.array_equal(to_np(out["xq"]), dbg["xq"]) and np.array_equal(to_np(out["sx"]), dbg["sx"])
+            assert np.array_equal(to_np(out["acc"])[:, rows], dbg["acc"])
+            hidden_close(to_np(out["y"])[:, rows], Y, "C4 linear %d M=%d" % (which, M))
+            del out
+    finally:
+        gsp.close()
+
+
 def test_c4_full_size_down_linear_with_many_outlier_columns():
     """Batched decode on the widest linear (K = 57344) when about 5% of its input columns are outliers, as the
     GeLU output of this configuration has them; one 16-column group is all outliers (more than the 8 values
