@@ -162,13 +162,12 @@ int petals_span_backward(petals_span *sp, void *dev_store, int32_t B, int32_t T,
     for (int b = c.n_blocks - 1; b >= 0; b--) {
         const BlockW &W = sp->blocks[b];
         // x2 = x1 + down(GeLU(pre)):  dpre = (gy Wd_down) * GeLU'(pre), written in tile order by the product's epilogue
-        HIP_TRY(ps_tile_rows(gy, M, H, bs.tiles, st));
+        if (b == c.n_blocks - 1) HIP_TRY(ps_tile_rows(gy, M, H, bs.tiles, st));   // later blocks: written by k_ln_bwd
         if (int rc = backward_product(sp, b, 3, bs.tiles, M, bs, bs.save.pre[b], bs.tiles2, st)) return rc;
         // pre = up(LayerNorm2(x1)):  dx1 = gy + LayerNorm2'(dpre Wd_up)
         if (int rc = backward_product(sp, b, 2, bs.tiles2, M, bs, nullptr, nullptr, st)) return rc;
-        HIP_TRY(ps_ln_bwd(bs.out32, bs.save.x1[b], W.ln2g, gy, c.ln_eps, M, H, bs.gx1, st));
-        // x1 = x + dense(ctx):  dctx = dx1 Wd_dense
-        HIP_TRY(ps_tile_rows(bs.gx1, M, H, bs.tiles, st));
+        HIP_TRY(ps_ln_bwd(bs.out32, bs.save.x1[b], W.ln2g, gy, c.ln_eps, M, H, bs.gx1, bs.tiles, st));
+        // x1 = x + dense(ctx):  dctx = dx1 Wd_dense (dx1 is in tile order already)
         if (int rc = backward_product(sp, b, 1, bs.tiles, M, bs, nullptr, nullptr, st)) return rc;
         HIP_TRY(ps_attn_bwd_prep(bs.out32, bs.save.ctx32[b], M, nh, d, bs.dO, bs.Dv, st));
         {
@@ -181,7 +180,7 @@ int petals_span_backward(petals_span *sp, void *dev_store, int32_t B, int32_t T,
         HIP_TRY(ps_tile_rows(bs.dqkv, M, 3 * H, bs.tiles, st));
         if (int rc = backward_product(sp, b, 0, bs.tiles, M, bs, nullptr, nullptr, st)) return rc;
         __half *gx = b == 0 ? (__half *)grad_in : bs.gy[b & 1];
-        HIP_TRY(ps_ln_bwd(bs.out32, bs.save.x[b], W.ln1g, bs.gx1, c.ln_eps, M, H, gx, st));
+        HIP_TRY(ps_ln_bwd(bs.out32, bs.save.x[b], W.ln1g, bs.gx1, c.ln_eps, M, H, gx, b > 0 ? bs.tiles : nullptr, st));
         gy = gx;
     }
     return PETALS_OK;

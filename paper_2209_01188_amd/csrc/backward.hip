@@ -60,15 +60,21 @@ __global__ void __launch_bounds__(256) k_transpose_w(LinearW w, __half *__restri
 }
 
 // dx = dres + LayerNorm'(x)^T (dz * gain): one workgroup per row, the row in registers (H <= 16384).
-// dz [M,H] fp32 is the backward product of the linear that read the LayerNorm output.
+// dz [M,H] fp32 is the backward product of the linear that read the LayerNorm output.  The four row sums the
+// derivative needs (x, x^2, dz g, dz g x) are formed in one pass and one reduction: fp32 over a thread's 16
+// elements, fp64 across threads; the elementwise part is fp32 (the kernel would otherwise be bound by fp64
+// arithmetic, and a gradient needs no exactly rounded result).
+// tiles (may be null): dx again, in the 16 x 32 tile order of the next backward product's token operand
+// (rows beyond M of the last tile row are zeroed by the workgroup of row M - 1).
 __global__ void __launch_bounds__(1024) k_ln_bwd(const float *__restrict__ dz, const __half *__restrict__ x,
                                                  const __half *__restrict__ g, const __half *__restrict__ dres,
-                                                 float eps, int H, __half *__restrict__ dx) {
-    constexpr int NT = 1024, PER = 8;
-    __shared__ double sm[NT / 64];
-    const size_t row = (size_t)blockIdx.x * H;
+                                                 float eps, int H, __half *__restrict__ dx, __half *__restrict__ tiles) {
+    constexpr int NT = 1024, PER = 8, NWV = NT / 64;
+    __shared__ double sm[4][NWV];
+    const int t = blockIdx.x, M = gridDim.x;
+    const size_t row = (size_t)t * H;
     float xv[PER][2], dv[PER][2];
-    double s = 0.0;
+    float p1 = 0.0f, p2 = 0.0f, pa = 0.0f, pb = 0.0f;
 #pragma unroll
     for (int i = 0; i < PER; i++) {
         const int k = (threadIdx.x + i * NT) * 2;
@@ -79,40 +85,42 @@ __global__ void __launch_bounds__(1024) k_ln_bwd(const float *__restrict__ dz, c
             const float2 z = *(const float2 *)(dz + row + k);
             xv[i][0] = f.x; xv[i][1] = f.y;
             dv[i][0] = z.x * gg.x; dv[i][1] = z.y * gg.y;
-            s += (double)f.x + (double)f.y;
-        }
-    }
-    const double mean = block_sum<NT / 64>(s, sm) / (double)H;
-    double q = 0.0;
-#pragma unroll
-    for (int i = 0; i < PER; i++)
-        if ((threadIdx.x + i * NT) * 2 < H) {
-            const double a = (double)xv[i][0] - mean, c = (double)xv[i][1] - mean;
-            q += a * a + c * c;
-        }
-    const double inv = 1.0 / sqrt(block_sum<NT / 64>(q, sm) / (double)H + (double)eps);
-    double sa = 0.0, sc = 0.0;
-#pragma unroll
-    for (int i = 0; i < PER; i++)
-        if ((threadIdx.x + i * NT) * 2 < H) {
 #pragma unroll
             for (int e = 0; e < 2; e++) {
-                const double xh = ((double)xv[i][e] - mean) * inv;
-                sa += (double)dv[i][e];
-                sc += (double)dv[i][e] * xh;
+                p1 += xv[i][e]; p2 += xv[i][e] * xv[i][e]; pa += dv[i][e]; pb += dv[i][e] * xv[i][e];
             }
         }
-    const double ma = block_sum<NT / 64>(sa, sm) / (double)H;
-    const double mc = block_sum<NT / 64>(sc, sm) / (double)H;
+    }
+    double s1 = wave_sum((double)p1), s2 = wave_sum((double)p2), sa = wave_sum((double)pa), sb = wave_sum((double)pb);
+    if ((threadIdx.x & 63) == 0) {
+        const int w = threadIdx.x >> 6;
+        sm[0][w] = s1; sm[1][w] = s2; sm[2][w] = sa; sm[3][w] = sb;
+    }
+    __syncthreads();
+    s1 = s2 = sa = sb = 0.0;
+#pragma unroll
+    for (int w = 0; w < NWV; w++) { s1 += sm[0][w]; s2 += sm[1][w]; sa += sm[2][w]; sb += sm[3][w]; }
+    const double rH = 1.0 / (double)H, mean_d = s1 * rH;
+    const double inv_d = 1.0 / sqrt(fmax(s2 * rH - mean_d * mean_d, 0.0) + (double)eps);
+    const double ma_d = sa * rH;                             // mean of dz g
+    const float mean = (float)mean_d, inv = (float)inv_d, ma = (float)ma_d;
+    const float imc = (float)(inv_d * inv_d * (sb * rH - mean_d * ma_d));   // inv * (mean of dz g x_hat)
+    const int CT = H >> 5;
 #pragma unroll
     for (int i = 0; i < PER; i++) {
         const int k = (threadIdx.x + i * NT) * 2;
         if (k < H) {
             const float2 r = __half22float2(*(const __half2 *)(dres + row + k));
             __half2 o;
-            o.x = d2h_rn((double)r.x + inv * ((double)dv[i][0] - ma - ((double)xv[i][0] - mean) * inv * mc));
-            o.y = d2h_rn((double)r.y + inv * ((double)dv[i][1] - ma - ((double)xv[i][1] - mean) * inv * mc));
+            o.x = __float2half_rn(r.x + inv * (dv[i][0] - ma - (xv[i][0] - mean) * imc));
+            o.y = __float2half_rn(r.y + inv * (dv[i][1] - ma - (xv[i][1] - mean) * imc));
             *(__half2 *)(dx + row + k) = o;
+            if (tiles) {
+                __half *tp = tiles + (((size_t)(t >> 4) * CT + (k >> 5)) * 64 + 16 * ((k & 31) >> 3)) * 8 + (k & 7);
+                *(__half2 *)(tp + (t & 15) * 8) = o;
+                if (t == M - 1)
+                    for (int pad = (t & 15) + 1; pad < 16; pad++) *(__half2 *)(tp + pad * 8) = __floats2half2_rn(0.0f, 0.0f);
+            }
         }
     }
 }
@@ -398,9 +406,9 @@ hipError_t ps_transpose_w(const LinearW &w, __half *wt16, hipStream_t st) {
 }
 
 hipError_t ps_ln_bwd(const float *dz, const __half *x, const __half *g, const __half *dres, float eps, int M, int H,
-                     __half *dx, hipStream_t st) {
+                     __half *dx, __half *tiles, hipStream_t st) {
     if (H > 16384) return hipErrorInvalidValue;
-    k_ln_bwd<<<M, 1024, 0, st>>>(dz, x, g, dres, eps, H, dx);
+    k_ln_bwd<<<M, 1024, 0, st>>>(dz, x, g, dres, eps, H, dx, tiles);
     return hipGetLastError();
 }
 

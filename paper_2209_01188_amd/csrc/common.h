@@ -134,8 +134,9 @@ hipError_t ps_transpose_w(const LinearW &w, __half *wt16, hipStream_t st);
 // goes to tile_out in token-tile order [ceil(M/16)][n_feat/32][512 halves], rows beyond M zero (out is unused).
 hipError_t ps_gemm_f16_tiles(const __half *feat_tiles, const __half *tok_tiles, int ktiles, int M, int n_feat,
                              float *out, const __half *gelu_pre, __half *tile_out, hipStream_t st);
+// tiles (may be null): the result again in token-tile order [ceil(M/16)][H/32][512 halves], rows beyond M zero
 hipError_t ps_ln_bwd(const float *dz, const __half *x, const __half *g, const __half *dres, float eps, int M, int H,
-                     __half *dx, hipStream_t st);
+                     __half *dx, __half *tiles, hipStream_t st);
 hipError_t ps_attn_bwd_prep(const float *dctx, const float *ctx32, int M, int nh, int d, __half *dO, float *Dv,
                             hipStream_t st);
 // QT, KT, dOT: scratch [B][nh][d][ceil(T/32)*32] halves each; dqkv [B*T, 3*nh*d] in the fused-QKV column order
