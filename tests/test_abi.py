@@ -102,3 +102,31 @@ def test_code_table_bits_equal_the_oracle_table(b):
     import oracle
     t = np.array(b.petals_hidden_code_table(), np.float32)
     assert np.array_equal(t.view(np.uint32), oracle.codebook().view(np.uint32))
+
+
+def test_backward_size_queries_and_host_side_checks(b):
+    """Sizes of the backward pass's store and weight cache follow the layout arithmetic; argument errors are
+    reported before any device work (Section 2.2 entry points)."""
+    cfg = b.make_config(12, 14336, 112, 57344, 4096)
+    H, F, M, nb = 14336, 57344, 4096, 12
+    store = b.petals_span_backward_bytes(cfg, 8, 512)
+    kept = nb * (M * H * 2 * 3 + M * H * 4 + M * F * 2 + 112 * M * 4) + 8 * nb * 2 * H * 512 * 2   # x, q, x1; fp32 context; GeLU input; lse; keys/values
+    assert kept <= store <= kept * 1.5
+    # a small call still holds the transposed fp16 weights of the largest linear (2 * F * H bytes)
+    assert 2 * F * H <= b.petals_span_backward_bytes(cfg, 1, 16) <= 2 * F * H * 1.05
+    assert b.petals_span_backward_cache_bytes(cfg) == nb * 12 * H * H * 2            # 2 bytes per weight
+    for B, T in ((0, 4), (4, 0), (65, 1), (8, 513)):                                  # empty, empty, too many sequences, too many rows
+        with pytest.raises(b.PetalsError):
+            b.petals_span_backward_bytes(cfg, B, T)
+    L = b.lib()
+    small = b.make_config(2, 64, 4, 256, 8)
+    fake, other, third = C.c_void_p(0x10000), C.c_void_p(0x20000), C.c_void_p(0x30000)
+    span = C.c_void_p()
+    assert L.petals_span_create(C.byref(small), fake, fake, C.byref(span)) == 0
+    assert L.petals_span_backward(span, fake, 1, 4, fake, other, None, fake, None) == -1        # grad_in aliases hidden_in
+    assert L.petals_span_backward(span, C.c_void_p(0x10010), 1, 4, fake, other, None, third, None) == -1   # store misaligned
+    assert L.petals_span_backward(span, fake, 3, 4, fake, other, None, third, None) == -2       # 12 rows > 8
+    assert L.petals_span_backward(span, fake, 1, 4, fake, other, None, third, None) == -4       # blocks not loaded
+    assert L.petals_span_backward_attach_cache(span, C.c_void_p(0x10010)) == -1                 # misaligned
+    assert L.petals_span_backward_attach_cache(span, other) == 0 and L.petals_span_backward_attach_cache(span, None) == 0
+    assert L.petals_span_destroy(span) == 0
