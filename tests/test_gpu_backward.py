@@ -90,7 +90,7 @@ def test_backward_c1_shape(B, T):
     _check(synth.CONFIGS["C1"], 2, B, T, wscale=8.0, seed=B * 100 + T)
 
 
-@pytest.mark.parametrize("hidden,heads,T", [(256, 8, 45), (512, 8, 80), (1024, 8, 37), (1024, 16, 129)])
+@pytest.mark.parametrize("hidden,heads,T", [(256, 8, 45), (512, 8, 80), (1024, 8, 37), (1024, 16, 129), (512, 4, 600)])
 def test_backward_head_dims_32_64_128(hidden, heads, T):
     cfg = synth.scaled(synth.CONFIGS["C2"], hidden=hidden, n_heads=heads)
     _check(cfg, 2, 2, T, wscale=1.5 / (0.02 * np.sqrt(hidden)), seed=hidden + T)
