@@ -231,8 +231,3 @@ def test_kv_import_export_round_trip():
     assert se.length == 5 and np.array_equal(se.export_kv(1), kv)
 
 
-def test_memory_arithmetic_of_the_paper():
-    # Section 3.1: 176B parameters -> 352 GB in 16 bits, half that in 8 bits; 70 blocks of 12 H^2
-    H = 14336
-    assert abs(12 * H * H * 70 / 1e9 - 172.6) < 0.1
-    assert 352 // 8 == 44 and 176 // 8 == 22
