@@ -153,7 +153,7 @@ int petals_span_backward(petals_span *sp, void *dev_store, int32_t B, int32_t T,
     memcpy(tab.slopes, sp->slopes, sizeof(tab.slopes));
     hipStream_t st = (hipStream_t)stream;
     Workspace &ws = sp->ws;
-    const int M = B * T, H = c.hidden, F = c.ffn, nh = c.n_heads, d = H / nh;
+    const int M = B * T, H = c.hidden, nh = c.n_heads, d = H / nh;
     HIP_TRY(ps_set_table(tab, ws.table, st));
     if (int rc = ps_forward_blocks(sp, M, T, T, (const __half *)hidden_in, y, &bs.save, st)) return rc;
 
