@@ -96,6 +96,11 @@ def test_backward_head_dims_32_64_128(hidden, heads, T):
     _check(cfg, 2, 2, T, wscale=1.5 / (0.02 * np.sqrt(hidden)), seed=hidden + T)
 
 
+def test_backward_odd_shape_six_heads_and_an_mlp_that_is_not_four_times_wider():
+    cfg = synth.scaled(synth.CONFIGS["C2"], hidden=192, n_heads=6, ffn=448, n_outlier_dims=2)
+    _check(cfg, 2, 3, 21, wscale=1.5 / (0.02 * np.sqrt(192)), seed=77)
+
+
 def test_backward_c2_shape_deeper_span_several_sequences():
     _check(synth.CONFIGS["C2"], 6, 4, 64, wscale=1.5 / (0.02 * 32.0), seed=5)
 
