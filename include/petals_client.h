@@ -3,7 +3,7 @@
  *
  * In Petals the client keeps the token embeddings locally: it looks up the
  * embedding vectors of its tokens, sends them through the servers' spans, and
- * from the output of the last block "computes next token probabilities"
+ * turns the output of the last block into the distribution of the next token
  * (Petals paper, Section 2.1 "Inference of billion-scale models"; Figure 2:
  * word_embeddings -> session.step -> lm_head -> next token).  For a BLOOM-style
  * model that is: embedding row -> LayerNorm on the way in; LayerNorm -> product

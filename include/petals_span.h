@@ -108,8 +108,8 @@ int petals_span_destroy(petals_span *span);
 
 /*
  * Open a session: per-client attention key/value memory kept while the client
- * generates (Section 2.1: "servers store attention keys and values from past
- * client inputs").  dev_kv_mem has petals_span_kv_bytes(cfg, max_len) bytes,
+ * generates (Section 2.1: for the life of a session the server keeps the keys
+ * and values of everything the client has sent so far).  dev_kv_mem has petals_span_kv_bytes(cfg, max_len) bytes,
  * laid out [block][key|value][head][max_len][head_dim] fp16.  Length starts at 0.
  */
 int petals_session_open(petals_span *span, void *dev_kv_mem, int32_t max_len,
@@ -196,9 +196,9 @@ int petals_span_profile_end(petals_span *span, double *ms_per_class, int64_t *la
 /* ------------------------------------------------------- backward pass */
 
 /*
- * Backward pass through the frozen span (Section 2.2, "Distributed fine-tuning": servers "run
- * backpropagation through their layers and return gradients with respect to activations", and never
- * update their own parameters).  B sequences of T tokens each, every sequence attending only to itself
+ * Backward pass through the frozen span (Section 2.2, "Distributed fine-tuning": a server backpropagates
+ * through the blocks it holds, hands back the gradient of its input activations, and never updates its
+ * own parameters).  B sequences of T tokens each, every sequence attending only to itself
  * (no session, no earlier cache).  The call runs the forward pass on hidden_in, keeping what the
  * backward pass needs in dev_store, then backpropagates grad_out:
  *   hidden_in  dev fp16 [B, T, H]  inputs of the span

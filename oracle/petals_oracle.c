@@ -454,8 +454,8 @@ static void tap(uint16_t *dst, int b, const uint16_t *src, size_t n)
 }
 
 /*
- * One server step (Section 2.1: a session "runs inputs through all blocks and
- * returns final representations"): B sessions, T new tokens each, X and Y are
+ * One server step (Section 2.1: within a session the server passes what the
+ * client sends through all of its blocks and sends back the result): B sessions, T new tokens each, X and Y are
  * [B,T,H] fp16.  Prefill (T > 1) and decode (T = 1) are this same function.
  * Every linear sees all M = B*T rows of the call as one matrix, so the outlier
  * column set is the union over those rows.  Block: a = LN1(x); qkv = Lin(a);
@@ -510,7 +510,7 @@ int orc_span_step(orc_span *s, orc_session *const *sess, int B, int T,
 /*
  * What the client computes around the server spans (Section 2.1: the client
  * keeps the token embeddings locally, looks up embedding vectors, and from the
- * outputs of the final block "computes next token probabilities"; Figure 2:
+ * outputs of the final block derives the distribution of the next token; Figure 2:
  * word_embeddings, lm_head, sample_next_token).  BLOOM-style reading: the
  * embedding row goes through a LayerNorm, the final hidden state goes through
  * a LayerNorm and is multiplied with the SAME embedding matrix (tied weights).
