@@ -52,8 +52,8 @@ int petals_client_create(const petals_client_config *cfg, const petals_client_pa
 int petals_client_destroy(petals_client *client);
 
 /*
- * hidden_out[t] = LayerNorm(embeddings[token_ids[t]]) for t < M (Section 2.1: "the client
- * uses the local embedding layer to look up embedding vectors").  token_ids: dev int32 [M],
+ * hidden_out[t] = LayerNorm(embeddings[token_ids[t]]) for t < M (Section 2.1: the embedding
+ * layer lives on the client, which looks its tokens' vectors up there).  token_ids: dev int32 [M],
  * read on the device so that a token chosen by petals_client_lm_head can be fed back with
  * no host round trip; an id outside [0, V) is clamped into the range.  hidden_out: dev fp16
  * [M, H].  M <= max_rows_per_call, else PETALS_ERR_CAPACITY.
@@ -62,8 +62,8 @@ int petals_client_embed(petals_client *client, const int32_t *token_ids, int32_t
                         void *hidden_out, void *stream);
 
 /*
- * Next-token scores from the final hidden states (Section 2.1: "computes next token
- * probabilities"): a = LayerNorm(hidden_in[t]) rounded to fp16, logits[t][v] = sum_k
+ * Next-token scores from the final hidden states (Section 2.1: the client derives the
+ * next-token distribution from the last block's output): a = LayerNorm(hidden_in[t]) rounded to fp16, logits[t][v] = sum_k
  * a[k] * embeddings[v][k] accumulated in fp64 (each product of two fp16 values is exact).
  * logits_out: dev fp32 [M, V], may be NULL.  next_token_out: dev int32 [M], the first index
  * of the largest logit (greedy decoding), decided on the fp64 values; may be NULL if

@@ -119,8 +119,8 @@ int petals_session_close(petals_session *session);
 
 /*
  * Run T new tokens of each of B sessions through all blocks of the span
- * (Section 2.1: the server "runs inputs through all blocks and returns final
- * representations"; Section 3.2: re-feeding stored inputs to a replacement
+ * (Section 2.1: the server passes what it receives through all of its blocks
+ * and returns the result; Section 3.2: re-feeding stored inputs to a replacement
  * server rebuilds its keys and values).
  *   hidden_in, hidden_out: dev fp16 [B, T, H]; they may not alias.
  * Per block: LayerNorm, fused QKV linear, ALiBi causal attention over the
@@ -141,9 +141,9 @@ int petals_span_decode_step(petals_span *span, petals_session *const *sessions, 
                             const void *hidden_in, void *hidden_out, void *stream);
 
 /*
- * Failure recovery (Section 2.1: clients "store past inputs to each server so that if any server
- * fails ... another one can quickly take its place"; Section 3.2: "the client sends all previous
- * inputs to the replacement server, so that it has the same attention keys and values").  Feeds the
+ * Failure recovery (Section 2.1: a client keeps everything it has sent to each server, so that a
+ * failed server can be replaced; Section 3.2: the replacement receives all of those inputs again and
+ * thereby arrives at the same attention keys and values).  Feeds the
  * recorded inputs of ONE session into this span again, call by call: call_tokens[i] (HOST array,
  * n_calls entries, each >= 1 and <= max_rows_per_call) is the number of tokens the i-th original call
  * carried for this session, hidden_log (dev fp16 [sum of call_tokens, H]) their inputs in order.
