@@ -60,45 +60,92 @@ __global__ void __launch_bounds__(1024) k_outlier_list(const uint32_t *__restric
 
 // fp16 tiles for v_mfma_f32_16x16x32_f16: 16 rows x 32 (compacted) columns = 1024 bytes, lane l owns
 // row l%16 and columns (l/16)*8 .. +8.  Tile (r, c) at ((r * CT) + c) * 1024 with CT = ceil(n_out/32).
-// One wave per tile; the grid is fixed and strides over the tiles the call actually has.
+// One wave per tile; the grid is fixed and strides over the tiles the call actually has, U tiles at a time:
+// the list entries of all U tiles are requested (two 16-byte loads per lane and tile), then all sources, then the
+// stores go out.  (One tile at a time, a wave spends most of its time waiting on the list -> source -> store
+// chain: 264 against 116 us per call for the weights, 86 against 61 us for the activations, averaged over the
+// linears of a 4096-row call at BLOOM-176B width.)
+template <int U>
 __global__ void __launch_bounds__(64) k_gather_x(const __half *__restrict__ X, int M, int K,
-                                                 const int *__restrict__ count, const int *__restrict__ list,
-                                                 __half *__restrict__ xo) {
+                                                    const int *__restrict__ count, const int *__restrict__ list,
+                                                    __half *__restrict__ xo) {
     const int n_out = *count;
     if (n_out <= PS_EXACT_OUTLIERS) return;
-    const int CT = (n_out + 31) >> 5, MTT = (M + 15) >> 4, lane = threadIdx.x;
-    for (int item = blockIdx.x; item < MTT * CT; item += gridDim.x) {
-        const int mt = item / CT, ct = item - mt * CT, t = mt * 16 + (lane & 15), c0 = ct * 32 + (lane >> 4) * 8;
-        v8h v;
+    const int CT = (n_out + 31) >> 5, MTT = (M + 15) >> 4, lane = threadIdx.x, total = MTT * CT;
+    for (int item0 = blockIdx.x; item0 < total; item0 += gridDim.x * U) {
+        int4 ia[U], ib[U];
+        int tt[U];
 #pragma unroll
-        for (int e = 0; e < 8; e++) {
-            const int idx = list[c0 + e];
-            v[e] = (t < M && idx >= 0) ? (_Float16)__half2float(X[(size_t)t * K + idx]) : (_Float16)0.0f;
+        for (int u = 0; u < U; u++) {
+            const int item = min(item0 + u * (int)gridDim.x, total - 1);
+            const int mt = item / CT, ct = item - mt * CT;
+            tt[u] = mt * 16 + (lane & 15);
+            const int4 *lp = (const int4 *)(list + ct * 32 + (lane >> 4) * 8);
+            ia[u] = lp[0];
+            ib[u] = lp[1];
         }
-        *(v8h *)(xo + ((size_t)item * 64 + lane) * 8) = v;
+        v8h v[U];
+#pragma unroll
+        for (int u = 0; u < U; u++) {
+            const int idx[8] = {ia[u].x, ia[u].y, ia[u].z, ia[u].w, ib[u].x, ib[u].y, ib[u].z, ib[u].w};
+            const __half *row = X + (size_t)min(tt[u], M - 1) * K;
+#pragma unroll
+            for (int e = 0; e < 8; e++)
+            {
+                const _Float16 xv = (_Float16)__half2float(row[max(idx[e], 0)]);      // always in bounds
+                v[u][e] = (tt[u] < M && idx[e] >= 0) ? xv : (_Float16)0.0f;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; u++) {
+            const int item = item0 + u * (int)gridDim.x;
+            if (item < total) *(v8h *)(xo + ((size_t)item * 64 + lane) * 8) = v[u];
+        }
     }
 }
 
+template <int U>
 __global__ void __launch_bounds__(64) k_gather_w(LinearW w, const int *__restrict__ count,
-                                                 const int *__restrict__ list, __half *__restrict__ wo) {
+                                                    const int *__restrict__ list, __half *__restrict__ wo) {
     const int n_out = *count;
     if (n_out <= PS_EXACT_OUTLIERS) return;
     const int CT = (n_out + 31) >> 5, NT = w.N >> 4, KT = w.K >> 6, lane = threadIdx.x, row = lane & 15;
-    for (int item = blockIdx.x; item < NT * CT; item += gridDim.x) {
-        const int nt = item / CT, ct = item - nt * CT, c0 = ct * 32 + (lane >> 4) * 8;
-        const float swd = w.sw[nt * 16 + row] / 127.0f;
-        v8h v;
+    const int total = NT * CT;
+    const int8_t *__restrict__ wt = w.wt;
+    for (int item0 = blockIdx.x; item0 < total; item0 += gridDim.x * U) {
+        int4 ia[U], ib[U];
+        int nts[U];
+        float swd[U];
 #pragma unroll
-        for (int e = 0; e < 8; e++) {
-            const int k = list[c0 + e];
-            float f = 0.0f;
-            if (k >= 0) {
-                const int code = w.wt[((size_t)nt * KT + (k >> 6)) * 1024 + (((k & 63) >> 4) * 16 + row) * 16 + (k & 15)];
-                f = dequant_w16(code, swd);
-            }
-            v[e] = (_Float16)f;
+        for (int u = 0; u < U; u++) {
+            const int item = min(item0 + u * (int)gridDim.x, total - 1);
+            const int nt = item / CT, ct = item - nt * CT;
+            nts[u] = nt;
+            const int4 *lp = (const int4 *)(list + ct * 32 + (lane >> 4) * 8);
+            ia[u] = lp[0];
+            ib[u] = lp[1];
+            swd[u] = w.sw[nt * 16 + row];
         }
-        *(v8h *)(wo + ((size_t)item * 64 + lane) * 8) = v;
+        int code[U][8];
+#pragma unroll
+        for (int u = 0; u < U; u++) {
+            const int idx[8] = {ia[u].x, ia[u].y, ia[u].z, ia[u].w, ib[u].x, ib[u].y, ib[u].z, ib[u].w};
+#pragma unroll
+            for (int e = 0; e < 8; e++) {
+                const int k = max(idx[e], 0);
+                const int c = wt[((size_t)nts[u] * KT + (k >> 6)) * 1024 + (((k & 63) >> 4) * 16 + row) * 16 + (k & 15)];
+                code[u][e] = idx[e] >= 0 ? c : 0;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; u++) {
+            const float s = swd[u] / 127.0f;
+            v8h v;
+#pragma unroll
+            for (int e = 0; e < 8; e++) v[e] = (_Float16)dequant_w16(code[u][e], s);
+            const int item = item0 + u * (int)gridDim.x;
+            if (item < total) *(v8h *)(wo + ((size_t)item * 64 + lane) * 8) = v;
+        }
     }
 }
 
@@ -522,8 +569,8 @@ hipError_t ps_gemm_lds(const LinearW &w, const int8_t *xq_tiled, const uint32_t 
                        hipStream_t st) {
     // the outlier-heavy case first (all four kernels return at once when the call has few outlier columns)
     k_outlier_list<<<1, 1024, 0, st>>>(mask, w.K, os.count, mo.list);
-    k_gather_x<<<2048, 64, 0, st>>>(X, M, w.K, os.count, mo.list, mo.xo);
-    k_gather_w<<<4096, 64, 0, st>>>(w, os.count, mo.list, mo.wo);
+    k_gather_x<4><<<2048, 64, 0, st>>>(X, M, w.K, os.count, mo.list, mo.xo);
+    k_gather_w<4><<<4096, 64, 0, st>>>(w, os.count, mo.list, mo.wo);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     GemmArgs gf = {(const unsigned char *)mo.wo, (const unsigned char *)mo.xo, 0, M, w.N, 0, 0, 0, nullptr, nullptr};

@@ -131,6 +131,65 @@ __global__ void __launch_bounds__(1024) k_layernorm_wide(const __half *__restric
     }
 }
 
+// Many rows (a prefill-size call): 256 threads per row and 16-byte loads, so that a compute unit holds eight rows
+// in different phases (loading, reducing, storing) instead of two; with two, memory idles during the reductions.
+// The elements a thread sums differ from the kernels above, i.e. the fp64 sums are rounded in another order.
+template <int PER>
+__global__ void __launch_bounds__(256) k_layernorm_rows(const __half *__restrict__ x, const __half *__restrict__ g,
+                                                        const __half *__restrict__ b, float eps, int H,
+                                                        __half *__restrict__ y, uint32_t *__restrict__ mask,
+                                                        float theta) {
+    constexpr int NT = 256;
+    __shared__ double sm[NT / 64];
+    const __half *xr = x + (size_t)blockIdx.x * H;
+    __half *yr = y + (size_t)blockIdx.x * H;
+    v8h v[PER];
+    double s = 0.0;
+#pragma unroll
+    for (int i = 0; i < PER; i++) {
+        const int k = (threadIdx.x + i * NT) * 8;
+        if (k < H) {
+            v[i] = *(const v8h *)(xr + k);
+#pragma unroll
+            for (int e = 0; e < 8; e++) s += (double)(float)v[i][e];
+        }
+    }
+    const double mean = block_sum<NT / 64>(s, sm) / (double)H;
+    double q = 0.0;
+#pragma unroll
+    for (int i = 0; i < PER; i++) {
+        if ((threadIdx.x + i * NT) * 8 < H) {
+#pragma unroll
+            for (int e = 0; e < 8; e++) {
+                const double a = (double)(float)v[i][e] - mean;
+                q += a * a;
+            }
+        }
+    }
+    const double inv = 1.0 / sqrt(block_sum<NT / 64>(q, sm) / (double)H + (double)eps);
+#pragma unroll
+    for (int i = 0; i < PER; i++) {
+        const int k = (threadIdx.x + i * NT) * 8;
+        if (k < H) {
+            const v8h gv = *(const v8h *)(g + k), bv = *(const v8h *)(b + k);
+            v8h ov;
+            uint32_t bits = 0;
+#pragma unroll
+            for (int e = 0; e < 8; e += 2) {
+                const __half2 o = ln_affine(__halves2half2(__float2half((float)v[i][e]), __float2half((float)v[i][e + 1])),
+                                            __halves2half2(__float2half((float)gv[e]), __float2half((float)gv[e + 1])),
+                                            __halves2half2(__float2half((float)bv[e]), __float2half((float)bv[e + 1])),
+                                            mean, inv);
+                ov[e] = (_Float16)__half2float(o.x);
+                ov[e + 1] = (_Float16)__half2float(o.y);
+                bits |= (fabsf(__half2float(o.x)) >= theta ? 1u : 0u) << e | (fabsf(__half2float(o.y)) >= theta ? 2u : 0u) << e;
+            }
+            *(v8h *)(yr + k) = ov;
+            if (mask) flag_outlier_bits(mask, k >> 5, bits << (k & 31));
+        }
+    }
+}
+
 // -------------------------------------------------- many rows: mask, then quantize
 
 // Column c is an outlier if any row reaches theta.  grid.x covers columns (64 per
@@ -218,31 +277,33 @@ __global__ void __launch_bounds__(256) k_rowquant_tiled(const __half *__restrict
     }
 }
 
-// The same for wide rows (4096 <= K <= 65536): 1024 threads, each keeps its (at most 4) chunks of 16
+// The same for wide rows (4096 <= K <= NT * CPT * 16): NT threads, each keeps its (at most CPT) chunks of 16
 // columns in registers between the absolute-maximum pass and the quantization, so X is read once;
-// for calls of few rows, where the latency of the loads is the whole cost, this halves it.
-__global__ void __launch_bounds__(1024) k_rowquant_tiled_wide(const __half *__restrict__ X, int M, int K,
+// for calls of few rows, where the latency of the loads is the whole cost, this halves it (1024 threads);
+// for calls of many rows, 256 threads per row put four times as many rows on a compute unit.
+template <int NT, int CPT>
+__global__ void __launch_bounds__(NT) k_rowquant_tiled_wide(const __half *__restrict__ X, int M, int K,
                                                              const uint32_t *__restrict__ mask,
                                                              int8_t *__restrict__ xq_tiled,
                                                              int8_t *__restrict__ xo_tiled, float *__restrict__ sx,
                                                              int8_t *__restrict__ xq_dbg) {
-    __shared__ float sm[16];
+    __shared__ float sm[NT / 64];
     const int t = blockIdx.x, KT = K >> 6, nchunk = K >> 4;
     const uint16_t *mask16 = (const uint16_t *)mask;
     const size_t tile_row = (size_t)(t >> 4) * KT;
     if (t >= M) {
-        for (int c = threadIdx.x; c < nchunk; c += 1024) {
+        for (int c = threadIdx.x; c < nchunk; c += NT) {
             v4i z = {0, 0, 0, 0};
             *(v4i *)(xq_tiled + ((tile_row + (c >> 2)) * 64 + (c & 3) * 16 + (t & 15)) * 16) = z;
         }
         return;
     }
     const __half *xr = X + (size_t)t * K;
-    v8h a[4], b[4];
-    uint32_t bits[4];
+    v8h a[CPT], b[CPT];
+    uint32_t bits[CPT];
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-        const int c = threadIdx.x + i * 1024;
+    for (int i = 0; i < CPT; i++) {
+        const int c = threadIdx.x + i * NT;
         if (c < nchunk) {
             a[i] = *(const v8h *)(xr + c * 16);
             b[i] = *(const v8h *)(xr + c * 16 + 8);
@@ -251,8 +312,8 @@ __global__ void __launch_bounds__(1024) k_rowquant_tiled_wide(const __half *__re
     }
     float m = 0.0f;
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-        if (threadIdx.x + i * 1024 < nchunk) {
+    for (int i = 0; i < CPT; i++) {
+        if (threadIdx.x + i * NT < nchunk) {
 #pragma unroll
             for (int j = 0; j < 8; j++) {
                 if (!((bits[i] >> j) & 1u)) m = fmaxf(m, fabsf((float)a[i][j]));
@@ -260,12 +321,12 @@ __global__ void __launch_bounds__(1024) k_rowquant_tiled_wide(const __half *__re
             }
         }
     }
-    const float s = block_max<16>(m, sm);
+    const float s = block_max<NT / 64>(m, sm);
     if (threadIdx.x == 0) sx[t] = s;
     const float r = s > 0.0f ? 127.0f / s : 0.0f;
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-        const int c = threadIdx.x + i * 1024;
+    for (int i = 0; i < CPT; i++) {
+        const int c = threadIdx.x + i * NT;
         if (c < nchunk) {
             int q[16];
 #pragma unroll
@@ -382,7 +443,8 @@ hipError_t ps_copy_bytes(const void *src, void *dst, size_t n, hipStream_t st) {
 hipError_t ps_layernorm(const __half *x, const __half *g, const __half *b, float eps, int M, int H, __half *y,
                         uint32_t *mask, float theta, hipStream_t st) {
     // few rows: more threads per row (latency), many rows: more rows in flight
-    if (H >= 4096 && H <= 16384) k_layernorm_wide<<<M, 1024, 0, st>>>(x, g, b, eps, H, y, mask, theta);
+    if (M >= 512 && H % 8 == 0 && H >= 4096 && H <= 16384) k_layernorm_rows<8><<<M, 256, 0, st>>>(x, g, b, eps, H, y, mask, theta);
+    else if (H >= 4096 && H <= 16384) k_layernorm_wide<<<M, 1024, 0, st>>>(x, g, b, eps, H, y, mask, theta);
     else if (M <= 256 && H >= 4096) k_layernorm<1024><<<M, 1024, 0, st>>>(x, g, b, eps, H, y, mask, theta);
     else k_layernorm<256><<<M, 256, 0, st>>>(x, g, b, eps, H, y, mask, theta);
     return hipGetLastError();
@@ -394,10 +456,13 @@ hipError_t ps_colmask(const __half *X, int M, int K, float theta, uint32_t *mask
 }
 hipError_t ps_rowquant_tiled(const __half *X, int M, int K, const uint32_t *mask, int8_t *xq_tiled, int8_t *xo_tiled,
                              float *sx, int8_t *xq_dbg, hipStream_t st) {
-    if (K >= 4096 && K <= 65536)   // wide rows: 1024 threads keep the row in registers, one pass over X
-        k_rowquant_tiled_wide<<<(M + 15) / 16 * 16, 1024, 0, st>>>(X, M, K, mask, xq_tiled, xo_tiled, sx, xq_dbg);
+    const int rows = (M + 15) / 16 * 16;
+    if (K >= 4096 && K <= 16384 && M >= 512)   // many rows: four times as many rows in flight per compute unit
+        k_rowquant_tiled_wide<256, 4><<<rows, 256, 0, st>>>(X, M, K, mask, xq_tiled, xo_tiled, sx, xq_dbg);
+    else if (K >= 4096 && K <= 65536)          // wide rows: 1024 threads keep the row in registers, one pass over X
+        k_rowquant_tiled_wide<1024, 4><<<rows, 1024, 0, st>>>(X, M, K, mask, xq_tiled, xo_tiled, sx, xq_dbg);
     else
-        k_rowquant_tiled<<<(M + 15) / 16 * 16, 256, 0, st>>>(X, M, K, mask, xq_tiled, xo_tiled, sx, xq_dbg);
+        k_rowquant_tiled<<<rows, 256, 0, st>>>(X, M, K, mask, xq_tiled, xo_tiled, sx, xq_dbg);
     return hipGetLastError();
 }
 hipError_t ps_mask_to_bytes(const uint32_t *mask, int K, uint8_t *out, hipStream_t st) {
