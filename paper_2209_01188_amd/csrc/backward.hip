@@ -61,32 +61,33 @@ __global__ void __launch_bounds__(256) k_transpose_w(LinearW w, __half *__restri
 
 // dx = dres + LayerNorm'(x)^T (dz * gain): one workgroup per row, the row in registers (H <= 16384).
 // dz [M,H] fp32 is the backward product of the linear that read the LayerNorm output.  The four row sums the
-// derivative needs (x, x^2, dz g, dz g x) are formed in one pass and one reduction: fp32 over a thread's 16
+// derivative needs (x, x^2, dz g, dz g x) are formed in one pass and one reduction: fp32 over a thread's
 // elements, fp64 across threads; the elementwise part is fp32 (the kernel would otherwise be bound by fp64
 // arithmetic, and a gradient needs no exactly rounded result).
 // tiles (may be null): dx again, in the 16 x 32 tile order of the next backward product's token operand
 // (rows beyond M of the last tile row are zeroed by the workgroup of row M - 1).
-__global__ void __launch_bounds__(1024) k_ln_bwd(const float *__restrict__ dz, const __half *__restrict__ x,
-                                                 const __half *__restrict__ g, const __half *__restrict__ dres,
-                                                 float eps, int H, __half *__restrict__ dx, __half *__restrict__ tiles) {
-    constexpr int NT = 1024, PER = 8, NWV = NT / 64;
+// NT threads per row, each with PER groups of 8 consecutive columns: 1024 x 2 for few rows (latency), 256 x 8 for
+// calls of many rows (a compute unit then works on eight rows in different phases instead of two).
+template <int NT, int PER>
+__global__ void __launch_bounds__(NT) k_ln_bwd(const float *__restrict__ dz, const __half *__restrict__ x,
+                                               const __half *__restrict__ g, const __half *__restrict__ dres,
+                                               float eps, int H, __half *__restrict__ dx, __half *__restrict__ tiles) {
+    constexpr int NWV = NT / 64;
     __shared__ double sm[4][NWV];
     const int t = blockIdx.x, M = gridDim.x;
     const size_t row = (size_t)t * H;
-    float xv[PER][2], dv[PER][2];
+    float xv[PER][8], dv[PER][8];
     float p1 = 0.0f, p2 = 0.0f, pa = 0.0f, pb = 0.0f;
 #pragma unroll
     for (int i = 0; i < PER; i++) {
-        const int k = (threadIdx.x + i * NT) * 2;
-        xv[i][0] = xv[i][1] = dv[i][0] = dv[i][1] = 0.0f;
+        const int k = (threadIdx.x + i * NT) * 8;
         if (k < H) {
-            const float2 f = __half22float2(*(const __half2 *)(x + row + k));
-            const float2 gg = __half22float2(*(const __half2 *)(g + k));
-            const float2 z = *(const float2 *)(dz + row + k);
-            xv[i][0] = f.x; xv[i][1] = f.y;
-            dv[i][0] = z.x * gg.x; dv[i][1] = z.y * gg.y;
+            const v8h f = *(const v8h *)(x + row + k), gg = *(const v8h *)(g + k);
+            const v4f z0 = *(const v4f *)(dz + row + k), z1 = *(const v4f *)(dz + row + k + 4);
 #pragma unroll
-            for (int e = 0; e < 2; e++) {
+            for (int e = 0; e < 8; e++) {
+                xv[i][e] = (float)f[e];
+                dv[i][e] = (e < 4 ? z0[e & 3] : z1[e & 3]) * (float)gg[e];
                 p1 += xv[i][e]; p2 += xv[i][e] * xv[i][e]; pa += dv[i][e]; pb += dv[i][e] * xv[i][e];
             }
         }
@@ -108,18 +109,21 @@ __global__ void __launch_bounds__(1024) k_ln_bwd(const float *__restrict__ dz, c
     const int CT = H >> 5;
 #pragma unroll
     for (int i = 0; i < PER; i++) {
-        const int k = (threadIdx.x + i * NT) * 2;
+        const int k = (threadIdx.x + i * NT) * 8;
         if (k < H) {
-            const float2 r = __half22float2(*(const __half2 *)(dres + row + k));
-            __half2 o;
-            o.x = __float2half_rn(r.x + inv * (dv[i][0] - ma - (xv[i][0] - mean) * imc));
-            o.y = __float2half_rn(r.y + inv * (dv[i][1] - ma - (xv[i][1] - mean) * imc));
-            *(__half2 *)(dx + row + k) = o;
-            if (tiles) {
-                __half *tp = tiles + (((size_t)(t >> 4) * CT + (k >> 5)) * 64 + 16 * ((k & 31) >> 3)) * 8 + (k & 7);
-                *(__half2 *)(tp + (t & 15) * 8) = o;
-                if (t == M - 1)
-                    for (int pad = (t & 15) + 1; pad < 16; pad++) *(__half2 *)(tp + pad * 8) = __floats2half2_rn(0.0f, 0.0f);
+            const v8h r = *(const v8h *)(dres + row + k);
+            v8h o;
+#pragma unroll
+            for (int e = 0; e < 8; e++)
+                o[e] = (_Float16)__half2float(__float2half_rn((float)r[e] + inv * (dv[i][e] - ma - (xv[i][e] - mean) * imc)));
+            *(v8h *)(dx + row + k) = o;
+            if (tiles) {   // 16 x 32 tile: lane slot 16 * (column group of 8) + row, 8 halves each
+                __half *tp = tiles + (((size_t)(t >> 4) * CT + (k >> 5)) * 64 + 16 * ((k & 31) >> 3)) * 8;
+                *(v8h *)(tp + (t & 15) * 8) = o;
+                if (t == M - 1) {
+                    const v8h zero = {0, 0, 0, 0, 0, 0, 0, 0};
+                    for (int pad = (t & 15) + 1; pad < 16; pad++) *(v8h *)(tp + pad * 8) = zero;
+                }
             }
         }
     }
@@ -407,8 +411,9 @@ hipError_t ps_transpose_w(const LinearW &w, __half *wt16, hipStream_t st) {
 
 hipError_t ps_ln_bwd(const float *dz, const __half *x, const __half *g, const __half *dres, float eps, int M, int H,
                      __half *dx, __half *tiles, hipStream_t st) {
-    if (H > 16384) return hipErrorInvalidValue;
-    k_ln_bwd<<<M, 1024, 0, st>>>(dz, x, g, dres, eps, H, dx, tiles);
+    if (H > 16384 || H % 8) return hipErrorInvalidValue;
+    if (M >= 512) k_ln_bwd<256, 8><<<M, 256, 0, st>>>(dz, x, g, dres, eps, H, dx, tiles);
+    else k_ln_bwd<1024, 2><<<M, 1024, 0, st>>>(dz, x, g, dres, eps, H, dx, tiles);
     return hipGetLastError();
 }
 
