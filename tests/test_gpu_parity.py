@@ -110,6 +110,42 @@ def test_linear_dense_outlier_sets():
     gsp.close(); osp.destroy()
 
 
+# ---------------------------------------------------------------- LayerNorm
+
+@pytest.mark.parametrize("M,H", [(1, 64), (7, 1024), (300, 1024), (1, 14336), (3, 14336), (300, 4096), (600, 4096),
+                                 (513, 4160), (520, 14336), (512, 16384)])
+def test_layernorm_kernels_against_the_oracle(M, H):
+    """Every LayerNorm kernel (inside the one-row linear; one workgroup per row with the row re-read or held in
+    registers; 256 threads per row for calls of 512 rows and more) on rows with outlier dims, a constant row and a
+    zero row.  fp64 on both sides: the fp16 results are the same bits."""
+    sp = binding.Span(1, H, H // 64, 64, M, device=DEV)
+    r = np.random.default_rng(M * 7 + H)
+    ln = {k: (1.0 + 0.1 * r.standard_normal(H) if k.endswith("g") else 0.1 * r.standard_normal(H)).astype(np.float16)
+          for k in ("ln1_g", "ln1_b", "ln2_g", "ln2_b")}
+    p = {k: to_dev(v) for k, v in ln.items()}
+    for name, (N, K) in zip(("qkv", "dense", "up", "down"), (sp.shapes(i) for i in range(4))):
+        p["w_" + name] = torch.zeros((N, K), dtype=torch.float32, device=DEV)
+        p["b_" + name] = torch.zeros(N, dtype=torch.float16, device=DEV)
+    sp.load_block(0, p)
+    x = r.standard_normal((M, H)) * r.uniform(0.05, 3.0, (M, 1)) + r.uniform(-1.0, 1.0, (M, 1))
+    x[:, r.choice(H, 3, replace=False)] = r.uniform(20.0, 60.0, (M, 3))
+    if M > 2:
+        x[1] = 0.0
+        x[2] = 3.25
+    x = x.astype(np.float16)
+    try:
+        for which in (0, 1):
+            y = sp.debug_layernorm(0, which, to_dev(x))
+            torch.cuda.synchronize()
+            ref = oracle.layernorm(x, ln["ln%d_g" % (which + 1)], ln["ln%d_b" % (which + 1)])
+            got = to_np(y)
+            same = got.view(np.uint16) == ref.view(np.uint16)
+            assert same.all(), "LayerNorm %d of %d x %d: %d elements differ, first at %s" % (
+                which, M, H, (~same).sum(), np.argwhere(~same)[:3].tolist())
+    finally:
+        sp.close()
+
+
 # --------------------------------------------------------------- end to end
 
 def _run_generation(cfg, nb, B, T, steps, theta=6.0, cap=None):
