@@ -505,6 +505,41 @@ def test_c4_full_size_linears_at_the_benchmark_row_count_sampled_against_the_ora
         gsp.close()
 
 
+@pytest.mark.parametrize("n_outlier_cols", [6, 300])
+def test_c4_full_size_down_linear_at_1024_rows_sampled_against_the_oracle(n_outlier_cols):
+    """The widest rows (K = 57344) in a prefill-size call: the row quantizer that keeps such a row in the registers
+    of 1024 threads, the int8 pipeline over 896 k-tiles, and - with 300 outlier columns - the sorted column list,
+    the gathers of activations and dequantized weights and the fp16 product.  The oracle computes a sample of
+    output features."""
+    cfg = synth.CONFIGS["C4"]
+    M = 1024
+    p = synth.block_params_device(cfg, 0, DEV)
+    gsp = binding.Span(1, cfg.hidden, cfg.n_heads, cfg.F, M, 1e-5, 6.0, DEV)
+    gsp.load_block(0, p)
+    r = np.random.default_rng(23 + n_outlier_cols)
+    try:
+        N, K = gsp.shapes(3)
+        rows = np.unique(np.concatenate([np.arange(8), r.choice(N, 24, replace=False), np.arange(N - 8, N)]))
+        wq, sw = oracle.quantize_weight(p["w_down"][torch.as_tensor(rows, device=DEV)].cpu().numpy())
+        bsub = p["b_down"].cpu().numpy()[rows]
+        X = r.standard_normal((M, K)) * 0.8
+        cols = r.choice(K, n_outlier_cols, replace=False)
+        X[r.integers(0, M, n_outlier_cols), cols] = r.uniform(6.5, 30, n_outlier_cols) * r.choice([-1, 1], n_outlier_cols)
+        X = X.astype(np.float16)
+        resid = r.standard_normal((M, N)).astype(np.float16)
+        Y, dbg = oracle.linear(X, wq, sw, bsub, 6.0, 2, resid[:, rows], want_debug=True)
+        assert dbg["mask"].sum() == n_outlier_cols
+        print("C4 down linear at %d rows, %d outlier columns" % (M, n_outlier_cols), flush=True)
+        out = gsp.debug_linear(0, 3, to_dev(X), 2, to_dev(resid))
+        torch.cuda.synchronize()
+        assert np.array_equal(to_np(out["mask"]), dbg["mask"])
+        assert np.array_equal(to_np(out["xq"]), dbg["xq"]) and np.array_equal(to_np(out["sx"]), dbg["sx"])
+        assert np.array_equal(to_np(out["acc"])[:, rows], dbg["acc"])
+        hidden_close(to_np(out["y"])[:, rows], Y, "C4 down linear M=%d" % M)
+    finally:
+        gsp.close()
+
+
 def test_c4_full_size_down_linear_with_many_outlier_columns():
     """Batched decode on the widest linear (K = 57344) when about 5% of its input columns are outliers, as the
     GeLU output of this configuration has them; one 16-column group is all outliers (more than the 8 values
