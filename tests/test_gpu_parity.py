@@ -505,6 +505,56 @@ def test_c4_full_size_linears_at_the_benchmark_row_count_sampled_against_the_ora
         gsp.close()
 
 
+def test_c4_full_size_prefill_attention_sampled_heads_against_the_oracle():
+    """The attention of the prefill benchmark's call (8 sessions x 512 tokens, 112 heads of 128 dims, empty caches:
+    896 (session, head) pairs x 8 query blocks, in the launch configuration bench.py times) on sampled heads.
+    A one-block span is arranged so that its output shows the attention context: threshold 0 makes every column
+    an outlier column, so no row-wise int8 scale couples the heads; the dense weight is the identity (its int8
+    code 127 times the scale 1/127 is 1.0 in fp16) and the down weight is zero, so the output is fp16(x + context).
+    The oracle runs LayerNorm, the sampled head's 384 rows of the QKV linear and the attention for one session."""
+    cfg = synth.CONFIGS["C4"]
+    B, T, H, nh = 8, 512, cfg.hidden, cfg.n_heads
+    d = H // nh
+    p = synth.block_params_device(cfg, 0, DEV)
+    p["w_dense"] = torch.eye(H, dtype=torch.float32, device=DEV)
+    p["b_dense"] = torch.zeros(H, dtype=torch.float16, device=DEV)
+    p["w_down"] = torch.zeros_like(p["w_down"])
+    p["b_down"] = torch.zeros(H, dtype=torch.float16, device=DEV)
+    gsp = binding.Span(1, H, nh, cfg.F, B * T, 1e-5, 0.0, DEV)
+    gsp.load_block(0, p)
+    try:
+        X = synth.hidden_states(cfg, 0, B, T)
+        sessions = [gsp.open_session(T) for _ in range(B)]
+        print("C4 prefill attention, %d x %d tokens" % (B, T), flush=True)
+        Y = to_np(gsp.prefill(sessions, to_dev(X)))
+        g1, b1 = p["ln1_g"].cpu().numpy(), p["ln1_b"].cpu().numpy()
+        slopes = oracle.alibi_slopes(nh)
+        for s, h in ((0, 0), (5, 57), (7, 111)):
+            a = oracle.layernorm(X[s], g1, b1)
+            rows = torch.arange(h * 3 * d, (h + 1) * 3 * d, device=DEV)
+            wq, sw = oracle.quantize_weight(p["w_qkv"][rows].cpu().numpy())
+            qkv_h = oracle.linear(a, wq, sw, p["b_qkv"][rows].cpu().numpy(), 0.0)          # [T, 3d]
+            qkv = np.zeros((T, 3 * H), np.float16)
+            qkv[:, h * 3 * d:(h + 1) * 3 * d] = qkv_h
+            kc, vc = np.zeros((nh, T, d), np.float16), np.zeros((nh, T, d), np.float16)
+            ctx = oracle.attention(qkv, nh, kc, vc, 0)[:, h * d:(h + 1) * d]
+            want = (X[s][:, h * d:(h + 1) * d].astype(np.float64) + ctx.astype(np.float64)).astype(np.float16)
+            got = Y[s][:, h * d:(h + 1) * d]
+            # the sampled head attends with its own slope, not uniformly: the context must differ from a plain mean
+            assert slopes[h] > 0 and np.abs(ctx.astype(np.float64)).max() > 0.5
+            # With every column an outlier column the QKV linear runs on the fp16 matrix instruction with fp32 sums,
+            # so a few percent of the queries, keys and values are one fp16 ulp off the oracle's, and so is the
+            # output where that matters: the tolerance of hidden states, and most elements the same bits.
+            hidden_close(got[None], want[None], "session %d head %d" % (s, h))
+            same = got.view(np.uint16) == want.view(np.uint16)
+            assert same.mean() > 0.9, same.mean()
+            kv = to_np(sessions[s].export_kv(0))
+            hidden_close(kv[0, h][None], qkv_h[None, :, d:2 * d], "keys of session %d head %d" % (s, h))
+            hidden_close(kv[1, h][None], qkv_h[None, :, 2 * d:], "values of session %d head %d" % (s, h))
+    finally:
+        gsp.close()
+
+
 @pytest.mark.parametrize("n_outlier_cols", [6, 300])
 def test_c4_full_size_down_linear_at_1024_rows_sampled_against_the_oracle(n_outlier_cols):
     """The widest rows (K = 57344) in a prefill-size call: the row quantizer that keeps such a row in the registers
