@@ -4,7 +4,6 @@ Argument marshalling only: every step of the arithmetic is in the C file.
 fp16 tensors are numpy float16 arrays (viewed as uint16 at the C boundary).
 """
 import ctypes as C
-import os
 
 import numpy as np
 

@@ -110,7 +110,7 @@ __global__ void __launch_bounds__(1024) k_layernorm_wide(const __half *__restric
     double q = 0.0;
 #pragma unroll
     for (int i = 0; i < PER; i++) {
-        if ((threadIdx.x + i * NT) * 2 < H) {
+        if ((int)(threadIdx.x + i * NT) * 2 < H) {
             const float2 f = __half22float2(v[i]);
             const double a = (double)f.x - mean, c = (double)f.y - mean;
             q += a * a + c * c;
@@ -158,7 +158,7 @@ __global__ void __launch_bounds__(256) k_layernorm_rows(const __half *__restrict
     double q = 0.0;
 #pragma unroll
     for (int i = 0; i < PER; i++) {
-        if ((threadIdx.x + i * NT) * 8 < H) {
+        if ((int)(threadIdx.x + i * NT) * 8 < H) {
 #pragma unroll
             for (int e = 0; e < 8; e++) {
                 const double a = (double)(float)v[i][e] - mean;
@@ -313,7 +313,7 @@ __global__ void __launch_bounds__(NT) k_rowquant_tiled_wide(const __half *__rest
     float m = 0.0f;
 #pragma unroll
     for (int i = 0; i < CPT; i++) {
-        if (threadIdx.x + i * NT < nchunk) {
+        if ((int)(threadIdx.x + i * NT) < nchunk) {
 #pragma unroll
             for (int j = 0; j < 8; j++) {
                 if (!((bits[i] >> j) & 1u)) m = fmaxf(m, fabsf((float)a[i][j]));
