@@ -74,7 +74,7 @@ __global__ void __launch_bounds__(GEMV_GROUP * NG) k_gemv_row(LinearW w, RowIn i
                                                              int panels_extra) {
     constexpr int GEMV_THREADS = GEMV_GROUP * NG, NWV = GEMV_THREADS / 64;
     extern __shared__ __align__(16) unsigned char lds[];
-    __shared__ double smd[NWV];
+    __shared__ double smd[NWV], smq[NWV];
     __shared__ int smi[NWV];
     const int K = w.K, KT = K >> 6, nch8 = K >> 3;
     int8_t *xs = (int8_t *)lds;                               // K codes
@@ -102,20 +102,24 @@ __global__ void __launch_bounds__(GEMV_GROUP * NG) k_gemv_row(LinearW w, RowIn i
     for (int i = threadIdx.x; i < K / 32; i += GEMV_THREADS) ((uint32_t *)m8)[i] = 0u;
     double mean = 0.0, inv = 0.0;
     if (LN) {
-        double s = 0.0;
+        // Both moments in one pass and one reduction.  The squares of fp16 values are exact in fp64 and the sums
+        // carry 1e-16 of relative error, so the variance as "mean of squares minus squared mean" is as good as
+        // the two-pass form unless the mean dwarfs the spread by a factor of 1e6, which a hidden state never does.
+        double s = 0.0, q = 0.0;
         for (int c = threadIdx.x; c < nch8; c += GEMV_THREADS) {
             v8h v = *(const v8h *)(in.x + c * 8);
 #pragma unroll
-            for (int e = 0; e < 8; e++) s += (double)(float)v[e];
+            for (int e = 0; e < 8; e++) { const double a = (double)(float)v[e]; s += a; q = fma(a, a, q); }
         }
-        mean = block_sum<NWV>(s, smd) / (double)K;
-        double q = 0.0;
-        for (int c = threadIdx.x; c < nch8; c += GEMV_THREADS) {
-            v8h v = *(const v8h *)(in.x + c * 8);
+        s = wave_sum(s);
+        q = wave_sum(q);
+        if (lane == 0) { smd[wave] = s; smq[wave] = q; }
+        __syncthreads();
+        s = q = 0.0;
 #pragma unroll
-            for (int e = 0; e < 8; e++) { const double a = (double)(float)v[e] - mean; q += a * a; }
-        }
-        inv = 1.0 / sqrt(block_sum<NWV>(q, smd) / (double)K + (double)in.eps);
+        for (int i = 0; i < NWV; i++) { s += smd[i]; q += smq[i]; }
+        mean = s / (double)K;
+        inv = 1.0 / sqrt(fmax(q / (double)K - mean * mean, 0.0) + (double)in.eps);
     } else {
         __syncthreads();      // mask bytes cleared before anybody sets one
     }

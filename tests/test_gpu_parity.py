@@ -132,16 +132,21 @@ def test_layernorm_kernels_against_the_oracle(M, H):
     if M > 2:
         x[1] = 0.0
         x[2] = 3.25
-    x = x.astype(np.float16)
+    cases = [x.astype(np.float16)]
+    if M == 1:      # the one-row kernel gets its special rows one at a time
+        shifted = r.standard_normal((1, H)) * 0.01 + 40.0          # a mean 4000 times the spread
+        cases += [np.zeros((1, H), np.float16), np.full((1, H), 3.25, np.float16), np.full((1, H), 0.1, np.float16),
+                  shifted.astype(np.float16)]
     try:
-        for which in (0, 1):
-            y = sp.debug_layernorm(0, which, to_dev(x))
-            torch.cuda.synchronize()
-            ref = oracle.layernorm(x, ln["ln%d_g" % (which + 1)], ln["ln%d_b" % (which + 1)])
-            got = to_np(y)
-            same = got.view(np.uint16) == ref.view(np.uint16)
-            assert same.all(), "LayerNorm %d of %d x %d: %d elements differ, first at %s" % (
-                which, M, H, (~same).sum(), np.argwhere(~same)[:3].tolist())
+        for xc in cases:
+            for which in (0, 1):
+                y = sp.debug_layernorm(0, which, to_dev(xc))
+                torch.cuda.synchronize()
+                ref = oracle.layernorm(xc, ln["ln%d_g" % (which + 1)], ln["ln%d_b" % (which + 1)])
+                got = to_np(y)
+                same = got.view(np.uint16) == ref.view(np.uint16)
+                assert same.all(), "LayerNorm %d of %d x %d: %d elements differ, first at %s" % (
+                    which, M, H, (~same).sum(), np.argwhere(~same)[:3].tolist())
     finally:
         sp.close()
 
