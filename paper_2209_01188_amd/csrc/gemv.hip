@@ -101,15 +101,28 @@ __global__ void __launch_bounds__(GEMV_GROUP * NG) k_gemv_row(LinearW w, RowIn i
 
     for (int i = threadIdx.x; i < K / 32; i += GEMV_THREADS) ((uint32_t *)m8)[i] = 0u;
     double mean = 0.0, inv = 0.0;
+    v8h xr[LN ? MAXCH : 1], gr[LN ? MAXCH : 1], br[LN ? MAXCH : 1];
     if (LN) {
         // Both moments in one pass and one reduction.  The squares of fp16 values are exact in fp64 and the sums
         // carry 1e-16 of relative error, so the variance as "mean of squares minus squared mean" is as good as
         // the two-pass form unless the mean dwarfs the spread by a factor of 1e6, which a hidden state never does.
-        double s = 0.0, q = 0.0;
-        for (int c = threadIdx.x; c < nch8; c += GEMV_THREADS) {
-            v8h v = *(const v8h *)(in.x + c * 8);
+        // the row, the gain and the bias are requested together and stay in registers
 #pragma unroll
-            for (int e = 0; e < 8; e++) { const double a = (double)(float)v[e]; s += a; q = fma(a, a, q); }
+        for (int i = 0; i < MAXCH; i++) {
+            const int c = threadIdx.x + GEMV_THREADS * i;
+            if (c < nch8) {
+                xr[i] = *(const v8h *)(in.x + c * 8);
+                gr[i] = *(const v8h *)(in.ln_g + c * 8);
+                br[i] = *(const v8h *)(in.ln_b + c * 8);
+            }
+        }
+        double s = 0.0, q = 0.0;
+#pragma unroll
+        for (int i = 0; i < MAXCH; i++) {
+            if (threadIdx.x + GEMV_THREADS * i < nch8) {
+#pragma unroll
+                for (int e = 0; e < 8; e++) { const double a = (double)(float)xr[i][e]; s += a; q = fma(a, a, q); }
+            }
         }
         s = wave_sum(s);
         q = wave_sum(q);
@@ -132,7 +145,7 @@ __global__ void __launch_bounds__(GEMV_GROUP * NG) k_gemv_row(LinearW w, RowIn i
         const int c = threadIdx.x + GEMV_THREADS * i;
         if (c < nch8) {
             if (LN) {
-                v8h v = *(const v8h *)(in.x + c * 8), gg = *(const v8h *)(in.ln_g + c * 8), bb = *(const v8h *)(in.ln_b + c * 8);
+                const v8h v = xr[i], gg = gr[i], bb = br[i];
                 __half out[8];
 #pragma unroll
                 for (int e = 0; e < 8; e++)
