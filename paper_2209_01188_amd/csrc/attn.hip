@@ -186,13 +186,15 @@ __device__ __forceinline__ void merge_state(double &m, double &l, double *o, dou
 // state, the groups, then the 4 waves, then the key ranges are merged at the end.  fp64
 // throughout: the kernel waits on HBM anyway, and the fp16 context then equals the exactly
 // rounded one.
-template <int D>
-__global__ void __launch_bounds__(256) k_attn_decode(const __half *__restrict__ q, const SessTable *__restrict__ sess,
+// NW waves per workgroup: 8 instead of 4 where that lets one workgroup take the whole key range of a (row, head),
+// so that no partial results go through memory.
+template <int D, int NW>
+__global__ void __launch_bounds__(64 * NW) k_attn_decode(const __half *__restrict__ q, const SessTable *__restrict__ sess,
                                                      int blk, int nh, int CH, int nsplit,
                                                      double *__restrict__ partials, __half *__restrict__ ctx,
                                                      uint32_t *__restrict__ mask, float theta) {
     constexpr int LPK = D / 8, KPI = 64 / LPK, NIT = LPK;
-    __shared__ double red_m[4], red_l[4], red_o[4][D];
+    __shared__ double red_m[NW], red_l[NW], red_o[NW][D];
     const int c = blockIdx.x, h = blockIdx.y, s = blockIdx.z;
     const int i = sess->len[s];                                // position of the query; keys 0..i
     const int k_begin = c * CH, k_end = min(i + 1, k_begin + CH);
@@ -204,7 +206,7 @@ __global__ void __launch_bounds__(256) k_attn_decode(const __half *__restrict__ 
     // (q . k) / sqrt(d) is computed as (q / sqrt(d)) . k: one division per query element instead of one per key;
     // the fp64 result moves by a few 1e-16 relative, far below the final fp16 rounding
     const double slope = sess->slopes[h], inv_rsd = 1.0 / sqrt((double)D);
-    const int per = (((k_end - k_begin + 3) >> 2) + 63) & ~63;
+    const int per = (((k_end - k_begin + NW - 1) / NW) + 63) & ~63;
     const int wb = k_begin + wave * per, we = min(k_end, wb + per);
     double qf[8];
     {
@@ -277,7 +279,7 @@ __global__ void __launch_bounds__(256) k_attn_decode(const __half *__restrict__ 
     __syncthreads();
     if (threadIdx.x < D) {
         double m = red_m[0], l = red_l[0], ov = red_o[0][threadIdx.x];
-        for (int w2 = 1; w2 < 4; w2++) {
+        for (int w2 = 1; w2 < NW; w2++) {
             const double o2 = red_o[w2][threadIdx.x];
             merge_state(m, l, &ov, red_m[w2], red_l[w2], &o2, 1);
         }
@@ -332,7 +334,11 @@ hipError_t attn_launch(const __half *q, const SessTable *sess, int blk, int M, i
         k_attn_prefill<D><<<(B * nh + 7) / 8 * 8 * ((T + 63) / 64), 256, (size_t)2 * 2 * 16 * D * 8, st>>>(q, sess, blk, B, T, nh, ctx, mask, theta, lse, ctx32);
         return hipGetLastError();
     }
-    k_attn_decode<D><<<dim3(nsplit, nh, M), 256, 0, st>>>(q, sess, blk, nh, CH, nsplit, partials, ctx, mask, theta);
+    if (nsplit == 2) {   // twice the waves per workgroup instead of two key ranges: nothing to merge afterwards
+        k_attn_decode<D, 8><<<dim3(1, nh, M), 512, 0, st>>>(q, sess, blk, nh, 1 << 30, 1, partials, ctx, mask, theta);
+        return hipGetLastError();
+    }
+    k_attn_decode<D, 4><<<dim3(nsplit, nh, M), 256, 0, st>>>(q, sess, blk, nh, CH, nsplit, partials, ctx, mask, theta);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || nsplit == 1) return e;
     k_attn_combine<D><<<dim3(nh, M), D, 0, st>>>(sess, T, nh, CH, nsplit, partials, ctx, mask, theta);
