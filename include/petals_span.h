@@ -247,10 +247,14 @@ int petals_debug_linear(petals_span *span, int32_t block, int32_t which, const v
 
 /*
  * One LayerNorm of a loaded block (which: 0 = before attention, 1 = before the MLP) on
- * dev fp16 x [M, H] -> y [M, H], through the kernel prefill/decode use for that M.
+ * dev fp16 x [M, H] -> y [M, H], through the kernels a call of M rows uses, together with what
+ * the linear behind it (QKV or up) makes of y before it multiplies (each may be NULL):
+ * xq dev int8 [M, H] row-major codes, sx dev fp32 [M] row scales, outlier_mask dev uint8 [H].
+ * The linear itself runs too; its result is discarded.
  */
 int petals_debug_layernorm(petals_span *span, int32_t block, int32_t which, const void *x,
-                           int32_t M, void *y, void *stream);
+                           int32_t M, void *y, int8_t *xq, float *sx, uint8_t *outlier_mask,
+                           void *stream);
 
 /* Row-major int8 codes [N, K] and row scales [N] of a loaded linear (dev outputs). */
 int petals_debug_export_weight(petals_span *span, int32_t block, int32_t which, int8_t *wq,

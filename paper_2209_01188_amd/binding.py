@@ -192,9 +192,9 @@ def petals_debug_linear(span, block, which, x, epilogue=EPILOGUE_NONE, resid=Non
                                      _ptr(acc), _ptr(y), _stream()))
 
 
-def petals_debug_layernorm(span, block, which, x, y):
+def petals_debug_layernorm(span, block, which, x, y, xq=None, sx=None, mask=None):
     _check(lib().petals_debug_layernorm(span, C.c_int32(block), C.c_int32(which), _ptr(x), C.c_int32(x.shape[0]),
-                                        _ptr(y), _stream()))
+                                        _ptr(y), _ptr(xq), _ptr(sx), _ptr(mask), _stream()))
 
 
 def petals_span_backward_bytes(cfg, B, T):
@@ -317,10 +317,18 @@ class Span:
                             out["acc"], out["y"])
         return out
 
-    def debug_layernorm(self, block, which, x):
+    def debug_layernorm(self, block, which, x, want_quantized=False):
+        """LayerNorm output; with want_quantized also what the linear behind it sees: dict(y, xq, sx, mask)."""
         y = torch.empty_like(x)
-        petals_debug_layernorm(self.handle, block, which, x, y)
-        return y
+        if not want_quantized:
+            petals_debug_layernorm(self.handle, block, which, x, y)
+            return y
+        M, H = x.shape
+        out = dict(y=y, xq=torch.empty((M, H), dtype=torch.int8, device=self.device),
+                   sx=torch.empty(M, dtype=torch.float32, device=self.device),
+                   mask=torch.empty(H, dtype=torch.uint8, device=self.device))
+        petals_debug_layernorm(self.handle, block, which, x, y, out["xq"], out["sx"], out["mask"])
+        return out
 
     def export_weight(self, block, which):
         N, K = self.shapes(which)

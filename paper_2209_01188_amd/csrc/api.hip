@@ -494,26 +494,26 @@ int petals_debug_linear(petals_span *sp, int32_t block, int32_t which, const voi
     return PETALS_OK;
 }
 
-int petals_debug_layernorm(petals_span *sp, int32_t block, int32_t which, const void *x, int32_t M, void *y, void *stream) {
+int petals_debug_layernorm(petals_span *sp, int32_t block, int32_t which, const void *x, int32_t M, void *y, int8_t *xq,
+                           float *sx, uint8_t *outlier_mask, void *stream) {
     if (!sp || !x || !y) return fail(PETALS_ERR_INVALID_ARG, "null pointer");
     if (block < 0 || block >= sp->cfg.n_blocks || which < 0 || which > 1) return fail(PETALS_ERR_INVALID_ARG, "block or LayerNorm index out of range");
     if (!sp->blocks[block].loaded) return fail(PETALS_ERR_STATE, "block %d has not been loaded", block);
     if (M < 1 || M > sp->cfg.max_rows_per_call) return fail(PETALS_ERR_CAPACITY, "M out of range");
     const BlockW &W = sp->blocks[block];
     const petals_span_config &c = sp->cfg;
+    Workspace &ws = sp->ws;
     hipStream_t st = (hipStream_t)stream;
-    if (M == 1) {
-        // the decode path normalises inside the linear that follows: run that kernel (QKV or up) and
-        // take its copy of the LayerNorm output; the linear's own result goes to scratch
-        Workspace &ws = sp->ws;
-        RowDebug dbg = {(__half *)y, nullptr, nullptr, nullptr};
-        HIP_TRY(ps_gemv_row(W.lin[which ? 2 : 0], (const __half *)x, which ? W.ln2g : W.ln1g, which ? W.ln2b : W.ln1b,
-                            c.ln_eps, c.outlier_threshold, dbg, plain_out(ws.g, PETALS_EPILOGUE_NONE, nullptr),
-                            ws.table, st));
-    } else {
-        HIP_TRY(ps_layernorm((const __half *)x, which ? W.ln2g : W.ln1g, which ? W.ln2b : W.ln1b, c.ln_eps, M, c.hidden,
-                             (__half *)y, nullptr, 0.0f, st));
-    }
+    // the linear that reads this LayerNorm (QKV or up), with its result going to scratch: run_linear picks the
+    // kernels a call of M rows uses and copies the LayerNorm output and the integer intermediates out
+    const LinearW &L = W.lin[which ? 2 : 0];
+    uint32_t *mk = ws.masks;
+    if (M > 1) HIP_TRY(ps_fill_u32(mk, ws.mask_words, 0u, st));
+    if (int rc = run_linear(sp, which ? 2 : 0, L, (const __half *)x, which ? W.ln2g : W.ln1g, which ? W.ln2b : W.ln1b, M, mk,
+                            M > 1, plain_out(ws.g, PETALS_EPILOGUE_NONE, nullptr), xq, true, st)) return rc;
+    HIP_TRY(ps_copy_bytes(ws.a, y, (size_t)M * c.hidden * 2, st));
+    if (sx) HIP_TRY(ps_copy_bytes(ws.sx, sx, (size_t)M * 4, st));
+    if (outlier_mask) HIP_TRY(ps_mask_to_bytes(mk, L.K, outlier_mask, st));
     return PETALS_OK;
 }
 

@@ -113,11 +113,12 @@ def test_linear_dense_outlier_sets():
 # ---------------------------------------------------------------- LayerNorm
 
 @pytest.mark.parametrize("M,H", [(1, 64), (7, 1024), (300, 1024), (1, 14336), (3, 14336), (300, 4096), (600, 4096),
-                                 (513, 4160), (520, 14336), (512, 16384)])
+                                 (513, 4160), (520, 14336), (512, 16384), (2, 1024), (16, 4096), (65, 2048)])
 def test_layernorm_kernels_against_the_oracle(M, H):
     """Every LayerNorm kernel (inside the one-row linear; one workgroup per row with the row re-read or held in
     registers; 256 threads per row for calls of 512 rows and more) on rows with outlier dims, a constant row and a
-    zero row.  fp64 on both sides: the fp16 results are the same bits."""
+    zero row.  fp64 on both sides: the fp16 results are the same bits, and so are the outlier columns, row scales and
+    int8 codes the linear behind the LayerNorm derives from them."""
     sp = binding.Span(1, H, H // 64, 64, M, device=DEV)
     r = np.random.default_rng(M * 7 + H)
     ln = {k: (1.0 + 0.1 * r.standard_normal(H) if k.endswith("g") else 0.1 * r.standard_normal(H)).astype(np.float16)
@@ -140,13 +141,19 @@ def test_layernorm_kernels_against_the_oracle(M, H):
     try:
         for xc in cases:
             for which in (0, 1):
-                y = sp.debug_layernorm(0, which, to_dev(xc))
+                out = sp.debug_layernorm(0, which, to_dev(xc), want_quantized=True)
                 torch.cuda.synchronize()
                 ref = oracle.layernorm(xc, ln["ln%d_g" % (which + 1)], ln["ln%d_b" % (which + 1)])
-                got = to_np(y)
+                got = to_np(out["y"])
                 same = got.view(np.uint16) == ref.view(np.uint16)
                 assert same.all(), "LayerNorm %d of %d x %d: %d elements differ, first at %s" % (
                     which, M, H, (~same).sum(), np.argwhere(~same)[:3].tolist())
+                # one output feature is enough to get the oracle's view of the rows
+                _, dbg = oracle.linear(ref, np.zeros((1, H), np.int8), np.ones(1, np.float32), np.zeros(1, np.float16),
+                                       6.0, want_debug=True)
+                assert np.array_equal(to_np(out["mask"]), dbg["mask"]), "outlier columns"
+                assert np.array_equal(to_np(out["sx"]).view(np.uint32), dbg["sx"].view(np.uint32)), "row scales"
+                assert np.array_equal(to_np(out["xq"]), dbg["xq"]), "int8 codes"
     finally:
         sp.close()
 
