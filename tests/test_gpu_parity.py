@@ -302,6 +302,45 @@ def test_prefill_onto_a_filled_cache_and_ragged_batched_decode(hidden, heads):
     gsp.close(); osp.destroy()
 
 
+def test_chained_spans_sharing_one_workspace_equal_one_long_span():
+    """Consecutive blocks split over several spans (Section 2.1: a chain of servers, each holding a span), here on
+    one GPU with ONE workspace handed to all of them, since they never run at the same time: prefill and decode
+    through the chain give the bits of a single span over all the blocks, and match the oracle."""
+    cfg = synth.scaled(C2, n_blocks=5)
+    osp, whole, params = build_pair(cfg, n_blocks=5, max_rows=24)
+    need = binding.petals_span_workspace_bytes(whole.cfg)
+    shared = torch.empty(need, dtype=torch.uint8, device=DEV)
+    chain, first = [], 0
+    for n in (2, 1, 2):
+        sp = binding.Span(n, cfg.hidden, cfg.n_heads, cfg.F, 24, 1e-5, 6.0, DEV, workspace=shared)
+        for b in range(n):
+            sp.load_block(b, params[first + b])
+        chain.append(sp)
+        first += n
+    B, T = 2, 12
+    X = synth.hidden_states(cfg, 0, B, T)
+    oses = [osp.open_session(16) for _ in range(B)]
+    wses = [whole.open_session(16) for _ in range(B)]
+    cses = [[sp.open_session(16) for _ in range(B)] for sp in chain]
+    try:
+        def through_chain(x, decode):
+            for sp, ses in zip(chain, cses):
+                x = sp.decode_step(ses, x) if decode else sp.prefill(ses, x)
+            return x
+        y_chain, y_whole = through_chain(to_dev(X), False), whole.prefill(wses, to_dev(X))
+        assert torch.equal(y_chain, y_whole)
+        hidden_close(to_np(y_chain), osp.step(oses, X), "chained prefill")
+        for i in (1, 2, 3):
+            x = synth.hidden_states(cfg, i, B, 1)
+            y_chain, y_whole = through_chain(to_dev(x[:, 0]), True), whole.decode_step(wses, to_dev(x[:, 0]))
+            assert torch.equal(y_chain, y_whole)
+            hidden_close(to_np(y_chain)[:, None], osp.step(oses, x), "chained decode %d" % i)
+    finally:
+        for sp in chain:
+            sp.close()
+        whole.close(); osp.destroy()
+
+
 def test_replay_of_recorded_inputs_rebuilds_the_cache_bit_for_bit():
     """Failure recovery (paper Section 3.2): the recorded inputs of a session, replayed call by call into a fresh
     session, give the same keys and values and the same next output as the original."""
