@@ -302,6 +302,36 @@ def test_prefill_onto_a_filled_cache_and_ragged_batched_decode(hidden, heads):
     gsp.close(); osp.destroy()
 
 
+def test_calls_run_on_the_stream_they_are_given():
+    """The library enqueues on the caller's stream and never synchronizes: a prefill and decode steps issued on a
+    second stream (default priority), with a long-running fill queued ahead of them on that stream, give the bits
+    of the same calls on the default stream; the test waits for that stream's event only."""
+    cfg = synth.scaled(C2, n_blocks=2)
+    osp, gsp, _ = build_pair(cfg, n_blocks=2, max_rows=16)
+    X = to_dev(synth.hidden_states(cfg, 0, 2, 8))
+    xs = [to_dev(synth.hidden_states(cfg, i, 2, 1)[:, 0]) for i in (1, 2)]
+    try:
+        a = [gsp.open_session(12) for _ in range(2)]
+        want = [gsp.prefill(a, X)] + [gsp.decode_step(a, x) for x in xs]
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream(device=DEV)
+        b = [gsp.open_session(12) for _ in range(2)]
+        ballast = torch.empty(1 << 28, dtype=torch.float32, device=DEV)
+        with torch.cuda.stream(side):
+            for _ in range(4):
+                ballast.normal_()                         # work queued ahead of the calls on the side stream
+            got = [gsp.prefill(b, X)] + [gsp.decode_step(b, x) for x in xs]
+            done = torch.cuda.Event()
+            done.record(side)
+        done.synchronize()
+        for g, w in zip(got, want):
+            assert torch.equal(g, w)
+        assert [s.length for s in b] == [10, 10]
+    finally:
+        torch.cuda.synchronize()
+        gsp.close(); osp.destroy()
+
+
 def test_chained_spans_sharing_one_workspace_equal_one_long_span():
     """Consecutive blocks split over several spans (Section 2.1: a chain of servers, each holding a span), here on
     one GPU with ONE workspace handed to all of them, since they never run at the same time: prefill and decode
