@@ -32,6 +32,24 @@ def step_bytes(cfg, L):
     return cfg.n_blocks * per_block + 4 * H
 
 
+def _block_params(args, cfg, block, dev):
+    """The recipe's block parameters, drawn on the device; --weight-std other than the recipe's 0.02 rescales the
+    four weight matrices (a context measurement: how the figures move with the number of outlier columns)."""
+    from paper_2209_01188_amd import synth
+    p = synth.block_params_device(cfg, block, dev)
+    if args.weight_std != 0.02:
+        for name in ("w_qkv", "w_dense", "w_up", "w_down"):
+            p[name].mul_(args.weight_std / 0.02)
+    return p
+
+
+def _emit(args, line):
+    if args.weight_std != 0.02:      # not the recipe: say so in the line
+        line["config"]["weight_std"] = args.weight_std
+        line["data"] = "synthetic (weights N(0, %g^2) instead of the recipe's N(0, 0.02^2))" % args.weight_std
+    print(json.dumps(line))
+
+
 def traffic_from_profile():
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary, if present."""
     path = os.path.join(ROOT, "profiles", "k_gemv_row_c4_decode_pmc.txt")
@@ -60,6 +78,9 @@ def main():
                          "70-block BLOOM-176B-shaped stack, 32 sessions; C5 = the whole 70-block stack (six chained "
                          "spans, about 250 GB of HBM), 32 sessions")
     ap.add_argument("--prefill-batch", type=int, default=8, help="sessions in the prefill call (512 tokens each)")
+    ap.add_argument("--weight-std", type=float, default=0.02,
+                    help="standard deviation of the synthetic weights (0.02 is the recipe; smaller weights give "
+                         "smaller activations and so fewer outlier columns in calls of many rows)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy, the known-size kernel that scales rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters")
@@ -92,7 +113,7 @@ def main():
     span = binding.Span(NB, H, nh, F, 1, 1e-5, 6.0, dev)
     block0_host = None
     for b in range(NB):
-        p = synth.block_params_device(cfg, b, dev)
+        p = _block_params(args, cfg, b, dev)
         span.load_block(b, p)
         if b == 0 and not args.no_cpu_baseline:
             block0_host = {k: v.cpu().numpy() for k, v in p.items()}
@@ -186,7 +207,7 @@ def main():
         "roofline": roofline, "cpu_baseline": cpu_baseline,
     }
     span.close()
-    print(json.dumps(line))
+    _emit(args, line)
 
 
 def prefill_main(args, dev):
@@ -207,7 +228,7 @@ def prefill_main(args, dev):
     K_steps, W = max(1, min(args.steps, 4)), max(1, min(args.warmup, 1))
     span = binding.Span(NB, H, nh, F, M, 1e-5, 6.0, dev)
     for b in range(NB):
-        span.load_block(b, synth.block_params_device(cfg, b, dev))
+        span.load_block(b, _block_params(args, cfg, b, dev))
     X = torch.from_numpy(synth.hidden_states(cfg, 0, B, T)).to(dev)
     out = torch.empty_like(X)
     kv = [torch.zeros(binding.petals_span_kv_bytes(span.cfg, T), dtype=torch.uint8, device=dev) for _ in range(B)]
@@ -257,7 +278,7 @@ def prefill_main(args, dev):
         "cpu_baseline": None,
     }
     span.close()
-    print(json.dumps(line))
+    _emit(args, line)
 
 
 def backward_main(args, dev):
@@ -275,7 +296,7 @@ def backward_main(args, dev):
     K_steps, W = max(1, min(args.steps, 3)), max(1, min(args.warmup, 1))
     span = binding.Span(NB, H, nh, F, M, 1e-5, 6.0, dev)
     for b in range(NB):
-        span.load_block(b, synth.block_params_device(cfg, b, dev))
+        span.load_block(b, _block_params(args, cfg, b, dev))
     X = torch.from_numpy(synth.hidden_states(cfg, 0, B, T)).to(dev)
     g = torch.Generator(device=dev)
     g.manual_seed(1234)
@@ -330,7 +351,7 @@ def backward_main(args, dev):
         "cpu_baseline": None,
     }
     span.close()
-    print(json.dumps(line))
+    _emit(args, line)
 
 
 def batched_main(args, dev):
@@ -356,7 +377,7 @@ def batched_main(args, dev):
     chunk = max(1, min(B, 4096 // T))                      # sessions per prefill call
     span = binding.Span(NB, H, nh, F, max(B, chunk * T), 1e-5, 6.0, dev)
     for b in range(NB):
-        span.load_block(b, synth.block_params_device(cfg, b, dev))
+        span.load_block(b, _block_params(args, cfg, b, dev))
     ses = [span.open_session(T + W + K + 1) for _ in range(B)]
     Xp = synth.hidden_states(cfg, 0, B, T)
     for s0 in range(0, B, chunk):
@@ -428,7 +449,7 @@ def batched_main(args, dev):
         "cpu_baseline": None,
     }
     span.close()
-    print(json.dumps(line))
+    _emit(args, line)
 
 
 def c5_main(args, dev):
@@ -452,7 +473,7 @@ def c5_main(args, dev):
     for n in sizes:
         sp = binding.Span(n, H, nh, F, chunk * T, 1e-5, 6.0, dev, workspace=shared_ws)
         for b in range(n):
-            p = synth.block_params_device(cfg, blk, dev)
+            p = _block_params(args, cfg, blk, dev)
             sp.load_block(b, p)
             del p
             blk += 1
@@ -539,7 +560,7 @@ def c5_main(args, dev):
     }
     for sp in spans:
         sp.close()
-    print(json.dumps(line))
+    _emit(args, line)
 
 
 def generate_main(args, dev):
@@ -556,7 +577,7 @@ def generate_main(args, dev):
     K, W, L = args.steps, args.warmup, args.prefix
     span = binding.Span(NB, H, nh, F, 1, 1e-5, 6.0, dev)
     for b in range(NB):
-        span.load_block(b, synth.block_params_device(cfg, b, dev))
+        span.load_block(b, _block_params(args, cfg, b, dev))
     g = torch.Generator(device=dev)
     g.manual_seed(1234)
     E = torch.empty((V, H), dtype=torch.float16, device=dev)
@@ -630,7 +651,7 @@ def generate_main(args, dev):
     }
     cl.close()
     span.close()
-    print(json.dumps(line))
+    _emit(args, line)
 
 
 def run_cpu_baseline(cfg, block0_host, dev, prefix=2048, budget_s=12.0):
