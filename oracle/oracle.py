@@ -11,7 +11,7 @@ from .build_oracle import LIB, build
 
 __all__ = ["f16_to_f64", "f64_to_f16", "quantize_weight", "layernorm", "gelu", "linear",
            "alibi_slopes", "attention", "Span", "Session", "codebook", "hidden_quantize",
-           "hidden_dequantize", "num_threads", "embed", "lm_head", "EPI_NONE", "EPI_GELU", "EPI_RESIDUAL"]
+           "hidden_dequantize", "num_threads", "embed", "lm_head", "sample", "EPI_NONE", "EPI_GELU", "EPI_RESIDUAL"]
 
 EPI_NONE, EPI_GELU, EPI_RESIDUAL = 0, 1, 2
 
@@ -130,6 +130,17 @@ def lm_head(x, E, g, b, eps=1e-5, want_logits=False):
     lib().orc_lm_head(_p(x), C.c_int(M), _p(E), C.c_int(V), C.c_int(H), _p(g), _p(b), C.c_double(eps),
                       _p(logits), _p(nxt))
     return (nxt, logits) if want_logits else nxt
+
+
+def sample(logits, temperature, top_k, u):
+    """Next tokens int32 [M] from fp32 logits [M, V] by temperature / top-k sampling with the uniforms u [M]."""
+    logits = np.ascontiguousarray(logits, np.float32)
+    u = np.ascontiguousarray(u, np.float32)
+    M, V = logits.shape
+    assert u.shape == (M,) and (u >= 0).all() and (u < 1).all()
+    nxt = np.empty(M, np.int32)
+    lib().orc_sample(_p(logits), C.c_int(M), C.c_int(V), C.c_float(temperature), C.c_int(top_k), _p(u), _p(nxt))
+    return nxt
 
 
 def alibi_slopes(nh):

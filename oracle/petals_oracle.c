@@ -555,6 +555,71 @@ void orc_lm_head(const uint16_t *x, int M, const uint16_t *E, int V, int H,
     free(a); free(ad); free(row);
 }
 
+/*
+ * Choice of the next token from the logits (Figure 2: the client samples the
+ * next token from what the LM head returns; the paper names no method).
+ * Reading: temperature and top-k sampling by inversion.  temperature == 0 is
+ * the greedy choice (first index of the largest logit).  Otherwise the k
+ * largest logits stay in play (equal logits: lower index first; k <= 0 or
+ * k >= V: all of them), p_v = exp((l_v - l_max) / temperature) in fp64,
+ * S = sum of p_v in index order, and the answer is the first index in play
+ * whose running sum of p exceeds u * S, for the caller's uniform u in [0, 1)
+ * (the last index in play if rounding lets none exceed it).
+ * logits [M][V] fp32, u [M] fp32, next [M].
+ */
+typedef struct { float l; int32_t v; } orc_lv;
+
+static int cmp_lv(const void *a, const void *b)
+{
+    const orc_lv *x = (const orc_lv *)a, *y = (const orc_lv *)b;
+    if (x->l != y->l) return x->l > y->l ? -1 : 1;
+    return (x->v > y->v) - (x->v < y->v);
+}
+
+void orc_sample(const float *logits, int M, int V, float temperature, int top_k,
+                const float *u, int32_t *next)
+{
+    orc_lv *order = (orc_lv *)malloc((size_t)V * sizeof(orc_lv));
+    unsigned char *play = (unsigned char *)malloc((size_t)V);
+    double *p = (double *)malloc((size_t)V * 8);
+    for (int t = 0; t < M; t++) {
+        const float *l = logits + (size_t)t * V;
+        int best = 0;
+        for (int v = 1; v < V; v++)
+            if (l[v] > l[best]) best = v;
+        if (temperature == 0.0f) { next[t] = best; continue; }
+        if (top_k <= 0 || top_k >= V) {
+            memset(play, 1, (size_t)V);
+        } else {
+            for (int v = 0; v < V; v++) { order[v].l = l[v]; order[v].v = v; }
+            qsort(order, (size_t)V, sizeof(orc_lv), cmp_lv);
+            memset(play, 0, (size_t)V);
+            for (int i = 0; i < top_k; i++) play[order[i].v] = 1;
+        }
+        double S = 0.0;
+        for (int v = 0; v < V; v++) {
+            p[v] = play[v] ? exp(((double)l[v] - (double)l[best]) / (double)temperature) : 0.0;
+            S += p[v];
+        }
+        const double target = (double)u[t] * S;
+        double c = 0.0;
+        int pick = -1, last = -1;
+        for (int v = 0; v < V && pick < 0; v++) {
+            if (!play[v]) continue;
+            last = v;
+            c += p[v];
+            if (c > target) pick = v;
+        }
+        if (pick < 0) {
+            for (int v = V - 1; v > last; v--)
+                if (play[v]) { last = v; break; }
+            pick = last;
+        }
+        next[t] = pick;
+    }
+    free(order); free(play); free(p);
+}
+
 /* ---------------------------------------------------------------- codec */
 
 /*
