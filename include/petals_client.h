@@ -74,6 +74,24 @@ int petals_client_embed(petals_client *client, const int32_t *token_ids, int32_t
 int petals_client_lm_head(petals_client *client, const void *hidden_in, int32_t M,
                           float *logits_out, int32_t *next_token_out, void *stream);
 
+/*
+ * Choice of the next token from logits (Figure 2: the client samples the next token from the
+ * LM head's output; the paper names no method - this is temperature / top-k sampling by
+ * inversion with the CALLER's random numbers, so that a run can be repeated).
+ *   logits    dev fp32 [M, V] (finite), e.g. logits_out of petals_client_lm_head
+ *   uniforms  dev fp32 [M], each in [0, 1)
+ *   next_token_out dev int32 [M]
+ * temperature == 0, or top_k == 1: the first index of the largest logit.  Otherwise the top_k
+ * largest logits of a row stay in play (equal logits: lower index first; top_k <= 0 or >= V:
+ * all), p_v = exp((l_v - l_max) / temperature) in fp64, and the answer is the first index in
+ * play whose running sum of p, taken in index order, exceeds uniforms[t] * (sum of all p in
+ * play); the last index in play if rounding lets none exceed it.  temperature < 0 or NaN ->
+ * PETALS_ERR_INVALID_ARG.  Needs no workspace; one workgroup per row.
+ */
+int petals_client_sample(petals_client *client, const float *logits, int32_t M, float temperature,
+                         int32_t top_k, const float *uniforms, int32_t *next_token_out,
+                         void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -60,7 +60,7 @@ EXPORTS = ["petals_span_weight_bytes", "petals_span_workspace_bytes", "petals_sp
            "petals_span_backward_bytes", "petals_span_backward", "petals_debug_backward_product",
            "petals_span_backward_cache_bytes", "petals_span_backward_attach_cache"]
 CLIENT_EXPORTS = ["petals_client_workspace_bytes", "petals_client_create", "petals_client_destroy",
-                  "petals_client_embed", "petals_client_lm_head"]
+                  "petals_client_embed", "petals_client_lm_head", "petals_client_sample"]
 PROFILE_GEMV, PROFILE_GEMM, PROFILE_ATTENTION, PROFILE_LINEAR0 = 0, 1, 2, 3
 PROFILE_BWD_GEMM, PROFILE_BWD_ATTENTION, PROFILE_CLASSES = 7, 8, 9
 
@@ -410,6 +410,11 @@ def petals_client_lm_head(client, hidden_in, logits_out, next_token_out):
                                        _ptr(next_token_out), _stream()))
 
 
+def petals_client_sample(client, logits, temperature, top_k, uniforms, next_token_out):
+    _check(lib().petals_client_sample(client, _ptr(logits), C.c_int32(logits.shape[0]), C.c_float(temperature),
+                                      C.c_int32(top_k), _ptr(uniforms), _ptr(next_token_out), _stream()))
+
+
 class Client:
     """Embedding lookup and LM head over one fp16 embedding matrix that stays where the caller put it."""
 
@@ -435,6 +440,14 @@ class Client:
         nxt = torch.empty(M, dtype=torch.int32, device=self.device) if next_out is None else next_out
         petals_client_lm_head(self.handle, hidden.contiguous(), logits, nxt)
         return (nxt, logits) if want_logits else nxt
+
+    def sample(self, logits, temperature, top_k, uniforms, next_out=None):
+        """Next tokens int32 [M] from fp32 logits [M, V] with the caller's uniforms fp32 [M] in [0, 1)."""
+        assert logits.dtype == torch.float32 and logits.shape[1] == self.vocab and logits.is_contiguous()
+        assert uniforms.dtype == torch.float32 and uniforms.shape == (logits.shape[0],)
+        nxt = torch.empty(logits.shape[0], dtype=torch.int32, device=self.device) if next_out is None else next_out
+        petals_client_sample(self.handle, logits, temperature, top_k, uniforms, nxt)
+        return nxt
 
     def close(self):
         if self.handle is not None:

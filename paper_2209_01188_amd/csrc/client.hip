@@ -214,6 +214,214 @@ int rows_per_pass(int H) {
 
 }  // namespace
 
+// ------------------------------------------------------------------------------------------------
+// Choice of the next token by temperature / top-k sampling with the caller's uniform numbers.
+// One workgroup of 16 waves per row of logits.  Wave w owns the contiguous indices [w Cw, (w+1) Cw); in
+// iteration j its lanes read 4 x 64 consecutive floats (index = start + 256 j + 64 e + lane, e = 0..3), so every
+// load instruction is 256 contiguous bytes and "index order" is the order (wave, j, e, lane).  Whatever depends
+// on that order (which of several equal logits at the top-k boundary stay in play; whose running sum first
+// exceeds the target) is resolved level by level: waves, then iterations of one wave, then the 256 elements of
+// one iteration, with ballots and ordered scans.
+namespace {
+
+// unsigned keys that order like the floats they come from (-0 counts as +0)
+__device__ __forceinline__ uint32_t order_key(float f) {
+    const uint32_t u = __float_as_uint(f + 0.0f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__device__ __forceinline__ double wave_scan_incl(double v, int lane) {
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const double o = __shfl_up(v, off);
+        if (lane >= off) v += o;
+    }
+    return v;
+}
+
+__global__ void __launch_bounds__(1024) k_sample(const float *__restrict__ logits, int V, float temperature, int top_k,
+                                                 const float *__restrict__ uni, int32_t *__restrict__ next) {
+    __shared__ uint32_t s_key[16];
+    __shared__ int s_idx[16], s_eq[16], hist[256];
+    __shared__ double s_sum[16];
+    __shared__ uint32_t sh_prefix;
+    __shared__ int sh_need;
+    const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const float *l = logits + (size_t)row * V;
+    const int Cw = (((V + 15) / 16) + 255) / 256 * 256;
+    const int seg0 = min(V, wave * Cw), seg1 = min(V, seg0 + Cw), nit = (seg1 - seg0 + 255) / 256;
+    const unsigned long long lt = (1ull << lane) - 1ull;               // lanes below this one
+
+    // 1. the largest logit, lowest index first (a thread meets its indices in ascending order)
+    uint32_t bk = 0;
+    int bi = 0x7fffffff;
+    for (int j0 = 0; j0 < nit; j0 += 4) {                 // 16 loads in flight: the pass is bound by their latency
+        float f[16];
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+            const int v = seg0 + j0 * 256 + i * 64 + lane;
+            f[i] = v < seg1 ? l[v] : -INFINITY;
+        }
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+            const int v = seg0 + j0 * 256 + i * 64 + lane;
+            const uint32_t k = order_key(f[i]);
+            if (v < seg1 && k > bk) { bk = k; bi = v; }
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const uint32_t k2 = (uint32_t)__shfl_xor((int)bk, off);
+        const int i2 = __shfl_xor(bi, off);
+        if (k2 > bk || (k2 == bk && i2 < bi)) { bk = k2; bi = i2; }
+    }
+    if (lane == 0) { s_key[wave] = bk; s_idx[wave] = bi; }
+    __syncthreads();
+    bk = s_key[0]; bi = s_idx[0];
+    for (int w = 1; w < 16; w++)
+        if (s_key[w] > bk || (s_key[w] == bk && s_idx[w] < bi)) { bk = s_key[w]; bi = s_idx[w]; }
+    const int best = bi;
+    if (temperature == 0.0f || top_k == 1) {               // the greedy choice (uniform over the workgroup)
+        if (tid == 0) next[row] = best;
+        return;
+    }
+
+    // 2. key of the top_k-th largest logit by a radix select over the four bytes of the keys
+    const bool all = top_k <= 0 || top_k >= V;
+    uint32_t thr = 0;
+    int need_eq = 0;                                        // in play: key > thr, and the first need_eq with key == thr
+    if (!all) {
+        uint32_t prefix = 0;
+        int remaining = top_k;
+        for (int pass = 3; pass >= 0; pass--) {
+            for (int i = tid; i < 256; i += 1024) hist[i] = 0;
+            __syncthreads();
+            const int shift = pass * 8;
+            for (int j = 0; j < nit; j++)
+#pragma unroll
+                for (int e = 0; e < 4; e++) {
+                    const int v = seg0 + j * 256 + e * 64 + lane;
+                    bool in = v < seg1;
+                    uint32_t k = 0;
+                    if (in) {
+                        k = order_key(l[v]);
+                        in = pass == 3 || (k >> (shift + 8)) == prefix;
+                    }
+                    // lanes of a wave that hit the same bin add once: the high bytes of logits crowd a few bins
+                    uint32_t bin = (k >> shift) & 255u;
+                    unsigned long long todo = __ballot(in);
+                    while (todo) {
+                        const int first = __ffsll((long long)todo) - 1;
+                        const uint32_t b0 = (uint32_t)__shfl((int)bin, first);
+                        const unsigned long long same = __ballot(in && bin == b0);
+                        if (lane == first) atomicAdd(&hist[b0], __popcll(same));
+                        todo &= ~same;
+                    }
+                }
+            __syncthreads();
+            if (tid == 0) {
+                int cum = 0, b = 255;
+                for (; b > 0; b--) {
+                    if (cum + hist[b] >= remaining) break;
+                    cum += hist[b];
+                }
+                sh_prefix = (prefix << 8) | (uint32_t)b;
+                sh_need = remaining - cum;
+            }
+            __syncthreads();
+            prefix = sh_prefix;
+            remaining = sh_need;
+        }
+        thr = prefix;
+        need_eq = remaining;
+    }
+
+    // 3. one pass: per wave the number of logits equal to the threshold and the sum of
+    //    p = exp((l - l_max) / temperature) over its logits in play, given how many equal ones precede the wave.
+    //    The count comes first (its own pass) because the sum needs it.
+    int eq_wave = 0;
+    if (!all) {
+        for (int j = 0; j < nit; j++)
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                const int v = seg0 + j * 256 + e * 64 + lane;
+                eq_wave += __popcll(__ballot(v < seg1 && order_key(l[v]) == thr));
+            }
+        if (lane == 0) s_eq[wave] = eq_wave;
+        __syncthreads();
+    }
+    int eq_before_wave = 0;
+    if (!all)
+        for (int w = 0; w < wave; w++) eq_before_wave += s_eq[w];
+
+    const double Td = (double)temperature, lm = (double)l[best];
+    // p of the element (j, e) of this lane, 0 if it is not in play; eq_seen = equal ones before iteration j's
+    // element group e in this wave (updated here)
+    auto weight = [&](int j, int e, int &eq_seen) -> double {
+        const int v = seg0 + j * 256 + e * 64 + lane;
+        const bool valid = v < seg1;
+        const float lv = valid ? l[v] : 0.0f;
+        bool keep = valid;
+        if (!all) {
+            const uint32_t k = order_key(lv);
+            const bool eq = valid && k == thr;
+            const unsigned long long m = __ballot(eq);
+            keep = valid && (k > thr || (eq && eq_seen + __popcll(m & lt) < need_eq));
+            eq_seen += __popcll(m);
+        }
+        return keep ? exp(((double)lv - lm) / Td) : 0.0;
+    };
+    double sum = 0.0;
+    {
+        int eq_seen = eq_before_wave;
+        for (int j = 0; j < nit; j++)
+#pragma unroll
+            for (int e = 0; e < 4; e++) sum += weight(j, e, eq_seen);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+    if (lane == 0) s_sum[wave] = sum;
+    __syncthreads();
+    double total = 0.0;
+    for (int w = 0; w < 16; w++) total += s_sum[w];
+    const double target = (double)uni[row] * total;
+
+    // 4. the wave whose segment holds the target (the last wave with anything in play if rounding leaves none)
+    int wstar = -1, wlast = -1;
+    double before = 0.0;
+    {
+        double c = 0.0;
+        for (int w = 0; w < 16; w++) {
+            if (s_sum[w] > 0.0) wlast = w;
+            if (wstar < 0 && s_sum[w] > 0.0 && c + s_sum[w] > target) { wstar = w; before = c; }
+            if (wstar < 0) c += s_sum[w];
+        }
+        if (wstar < 0) { wstar = wlast; before = c - (wlast >= 0 ? s_sum[wlast] : 0.0); }
+    }
+    if (wave != wstar) return;                              // whole waves leave; no barrier follows
+
+    // 5. inside that wave: walk the iterations, then the four groups of the iteration, then the lanes
+    int eq_seen = eq_before_wave, pick = -1, last_in_play = -1;
+    double c = before;
+    for (int j = 0; j < nit && pick < 0; j++) {
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            if (pick >= 0) break;
+            const double p = weight(j, e, eq_seen);
+            const unsigned long long has = __ballot(p > 0.0);
+            if (!has) continue;
+            last_in_play = seg0 + j * 256 + e * 64 + (63 - __clzll((long long)has));
+            const double incl = wave_scan_incl(p, lane);
+            const unsigned long long over = __ballot(p > 0.0 && c + incl > target);
+            if (over) pick = seg0 + j * 256 + e * 64 + (__ffsll((long long)over) - 1);
+            c += __shfl(incl, 63);
+        }
+    }
+    if (lane == 0) next[row] = pick >= 0 ? pick : last_in_play;
+}
+
+}  // namespace
+
 struct petals_client {
     petals_client_config cfg;
     petals_client_params p;
@@ -334,6 +542,16 @@ int petals_client_lm_head(petals_client *c, const void *hidden_in, int32_t M, fl
             HIP_TRY(hipGetLastError());
         }
     }
+    return PETALS_OK;
+}
+
+int petals_client_sample(petals_client *c, const float *logits, int32_t M, float temperature, int32_t top_k,
+                         const float *uniforms, int32_t *next_token_out, void *stream) {
+    if (!c || !logits || !uniforms || !next_token_out) return ps_fail(PETALS_ERR_INVALID_ARG, "null pointer");
+    if (M < 1) return ps_fail(PETALS_ERR_INVALID_ARG, "M must be positive");
+    if (!(temperature >= 0.0f)) return ps_fail(PETALS_ERR_INVALID_ARG, "temperature must be zero (greedy) or positive");
+    k_sample<<<M, 1024, 0, (hipStream_t)stream>>>(logits, c->cfg.vocab, temperature, top_k, uniforms, next_token_out);
+    HIP_TRY(hipGetLastError());
     return PETALS_OK;
 }
 

@@ -32,7 +32,7 @@ def test_library_exports_every_symbol_of_the_client_header(b):
     header = open(os.path.join(ROOT, "include", "petals_client.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b(petals_[a-z0-9_]+)\s*\(", header))
-    assert len(declared) == 5
+    assert len(declared) == 6
     L = b.lib()
     for name in declared:
         assert hasattr(L, name), name

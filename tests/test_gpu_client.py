@@ -1,5 +1,5 @@
 """GPU parity of the client-side ends of a generation step (embedding lookup + LayerNorm, final LayerNorm +
-tied LM head + greedy choice) against the CPU oracle, through the C ABI."""
+tied LM head + greedy choice, temperature / top-k sampling) against the CPU oracle, through the C ABI."""
 import numpy as np
 import pytest
 import torch
@@ -110,3 +110,54 @@ def test_greedy_generation_loop_stays_on_the_device_and_matches_the_oracle():
         cl.lm_head(yg, next_out=out[i:i + 1])
     assert out.cpu().tolist() == ref
     cl.close(); gsp.close(); osp.destroy()
+
+
+# ------------------------------------------------------------------ choice of the next token (Figure 2)
+
+def _client(V, H=64):
+    _, E, lg = _model(V, V, H)
+    return binding.Client(to_dev(E), *[to_dev(t) for t in lg], max_rows=4)
+
+
+@pytest.mark.parametrize("V", [8, 1000, 1024, 1025, 50257, 250880])
+@pytest.mark.parametrize("temperature,top_k", [(0.0, 0), (1.0, 0), (0.7, 1), (0.7, 5), (1.3, 50), (2.5, 1000), (0.25, 0),
+                                               (1.0, -3), (1.0, 10 ** 9)])
+def test_sampling_picks_the_oracles_token(V, temperature, top_k):
+    """Logits with the spread of an LM head's, rounded to a coarse grid so that equal logits (also at the top-k
+    boundary) are common; uniforms including 0 and the largest float below 1."""
+    r = np.random.default_rng(V + 31 * top_k % 1000)
+    M = 24
+    logits = (np.round(r.standard_normal((M, V)) * 3.0 * 8) / 8).astype(np.float32)
+    logits[1] = 0.0                                           # all equal
+    logits[2, : V // 2] = -0.0                                # signed zeros are one value
+    logits[3] = np.sort(logits[3])[::-1]                      # the head of the row in play
+    logits[4] = np.sort(logits[4])                            # the tail
+    u = r.random(M).astype(np.float32)
+    u[0], u[5] = 0.0, np.float32(0.99999994)
+    cl = _client(V)
+    try:
+        got = cl.sample(to_dev(logits), temperature, top_k, to_dev(u))
+        torch.cuda.synchronize()
+        want = oracle.sample(logits, temperature, top_k, u)
+        assert np.array_equal(got.cpu().numpy(), want), np.flatnonzero(got.cpu().numpy() != want)[:5]
+    finally:
+        cl.close()
+
+
+def test_sampling_on_the_lm_heads_own_logits_and_its_argument_checks():
+    V, H, M = 3001, 256, 4
+    r, E, lg = _model(9, V, H)
+    cl = binding.Client(to_dev(E), *[to_dev(t) for t in lg], max_rows=M)
+    try:
+        x = to_dev(h(r.standard_normal((M, H))))
+        nxt, logits = cl.lm_head(x, want_logits=True)
+        u = to_dev(r.random(M).astype(np.float32))
+        assert torch.equal(cl.sample(logits, 0.0, 0, u), nxt)               # temperature 0 is the head's greedy choice
+        got = cl.sample(logits, 0.9, 40, u)
+        want = oracle.sample(logits.cpu().numpy(), 0.9, 40, u.cpu().numpy())
+        assert np.array_equal(got.cpu().numpy(), want)
+        for bad in (-1.0, float("nan")):
+            with pytest.raises(binding.PetalsError):
+                cl.sample(logits, bad, 0, u)
+    finally:
+        cl.close()
