@@ -420,6 +420,156 @@ __global__ void __launch_bounds__(1024) k_sample(const float *__restrict__ logit
     if (lane == 0) next[row] = pick >= 0 ? pick : last_in_play;
 }
 
+// The same choice with a row spread over many workgroups, for the two cases that need no top-k selection (greedy;
+// all tokens in play): segments of SAMPLE_SEG consecutive logits, one workgroup each.
+//   k_sample_segmax   largest logit of every segment (lowest index first)
+//   k_sample_segsum   every workgroup reduces those to the row's largest logit, then sums p over its segment
+//   k_sample_pick     one wave per row: greedy answer, or the segment that holds the target and the walk through it
+constexpr int SAMPLE_SEG = 4096;
+struct SegStat {
+    uint32_t key;
+    int idx;
+    double sum;
+};
+
+// (key, index) of the best of the workgroup's candidates, lowest index among equal keys; all threads get it
+template <int NWV>
+__device__ __forceinline__ void block_best(uint32_t &bk, int &bi, uint32_t *s_key, int *s_idx) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const uint32_t k2 = (uint32_t)__shfl_xor((int)bk, off);
+        const int i2 = __shfl_xor(bi, off);
+        if (k2 > bk || (k2 == bk && i2 < bi)) { bk = k2; bi = i2; }
+    }
+    if (lane == 0) { s_key[wave] = bk; s_idx[wave] = bi; }
+    __syncthreads();
+    bk = s_key[0]; bi = s_idx[0];
+#pragma unroll
+    for (int w = 1; w < NWV; w++)
+        if (s_key[w] > bk || (s_key[w] == bk && s_idx[w] < bi)) { bk = s_key[w]; bi = s_idx[w]; }
+    __syncthreads();
+}
+
+__global__ void __launch_bounds__(256) k_sample_segmax(const float *__restrict__ logits, int V, SegStat *__restrict__ st) {
+    __shared__ uint32_t s_key[4];
+    __shared__ int s_idx[4];
+    const int g = blockIdx.x, row = blockIdx.y, G = gridDim.x;
+    const float *l = logits + (size_t)row * V;
+    const int base = g * SAMPLE_SEG, end = min(V, base + SAMPLE_SEG);
+    float f[SAMPLE_SEG / 256];
+#pragma unroll
+    for (int i = 0; i < SAMPLE_SEG / 256; i++) {
+        const int v = base + i * 256 + threadIdx.x;
+        f[i] = v < end ? l[v] : -INFINITY;
+    }
+    uint32_t bk = 0;
+    int bi = 0x7fffffff;
+#pragma unroll
+    for (int i = 0; i < SAMPLE_SEG / 256; i++) {
+        const int v = base + i * 256 + threadIdx.x;
+        const uint32_t k = order_key(f[i]);
+        if (v < end && k > bk) { bk = k; bi = v; }
+    }
+    block_best<4>(bk, bi, s_key, s_idx);
+    if (threadIdx.x == 0) { st[(size_t)row * G + g].key = bk; st[(size_t)row * G + g].idx = bi; }
+}
+
+// the row's best (key, index) from the G segment results; all threads of the workgroup get it
+template <int NWV>
+__device__ __forceinline__ void row_best(const SegStat *__restrict__ st, int G, uint32_t &bk, int &bi, uint32_t *s_key,
+                                         int *s_idx) {
+    bk = 0;
+    bi = 0x7fffffff;
+    for (int i = threadIdx.x; i < G; i += 64 * NWV) {
+        const uint32_t k = st[i].key;
+        const int v = st[i].idx;
+        if (k > bk || (k == bk && v < bi)) { bk = k; bi = v; }
+    }
+    block_best<NWV>(bk, bi, s_key, s_idx);
+}
+
+__global__ void __launch_bounds__(256) k_sample_segsum(const float *__restrict__ logits, int V, float temperature,
+                                                        SegStat *__restrict__ st) {
+    __shared__ uint32_t s_key[4];
+    __shared__ int s_idx[4];
+    __shared__ double s_sum[4];
+    const int g = blockIdx.x, row = blockIdx.y, G = gridDim.x;
+    const float *l = logits + (size_t)row * V;
+    uint32_t bk;
+    int bi;
+    row_best<4>(st + (size_t)row * G, G, bk, bi, s_key, s_idx);
+    const double lm = (double)l[bi], Td = (double)temperature;
+    const int base = g * SAMPLE_SEG, end = min(V, base + SAMPLE_SEG);
+    double sum = 0.0;
+#pragma unroll
+    for (int i = 0; i < SAMPLE_SEG / 256; i++) {
+        const int v = base + i * 256 + threadIdx.x;
+        if (v < end) sum += exp(((double)l[v] - lm) / Td);
+    }
+    sum = wave_sum(sum);
+    if ((threadIdx.x & 63) == 0) s_sum[threadIdx.x >> 6] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) st[(size_t)row * G + g].sum = (s_sum[0] + s_sum[1]) + (s_sum[2] + s_sum[3]);
+}
+
+__global__ void __launch_bounds__(64) k_sample_pick(const float *__restrict__ logits, int V, float temperature, int G,
+                                                    const SegStat *__restrict__ st_all, const float *__restrict__ uni,
+                                                    int32_t *__restrict__ next) {
+    __shared__ uint32_t s_key[1];
+    __shared__ int s_idx[1];
+    const int row = blockIdx.x, lane = threadIdx.x;
+    const float *l = logits + (size_t)row * V;
+    const SegStat *st = st_all + (size_t)row * G;
+    uint32_t bk;
+    int bi;
+    row_best<1>(st, G, bk, bi, s_key, s_idx);
+    if (temperature == 0.0f) {
+        if (lane == 0) next[row] = bi;
+        return;
+    }
+    // running sum over the segments in order, 64 at a time
+    double total = 0.0;
+    for (int g0 = 0; g0 < G; g0 += 64) {
+        const double v = g0 + lane < G ? st[g0 + lane].sum : 0.0;
+        total += __shfl(wave_scan_incl(v, lane), 63);
+    }
+    const double target = (double)uni[row] * total;
+    int gstar = -1, glast = -1;
+    double before = 0.0, c = 0.0;
+    for (int g0 = 0; g0 < G && gstar < 0; g0 += 64) {
+        const double v = g0 + lane < G ? st[g0 + lane].sum : 0.0;
+        const double incl = wave_scan_incl(v, lane);
+        const unsigned long long has = __ballot(v > 0.0);
+        if (has) glast = g0 + 63 - __clzll((long long)has);
+        const unsigned long long over = __ballot(v > 0.0 && c + incl > target);
+        if (over) {
+            const int k = __ffsll((long long)over) - 1;
+            gstar = g0 + k;
+            before = c + __shfl(incl - v, k);
+        }
+        c += __shfl(incl, 63);
+    }
+    if (gstar < 0) {                                        // rounding left no segment above the target: the last one
+        gstar = glast;
+        before = total - st[glast].sum;
+    }
+    // walk the segment in index order: 16 iterations of 4 groups of 64 consecutive logits
+    const double lm = (double)l[bi], Td = (double)temperature;
+    const int base = gstar * SAMPLE_SEG, end = min(V, base + SAMPLE_SEG);
+    int pick = -1;
+    c = before;
+    for (int v0 = base; v0 < end && pick < 0; v0 += 64) {
+        const int v = v0 + lane;
+        const double p = v < end ? exp(((double)l[v] - lm) / Td) : 0.0;
+        const double incl = wave_scan_incl(p, lane);
+        const unsigned long long over = __ballot(v < end && c + incl > target);
+        if (over) pick = v0 + __ffsll((long long)over) - 1;
+        c += __shfl(incl, 63);
+    }
+    if (lane == 0) next[row] = pick >= 0 ? pick : end - 1;
+}
+
 }  // namespace
 
 struct petals_client {
@@ -427,6 +577,7 @@ struct petals_client {
     petals_client_params p;
     __half *a;          // LayerNorm output of the rows of one lm_head call
     Best *partial;      // [LM_MAX_ROWS][LM_GROUPS]
+    SegStat *seg;       // [max_rows_per_call][segments of the vocabulary]: per-segment results of the sampler
     bool lds_attr_set[3];
 };
 
@@ -446,7 +597,8 @@ extern "C" {
 int petals_client_workspace_bytes(const petals_client_config *cfg, size_t *bytes) {
     if (!bytes) return ps_fail(PETALS_ERR_INVALID_ARG, "null pointer");
     if (int rc = check_client_config(cfg)) return rc;
-    *bytes = align_up((size_t)cfg->max_rows_per_call * cfg->hidden * 2) + align_up(sizeof(Best) * LM_MAX_ROWS * LM_GROUPS);
+    *bytes = align_up((size_t)cfg->max_rows_per_call * cfg->hidden * 2) + align_up(sizeof(Best) * LM_MAX_ROWS * LM_GROUPS) +
+             align_up(sizeof(SegStat) * (size_t)cfg->max_rows_per_call * ((cfg->vocab + SAMPLE_SEG - 1) / SAMPLE_SEG));
     return PETALS_OK;
 }
 
@@ -464,6 +616,7 @@ int petals_client_create(const petals_client_config *cfg, const petals_client_pa
     c->p = *params;
     c->a = (__half *)dev_workspace;
     c->partial = (Best *)((uint8_t *)dev_workspace + align_up((size_t)cfg->max_rows_per_call * cfg->hidden * 2));
+    c->seg = (SegStat *)((uint8_t *)c->partial + align_up(sizeof(Best) * LM_MAX_ROWS * LM_GROUPS));
     c->lds_attr_set[0] = c->lds_attr_set[1] = c->lds_attr_set[2] = false;
     *out = c;
     return PETALS_OK;
@@ -550,7 +703,17 @@ int petals_client_sample(petals_client *c, const float *logits, int32_t M, float
     if (!c || !logits || !uniforms || !next_token_out) return ps_fail(PETALS_ERR_INVALID_ARG, "null pointer");
     if (M < 1) return ps_fail(PETALS_ERR_INVALID_ARG, "M must be positive");
     if (!(temperature >= 0.0f)) return ps_fail(PETALS_ERR_INVALID_ARG, "temperature must be zero (greedy) or positive");
-    k_sample<<<M, 1024, 0, (hipStream_t)stream>>>(logits, c->cfg.vocab, temperature, top_k, uniforms, next_token_out);
+    hipStream_t st = (hipStream_t)stream;
+    const int V = c->cfg.vocab, G = (V + SAMPLE_SEG - 1) / SAMPLE_SEG;
+    const bool greedy = temperature == 0.0f || top_k == 1, all = top_k <= 0 || top_k >= V;
+    if ((greedy || all) && M <= c->cfg.max_rows_per_call && M <= 65535) {
+        // no top-k selection: the row is spread over G workgroups (per-segment results in the workspace)
+        k_sample_segmax<<<dim3(G, M), 256, 0, st>>>(logits, V, c->seg);
+        if (!greedy) k_sample_segsum<<<dim3(G, M), 256, 0, st>>>(logits, V, temperature, c->seg);
+        k_sample_pick<<<M, 64, 0, st>>>(logits, V, greedy ? 0.0f : temperature, G, c->seg, uniforms, next_token_out);
+    } else {
+        k_sample<<<M, 1024, 0, st>>>(logits, V, temperature, top_k, uniforms, next_token_out);
+    }
     HIP_TRY(hipGetLastError());
     return PETALS_OK;
 }

@@ -114,9 +114,9 @@ def test_greedy_generation_loop_stays_on_the_device_and_matches_the_oracle():
 
 # ------------------------------------------------------------------ choice of the next token (Figure 2)
 
-def _client(V, H=64):
+def _client(V, H=64, max_rows=24):
     _, E, lg = _model(V, V, H)
-    return binding.Client(to_dev(E), *[to_dev(t) for t in lg], max_rows=4)
+    return binding.Client(to_dev(E), *[to_dev(t) for t in lg], max_rows=max_rows)
 
 
 @pytest.mark.parametrize("V", [8, 1000, 1024, 1025, 50257, 250880])
@@ -142,6 +142,24 @@ def test_sampling_picks_the_oracles_token(V, temperature, top_k):
         assert np.array_equal(got.cpu().numpy(), want), np.flatnonzero(got.cpu().numpy() != want)[:5]
     finally:
         cl.close()
+
+
+@pytest.mark.parametrize("temperature,top_k", [(0.0, 0), (0.9, 0), (0.9, 7)])
+def test_sampling_more_rows_than_the_workspace_was_sized_for(temperature, top_k):
+    """Greedy and all-token sampling spread a row over many workgroups and keep per-segment results in the
+    workspace; a call with more rows than the workspace was sized for takes the one-workgroup-per-row kernel."""
+    V, M = 9000, 12
+    r = np.random.default_rng(5)
+    logits = (np.round(r.standard_normal((M, V)) * 3.0 * 4) / 4).astype(np.float32)
+    u = r.random(M).astype(np.float32)
+    want = oracle.sample(logits, temperature, top_k, u)
+    for rows in (12, 3):
+        cl = _client(V, max_rows=rows)
+        try:
+            got = cl.sample(to_dev(logits), temperature, top_k, to_dev(u))
+            assert np.array_equal(got.cpu().numpy(), want), rows
+        finally:
+            cl.close()
 
 
 def test_sampling_on_the_lm_heads_own_logits_and_its_argument_checks():
