@@ -230,6 +230,29 @@ __device__ __forceinline__ uint32_t order_key(float f) {
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// One radix step, done by the first wave: the bin b (from 255 downwards) in which the running count of keys reaches
+// `remaining`, and how many of that bin's keys are still needed.  hist: 256 counts; lane L takes bins 4L .. 4L+3.
+__device__ __forceinline__ void radix_pick_bin(const int *hist, int remaining, int lane, uint32_t &bin, int &need) {
+    const int h0 = hist[4 * lane], h1 = hist[4 * lane + 1], h2 = hist[4 * lane + 2], h3 = hist[4 * lane + 3];
+    int suf = h0 + h1 + h2 + h3;                                 // becomes the count of this lane's and all higher bins
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int o = __shfl_down(suf, off);
+        if (lane + off < 64) suf += o;
+    }
+    const int above = __shfl_down(suf, 1);
+    int cum = lane < 63 ? above : 0;                             // keys in bins above this lane's
+    const bool mine = suf >= remaining && cum < remaining;       // exactly one lane, if remaining <= total
+    int b = 4 * lane + 3, n = remaining - cum;
+    if (cum + h3 < remaining) { cum += h3; b = 4 * lane + 2; n = remaining - cum;
+        if (cum + h2 < remaining) { cum += h2; b = 4 * lane + 1; n = remaining - cum;
+            if (cum + h1 < remaining) { cum += h1; b = 4 * lane; n = remaining - cum; } } }
+    const unsigned long long who = __ballot(mine);
+    const int src = who ? __ffsll((long long)who) - 1 : 0;       // lane 0 (bin 0 .. 3) if the counts fall short
+    bin = (uint32_t)__shfl(b, src);
+    need = __shfl(n, src);
+}
+
 __device__ __forceinline__ double wave_scan_incl(double v, int lane) {
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {
@@ -309,6 +332,10 @@ __global__ void __launch_bounds__(1024) k_sample(const float *__restrict__ logit
                     }
                     // lanes of a wave that hit the same bin add once: the high bytes of logits crowd a few bins
                     uint32_t bin = (k >> shift) & 255u;
+                    if (pass < 3) {                          // few keys share the prefix by now
+                        if (in) atomicAdd(&hist[bin], 1);
+                        continue;
+                    }
                     unsigned long long todo = __ballot(in);
                     while (todo) {
                         const int first = __ffsll((long long)todo) - 1;
@@ -319,14 +346,11 @@ __global__ void __launch_bounds__(1024) k_sample(const float *__restrict__ logit
                     }
                 }
             __syncthreads();
-            if (tid == 0) {
-                int cum = 0, b = 255;
-                for (; b > 0; b--) {
-                    if (cum + hist[b] >= remaining) break;
-                    cum += hist[b];
-                }
-                sh_prefix = (prefix << 8) | (uint32_t)b;
-                sh_need = remaining - cum;
+            if (wave == 0) {
+                uint32_t b;
+                int n;
+                radix_pick_bin(hist, remaining, lane, b, n);
+                if (lane == 0) { sh_prefix = (prefix << 8) | b; sh_need = n; }
             }
             __syncthreads();
             prefix = sh_prefix;
@@ -570,6 +594,168 @@ __global__ void __launch_bounds__(64) k_sample_pick(const float *__restrict__ lo
     if (lane == 0) next[row] = pick >= 0 ? pick : end - 1;
 }
 
+// Top-k sampling with k <= SAMPLE_KMAX, a row again spread over segments: the k largest of the row are among the
+// k largest of every segment, so k_sample_segtop writes each segment's k largest (in index order) and
+// k_sample_pick_topk, one workgroup per row, selects among those few thousand candidates.
+constexpr int SAMPLE_KMAX = 64;
+struct Cand {
+    uint32_t key;
+    int idx;
+};
+
+// 256 threads hold NPT keys each, in the order (i, wave, lane).  Marks the k largest (equal keys: earlier first) in
+// take (bit i) and gives each marked key its position among the marked, in that order.  LDS: hist[256], grp[64],
+// two words sh.  Every thread of the workgroup must call it; k >= 1 and at most the number of valid keys.
+template <int NPT>
+__device__ __forceinline__ void block_topk_ordered(const uint32_t (&key)[NPT], uint32_t valid, int k, int *hist, int *grp,
+                                                   uint32_t *sh, uint32_t &take, int (&pos)[NPT]) {
+    static_assert(NPT <= 16, "64 (i, wave) groups are scanned by one wave");
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const unsigned long long lt = (1ull << lane) - 1ull;
+    uint32_t prefix = 0;
+    int remaining = k;
+    for (int pass = 3; pass >= 0; pass--) {
+        hist[tid] = 0;
+        __syncthreads();
+        const int shift = pass * 8;
+#pragma unroll
+        for (int i = 0; i < NPT; i++) {
+            const bool in = ((valid >> i) & 1u) && (pass == 3 || (key[i] >> (shift + 8)) == prefix);
+            const uint32_t bin = (key[i] >> shift) & 255u;
+            if (pass < 3) {                                  // few keys share the prefix by now
+                if (in) atomicAdd(&hist[bin], 1);
+                continue;
+            }
+            unsigned long long todo = __ballot(in);
+            while (todo) {                                   // high bytes crowd a few bins: lanes that hit the same one add once
+                const int first = __ffsll((long long)todo) - 1;
+                const uint32_t b0 = (uint32_t)__shfl((int)bin, first);
+                const unsigned long long same = __ballot(in && bin == b0);
+                if (lane == first) atomicAdd(&hist[b0], __popcll(same));
+                todo &= ~same;
+            }
+        }
+        __syncthreads();
+        if (wave == 0) {
+            uint32_t b;
+            int n;
+            radix_pick_bin(hist, remaining, lane, b, n);
+            if (lane == 0) { sh[0] = (prefix << 8) | b; sh[1] = (uint32_t)n; }
+        }
+        __syncthreads();
+        prefix = sh[0];
+        remaining = (int)sh[1];
+        __syncthreads();
+    }
+    const uint32_t thr = prefix;
+    const int need = remaining;
+    // ordered rank of the keys equal to thr, then ordered position of the marked keys: per (i, wave) group a
+    // count, an exclusive scan of the 4 NPT counts by the first wave, and the lanes below within the group
+    auto ordered = [&](auto flag, int (&out)[NPT]) {
+#pragma unroll
+        for (int i = 0; i < NPT; i++) {
+            const unsigned long long m = __ballot(flag(i));
+            if (lane == 0) grp[i * 4 + wave] = __popcll(m);
+            out[i] = __popcll(m & lt);
+        }
+        __syncthreads();
+        if (wave == 0) {
+            const int c = lane < NPT * 4 ? grp[lane] : 0;
+            int inc = c;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const int o = __shfl_up(inc, off);
+                if (lane >= off) inc += o;
+            }
+            if (lane < NPT * 4) grp[lane] = inc - c;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < NPT; i++) out[i] += grp[i * 4 + wave];
+        __syncthreads();
+    };
+    int rank[NPT];
+    ordered([&](int i) { return ((valid >> i) & 1u) && key[i] == thr; }, rank);
+    take = 0;
+#pragma unroll
+    for (int i = 0; i < NPT; i++)
+        if (((valid >> i) & 1u) && (key[i] > thr || (key[i] == thr && rank[i] < need))) take |= 1u << i;
+    ordered([&](int i) { return (take >> i) & 1u; }, pos);
+}
+
+__global__ void __launch_bounds__(256) k_sample_segtop(const float *__restrict__ logits, int V, int top_k,
+                                                       Cand *__restrict__ cand) {
+    constexpr int NPT = SAMPLE_SEG / 256;
+    __shared__ int hist[256], grp[64];
+    __shared__ uint32_t sh[2];
+    const int g = blockIdx.x, row = blockIdx.y, G = gridDim.x;
+    const float *l = logits + (size_t)row * V;
+    const int base = g * SAMPLE_SEG, end = min(V, base + SAMPLE_SEG);
+    uint32_t key[NPT], valid = 0;
+#pragma unroll
+    for (int i = 0; i < NPT; i++) {
+        const int v = base + i * 256 + threadIdx.x;
+        key[i] = 0;
+        if (v < end) { key[i] = order_key(l[v]); valid |= 1u << i; }
+    }
+    uint32_t take;
+    int pos[NPT];
+    block_topk_ordered<NPT>(key, valid, min(top_k, end - base), hist, grp, sh, take, pos);
+    Cand *out = cand + ((size_t)row * G + g) * SAMPLE_KMAX;
+#pragma unroll
+    for (int i = 0; i < NPT; i++)
+        if ((take >> i) & 1u) out[pos[i]] = Cand{key[i], base + i * 256 + (int)threadIdx.x};
+}
+
+__global__ void __launch_bounds__(256) k_sample_pick_topk(const float *__restrict__ logits, int V, float temperature,
+                                                          int top_k, int G, const Cand *__restrict__ cand_all,
+                                                          const float *__restrict__ uni, int32_t *__restrict__ next) {
+    constexpr int NPT = 16;                                  // 4096 candidates at most: 64 segments x 64
+    __shared__ int hist[256], grp[64], play_idx[SAMPLE_KMAX];
+    __shared__ uint32_t sh[2], s_key[4];
+    __shared__ int s_idx[4];
+    const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
+    const float *l = logits + (size_t)row * V;
+    const Cand *cand = cand_all + (size_t)row * G * SAMPLE_KMAX;
+    // candidate j = (segment, position): every segment gave min(top_k, its size); only the last can be short
+    const int per = min(top_k, SAMPLE_SEG), n_last = min(top_k, V - (G - 1) * SAMPLE_SEG), Nc = (G - 1) * per + n_last;
+    uint32_t key[NPT], valid = 0;
+    int idx[NPT];
+    uint32_t bk = 0;
+    int bi = 0x7fffffff;
+#pragma unroll
+    for (int i = 0; i < NPT; i++) {
+        const int j = i * 256 + tid;
+        key[i] = 0;
+        idx[i] = 0;
+        if (j < Nc) {
+            const int g = min(j / per, G - 1);
+            const Cand c = cand[(size_t)g * SAMPLE_KMAX + (j - g * per)];
+            key[i] = c.key;
+            idx[i] = c.idx;
+            valid |= 1u << i;
+            if (c.key > bk) { bk = c.key; bi = c.idx; }      // a thread meets its candidates in index order
+        }
+    }
+    block_best<4>(bk, bi, s_key, s_idx);
+    uint32_t take;
+    int pos[NPT];
+    block_topk_ordered<NPT>(key, valid, top_k, hist, grp, sh, take, pos);
+#pragma unroll
+    for (int i = 0; i < NPT; i++)
+        if ((take >> i) & 1u) play_idx[pos[i]] = idx[i];
+    __syncthreads();
+    if (tid >= 64) return;
+    // the top_k tokens in play, in index order, one per lane
+    const int v = lane < top_k ? play_idx[lane] : 0;
+    const double p = lane < top_k ? exp(((double)l[v] - (double)l[bi]) / (double)temperature) : 0.0;
+    const double incl = wave_scan_incl(p, lane);
+    const double target = (double)uni[row] * __shfl(incl, 63);
+    const unsigned long long over = __ballot(lane < top_k && incl > target);
+    const int which = over ? __ffsll((long long)over) - 1 : top_k - 1;
+    if (lane == 0) next[row] = play_idx[which];
+}
+
 }  // namespace
 
 struct petals_client {
@@ -578,6 +764,7 @@ struct petals_client {
     __half *a;          // LayerNorm output of the rows of one lm_head call
     Best *partial;      // [LM_MAX_ROWS][LM_GROUPS]
     SegStat *seg;       // [max_rows_per_call][segments of the vocabulary]: per-segment results of the sampler
+    Cand *cand;         // [max_rows_per_call][segments][SAMPLE_KMAX]: per-segment candidates of top-k sampling
     bool lds_attr_set[3];
 };
 
@@ -598,7 +785,8 @@ int petals_client_workspace_bytes(const petals_client_config *cfg, size_t *bytes
     if (!bytes) return ps_fail(PETALS_ERR_INVALID_ARG, "null pointer");
     if (int rc = check_client_config(cfg)) return rc;
     *bytes = align_up((size_t)cfg->max_rows_per_call * cfg->hidden * 2) + align_up(sizeof(Best) * LM_MAX_ROWS * LM_GROUPS) +
-             align_up(sizeof(SegStat) * (size_t)cfg->max_rows_per_call * ((cfg->vocab + SAMPLE_SEG - 1) / SAMPLE_SEG));
+             align_up(sizeof(SegStat) * (size_t)cfg->max_rows_per_call * ((cfg->vocab + SAMPLE_SEG - 1) / SAMPLE_SEG)) +
+             align_up(sizeof(Cand) * SAMPLE_KMAX * (size_t)cfg->max_rows_per_call * ((cfg->vocab + SAMPLE_SEG - 1) / SAMPLE_SEG));
     return PETALS_OK;
 }
 
@@ -617,6 +805,8 @@ int petals_client_create(const petals_client_config *cfg, const petals_client_pa
     c->a = (__half *)dev_workspace;
     c->partial = (Best *)((uint8_t *)dev_workspace + align_up((size_t)cfg->max_rows_per_call * cfg->hidden * 2));
     c->seg = (SegStat *)((uint8_t *)c->partial + align_up(sizeof(Best) * LM_MAX_ROWS * LM_GROUPS));
+    c->cand = (Cand *)((uint8_t *)c->seg + align_up(sizeof(SegStat) * (size_t)cfg->max_rows_per_call *
+                                                     ((cfg->vocab + SAMPLE_SEG - 1) / SAMPLE_SEG)));
     c->lds_attr_set[0] = c->lds_attr_set[1] = c->lds_attr_set[2] = false;
     *out = c;
     return PETALS_OK;
@@ -711,6 +901,10 @@ int petals_client_sample(petals_client *c, const float *logits, int32_t M, float
         k_sample_segmax<<<dim3(G, M), 256, 0, st>>>(logits, V, c->seg);
         if (!greedy) k_sample_segsum<<<dim3(G, M), 256, 0, st>>>(logits, V, temperature, c->seg);
         k_sample_pick<<<M, 64, 0, st>>>(logits, V, greedy ? 0.0f : temperature, G, c->seg, uniforms, next_token_out);
+    } else if (top_k <= SAMPLE_KMAX && G <= 64 && M <= c->cfg.max_rows_per_call && M <= 65535) {
+        // a small k: every segment hands in its k largest, one workgroup per row selects among those
+        k_sample_segtop<<<dim3(G, M), 256, 0, st>>>(logits, V, top_k, c->cand);
+        k_sample_pick_topk<<<M, 256, 0, st>>>(logits, V, temperature, top_k, G, c->cand, uniforms, next_token_out);
     } else {
         k_sample<<<M, 1024, 0, st>>>(logits, V, temperature, top_k, uniforms, next_token_out);
     }
