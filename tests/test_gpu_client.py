@@ -144,6 +144,28 @@ def test_sampling_picks_the_oracles_token(V, temperature, top_k):
         cl.close()
 
 
+@pytest.mark.parametrize("V,top_k", [(4096, 64), (4097, 64), (4097, 65), (262144, 64), (262145, 64), (262144, 2),
+                                     (12289, 63), (8192, 4095)])
+def test_sampling_at_the_limits_of_the_segmented_top_k(V, top_k):
+    """Segments of 4096 logits, at most 64 of them and k <= 64 for the path that hands in per-segment candidates:
+    sizes on both sides of each limit, with many equal logits so that the k-th largest is shared across segments."""
+    r = np.random.default_rng(V + top_k)
+    M = 6
+    logits = (np.round(r.standard_normal((M, V)) * 2.0 * 2) / 2).astype(np.float32)      # steps of 0.5: heavy ties
+    logits[1] = 1.0
+    logits[2, ::4096] = 9.0                                   # one maximum per segment
+    u = r.random(M).astype(np.float32)
+    u[3] = np.float32(0.99999994)
+    cl = _client(V, max_rows=M)
+    try:
+        got = cl.sample(to_dev(logits), 1.1, top_k, to_dev(u))
+        torch.cuda.synchronize()
+        want = oracle.sample(logits, 1.1, top_k, u)
+        assert np.array_equal(got.cpu().numpy(), want), (got.cpu().numpy(), want)
+    finally:
+        cl.close()
+
+
 @pytest.mark.parametrize("temperature,top_k", [(0.0, 0), (0.9, 0), (0.9, 7)])
 def test_sampling_more_rows_than_the_workspace_was_sized_for(temperature, top_k):
     """Greedy and all-token sampling spread a row over many workgroups and keep per-segment results in the
