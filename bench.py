@@ -78,6 +78,9 @@ def main():
                          "70-block BLOOM-176B-shaped stack, 32 sessions; C5 = the whole 70-block stack (six chained "
                          "spans, about 250 GB of HBM), 32 sessions")
     ap.add_argument("--prefill-batch", type=int, default=8, help="sessions in the prefill call (512 tokens each)")
+    ap.add_argument("--temperature", type=float, default=0.0,
+                    help="generate mode: 0 = greedy (the LM head's own choice); > 0 = sample the next token")
+    ap.add_argument("--top-k", type=int, default=0, help="generate mode with --temperature > 0: tokens in play (0 = all)")
     ap.add_argument("--weight-std", type=float, default=0.02,
                     help="standard deviation of the synthetic weights (0.02 is the recipe; smaller weights give "
                          "smaller activations and so fewer outlier columns in calls of many rows)")
@@ -595,10 +598,19 @@ def generate_main(args, dev):
     out = torch.empty((1, H), dtype=torch.float16, device=dev)
     stream = torch.cuda.current_stream()
 
+    sampling = args.temperature > 0.0
+    if sampling:     # the uniform numbers of all steps are drawn beforehand: nothing random inside the timed loop
+        uniforms = torch.rand(W + K + 1, generator=g, device=dev, dtype=torch.float32).clamp_(max=0.99999994)
+        logits = torch.empty((1, V), dtype=torch.float32, device=dev)
+
     def step(i):
         cl.embed(tok[i:i + 1], out=hid)
         span.decode_step([se], hid, out)
-        cl.lm_head(out, next_out=tok[i + 1:i + 2])
+        if sampling:
+            binding.petals_client_lm_head(cl.handle, out, logits, None)
+            cl.sample(logits, args.temperature, args.top_k, uniforms[i:i + 1], next_out=tok[i + 1:i + 2])
+        else:
+            cl.lm_head(out, next_out=tok[i + 1:i + 2])
 
     for i in range(W):
         step(i)
@@ -638,12 +650,15 @@ def generate_main(args, dev):
                "kind": "oracle", "sample": "LM head over the first %d of %d embedding rows (%.2f s), extrapolated; "
                "GPU choice on the same rows %s the oracle's" % (sample, V, dt, "equals" if same else "DIFFERS FROM")}
     line = {
-        "metric": "greedy generation tokens/s, client ends + 12-block BLOOM-176B span on one GPU (batch 1)",
+        "metric": "%s generation tokens/s, client ends + 12-block BLOOM-176B span on one GPU (batch 1)"
+                  % ("sampled" if sampling else "greedy"),
         "value": round(1e3 / ms, 2), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8 span, fp16 embeddings", "data": "synthetic",
         "config": {"workload": "embedding lookup + LayerNorm, 12-block BLOOM-176B-shaped span decode step at KV prefix %d, "
-                               "final LayerNorm + tied LM head (%d x %d fp16) + greedy choice, token fed back on the device"
-                               % (L, V, H), "lm_head_ms": round(lm_ms, 4), "distinct_tokens_generated": distinct},
+                               "final LayerNorm + tied LM head (%d x %d fp16) + %s, token fed back on the device"
+                               % (L, V, H, ("sampling at temperature %g, top_k %d" % (args.temperature, args.top_k))
+                                  if sampling else "greedy choice"),
+                   "lm_head_ms": round(lm_ms, 4), "distinct_tokens_generated": distinct},
         "roofline": {"bound": "hbm", "achieved": round(lm_bytes / (lm_ms * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(lm_bytes / (lm_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
                      "kernel": "k_lm_head (LayerNorm and the final pick included in the timed call)"},
