@@ -112,6 +112,47 @@ def test_greedy_generation_loop_stays_on_the_device_and_matches_the_oracle():
     cl.close(); gsp.close(); osp.destroy()
 
 
+def test_sampled_generation_loop_on_the_device_matches_the_oracle():
+    """The same loop with the next token sampled (top 20, at a temperature that matches the spread of these logits) from the LM head's fp32 logits with
+    uniforms drawn beforehand: the token ids, which steer every later step, equal the oracle's."""
+    from paper_2209_01188_amd import synth
+    from tests.gpu_util import build_pair
+    cfg = synth.scaled(synth.CONFIGS["C2"], n_blocks=2)
+    V, H = 2000, cfg.hidden
+    r, E, (eg, eb, fg, fb) = _model(22, V, H)
+    E = h(E.astype(np.float64) * 20.0)
+    osp, gsp, _ = build_pair(cfg, n_blocks=2, max_rows=8)
+    cl = binding.Client(to_dev(E), to_dev(eg), to_dev(eb), to_dev(fg), to_dev(fb), max_rows=8)
+    prompt = r.integers(0, V, 8).astype(np.int32)
+    steps, T, K = 8, 400.0, 20     # tied random embeddings: the fed-back token leads the others by about 1000
+    u = r.random(steps).astype(np.float32)
+    try:
+        # oracle: its fp64 logits rounded to fp32 are what the library's LM head returns
+        ose = osp.open_session(8 + steps)
+        y = osp.step([ose], oracle.embed(prompt, E, eg, eb)[None])[0, -1:]
+        ref = []
+        for i in range(steps):
+            _, lg = oracle.lm_head(y, E, fg, fb, want_logits=True)
+            tok = oracle.sample(lg.astype(np.float32), T, K, u[i:i + 1])
+            ref.append(int(tok[0]))
+            if i + 1 < steps:
+                y = osp.step([ose], oracle.embed(tok, E, eg, eb)[None])[0]
+        # GPU: token ids and uniforms stay on the device
+        gse = gsp.open_session(8 + steps)
+        ud = to_dev(u)
+        yg = gsp.prefill([gse], cl.embed(to_dev(prompt))[None])[0, -1:]
+        out = torch.empty(steps, dtype=torch.int32, device=DEV)
+        for i in range(steps):
+            _, lg = cl.lm_head(yg, want_logits=True)
+            cl.sample(lg, T, K, ud[i:i + 1], next_out=out[i:i + 1])
+            if i + 1 < steps:
+                yg = gsp.decode_step([gse], cl.embed(out[i:i + 1]))
+        assert out.cpu().tolist() == ref
+        assert len(set(ref)) > 2                                # it does sample: not the greedy loop's fixed point
+    finally:
+        cl.close(); gsp.close(); osp.destroy()
+
+
 # ------------------------------------------------------------------ choice of the next token (Figure 2)
 
 def _client(V, H=64, max_rows=24):
