@@ -303,7 +303,7 @@ __global__ void __launch_bounds__(1024) k_sample(const float *__restrict__ logit
     bk = s_key[0]; bi = s_idx[0];
     for (int w = 1; w < 16; w++)
         if (s_key[w] > bk || (s_key[w] == bk && s_idx[w] < bi)) { bk = s_key[w]; bi = s_idx[w]; }
-    const int best = bi;
+    const int best = min(bi, V - 1);                        // (a row of nothing but NaN patterns has no best: stay in bounds)
     if (temperature == 0.0f || top_k == 1) {               // the greedy choice (uniform over the workgroup)
         if (tid == 0) next[row] = best;
         return;
@@ -523,6 +523,7 @@ __global__ void __launch_bounds__(256) k_sample_segsum(const float *__restrict__
     uint32_t bk;
     int bi;
     row_best<4>(st + (size_t)row * G, G, bk, bi, s_key, s_idx);
+    bi = min(bi, V - 1);                                     // stays in bounds whatever the logits hold
     const double lm = (double)l[bi], Td = (double)temperature;
     const int base = g * SAMPLE_SEG, end = min(V, base + SAMPLE_SEG);
     double sum = 0.0;
@@ -548,6 +549,7 @@ __global__ void __launch_bounds__(64) k_sample_pick(const float *__restrict__ lo
     uint32_t bk;
     int bi;
     row_best<1>(st, G, bk, bi, s_key, s_idx);
+    bi = min(bi, V - 1);                                     // stays in bounds whatever the logits hold
     if (temperature == 0.0f) {
         if (lane == 0) next[row] = bi;
         return;
@@ -575,6 +577,7 @@ __global__ void __launch_bounds__(64) k_sample_pick(const float *__restrict__ lo
         c += __shfl(incl, 63);
     }
     if (gstar < 0) {                                        // rounding left no segment above the target: the last one
+        if (glast < 0) glast = G - 1;                       // (no positive sum at all: logits that are not numbers)
         gstar = glast;
         before = total - st[glast].sum;
     }
@@ -738,6 +741,7 @@ __global__ void __launch_bounds__(256) k_sample_pick_topk(const float *__restric
         }
     }
     block_best<4>(bk, bi, s_key, s_idx);
+    bi = min(bi, V - 1);                                     // stays in bounds whatever the logits hold
     uint32_t take;
     int pos[NPT];
     block_topk_ordered<NPT>(key, valid, top_k, hist, grp, sh, take, pos);

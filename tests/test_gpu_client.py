@@ -242,3 +242,26 @@ def test_sampling_on_the_lm_heads_own_logits_and_its_argument_checks():
                 cl.sample(logits, bad, 0, u)
     finally:
         cl.close()
+
+
+@pytest.mark.parametrize("temperature,top_k", [(0.0, 0), (1.0, 0), (1.0, 8), (1.0, 300)])
+def test_sampling_logits_that_are_not_numbers_stay_in_bounds(temperature, top_k):
+    """The header asks for finite logits.  Rows of NaN (both signs, the all-ones pattern), of -inf and with +inf
+    give no meaningful token, but whatever comes back is a token id (or the output is left alone)."""
+    V, M = 9000, 6
+    logits = np.zeros((M, V), np.float32)
+    logits[0] = np.nan
+    logits[1] = -np.inf
+    logits[2, 17] = np.inf
+    logits[3] = np.frombuffer(np.full(V, 0xffffffff, np.uint32).tobytes(), np.float32)
+    logits[4] = -np.nan
+    logits[5, ::2] = np.nan
+    cl = _client(V, max_rows=M)
+    try:
+        out = torch.full((M,), -1, dtype=torch.int32, device=DEV)
+        cl.sample(to_dev(logits), temperature, top_k, to_dev(np.full(M, 0.5, np.float32)), next_out=out)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        assert ((got >= -1) & (got < V)).all(), got
+    finally:
+        cl.close()
