@@ -86,7 +86,10 @@ int petals_client_lm_head(petals_client *client, const void *hidden_in, int32_t 
  * all), p_v = exp((l_v - l_max) / temperature) in fp64, and the answer is the first index in
  * play whose running sum of p, taken in index order, exceeds uniforms[t] * (sum of all p in
  * play); the last index in play if rounding lets none exceed it.  temperature < 0 or NaN ->
- * PETALS_ERR_INVALID_ARG.  Needs no workspace; one workgroup per row.
+ * PETALS_ERR_INVALID_ARG.  A row is spread over workgroups whose per-segment results go through the
+ * handle's workspace (calls of up to max_rows_per_call rows; larger ones fall back to one workgroup per row
+ * and no workspace): like every call on a handle, one stream at a time - two sample calls of one handle
+ * that overlap in time race.  Logits that are not numbers: some in-range index is returned.
  */
 int petals_client_sample(petals_client *client, const float *logits, int32_t M, float temperature,
                          int32_t top_k, const float *uniforms, int32_t *next_token_out,

@@ -100,24 +100,24 @@ int check_config(const petals_span_config *c) {
 
 // The 256 entries of the 8-bit dynamic data type: per decade 10^-e (e = 0..6) the centres
 // of 2^(6-e) equal buckets spanning [0.1, 1.0], both signs, plus 0 and 1.0; ascending.
-const CodeTable &code_table() {
-    static CodeTable tab;
-    static bool ready = false;
-    if (!ready) {
-        static const double decade[7] = {1.0, 1e-1, 1e-2, 1e-3, 1e-4, 1e-5, 1e-6};
-        std::vector<float> pos;
-        for (int e = 6; e >= 0; e--) {
-            const int cnt = 64 >> e;
-            for (int j = 0; j < cnt; j++) pos.push_back((float)(decade[e] * (0.1 + 0.9 * (j + 0.5) / cnt)));
-        }
-        // pos ascends: decades from small to large, buckets ascending inside a decade
-        int k = 0;
-        for (int i = (int)pos.size() - 1; i >= 0; i--) tab.code[k++] = -pos[i];
-        tab.code[k++] = 0.0f;
-        for (size_t i = 0; i < pos.size(); i++) tab.code[k++] = pos[i];
-        tab.code[k++] = 1.0f;
-        ready = true;
+CodeTable make_code_table() {
+    CodeTable tab;
+    static const double decade[7] = {1.0, 1e-1, 1e-2, 1e-3, 1e-4, 1e-5, 1e-6};
+    std::vector<float> pos;
+    for (int e = 6; e >= 0; e--) {
+        const int cnt = 64 >> e;
+        for (int j = 0; j < cnt; j++) pos.push_back((float)(decade[e] * (0.1 + 0.9 * (j + 0.5) / cnt)));
     }
+    // pos ascends: decades from small to large, buckets ascending inside a decade
+    int k = 0;
+    for (int i = (int)pos.size() - 1; i >= 0; i--) tab.code[k++] = -pos[i];
+    tab.code[k++] = 0.0f;
+    for (size_t i = 0; i < pos.size(); i++) tab.code[k++] = pos[i];
+    tab.code[k++] = 1.0f;
+    return tab;
+}
+const CodeTable &code_table() {
+    static const CodeTable tab = make_code_table();   // initialised once, also when several threads arrive together
     return tab;
 }
 

@@ -422,6 +422,10 @@ __global__ void __launch_bounds__(1024) k_sample(const float *__restrict__ logit
         }
         if (wstar < 0) { wstar = wlast; before = c - (wlast >= 0 ? s_sum[wlast] : 0.0); }
     }
+    if (wstar < 0) {                                        // no wave has a positive sum (logits that are not numbers):
+        if (threadIdx.x == 0) next[row] = min(max(best, 0), V - 1);   // the same in-range answer the segmented kernels give
+        return;
+    }
     if (wave != wstar) return;                              // whole waves leave; no barrier follows
 
     // 5. inside that wave: walk the iterations, then the four groups of the iteration, then the lanes

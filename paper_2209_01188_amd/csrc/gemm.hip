@@ -4,6 +4,8 @@
 // 64-column tile that holds outliers, each of the four 16-column lane groups hands its next outlier
 // column to one k-slot of v_mfma_f64_16x16x4_f64 (products of fp16 values are exact in fp64).
 // Also here: the compaction kernel that prefill-size calls use for the same exact product.
+#include <mutex>
+
 #include "common.h"
 #include "epilogue.h"
 
@@ -243,7 +245,9 @@ hipError_t launch(const LinearW &w, const int8_t *xq_tiled, const int8_t *xo_til
     constexpr int WVK = 8, G = WN * MT, NPP = G < 4 ? G : 4;
     const size_t lds = (size_t)WVK * NPP * 64 * (16 + 32);   // up to 96 KB
     auto kern = k_gemm<WN, MT, UK, WVK>;
+    static std::mutex attr_lock;
     static bool attr_set = false;
+    std::lock_guard<std::mutex> hold(attr_lock);
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;

@@ -15,6 +15,8 @@
 // The fp16 form of the pipeline also serves the backward pass as a plain product of two tile arrays
 // (ps_gemm_f16_tiles): fp32 result, or for the down linear fp16(result * GeLU') in the tile order of the
 // next product.
+#include <mutex>
+
 #include "common.h"
 #include "epilogue.h"
 
@@ -509,7 +511,9 @@ hipError_t launch_one(const GemmArgs &ga, const LinearW &w, const float *sx, con
     const size_t lds_epi = (size_t)WVN * WVM * (TN / 2) * TM * 1024 + (size_t)BN * 16 * 16 + (size_t)BN * 4 * 8 + (size_t)BN / 2 * 4;
     const size_t lds = lds_stage > lds_epi ? lds_stage : lds_epi;
     auto kern = k_gemm_lds<F16, WVN, WVM, TN, TM, NSLOT>;
+    static std::mutex attr_lock;
     static bool attr_set = false;
+    std::lock_guard<std::mutex> hold(attr_lock);
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;

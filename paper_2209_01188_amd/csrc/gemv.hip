@@ -5,6 +5,8 @@
 // token; the input row (a few tens of KB) comes from L2.
 #include <stdlib.h>
 
+#include <mutex>
+
 #include "common.h"
 #include "epilogue.h"
 
@@ -271,7 +273,9 @@ hipError_t launch3(bool ln, const LinearW &w, const RowIn &in, const OutDesc &o,
     auto kern = ln ? k_gemv_row<U, MAXCH, true, NG> : k_gemv_row<U, MAXCH, false, NG>;
     if (lds > 96 * 1024) return hipErrorInvalidValue;   // K <= 65536: at most 86 KB
     if (lds > 64 * 1024) {
+        static std::mutex attr_lock;
         static bool attr_set[2] = {false, false};
+        std::lock_guard<std::mutex> hold(attr_lock);
         if (!attr_set[ln]) {
             hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
             if (e != hipSuccess) return e;
