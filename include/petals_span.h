@@ -141,6 +141,20 @@ int petals_span_decode_step(petals_span *span, petals_session *const *sessions, 
                             const void *hidden_in, void *hidden_out, void *stream);
 
 /*
+ * petals_span_decode_step for callers that cannot provide or allocate device memory at the time of the call
+ * (code running under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same step,
+ * same arguments, same results bit for bit, but every intermediate buffer lives in a fixed device array that
+ * is part of the library image (32 MiB per GPU, held until the process ends) instead of the span's workspace.
+ * The call allocates nothing, on the host or on the device.  A step whose intermediates do not fit
+ * (B * hidden of the order of a few hundred thousand; for BLOOM-176B-shaped blocks up to about 40 sessions)
+ * returns PETALS_ERR_CAPACITY and changes nothing.  All spans of the process share the array of their GPU:
+ * calls of this entry point that overlap in time on one GPU (different streams or threads) race; calls on one
+ * stream are ordered and safe.  The span's own workspace is not touched.
+ */
+int petals_span_decode_step_static(petals_span *span, petals_session *const *sessions, int32_t B,
+                                   const void *hidden_in, void *hidden_out, void *stream);
+
+/*
  * Failure recovery (Section 2.1: a client keeps everything it has sent to each server, so that a
  * failed server can be replaced; Section 3.2: the replacement receives all of those inputs again and
  * thereby arrives at the same attention keys and values).  Feeds the

@@ -53,7 +53,8 @@ def lib():
 
 EXPORTS = ["petals_span_weight_bytes", "petals_span_workspace_bytes", "petals_span_kv_bytes", "petals_span_create",
            "petals_span_load_block", "petals_span_destroy", "petals_session_open", "petals_session_length",
-           "petals_session_close", "petals_span_prefill", "petals_span_decode_step", "petals_hidden_quantize",
+           "petals_session_close", "petals_span_prefill", "petals_span_decode_step", "petals_span_decode_step_static",
+           "petals_hidden_quantize",
            "petals_hidden_dequantize", "petals_hidden_code_table", "petals_last_error", "petals_debug_linear",
            "petals_debug_export_weight", "petals_debug_export_kv", "petals_debug_import_kv",
            "petals_span_profile_begin", "petals_span_profile_end", "petals_debug_layernorm", "petals_session_replay",
@@ -149,6 +150,11 @@ def petals_span_prefill(span, sessions, T, hidden_in, hidden_out):
 def petals_span_decode_step(span, sessions, hidden_in, hidden_out):
     _check(lib().petals_span_decode_step(span, _session_array(sessions), C.c_int32(len(sessions)),
                                          _ptr(hidden_in), _ptr(hidden_out), _stream()))
+
+
+def petals_span_decode_step_static(span, sessions, hidden_in, hidden_out):
+    _check(lib().petals_span_decode_step_static(span, _session_array(sessions), C.c_int32(len(sessions)),
+                                                _ptr(hidden_in), _ptr(hidden_out), _stream()))
 
 
 def petals_session_replay(span, session, hidden_log, call_tokens, scratch_out):
@@ -285,6 +291,12 @@ class Span:
     def decode_step(self, sessions, hidden_in, out=None):
         out = torch.empty_like(hidden_in) if out is None else out
         petals_span_decode_step(self.handle, [s.handle for s in sessions], hidden_in, out)
+        return out
+
+    def decode_step_static(self, sessions, hidden_in, out=None):
+        """decode_step with the intermediates in the library's own fixed device array (allocates nothing)."""
+        out = torch.empty_like(hidden_in) if out is None else out
+        petals_span_decode_step_static(self.handle, [s.handle for s in sessions], hidden_in, out)
         return out
 
     def attach_backward_cache(self, on=True):

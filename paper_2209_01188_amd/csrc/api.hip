@@ -5,6 +5,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 
 #include "span_internal.h"
@@ -12,6 +13,11 @@
 namespace {
 thread_local char g_err[512] = "";
 }
+
+// Scratch of petals_span_decode_step_static: device memory that belongs to the library image, so that the call
+// needs no workspace from anybody.  Every GPU the library runs on holds its own copy at its own address.
+#define PS_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+static __device__ __align__(256) unsigned char scratch[PS_STATIC_SCRATCH_BYTES];
 
 int ps_fail(int code, const char *fmt, ...) {
     va_list ap;
@@ -67,10 +73,11 @@ Workspace carve(const petals_span_config &c, uint8_t *base) {
     w.partials = (double *)take((size_t)PS_ATTN_PARTIAL_SLOTS * (128 + 2) * 8);
     w.ocount = (int *)take(256);
     const size_t Nmax = 3 * H > F ? 3 * H : F;
-    w.wd64 = (double *)take(Nmax / 16 * PS_OUTLIER_CHUNKS * 64 * 8);
-    w.x64 = (double *)take(Mp / 16 * PS_OUTLIER_CHUNKS * 64 * 8);
+    w.wd64 = w.x64 = nullptr;
     w.many = ManyOutliers{nullptr, nullptr, nullptr, nullptr};
-    if (M > 64) {   // prefill-size calls: room for the case that most columns are outliers
+    if (M > 64) {   // prefill-size calls: compacted exact outlier operands, and room for the case that most columns are outliers
+        w.wd64 = (double *)take(Nmax / 16 * PS_OUTLIER_CHUNKS * 64 * 8);
+        w.x64 = (double *)take(Mp / 16 * PS_OUTLIER_CHUNKS * 64 * 8);
         const size_t NKmax = (size_t)(3 * H > F ? 3 * H : F) * H > H * F ? (size_t)(3 * H > F ? 3 * H : F) * H : H * F;
         w.many.list = (int *)take((Kmax + 32) * 4);
         w.many.xo = (__half *)take(Mp * (Kmax + 32) * 2);
@@ -215,6 +222,62 @@ int forward_blocks(petals_span *sp, int M, int T, int max_keys, const __half *hi
                                 plain_out(xout, PETALS_EPILOGUE_RESIDUAL, x1b), nullptr, false, st)) return rc;
         x = xout;
     }
+    return PETALS_OK;
+}
+
+// Checks, session table, the blocks, session lengths: the body of every forward call.  Works on sp->ws.
+int run_call(petals_span *sp, petals_session *const *sessions, int32_t B, int32_t T, const void *hidden_in,
+             void *hidden_out, hipStream_t st) {
+    if (!sp || !sessions || !hidden_in || !hidden_out) return fail(PETALS_ERR_INVALID_ARG, "null pointer");
+    if (B < 1 || T < 1) return fail(PETALS_ERR_INVALID_ARG, "B and T must be positive");
+    if (hidden_in == hidden_out) return fail(PETALS_ERR_INVALID_ARG, "hidden_in and hidden_out alias");
+    if (B > PETALS_MAX_SESSIONS_PER_CALL) return fail(PETALS_ERR_CAPACITY, "more than %d sessions in one call", PETALS_MAX_SESSIONS_PER_CALL);
+    if ((int64_t)B * T > sp->cfg.max_rows_per_call)
+        return fail(PETALS_ERR_CAPACITY, "%lld rows exceed max_rows_per_call %d", (long long)B * T, sp->cfg.max_rows_per_call);
+    const petals_span_config &c = sp->cfg;
+    SessTable tab;
+    memset(&tab, 0, sizeof(tab));
+    int max_keys = 0;
+    for (int s = 0; s < B; s++) {
+        petals_session *se = sessions[s];
+        if (!se || se->span != sp) return fail(PETALS_ERR_INVALID_ARG, "session %d is null or belongs to another span", s);
+        for (int r = 0; r < s; r++)
+            if (sessions[r] == se) return fail(PETALS_ERR_INVALID_ARG, "session listed twice");
+        if (se->len + T > se->cap) return fail(PETALS_ERR_CAPACITY, "session %d: %d cached + %d new > capacity %d", s, se->len, T, se->cap);
+        tab.kv[s] = se->kv;
+        tab.len[s] = se->len;
+        tab.cap[s] = se->cap;
+        if (se->len + T > max_keys) max_keys = se->len + T;
+    }
+    for (int b = 0; b < c.n_blocks; b++)
+        if (!sp->blocks[b].loaded) return fail(PETALS_ERR_STATE, "block %d has not been loaded", b);
+    memcpy(tab.slopes, sp->slopes, sizeof(tab.slopes));
+
+    Workspace &ws = sp->ws;
+    const int M = B * T;
+    HIP_TRY(ps_set_table(tab, ws.table, st));
+    if (int rc = forward_blocks(sp, M, T, max_keys, (const __half *)hidden_in, (__half *)hidden_out, nullptr, st)) return rc;
+    for (int s = 0; s < B; s++) sessions[s]->len += T;
+    return PETALS_OK;
+}
+
+// Address of this device's copy of `scratch` (looked up once per device, with that device current).
+constexpr int PS_MAX_DEVICES = 64;
+std::mutex g_scratch_lock;
+void *g_scratch_ptr[PS_MAX_DEVICES] = {};
+
+int static_scratch(void **out) {
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= PS_MAX_DEVICES) return fail(PETALS_ERR_UNSUPPORTED, "device index %d out of range", dev);
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p || ((uintptr_t)p & 255)) return fail(PETALS_ERR_HIP, "static scratch memory is missing or misaligned");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
     return PETALS_OK;
 }
 
@@ -390,43 +453,37 @@ int petals_session_close(petals_session *se) {
 
 int petals_span_prefill(petals_span *sp, petals_session *const *sessions, int32_t B, int32_t T,
                         const void *hidden_in, void *hidden_out, void *stream) {
-    if (!sp || !sessions || !hidden_in || !hidden_out) return fail(PETALS_ERR_INVALID_ARG, "null pointer");
-    if (B < 1 || T < 1) return fail(PETALS_ERR_INVALID_ARG, "B and T must be positive");
-    if (hidden_in == hidden_out) return fail(PETALS_ERR_INVALID_ARG, "hidden_in and hidden_out alias");
-    if (B > PETALS_MAX_SESSIONS_PER_CALL) return fail(PETALS_ERR_CAPACITY, "more than %d sessions in one call", PETALS_MAX_SESSIONS_PER_CALL);
-    if ((int64_t)B * T > sp->cfg.max_rows_per_call)
-        return fail(PETALS_ERR_CAPACITY, "%lld rows exceed max_rows_per_call %d", (long long)B * T, sp->cfg.max_rows_per_call);
-    const petals_span_config &c = sp->cfg;
-    SessTable tab;
-    memset(&tab, 0, sizeof(tab));
-    int max_keys = 0;
-    for (int s = 0; s < B; s++) {
-        petals_session *se = sessions[s];
-        if (!se || se->span != sp) return fail(PETALS_ERR_INVALID_ARG, "session %d is null or belongs to another span", s);
-        for (int r = 0; r < s; r++)
-            if (sessions[r] == se) return fail(PETALS_ERR_INVALID_ARG, "session listed twice");
-        if (se->len + T > se->cap) return fail(PETALS_ERR_CAPACITY, "session %d: %d cached + %d new > capacity %d", s, se->len, T, se->cap);
-        tab.kv[s] = se->kv;
-        tab.len[s] = se->len;
-        tab.cap[s] = se->cap;
-        if (se->len + T > max_keys) max_keys = se->len + T;
-    }
-    for (int b = 0; b < c.n_blocks; b++)
-        if (!sp->blocks[b].loaded) return fail(PETALS_ERR_STATE, "block %d has not been loaded", b);
-    memcpy(tab.slopes, sp->slopes, sizeof(tab.slopes));
-
-    hipStream_t st = (hipStream_t)stream;
-    Workspace &ws = sp->ws;
-    const int M = B * T;
-    HIP_TRY(ps_set_table(tab, ws.table, st));
-    if (int rc = forward_blocks(sp, M, T, max_keys, (const __half *)hidden_in, (__half *)hidden_out, nullptr, st)) return rc;
-    for (int s = 0; s < B; s++) sessions[s]->len += T;
-    return PETALS_OK;
+    return run_call(sp, sessions, B, T, hidden_in, hidden_out, (hipStream_t)stream);
 }
 
 int petals_span_decode_step(petals_span *sp, petals_session *const *sessions, int32_t B, const void *hidden_in,
                             void *hidden_out, void *stream) {
     return petals_span_prefill(sp, sessions, B, 1, hidden_in, hidden_out, stream);
+}
+
+int petals_span_decode_step_static(petals_span *sp, petals_session *const *sessions, int32_t B, const void *hidden_in,
+                                   void *hidden_out, void *stream) {
+    if (!sp) return fail(PETALS_ERR_INVALID_ARG, "null pointer");
+    if (B < 1) return fail(PETALS_ERR_INVALID_ARG, "B must be positive");
+    if (B > PETALS_MAX_SESSIONS_PER_CALL) return fail(PETALS_ERR_CAPACITY, "more than %d sessions in one call", PETALS_MAX_SESSIONS_PER_CALL);
+    // the intermediates of a B-row step, laid out like a workspace sized for exactly B rows
+    petals_span_config c = sp->cfg;
+    c.max_rows_per_call = B;
+    const size_t need = carve(c, nullptr).total;
+    if (need > PS_STATIC_SCRATCH_BYTES)
+        return fail(PETALS_ERR_CAPACITY, "a step of %d rows of this span needs %zu bytes of scratch memory, the static buffer holds %zu",
+                    B, need, (size_t)PS_STATIC_SCRATCH_BYTES);
+    void *base = nullptr;
+    if (int rc = static_scratch(&base)) return rc;
+    // the span's kernels take every intermediate buffer from sp->ws: point it at the static memory for this call
+    const Workspace own = sp->ws;
+    const int own_rows = sp->cfg.max_rows_per_call;
+    sp->ws = carve(c, (uint8_t *)base);
+    sp->cfg.max_rows_per_call = B;
+    const int rc = run_call(sp, sessions, B, 1, hidden_in, hidden_out, (hipStream_t)stream);
+    sp->ws = own;
+    sp->cfg.max_rows_per_call = own_rows;
+    return rc;
 }
 
 int petals_session_replay(petals_span *sp, petals_session *se, const void *hidden_log, const int32_t *call_tokens,
