@@ -62,7 +62,7 @@ struct CodeTable { float code[256]; };
 // chunk c of tile r holds 64 doubles, lane l = column list[4c + l/16] of row 16r + l%16
 // (weight rows permuted inside a tile, see k_outlier_prep).
 struct OutlierSet {
-    const int *count;       // number of outlier columns of this call
+    const int *count;       // [0] number of outlier columns of this call, [1] digit planes its activations need
     const double *wd64;     // [N/16][PS_OUTLIER_CHUNKS][64] dequantized fp16 weights
     const double *x64;      // [ceil(M/16)][PS_OUTLIER_CHUNKS][64] fp16 activations
 };
@@ -83,13 +83,18 @@ hipError_t ps_rowquant_tiled(const __half *X, int M, int K, const uint32_t *mask
                              float *sx, int8_t *xq_rowmajor_dbg, hipStream_t st);
 hipError_t ps_mask_to_bytes(const uint32_t *mask, int K, uint8_t *out, hipStream_t st);
 
-// Scratch of the outlier-heavy case of a prefill-size call (more than PS_EXACT_OUTLIERS columns)
+// Scratch of the outlier-heavy case of a prefill-size call (more than PS_EXACT_OUTLIERS columns): the fp16
+// product over the outlier columns is taken exactly, as int8 digit products (see gemm_lds.hip)
+#define PS_X_DIGITS 6            // balanced 8-bit digits of an fp16 activation in units of 2^-24 (4 cover |x| < 127.5)
+#define PS_MANY_CHUNK 14336      // output features per digit product (bounds the raw-sum buffer)
 struct ManyOutliers {
-    int *list;      // [K] outlier column indices, ascending, padded with -1 to a multiple of 32
-    __half *xo;     // gathered fp16 activations, tiles [ceil(M/16)][ceil(n_out/32)][512 halves]
-    __half *wo;     // gathered dequantized fp16 weights, tiles [N/16][ceil(n_out/32)][512 halves]
-    float *outl;    // [M, N] fp32 outlier product
+    int *list;      // [K] outlier column indices, ascending, padded with -1 to a multiple of 64
+    int8_t *xl;     // digit tiles of the activations [PS_X_DIGITS][ceil(M/16)][ceil(n_out/64)][1024]
+    int8_t *wd;     // digit tiles of the dequantized weights [2][N/16][ceil(n_out/64)][1024]
+    int32_t *raw;   // [PS_X_DIGITS * 16 ceil(M/16)][2 * chunk] digit products of one chunk of output features
+    double *od;     // [M, N] the outlier product
 };
+size_t ps_many_chunk_features(int N);
 // LDS-staged linear for M > 64 rows (any number of outlier columns)
 hipError_t ps_gemm_lds(const LinearW &w, const int8_t *xq_tiled, const uint32_t *mask, const __half *X, const float *sx,
                        int M, const OutlierSet &os, const ManyOutliers &mo, const OutDesc &o, const SessTable *sess,

@@ -30,7 +30,7 @@ __global__ void __launch_bounds__(64) k_outlier_prep(LinearW w, const uint32_t *
         if (lane >= off) incl += v;
     }
     const int total = __shfl(incl, 63);
-    if (blockIdx.x == 0 && lane == 0) *count = total;
+    if (blockIdx.x == 0 && lane == 0) { count[0] = total; count[1] = 4; }   // [1]: digit planes, raised by k_limb_x
     if (total == 0 || total > PS_EXACT_OUTLIERS) return;
     int pos = incl - cnt;
     for (int i = w0; i < w1; i++) {

@@ -7,12 +7,20 @@
 // 4-slot LDS ring filled by asynchronous global->LDS copies.
 //
 // Outlier columns: up to PS_EXACT_OUTLIERS of them are added exactly in the epilogue (fp64 matrix
-// instruction on compacted operands, see k_outlier_prep).  More than that: the outlier columns of
-// the activations and of the dequantized weights are gathered into dense fp16 tile arrays and
-// multiplied by the same pipeline with v_mfma_f32_16x16x32_f16 into an fp32 [M,N] buffer that the
-// int8 kernel's epilogue adds.
+// instruction on compacted operands, see k_outlier_prep).  More than that: the fp16 x fp16 product over the
+// outlier columns is computed EXACTLY in integer arithmetic on the int8 matrix cores.  Every fp16 value
+// is an integer multiple of 2^-24, so an activation is x = 2^-24 * sum_j 256^j * L_j with balanced
+// 8-bit digits L_j (4 of them up to |x| < 127.5, at most 6); a dequantized weight of output row n,
+// Wd = fp16(code * a_n), is u_n * (m_n * code + r) with u_n the fp16 spacing at a_n, m_n = a_n / u_n
+// rounded to an integer (11 bits) and a remainder r that always fits 8 bits.  The gathered digit
+// matrices [digits * M, n_out] and [2 * N, n_out] go through the same pipeline as the regular
+// columns (int32 sums: exact), and k_combine_digits reassembles
+//   sum_k x * Wd = u_n * 2^-24 * (m_n * sum_j 256^j * A_c[j] + sum_j 256^j * A_r[j])
+// in fp64 for the int8 kernel's epilogue to add.  (The fp16 matrix instruction with its fp32 sums
+// lands one fp16 rounding step off in about one output of 300 at 57344 columns, and a neighbouring
+// value is enough to move a row maximum or cross the outlier threshold downstream.)
 //
-// The fp16 form of the pipeline also serves the backward pass as a plain product of two tile arrays
+// The fp16 form of the pipeline serves the backward pass as a plain product of two tile arrays
 // (ps_gemm_f16_tiles): fp32 result, or for the down linear fp16(result * GeLU') in the tile order of the
 // next product.
 #include <mutex>
@@ -28,7 +36,7 @@ constexpr int STRIP = 4;       // m-blocks per rasterization strip
 // outlier column list and fp16 gathers (only do work when the call has > PS_EXACT_OUTLIERS)
 
 // One workgroup: ascending list of the set bits of mask[0 .. K/32); entries up to the next multiple
-// of 32 are -1.  count must already hold the number of set bits.
+// of 64 are -1.  count must already hold the number of set bits.
 __global__ void __launch_bounds__(1024) k_outlier_list(const uint32_t *__restrict__ mask, int K,
                                                        const int *__restrict__ count, int *__restrict__ list) {
     __shared__ int wave_tot[16];
@@ -56,108 +64,212 @@ __global__ void __launch_bounds__(1024) k_outlier_list(const uint32_t *__restric
             list[pos++] = i * 32 + j;
         }
     }
-    const int padded = (n_out + 31) & ~31;
+    const int padded = (n_out + 63) & ~63;
     for (int i = n_out + threadIdx.x; i < padded; i += 1024) list[i] = -1;
 }
 
-// fp16 tiles for v_mfma_f32_16x16x32_f16: 16 rows x 32 (compacted) columns = 1024 bytes, lane l owns
-// row l%16 and columns (l/16)*8 .. +8.  Tile (r, c) at ((r * CT) + c) * 1024 with CT = ceil(n_out/32).
-// One wave per tile; the grid is fixed and strides over the tiles the call actually has, U tiles at a time:
-// the list entries of all U tiles are requested (two 16-byte loads per lane and tile), then all sources, then the
-// stores go out.  (One tile at a time, a wave spends most of its time waiting on the list -> source -> store
-// chain: 264 against 116 us per call for the weights, 86 against 61 us for the activations, averaged over the
-// linears of a 4096-row call at BLOOM-176B width.)
+// Scale of the digit form of output row n's dequantized weights: a = sw / 127 (fp32, as everywhere),
+// E = its binary exponent (not below fp16's smallest normal one), so that every fp16(code * a) is a
+// multiple of u = 2^(E - 10); m = a / u rounded to an integer (0 is possible for a row whose scale is
+// below fp16's subnormal spacing; its products can still round up to a few u).  False for a zero row.
+__device__ __forceinline__ bool digit_scale(float sw, float &a, int &E, int &m) {
+    a = sw / 127.0f;
+    E = -14;
+    m = 0;
+    if (!(a > 0.0f) || !(a < 1.0e30f)) return false;
+    E = max(ilogbf(a), -14);
+    m = (int)rintf(ldexpf(a, 10 - E));
+    return true;
+}
+
+// Digit tiles of the outlier columns, in the int8 operand order (16 rows x 64 compacted columns = 1024 bytes,
+// lane l owns row l%16 and columns (l/16)*16 .. +16).  One wave per tile; the grid is fixed and strides over the
+// tiles the call actually has, U tiles at a time: all list entries first, then all sources, then the stores.
+//
+// Activations: digit j of token tile mt, column tile ct at ((j * MTT + mt) * CT + ct) * 1024.  All
+// PS_X_DIGITS digit planes are written; count[1] receives the number of planes that hold anything (at
+// least 4), which is what the product walks.
 template <int U>
-__global__ void __launch_bounds__(64) k_gather_x(const __half *__restrict__ X, int M, int K,
-                                                    const int *__restrict__ count, const int *__restrict__ list,
-                                                    __half *__restrict__ xo) {
-    const int n_out = *count;
+__global__ void __launch_bounds__(64) k_limb_x(const __half *__restrict__ X, int M, int K, int *__restrict__ count,
+                                                 const int *__restrict__ list, int8_t *__restrict__ xl) {
+    const int n_out = count[0];
     if (n_out <= PS_EXACT_OUTLIERS) return;
-    const int CT = (n_out + 31) >> 5, MTT = (M + 15) >> 4, lane = threadIdx.x, total = MTT * CT;
+    const int CT = (n_out + 63) >> 6, MTT = (M + 15) >> 4, lane = threadIdx.x, total = MTT * CT;
+    int need = 0;
     for (int item0 = blockIdx.x; item0 < total; item0 += gridDim.x * U) {
-        int4 ia[U], ib[U];
+        int4 idx4[U][4];
         int tt[U];
 #pragma unroll
         for (int u = 0; u < U; u++) {
             const int item = min(item0 + u * (int)gridDim.x, total - 1);
             const int mt = item / CT, ct = item - mt * CT;
             tt[u] = mt * 16 + (lane & 15);
-            const int4 *lp = (const int4 *)(list + ct * 32 + (lane >> 4) * 8);
-            ia[u] = lp[0];
-            ib[u] = lp[1];
+            const int4 *lp = (const int4 *)(list + ct * 64 + (lane >> 4) * 16);
+#pragma unroll
+            for (int q = 0; q < 4; q++) idx4[u][q] = lp[q];
         }
-        v8h v[U];
+        __half xv[U][16];
 #pragma unroll
         for (int u = 0; u < U; u++) {
-            const int idx[8] = {ia[u].x, ia[u].y, ia[u].z, ia[u].w, ib[u].x, ib[u].y, ib[u].z, ib[u].w};
             const __half *row = X + (size_t)min(tt[u], M - 1) * K;
 #pragma unroll
-            for (int e = 0; e < 8; e++)
-            {
-                const _Float16 xv = (_Float16)__half2float(row[max(idx[e], 0)]);      // always in bounds
-                v[u][e] = (tt[u] < M && idx[e] >= 0) ? xv : (_Float16)0.0f;
+            for (int q = 0; q < 4; q++) {
+                const int id[4] = {idx4[u][q].x, idx4[u][q].y, idx4[u][q].z, idx4[u][q].w};
+#pragma unroll
+                for (int e = 0; e < 4; e++) xv[u][q * 4 + e] = row[max(id[e], 0)];       // always in bounds
             }
         }
 #pragma unroll
         for (int u = 0; u < U; u++) {
             const int item = item0 + u * (int)gridDim.x;
-            if (item < total) *(v8h *)(xo + ((size_t)item * 64 + lane) * 8) = v[u];
+            if (item >= total) continue;                                   // wave-uniform
+            const int mt = item / CT, ct = item - mt * CT;
+            int dig[PS_X_DIGITS][4];
+#pragma unroll
+            for (int j = 0; j < PS_X_DIGITS; j++)
+#pragma unroll
+                for (int q = 0; q < 4; q++) dig[j][q] = 0;
+#pragma unroll
+            for (int q = 0; q < 4; q++) {
+                const int id[4] = {idx4[u][q].x, idx4[u][q].y, idx4[u][q].z, idx4[u][q].w};
+#pragma unroll
+                for (int e = 0; e < 4; e++) {
+                    const bool live = tt[u] < M && id[e] >= 0;
+                    float f = live ? __half2float(xv[u][q * 4 + e]) : 0.0f;
+                    if (!(fabsf(f) <= 65504.0f)) f = 0.0f;                 // not a number / infinite: unspecified, stay defined
+                    long long I = (long long)((double)f * 16777216.0);     // exact: every fp16 value is a multiple of 2^-24
+#pragma unroll
+                    for (int j = 0; j < PS_X_DIGITS; j++) {
+                        const int d = (int)((I + 128) & 255) - 128;        // balanced digit in [-128, 127]
+                        I = (I - d) >> 8;
+                        dig[j][q] |= (d & 0xff) << (8 * e);
+                        if (d != 0) need = max(need, j + 1);
+                    }
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < PS_X_DIGITS; j++) {
+                const v4i o = {dig[j][0], dig[j][1], dig[j][2], dig[j][3]};
+                *(v4i *)(xl + ((((size_t)j * MTT + mt) * CT + ct) * 64 + lane) * 16) = o;
+            }
         }
     }
+    if (need > 4) atomicMax(count + 1, need);
 }
 
+// Weights: digit 0 (the int8 codes) of panel nt, column tile ct at ((nt) * CT + ct) * 1024, digit 1 (the
+// remainders) at ((NT + nt) * CT + ct) * 1024.
 template <int U>
-__global__ void __launch_bounds__(64) k_gather_w(LinearW w, const int *__restrict__ count,
-                                                    const int *__restrict__ list, __half *__restrict__ wo) {
-    const int n_out = *count;
+__global__ void __launch_bounds__(64) k_digit_w(LinearW w, const int *__restrict__ count,
+                                                  const int *__restrict__ list, int8_t *__restrict__ wd) {
+    const int n_out = count[0];
     if (n_out <= PS_EXACT_OUTLIERS) return;
-    const int CT = (n_out + 31) >> 5, NT = w.N >> 4, KT = w.K >> 6, lane = threadIdx.x, row = lane & 15;
+    const int CT = (n_out + 63) >> 6, NT = w.N >> 4, KT = w.K >> 6, lane = threadIdx.x, row = lane & 15;
     const int total = NT * CT;
     const int8_t *__restrict__ wt = w.wt;
     for (int item0 = blockIdx.x; item0 < total; item0 += gridDim.x * U) {
-        int4 ia[U], ib[U];
+        int4 idx4[U][4];
         int nts[U];
-        float swd[U];
+        float swr[U];
 #pragma unroll
         for (int u = 0; u < U; u++) {
             const int item = min(item0 + u * (int)gridDim.x, total - 1);
             const int nt = item / CT, ct = item - nt * CT;
             nts[u] = nt;
-            const int4 *lp = (const int4 *)(list + ct * 32 + (lane >> 4) * 8);
-            ia[u] = lp[0];
-            ib[u] = lp[1];
-            swd[u] = w.sw[nt * 16 + row];
+            const int4 *lp = (const int4 *)(list + ct * 64 + (lane >> 4) * 16);
+#pragma unroll
+            for (int q = 0; q < 4; q++) idx4[u][q] = lp[q];
+            swr[u] = w.sw[nt * 16 + row];
         }
-        int code[U][8];
+        int code[U][16];
 #pragma unroll
         for (int u = 0; u < U; u++) {
-            const int idx[8] = {ia[u].x, ia[u].y, ia[u].z, ia[u].w, ib[u].x, ib[u].y, ib[u].z, ib[u].w};
 #pragma unroll
-            for (int e = 0; e < 8; e++) {
-                const int k = max(idx[e], 0);
-                const int c = wt[((size_t)nts[u] * KT + (k >> 6)) * 1024 + (((k & 63) >> 4) * 16 + row) * 16 + (k & 15)];
-                code[u][e] = idx[e] >= 0 ? c : 0;
+            for (int q = 0; q < 4; q++) {
+                const int id[4] = {idx4[u][q].x, idx4[u][q].y, idx4[u][q].z, idx4[u][q].w};
+#pragma unroll
+                for (int e = 0; e < 4; e++) {
+                    const int k = max(id[e], 0);
+                    const int c = wt[((size_t)nts[u] * KT + (k >> 6)) * 1024 + (((k & 63) >> 4) * 16 + row) * 16 + (k & 15)];
+                    code[u][q * 4 + e] = id[e] >= 0 ? c : 0;
+                }
             }
         }
 #pragma unroll
         for (int u = 0; u < U; u++) {
-            const float s = swd[u] / 127.0f;
-            v8h v;
-#pragma unroll
-            for (int e = 0; e < 8; e++) v[e] = (_Float16)dequant_w16(code[u][e], s);
             const int item = item0 + u * (int)gridDim.x;
-            if (item < total) *(v8h *)(wo + ((size_t)item * 64 + lane) * 8) = v;
+            if (item >= total) continue;                                   // wave-uniform
+            const int ct = item - nts[u] * CT;
+            float a;
+            int E, m;
+            const bool scaled = digit_scale(swr[u], a, E, m);
+            v4i oc, orr;
+#pragma unroll
+            for (int q = 0; q < 4; q++) {
+                int pc = 0, pr = 0;
+#pragma unroll
+                for (int e = 0; e < 4; e++) {
+                    const int c = code[u][q * 4 + e];
+                    int r = 0;
+                    if (scaled) {
+                        const float v = dequant_w16(c, a);                 // the fp16 weight, as a float
+                        if (fabsf(v) <= 65504.0f) r = (int)ldexpf(v, 10 - E) - m * c;   // exact: v is a multiple of 2^(E-10)
+                    }
+                    r = min(max(r, -128), 127);                            // |r| <= 127 always holds; stay defined regardless
+                    pc |= (c & 0xff) << (8 * e);
+                    pr |= (r & 0xff) << (8 * e);
+                }
+                oc[q] = pc;
+                orr[q] = pr;
+            }
+            *(v4i *)(wd + (((size_t)nts[u] * CT + ct) * 64 + lane) * 16) = oc;
+            *(v4i *)(wd + (((size_t)(NT + nts[u]) * CT + ct) * 64 + lane) * 16) = orr;
         }
     }
+}
+
+// od[t][n] = sum over the outlier columns of x * Wd, reassembled from the digit products:
+// raw[(j * Mp + t) * ldr + d * NC + (n - n_first)] = sum_k L_j[t][k] * (d == 0 ? code : r)[n][k]  (exact int32).
+// One thread per token and 4 consecutive features.  Sums of 256^j * A_j are taken in fp64 from the top digit
+// down: exact below 2^53, i.e. always for 4 digits short of the last step, and good to 1 part in 2^53 after it.
+__global__ void __launch_bounds__(256) k_combine_digits(const int32_t *__restrict__ raw, const int *__restrict__ count,
+                                                        const float *__restrict__ sw, int M, int N, int n_first,
+                                                        int NC, double *__restrict__ od) {
+    if (count[0] <= PS_EXACT_OUTLIERS) return;
+    const int nd = count[1], Mp = ((M + 15) >> 4) * 16, q4 = NC >> 2;
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (size_t)M * q4) return;
+    const int t = (int)(i / q4), nl = (int)(i - (size_t)t * q4) * 4, ldr = 2 * NC;
+    double tc[4] = {0.0, 0.0, 0.0, 0.0}, tr[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int j = nd - 1; j >= 0; j--) {
+        const int32_t *p = raw + ((size_t)j * Mp + t) * ldr + nl;
+        const v4i ac = *(const v4i *)p, ar = *(const v4i *)(p + NC);
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            tc[e] = tc[e] * 256.0 + (double)ac[e];
+            tr[e] = tr[e] * 256.0 + (double)ar[e];
+        }
+    }
+    const float4 s4 = *(const float4 *)(sw + n_first + nl);
+    const float sv[4] = {s4.x, s4.y, s4.z, s4.w};
+    v4d o;
+#pragma unroll
+    for (int e = 0; e < 4; e++) {
+        float a;
+        int E, m;
+        digit_scale(sv[e], a, E, m);
+        o[e] = ldexp((double)m * tc[e] + tr[e], E - 34);                   // u = 2^(E-10), activations in units of 2^-24
+    }
+    *(v4d *)(od + (size_t)t * N + n_first + nl) = o;
 }
 
 // ---------------------------------------------------------------------------------------------
 // the tile pipeline
 
 struct GemmArgs {
-    const unsigned char *a_tiles;   // weight-side tiles: [N/16][KTILES][1024]
-    const unsigned char *b_tiles;   // token-side tiles:  [ceil(M/16)][KTILES][1024]
-    int ktiles;                     // int8: K/64.  fp16: 0 = derived from the outlier count, else the plain product's tile count
+    const unsigned char *a_tiles;   // weight-side tiles: [rows][KTILES][1024]
+    const unsigned char *b_tiles;   // token-side tiles:  [rows][KTILES][1024]
+    int ktiles;                     // int8: K/64.  fp16: the plain product's tile count.  digits: derived from the outlier count
     int M, N;
     int nb_n, nb_m;                 // output blocks of this launch along the features and along the tokens
     int nb_n0;                      // first feature block of this launch (a linear may be split over two launches)
@@ -165,26 +277,34 @@ struct GemmArgs {
     // of the next product's token-side operand (16 x 32 tiles, rows beyond M zero)
     const __half *gelu_pre;   // [M, N] fp16, or null
     __half *tile_out;
+    // digit product only: weight-side tile rows [a_row0, a_row0 + a_rows) of a_tiles are this launch's features;
+    // the int32 sums go to raw[token row * ldr + feature], token rows = digit planes of 16-padded M stacked
+    int a_row0, a_rows;
+    int32_t *raw;
+    int ldr;
+    float *f32_out;           // plain fp16 product: [M, N] fp32 result
 };
 
-// F16 = false: int8 main product with the full epilogue.  F16 = true: fp16 outlier product into outl.
+enum { GEMM_INT8 = 0, GEMM_F16 = 1, GEMM_DIGITS = 2 };
+
+// MODE GEMM_INT8: the regular columns with the full epilogue.  GEMM_F16: plain fp16 product (backward pass).
+// GEMM_DIGITS: int8 digit product of the outlier columns, raw int32 sums out.
 // NSLOT: LDS ring slots (NSLOT - 1 stages are requested ahead).
-template <bool F16, int WVN, int WVM, int TN, int TM, int NSLOT>
+template <int MODE, int WVN, int WVM, int TN, int TM, int NSLOT>
 __global__ void __launch_bounds__(64 * WVN * WVM, 2)   // two waves per SIMD: at most 256 registers
-k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, float *__restrict__ outl, OutDesc o,
+k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, const double *__restrict__ outl, OutDesc o,
            const SessTable *__restrict__ sess) {
+    constexpr bool F16 = MODE == GEMM_F16, DIG = MODE == GEMM_DIGITS;
     constexpr int NW = WVN * WVM, BN = WVN * TN, BM = WVM * TM, STAGE = BN + BM, LOADS = STAGE / NW;
     constexpr int PD = NSLOT - 1;                    // stages requested ahead
     static_assert(STAGE % NW == 0, "every wave copies the same number of tiles per stage");
     extern __shared__ __align__(16) unsigned char lds[];
-    // F16 with a tile count given: a plain fp16 product over ga.ktiles tiles (backward pass), no outlier set
-    const bool plain16 = F16 && ga.ktiles > 0;
-    const int n_out = plain16 ? ga.ktiles * 32 : *os.count;
-    const bool many = plain16 || n_out > PS_EXACT_OUTLIERS;
-    if (F16 && !many) return;
+    const int n_out = F16 ? ga.ktiles * 32 : os.count[0];
+    const bool many = F16 || n_out > PS_EXACT_OUTLIERS;
+    if (DIG && !many) return;
     // k-tiles to walk (64 int8 or 32 fp16 columns each).  If EVERY column is an outlier all int8 codes are
     // zero: the int8 product is skipped and only the epilogue runs.
-    const int NS = F16 ? (n_out + 31) >> 5 : (n_out == ga.ktiles * 64 ? 0 : ga.ktiles);
+    const int NS = F16 ? ga.ktiles : DIG ? (n_out + 63) >> 6 : (n_out == ga.ktiles * 64 ? 0 : ga.ktiles);
 
     // Workgroup -> output block.  Consecutive workgroup ids land on different XCDs (8 of them, each
     // with its own L2); give each XCD a contiguous run of blocks, ordered in strips of STRIP
@@ -197,17 +317,22 @@ k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, 
     const int rem = ord - strip * STRIP * nb_n, sw_this = min(STRIP, nb_m - strip * STRIP);
     const int bn = rem / sw_this, bm = strip * STRIP + rem % sw_this;
 
-    const int M = ga.M, N = ga.N, NT = N >> 4, MTT = (M + 15) >> 4;
+    const int M = ga.M, N = ga.N;
+    // tile rows on either side: the digit product stacks count[1] digit planes of the 16-padded token rows and
+    // takes its features from a window of the digit tile array
+    const int NT = DIG ? ga.a_rows : N >> 4, MTT = DIG ? os.count[1] * ((M + 15) >> 4) : (M + 15) >> 4;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, row = lane & 15, kg = lane >> 4;
     const int wn = wave / WVM, wm = wave % WVM;
     const int nt0 = (ga.nb_n0 + bn) * BN, mt0 = bm * BM;
+    if (DIG && mt0 >= MTT) return;                   // a digit plane nobody needs (the grid is sized for all of them)
+    const int a_row0 = DIG ? ga.a_row0 : 0;
 
     // the stage tiles this wave copies: s = wave + NW*j; s < BN: weight tile, else token tile
     const unsigned char *src[LOADS];
 #pragma unroll
     for (int j = 0; j < LOADS; j++) {
         const int s = wave + NW * j;
-        if (s < BN) src[j] = ga.a_tiles + (size_t)min(nt0 + s, NT - 1) * NS * 1024 + lane * 16;
+        if (s < BN) src[j] = ga.a_tiles + (size_t)(a_row0 + min(nt0 + s, NT - 1)) * NS * 1024 + lane * 16;
         else src[j] = ga.b_tiles + (size_t)min(mt0 + s - BN, MTT - 1) * NS * 1024 + lane * 16;
     }
 
@@ -341,7 +466,20 @@ k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, 
     constexpr int QN = TN / 2, NPARK = 2;                                // weight panels per parked half
     static_assert(TN % 8 == 0, "a stage is multiplied in eighths; the epilogue parks half of the accumulators at a time");
     acc_t *mine = (acc_t *)lds + (size_t)wave * (QN * TM * 64) + lane;
-    if constexpr (F16) {
+    if constexpr (DIG) {
+        // raw sums: D[lane][r] = feature 4 * (l/16) + r of the weight tile, token row l%16 of the token tile
+#pragma unroll
+        for (int i = 0; i < TN; i++) {
+            const int nt = nt0 + wn * TN + i;
+            if (nt >= NT) continue;                                      // wave-uniform
+#pragma unroll
+            for (int j = 0; j < TM; j++) {
+                const int mt = mt0 + wm * TM + j;
+                if (mt >= MTT) continue;                                 // wave-uniform
+                *(v4i *)(ga.raw + (size_t)(mt * 16 + row) * ga.ldr + nt * 16 + 4 * kg) = acc[i][j];
+            }
+        }
+    } else if constexpr (F16) {
 #pragma unroll
         for (int p = 0; p < NPARK; p++) {
 #pragma unroll
@@ -363,7 +501,7 @@ k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, 
                     }
                     *(v4h *)(ga.tile_out + (((size_t)mt * (N >> 5) + (n0 >> 5)) * 64 + row + 16 * ((n0 & 31) >> 3)) * 8 + (n0 & 7)) = du;
                 } else if (t < M) {
-                    *(v4f *)(outl + (size_t)t * N + n0) = mine[idx * 64];
+                    *(v4f *)(ga.f32_out + (size_t)t * N + n0) = mine[idx * 64];
                 }
             }
         }
@@ -447,10 +585,7 @@ k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, 
                     const int t = trow[j];
                     v4d od = {0.0, 0.0, 0.0, 0.0};
                     if (many) {
-                        if (t >= 0) {
-                            const v4f f = *(const v4f *)(outl + (size_t)t * N + n0);
-                            od = (v4d){(double)f[0], (double)f[1], (double)f[2], (double)f[3]};
-                        }
+                        if (t >= 0) od = *(const v4d *)(outl + (size_t)t * N + n0);
                     } else if (nch > 0) {
 #pragma unroll
                         for (int c = 0; c < XC; c++)
@@ -502,22 +637,24 @@ k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, 
     }
 }
 
-template <bool F16, int TM>
-hipError_t launch_one(const GemmArgs &ga, const LinearW &w, const float *sx, const OutlierSet &os, float *outl,
+template <int MODE, int TM>
+hipError_t launch_one(const GemmArgs &ga, const LinearW &w, const float *sx, const OutlierSet &os, const double *outl,
                       const OutDesc &o, const SessTable *sess, hipStream_t st) {
     constexpr int WVN = 2, WVM = 4, TN = 8, NSLOT = 4, BN = WVN * TN, BM = WVM * TM;   // 8 waves, 128 x (16 TM) per wave
     const int total = ga.nb_n * ga.nb_m;
     const size_t lds_stage = (size_t)NSLOT * (BN + BM) * 1024;
     const size_t lds_epi = (size_t)WVN * WVM * (TN / 2) * TM * 1024 + (size_t)BN * 16 * 16 + (size_t)BN * 4 * 8 + (size_t)BN / 2 * 4;
     const size_t lds = lds_stage > lds_epi ? lds_stage : lds_epi;
-    auto kern = k_gemm_lds<F16, WVN, WVM, TN, TM, NSLOT>;
+    auto kern = k_gemm_lds<MODE, WVN, WVM, TN, TM, NSLOT>;
     static std::mutex attr_lock;
     static bool attr_set = false;
-    std::lock_guard<std::mutex> hold(attr_lock);
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
+    {
+        std::lock_guard<std::mutex> hold(attr_lock);
+        if (!attr_set) {
+            hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            attr_set = true;
+        }
     }
     kern<<<((total + 7) / 8) * 8, 64 * WVN * WVM, lds, st>>>(ga, w, sx, os, outl, o, sess);
     return hipGetLastError();
@@ -528,8 +665,8 @@ hipError_t launch_one(const GemmArgs &ga, const LinearW &w, const float *sx, con
 // rounds for the work of 3.5).  In that case the feature blocks of the last round go to a second launch with
 // blocks of half the token height (256 x 128, 128 x 32 per wave), which fills all units for a shorter round
 // (measured: 2 to 4 % of the linear's time; 4-wave workgroups with a 3-slot ring, two per unit, were slower).
-template <bool F16>
-hipError_t launch_lds(const GemmArgs &ga0, const LinearW &w, const float *sx, const OutlierSet &os, float *outl,
+template <int MODE>
+hipError_t launch_lds(const GemmArgs &ga0, const LinearW &w, const float *sx, const OutlierSet &os, const double *outl,
                       const OutDesc &o, const SessTable *sess, hipStream_t st) {
     constexpr int BN = 16, BM = 16, UNITS = 256;
     GemmArgs ga = ga0;
@@ -544,11 +681,22 @@ hipError_t launch_lds(const GemmArgs &ga0, const LinearW &w, const float *sx, co
         ga.nb_n -= gb.nb_n;
         gb.nb_n0 = ga.nb_n;
         gb.nb_m = (MTT + BM / 2 - 1) / (BM / 2);
-        hipError_t e = launch_one<F16, 4>(ga, w, sx, os, outl, o, sess, st);
+        hipError_t e = launch_one<MODE, 4>(ga, w, sx, os, outl, o, sess, st);
         if (e != hipSuccess) return e;
-        return launch_one<F16, 2>(gb, w, sx, os, outl, o, sess, st);
+        return launch_one<MODE, 2>(gb, w, sx, os, outl, o, sess, st);
     }
-    return launch_one<F16, 4>(ga, w, sx, os, outl, o, sess, st);
+    return launch_one<MODE, 4>(ga, w, sx, os, outl, o, sess, st);
+}
+
+GemmArgs gemm_args(const void *a_tiles, const void *b_tiles, int ktiles, int M, int N) {
+    GemmArgs g;
+    memset(&g, 0, sizeof(g));
+    g.a_tiles = (const unsigned char *)a_tiles;
+    g.b_tiles = (const unsigned char *)b_tiles;
+    g.ktiles = ktiles;
+    g.M = M;
+    g.N = N;
+    return g;
 }
 
 }  // namespace
@@ -557,29 +705,51 @@ hipError_t ps_gemm_f16_tiles(const __half *feat_tiles, const __half *tok_tiles, 
                              float *out, const __half *gelu_pre, __half *tile_out, hipStream_t st) {
     if (ktiles < 1 || M < 1 || n_feat < 16 || n_feat % 16) return hipErrorInvalidValue;
     if (gelu_pre && (!tile_out || n_feat % 32)) return hipErrorInvalidValue;
-    GemmArgs ga = {(const unsigned char *)feat_tiles, (const unsigned char *)tok_tiles, ktiles, M, n_feat, 0, 0, 0,
-                   gelu_pre, tile_out};
+    GemmArgs ga = gemm_args(feat_tiles, tok_tiles, ktiles, M, n_feat);
+    ga.gelu_pre = gelu_pre;
+    ga.tile_out = tile_out;
+    ga.f32_out = out;
     LinearW w;
     OutlierSet os;
     OutDesc o;
     memset(&w, 0, sizeof(w));
     memset(&os, 0, sizeof(os));
     memset(&o, 0, sizeof(o));
-    return launch_lds<true>(ga, w, nullptr, os, out, o, nullptr, st);
+    return launch_lds<GEMM_F16>(ga, w, nullptr, os, nullptr, o, nullptr, st);
 }
+
+size_t ps_many_chunk_features(int N) { return (size_t)(N < PS_MANY_CHUNK ? N : PS_MANY_CHUNK); }
 
 hipError_t ps_gemm_lds(const LinearW &w, const int8_t *xq_tiled, const uint32_t *mask, const __half *X, const float *sx,
                        int M, const OutlierSet &os, const ManyOutliers &mo, const OutDesc &o, const SessTable *sess,
                        hipStream_t st) {
-    // the outlier-heavy case first (all four kernels return at once when the call has few outlier columns)
+    // The outlier-heavy case first (every kernel of it returns at once when the call has few outlier columns):
+    // column list, digit tiles of the activations and of the dequantized weights, then per chunk of output
+    // features the two digit products (codes, remainders) and their reassembly into od[M, N].
     k_outlier_list<<<1, 1024, 0, st>>>(mask, w.K, os.count, mo.list);
-    k_gather_x<4><<<2048, 64, 0, st>>>(X, M, w.K, os.count, mo.list, mo.xo);
-    k_gather_w<4><<<4096, 64, 0, st>>>(w, os.count, mo.list, mo.wo);
+    k_limb_x<2><<<2048, 64, 0, st>>>(X, M, w.K, (int *)os.count, mo.list, mo.xl);
+    k_digit_w<2><<<4096, 64, 0, st>>>(w, os.count, mo.list, mo.wd);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    GemmArgs gf = {(const unsigned char *)mo.wo, (const unsigned char *)mo.xo, 0, M, w.N, 0, 0, 0, nullptr, nullptr};
-    e = launch_lds<true>(gf, w, sx, os, mo.outl, o, sess, st);
-    if (e != hipSuccess) return e;
-    GemmArgs gi = {(const unsigned char *)w.wt, (const unsigned char *)xq_tiled, w.K / 64, M, w.N, 0, 0, 0, nullptr, nullptr};
-    return launch_lds<false>(gi, w, sx, os, mo.outl, o, sess, st);
+    const int NT = w.N / 16, MTT = (M + 15) / 16, NC = (int)ps_many_chunk_features(w.N);
+    for (int n0 = 0; n0 < w.N; n0 += NC) {
+        const int nc = min(NC, w.N - n0);
+        for (int d = 0; d < 2; d++) {
+            GemmArgs gd = gemm_args(mo.wd, mo.xl, 0, M, nc);
+            gd.a_row0 = d * NT + n0 / 16;
+            gd.a_rows = nc / 16;
+            gd.raw = mo.raw + (size_t)d * nc;
+            gd.ldr = 2 * nc;
+            gd.nb_n = (nc / 16 + 15) / 16;
+            gd.nb_m = (PS_X_DIGITS * MTT + 15) / 16;
+            e = launch_one<GEMM_DIGITS, 4>(gd, w, sx, os, nullptr, o, sess, st);
+            if (e != hipSuccess) return e;
+        }
+        const size_t quads = (size_t)M * (nc / 4);
+        k_combine_digits<<<(unsigned)((quads + 255) / 256), 256, 0, st>>>(mo.raw, os.count, w.sw, M, w.N, n0, nc, mo.od);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    GemmArgs gi = gemm_args(w.wt, xq_tiled, w.K / 64, M, w.N);
+    return launch_lds<GEMM_INT8>(gi, w, sx, os, mo.od, o, sess, st);
 }

@@ -51,7 +51,7 @@ def _grad(cfg, B, T, seed):
     return np.random.default_rng([cfg.seed, 77, seed]).standard_normal((B, T, cfg.hidden)).astype(np.float16)
 
 
-def _check(cfg, nb, B, T, wscale, seed=0, min_branch=0.05, strict=True):
+def _check(cfg, nb, B, T, wscale, seed=0, min_branch=0.05):
     osp, gsp, params = _pair(cfg, nb, B * T, wscale)
     try:
         X = synth.hidden_states(cfg, 0, B, T)
@@ -61,19 +61,8 @@ def _check(cfg, nb, B, T, wscale, seed=0, min_branch=0.05, strict=True):
         Y, dX = gsp.backward(to_dev(X), to_dev(dY))
         torch.cuda.synchronize()
         Y, dX = to_np(Y), to_np(dX)
-        if strict:
-            hidden_close(Y, Y_ref, "forward output")
-            rel, mx = grad_close(dX, dX_ref)
-        else:
-            # A linear with more than 64 outlier columns multiplies them on the fp16 matrix cores with fp32
-            # accumulation, so a few outputs differ from the oracle by one fp16 ulp; downstream such a difference
-            # can move a value across the outlier threshold and so change the int8 scale of a whole row, in the
-            # forward pass already.  Such cases are judged by the relative L2 error alone.
-            f64 = lambda a: a.astype(np.float64)
-            fwd = np.linalg.norm(f64(Y) - f64(Y_ref)) / np.linalg.norm(f64(Y_ref))
-            rel = np.linalg.norm(f64(dX) - f64(dX_ref)) / np.linalg.norm(f64(dX_ref))
-            mx = np.abs(f64(dX) - f64(dX_ref)).max()
-            assert fwd <= 3e-3 and rel <= 3e-3, (fwd, rel)
+        hidden_close(Y, Y_ref, "forward output")
+        rel, mx = grad_close(dX, dX_ref)
         print("  gradient rel-L2 %.2e max-abs %.2e" % (rel, mx), flush=True)
         # the case exercises the branches, not just the residual path
         branch = np.linalg.norm(dX_ref.astype(np.float64) - dY.astype(np.float64)) / np.linalg.norm(dY.astype(np.float64))
@@ -204,15 +193,15 @@ def test_backward_argument_errors():
         osp.destroy()
 
 
-@pytest.mark.parametrize("wscale,strict", [(0.5, True), (1.0, False)])
-def test_backward_c4_width_one_block_ragged_rows(wscale, strict):
+@pytest.mark.parametrize("wscale", [0.5, 1.0])
+def test_backward_c4_width_one_block_ragged_rows(wscale):
     """One BLOOM-176B-shaped block, 2 sequences of 40 tokens: 80 rows take the same LDS-pipelined kernels as the
     benchmark's 4096-row calls (more than 64 rows), with a ragged last row tile.  With the recipe's weights
-    (wscale 1) the dense and down linears see thousands of outlier columns; with weights half as large every
-    linear stays at 64 outlier columns or fewer, the forward pass is bit-identical to the oracle's and the full
-    tolerance applies."""
+    (wscale 1) the dense and down linears see thousands of outlier columns (the forward pass adds them through
+    exact int8 digit products); with weights half as large every linear stays at 64 outlier columns or fewer.
+    The full tolerance applies either way."""
     cfg = synth.CONFIGS["C4"]
-    _check(cfg, 1, 2, 40, wscale=wscale, seed=9, min_branch=0.2, strict=strict)
+    _check(cfg, 1, 2, 40, wscale=wscale, seed=9, min_branch=0.2)
 
 
 def test_backward_products_at_full_size_sampled_against_the_oracle():
