@@ -67,8 +67,12 @@ def main():
     ap.add_argument("--prefix", type=int, default=2048, help="KV-cache prefix length of the headline figure")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile-events", action="store_true")
-    ap.add_argument("--mode", choices=["decode", "prefill", "batched", "generate", "backward"], default="decode",
-                    help="decode: the headline batch-1 decode benchmark; prefill: secondary, int8 MFMA GEMM regime; "
+    ap.add_argument("--no-secondary", action="store_true",
+                    help="decode mode: leave out the prefill call and the batched configuration (config.prefill, config.batched)")
+    ap.add_argument("--mode", choices=["decode", "prefill", "batched", "generate", "backward", "mfma-peak"], default="decode",
+                    help="decode: the headline batch-1 decode benchmark (its line also carries a prefill call and a batched "
+                         "decode configuration as config.prefill / config.batched); mfma-peak: register-only loop of the "
+                         "int8 matrix instruction; prefill: secondary, int8 MFMA GEMM regime; "
                          "batched: secondary, several sessions per decode step; generate: secondary, greedy "
                          "generation loop with the client-side embedding and LM head on the same GPU; backward: secondary, "
                          "forward + backward (gradients w.r.t. activations) of a fine-tuning batch")
@@ -107,13 +111,17 @@ def main():
         return generate_main(args, dev)
     if args.mode == "backward":
         return backward_main(args, dev)
+    if args.mode == "mfma-peak":
+        return mfma_peak_main(args, dev)
     cfg = synth.CONFIGS["C4"]
     H, F, nh, NB = cfg.hidden, cfg.F, cfg.n_heads, cfg.n_blocks
     K, W = args.steps, args.warmup
     prefixes = sorted(set(cfg.prefixes) | {args.prefix})
 
     t_setup = time.time()
-    span = binding.Span(NB, H, nh, F, 1, 1e-5, 6.0, dev)
+    # sized for the 8 x 512 prefill call of the secondary figure too (the decode steps use one row of it)
+    PRE_B, PRE_T = 8, 512
+    span = binding.Span(NB, H, nh, F, 1 if args.no_secondary else PRE_B * PRE_T, 1e-5, 6.0, dev)
     block0_host = None
     for b in range(NB):
         p = _block_params(args, cfg, b, dev)
@@ -179,7 +187,9 @@ def main():
     main_r = results[args.prefix]
     # dominant kernel: the one-row int8 linear (4 launches per block), from the events of the headline run
     roofline = {"bound": "hbm", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None,
-                "traffic": traffic_from_profile(), "kernel": "k_gemv_row"}
+                "traffic": traffic_from_profile(),
+                "traffic_source": "committed rocprofv3 counter summary profiles/k_gemv_row_c4_decode_pmc.txt, not this run",
+                "kernel": "k_gemv_row"}
     if main_r["prof"] is not None:
         ms_cls, n_cls = main_r["prof"]
         n_gemv = n_cls[binding.PROFILE_GEMV]
@@ -191,6 +201,31 @@ def main():
                             avg_launch_us=round(ms_cls[binding.PROFILE_GEMV] * 1e3 / n_gemv, 2), launches=n_gemv,
                             bytes_per_launch=round(per_block / 4.0),
                             attention_ms_per_step=round(ms_cls[binding.PROFILE_ATTENTION] / K, 4))
+
+    # secondary figures, timed after the headline: one prefill call of 8 x 512 tokens through the same span
+    # (int8 MFMA GEMM regime) and batched decode steps of the 30-block BLOOM-7B1-shaped configuration
+    secondary = {}
+    if not args.no_secondary:
+        r = measure_prefill(args, span, dev, PRE_B, PRE_T, steps=2, warmup=1)
+        secondary["prefill"] = {"workload": "%d sessions x %d tokens through the same 12-block span (%d rows per linear)"
+                                            % (PRE_B, PRE_T, r["rows"]),
+                                "ms_per_call": round(r["ms_per_call"], 3), "tokens_per_s": round(r["tokens_per_s"], 1),
+                                "int8_top_s": round(r["int8_top_s"], 1), "mfma_frac": round(r["int8_top_s"] / 5000.0, 4),
+                                "mfma_kernel": "k_gemm_lds on the QKV and up linears, against the 5000 TOP/s dense int8 peak",
+                                "per_block_ms": r["per_block_ms"], "per_linear_top_s": r["per_linear_top_s"]}
+        print("[bench] prefill %d x %d: %.1f ms per call, int8 GEMM %.0f TOP/s" %
+              (PRE_B, PRE_T, r["ms_per_call"], r["int8_top_s"]), file=sys.stderr, flush=True)
+    span.close()
+    del span
+    torch.cuda.empty_cache()
+    if not args.no_secondary:
+        r = measure_batched(args, dev, "C3", 32, 4)
+        secondary["batched"] = {"workload": r["name"] + ", 512-token prompts, one token per session per step, 8-bit codec "
+                                            "at the span boundary",
+                                "ms_per_step": round(r["ms_per_step"], 4), "tokens_per_s": round(r["tokens_per_s"], 1),
+                                "hbm_frac": round(r["hbm_frac"], 4), "linears_ms_per_step": round(r["linears_ms_per_step"], 4),
+                                "attention_ms_per_step": round(r["attention_ms_per_step"], 4)}
+        print("[bench] batched C3: %.3f ms per step" % r["ms_per_step"], file=sys.stderr, flush=True)
 
     cpu_baseline = None
     if block0_host is not None:
@@ -209,29 +244,20 @@ def main():
                                           "achieved_hbm_gbs": round(r["gbs"], 1)} for L, r in results.items()}},
         "roofline": roofline, "cpu_baseline": cpu_baseline,
     }
-    span.close()
+    line["config"].update(secondary)
     _emit(args, line)
 
 
-def prefill_main(args, dev):
-    """Secondary benchmark: a prefill call (sessions x 512 new tokens) through a 12-block BLOOM-176B-shaped span.
-    One step = one prefill call on fresh sessions.  Reports tokens/s and, for the dominant kernel (the LDS-staged
-    int8 MFMA GEMM, here on the QKV and up linears whose inputs carry few outlier columns), int8 TOP/s against
-    the 5 POP/s dense int8 peak.  With the synthetic N(0, 0.02) weights the inputs of the dense and down linears
-    have Gaussian tails beyond the threshold in almost every column at this row count, so those two run on the
-    fp16 outlier path; their time is reported separately."""
-    import numpy as np
+def measure_prefill(args, span, dev, B, T=512, steps=2, warmup=1):
+    """One prefill call (B sessions x T new tokens on fresh sessions) through `span`, timed over `steps` calls;
+    a further call brackets every linear and the attention with HIP events.  Returns per-call and per-linear
+    figures; int8_top_s is the int8 MFMA rate of the QKV and up linears (whose inputs carry few outlier columns,
+    so their time is the int8 kernel's)."""
     import torch
     from paper_2209_01188_amd import binding, synth
 
     cfg = synth.CONFIGS["C4"]
-    H, F, nh, NB = cfg.hidden, cfg.F, cfg.n_heads, cfg.n_blocks
-    B, T = args.prefill_batch, 512
-    M = B * T
-    K_steps, W = max(1, min(args.steps, 4)), max(1, min(args.warmup, 1))
-    span = binding.Span(NB, H, nh, F, M, 1e-5, 6.0, dev)
-    for b in range(NB):
-        span.load_block(b, _block_params(args, cfg, b, dev))
+    NB, M = span.n_blocks, B * T
     X = torch.from_numpy(synth.hidden_states(cfg, 0, B, T)).to(dev)
     out = torch.empty_like(X)
     kv = [torch.zeros(binding.petals_span_kv_bytes(span.cfg, T), dtype=torch.uint8, device=dev) for _ in range(B)]
@@ -247,14 +273,14 @@ def prefill_main(args, dev):
         for s in ses:
             binding.petals_session_close(s)
 
-    for _ in range(W):
+    for _ in range(warmup):
         close(one_call())
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record(stream)
-    opened = [one_call() for _ in range(K_steps)]
+    opened = [one_call() for _ in range(steps)]
     e1.record(stream)
     torch.cuda.synchronize()
-    ms = e0.elapsed_time(e1) / K_steps
+    ms = e0.elapsed_time(e1) / steps
     for ses in opened:
         close(ses)
     binding.petals_span_profile_begin(span.handle, NB * 8)
@@ -265,23 +291,89 @@ def prefill_main(args, dev):
     ops = [2.0 * M * n * k for n, k in (span.shapes(i) for i in range(4))]
     lin_ms = [pm[binding.PROFILE_LINEAR0 + i] / NB for i in range(4)]
     int8_ops, int8_ms = ops[0] + ops[2], lin_ms[0] + lin_ms[2]
-    achieved = int8_ops / (int8_ms * 1e-3) / 1e12
+    names = ("qkv", "dense", "up", "down")
+    return {"ms_per_call": ms, "tokens_per_s": M / (ms * 1e-3), "rows": M, "sessions": B, "tokens_per_session": T,
+            "int8_top_s": int8_ops / (int8_ms * 1e-3) / 1e12,
+            "per_block_ms": dict({n: round(lin_ms[i], 3) for i, n in enumerate(names)},
+                                 attention=round(pm[binding.PROFILE_ATTENTION] / NB, 3)),
+            "per_linear_top_s": {n: round(ops[i] / (lin_ms[i] * 1e-3) / 1e12, 1) for i, n in enumerate(names)}}
+
+
+def prefill_main(args, dev):
+    """Secondary benchmark: a prefill call (sessions x 512 new tokens) through a 12-block BLOOM-176B-shaped span.
+    One step = one prefill call on fresh sessions.  Reports tokens/s and, for the dominant kernel (the LDS-staged
+    int8 MFMA GEMM, here on the QKV and up linears whose inputs carry few outlier columns), int8 TOP/s against
+    the 5 POP/s dense int8 peak.  With the synthetic N(0, 0.02) weights the inputs of the dense and down linears
+    have Gaussian tails beyond the threshold in thousands of columns at this row count, so those two also run the
+    exact int8 digit products of their outlier columns; their time is reported separately."""
+    from paper_2209_01188_amd import binding, synth
+
+    cfg = synth.CONFIGS["C4"]
+    H, F, nh, NB = cfg.hidden, cfg.F, cfg.n_heads, cfg.n_blocks
+    B, T = args.prefill_batch, 512
+    M = B * T
+    K_steps, W = max(1, min(args.steps, 4)), max(1, min(args.warmup, 1))
+    span = binding.Span(NB, H, nh, F, M, 1e-5, 6.0, dev)
+    for b in range(NB):
+        span.load_block(b, _block_params(args, cfg, b, dev))
+    r = measure_prefill(args, span, dev, B, T, K_steps, W)
+    achieved = r["int8_top_s"]
     line = {
-        "metric": "prefill tokens/s per 12-block BLOOM-176B span; int8 MFMA TOP/s", "value": round(M / (ms * 1e-3), 1),
-        "unit": "tokens/s", "n_gpus": 1, "steps": K_steps, "warmup": W, "ms_per_step": round(ms, 3),
+        "metric": "prefill tokens/s per 12-block BLOOM-176B span; int8 MFMA TOP/s", "value": round(r["tokens_per_s"], 1),
+        "unit": "tokens/s", "n_gpus": 1, "steps": K_steps, "warmup": W, "ms_per_step": round(r["ms_per_call"], 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": "12-block BLOOM-176B-shaped span (H=14336, F=57344), prefill of %d sessions x 512 tokens "
                                "(%d rows per linear)" % (B, M),
-                   "per_block_ms": {"qkv": round(lin_ms[0], 3), "dense": round(lin_ms[1], 3), "up": round(lin_ms[2], 3),
-                                    "down": round(lin_ms[3], 3), "attention": round(pm[binding.PROFILE_ATTENTION] / NB, 3)},
-                   "per_linear_top_s": {n: round(ops[i] / (lin_ms[i] * 1e-3) / 1e12, 1) for i, n in
-                                        enumerate(("qkv", "dense", "up", "down"))}},
+                   "per_block_ms": r["per_block_ms"], "per_linear_top_s": r["per_linear_top_s"]},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 1), "peak": 5000.0, "unit": "TOP/s",
                      "frac": round(achieved / 5000.0, 4), "traffic": None, "kernel": "k_gemm_lds (qkv and up linears)"},
         "cpu_baseline": None,
     }
     span.close()
     _emit(args, line)
+
+
+def mfma_peak_main(args, dev):
+    """What the int8 matrix pipes sustain with no memory traffic: a register-only loop of the matrix instruction
+    the prefill linear uses (and of its 32x32x32 sibling), with operands of one constant byte and of pseudo-random
+    bytes.  One step = one launch of the loop on 512 workgroups of 4 waves (two per compute unit)."""
+    import torch
+    from paper_2209_01188_amd import binding
+
+    wgs, iters = 512, 20000
+    out = torch.empty(wgs * 256, dtype=torch.int32, device=dev)
+    stream = torch.cuda.current_stream()
+    res = {}
+    for kind, kname in ((0, "v_mfma_i32_16x16x64_i8"), (1, "v_mfma_i32_32x32x32_i8")):
+        for rnd, rname in ((0, "constant"), (1, "random")):
+            for _ in range(max(1, args.warmup)):
+                binding.petals_bench_mfma(kind, rnd, iters, wgs, out)
+            torch.cuda.synchronize()
+            best = None
+            for _ in range(max(1, min(args.steps, 8))):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                ops = binding.petals_bench_mfma(kind, rnd, iters, wgs, out)
+                e1.record(stream)
+                torch.cuda.synchronize()
+                ms = e0.elapsed_time(e1)
+                best = ms if best is None else min(best, ms)
+            tops = ops / (best * 1e-3) / 1e12
+            # 256 compute units x 4 SIMDs x 2048 int8 operations per clock at the data-sheet rate
+            res["%s, %s operands" % (kname, rname)] = {"top_s": round(tops, 1), "frac_of_5000": round(tops / 5000.0, 4),
+                                                       "ms": round(best, 3),
+                                                       "implied_clock_ghz": round(tops * 1e12 / (256 * 4 * 2048) / 1e9, 3)}
+            print("[bench] %s, %s operands: %.0f TOP/s" % (kname, rname, tops), file=sys.stderr, flush=True)
+    key = "v_mfma_i32_16x16x64_i8, random operands"
+    line = {"metric": "sustained int8 MFMA TOP/s, register-only loop", "value": res[key]["top_s"], "unit": "TOP/s",
+            "n_gpus": 1, "steps": max(1, min(args.steps, 8)), "warmup": max(1, args.warmup), "ms_per_step": res[key]["ms"],
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+            "config": {"workload": "register-only loop of the int8 matrix instruction, 512 workgroups x 4 waves x %d "
+                                   "iterations, no memory traffic" % iters, "variants": res},
+            "roofline": {"bound": "mfma", "achieved": res[key]["top_s"], "peak": 5000.0, "unit": "TOP/s",
+                         "frac": res[key]["frac_of_5000"], "traffic": None, "kernel": "k_mfma_loop"},
+            "cpu_baseline": None}
+    print(json.dumps(line))
 
 
 def backward_main(args, dev):
@@ -357,8 +449,8 @@ def backward_main(args, dev):
     _emit(args, line)
 
 
-def batched_main(args, dev):
-    """Secondary benchmark: decode steps with several sessions in one call (one new token per session), hidden
+def measure_batched(args, dev, which, K, W):
+    """ decode steps with several sessions in one call (one new token per session), hidden
     states crossing the span boundary as blockwise 8-bit codes.  The prompts (512 tokens per session) go through
     the library's own prefill first.  One step = dequantize the incoming codes, one decode step for all sessions,
     quantize the result.  Reports aggregate tokens/s and, for the dominant kernel (the batched-decode int8
@@ -367,16 +459,13 @@ def batched_main(args, dev):
     import torch
     from paper_2209_01188_amd import binding, synth
 
-    if args.batched_config == "C5":
-        return c5_main(args, dev)
-    if args.batched_config == "C3":
+    if which == "C3":
         cfg, NB, B = synth.CONFIGS["C3"], synth.CONFIGS["C3"].n_blocks, synth.CONFIGS["C3"].batch
         name = "C3: 30-block BLOOM-7B1-shaped span (H=4096, 32 heads, F=16384), %d sessions" % B
     else:
         cfg, NB, B = synth.CONFIGS["C4"], 12, 32
         name = "one 12-block span of C5 (H=14336, 112 heads, F=57344), %d sessions" % B
     H, F, nh, T = cfg.hidden, cfg.F, cfg.n_heads, 512
-    K, W = args.steps, args.warmup
     chunk = max(1, min(B, 4096 // T))                      # sessions per prefill call
     span = binding.Span(NB, H, nh, F, max(B, chunk * T), 1e-5, 6.0, dev)
     for b in range(NB):
@@ -403,9 +492,10 @@ def batched_main(args, dev):
     ao = torch.empty(nblk, dtype=torch.float32, device=dev)
     stream = torch.cuda.current_stream()
 
-    def step(i):
-        binding.petals_hidden_dequantize(codes[i], absmax[i], CB, xin)
-        span.decode_step(ses, xin, out)
+    handles = [s.handle for s in ses]
+
+    def step(i):                                            # codes in (decoded inside the first LayerNorm), codes out
+        binding.petals_span_prefill_q8(span.handle, handles, 1, codes[i], absmax[i], CB, out)
         binding.petals_hidden_quantize(out, CB, qo, ao)
 
     for i in range(W):
@@ -425,6 +515,7 @@ def batched_main(args, dev):
     for s0 in range(0, B, chunk):
         span.prefill(ses[s0:s0 + chunk], torch.from_numpy(Xp[s0:s0 + chunk]).to(dev))
     torch.cuda.synchronize()
+    handles = [s.handle for s in ses]
     binding.petals_span_profile_begin(span.handle, NB * 8)
     step(W)
     torch.cuda.synchronize()
@@ -434,24 +525,39 @@ def batched_main(args, dev):
     total_bytes = NB * (12 * H * H + 62 * H) + B * NB * (4 * (L + 1) * H + 4 * H) + 2 * B * H * 3
     gemm_ms, n_gemm = pm[binding.PROFILE_GEMM], pn[binding.PROFILE_GEMM]
     achieved = wbytes / (gemm_ms * 1e-3) / 1e9 if n_gemm else None
+    span.close()
+    return {"name": name, "sessions": B, "ms_per_step": ms, "tokens_per_s": B / (ms * 1e-3),
+            "hbm_gbs_whole_step": total_bytes / (ms * 1e-3) / 1e9,
+            "hbm_frac": total_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "linears_ms_per_step": gemm_ms, "attention_ms_per_step": pm[binding.PROFILE_ATTENTION],
+            "gemm_launches": n_gemm, "gemm_gbs": achieved,
+            "per_linear_gbs": {n: round(NB * gemv_bytes(*span.shapes(i)) / (pm[binding.PROFILE_LINEAR0 + i] * 1e-3) / 1e9, 1)
+                               for i, n in enumerate(("qkv", "dense", "up", "down")) if pm[binding.PROFILE_LINEAR0 + i] > 0}}
+
+
+def batched_main(args, dev):
+    """Secondary benchmark: decode steps with several sessions in one call (see measure_batched)."""
+    if args.batched_config == "C5":
+        return c5_main(args, dev)
+    r = measure_batched(args, dev, args.batched_config, args.steps, args.warmup)
+    achieved = r["gemm_gbs"]
     line = {
         "metric": "decode tokens/s per span, all sessions of the call together; achieved HBM GB/s",
-        "value": round(B / (ms * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
-        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": round(r["tokens_per_s"], 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(r["ms_per_step"], 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8", "data": "synthetic",
-        "config": {"workload": name + ", 512-token prompts, one token per session per step, 8-bit codec at the span "
-                               "boundary", "sessions": B,
-                   "achieved_hbm_gbs": round(total_bytes / (ms * 1e-3) / 1e9, 1),
-                   "hbm_frac_whole_step": round(total_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                   "linears_ms_per_step": round(gemm_ms, 4), "attention_ms_per_step": round(pm[binding.PROFILE_ATTENTION], 4),
-                   "per_linear_gbs": {n: round(NB * gemv_bytes(*span.shapes(i)) / (pm[binding.PROFILE_LINEAR0 + i] * 1e-3) / 1e9, 1)
-                                      for i, n in enumerate(("qkv", "dense", "up", "down")) if pm[binding.PROFILE_LINEAR0 + i] > 0}},
+        "config": {"workload": r["name"] + ", 512-token prompts, one token per session per step, 8-bit codec at the span "
+                               "boundary", "sessions": r["sessions"],
+                   "achieved_hbm_gbs": round(r["hbm_gbs_whole_step"], 1),
+                   "hbm_frac_whole_step": round(r["hbm_frac"], 4),
+                   "linears_ms_per_step": round(r["linears_ms_per_step"], 4),
+                   "attention_ms_per_step": round(r["attention_ms_per_step"], 4),
+                   "per_linear_gbs": r["per_linear_gbs"]},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1) if achieved else None, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4) if achieved else None, "traffic": None,
-                     "kernel": "k_gemm (batched-decode int8 linear)", "launches": n_gemm},
+                     "kernel": "k_gemm (batched-decode int8 linear)", "launches": r["gemm_launches"]},
         "cpu_baseline": None,
     }
-    span.close()
     _emit(args, line)
 
 

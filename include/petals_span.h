@@ -136,6 +136,18 @@ int petals_session_close(petals_session *session);
 int petals_span_prefill(petals_span *span, petals_session *const *sessions, int32_t B,
                         int32_t T, const void *hidden_in, void *hidden_out, void *stream);
 
+/*
+ * petals_span_prefill for hidden states that arrive as the blockwise 8-bit codes of petals_hidden_quantize
+ * (Section 3.1 "Compressing communication buffers": what a server receives from the previous one): u8_in dev
+ * [B*T*H] codes and absmax_in dev [ceil(B*T*H / block)] of the flat [B, T, H] tensor.  The codes are decoded
+ * inside the first block's LayerNorm (no separate pass over the tensor, no fp16 input buffer); results are
+ * those of petals_hidden_dequantize followed by petals_span_prefill, bit for bit.  T = 1 is a decode step.
+ * hidden_out and the errors are petals_span_prefill's; block as for petals_hidden_quantize.
+ */
+int petals_span_prefill_q8(petals_span *span, petals_session *const *sessions, int32_t B, int32_t T,
+                           const void *u8_in, const float *absmax_in, int32_t block, void *hidden_out,
+                           void *stream);
+
 /* One token per session: petals_span_prefill with T = 1; hidden_* are [B, H]. */
 int petals_span_decode_step(petals_span *span, petals_session *const *sessions, int32_t B,
                             const void *hidden_in, void *hidden_out, void *stream);
@@ -288,6 +300,17 @@ int petals_debug_import_kv(petals_session *session, int32_t block, const void *i
  */
 int petals_debug_backward_product(petals_span *span, void *dev_store, int32_t B, int32_t T, int32_t block,
                                   int32_t which, const void *dy, float *dx, void *stream);
+
+/*
+ * Measurement aid, not part of the method: a register-only loop of the int8 matrix instruction (no memory
+ * traffic), to put the rate of the prefill linear (Section 3.1, 8-bit weights on the matrix cores) next to
+ * what the part sustains.  kind 0: v_mfma_i32_16x16x64_i8, 1: v_mfma_i32_32x32x32_i8; random_operands 0: all
+ * operand bytes one constant, 1: pseudo-random bytes; `workgroups` workgroups of 4 waves run `iters`
+ * iterations.  dev_out: dev int32 [workgroups * 256] (receives checksums); ops_out (host): integer operations
+ * the launch performs.  Enqueues one kernel; the caller times it.
+ */
+int petals_bench_mfma(int32_t kind, int32_t random_operands, int32_t iters, int32_t workgroups,
+                      int32_t *dev_out, double *ops_out, void *stream);
 
 #ifdef __cplusplus
 }

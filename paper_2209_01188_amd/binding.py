@@ -53,13 +53,13 @@ def lib():
 
 EXPORTS = ["petals_span_weight_bytes", "petals_span_workspace_bytes", "petals_span_kv_bytes", "petals_span_create",
            "petals_span_load_block", "petals_span_destroy", "petals_session_open", "petals_session_length",
-           "petals_session_close", "petals_span_prefill", "petals_span_decode_step", "petals_span_decode_step_static",
+           "petals_session_close", "petals_span_prefill", "petals_span_decode_step", "petals_span_decode_step_static", "petals_span_prefill_q8",
            "petals_hidden_quantize",
            "petals_hidden_dequantize", "petals_hidden_code_table", "petals_last_error", "petals_debug_linear",
            "petals_debug_export_weight", "petals_debug_export_kv", "petals_debug_import_kv",
            "petals_span_profile_begin", "petals_span_profile_end", "petals_debug_layernorm", "petals_session_replay",
            "petals_span_backward_bytes", "petals_span_backward", "petals_debug_backward_product",
-           "petals_span_backward_cache_bytes", "petals_span_backward_attach_cache"]
+           "petals_span_backward_cache_bytes", "petals_span_backward_attach_cache", "petals_bench_mfma"]
 CLIENT_EXPORTS = ["petals_client_workspace_bytes", "petals_client_create", "petals_client_destroy",
                   "petals_client_embed", "petals_client_lm_head", "petals_client_sample"]
 PROFILE_GEMV, PROFILE_GEMM, PROFILE_ATTENTION, PROFILE_LINEAR0 = 0, 1, 2, 3
@@ -145,6 +145,11 @@ def _session_array(sessions):
 def petals_span_prefill(span, sessions, T, hidden_in, hidden_out):
     _check(lib().petals_span_prefill(span, _session_array(sessions), C.c_int32(len(sessions)), C.c_int32(T),
                                      _ptr(hidden_in), _ptr(hidden_out), _stream()))
+
+
+def petals_span_prefill_q8(span, sessions, T, codes, absmax, block, hidden_out):
+    _check(lib().petals_span_prefill_q8(span, _session_array(sessions), C.c_int32(len(sessions)), C.c_int32(T),
+                                        _ptr(codes), _ptr(absmax), C.c_int32(block), _ptr(hidden_out), _stream()))
 
 
 def petals_span_decode_step(span, sessions, hidden_in, hidden_out):
@@ -235,6 +240,14 @@ def petals_debug_backward_product(span, store, B, T, block, which, dy, dx):
                                                C.c_int32(which), _ptr(dy), _ptr(dx), _stream()))
 
 
+def petals_bench_mfma(kind, random_operands, iters, workgroups, out):
+    """Enqueues the register-only int8 matrix-instruction loop; returns the integer operations it performs."""
+    ops = C.c_double()
+    _check(lib().petals_bench_mfma(C.c_int32(kind), C.c_int32(1 if random_operands else 0), C.c_int32(iters),
+                                   C.c_int32(workgroups), _ptr(out), C.byref(ops), _stream()))
+    return ops.value
+
+
 def petals_debug_export_weight(span, block, which, wq, sw):
     _check(lib().petals_debug_export_weight(span, C.c_int32(block), C.c_int32(which), _ptr(wq), _ptr(sw), _stream()))
 
@@ -291,6 +304,13 @@ class Span:
     def decode_step(self, sessions, hidden_in, out=None):
         out = torch.empty_like(hidden_in) if out is None else out
         petals_span_decode_step(self.handle, [s.handle for s in sessions], hidden_in, out)
+        return out
+
+    def prefill_q8(self, sessions, T, codes, absmax, block, out=None):
+        """prefill (T = 1: a decode step) of hidden states given as blockwise 8-bit codes; returns fp16 [B, T, H]."""
+        if out is None:
+            out = torch.empty((len(sessions), T, self.hidden), dtype=torch.float16, device=self.device)
+        petals_span_prefill_q8(self.handle, [s.handle for s in sessions], T, codes, absmax, block, out)
         return out
 
     def decode_step_static(self, sessions, hidden_in, out=None):

@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpetals_span.so")
 OBJ = os.path.join(HERE, "_build")
-SOURCES = ["api.hip", "api_backward.hip", "quant.hip", "gemv.hip", "gemm.hip", "gemm_lds.hip", "attn.hip", "client.hip", "backward.hip"]
+SOURCES = ["api.hip", "api_backward.hip", "quant.hip", "gemv.hip", "gemm.hip", "gemm_lds.hip", "attn.hip", "client.hip", "backward.hip", "microbench.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 ops are disabled on the test machines.
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17",

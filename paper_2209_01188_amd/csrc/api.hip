@@ -74,7 +74,7 @@ Workspace carve(const petals_span_config &c, uint8_t *base) {
     w.ocount = (int *)take(256);
     const size_t Nmax = 3 * H > F ? 3 * H : F;
     w.wd64 = w.x64 = nullptr;
-    w.many = ManyOutliers{nullptr, nullptr, nullptr, nullptr, nullptr};
+    w.many = ManyOutliers{nullptr, nullptr, nullptr, nullptr, nullptr, 0};
     if (M > 64) {   // prefill-size calls: compacted exact outlier operands, and room for the case that most columns are outliers
         w.wd64 = (double *)take(Nmax / 16 * PS_OUTLIER_CHUNKS * 64 * 8);
         w.x64 = (double *)take(Mp / 16 * PS_OUTLIER_CHUNKS * 64 * 8);
@@ -82,7 +82,8 @@ Workspace carve(const petals_span_config &c, uint8_t *base) {
         w.many.list = (int *)take((Kmax + 64) * 4);
         w.many.xl = (int8_t *)take((size_t)PS_X_DIGITS * Mp * (Kmax + 64));
         w.many.wd = (int8_t *)take(2 * (NKmax + 64 * Nmax));
-        w.many.raw = (int32_t *)take((size_t)PS_X_DIGITS * Mp * 2 * ps_many_chunk_features((int)Nmax) * 4);
+        w.many.chunk = (int)ps_many_chunk_features((int)Nmax, (int)M);
+        w.many.raw = (int32_t *)take((size_t)PS_X_DIGITS * Mp * 2 * w.many.chunk * 4);
         w.many.od = (double *)take(Mp * Nmax * 8);
     }
     w.total = off;
@@ -106,26 +107,8 @@ int check_config(const petals_span_config *c) {
     return PETALS_OK;
 }
 
-// The 256 entries of the 8-bit dynamic data type: per decade 10^-e (e = 0..6) the centres
-// of 2^(6-e) equal buckets spanning [0.1, 1.0], both signs, plus 0 and 1.0; ascending.
-CodeTable make_code_table() {
-    CodeTable tab;
-    static const double decade[7] = {1.0, 1e-1, 1e-2, 1e-3, 1e-4, 1e-5, 1e-6};
-    std::vector<float> pos;
-    for (int e = 6; e >= 0; e--) {
-        const int cnt = 64 >> e;
-        for (int j = 0; j < cnt; j++) pos.push_back((float)(decade[e] * (0.1 + 0.9 * (j + 0.5) / cnt)));
-    }
-    // pos ascends: decades from small to large, buckets ascending inside a decade
-    int k = 0;
-    for (int i = (int)pos.size() - 1; i >= 0; i--) tab.code[k++] = -pos[i];
-    tab.code[k++] = 0.0f;
-    for (size_t i = 0; i < pos.size(); i++) tab.code[k++] = pos[i];
-    tab.code[k++] = 1.0f;
-    return tab;
-}
 const CodeTable &code_table() {
-    static const CodeTable tab = make_code_table();   // initialised once, also when several threads arrive together
+    static constexpr CodeTable tab = ps_make_code_table();
     return tab;
 }
 
@@ -139,7 +122,8 @@ namespace {
 // mask_ready (multi-row calls without LayerNorm): the kernel that wrote X has already flagged the outlier
 // columns in mask; with a LayerNorm the mask must arrive cleared and the LayerNorm kernel flags them.
 int run_linear(petals_span *sp, int which, const LinearW &w, const __half *X, const __half *ln_g, const __half *ln_b, int M,
-               uint32_t *mask, bool mask_ready, const OutDesc &o, int8_t *xq_dbg, bool debug, hipStream_t st) {
+               uint32_t *mask, bool mask_ready, const OutDesc &o, int8_t *xq_dbg, bool debug, hipStream_t st,
+               const QuantIn *qin = nullptr) {
     Workspace &ws = sp->ws;
     const petals_span_config &c = sp->cfg;
     const float theta = c.outlier_threshold;
@@ -147,12 +131,13 @@ int run_linear(petals_span *sp, int which, const LinearW &w, const __half *X, co
         RowDebug dbg = {nullptr, nullptr, nullptr, nullptr};
         if (debug) dbg = RowDebug{ln_g ? ws.a : nullptr, xq_dbg, mask, ws.sx};
         const bool pr = sp->prof.begin(PETALS_PROFILE_GEMV, which, st);
-        HIP_TRY(ps_gemv_row(w, X, ln_g, ln_b, c.ln_eps, theta, dbg, o, ws.table, st));
+        HIP_TRY(ps_gemv_row(w, X, ln_g, ln_b, c.ln_eps, theta, dbg, o, ws.table, qin, st));
         sp->prof.end(pr, st);
     } else {
         if (!mask_ready) HIP_TRY(ps_fill_u32(mask, ws.mask_words, 0u, st));
         if (ln_g) {
-            HIP_TRY(ps_layernorm(X, ln_g, ln_b, c.ln_eps, M, c.hidden, ws.a, mask, theta, st));
+            if (qin) HIP_TRY(ps_layernorm_q8(*qin, ln_g, ln_b, c.ln_eps, M, c.hidden, ws.a, mask, theta, st));
+            else HIP_TRY(ps_layernorm(X, ln_g, ln_b, c.ln_eps, M, c.hidden, ws.a, mask, theta, st));
             X = ws.a;
         } else if (!mask_ready) {
             HIP_TRY(ps_colmask(X, M, w.K, theta, mask, st));
@@ -182,7 +167,7 @@ OutDesc plain_out(__half *y, int epilogue, const __half *resid) {
 // save == nullptr: intermediates live in the workspace.  Otherwise they are written where save says and
 // the up linear also stores the sum it feeds to GeLU.
 int forward_blocks(petals_span *sp, int M, int T, int max_keys, const __half *hidden_in, __half *hidden_out,
-                   const SaveSet *save, hipStream_t st) {
+                   const SaveSet *save, hipStream_t st, const QuantIn *qin = nullptr) {
     const petals_span_config &c = sp->cfg;
     Workspace &ws = sp->ws;
     const int H = c.hidden, nh = c.n_heads, d = H / nh;
@@ -192,7 +177,8 @@ int forward_blocks(petals_span *sp, int M, int T, int max_keys, const __half *hi
     const bool multi = M > 1;
     const float theta = c.outlier_threshold;
     if (multi) HIP_TRY(ps_fill_u32(ws.masks, (size_t)c.n_blocks * 4 * ws.mask_words, 0u, st));
-    const __half *x = hidden_in;
+    // hidden states arriving as 8-bit codes: the first LayerNorm decodes them and leaves the fp16 rows in qin->x_out
+    const __half *x = qin ? qin->x_out : hidden_in;
     for (int b = 0; b < c.n_blocks; b++) {
         const BlockW &W = sp->blocks[b];
         __half *xout = (b == c.n_blocks - 1) ? hidden_out : (save ? save->x[b + 1] : ((b & 1) ? ws.xb : ws.xa));
@@ -201,7 +187,8 @@ int forward_blocks(petals_span *sp, int M, int T, int max_keys, const __half *hi
         OutDesc oq = plain_out(qb, PETALS_EPILOGUE_NONE, nullptr);
         oq.scatter = 1; oq.T = T; oq.nh = nh; oq.d = d; oq.blk = b;
         // LayerNorm 1 -> fused QKV (queries to qb, keys/values appended to the caches)
-        if (int rc = run_linear(sp, 0, W.lin[0], x, W.ln1g, W.ln1b, M, mk, multi, oq, nullptr, false, st)) return rc;
+        if (int rc = run_linear(sp, 0, W.lin[0], x, W.ln1g, W.ln1b, M, mk, multi, oq, nullptr, false, st,
+                                b == 0 ? qin : nullptr)) return rc;
         {
             const bool pr = sp->prof.begin(PETALS_PROFILE_ATTENTION, -1, st);
             HIP_TRY(ps_attention(qb, ws.table, b, M, T, nh, d, max_keys, ws.partials, ctxb,
@@ -228,7 +215,7 @@ int forward_blocks(petals_span *sp, int M, int T, int max_keys, const __half *hi
 
 // Checks, session table, the blocks, session lengths: the body of every forward call.  Works on sp->ws.
 int run_call(petals_span *sp, petals_session *const *sessions, int32_t B, int32_t T, const void *hidden_in,
-             void *hidden_out, hipStream_t st) {
+             void *hidden_out, hipStream_t st, const QuantIn *qin_arg = nullptr) {
     if (!sp || !sessions || !hidden_in || !hidden_out) return fail(PETALS_ERR_INVALID_ARG, "null pointer");
     if (B < 1 || T < 1) return fail(PETALS_ERR_INVALID_ARG, "B and T must be positive");
     if (hidden_in == hidden_out) return fail(PETALS_ERR_INVALID_ARG, "hidden_in and hidden_out alias");
@@ -257,7 +244,15 @@ int run_call(petals_span *sp, petals_session *const *sessions, int32_t B, int32_
     Workspace &ws = sp->ws;
     const int M = B * T;
     HIP_TRY(ps_set_table(tab, ws.table, st));
-    if (int rc = forward_blocks(sp, M, T, max_keys, (const __half *)hidden_in, (__half *)hidden_out, nullptr, st)) return rc;
+    QuantIn qin;
+    if (qin_arg) {
+        // the decoded rows live in the buffer that only the outputs of odd blocks use: block 0 reads them (LayerNorm,
+        // residual of its dense linear), block 1 is the first to overwrite them
+        qin = *qin_arg;
+        qin.x_out = ws.xb;
+    }
+    if (int rc = forward_blocks(sp, M, T, max_keys, (const __half *)hidden_in, (__half *)hidden_out, nullptr, st,
+                                qin_arg ? &qin : nullptr)) return rc;
     for (int s = 0; s < B; s++) sessions[s]->len += T;
     return PETALS_OK;
 }
@@ -455,6 +450,14 @@ int petals_session_close(petals_session *se) {
 int petals_span_prefill(petals_span *sp, petals_session *const *sessions, int32_t B, int32_t T,
                         const void *hidden_in, void *hidden_out, void *stream) {
     return run_call(sp, sessions, B, T, hidden_in, hidden_out, (hipStream_t)stream);
+}
+
+int petals_span_prefill_q8(petals_span *sp, petals_session *const *sessions, int32_t B, int32_t T, const void *u8_in,
+                           const float *absmax_in, int32_t block, void *hidden_out, void *stream) {
+    if (!absmax_in) return fail(PETALS_ERR_INVALID_ARG, "null pointer");
+    if (block < 64 || block % 64 || block > 16384) return fail(PETALS_ERR_INVALID_ARG, "block must be a multiple of 64 in [64, 16384]");
+    const QuantIn qin = {(const uint8_t *)u8_in, absmax_in, block, nullptr};
+    return run_call(sp, sessions, B, T, u8_in, hidden_out, (hipStream_t)stream, &qin);
 }
 
 int petals_span_decode_step(petals_span *sp, petals_session *const *sessions, int32_t B, const void *hidden_in,

@@ -53,6 +53,35 @@ struct OutDesc {
 };
 
 struct CodeTable { float code[256]; };
+// The 256 entries of the 8-bit dynamic data type of the hidden-state codec, ascending: per decade 10^-e
+// (e = 0..6) the centres of 2^(6-e) equal buckets spanning [0.1, 1.0], both signs, plus 0 and 1.0.
+// constexpr: host code and device-side constant tables are built from the same evaluation.
+constexpr CodeTable ps_make_code_table() {
+    CodeTable tab{};
+    const double decade[7] = {1.0, 1e-1, 1e-2, 1e-3, 1e-4, 1e-5, 1e-6};
+    float pos[127] = {};
+    int n = 0;
+    for (int e = 6; e >= 0; e--) {          // ascending: decades from small to large, buckets ascending inside a decade
+        const int cnt = 64 >> e;
+        for (int j = 0; j < cnt; j++) pos[n++] = (float)(decade[e] * (0.1 + 0.9 * (j + 0.5) / cnt));
+    }
+    int k = 0;
+    for (int i = n - 1; i >= 0; i--) tab.code[k++] = -pos[i];
+    tab.code[k++] = 0.0f;
+    for (int i = 0; i < n; i++) tab.code[k++] = pos[i];
+    tab.code[k++] = 1.0f;
+    return tab;
+}
+
+// Hidden states that arrive as blockwise 8-bit codes and are decoded by the first LayerNorm of a call:
+// value i = fp16(table[q[i]] * absmax[i / block]) over the flat [M, H] buffer.  x_out receives the decoded
+// fp16 rows (the first block's residual reads them).
+struct QuantIn {
+    const uint8_t *q;
+    const float *absmax;
+    int block;
+    __half *x_out;
+};
 
 // Up to this many outlier columns the fp16 part of a multi-row linear is computed exactly
 // (fp64 matrix instructions on compacted operands); beyond it, on the fp16 matrix cores.
@@ -75,6 +104,9 @@ hipError_t ps_copy_bytes(const void *src, void *dst, size_t n, hipStream_t st);
 // mask (may be null): outlier-column bits of y are ORed into it (|y| >= theta)
 hipError_t ps_layernorm(const __half *x, const __half *g, const __half *b, float eps, int M, int H,
                         __half *y, uint32_t *mask, float theta, hipStream_t st);
+// LayerNorm of rows that arrive as 8-bit codes (also writes the decoded rows to qin.x_out)
+hipError_t ps_layernorm_q8(const QuantIn &qin, const __half *g, const __half *b, float eps, int M,
+                           int H, __half *y, uint32_t *mask, float theta, hipStream_t st);
 hipError_t ps_colmask(const __half *X, int M, int K, float theta, uint32_t *mask, hipStream_t st);
 // M rows -> tiled int8 codes (rows padded to 16 with zeros), row scales; mask given
 // xo_tiled (may be null): same tile order, 16 bytes per (token, 16-column group) = the fp16 values of the
@@ -86,15 +118,16 @@ hipError_t ps_mask_to_bytes(const uint32_t *mask, int K, uint8_t *out, hipStream
 // Scratch of the outlier-heavy case of a prefill-size call (more than PS_EXACT_OUTLIERS columns): the fp16
 // product over the outlier columns is taken exactly, as int8 digit products (see gemm_lds.hip)
 #define PS_X_DIGITS 6            // balanced 8-bit digits of an fp16 activation in units of 2^-24 (4 cover |x| < 127.5)
-#define PS_MANY_CHUNK 14336      // output features per digit product (bounds the raw-sum buffer)
+#define PS_MANY_RAW_BYTES ((size_t)4 << 30)   // bound on the raw digit sums of one chunk of output features
 struct ManyOutliers {
     int *list;      // [K] outlier column indices, ascending, padded with -1 to a multiple of 64
     int8_t *xl;     // digit tiles of the activations [PS_X_DIGITS][ceil(M/16)][ceil(n_out/64)][1024]
     int8_t *wd;     // digit tiles of the dequantized weights [2][N/16][ceil(n_out/64)][1024]
     int32_t *raw;   // [PS_X_DIGITS * 16 ceil(M/16)][2 * chunk] digit products of one chunk of output features
     double *od;     // [M, N] the outlier product
+    int chunk;      // output features per digit product, fixed when the workspace is laid out
 };
-size_t ps_many_chunk_features(int N);
+size_t ps_many_chunk_features(int N, int M);
 // LDS-staged linear for M > 64 rows (any number of outlier columns)
 hipError_t ps_gemm_lds(const LinearW &w, const int8_t *xq_tiled, const uint32_t *mask, const __half *X, const float *sx,
                        int M, const OutlierSet &os, const ManyOutliers &mo, const OutDesc &o, const SessTable *sess,
@@ -108,8 +141,10 @@ struct RowDebug {
 };
 // y = mixed int8/fp16 linear of ONE fp16 row x[K] (decode, batch 1); with ln_g/ln_b non-null the row
 // first goes through LayerNorm.  Outlier detection and int8 quantization happen inside the kernel.
+// qin (may be null; needs ln_g): the row arrives as 8-bit codes, x is ignored
 hipError_t ps_gemv_row(const LinearW &w, const __half *x, const __half *ln_g, const __half *ln_b, float eps,
-                       float theta, const RowDebug &dbg, const OutDesc &o, const SessTable *sess, hipStream_t st);
+                       float theta, const RowDebug &dbg, const OutDesc &o, const SessTable *sess, const QuantIn *qin,
+                       hipStream_t st);
 // counts the outlier columns of a prefill-size call and, if they are few, compacts their operands
 hipError_t ps_outlier_prep(const LinearW &w, const uint32_t *mask, const __half *X, int M, int *count, double *wd64,
                            double *x64, hipStream_t st);
@@ -221,6 +256,10 @@ __device__ __forceinline__ float block_sum(float v, float *sm) {
 __device__ __forceinline__ float keep_f32(float v) {
     asm volatile("" : "+v"(v));
     return v;
+}
+// one decoded hidden-state value: fp32 product, one rounding to fp16
+__device__ __forceinline__ __half decode_q8(const float *table, uint32_t code, float absmax) {
+    return __float2half_rn(keep_f32(table[code] * absmax));
 }
 // tanh-form GeLU in fp64: 0.5 v (1 + tanh u) == v / (1 + exp(-2u))
 __device__ __forceinline__ double gelu_tanh(double v) {

@@ -277,9 +277,10 @@ struct GemmArgs {
     // of the next product's token-side operand (16 x 32 tiles, rows beyond M zero)
     const __half *gelu_pre;   // [M, N] fp16, or null
     __half *tile_out;
-    // digit product only: weight-side tile rows [a_row0, a_row0 + a_rows) of a_tiles are this launch's features;
-    // the int32 sums go to raw[token row * ldr + feature], token rows = digit planes of 16-padded M stacked
-    int a_row0, a_rows;
+    // digit product only: the launch's a_rows feature tiles are tile rows a_row0 .. of a_tiles for the first
+    // a_split of them (the codes of a chunk of output features) and a_row1 .. for the rest (their remainders);
+    // the int32 sums go to raw[token row * ldr + 16 * feature tile], token rows = digit planes of 16-padded M stacked
+    int a_row0, a_row1, a_split, a_rows;
     int32_t *raw;
     int ldr;
     float *f32_out;           // plain fp16 product: [M, N] fp32 result
@@ -325,14 +326,14 @@ k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, 
     const int wn = wave / WVM, wm = wave % WVM;
     const int nt0 = (ga.nb_n0 + bn) * BN, mt0 = bm * BM;
     if (DIG && mt0 >= MTT) return;                   // a digit plane nobody needs (the grid is sized for all of them)
-    const int a_row0 = DIG ? ga.a_row0 : 0;
+    auto a_tile_row = [&](int nt) { return !DIG ? nt : (nt < ga.a_split ? ga.a_row0 + nt : ga.a_row1 + nt - ga.a_split); };
 
     // the stage tiles this wave copies: s = wave + NW*j; s < BN: weight tile, else token tile
     const unsigned char *src[LOADS];
 #pragma unroll
     for (int j = 0; j < LOADS; j++) {
         const int s = wave + NW * j;
-        if (s < BN) src[j] = ga.a_tiles + (size_t)(a_row0 + min(nt0 + s, NT - 1)) * NS * 1024 + lane * 16;
+        if (s < BN) src[j] = ga.a_tiles + (size_t)a_tile_row(min(nt0 + s, NT - 1)) * NS * 1024 + lane * 16;
         else src[j] = ga.b_tiles + (size_t)min(mt0 + s - BN, MTT - 1) * NS * 1024 + lane * 16;
     }
 
@@ -718,7 +719,13 @@ hipError_t ps_gemm_f16_tiles(const __half *feat_tiles, const __half *tok_tiles, 
     return launch_lds<GEMM_F16>(ga, w, nullptr, os, nullptr, o, nullptr, st);
 }
 
-size_t ps_many_chunk_features(int N) { return (size_t)(N < PS_MANY_CHUNK ? N : PS_MANY_CHUNK); }
+// Output features per digit product: as many as keep the raw sums of a call of M rows within PS_MANY_RAW_BYTES
+size_t ps_many_chunk_features(int N, int M) {
+    const size_t Mp = ((size_t)M + 15) / 16 * 16;
+    size_t nc = PS_MANY_RAW_BYTES / ((size_t)PS_X_DIGITS * Mp * 2 * 4) / 256 * 256;
+    if (nc < 256) nc = 256;
+    return nc < (size_t)N ? nc : (size_t)N;
+}
 
 hipError_t ps_gemm_lds(const LinearW &w, const int8_t *xq_tiled, const uint32_t *mask, const __half *X, const float *sx,
                        int M, const OutlierSet &os, const ManyOutliers &mo, const OutDesc &o, const SessTable *sess,
@@ -731,20 +738,20 @@ hipError_t ps_gemm_lds(const LinearW &w, const int8_t *xq_tiled, const uint32_t 
     k_digit_w<2><<<4096, 64, 0, st>>>(w, os.count, mo.list, mo.wd);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const int NT = w.N / 16, MTT = (M + 15) / 16, NC = (int)ps_many_chunk_features(w.N);
+    const int NT = w.N / 16, MTT = (M + 15) / 16, NC = min(mo.chunk, w.N);
     for (int n0 = 0; n0 < w.N; n0 += NC) {
         const int nc = min(NC, w.N - n0);
-        for (int d = 0; d < 2; d++) {
-            GemmArgs gd = gemm_args(mo.wd, mo.xl, 0, M, nc);
-            gd.a_row0 = d * NT + n0 / 16;
-            gd.a_rows = nc / 16;
-            gd.raw = mo.raw + (size_t)d * nc;
-            gd.ldr = 2 * nc;
-            gd.nb_n = (nc / 16 + 15) / 16;
-            gd.nb_m = (PS_X_DIGITS * MTT + 15) / 16;
-            e = launch_one<GEMM_DIGITS, 4>(gd, w, sx, os, nullptr, o, sess, st);
-            if (e != hipSuccess) return e;
-        }
+        GemmArgs gd = gemm_args(mo.wd, mo.xl, 0, M, 2 * nc);
+        gd.a_row0 = n0 / 16;                   // codes of features n0 .. n0 + nc
+        gd.a_row1 = NT + n0 / 16;              // their remainders
+        gd.a_split = nc / 16;
+        gd.a_rows = 2 * (nc / 16);
+        gd.raw = mo.raw;
+        gd.ldr = 2 * nc;
+        gd.nb_n = (gd.a_rows + 15) / 16;
+        gd.nb_m = (PS_X_DIGITS * MTT + 15) / 16;
+        e = launch_one<GEMM_DIGITS, 4>(gd, w, sx, os, nullptr, o, sess, st);
+        if (e != hipSuccess) return e;
         const size_t quads = (size_t)M * (nc / 4);
         k_combine_digits<<<(unsigned)((quads + 255) / 256), 256, 0, st>>>(mo.raw, os.count, w.sw, M, w.N, n0, nc, mo.od);
         e = hipGetLastError();

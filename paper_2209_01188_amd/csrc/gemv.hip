@@ -29,6 +29,12 @@ struct RowIn {
     const __half *ln_g, *ln_b;  // LayerNorm gain/bias (used by the LN variant)
     float eps;
     uint32_t theta_bits;
+    // LN variant only: the row arrives as blockwise 8-bit codes (q8 non-null; x is then unused) and is decoded
+    // while it is loaded; workgroup 0 stores the decoded fp16 row to q8_x_out for the residual that follows
+    const uint8_t *q8;
+    const float *q8_absmax;
+    int q8_block;
+    __half *q8_x_out;
     // optional copies for tests, written by workgroup 0 (each may be null)
     __half *a_out;              // LayerNorm output
     int8_t *xq_out;
@@ -36,11 +42,14 @@ struct RowIn {
     float *sx_out;
 };
 
+static __device__ const CodeTable d_code_table = ps_make_code_table();
+
 // The fp16 value of column k the linear sees: the input itself, or its LayerNorm.
 template <bool LN>
 __device__ __forceinline__ __half row_value(const RowIn &in, int k, double mean, double inv) {
     if (!LN) return in.x[k];
-    return d2h_rn(((double)__half2float(in.x[k]) - mean) * inv * (double)__half2float(in.ln_g[k]) +
+    const __half xk = in.q8 ? decode_q8(d_code_table.code, in.q8[k], in.q8_absmax[k / in.q8_block]) : in.x[k];
+    return d2h_rn(((double)__half2float(xk) - mean) * inv * (double)__half2float(in.ln_g[k]) +
                   (double)__half2float(in.ln_b[k]));
 }
 
@@ -113,7 +122,18 @@ __global__ void __launch_bounds__(GEMV_GROUP * NG) k_gemv_row(LinearW w, RowIn i
         for (int i = 0; i < MAXCH; i++) {
             const int c = threadIdx.x + GEMV_THREADS * i;
             if (c < nch8) {
-                xr[i] = *(const v8h *)(in.x + c * 8);
+                if (in.q8) {                        // uniform over the grid; the 8 columns share a codec block
+                    const uint2 qq = *(const uint2 *)(in.q8 + c * 8);
+                    const float am = in.q8_absmax[(c * 8) / in.q8_block];
+                    __half dec[8];
+#pragma unroll
+                    for (int e = 0; e < 8; e++)
+                        dec[e] = decode_q8(d_code_table.code, ((e < 4 ? qq.x : qq.y) >> ((e & 3) * 8)) & 255u, am);
+                    xr[i] = *(const v8h *)dec;
+                    if (first) *(v8h *)(in.q8_x_out + c * 8) = xr[i];
+                } else {
+                    xr[i] = *(const v8h *)(in.x + c * 8);
+                }
                 gr[i] = *(const v8h *)(in.ln_g + c * 8);
                 br[i] = *(const v8h *)(in.ln_b + c * 8);
             }
@@ -315,9 +335,15 @@ uint32_t theta_to_bits(float theta) {
 }  // namespace
 
 hipError_t ps_gemv_row(const LinearW &w, const __half *x, const __half *ln_g, const __half *ln_b, float eps,
-                       float theta, const RowDebug &dbg, const OutDesc &o, const SessTable *sess, hipStream_t st) {
+                       float theta, const RowDebug &dbg, const OutDesc &o, const SessTable *sess, const QuantIn *qin,
+                       hipStream_t st) {
     RowIn in;
     in.x = x; in.ln_g = ln_g; in.ln_b = ln_b; in.eps = eps; in.theta_bits = theta_to_bits(theta);
+    in.q8 = nullptr; in.q8_absmax = nullptr; in.q8_block = 1; in.q8_x_out = nullptr;
+    if (qin) {
+        if (!ln_g) return hipErrorInvalidValue;   // codes are only decoded in front of a LayerNorm
+        in.q8 = qin->q; in.q8_absmax = qin->absmax; in.q8_block = qin->block; in.q8_x_out = qin->x_out;
+    }
     in.a_out = dbg.a_out; in.xq_out = dbg.xq_out; in.mask_out = dbg.mask_out; in.sx_out = dbg.sx_out;
     const bool ln = ln_g != nullptr;
     const int KT = w.K / 64;

@@ -84,6 +84,41 @@ __global__ void __launch_bounds__(NT) k_layernorm(const __half *__restrict__ x, 
     }
 }
 
+// Rows that arrive as blockwise 8-bit codes: every thread decodes the elements it will normalise (same
+// assignment of elements to threads as k_layernorm), stores them as the fp16 row the residual reads later, and
+// goes on as k_layernorm does on that row.
+static __device__ const CodeTable d_code_table = ps_make_code_table();
+
+template <int NT>
+__global__ void __launch_bounds__(NT) k_layernorm_q8(QuantIn qin, const __half *__restrict__ g,
+                                                     const __half *__restrict__ b, float eps, int H,
+                                                     __half *__restrict__ y, uint32_t *__restrict__ mask, float theta) {
+    __shared__ double sm[NT / 64];
+    __shared__ float table[256];
+    for (int i = threadIdx.x; i < 256; i += NT) table[i] = d_code_table.code[i];
+    __syncthreads();
+    const size_t row0 = (size_t)blockIdx.x * H;
+    __half *xr = qin.x_out + row0;
+    __half *yr = y + row0;
+    for (int k = threadIdx.x * 2; k < H; k += NT * 2) {
+        const size_t i = row0 + k;                           // H and the codec block are even: both share a block
+        const float am = qin.absmax[i / (size_t)qin.block];
+        const uint32_t two = *(const uint16_t *)(qin.q + i);
+        *(__half2 *)(xr + k) = __halves2half2(decode_q8(table, two & 255u, am), decode_q8(table, two >> 8, am));
+    }
+    double mean, inv;
+    row_moments<NT>(xr, H, sm, mean, inv, (double)eps);     // every thread reads back what it wrote itself
+    for (int k = threadIdx.x * 2; k < H; k += NT * 2) {
+        const __half2 o = ln_affine(*(const __half2 *)(xr + k), *(const __half2 *)(g + k),
+                                    *(const __half2 *)(b + k), mean, inv);
+        *(__half2 *)(yr + k) = o;
+        if (mask) {
+            const uint32_t bits = (fabsf(__half2float(o.x)) >= theta ? 1u : 0u) | (fabsf(__half2float(o.y)) >= theta ? 2u : 0u);
+            flag_outlier_bits(mask, k >> 5, bits << (k & 31));
+        }
+    }
+}
+
 // The same with the row held in registers (4096 <= H <= 16384: at most 8 pairs per thread of 1024), so the
 // row is read from memory once instead of three times.  Same assignment of elements to threads and same
 // reduction order as k_layernorm: identical results.
@@ -447,6 +482,12 @@ hipError_t ps_layernorm(const __half *x, const __half *g, const __half *b, float
     else if (H >= 4096 && H <= 16384) k_layernorm_wide<<<M, 1024, 0, st>>>(x, g, b, eps, H, y, mask, theta);
     else if (M <= 256 && H >= 4096) k_layernorm<1024><<<M, 1024, 0, st>>>(x, g, b, eps, H, y, mask, theta);
     else k_layernorm<256><<<M, 256, 0, st>>>(x, g, b, eps, H, y, mask, theta);
+    return hipGetLastError();
+}
+hipError_t ps_layernorm_q8(const QuantIn &qin, const __half *g, const __half *b, float eps, int M,
+                           int H, __half *y, uint32_t *mask, float theta, hipStream_t st) {
+    if (M <= 256 && H >= 4096) k_layernorm_q8<1024><<<M, 1024, 0, st>>>(qin, g, b, eps, H, y, mask, theta);
+    else k_layernorm_q8<256><<<M, 256, 0, st>>>(qin, g, b, eps, H, y, mask, theta);
     return hipGetLastError();
 }
 hipError_t ps_colmask(const __half *X, int M, int K, float theta, uint32_t *mask, hipStream_t st) {

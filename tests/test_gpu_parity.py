@@ -845,3 +845,42 @@ def test_c3_two_blocks_eight_sessions_of_512_tokens_with_the_codec_then_four_dec
         assert [s.length for s in gses] == [s.length for s in oses] == [T + 4] * B
     finally:
         gsp.close(); osp.destroy()
+
+
+# ------------------------------------------- hidden states arriving as 8-bit codes, decoded by the first LayerNorm
+
+@pytest.mark.parametrize("name,nb,B,T,H", [("C1", 2, 1, 8, None), ("C1", 2, 3, 1, None), ("C2", 3, 2, 35, None), ("C2", 2, 1, 1, None),
+                                           ("C2", 2, 5, 1, None), ("C3", 1, 2, 300, None), ("C3", 2, 8, 1, None), ("C3", 1, 1, 1, None),
+                                           ("C2", 1, 1, 1, 14336), ("C2", 1, 3, 1, 14336)])
+def test_codes_as_span_input_equal_dequantize_then_step(name, nb, B, T, H):
+    """petals_span_prefill_q8 (codes decoded inside the first LayerNorm: the fused one-row kernel for one row, a
+    LayerNorm kernel of its own otherwise) against the oracle's dequantize -> span step, and bit for bit against
+    the library's own dequantize -> prefill; then one more ordinary call on the same sessions (the caches match).
+    H = 14336 with blocks of 4096: 3.5 codec blocks per row."""
+    cfg = synth.CONFIGS[name]
+    if H:
+        cfg = synth.scaled(cfg, hidden=H, n_heads=H // 128, ffn=256)
+    CB = 4096
+    osp, gsp, _ = build_pair(cfg, n_blocks=nb, max_rows=B * T)
+    try:
+        X = synth.hidden_states(cfg, 0, B, T)
+        q, am = oracle.hidden_quantize(X, CB)
+        Xd = oracle.hidden_dequantize(q, am, CB).reshape(X.shape)
+        oses = [osp.open_session(T + 1) for _ in range(B)]
+        s_q8 = [gsp.open_session(T + 1) for _ in range(B)]
+        s_two = [gsp.open_session(T + 1) for _ in range(B)]
+        Yo = osp.step(oses, Xd)
+        Yq = gsp.prefill_q8(s_q8, T, to_dev(q.reshape(-1)), to_dev(am), CB)
+        xd = torch.empty((B, T, cfg.hidden), dtype=torch.float16, device=DEV)
+        binding.petals_hidden_dequantize(to_dev(q.reshape(-1)), to_dev(am), CB, xd)
+        Yt = gsp.prefill(s_two, xd)
+        torch.cuda.synchronize()
+        assert torch.equal(Yq, Yt), "fused and two-step results differ"
+        hidden_close(to_np(Yq), Yo, "codes in, %s %dx%d" % (name, B, T))
+        x = synth.hidden_states(cfg, 1, B, 1)
+        y1 = gsp.decode_step(s_q8, to_dev(x[:, 0]))
+        y2 = gsp.decode_step(s_two, to_dev(x[:, 0]))
+        assert torch.equal(y1, y2)
+        hidden_close(to_np(y1)[:, None], osp.step(oses, x), "step after codes in")
+    finally:
+        gsp.close(); osp.destroy()
