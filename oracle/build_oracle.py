@@ -18,5 +18,18 @@ def build(force=True):
     return LIB
 
 
+SELFCHECK = os.path.join(HERE, "selfcheck_san")
+
+
+def build_selfcheck():
+    """The oracle and its driver (selfcheck.c) as one executable under AddressSanitizer and
+    UndefinedBehaviorSanitizer; running it exits non-zero on any report."""
+    cmd = ["gcc", "-O1", "-g", "-fopenmp", "-ffp-contract=off", "-fno-fast-math", "-fno-omit-frame-pointer",
+           "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-static-libasan", "-Wall", "-Wextra",
+           SRC, os.path.join(HERE, "selfcheck.c"), "-o", SELFCHECK, "-lm"]
+    subprocess.check_call(cmd)
+    return SELFCHECK
+
+
 if __name__ == "__main__":
     print(build())
