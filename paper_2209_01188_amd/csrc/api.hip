@@ -74,7 +74,7 @@ Workspace carve(const petals_span_config &c, uint8_t *base) {
     w.ocount = (int *)take(256);
     const size_t Nmax = 3 * H > F ? 3 * H : F;
     w.wd64 = w.x64 = nullptr;
-    w.many = ManyOutliers{nullptr, nullptr, nullptr, nullptr, nullptr, 0};
+    w.many = ManyOutliers{nullptr, nullptr, nullptr, nullptr};
     if (M > 64) {   // prefill-size calls: compacted exact outlier operands, and room for the case that most columns are outliers
         w.wd64 = (double *)take(Nmax / 16 * PS_OUTLIER_CHUNKS * 64 * 8);
         w.x64 = (double *)take(Mp / 16 * PS_OUTLIER_CHUNKS * 64 * 8);
@@ -82,8 +82,6 @@ Workspace carve(const petals_span_config &c, uint8_t *base) {
         w.many.list = (int *)take((Kmax + 64) * 4);
         w.many.xl = (int8_t *)take((size_t)PS_X_DIGITS * Mp * (Kmax + 64));
         w.many.wd = (int8_t *)take(2 * (NKmax + 64 * Nmax));
-        w.many.chunk = (int)ps_many_chunk_features((int)Nmax, (int)M);
-        w.many.raw = (int32_t *)take((size_t)PS_X_DIGITS * Mp * 2 * w.many.chunk * 4);
         w.many.od = (double *)take(Mp * Nmax * 8);
     }
     w.total = off;

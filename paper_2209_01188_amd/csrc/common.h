@@ -118,16 +118,12 @@ hipError_t ps_mask_to_bytes(const uint32_t *mask, int K, uint8_t *out, hipStream
 // Scratch of the outlier-heavy case of a prefill-size call (more than PS_EXACT_OUTLIERS columns): the fp16
 // product over the outlier columns is taken exactly, as int8 digit products (see gemm_lds.hip)
 #define PS_X_DIGITS 6            // balanced 8-bit digits of an fp16 activation in units of 2^-24 (4 cover |x| < 127.5)
-#define PS_MANY_RAW_BYTES ((size_t)4 << 30)   // bound on the raw digit sums of one chunk of output features
 struct ManyOutliers {
     int *list;      // [K] outlier column indices, ascending, padded with -1 to a multiple of 64
     int8_t *xl;     // digit tiles of the activations [PS_X_DIGITS][ceil(M/16)][ceil(n_out/64)][1024]
     int8_t *wd;     // digit tiles of the dequantized weights [2][N/16][ceil(n_out/64)][1024]
-    int32_t *raw;   // [PS_X_DIGITS * 16 ceil(M/16)][2 * chunk] digit products of one chunk of output features
     double *od;     // [M, N] the outlier product
-    int chunk;      // output features per digit product, fixed when the workspace is laid out
 };
-size_t ps_many_chunk_features(int N, int M);
 // LDS-staged linear for M > 64 rows (any number of outlier columns)
 hipError_t ps_gemm_lds(const LinearW &w, const int8_t *xq_tiled, const uint32_t *mask, const __half *X, const float *sx,
                        int M, const OutlierSet &os, const ManyOutliers &mo, const OutDesc &o, const SessTable *sess,

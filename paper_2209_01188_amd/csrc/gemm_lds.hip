@@ -14,7 +14,7 @@
 // Wd = fp16(code * a_n), is u_n * (m_n * code + r) with u_n the fp16 spacing at a_n, m_n = a_n / u_n
 // rounded to an integer (11 bits) and a remainder r that always fits 8 bits.  The gathered digit
 // matrices [digits * M, n_out] and [2 * N, n_out] go through the same pipeline as the regular
-// columns (int32 sums: exact), and k_combine_digits reassembles
+// columns (int32 sums: exact), and each wave reassembles
 //   sum_k x * Wd = u_n * 2^-24 * (m_n * sum_j 256^j * A_c[j] + sum_j 256^j * A_r[j])
 // in fp64 for the int8 kernel's epilogue to add.  (The fp16 matrix instruction with its fp32 sums
 // lands one fp16 rounding step off in about one output of 300 at 57344 columns, and a neighbouring
@@ -228,41 +228,6 @@ __global__ void __launch_bounds__(64) k_digit_w(LinearW w, const int *__restrict
     }
 }
 
-// od[t][n] = sum over the outlier columns of x * Wd, reassembled from the digit products:
-// raw[(j * Mp + t) * ldr + d * NC + (n - n_first)] = sum_k L_j[t][k] * (d == 0 ? code : r)[n][k]  (exact int32).
-// One thread per token and 4 consecutive features.  Sums of 256^j * A_j are taken in fp64 from the top digit
-// down: exact below 2^53, i.e. always for 4 digits short of the last step, and good to 1 part in 2^53 after it.
-__global__ void __launch_bounds__(256) k_combine_digits(const int32_t *__restrict__ raw, const int *__restrict__ count,
-                                                        const float *__restrict__ sw, int M, int N, int n_first,
-                                                        int NC, double *__restrict__ od) {
-    if (count[0] <= PS_EXACT_OUTLIERS) return;
-    const int nd = count[1], Mp = ((M + 15) >> 4) * 16, q4 = NC >> 2;
-    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= (size_t)M * q4) return;
-    const int t = (int)(i / q4), nl = (int)(i - (size_t)t * q4) * 4, ldr = 2 * NC;
-    double tc[4] = {0.0, 0.0, 0.0, 0.0}, tr[4] = {0.0, 0.0, 0.0, 0.0};
-    for (int j = nd - 1; j >= 0; j--) {
-        const int32_t *p = raw + ((size_t)j * Mp + t) * ldr + nl;
-        const v4i ac = *(const v4i *)p, ar = *(const v4i *)(p + NC);
-#pragma unroll
-        for (int e = 0; e < 4; e++) {
-            tc[e] = tc[e] * 256.0 + (double)ac[e];
-            tr[e] = tr[e] * 256.0 + (double)ar[e];
-        }
-    }
-    const float4 s4 = *(const float4 *)(sw + n_first + nl);
-    const float sv[4] = {s4.x, s4.y, s4.z, s4.w};
-    v4d o;
-#pragma unroll
-    for (int e = 0; e < 4; e++) {
-        float a;
-        int E, m;
-        digit_scale(sv[e], a, E, m);
-        o[e] = ldexp((double)m * tc[e] + tr[e], E - 34);                   // u = 2^(E-10), activations in units of 2^-24
-    }
-    *(v4d *)(od + (size_t)t * N + n_first + nl) = o;
-}
-
 // ---------------------------------------------------------------------------------------------
 // the tile pipeline
 
@@ -277,19 +242,19 @@ struct GemmArgs {
     // of the next product's token-side operand (16 x 32 tiles, rows beyond M zero)
     const __half *gelu_pre;   // [M, N] fp16, or null
     __half *tile_out;
-    // digit product only: the launch's a_rows feature tiles are tile rows a_row0 .. of a_tiles for the first
-    // a_split of them (the codes of a chunk of output features) and a_row1 .. for the rest (their remainders);
-    // the int32 sums go to raw[token row * ldr + 16 * feature tile], token rows = digit planes of 16-padded M stacked
-    int a_row0, a_row1, a_split, a_rows;
-    int32_t *raw;
-    int ldr;
+    // digit product only: plane_group 0 takes digit planes 0..3 of the activations and stores the product,
+    // 1 takes planes 4.. (present only when some outlier value reaches 127.5 in magnitude) and adds to it
+    int plane_group;
+    double *od;               // [M, N] fp64: the product over the outlier columns
     float *f32_out;           // plain fp16 product: [M, N] fp32 result
 };
 
 enum { GEMM_INT8 = 0, GEMM_F16 = 1, GEMM_DIGITS = 2 };
 
 // MODE GEMM_INT8: the regular columns with the full epilogue.  GEMM_F16: plain fp16 product (backward pass).
-// GEMM_DIGITS: int8 digit product of the outlier columns, raw int32 sums out.
+// GEMM_DIGITS: int8 digit products of the outlier columns, reassembled per wave into the fp64 product.  A
+// wave's 8 x 4 accumulator tiles are then 2 weight digits x 4 panels against the 4 digit planes of ONE token
+// tile, so every lane holds all eight partial sums of its 16 outputs and nothing has to meet in memory.
 // NSLOT: LDS ring slots (NSLOT - 1 stages are requested ahead).
 template <int MODE, int WVN, int WVM, int TN, int TM, int NSLOT>
 __global__ void __launch_bounds__(64 * WVN * WVM, 2)   // two waves per SIMD: at most 256 registers
@@ -318,23 +283,30 @@ k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, 
     const int rem = ord - strip * STRIP * nb_n, sw_this = min(STRIP, nb_m - strip * STRIP);
     const int bn = rem / sw_this, bm = strip * STRIP + rem % sw_this;
 
-    const int M = ga.M, N = ga.N;
-    // tile rows on either side: the digit product stacks count[1] digit planes of the 16-padded token rows and
-    // takes its features from a window of the digit tile array
-    const int NT = DIG ? ga.a_rows : N >> 4, MTT = DIG ? os.count[1] * ((M + 15) >> 4) : (M + 15) >> 4;
+    const int M = ga.M, N = ga.N, NT = N >> 4, MTT = (M + 15) >> 4;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, row = lane & 15, kg = lane >> 4;
     const int wn = wave / WVM, wm = wave % WVM;
     const int nt0 = (ga.nb_n0 + bn) * BN, mt0 = bm * BM;
-    if (DIG && mt0 >= MTT) return;                   // a digit plane nobody needs (the grid is sized for all of them)
-    auto a_tile_row = [&](int nt) { return !DIG ? nt : (nt < ga.a_split ? ga.a_row0 + nt : ga.a_row1 + nt - ga.a_split); };
+    if (DIG && ga.plane_group * 4 >= os.count[1]) return;     // no activation needs these digit planes
 
     // the stage tiles this wave copies: s = wave + NW*j; s < BN: weight tile, else token tile
     const unsigned char *src[LOADS];
 #pragma unroll
     for (int j = 0; j < LOADS; j++) {
         const int s = wave + NW * j;
-        if (s < BN) src[j] = ga.a_tiles + (size_t)a_tile_row(min(nt0 + s, NT - 1)) * NS * 1024 + lane * 16;
-        else src[j] = ga.b_tiles + (size_t)min(mt0 + s - BN, MTT - 1) * NS * 1024 + lane * 16;
+        if constexpr (DIG) {
+            static_assert(MODE != GEMM_DIGITS || (TN == 8 && TM == 4), "digit slots: 2 digits x 4 panels, 4 planes of one token tile");
+            if (s < BN) {                    // slot: wave column s / 8, digit (s % 8) / 4, panel 4 * (2 bn + s / 8) + s % 4
+                const int panel = min((bn * WVN + s / TN) * 4 + (s & 3), NT - 1);
+                src[j] = ga.a_tiles + ((size_t)((s % TN) / 4) * NT + panel) * NS * 1024 + lane * 16;
+            } else {                         // slot: wave row t / 4 = token tile, plane t % 4 of the group
+                const int t = s - BN, plane = min(ga.plane_group * 4 + (t & 3), PS_X_DIGITS - 1);
+                src[j] = ga.b_tiles + ((size_t)plane * MTT + min(bm * WVM + t / TM, MTT - 1)) * NS * 1024 + lane * 16;
+            }
+        } else {
+            if (s < BN) src[j] = ga.a_tiles + (size_t)min(nt0 + s, NT - 1) * NS * 1024 + lane * 16;
+            else src[j] = ga.b_tiles + (size_t)min(mt0 + s - BN, MTT - 1) * NS * 1024 + lane * 16;
+        }
     }
 
     typedef typename std::conditional<F16, v4f, v4i>::type acc_t;
@@ -468,16 +440,40 @@ k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, 
     static_assert(TN % 8 == 0, "a stage is multiplied in eighths; the epilogue parks half of the accumulators at a time");
     acc_t *mine = (acc_t *)lds + (size_t)wave * (QN * TM * 64) + lane;
     if constexpr (DIG) {
-        // raw sums: D[lane][r] = feature 4 * (l/16) + r of the weight tile, token row l%16 of the token tile
+        // acc[digit * 4 + p][j]: lane (token row l%16, features 4 * (l/16) + r) of panel p, weight digit, plane j.
+        // sum_k x * Wd = u_n * 2^-24 * (m_n * sum_j 256^j A_code[j] + sum_j 256^j A_rem[j]), taken in fp64 from the top
+        // plane down: exact below 2^53, i.e. up to the last step, and good to 1 part in 2^53 after it.
+        const int tt = bm * WVM + wm, t = tt * 16 + row;
+        const int live = min(4, os.count[1] - ga.plane_group * 4);       // planes 6, 7 do not exist
+        if (tt < MTT) {                                                  // wave-uniform
 #pragma unroll
-        for (int i = 0; i < TN; i++) {
-            const int nt = nt0 + wn * TN + i;
-            if (nt >= NT) continue;                                      // wave-uniform
+            for (int p = 0; p < 4; p++) {
+                const int panel = (bn * WVN + wn) * 4 + p;
+                if (panel >= NT) continue;                               // wave-uniform
+                const int n0 = panel * 16 + 4 * kg;
+                const float4 s4 = *(const float4 *)(w.sw + n0);
+                const float sv[4] = {s4.x, s4.y, s4.z, s4.w};
+                v4d res;
 #pragma unroll
-            for (int j = 0; j < TM; j++) {
-                const int mt = mt0 + wm * TM + j;
-                if (mt >= MTT) continue;                                 // wave-uniform
-                *(v4i *)(ga.raw + (size_t)(mt * 16 + row) * ga.ldr + nt * 16 + 4 * kg) = acc[i][j];
+                for (int r = 0; r < 4; r++) {
+                    double tc = 0.0, tr = 0.0;
+#pragma unroll
+                    for (int j = 3; j >= 0; j--) {
+                        if (j < live) {
+                            tc = tc * 256.0 + (double)acc[p][j][r];
+                            tr = tr * 256.0 + (double)acc[4 + p][j][r];
+                        }
+                    }
+                    float a;
+                    int E, m;
+                    digit_scale(sv[r], a, E, m);
+                    res[r] = ldexp((double)m * tc + tr, E - 34 + 32 * ga.plane_group);   // u = 2^(E-10), activations in units of 2^-24
+                }
+                if (t < M) {
+                    double *dst = ga.od + (size_t)t * N + n0;
+                    if (ga.plane_group) res += *(const v4d *)dst;
+                    *(v4d *)dst = res;
+                }
             }
         }
     } else if constexpr (F16) {
@@ -719,42 +715,24 @@ hipError_t ps_gemm_f16_tiles(const __half *feat_tiles, const __half *tok_tiles, 
     return launch_lds<GEMM_F16>(ga, w, nullptr, os, nullptr, o, nullptr, st);
 }
 
-// Output features per digit product: as many as keep the raw sums of a call of M rows within PS_MANY_RAW_BYTES
-size_t ps_many_chunk_features(int N, int M) {
-    const size_t Mp = ((size_t)M + 15) / 16 * 16;
-    size_t nc = PS_MANY_RAW_BYTES / ((size_t)PS_X_DIGITS * Mp * 2 * 4) / 256 * 256;
-    if (nc < 256) nc = 256;
-    return nc < (size_t)N ? nc : (size_t)N;
-}
-
 hipError_t ps_gemm_lds(const LinearW &w, const int8_t *xq_tiled, const uint32_t *mask, const __half *X, const float *sx,
                        int M, const OutlierSet &os, const ManyOutliers &mo, const OutDesc &o, const SessTable *sess,
                        hipStream_t st) {
     // The outlier-heavy case first (every kernel of it returns at once when the call has few outlier columns):
-    // column list, digit tiles of the activations and of the dequantized weights, then per chunk of output
-    // features the two digit products (codes, remainders) and their reassembly into od[M, N].
+    // column list, digit tiles of the activations and of the dequantized weights, the digit products (a second
+    // launch for digit planes 4 and 5, which only activations of magnitude 127.5 and more have).
     k_outlier_list<<<1, 1024, 0, st>>>(mask, w.K, os.count, mo.list);
     k_limb_x<2><<<2048, 64, 0, st>>>(X, M, w.K, (int *)os.count, mo.list, mo.xl);
     k_digit_w<2><<<4096, 64, 0, st>>>(w, os.count, mo.list, mo.wd);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const int NT = w.N / 16, MTT = (M + 15) / 16, NC = min(mo.chunk, w.N);
-    for (int n0 = 0; n0 < w.N; n0 += NC) {
-        const int nc = min(NC, w.N - n0);
-        GemmArgs gd = gemm_args(mo.wd, mo.xl, 0, M, 2 * nc);
-        gd.a_row0 = n0 / 16;                   // codes of features n0 .. n0 + nc
-        gd.a_row1 = NT + n0 / 16;              // their remainders
-        gd.a_split = nc / 16;
-        gd.a_rows = 2 * (nc / 16);
-        gd.raw = mo.raw;
-        gd.ldr = 2 * nc;
-        gd.nb_n = (gd.a_rows + 15) / 16;
-        gd.nb_m = (PS_X_DIGITS * MTT + 15) / 16;
+    for (int pg = 0; pg < 2; pg++) {
+        GemmArgs gd = gemm_args(mo.wd, mo.xl, 0, M, w.N);
+        gd.plane_group = pg;
+        gd.od = mo.od;
+        gd.nb_n = (w.N / 16 + 7) / 8;            // 8 panels and 4 token tiles per block (times 2 digits, 4 planes)
+        gd.nb_m = ((M + 15) / 16 + 3) / 4;
         e = launch_one<GEMM_DIGITS, 4>(gd, w, sx, os, nullptr, o, sess, st);
-        if (e != hipSuccess) return e;
-        const size_t quads = (size_t)M * (nc / 4);
-        k_combine_digits<<<(unsigned)((quads + 255) / 256), 256, 0, st>>>(mo.raw, os.count, w.sw, M, w.N, n0, nc, mo.od);
-        e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     GemmArgs gi = gemm_args(w.wt, xq_tiled, w.K / 64, M, w.N);
