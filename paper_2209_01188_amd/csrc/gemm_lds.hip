@@ -256,7 +256,10 @@ enum { GEMM_INT8 = 0, GEMM_F16 = 1, GEMM_DIGITS = 2 };
 // wave's 8 x 4 accumulator tiles are then 2 weight digits x 4 panels against the 4 digit planes of ONE token
 // tile, so every lane holds all eight partial sums of its 16 outputs and nothing has to meet in memory.
 // NSLOT: LDS ring slots (NSLOT - 1 stages are requested ahead).
-template <int MODE, int WVN, int WVM, int TN, int TM, int NSLOT>
+// EPI (GEMM_INT8 only): what is fused before the fp16 rounding, 0 nothing, 1 tanh-GeLU, 2 + residual; a template
+// argument because the tail's arithmetic must be straight-line code for the 16 outputs a lane finishes at a time
+// to overlap (with run-time switches inside, every output's chain of dependent fp64 operations ran on its own).
+template <int MODE, int WVN, int WVM, int TN, int TM, int NSLOT, int EPI>
 __global__ void __launch_bounds__(64 * WVN * WVM, 2)   // two waves per SIMD: at most 256 registers
 k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, const double *__restrict__ outl, OutDesc o,
            const SessTable *__restrict__ sess) {
@@ -526,7 +529,6 @@ k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, 
         __half *yrow[TM];            // plain: y row; fused QKV: query row
         __half *kvrow[TM];           // fused QKV: session cache + position * d
         int capd[TM];
-        const __half *rrow[TM];
         int trow[TM];
 #pragma unroll
         for (int j = 0; j < TM; j++) {
@@ -535,7 +537,6 @@ k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, 
             trow[j] = ok ? t : -1;
             const int tc = ok ? t : 0;
             sxd[j] = (double)(sx[tc] / 127.0f);
-            rrow[j] = o.epilogue == 2 ? o.resid + (size_t)tc * N : nullptr;
             kvrow[j] = nullptr;
             capd[j] = 0;
             if (!o.scatter) {
@@ -576,52 +577,107 @@ k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, 
 #pragma unroll
                 for (int c = 0; c < XC; c++)
                     aw[c] = c < nch ? os.wd64[((size_t)nt * PS_OUTLIER_CHUNKS + c) * 64 + lane] : 0.0;
+                // 1. operands of the TM token tiles of this panel: parked sums, residuals, the outlier part
+                v4i a4[TM];
+                v4h r4[TM];
+                v4d od[TM];
 #pragma unroll
                 for (int j = 0; j < TM; j++) {
-                    const v4i a4 = mine[(i * TM + j) * 64];
-                    const int t = trow[j];
-                    v4d od = {0.0, 0.0, 0.0, 0.0};
-                    if (many) {
-                        if (t >= 0) od = *(const v4d *)(outl + (size_t)t * N + n0);
-                    } else if (nch > 0) {
+                    a4[j] = mine[(i * TM + j) * 64];
+                    if constexpr (EPI == 2) r4[j] = *(const v4h *)(o.resid + (size_t)max(trow[j], 0) * N + n0);   // rows out of range read row 0
+                    od[j] = (v4d){0.0, 0.0, 0.0, 0.0};
+                }
+                if (many) {
+#pragma unroll
+                    for (int j = 0; j < TM; j++)
+                        if (trow[j] >= 0) od[j] = *(const v4d *)(outl + (size_t)trow[j] * N + n0);
+                } else if (nch > 0) {
+#pragma unroll
+                    for (int j = 0; j < TM; j++) {
 #pragma unroll
                         for (int c = 0; c < XC; c++)
-                            if (c < nch) od = __builtin_amdgcn_mfma_f64_16x16x4f64(aw[c], xw[j][c], od, 0, 0, 0);
+                            if (c < nch) od[j] = __builtin_amdgcn_mfma_f64_16x16x4f64(aw[c], xw[j][c], od[j], 0, 0, 0);
                         if (nch > XC) {
                             const double *ap = os.wd64 + (size_t)nt * PS_OUTLIER_CHUNKS * 64 + lane;
                             const double *bp = os.x64 + (size_t)min(mt0 + wm * TM + j, MTT - 1) * PS_OUTLIER_CHUNKS * 64 + lane;
                             for (int c = XC; c < nch; c++)
-                                od = __builtin_amdgcn_mfma_f64_16x16x4f64(ap[c * 64], bp[c * 64], od, 0, 0, 0);
+                                od[j] = __builtin_amdgcn_mfma_f64_16x16x4f64(ap[c * 64], bp[c * 64], od[j], 0, 0, 0);
                         }
                     }
-                    if (t < 0) continue;
-                    v4h r4 = {(_Float16)0, (_Float16)0, (_Float16)0, (_Float16)0};
-                    if (o.epilogue == 2) r4 = *(const v4h *)(rrow[j] + n0);
-                    __half out[4], pre[4];
+                }
+                // 2. the arithmetic of the 4 TM outputs, no branch inside, written one operation at a time over all of
+                //    them so that consecutive instructions are independent (a wave issues in order)
+                constexpr int NE = 4 * TM;
+                double vv[NE];
 #pragma unroll
-                    for (int r = 0; r < 4; r++) {
-                        double v = (double)a4[r] * sxd[j] * swd4[r] + od[r] + bias4[r];
-                        if (o.pre_out) pre[r] = d2h_rn(v);
-                        if (o.epilogue == 1) v = gelu_tanh(v);
-                        else if (o.epilogue == 2) v += (double)(float)r4[r];
-                        out[r] = d2h_rn(v);
+                for (int e = 0; e < NE; e++) vv[e] = (double)a4[e >> 2][e & 3];
+#pragma unroll
+                for (int e = 0; e < NE; e++) vv[e] *= sxd[e >> 2];
+#pragma unroll
+                for (int e = 0; e < NE; e++) vv[e] = vv[e] * swd4[e & 3] + od[e >> 2][e & 3];
+#pragma unroll
+                for (int e = 0; e < NE; e++) vv[e] += bias4[e & 3];
+                if constexpr (EPI == 1) {
+#pragma unroll
+                    for (int e = 0; e < NE; e++) vv[e] = gelu_tanh(vv[e]);
+                } else if constexpr (EPI == 2) {
+#pragma unroll
+                    for (int e = 0; e < NE; e++) vv[e] += (double)(float)r4[e >> 2][e & 3];
+                }
+                // one rounding to fp16: through fp32 rounded to odd (see d2h_rn)
+                float ff[NE];
+#pragma unroll
+                for (int e = 0; e < NE; e++) ff[e] = (float)vv[e];
+                bool inexact[NE], away[NE];
+#pragma unroll
+                for (int e = 0; e < NE; e++) {
+                    const double fd = (double)ff[e];
+                    inexact[e] = fd != vv[e];
+                    away[e] = fabs(fd) > fabs(vv[e]);
+                }
+                __half out[TM][4];
+#pragma unroll
+                for (int e = 0; e < NE; e++) {
+                    uint32_t u = __float_as_uint(ff[e]);
+                    u = inexact[e] ? ((away[e] ? u - 1u : u) | 1u) : u;
+                    out[e >> 2][e & 3] = __float2half_rn(__uint_as_float(u));
+                }
+                // (pins the arithmetic above this point: otherwise the compiler sinks each token tile's share of it
+                // into that tile's conditional store below, and the chains no longer overlap)
+                v2i packed[TM];
+#pragma unroll
+                for (int j = 0; j < TM; j++) {
+                    packed[j] = *(const v2i *)out[j];
+                    asm volatile("" : "+v"(packed[j][0]), "+v"(packed[j][1]));
+                }
+                // 3. stores and the optional by-products
+#pragma unroll
+                for (int j = 0; j < TM; j++) {
+                    const int t = trow[j];
+                    if (t < 0) continue;
+                    if (o.acc_out) *(v4i *)(o.acc_out + (size_t)t * N + n0) = a4[j];
+                    if (o.pre_out) {                     // the sum before the fused GeLU / residual (backward pass)
+                        __half pre[4];
+#pragma unroll
+                        for (int r = 0; r < 4; r++) pre[r] = d2h_rn((double)a4[j][r] * sxd[j] * swd4[r] + od[j][r] + bias4[r]);
+                        *(v2i *)(o.pre_out + (size_t)t * N + n0) = *(const v2i *)pre;
                     }
-                    if (o.acc_out) *(v4i *)(o.acc_out + (size_t)t * N + n0) = a4;
-                    if (o.pre_out) *(v2i *)(o.pre_out + (size_t)t * N + n0) = *(const v2i *)pre;
                     __half *dst;
                     if (sc.x < 0) {
                         dst = yrow[j] + sc.y;
                         if (o.next_mask) {               // collected per block in LDS, sent once below
                             uint32_t bits = 0;
 #pragma unroll
-                            for (int r = 0; r < 4; r++)
-                                if (fabsf(__half2float(out[r])) >= o.next_theta) bits |= 1u << ((n0 + r) & 31);
+                            for (int r = 0; r < 4; r++) {
+                                const __half hv = __ushort_as_half((unsigned short)((uint32_t)packed[j][r >> 1] >> ((r & 1) * 16)));
+                                if (fabsf(__half2float(hv)) >= o.next_theta) bits |= 1u << ((n0 + r) & 31);
+                            }
                             if (bits) atomicOr(&col_flag[(ntl * 16 + 4 * kg) >> 5], bits);
                         }
                     } else {
                         dst = kvrow[j] + (size_t)sc.x * capd[j] + sc.y;
                     }
-                    *(v2i *)dst = *(const v2i *)out;
+                    *(v2i *)dst = packed[j];
                 }
             }
         }
@@ -634,7 +690,7 @@ k_gemm_lds(GemmArgs ga, LinearW w, const float *__restrict__ sx, OutlierSet os, 
     }
 }
 
-template <int MODE, int TM>
+template <int MODE, int TM, int EPI = 0>
 hipError_t launch_one(const GemmArgs &ga, const LinearW &w, const float *sx, const OutlierSet &os, const double *outl,
                       const OutDesc &o, const SessTable *sess, hipStream_t st) {
     constexpr int WVN = 2, WVM = 4, TN = 8, NSLOT = 4, BN = WVN * TN, BM = WVM * TM;   // 8 waves, 128 x (16 TM) per wave
@@ -642,7 +698,7 @@ hipError_t launch_one(const GemmArgs &ga, const LinearW &w, const float *sx, con
     const size_t lds_stage = (size_t)NSLOT * (BN + BM) * 1024;
     const size_t lds_epi = (size_t)WVN * WVM * (TN / 2) * TM * 1024 + (size_t)BN * 16 * 16 + (size_t)BN * 4 * 8 + (size_t)BN / 2 * 4;
     const size_t lds = lds_stage > lds_epi ? lds_stage : lds_epi;
-    auto kern = k_gemm_lds<MODE, WVN, WVM, TN, TM, NSLOT>;
+    auto kern = k_gemm_lds<MODE, WVN, WVM, TN, TM, NSLOT, EPI>;
     static std::mutex attr_lock;
     static bool attr_set = false;
     {
@@ -662,6 +718,16 @@ hipError_t launch_one(const GemmArgs &ga, const LinearW &w, const float *sx, con
 // rounds for the work of 3.5).  In that case the feature blocks of the last round go to a second launch with
 // blocks of half the token height (256 x 128, 128 x 32 per wave), which fills all units for a shorter round
 // (measured: 2 to 4 % of the linear's time; 4-wave workgroups with a 3-slot ring, two per unit, were slower).
+template <int MODE, int TM>
+hipError_t launch_epi(const GemmArgs &ga, const LinearW &w, const float *sx, const OutlierSet &os, const double *outl,
+                      const OutDesc &o, const SessTable *sess, hipStream_t st) {
+    if constexpr (MODE == GEMM_INT8) {
+        if (o.epilogue == 1) return launch_one<MODE, TM, 1>(ga, w, sx, os, outl, o, sess, st);
+        if (o.epilogue == 2) return launch_one<MODE, TM, 2>(ga, w, sx, os, outl, o, sess, st);
+    }
+    return launch_one<MODE, TM, 0>(ga, w, sx, os, outl, o, sess, st);
+}
+
 template <int MODE>
 hipError_t launch_lds(const GemmArgs &ga0, const LinearW &w, const float *sx, const OutlierSet &os, const double *outl,
                       const OutDesc &o, const SessTable *sess, hipStream_t st) {
@@ -678,11 +744,11 @@ hipError_t launch_lds(const GemmArgs &ga0, const LinearW &w, const float *sx, co
         ga.nb_n -= gb.nb_n;
         gb.nb_n0 = ga.nb_n;
         gb.nb_m = (MTT + BM / 2 - 1) / (BM / 2);
-        hipError_t e = launch_one<MODE, 4>(ga, w, sx, os, outl, o, sess, st);
+        hipError_t e = launch_epi<MODE, 4>(ga, w, sx, os, outl, o, sess, st);
         if (e != hipSuccess) return e;
-        return launch_one<MODE, 2>(gb, w, sx, os, outl, o, sess, st);
+        return launch_epi<MODE, 2>(gb, w, sx, os, outl, o, sess, st);
     }
-    return launch_one<MODE, 4>(ga, w, sx, os, outl, o, sess, st);
+    return launch_epi<MODE, 4>(ga, w, sx, os, outl, o, sess, st);
 }
 
 GemmArgs gemm_args(const void *a_tiles, const void *b_tiles, int ktiles, int M, int N) {
