@@ -212,7 +212,8 @@ def main():
                                 "ms_per_call": round(r["ms_per_call"], 3), "tokens_per_s": round(r["tokens_per_s"], 1),
                                 "int8_top_s": round(r["int8_top_s"], 1), "mfma_frac": round(r["int8_top_s"] / 5000.0, 4),
                                 "mfma_kernel": "k_gemm_lds on the QKV and up linears, against the 5000 TOP/s dense int8 peak",
-                                "per_block_ms": r["per_block_ms"], "per_linear_top_s": r["per_linear_top_s"]}
+                                "per_block_ms": r["per_block_ms"], "per_linear_top_s": r["per_linear_top_s"],
+                                "outlier_columns_mean_over_blocks": r["outlier_columns"]}
         print("[bench] prefill %d x %d: %.1f ms per call, int8 GEMM %.0f TOP/s" %
               (PRE_B, PRE_T, r["ms_per_call"], r["int8_top_s"]), file=sys.stderr, flush=True)
     span.close()
@@ -292,7 +293,8 @@ def measure_prefill(args, span, dev, B, T=512, steps=2, warmup=1):
     lin_ms = [pm[binding.PROFILE_LINEAR0 + i] / NB for i in range(4)]
     int8_ops, int8_ms = ops[0] + ops[2], lin_ms[0] + lin_ms[2]
     names = ("qkv", "dense", "up", "down")
-    return {"ms_per_call": ms, "tokens_per_s": M / (ms * 1e-3), "rows": M, "sessions": B, "tokens_per_session": T,
+    counts = span.outlier_counts().float().mean(0).cpu().tolist()       # of the call just run, averaged over the blocks
+    return {"outlier_columns": {n: round(counts[i], 1) for i, n in enumerate(names)},"ms_per_call": ms, "tokens_per_s": M / (ms * 1e-3), "rows": M, "sessions": B, "tokens_per_session": T,
             "int8_top_s": int8_ops / (int8_ms * 1e-3) / 1e12,
             "per_block_ms": dict({n: round(lin_ms[i], 3) for i, n in enumerate(names)},
                                  attention=round(pm[binding.PROFILE_ATTENTION] / NB, 3)),
@@ -324,7 +326,8 @@ def prefill_main(args, dev):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": "12-block BLOOM-176B-shaped span (H=14336, F=57344), prefill of %d sessions x 512 tokens "
                                "(%d rows per linear)" % (B, M),
-                   "per_block_ms": r["per_block_ms"], "per_linear_top_s": r["per_linear_top_s"]},
+                   "per_block_ms": r["per_block_ms"], "per_linear_top_s": r["per_linear_top_s"],
+                   "outlier_columns_mean_over_blocks": r["outlier_columns"]},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 1), "peak": 5000.0, "unit": "TOP/s",
                      "frac": round(achieved / 5000.0, 4), "traffic": None, "kernel": "k_gemm_lds (qkv and up linears)"},
         "cpu_baseline": None,

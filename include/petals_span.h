@@ -282,6 +282,14 @@ int petals_debug_layernorm(petals_span *span, int32_t block, int32_t which, cons
                            int32_t M, void *y, int8_t *xq, float *sx, uint8_t *outlier_mask,
                            void *stream);
 
+/*
+ * Outlier columns of the span's last call of MORE THAN ONE row, per linear: counts dev int32 [n_blocks][4]
+ * (qkv, dense, up, down) = the number of input columns that call sent through the 16-bit part of the mixed
+ * decomposition (Section 3.1).  One-row calls detect their outlier columns inside the fused kernel and leave
+ * these counts untouched.
+ */
+int petals_debug_outlier_counts(petals_span *span, int32_t *counts, void *stream);
+
 /* Row-major int8 codes [N, K] and row scales [N] of a loaded linear (dev outputs). */
 int petals_debug_export_weight(petals_span *span, int32_t block, int32_t which, int8_t *wq,
                                float *sw, void *stream);

@@ -59,7 +59,7 @@ EXPORTS = ["petals_span_weight_bytes", "petals_span_workspace_bytes", "petals_sp
            "petals_debug_export_weight", "petals_debug_export_kv", "petals_debug_import_kv",
            "petals_span_profile_begin", "petals_span_profile_end", "petals_debug_layernorm", "petals_session_replay",
            "petals_span_backward_bytes", "petals_span_backward", "petals_debug_backward_product",
-           "petals_span_backward_cache_bytes", "petals_span_backward_attach_cache", "petals_bench_mfma"]
+           "petals_span_backward_cache_bytes", "petals_span_backward_attach_cache", "petals_bench_mfma", "petals_debug_outlier_counts"]
 CLIENT_EXPORTS = ["petals_client_workspace_bytes", "petals_client_create", "petals_client_destroy",
                   "petals_client_embed", "petals_client_lm_head", "petals_client_sample"]
 PROFILE_GEMV, PROFILE_GEMM, PROFILE_ATTENTION, PROFILE_LINEAR0 = 0, 1, 2, 3
@@ -248,6 +248,10 @@ def petals_bench_mfma(kind, random_operands, iters, workgroups, out):
     return ops.value
 
 
+def petals_debug_outlier_counts(span, counts):
+    _check(lib().petals_debug_outlier_counts(span, _ptr(counts), _stream()))
+
+
 def petals_debug_export_weight(span, block, which, wq, sw):
     _check(lib().petals_debug_export_weight(span, C.c_int32(block), C.c_int32(which), _ptr(wq), _ptr(sw), _stream()))
 
@@ -360,6 +364,12 @@ class Span:
                    sx=torch.empty(M, dtype=torch.float32, device=self.device),
                    mask=torch.empty(H, dtype=torch.uint8, device=self.device))
         petals_debug_layernorm(self.handle, block, which, x, y, out["xq"], out["sx"], out["mask"])
+        return out
+
+    def outlier_counts(self):
+        """int32 [n_blocks, 4]: outlier columns per linear in the last call of more than one row."""
+        out = torch.empty((self.n_blocks, 4), dtype=torch.int32, device=self.device)
+        petals_debug_outlier_counts(self.handle, out)
         return out
 
     def export_weight(self, block, which):

@@ -576,6 +576,12 @@ int petals_debug_layernorm(petals_span *sp, int32_t block, int32_t which, const 
     return PETALS_OK;
 }
 
+int petals_debug_outlier_counts(petals_span *sp, int32_t *counts, void *stream) {
+    if (!sp || !counts) return fail(PETALS_ERR_INVALID_ARG, "null pointer");
+    HIP_TRY(ps_mask_count(sp->ws.masks, sp->cfg.n_blocks * 4, (int)sp->ws.mask_words, counts, (hipStream_t)stream));
+    return PETALS_OK;
+}
+
 int petals_debug_export_weight(petals_span *sp, int32_t block, int32_t which, int8_t *wq, float *sw, void *stream) {
     if (!sp) return fail(PETALS_ERR_INVALID_ARG, "null span");
     if (block < 0 || block >= sp->cfg.n_blocks || which < 0 || which > 3) return fail(PETALS_ERR_INVALID_ARG, "block or linear index out of range");

@@ -114,6 +114,7 @@ hipError_t ps_colmask(const __half *X, int M, int K, float theta, uint32_t *mask
 hipError_t ps_rowquant_tiled(const __half *X, int M, int K, const uint32_t *mask, int8_t *xq_tiled, int8_t *xo_tiled,
                              float *sx, int8_t *xq_rowmajor_dbg, hipStream_t st);
 hipError_t ps_mask_to_bytes(const uint32_t *mask, int K, uint8_t *out, hipStream_t st);
+hipError_t ps_mask_count(const uint32_t *masks, int n_masks, int words, int32_t *out, hipStream_t st);
 
 // Scratch of the outlier-heavy case of a prefill-size call (more than PS_EXACT_OUTLIERS columns): the fp16
 // product over the outlier columns is taken exactly, as int8 digit products (see gemm_lds.hip)

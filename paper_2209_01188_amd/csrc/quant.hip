@@ -396,6 +396,15 @@ __global__ void __launch_bounds__(NT) k_rowquant_tiled_wide(const __half *__rest
     }
 }
 
+// out[i] = number of set bits of the i-th mask of `words` words (one workgroup per mask)
+__global__ void __launch_bounds__(256) k_mask_count(const uint32_t *__restrict__ masks, int words, int32_t *__restrict__ out) {
+    __shared__ float sm[4];
+    int c = 0;
+    for (int i = threadIdx.x; i < words; i += 256) c += __popc(masks[(size_t)blockIdx.x * words + i]);
+    const float total = block_sum<4>((float)c, sm);          // at most 65536 bits: exact in fp32
+    if (threadIdx.x == 0) out[blockIdx.x] = (int32_t)total;
+}
+
 __global__ void k_mask_to_bytes(const uint32_t *__restrict__ mask, int K, uint8_t *__restrict__ out) {
     int k = blockIdx.x * blockDim.x + threadIdx.x;
     if (k < K) out[k] = (mask[k >> 5] >> (k & 31)) & 1u;
@@ -504,6 +513,10 @@ hipError_t ps_rowquant_tiled(const __half *X, int M, int K, const uint32_t *mask
         k_rowquant_tiled_wide<1024, 4><<<rows, 1024, 0, st>>>(X, M, K, mask, xq_tiled, xo_tiled, sx, xq_dbg);
     else
         k_rowquant_tiled<<<rows, 256, 0, st>>>(X, M, K, mask, xq_tiled, xo_tiled, sx, xq_dbg);
+    return hipGetLastError();
+}
+hipError_t ps_mask_count(const uint32_t *masks, int n_masks, int words, int32_t *out, hipStream_t st) {
+    k_mask_count<<<n_masks, 256, 0, st>>>(masks, words, out);
     return hipGetLastError();
 }
 hipError_t ps_mask_to_bytes(const uint32_t *mask, int K, uint8_t *out, hipStream_t st) {

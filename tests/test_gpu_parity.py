@@ -737,6 +737,7 @@ def test_many_outlier_columns_give_the_oracles_bits(M, n_out, scale):
             torch.cuda.synchronize()
             assert np.array_equal(to_np(out["mask"]), dbg["mask"]) and np.array_equal(to_np(out["xq"]), dbg["xq"])
             assert np.array_equal(to_np(out["acc"]), dbg["acc"])
+            assert int(gsp.outlier_counts()[0, 0]) == n_out        # the test hook runs its linear on the first mask slot
             _bits_equal(to_np(out["y"]), Y, "linear %d, %d rows, %d outlier columns up to %g" % (which, M, n_out, scale))
     finally:
         gsp.close(); osp.destroy()
@@ -884,3 +885,46 @@ def test_codes_as_span_input_equal_dequantize_then_step(name, nb, B, T, H):
         hidden_close(to_np(y1)[:, None], osp.step(oses, x), "step after codes in")
     finally:
         gsp.close(); osp.destroy()
+
+
+@pytest.mark.timeout(600)
+def test_c4_full_size_dense_and_down_linears_at_4096_rows_with_thousands_of_outlier_columns():
+    """The prefill benchmark's call (4096 rows) on the two linears whose inputs carry Gaussian tails past the
+    threshold in thousands of columns (dense: attention contexts, down: GeLU outputs), in the launch configuration
+    bench.py times: column list, digit tiles, the digit products over 7168 output blocks and the int8 product over
+    what remains, with the residual added.  The oracle computes a sample of output features; same bits."""
+    cfg = synth.CONFIGS["C4"]
+    M = 4096
+    p = synth.block_params_device(cfg, 0, DEV)
+    gsp = binding.Span(1, cfg.hidden, cfg.n_heads, cfg.F, M, 1e-5, 6.0, DEV)
+    gsp.load_block(0, p)
+    r = np.random.default_rng(41)
+
+    def gelu(v):
+        return 0.5 * v * (1 + np.tanh(0.7978845608028654 * (v + 0.044715 * v ** 3)))
+    try:
+        for which, wname, bname, std in ((1, "w_dense", "b_dense", 1.9), (3, "w_down", "b_down", 1.9)):
+            N, K = gsp.shapes(which)
+            rows = np.unique(np.concatenate([np.arange(8), r.choice(N, 20, replace=False), np.arange(N - 2048, N - 2044),
+                                             np.arange(N - 4, N)]))
+            wq, sw = oracle.quantize_weight(p[wname][torch.as_tensor(rows, device=DEV)].cpu().numpy())
+            bsub = p[bname].cpu().numpy()[rows]
+            X = r.standard_normal((M, K)) * std
+            if which == 3:
+                X = gelu(X)
+            X = X.astype(np.float16)
+            resid = (r.standard_normal((M, N)) * 9).astype(np.float16)
+            Y, dbg = oracle.linear(X, wq, sw, bsub, 6.0, 2, resid[:, rows], want_debug=True)
+            n_out = int(dbg["mask"].sum())
+            assert n_out > 2000
+            print("C4 linear %d at %d rows, %d outlier columns" % (which, M, n_out), flush=True)
+            out = gsp.debug_linear(0, which, to_dev(X), 2, to_dev(resid))
+            torch.cuda.synchronize()
+            assert int(gsp.outlier_counts()[0, 0]) == n_out
+            assert np.array_equal(to_np(out["mask"]), dbg["mask"])
+            assert np.array_equal(to_np(out["xq"]), dbg["xq"]) and np.array_equal(to_np(out["sx"]), dbg["sx"])
+            assert np.array_equal(to_np(out["acc"])[:, rows], dbg["acc"])
+            _bits_equal(to_np(out["y"])[:, rows], Y, "C4 linear %d at %d rows, %d outlier columns" % (which, M, n_out))
+            del out
+    finally:
+        gsp.close()
