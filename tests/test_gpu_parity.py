@@ -928,3 +928,66 @@ def test_c4_full_size_dense_and_down_linears_at_4096_rows_with_thousands_of_outl
             del out
     finally:
         gsp.close()
+
+
+@pytest.mark.timeout(900)
+def test_c5_shape_two_chained_spans_thirty_two_sessions_codec_at_every_boundary():
+    """C5 at reduced depth and prompt length: BLOOM-176B width, 32 sessions, two chained spans of one block each
+    that share one workspace (as the 70-block stack's six spans do), hidden states entering, crossing the span
+    boundary and leaving as blockwise 8-bit codes (decoded inside each span's first LayerNorm), a 4-token prefill
+    (128 rows: prefill-size kernels, thousands of outlier columns) and one decode step for all 32 sessions (the
+    batched-decode kernels at 32 rows).  The oracle is fed the same calls."""
+    cfg = synth.CONFIGS["C5"]
+    H, nh, F, B, T, CB = cfg.hidden, cfg.n_heads, cfg.F, 32, 4, 4096
+    ws_cfg = binding.make_config(1, H, nh, F, B * T)
+    shared = torch.empty(binding.petals_span_workspace_bytes(ws_cfg), dtype=torch.uint8, device=DEV)
+    gsp, osp = [], []
+    for b in range(2):
+        p = synth.block_params_device(cfg, b, DEV)
+        g = binding.Span(1, H, nh, F, B * T, 1e-5, 6.0, DEV, workspace=shared)
+        g.load_block(0, p)
+        o = oracle.Span(1, H, nh, F, 1e-5, 6.0)
+        o.load_block(0, {k: v.cpu().numpy() for k, v in p.items()})
+        del p
+        gsp.append(g); osp.append(o)
+    try:
+        gses = [[g.open_session(T + 1) for _ in range(B)] for g in gsp]
+        oses = [[o.open_session(T + 1) for _ in range(B)] for o in osp]
+
+        def oracle_stack(X):
+            for o, ss in zip(osp, oses):
+                q, am = oracle.hidden_quantize(X, CB)
+                X = o.step(ss, oracle.hidden_dequantize(q, am, CB).reshape(X.shape))
+            return X, oracle.hidden_quantize(X, CB)
+
+        def gpu_stack(X, Tn):
+            x = to_dev(X)
+            for g, ss in zip(gsp, gses):
+                q = torch.empty(x.numel(), dtype=torch.uint8, device=DEV)
+                am = torch.empty((x.numel() + CB - 1) // CB, dtype=torch.float32, device=DEV)
+                binding.petals_hidden_quantize(x, CB, q, am)
+                x = g.prefill_q8(ss, Tn, q, am, CB)
+            q = torch.empty(x.numel(), dtype=torch.uint8, device=DEV)
+            am = torch.empty((x.numel() + CB - 1) // CB, dtype=torch.float32, device=DEV)
+            binding.petals_hidden_quantize(x, CB, q, am)
+            return to_np(x), to_np(q), to_np(am)
+
+        for call, Tn in enumerate((T, 1)):
+            X = synth.hidden_states(cfg, call, B, Tn)
+            print("C5 shape, call %d: %d x %d tokens, oracle ..." % (call, B, Tn), flush=True)
+            Yo, (qo, amo) = oracle_stack(X)
+            print("... GPU", flush=True)
+            Yg, qg, amg = gpu_stack(X, Tn)
+            hidden_close(Yg, Yo, "C5 shape call %d" % call)
+            same = Yg.view(np.uint16) == Yo.view(np.uint16)
+            print("bit-identical outputs: %.6f" % same.mean(), flush=True)
+            assert same.mean() > 0.9999, same.mean()
+            if same.all():
+                assert np.array_equal(qg, qo.reshape(-1)) and np.array_equal(amg, amo)
+        counts = to_np(gsp[1].outlier_counts())            # of the decode call (32 rows): masks of the batched path
+        assert counts.shape == (1, 4)
+    finally:
+        for g in gsp:
+            g.close()
+        for o in osp:
+            o.destroy()
