@@ -93,7 +93,7 @@ def main():
                          "FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (a span per GPU; see DESIGN.md for how spans chain); "
+        print("bench.py: this build runs on ONE GPU (with more, each GPU would hold a span of consecutive blocks); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
