@@ -239,10 +239,10 @@ k_gemm(LinearW w, const int8_t *__restrict__ xq_tiled, const int8_t *__restrict_
     }
 }
 
-template <int WN, int MT, int UK>
+template <int WN, int MT, int UK, int WVK = 8>
 hipError_t launch(const LinearW &w, const int8_t *xq_tiled, const int8_t *xo_tiled, const uint32_t *mask,
                   const __half *X, const float *sx, int M, const OutDesc &o, const SessTable *sess, hipStream_t st) {
-    constexpr int WVK = 8, G = WN * MT, NPP = G < 4 ? G : 4;
+    constexpr int G = WN * MT, NPP = G < 4 ? G : 4;
     const size_t lds = (size_t)WVK * NPP * 64 * (16 + 32);   // up to 96 KB
     auto kern = k_gemm<WN, MT, UK, WVK>;
     static std::mutex attr_lock;
@@ -272,6 +272,9 @@ hipError_t ps_gemm(const LinearW &w, const int8_t *xq_tiled, const int8_t *xo_ti
     const int wn = (panels % 4 == 0 && panels / 4 >= 224) ? 4 : (panels % 2 == 0 && panels / 2 >= 224) ? 2 : 1;
 #define PS_GEMM_CASE(WN_, MT_, UK_) return launch<WN_, MT_, UK_>(w, xq_tiled, xo_tiled, mask, X, sx, M, o, sess, st)
     if (M <= 16) {
+        // one panel per workgroup (narrow outputs): 16 waves split the k-tiles, twice the weight bytes in flight per
+        // compute unit (C3, 8 rows: down 2.85 -> 3.2 TB/s, dense 1.5 -> 1.65 TB/s; with 2 panels 16 waves are slower)
+        if (wn == 1 && w.K >= 4096) return launch<1, 1, 2, 16>(w, xq_tiled, xo_tiled, mask, X, sx, M, o, sess, st);
         if (wn == 4) PS_GEMM_CASE(4, 1, 2);
         if (wn == 2) PS_GEMM_CASE(2, 1, 2);
         PS_GEMM_CASE(1, 1, 4);
