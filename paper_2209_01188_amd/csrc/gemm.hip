@@ -275,8 +275,11 @@ hipError_t ps_gemm(const LinearW &w, const int8_t *xq_tiled, const int8_t *xo_ti
         // one panel per workgroup (narrow outputs): 16 waves split the k-tiles, twice the weight bytes in flight per
         // compute unit (C3, 8 rows: down 2.85 -> 3.2 TB/s, dense 1.5 -> 1.65 TB/s; with 2 panels 16 waves are slower)
         if (wn == 1 && w.K >= 4096) return launch<1, 1, 2, 16>(w, xq_tiled, xo_tiled, mask, X, sx, M, o, sess, st);
+        // small matrices (C3: 50-67 MB, 13-16 us per launch) do better with two workgroups per compute unit and
+        // short chunks (up 3.5 -> 3.8, QKV 3.2 -> 3.25 TB/s); large ones with four panels per workgroup
+        if (wn == 4 && panels / 4 < 448 && (size_t)w.N * w.K <= ((size_t)1 << 27)) PS_GEMM_CASE(2, 1, 2);
         if (wn == 4) PS_GEMM_CASE(4, 1, 2);
-        if (wn == 2) PS_GEMM_CASE(2, 1, 2);
+        if (wn == 2) PS_GEMM_CASE(2, 1, 1);
         PS_GEMM_CASE(1, 1, 4);
     }
     if (M <= 32) {
