@@ -129,6 +129,9 @@ int petals_session_close(petals_session *session);
  * Every linear uses the 8-bit mixed decomposition (Section 3.1): columns whose
  * magnitude reaches outlier_threshold in any of the B*T rows go through fp16
  * with weights dequantized from int8, the rest through int8 x int8 -> int32.
+ * Calls of 65 to 512 rows run each linear either as 256 x 256 output blocks or 64 rows at a time through the
+ * batched-decode kernel, whichever a cost estimate says is faster for that matrix; both give the same bits.
+ * Test hook: PETALS_SPAN_MIDSIZE=blocks or =chunks in the environment (read at every call) forces one of them.
  * Each session's length grows by T.  Errors: B > PETALS_MAX_SESSIONS_PER_CALL,
  * B*T > max_rows_per_call or a full cache -> PETALS_ERR_CAPACITY; the same
  * session twice -> PETALS_ERR_INVALID_ARG.

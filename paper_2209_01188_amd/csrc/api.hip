@@ -66,7 +66,7 @@ Workspace carve(const petals_span_config &c, uint8_t *base) {
     w.xb = (__half *)take(M * H * 2);
     w.g = (__half *)take(M * (F > 3 * H ? F : 3 * H) * 2);   // MLP activations; also scratch for a [M,3H] result
     w.xq = (int8_t *)take(Mp * Kmax);
-    w.xo = (int8_t *)take((Mp < 64 ? Mp : 64) * Kmax);
+    w.xo = (int8_t *)take((Mp < PS_CHUNKED_ROWS_MAX ? Mp : PS_CHUNKED_ROWS_MAX) * Kmax);   // outlier values of calls that take the batched-decode kernel
     w.sx = (float *)take(Mp * 4);
     w.mask_words = (Kmax + 63) / 64 * 2;
     w.masks = (uint32_t *)take((size_t)c.n_blocks * 4 * w.mask_words * 4);
@@ -140,12 +140,34 @@ int run_linear(petals_span *sp, int which, const LinearW &w, const __half *X, co
         } else if (!mask_ready) {
             HIP_TRY(ps_colmask(X, M, w.K, theta, mask, st));
         }
-        HIP_TRY(ps_rowquant_tiled(X, M, w.K, mask, ws.xq, M <= 64 ? ws.xo : nullptr, ws.sx, xq_dbg, st));
+        // calls of a few hundred rows whose output would be too few 256 x 256 blocks to fill the GPU go through
+        // the batched-decode kernel 64 rows at a time (same outlier columns for every pass: those of the whole call)
+        const bool chunks = ps_gemm_prefers_chunks(w, M);
+        HIP_TRY(ps_rowquant_tiled(X, M, w.K, mask, ws.xq, (M <= 64 || chunks) ? ws.xo : nullptr, ws.sx, xq_dbg, st));
         const OutlierSet os = {ws.ocount, ws.wd64, ws.x64};
-        if (M > 64) HIP_TRY(ps_outlier_prep(w, mask, X, M, ws.ocount, ws.wd64, ws.x64, st));
+        if (M > 64 && !chunks) HIP_TRY(ps_outlier_prep(w, mask, X, M, ws.ocount, ws.wd64, ws.x64, st));
         const bool pr = sp->prof.begin(PETALS_PROFILE_GEMM, which, st);
-        if (M <= 64) HIP_TRY(ps_gemm(w, ws.xq, ws.xo, mask, X, ws.sx, M, o, ws.table, st));
-        else HIP_TRY(ps_gemm_lds(w, ws.xq, mask, X, ws.sx, M, os, ws.many, o, ws.table, st));
+        if (M <= 64) {
+            HIP_TRY(ps_gemm(w, ws.xq, ws.xo, mask, X, ws.sx, M, o, ws.table, st));
+        } else if (chunks) {
+            const size_t tile_bytes = (size_t)(w.K / 64) * 1024;
+            for (int r0 = 0; r0 < M; r0 += 64) {
+                OutDesc oc = o;
+                const size_t at = (size_t)r0 * w.N;
+                if (o.scatter) {
+                    oc.t0 = r0;
+                } else {
+                    oc.y = o.y + at;
+                    if (o.resid) oc.resid = o.resid + at;
+                    if (o.pre_out) oc.pre_out = o.pre_out + at;
+                }
+                if (o.acc_out) oc.acc_out = o.acc_out + at;
+                HIP_TRY(ps_gemm(w, ws.xq + (r0 / 16) * tile_bytes, ws.xo + (r0 / 16) * tile_bytes, mask, X + (size_t)r0 * w.K,
+                                ws.sx + r0, M - r0 < 64 ? M - r0 : 64, oc, ws.table, st));
+            }
+        } else {
+            HIP_TRY(ps_gemm_lds(w, ws.xq, mask, X, ws.sx, M, os, ws.many, o, ws.table, st));
+        }
         sp->prof.end(pr, st);
     }
     return PETALS_OK;

@@ -47,6 +47,7 @@ struct OutDesc {
     const __half *resid;  // [M,N]
     int32_t *acc_out;     // optional int32 [M,N] copy of the integer accumulators
     int T, nh, d, blk;    // scatter: row t belongs to session t / T at position len + t % T of block blk
+    int t0;               // scatter: the launch's row 0 is row t0 of the call (a call may be split over launches)
     uint32_t *next_mask;  // optional (scatter == 0): outlier-column bit mask [N/32] of the linear that reads y
     float next_theta;     // a column of y is flagged when any |y| >= next_theta
     __half *pre_out;      // optional (scatter == 0): [M,N] copy of the sum BEFORE the fused GeLU / residual
@@ -149,6 +150,11 @@ hipError_t ps_outlier_prep(const LinearW &w, const uint32_t *mask, const __half 
 // loop); xq_tiled and xo_tiled as written by ps_rowquant_tiled
 hipError_t ps_gemm(const LinearW &w, const int8_t *xq_tiled, const int8_t *xo_tiled, const uint32_t *mask,
                    const __half *X, const float *sx, int M, const OutDesc &o, const SessTable *sess, hipStream_t st);
+// Calls of more than 64 rows that are better served by ps_gemm on 64 rows at a time (each pass streams the
+// weights once, with every compute unit busy) than by the 256 x 256 output blocks of ps_gemm_lds, which
+// leave most of the GPU idle when the call has few of them.  PS_CHUNKED_ROWS_MAX bounds such calls.
+#define PS_CHUNKED_ROWS_MAX 512
+bool ps_gemm_prefers_chunks(const LinearW &w, int M);
 
 // attention of M = B*T query rows against the caches (new keys/values already appended)
 hipError_t ps_set_table(const SessTable &host_table, SessTable *dev_table, hipStream_t st);

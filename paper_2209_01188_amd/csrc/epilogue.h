@@ -18,11 +18,11 @@ __device__ __forceinline__ void emit_output(const OutDesc &o, const SessTable *_
         flag_outlier(o.next_mask, o.next_theta, n, hv);
     } else {
         // fused QKV: output row n = h*3d + p*d + j ; queries to y[M,H], keys/values appended to the caches
-        const int d = o.d, h = n / (3 * d), rem = n - h * 3 * d, p = rem / d, j = rem - p * d;
+        const int d = o.d, h = n / (3 * d), rem = n - h * 3 * d, p = rem / d, j = rem - p * d, tc = t + o.t0;
         if (p == 0) {
-            o.y[(size_t)t * (o.nh * d) + h * d + j] = hv;
+            o.y[(size_t)tc * (o.nh * d) + h * d + j] = hv;
         } else {
-            const int s = t / o.T, cap = sess->cap[s], pos = sess->len[s] + (t - s * o.T);
+            const int s = tc / o.T, cap = sess->cap[s], pos = sess->len[s] + (tc - s * o.T);
             __half *base = sess->kv[s] + ((size_t)o.blk * 2 + (p == 2 ? 1 : 0)) * o.nh * cap * d;
             base[((size_t)h * cap + pos) * d + j] = hv;
         }
@@ -62,11 +62,11 @@ __device__ __forceinline__ void emit_output4(const OutDesc &o, const SessTable *
             flag_outlier_bits(o.next_mask, n0 >> 5, bits);
         }
     } else {
-        const int d = o.d, h = n0 / (3 * d), rem = n0 - h * 3 * d, p = rem / d, j = rem - p * d;
+        const int d = o.d, h = n0 / (3 * d), rem = n0 - h * 3 * d, p = rem / d, j = rem - p * d, tc = t + o.t0;
         if (p == 0) {
-            dst = o.y + (size_t)t * (o.nh * d) + h * d + j;
+            dst = o.y + (size_t)tc * (o.nh * d) + h * d + j;
         } else {
-            const int s = t / o.T, cap = sess->cap[s], pos = sess->len[s] + (t - s * o.T);
+            const int s = tc / o.T, cap = sess->cap[s], pos = sess->len[s] + (tc - s * o.T);
             dst = sess->kv[s] + (((size_t)o.blk * 2 + (p == 2 ? 1 : 0)) * o.nh * cap + (size_t)h * cap + pos) * d + j;
         }
     }

@@ -4,6 +4,10 @@
 // 64-column tile that holds outliers, each of the four 16-column lane groups hands its next outlier
 // column to one k-slot of v_mfma_f64_16x16x4_f64 (products of fp16 values are exact in fp64).
 // Also here: the compaction kernel that prefill-size calls use for the same exact product.
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
 #include <mutex>
 
 #include "common.h"
@@ -263,6 +267,24 @@ hipError_t ps_outlier_prep(const LinearW &w, const uint32_t *mask, const __half 
                            double *x64, hipStream_t st) {
     k_outlier_prep<<<w.N / 16 + (M + 15) / 16, 64, 0, st>>>(w, mask, X, M, count, wd64, x64);
     return hipGetLastError();
+}
+
+// Rough times in microseconds, fitted to measurements on BLOOM-560M-, 7B1- and 176B-shaped linears at 96 to 512
+// rows.  64-row passes: each streams the N*K weight bytes at about 3 TB/s (what the 64-row form reaches), 5 us per
+// launch, 20 us for the row kernels in front.  Output blocks: a 256 x 256 block walks K/64 stages of about 0.7 us,
+// 256 blocks at a time, behind about 45 us of row, outlier and digit kernels that are launched whatever the data.
+// PETALS_SPAN_MIDSIZE=blocks / =chunks in the environment overrides the choice (tests run both ways).
+bool ps_gemm_prefers_chunks(const LinearW &w, int M) {
+    if (M <= 64 || M > PS_CHUNKED_ROWS_MAX) return false;
+    if (const char *force = getenv("PETALS_SPAN_MIDSIZE")) {
+        if (!strcmp(force, "blocks")) return false;
+        if (!strcmp(force, "chunks")) return true;
+    }
+    const double passes = (M + 63) / 64, bytes = (double)w.N * w.K;
+    const double t_chunks = 20.0 + passes * (bytes / 3.0e6 + 5.0);
+    const double blocks = (double)((w.N + 255) / 256) * ((M + 255) / 256);
+    const double t_blocks = 45.0 + ceil(blocks / 256.0) * (w.K / 64) * 0.7;
+    return t_chunks < t_blocks;
 }
 
 hipError_t ps_gemm(const LinearW &w, const int8_t *xq_tiled, const int8_t *xo_tiled, const uint32_t *mask,

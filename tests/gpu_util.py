@@ -1,4 +1,7 @@
 """Helpers shared by the GPU parity tests."""
+import contextlib
+import os
+
 import numpy as np
 import torch
 
@@ -6,6 +9,26 @@ import oracle
 from paper_2209_01188_amd import binding, synth
 
 DEV = "cuda:0"
+
+
+@contextlib.contextmanager
+def midsize(mode):
+    """How the library runs the linears of calls of 65 to 512 rows inside the block: "blocks" = 256 x 256 output
+    blocks on the LDS-pipelined kernel (with the digit products for many outlier columns), "chunks" = the
+    batched-decode kernel on 64 rows at a time, None = its own choice (a cost estimate per linear).  The library
+    reads PETALS_SPAN_MIDSIZE at every call."""
+    old = os.environ.get("PETALS_SPAN_MIDSIZE")
+    if mode is None:
+        os.environ.pop("PETALS_SPAN_MIDSIZE", None)
+    else:
+        os.environ["PETALS_SPAN_MIDSIZE"] = mode
+    try:
+        yield
+    finally:
+        if old is None:
+            os.environ.pop("PETALS_SPAN_MIDSIZE", None)
+        else:
+            os.environ["PETALS_SPAN_MIDSIZE"] = old
 
 
 def to_dev(a):

@@ -5,7 +5,7 @@ import torch
 
 import oracle
 from paper_2209_01188_amd import binding, synth
-from tests.gpu_util import DEV, build_pair, hidden_close, to_dev, to_np
+from tests.gpu_util import DEV, build_pair, hidden_close, midsize, to_dev, to_np
 
 pytestmark = pytest.mark.gpu
 INF = float("inf")
@@ -61,13 +61,15 @@ def _linear_case(cfg, theta, M, which, epilogue, seed, outlier_cols=3):
     wq, sw = osp.get_weight(0, which)
     bias = params[0][("b_qkv", "b_dense", "b_up", "b_down")[which]]
     Y, dbg = oracle.linear(X, wq, sw, bias, theta, epilogue, resid, want_debug=True)
-    out = gsp.debug_linear(0, which, to_dev(X), epilogue, None if resid is None else to_dev(resid))
-    torch.cuda.synchronize()
-    assert np.array_equal(to_np(out["mask"]), dbg["mask"]), "outlier set"
-    assert np.array_equal(to_np(out["sx"]).view(np.uint32), dbg["sx"].view(np.uint32)), "row scales"
-    assert np.array_equal(to_np(out["xq"]), dbg["xq"]), "int8 codes"
-    assert np.array_equal(to_np(out["acc"]), dbg["acc"]), "int32 accumulators"
-    hidden_close(to_np(out["y"]), Y, "linear %d M=%d" % (which, M))
+    for path in (("blocks", "chunks") if 64 < M <= 512 else (None,)):    # mid-size calls: both kernels that may serve them
+        with midsize(path):
+            out = gsp.debug_linear(0, which, to_dev(X), epilogue, None if resid is None else to_dev(resid))
+            torch.cuda.synchronize()
+        assert np.array_equal(to_np(out["mask"]), dbg["mask"]), "outlier set"
+        assert np.array_equal(to_np(out["sx"]).view(np.uint32), dbg["sx"].view(np.uint32)), "row scales"
+        assert np.array_equal(to_np(out["xq"]), dbg["xq"]), "int8 codes"
+        assert np.array_equal(to_np(out["acc"]), dbg["acc"]), "int32 accumulators"
+        hidden_close(to_np(out["y"]), Y, "linear %d M=%d (%s)" % (which, M, path))
     gsp.close(); osp.destroy()
 
 
@@ -710,11 +712,14 @@ def _bits_equal(got, ref, what):
     assert same.all(), "%s: %d of %d outputs differ, first at %s" % (what, (~same).sum(), same.size, np.argwhere(~same)[:3].tolist())
 
 
+@pytest.mark.parametrize("path", ["blocks", "chunks"])
 @pytest.mark.parametrize("M", [65, 200])
 @pytest.mark.parametrize("n_out,scale", [(65, 9.0), (130, 30.0), (700, 9.0), (1024, 9.0), (200, 300.0), (90, 40000.0)])
-def test_many_outlier_columns_give_the_oracles_bits(M, n_out, scale):
+def test_many_outlier_columns_give_the_oracles_bits(M, n_out, scale, path):
     """Prefill-size calls whose outlier columns outnumber the exact fp64 path's limit: the fp16 product over
-    those columns is rebuilt from int8 digit products, which is exact - the outputs are the oracle's bit for bit.
+    those columns is rebuilt from int8 digit products, which is exact - the outputs are the oracle's bit for bit
+    (path "blocks"; with "chunks" the same calls go 64 rows at a time through the batched-decode kernel, whose
+    fp64 products are exact too).
     Outlier magnitudes up to 9, 30 (4 digit planes), 300 (5) and 40000 (6); the other entries of those columns run
     down to fp16's subnormal range; some regular columns remain, or none (1024 of 1024)."""
     cfg = C2
@@ -733,8 +738,9 @@ def test_many_outlier_columns_give_the_oracles_bits(M, n_out, scale):
             bias = params[0][("b_qkv", "b_dense", "b_up", "b_down")[which]]
             Y, dbg = oracle.linear(X, wq, sw, bias, 6.0, epilogue, resid, want_debug=True)
             assert dbg["mask"].sum() == n_out
-            out = gsp.debug_linear(0, which, to_dev(X), epilogue, None if resid is None else to_dev(resid))
-            torch.cuda.synchronize()
+            with midsize(path):
+                out = gsp.debug_linear(0, which, to_dev(X), epilogue, None if resid is None else to_dev(resid))
+                torch.cuda.synchronize()
             assert np.array_equal(to_np(out["mask"]), dbg["mask"]) and np.array_equal(to_np(out["xq"]), dbg["xq"])
             assert np.array_equal(to_np(out["acc"]), dbg["acc"])
             assert int(gsp.outlier_counts()[0, 0]) == n_out        # the test hook runs its linear on the first mask slot
@@ -763,12 +769,14 @@ def test_many_outlier_columns_with_weight_rows_of_every_scale():
         wq, sw = osp.get_weight(0, 2)
         Y, dbg = oracle.linear(X, wq, sw, p["b_up"], 6.0, 0, None, want_debug=True)
         assert dbg["mask"].sum() > 64
-        out = gsp.debug_linear(0, 2, to_dev(X))
-        torch.cuda.synchronize()
-        assert np.array_equal(to_np(out["mask"]), dbg["mask"]) and np.array_equal(to_np(out["acc"]), dbg["acc"])
         finite = np.isfinite(Y)
         assert finite.mean() > 0.99
-        _bits_equal(to_np(out["y"])[finite], Y[finite], "weight rows of every scale")
+        for path in ("blocks", "chunks"):
+            with midsize(path):
+                out = gsp.debug_linear(0, 2, to_dev(X))
+                torch.cuda.synchronize()
+            assert np.array_equal(to_np(out["mask"]), dbg["mask"]) and np.array_equal(to_np(out["acc"]), dbg["acc"])
+            _bits_equal(to_np(out["y"])[finite], Y[finite], "weight rows of every scale (%s)" % path)
     finally:
         gsp.close(); osp.destroy()
 
@@ -787,7 +795,9 @@ def test_c4_width_two_blocks_prefill_of_128_tokens_end_to_end():
         print("C4 width, 2 blocks, %d x %d tokens: oracle ..." % (B, T), flush=True)
         Yo = osp.step(oses, X)
         print("... GPU", flush=True)
-        Yg = to_np(gsp.prefill(gses, to_dev(X)))
+        with midsize("blocks"):       # on its own the library would run dense and down 64 rows at a time at this size
+            Yg = to_np(gsp.prefill(gses, to_dev(X)))
+            torch.cuda.synchronize()
         hidden_close(Yg, Yo, "C4 width 2 blocks prefill")
         same = (Yg.view(np.uint16) == Yo.view(np.uint16)).mean()
         print("bit-identical outputs: %.6f" % same, flush=True)

@@ -9,7 +9,7 @@ import torch
 
 import oracle
 from paper_2209_01188_amd import synth
-from tests.gpu_util import build_pair, hidden_close, to_dev, to_np
+from tests.gpu_util import build_pair, hidden_close, midsize, to_dev, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -55,11 +55,12 @@ def test_random_span_and_schedule_against_the_oracle(seed):
         for c, (who, T) in enumerate(calls):
             X = synth.hidden_states(cfg, c, len(who), T)
             Yo = osp.step([oses[s] for s in who], X)
-            if T == 1:
-                Yg = to_np(gsp.decode_step([gses[s] for s in who], to_dev(X[:, 0])))[:, None]
-            else:
-                Yg = to_np(gsp.prefill([gses[s] for s in who], to_dev(X)))
-            torch.cuda.synchronize()
+            with midsize((None, "blocks", "chunks")[seed % 3]):     # calls of 65 to 512 rows: either kernel, or the library's choice
+                if T == 1:
+                    Yg = to_np(gsp.decode_step([gses[s] for s in who], to_dev(X[:, 0])))[:, None]
+                else:
+                    Yg = to_np(gsp.prefill([gses[s] for s in who], to_dev(X)))
+                torch.cuda.synchronize()
             what = "seed %d (H %d, %d heads, %d blocks, theta %s) call %d: sessions %s x %d tokens" % (
                 seed, cfg.hidden, cfg.n_heads, cfg.n_blocks, theta, c, who, T)
             hidden_close(Yg, Yo, what)
