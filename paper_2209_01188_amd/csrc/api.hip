@@ -145,7 +145,7 @@ int run_linear(petals_span *sp, int which, const LinearW &w, const __half *X, co
         const bool chunks = ps_gemm_prefers_chunks(w, M);
         HIP_TRY(ps_rowquant_tiled(X, M, w.K, mask, ws.xq, (M <= 64 || chunks) ? ws.xo : nullptr, ws.sx, xq_dbg, st));
         const OutlierSet os = {ws.ocount, ws.wd64, ws.x64};
-        if (M > 64 && !chunks) HIP_TRY(ps_outlier_prep(w, mask, X, M, ws.ocount, ws.wd64, ws.x64, st));
+        if (M > 64 && !chunks) HIP_TRY(ps_outlier_prep(w, mask, X, M, ws.ocount, ws.wd64, ws.x64, ws.many.list, st));
         const bool pr = sp->prof.begin(PETALS_PROFILE_GEMM, which, st);
         if (M <= 64) {
             HIP_TRY(ps_gemm(w, ws.xq, ws.xo, mask, X, ws.sx, M, o, ws.table, st));

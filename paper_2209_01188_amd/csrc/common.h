@@ -144,8 +144,9 @@ hipError_t ps_gemv_row(const LinearW &w, const __half *x, const __half *ln_g, co
                        float theta, const RowDebug &dbg, const OutDesc &o, const SessTable *sess, const QuantIn *qin,
                        hipStream_t st);
 // counts the outlier columns of a prefill-size call and, if they are few, compacts their operands
+// full_list (may be null): receives the ascending list of all outlier columns when they are more than that
 hipError_t ps_outlier_prep(const LinearW &w, const uint32_t *mask, const __half *X, int M, int *count, double *wd64,
-                           double *x64, hipStream_t st);
+                           double *x64, int *full_list, hipStream_t st);
 // batched-decode linear, 2 <= M <= 64 rows (int8 MFMA, outlier columns exactly on fp64 MFMA inside the
 // loop); xq_tiled and xo_tiled as written by ps_rowquant_tiled
 hipError_t ps_gemm(const LinearW &w, const int8_t *xq_tiled, const int8_t *xo_tiled, const uint32_t *mask,

@@ -21,7 +21,8 @@ namespace {
 // column list from the bit mask itself.
 __global__ void __launch_bounds__(64) k_outlier_prep(LinearW w, const uint32_t *__restrict__ mask,
                                                      const __half *__restrict__ X, int M, int *__restrict__ count,
-                                                     double *__restrict__ wd64, double *__restrict__ x64) {
+                                                     double *__restrict__ wd64, double *__restrict__ x64,
+                                                     int *__restrict__ full_list) {
     __shared__ int list[PS_EXACT_OUTLIERS];
     const int K = w.K, KT = K >> 6, nwords = K >> 5, lane = threadIdx.x;
     const int wpt = (nwords + 63) / 64, w0 = min(nwords, lane * wpt), w1 = min(nwords, w0 + wpt);
@@ -34,7 +35,22 @@ __global__ void __launch_bounds__(64) k_outlier_prep(LinearW w, const uint32_t *
         if (lane >= off) incl += v;
     }
     const int total = __shfl(incl, 63);
-    if (blockIdx.x == 0 && lane == 0) { count[0] = total; count[1] = 4; }   // [1]: digit planes, raised by k_limb_x
+    if (blockIdx.x == 0 && lane == 0) { count[0] = total; count[1] = 4; }   // [1]: digit planes, raised by k_digit_tiles
+    if (total > PS_EXACT_OUTLIERS && blockIdx.x == 0 && full_list) {
+        // more columns than the fp64 path takes: workgroup 0 leaves their ascending list for the digit products,
+        // padded with -1 up to the next multiple of 64
+        int at = incl - cnt;
+        for (int i = w0; i < w1; i++) {
+            uint32_t b = mask[i];
+            while (b) {
+                const int j = __ffs(b) - 1;
+                b &= b - 1;
+                full_list[at++] = i * 32 + j;
+            }
+        }
+        const int padded = (total + 63) & ~63;
+        for (int i = total + lane; i < padded; i += 64) full_list[i] = -1;
+    }
     if (total == 0 || total > PS_EXACT_OUTLIERS) return;
     int pos = incl - cnt;
     for (int i = w0; i < w1; i++) {
@@ -264,8 +280,8 @@ hipError_t launch(const LinearW &w, const int8_t *xq_tiled, const int8_t *xo_til
 }  // namespace
 
 hipError_t ps_outlier_prep(const LinearW &w, const uint32_t *mask, const __half *X, int M, int *count, double *wd64,
-                           double *x64, hipStream_t st) {
-    k_outlier_prep<<<w.N / 16 + (M + 15) / 16, 64, 0, st>>>(w, mask, X, M, count, wd64, x64);
+                           double *x64, int *full_list, hipStream_t st) {
+    k_outlier_prep<<<w.N / 16 + (M + 15) / 16, 64, 0, st>>>(w, mask, X, M, count, wd64, x64, full_list);
     return hipGetLastError();
 }
 

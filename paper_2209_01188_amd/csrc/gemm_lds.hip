@@ -35,39 +35,6 @@ constexpr int STRIP = 4;       // m-blocks per rasterization strip
 // ---------------------------------------------------------------------------------------------
 // outlier column list and fp16 gathers (only do work when the call has > PS_EXACT_OUTLIERS)
 
-// One workgroup: ascending list of the set bits of mask[0 .. K/32); entries up to the next multiple
-// of 64 are -1.  count must already hold the number of set bits.
-__global__ void __launch_bounds__(1024) k_outlier_list(const uint32_t *__restrict__ mask, int K,
-                                                       const int *__restrict__ count, int *__restrict__ list) {
-    __shared__ int wave_tot[16];
-    const int n_out = *count;
-    if (n_out <= PS_EXACT_OUTLIERS) return;
-    const int nwords = K >> 5, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wpt = (nwords + 1023) / 1024, w0 = min(nwords, (int)threadIdx.x * wpt), w1 = min(nwords, w0 + wpt);
-    int cnt = 0;
-    for (int i = w0; i < w1; i++) cnt += __popc(mask[i]);
-    int incl = cnt;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const int v = __shfl_up(incl, off);
-        if (lane >= off) incl += v;
-    }
-    if (lane == 63) wave_tot[wave] = incl;
-    __syncthreads();
-    int pos = incl - cnt;
-    for (int i = 0; i < wave; i++) pos += wave_tot[i];
-    for (int i = w0; i < w1; i++) {
-        uint32_t b = mask[i];
-        while (b) {
-            const int j = __ffs(b) - 1;
-            b &= b - 1;
-            list[pos++] = i * 32 + j;
-        }
-    }
-    const int padded = (n_out + 63) & ~63;
-    for (int i = n_out + threadIdx.x; i < padded; i += 1024) list[i] = -1;
-}
-
 // Scale of the digit form of output row n's dequantized weights: a = sw / 127 (fp32, as everywhere),
 // E = its binary exponent (not below fp16's smallest normal one), so that every fp16(code * a) is a
 // multiple of u = 2^(E - 10); m = a / u rounded to an integer (0 is possible for a row whose scale is
@@ -90,18 +57,17 @@ __device__ __forceinline__ bool digit_scale(float sw, float &a, int &E, int &m) 
 // PS_X_DIGITS digit planes are written; count[1] receives the number of planes that hold anything (at
 // least 4), which is what the product walks.
 template <int U>
-__global__ void __launch_bounds__(64) k_limb_x(const __half *__restrict__ X, int M, int K, int *__restrict__ count,
-                                                 const int *__restrict__ list, int8_t *__restrict__ xl) {
-    const int n_out = count[0];
-    if (n_out <= PS_EXACT_OUTLIERS) return;
+__device__ __forceinline__ void limb_x_tiles(const __half *__restrict__ X, int M, int K, int *__restrict__ count,
+                                             const int *__restrict__ list, int8_t *__restrict__ xl, int n_out,
+                                             int bid, int nblk) {
     const int CT = (n_out + 63) >> 6, MTT = (M + 15) >> 4, lane = threadIdx.x, total = MTT * CT;
     int need = 0;
-    for (int item0 = blockIdx.x; item0 < total; item0 += gridDim.x * U) {
+    for (int item0 = bid; item0 < total; item0 += nblk * U) {
         int4 idx4[U][4];
         int tt[U];
 #pragma unroll
         for (int u = 0; u < U; u++) {
-            const int item = min(item0 + u * (int)gridDim.x, total - 1);
+            const int item = min(item0 + u * nblk, total - 1);
             const int mt = item / CT, ct = item - mt * CT;
             tt[u] = mt * 16 + (lane & 15);
             const int4 *lp = (const int4 *)(list + ct * 64 + (lane >> 4) * 16);
@@ -121,7 +87,7 @@ __global__ void __launch_bounds__(64) k_limb_x(const __half *__restrict__ X, int
         }
 #pragma unroll
         for (int u = 0; u < U; u++) {
-            const int item = item0 + u * (int)gridDim.x;
+            const int item = item0 + u * nblk;
             if (item >= total) continue;                                   // wave-uniform
             const int mt = item / CT, ct = item - mt * CT;
             int dig[PS_X_DIGITS][4];
@@ -160,20 +126,18 @@ __global__ void __launch_bounds__(64) k_limb_x(const __half *__restrict__ X, int
 // Weights: digit 0 (the int8 codes) of panel nt, column tile ct at ((nt) * CT + ct) * 1024, digit 1 (the
 // remainders) at ((NT + nt) * CT + ct) * 1024.
 template <int U>
-__global__ void __launch_bounds__(64) k_digit_w(LinearW w, const int *__restrict__ count,
-                                                  const int *__restrict__ list, int8_t *__restrict__ wd) {
-    const int n_out = count[0];
-    if (n_out <= PS_EXACT_OUTLIERS) return;
+__device__ __forceinline__ void digit_w_tiles(const LinearW &w, const int *__restrict__ list, int8_t *__restrict__ wd,
+                                              int n_out, int bid, int nblk) {
     const int CT = (n_out + 63) >> 6, NT = w.N >> 4, KT = w.K >> 6, lane = threadIdx.x, row = lane & 15;
     const int total = NT * CT;
     const int8_t *__restrict__ wt = w.wt;
-    for (int item0 = blockIdx.x; item0 < total; item0 += gridDim.x * U) {
+    for (int item0 = bid; item0 < total; item0 += nblk * U) {
         int4 idx4[U][4];
         int nts[U];
         float swr[U];
 #pragma unroll
         for (int u = 0; u < U; u++) {
-            const int item = min(item0 + u * (int)gridDim.x, total - 1);
+            const int item = min(item0 + u * nblk, total - 1);
             const int nt = item / CT, ct = item - nt * CT;
             nts[u] = nt;
             const int4 *lp = (const int4 *)(list + ct * 64 + (lane >> 4) * 16);
@@ -197,7 +161,7 @@ __global__ void __launch_bounds__(64) k_digit_w(LinearW w, const int *__restrict
         }
 #pragma unroll
         for (int u = 0; u < U; u++) {
-            const int item = item0 + u * (int)gridDim.x;
+            const int item = item0 + u * nblk;
             if (item >= total) continue;                                   // wave-uniform
             const int ct = item - nts[u] * CT;
             float a;
@@ -248,6 +212,19 @@ struct GemmArgs {
     double *od;               // [M, N] fp64: the product over the outlier columns
     float *f32_out;           // plain fp16 product: [M, N] fp32 result
 };
+
+// Both kinds of digit tiles in one launch (a launch costs as much as the work of a call with few tiles): the first
+// NBX workgroups cut the activations, the rest the weights.  Does nothing unless the call has more outlier columns
+// than the fp64 path takes.
+template <int U>
+__global__ void __launch_bounds__(64) k_digit_tiles(const __half *__restrict__ X, int M, LinearW w, int *__restrict__ count,
+                                                      const int *__restrict__ list, int8_t *__restrict__ xl,
+                                                      int8_t *__restrict__ wd, int NBX) {
+    const int n_out = count[0];
+    if (n_out <= PS_EXACT_OUTLIERS) return;
+    if ((int)blockIdx.x < NBX) limb_x_tiles<U>(X, M, w.K, count, list, xl, n_out, (int)blockIdx.x, NBX);
+    else digit_w_tiles<U>(w, list, wd, n_out, (int)blockIdx.x - NBX, (int)gridDim.x - NBX);
+}
 
 enum { GEMM_INT8 = 0, GEMM_F16 = 1, GEMM_DIGITS = 2 };
 
@@ -787,9 +764,7 @@ hipError_t ps_gemm_lds(const LinearW &w, const int8_t *xq_tiled, const uint32_t 
     // The outlier-heavy case first (every kernel of it returns at once when the call has few outlier columns):
     // column list, digit tiles of the activations and of the dequantized weights, the digit products (a second
     // launch for digit planes 4 and 5, which only activations of magnitude 127.5 and more have).
-    k_outlier_list<<<1, 1024, 0, st>>>(mask, w.K, os.count, mo.list);
-    k_limb_x<2><<<2048, 64, 0, st>>>(X, M, w.K, (int *)os.count, mo.list, mo.xl);
-    k_digit_w<2><<<4096, 64, 0, st>>>(w, os.count, mo.list, mo.wd);
+    k_digit_tiles<2><<<2048 + 4096, 64, 0, st>>>(X, M, w, (int *)os.count, mo.list, mo.xl, mo.wd, 2048);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     for (int pg = 0; pg < 2; pg++) {
