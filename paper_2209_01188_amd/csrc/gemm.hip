@@ -287,8 +287,10 @@ hipError_t ps_outlier_prep(const LinearW &w, const uint32_t *mask, const __half 
 
 // Rough times in microseconds, fitted to measurements on BLOOM-560M-, 7B1- and 176B-shaped linears at 96 to 512
 // rows.  64-row passes: each streams the N*K weight bytes at about 3 TB/s (what the 64-row form reaches), 5 us per
-// launch, 20 us for the row kernels in front.  Output blocks: a 256 x 256 block walks K/64 stages of about 0.7 us,
-// 256 blocks at a time, behind about 45 us of row, outlier and digit kernels that are launched whatever the data.
+// launch, 20 us for the row kernels in front.  Output blocks: a 256 x 256 block walks K/64 stages of about 0.7 us
+// (0.45 us for the 256 x 128 blocks that ps_gemm_lds takes when the call has at most 128 rows or at most 128
+// blocks), 256 blocks at a time, never faster than the weights stream at 4 TB/s, behind about 45 us of row, outlier
+// and digit kernels that are launched whatever the data.
 // PETALS_SPAN_MIDSIZE=blocks / =chunks in the environment overrides the choice (tests run both ways).
 bool ps_gemm_prefers_chunks(const LinearW &w, int M) {
     if (M <= 64 || M > PS_CHUNKED_ROWS_MAX) return false;
@@ -298,8 +300,12 @@ bool ps_gemm_prefers_chunks(const LinearW &w, int M) {
     }
     const double passes = (M + 63) / 64, bytes = (double)w.N * w.K;
     const double t_chunks = 20.0 + passes * (bytes / 3.0e6 + 5.0);
-    const double blocks = (double)((w.N + 255) / 256) * ((M + 255) / 256);
-    const double t_blocks = 45.0 + ceil(blocks / 256.0) * (w.K / 64) * 0.7;
+    double blocks = (double)((w.N + 255) / 256) * ((M + 255) / 256), stage = 0.7;
+    if (M <= 128 || blocks * 2 <= 256) {
+        blocks = (double)((w.N + 255) / 256) * ((M + 127) / 128);
+        stage = 0.45;
+    }
+    const double t_blocks = 45.0 + fmax(ceil(blocks / 256.0) * (w.K / 64) * stage, bytes / 4.0e6);
     return t_chunks < t_blocks;
 }
 

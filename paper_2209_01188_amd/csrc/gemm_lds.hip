@@ -715,6 +715,12 @@ hipError_t launch_lds(const GemmArgs &ga0, const LinearW &w, const float *sx, co
     ga.nb_m = (MTT + BM - 1) / BM;
     ga.nb_n0 = 0;
     const int total = ga.nb_n * ga.nb_m, rest = total % UNITS;
+    if (MTT <= BM / 2 || total * 2 <= UNITS) {
+        // at most 128 rows, or so few blocks that half the compute units would idle: blocks of half the height
+        // (no block is half empty, and there are twice as many of them)
+        ga.nb_m = (MTT + BM / 2 - 1) / (BM / 2);
+        return launch_epi<MODE, 2>(ga, w, sx, os, outl, o, sess, st);
+    }
     if (total > UNITS && rest > 0 && rest <= UNITS / 2 && rest % ga.nb_m == 0) {
         GemmArgs gb = ga;
         gb.nb_n = rest / ga.nb_m;
