@@ -244,6 +244,16 @@ __global__ void __launch_bounds__(256) k_colmask(const __half *__restrict__ X, i
     }
 }
 
+// Row of a workgroup of the row quantizers.  Consecutive workgroup ids land on different XCDs (8, each with its
+// own L2), and the 16 rows of a token tile interleave their 16-byte pieces in every 128-byte line of the tile: each
+// XCD gets a contiguous run of whole tiles, so that a line is completed in ONE L2 instead of being written back
+// in pieces by eight.  The grid has 8 * per workgroups, per a multiple of 16; ids beyond `rows` have nothing to do.
+__device__ __forceinline__ int rowquant_row() {
+    const int per = (int)gridDim.x >> 3;
+    return ((int)blockIdx.x & 7) * per + ((int)blockIdx.x >> 3);
+}
+__host__ inline int rowquant_grid(int rows) { return 8 * (((rows / 16 + 7) / 8) * 16); }
+
 // One workgroup per row of the 16-padded row range.  Row scale = absolute maximum over
 // non-outlier columns; codes go to the MFMA operand tile order (same tiling as the
 // weights, rows = tokens); padding rows are written as zeros.
@@ -251,9 +261,10 @@ __global__ void __launch_bounds__(256) k_rowquant_tiled(const __half *__restrict
                                                         const uint32_t *__restrict__ mask,
                                                         int8_t *__restrict__ xq_tiled,
                                                         int8_t *__restrict__ xo_tiled, float *__restrict__ sx,
-                                                        int8_t *__restrict__ xq_dbg) {
+                                                        int8_t *__restrict__ xq_dbg, int rows) {
     __shared__ float sm[4];
-    const int t = blockIdx.x, KT = K >> 6, nchunk = K >> 4;
+    const int t = rowquant_row(), KT = K >> 6, nchunk = K >> 4;
+    if (t >= rows) return;
     const uint16_t *mask16 = (const uint16_t *)mask;
     const size_t tile_row = (size_t)(t >> 4) * KT;
     if (t >= M) {
@@ -321,9 +332,10 @@ __global__ void __launch_bounds__(NT) k_rowquant_tiled_wide(const __half *__rest
                                                              const uint32_t *__restrict__ mask,
                                                              int8_t *__restrict__ xq_tiled,
                                                              int8_t *__restrict__ xo_tiled, float *__restrict__ sx,
-                                                             int8_t *__restrict__ xq_dbg) {
+                                                             int8_t *__restrict__ xq_dbg, int rows) {
     __shared__ float sm[NT / 64];
-    const int t = blockIdx.x, KT = K >> 6, nchunk = K >> 4;
+    const int t = rowquant_row(), KT = K >> 6, nchunk = K >> 4;
+    if (t >= rows) return;
     const uint16_t *mask16 = (const uint16_t *)mask;
     const size_t tile_row = (size_t)(t >> 4) * KT;
     if (t >= M) {
@@ -506,13 +518,13 @@ hipError_t ps_colmask(const __half *X, int M, int K, float theta, uint32_t *mask
 }
 hipError_t ps_rowquant_tiled(const __half *X, int M, int K, const uint32_t *mask, int8_t *xq_tiled, int8_t *xo_tiled,
                              float *sx, int8_t *xq_dbg, hipStream_t st) {
-    const int rows = (M + 15) / 16 * 16;
+    const int rows = (M + 15) / 16 * 16, grid = rowquant_grid(rows);
     if (K >= 4096 && K <= 16384 && M >= 512)   // many rows: four times as many rows in flight per compute unit
-        k_rowquant_tiled_wide<256, 4><<<rows, 256, 0, st>>>(X, M, K, mask, xq_tiled, xo_tiled, sx, xq_dbg);
+        k_rowquant_tiled_wide<256, 4><<<grid, 256, 0, st>>>(X, M, K, mask, xq_tiled, xo_tiled, sx, xq_dbg, rows);
     else if (K >= 4096 && K <= 65536)          // wide rows: 1024 threads keep the row in registers, one pass over X
-        k_rowquant_tiled_wide<1024, 4><<<rows, 1024, 0, st>>>(X, M, K, mask, xq_tiled, xo_tiled, sx, xq_dbg);
+        k_rowquant_tiled_wide<1024, 4><<<grid, 1024, 0, st>>>(X, M, K, mask, xq_tiled, xo_tiled, sx, xq_dbg, rows);
     else
-        k_rowquant_tiled<<<rows, 256, 0, st>>>(X, M, K, mask, xq_tiled, xo_tiled, sx, xq_dbg);
+        k_rowquant_tiled<<<grid, 256, 0, st>>>(X, M, K, mask, xq_tiled, xo_tiled, sx, xq_dbg, rows);
     return hipGetLastError();
 }
 hipError_t ps_mask_count(const uint32_t *masks, int n_masks, int words, int32_t *out, hipStream_t st) {
