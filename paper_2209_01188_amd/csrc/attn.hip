@@ -40,10 +40,17 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(const __half *__restric
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, c = lane & 15, g = lane >> 4;
     // One-dimensional grid.  Consecutive workgroup ids land on different XCDs (8, each with its own L2): the id
     // is decoded so that all query blocks of one (session, head) run on the same XCD and share its keys/values.
-    const int nbx = (T + 63) / 64, grp = blockIdx.x / (8 * nbx), rem = blockIdx.x - grp * 8 * nbx;
+    // A workgroup takes TWO query blocks of its (session, head), number i and number nbx - 1 - i, one after the
+    // other: with the causal limit a block walks 4 i + 4 key tiles (plus the cached ones), so every workgroup of
+    // the launch does the same amount of work and none is left running alone at the end.
+    const int nbx = (T + 63) / 64, nbh = (nbx + 1) / 2, grp = blockIdx.x / (8 * nbh), rem = blockIdx.x - grp * 8 * nbh;
     const int pair = grp * 8 + (rem & 7);
     if (pair >= B * nh) return;                       // the whole workgroup
-    const int qb = rem >> 3, s = pair / nh, h = pair - s * nh;
+    const int qb0 = rem >> 3, s = pair / nh, h = pair - s * nh;
+    for (int pass = 0; pass < 2; pass++) {
+    const int qb = pass ? nbx - 1 - qb0 : qb0;
+    if (pass && qb == qb0) break;                     // odd count: the middle block stands alone
+    if (pass) __syncthreads();                        // the tile buffers are reused
     const int qt = qb * 4 + wave;
     const int L = sess->len[s], cap = sess->cap[s], H = nh * D;
     const __half *Kc = sess->kv[s] + ((size_t)blk * 2 * nh + h) * cap * D;
@@ -167,6 +174,7 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(const __half *__restric
             }
         }
     }
+    }   // pass
 }
 
 // softmax state of a set of keys: running maximum m, sum l of exp(z - m), weighted value sum o
@@ -331,7 +339,7 @@ hipError_t attn_launch(const __half *q, const SessTable *sess, int blk, int M, i
     if (nsplit == 1) CH = 1 << 30;
     if (T > 1 || lse) {   // the matrix-core kernel also covers T = 1; it is the one that can report the denominators
         const int B = M / T;
-        k_attn_prefill<D><<<(B * nh + 7) / 8 * 8 * ((T + 63) / 64), 256, (size_t)2 * 2 * 16 * D * 8, st>>>(q, sess, blk, B, T, nh, ctx, mask, theta, lse, ctx32);
+        k_attn_prefill<D><<<(B * nh + 7) / 8 * 8 * (((T + 63) / 64 + 1) / 2), 256, (size_t)2 * 2 * 16 * D * 8, st>>>(q, sess, blk, B, T, nh, ctx, mask, theta, lse, ctx32);
         return hipGetLastError();
     }
     if (nsplit == 2) {   // twice the waves per workgroup instead of two key ranges: nothing to merge afterwards
