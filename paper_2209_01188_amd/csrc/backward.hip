@@ -211,10 +211,18 @@ __global__ void __launch_bounds__(256) k_attn_bwd(const __half *__restrict__ q, 
     __shared__ __align__(16) __half y1[32 * PN], y2[32 * PN], y1t[D * PT], y2t[KV ? D * PT : 8];
     __shared__ __align__(16) float st_l[32], st_d[32];          // KV: lse * log2(e) and Dv of the tile's query rows
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, c = lane & 15, g = lane >> 4;
-    const int nbx = (T + 63) / 64, grp = blockIdx.x / (8 * nbx), rem = blockIdx.x - grp * 8 * nbx;
+    // A workgroup owns TWO blocks of 64 rows of its (sequence, head), number i and number nbx - 1 - i, one after the
+    // other: what a block walks grows (queries) or shrinks (keys) linearly with its number, so all workgroups of
+    // the launch do equal work.
+    const int nbx = (T + 63) / 64, nbh = (nbx + 1) / 2, grp = blockIdx.x / (8 * nbh), rem = blockIdx.x - grp * 8 * nbh;
     const int pair = grp * 8 + (rem & 7);                       // (sequence, head) index; same XCD for all its blocks
     if (pair >= B * nh) return;                                 // the whole workgroup
-    const int own0 = (rem >> 3) * 64, s = pair / nh, h = pair - s * nh, M = B * T, H = nh * D;
+    const int blk0 = rem >> 3;
+    for (int pass = 0; pass < 2; pass++) {
+    const int blk_own = pass ? nbx - 1 - blk0 : blk0;
+    if (pass && blk_own == blk0) break;                         // odd count: the middle block stands alone
+    if (pass) __syncthreads();                                  // the staging buffers are reused
+    const int own0 = blk_own * 64, s = pair / nh, h = pair - s * nh, M = B * T, H = nh * D;
     const int cap = sess->cap[s];
     const __half *Qn = q + (size_t)s * T * H + h * D, *dOn = dO + (size_t)s * T * H + h * D;
     const __half *Kn = sess->kv[s] + ((size_t)blk * 2 * nh + h) * cap * D, *Vn = Kn + (size_t)nh * cap * D;
@@ -381,6 +389,7 @@ __global__ void __launch_bounds__(256) k_attn_bwd(const __half *__restrict__ q, 
             }
         }
     }
+    }   // pass
 }
 
 template <int D>
@@ -391,7 +400,7 @@ hipError_t attn_bwd_launch(const __half *q, const SessTable *sess, int blk, int 
     k_head_transpose<D><<<gt, 256, 0, st>>>(q, sess, 0, blk, T, Tp, nh, QT);
     k_head_transpose<D><<<gt, 256, 0, st>>>(nullptr, sess, 1, blk, T, Tp, nh, KT);
     k_head_transpose<D><<<gt, 256, 0, st>>>(dO, sess, 0, blk, T, Tp, nh, dOT);
-    const int grid = (B * nh + 7) / 8 * 8 * ((T + 63) / 64);
+    const int grid = (B * nh + 7) / 8 * 8 * (((T + 63) / 64 + 1) / 2);
     k_attn_bwd<D, false><<<grid, 256, 0, st>>>(q, sess, blk, B, T, Tp, nh, dO, QT, KT, dOT, lse, Dv, dqkv);
     k_attn_bwd<D, true><<<grid, 256, 0, st>>>(q, sess, blk, B, T, Tp, nh, dO, QT, KT, dOT, lse, Dv, dqkv);
     return hipGetLastError();
