@@ -381,12 +381,43 @@ def mfma_peak_main(args, dev):
                                                        "ms": round(best, 3),
                                                        "implied_clock_ghz": round(tops * 1e12 / (256 * 4 * 2048) / 1e9, 3)}
             print("[bench] %s, %s operands: %.0f TOP/s" % (kname, rname, tops), file=sys.stderr, flush=True)
+    # One compute unit's share of the prefill linear's main loop (a 256 x 256 block's k-tile stage: 32 KiB of
+    # asynchronous copies into LDS, 12 fragment reads and 32 matrix instructions per wave, 8 waves), piece by
+    # piece and together, on random and on constant operand bytes: nanoseconds per stage, and the int8 rate the
+    # stage's 2 * 256 * 256 * 64 operations would then have on 256 compute units.
+    stages, regions, rounds = 224, 4, 4
+    stage = {}
+    for rname in ("random", "constant"):
+        if rname == "random":
+            src = torch.randint(0, 256, (regions * stages * 32 * 1024,), dtype=torch.uint8, device=dev)
+        else:
+            src = torch.full((regions * stages * 32 * 1024,), 1, dtype=torch.uint8, device=dev)
+        sout = torch.empty(256 * rounds * 512, dtype=torch.int32, device=dev)
+        for parts, pname in ((4, "products"), (6, "products + fragment reads"), (5, "products + copies"),
+                             (7, "products + fragment reads + copies"), (1, "copies"), (2, "fragment reads")):
+            binding.petals_bench_stage(parts, stages, regions, 256 * rounds, src, sout)
+            torch.cuda.synchronize()
+            best = None
+            for _ in range(max(1, min(args.steps, 8))):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                binding.petals_bench_stage(parts, stages, regions, 256 * rounds, src, sout)
+                e1.record(stream)
+                torch.cuda.synchronize()
+                ms = e0.elapsed_time(e1)
+                best = ms if best is None else min(best, ms)
+            ns = best * 1e6 / (stages * rounds)
+            ent = {"ns_per_stage": round(ns, 1)}
+            if parts & 4:
+                ent["top_s"] = round(256 * 2.0 * 256 * 256 * 64 / (ns * 1e-9) / 1e12, 1)
+            stage["%s, %s operands" % (pname, rname)] = ent
+            print("[bench] stage loop, %s, %s operands: %.0f ns per stage" % (pname, rname, ns), file=sys.stderr, flush=True)
     key = "v_mfma_i32_16x16x64_i8, random operands"
     line = {"metric": "sustained int8 MFMA TOP/s, register-only loop", "value": res[key]["top_s"], "unit": "TOP/s",
             "n_gpus": 1, "steps": max(1, min(args.steps, 8)), "warmup": max(1, args.warmup), "ms_per_step": res[key]["ms"],
             "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
             "config": {"workload": "register-only loop of the int8 matrix instruction, 512 workgroups x 4 waves x %d "
-                                   "iterations, no memory traffic" % iters, "variants": res},
+                                   "iterations, no memory traffic" % iters, "variants": res, "stage_loop": stage},
             "roofline": {"bound": "mfma", "achieved": res[key]["top_s"], "peak": 5000.0, "unit": "TOP/s",
                          "frac": res[key]["frac_of_5000"], "traffic": None, "kernel": "k_mfma_loop"},
             "cpu_baseline": None}

@@ -323,6 +323,19 @@ int petals_debug_backward_product(petals_span *span, void *dev_store, int32_t B,
 int petals_bench_mfma(int32_t kind, int32_t random_operands, int32_t iters, int32_t workgroups,
                       int32_t *dev_out, double *ops_out, void *stream);
 
+/*
+ * Measurement aid, not part of the method: one compute unit's share of the main loop of the prefill linear
+ * (Section 3.1, 8-bit weights on the matrix cores) with its three pieces switchable.  Per k-tile stage a
+ * workgroup of 8 waves issues 32 asynchronous 1 KiB copies into a 4-slot LDS ring (parts bit 0), 12 fragment
+ * reads per wave (bit 1) and 32 v_mfma_i32_16x16x64_i8 per wave (bit 2), with one barrier.  dev_src: dev bytes,
+ * `regions` regions of stages * 32 KiB (workgroup b walks region (b / 8) % regions); src_bytes its size;
+ * dev_out: dev int32 [workgroups * 512] (checksums).  stages >= 4.  Enqueues one kernel; the caller times it
+ * and divides by stages * ceil(workgroups / compute units).  Errors: PETALS_ERR_INVALID_ARG,
+ * PETALS_ERR_CAPACITY (dev_src too small).
+ */
+int petals_bench_stage(int32_t parts, int32_t stages, int32_t regions, int32_t workgroups, const void *dev_src,
+                       size_t src_bytes, int32_t *dev_out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -59,7 +59,7 @@ EXPORTS = ["petals_span_weight_bytes", "petals_span_workspace_bytes", "petals_sp
            "petals_debug_export_weight", "petals_debug_export_kv", "petals_debug_import_kv",
            "petals_span_profile_begin", "petals_span_profile_end", "petals_debug_layernorm", "petals_session_replay",
            "petals_span_backward_bytes", "petals_span_backward", "petals_debug_backward_product",
-           "petals_span_backward_cache_bytes", "petals_span_backward_attach_cache", "petals_bench_mfma", "petals_debug_outlier_counts"]
+           "petals_span_backward_cache_bytes", "petals_span_backward_attach_cache", "petals_bench_mfma", "petals_bench_stage", "petals_debug_outlier_counts"]
 CLIENT_EXPORTS = ["petals_client_workspace_bytes", "petals_client_create", "petals_client_destroy",
                   "petals_client_embed", "petals_client_lm_head", "petals_client_sample"]
 PROFILE_GEMV, PROFILE_GEMM, PROFILE_ATTENTION, PROFILE_LINEAR0 = 0, 1, 2, 3
@@ -246,6 +246,13 @@ def petals_bench_mfma(kind, random_operands, iters, workgroups, out):
     _check(lib().petals_bench_mfma(C.c_int32(kind), C.c_int32(1 if random_operands else 0), C.c_int32(iters),
                                    C.c_int32(workgroups), _ptr(out), C.byref(ops), _stream()))
     return ops.value
+
+
+def petals_bench_stage(parts, stages, regions, workgroups, src, out):
+    """Enqueues the stage-shaped loop of the prefill linear with the pieces `parts` selects (1 copies, 2 reads, 4 products)."""
+    assert src.is_cuda and src.is_contiguous() and out.is_cuda and out.dtype == torch.int32
+    _check(lib().petals_bench_stage(C.c_int32(parts), C.c_int32(stages), C.c_int32(regions), C.c_int32(workgroups),
+                                    _ptr(src), C.c_size_t(src.numel() * src.element_size()), _ptr(out), _stream()))
 
 
 def petals_debug_outlier_counts(span, counts):

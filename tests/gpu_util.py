@@ -10,6 +10,18 @@ from paper_2209_01188_amd import binding, synth
 
 DEV = "cuda:0"
 
+_capture_manager = None          # set by conftest.py
+
+
+def say(msg):
+    """A progress line of a long test, written to the terminal even while pytest captures output: the long tests
+    spend up to a minute in one oracle call, and a run that prints nothing for minutes looks hung from outside."""
+    if _capture_manager is not None:
+        with _capture_manager.global_and_fixture_disabled():
+            print("\n[%s]" % msg, flush=True)
+    else:
+        print(msg, flush=True)
+
 
 @contextlib.contextmanager
 def midsize(mode):

@@ -7,7 +7,7 @@ import torch
 import oracle
 from oracle import backward as ob
 from paper_2209_01188_amd import binding, synth
-from tests.gpu_util import DEV, hidden_close, to_dev, to_np
+from tests.gpu_util import DEV, hidden_close, say, to_dev, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -57,7 +57,7 @@ def _check(cfg, nb, B, T, wscale, seed=0, min_branch=0.05):
         X = synth.hidden_states(cfg, 0, B, T)
         dY = _grad(cfg, B, T, seed)
         Y_ref, dX_ref = ob.span_backward(osp, params, X, dY)
-        print("backward case %s nb=%d B=%d T=%d" % (cfg.name, nb, B, T), flush=True)
+        (say if cfg.hidden >= 8192 else print)("backward case %s nb=%d B=%d T=%d" % (cfg.name, nb, B, T))
         Y, dX = gsp.backward(to_dev(X), to_dev(dY))
         torch.cuda.synchronize()
         Y, dX = to_np(Y), to_np(dX)
@@ -224,7 +224,7 @@ def test_backward_products_at_full_size_sampled_against_the_oracle():
             gen.manual_seed(100 + which)
             dY = torch.empty((M, N), dtype=torch.float32, device=DEV).normal_(0.0, 1.0, generator=gen).to(torch.float16)
             dX = torch.empty((M, K), dtype=torch.float32, device=DEV)
-            print("backward product of linear %d: [%d, %d] x [%d, %d]" % (which, M, N, N, K), flush=True)
+            say("backward product of linear %d: [%d, %d] x [%d, %d]" % (which, M, N, N, K))
             binding.petals_debug_backward_product(gsp.handle, store, B, T, 0, which, dY, dX)
             torch.cuda.synchronize()
             rows = np.unique(np.concatenate([[0, 15, 16, 255, 256, M - 1], r.choice(M, 18, replace=False)]))
@@ -256,7 +256,7 @@ def test_backward_full_size_call_is_deterministic_linear_and_keeps_the_prefill_o
         # the recipe's weights multiply the gradient by about 15 per block: keep it inside the fp16 range
         g = (torch.empty(X.shape, dtype=torch.float32, device=DEV).normal_(0.0, 1.0, generator=gen) * 0.05).to(torch.float16)
         store = torch.empty(binding.petals_span_backward_bytes(gsp.cfg, B, T), dtype=torch.uint8, device=DEV)
-        print("full-size backward calls", flush=True)
+        say("full-size backward calls")
         Y, d1 = gsp.backward(X, g, store=store)
         d1 = d1.clone()
         _, d1b = gsp.backward(X, g, store=store)

@@ -5,7 +5,7 @@ import torch
 
 import oracle
 from paper_2209_01188_amd import binding, synth
-from tests.gpu_util import DEV, build_pair, hidden_close, midsize, to_dev, to_np
+from tests.gpu_util import DEV, build_pair, hidden_close, midsize, say, to_dev, to_np
 
 pytestmark = pytest.mark.gpu
 INF = float("inf")
@@ -578,7 +578,7 @@ def test_c4_full_size_linears_at_the_benchmark_row_count_sampled_against_the_ora
             X[:, r.choice(K, 6, replace=False)] = r.uniform(20, 60, (M, 6))
             X = X.astype(np.float16)
             Y, dbg = oracle.linear(X, wq, sw, bsub, 6.0, want_debug=True)
-            print("C4 linear %d at %d rows" % (which, M), flush=True)
+            say("C4 linear %d at %d rows" % (which, M))
             out = gsp.debug_linear(0, which, to_dev(X))
             torch.cuda.synchronize()
             assert np.array_equal(to_np(out["mask"]), dbg["mask"])
@@ -610,7 +610,7 @@ def test_c4_full_size_prefill_attention_sampled_heads_against_the_oracle():
     try:
         X = synth.hidden_states(cfg, 0, B, T)
         sessions = [gsp.open_session(T) for _ in range(B)]
-        print("C4 prefill attention, %d x %d tokens" % (B, T), flush=True)
+        say("C4 prefill attention, %d x %d tokens" % (B, T))
         Y = to_np(gsp.prefill(sessions, to_dev(X)))
         g1, b1 = p["ln1_g"].cpu().numpy(), p["ln1_b"].cpu().numpy()
         slopes = oracle.alibi_slopes(nh)
@@ -663,7 +663,7 @@ def test_c4_full_size_down_linear_at_1024_rows_sampled_against_the_oracle(n_outl
         resid = r.standard_normal((M, N)).astype(np.float16)
         Y, dbg = oracle.linear(X, wq, sw, bsub, 6.0, 2, resid[:, rows], want_debug=True)
         assert dbg["mask"].sum() == n_outlier_cols
-        print("C4 down linear at %d rows, %d outlier columns" % (M, n_outlier_cols), flush=True)
+        say("C4 down linear at %d rows, %d outlier columns" % (M, n_outlier_cols))
         out = gsp.debug_linear(0, 3, to_dev(X), 2, to_dev(resid))
         torch.cuda.synchronize()
         assert np.array_equal(to_np(out["mask"]), dbg["mask"])
@@ -792,15 +792,15 @@ def test_c4_width_two_blocks_prefill_of_128_tokens_end_to_end():
         X = synth.hidden_states(cfg, 0, B, T)
         oses = [osp.open_session(T + 1) for _ in range(B)]
         gses = [gsp.open_session(T + 1) for _ in range(B)]
-        print("C4 width, 2 blocks, %d x %d tokens: oracle ..." % (B, T), flush=True)
+        say("C4 width, 2 blocks, %d x %d tokens: oracle ..." % (B, T))
         Yo = osp.step(oses, X)
-        print("... GPU", flush=True)
+        say("... GPU")
         with midsize("blocks"):       # on its own the library would run dense and down 64 rows at a time at this size
             Yg = to_np(gsp.prefill(gses, to_dev(X)))
             torch.cuda.synchronize()
         hidden_close(Yg, Yo, "C4 width 2 blocks prefill")
         same = (Yg.view(np.uint16) == Yo.view(np.uint16)).mean()
-        print("bit-identical outputs: %.6f" % same, flush=True)
+        say("bit-identical outputs: %.6f" % same)
         assert same > 0.9999, same
         for b in range(2):
             hidden_close(to_np(gses[1].export_kv(b)), oses[1].export_kv(b), "kv of block %d" % b)
@@ -837,9 +837,9 @@ def test_c3_two_blocks_eight_sessions_of_512_tokens_with_the_codec_then_four_dec
         Xo, q_in, _ = through_codec_cpu(X)
         xg, q_in_g, _ = through_codec_gpu(to_dev(X))
         assert np.array_equal(to_np(q_in_g), q_in.reshape(-1))
-        print("C3, 2 blocks, %d x %d tokens: oracle ..." % (B, T), flush=True)
+        say("C3, 2 blocks, %d x %d tokens: oracle ..." % (B, T))
         Yo = osp.step(oses, Xo)
-        print("... GPU", flush=True)
+        say("... GPU")
         Yg = gsp.prefill(gses, xg)
         hidden_close(to_np(Yg), Yo, "C3 prefill 8 x 512")
         _, qo_g, amo_g = through_codec_gpu(Yg)
@@ -927,7 +927,7 @@ def test_c4_full_size_dense_and_down_linears_at_4096_rows_with_thousands_of_outl
             Y, dbg = oracle.linear(X, wq, sw, bsub, 6.0, 2, resid[:, rows], want_debug=True)
             n_out = int(dbg["mask"].sum())
             assert n_out > 2000
-            print("C4 linear %d at %d rows, %d outlier columns" % (which, M, n_out), flush=True)
+            say("C4 linear %d at %d rows, %d outlier columns" % (which, M, n_out))
             out = gsp.debug_linear(0, which, to_dev(X), 2, to_dev(resid))
             torch.cuda.synchronize()
             assert int(gsp.outlier_counts()[0, 0]) == n_out
@@ -960,14 +960,16 @@ def test_c5_shape_two_chained_spans_thirty_two_sessions_codec_at_every_boundary(
         o.load_block(0, {k: v.cpu().numpy() for k, v in p.items()})
         del p
         gsp.append(g); osp.append(o)
+        say("C5 shape: span %d loaded on both sides" % b)
     try:
         gses = [[g.open_session(T + 1) for _ in range(B)] for g in gsp]
         oses = [[o.open_session(T + 1) for _ in range(B)] for o in osp]
 
         def oracle_stack(X):
-            for o, ss in zip(osp, oses):
+            for i, (o, ss) in enumerate(zip(osp, oses)):
                 q, am = oracle.hidden_quantize(X, CB)
                 X = o.step(ss, oracle.hidden_dequantize(q, am, CB).reshape(X.shape))
+                say("... oracle span %d done" % i)
             return X, oracle.hidden_quantize(X, CB)
 
         def gpu_stack(X, Tn):
@@ -984,13 +986,13 @@ def test_c5_shape_two_chained_spans_thirty_two_sessions_codec_at_every_boundary(
 
         for call, Tn in enumerate((T, 1)):
             X = synth.hidden_states(cfg, call, B, Tn)
-            print("C5 shape, call %d: %d x %d tokens, oracle ..." % (call, B, Tn), flush=True)
+            say("C5 shape, call %d: %d x %d tokens, oracle ..." % (call, B, Tn))
             Yo, (qo, amo) = oracle_stack(X)
-            print("... GPU", flush=True)
+            say("... GPU")
             Yg, qg, amg = gpu_stack(X, Tn)
             hidden_close(Yg, Yo, "C5 shape call %d" % call)
             same = Yg.view(np.uint16) == Yo.view(np.uint16)
-            print("bit-identical outputs: %.6f" % same.mean(), flush=True)
+            say("bit-identical outputs: %.6f" % same.mean())
             assert same.mean() > 0.9999, same.mean()
             if same.all():
                 assert np.array_equal(qg, qo.reshape(-1)) and np.array_equal(amg, amo)
