@@ -68,6 +68,12 @@ __device__ __forceinline__ double outlier_group(const v4i &w, uint32_t bits, con
 
 constexpr int GEMV_GROUP = 512;      // 8 waves share one 16-row panel at a time
 
+// Workgroup barrier of the row preparation: it orders the LDS traffic only.  (__syncthreads() would also wait for
+// every load from global memory in flight, i.e. for the weight chunks requested ahead.)
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // Persistent-style one-row linear.  The grid is sized so that every workgroup is resident at
 // once (up to two per compute unit) and owns a contiguous range of 16-row panels.  Each workgroup
 //  1. (LN variant) normalises the row in fp64,
@@ -79,7 +85,14 @@ constexpr int GEMV_GROUP = 512;      // 8 waves share one 16-row panel at a time
 //     load is 1 KB contiguous; v_dot4_i32_i8 accumulates exactly.
 // NG = 2: one workgroup of 16 waves per compute unit, two groups of 8 waves working on two panels at a
 // time - the row is then prepared once per compute unit instead of twice, by twice the threads.
-template <int U, int MAXCH, bool LN, int NG>
+// While the row is prepared (4 to 9 us: its loads, three workgroup-wide reductions, the quantization) nothing else
+// would keep HBM busy, so the waves request weights of their first panel ahead: one chunk into registers as soon
+// as the row has arrived, then one more chunk at each of up to three later points of the preparation - NPF of them
+// into a private LDS staging area (asynchronous copies), and, if NPF > 0, a last one into registers again.  One
+// chunk per wave at a time, because a compute unit keeps only about 64 KB of loads in flight (16 waves x 4 KB): a
+// wave that asks for more stalls at the request until earlier data has arrived, and the preparation would wait
+// with it (all chunks requested at once: the preparation takes 2.5 to 5 us longer, nothing gained).
+template <int U, int MAXCH, bool LN, int NG, int NPF>
 __global__ void __launch_bounds__(GEMV_GROUP * NG) k_gemv_row(LinearW w, RowIn in, OutDesc o,
                                                              const SessTable *__restrict__ sess, int panels_per_wg,
                                                              int panels_extra) {
@@ -102,22 +115,10 @@ __global__ void __launch_bounds__(GEMV_GROUP * NG) k_gemv_row(LinearW w, RowIn i
     const int p0 = g * panels_per_wg + min(g, panels_extra);
     const int nchunks = KT / U;
 
-    // start the first weight chunk now: HBM stays busy while the row is being quantized
-    v4i wv[U];
-    if (tw < nchunks && grp < np) {
-        const v4i *wp = (const v4i *)(w.wt + (size_t)(p0 + grp) * KT * 1024) + lane;
-#pragma unroll
-        for (int u = 0; u < U; u++) wv[u] = __builtin_nontemporal_load(wp + (size_t)(tw * U + u) * 64);
-    }
-
-    for (int i = threadIdx.x; i < K / 32; i += GEMV_THREADS) ((uint32_t *)m8)[i] = 0u;
-    double mean = 0.0, inv = 0.0;
+    // 1. the row (with LayerNorm also the gain and the bias): requested first, kept in registers
     v8h xr[LN ? MAXCH : 1], gr[LN ? MAXCH : 1], br[LN ? MAXCH : 1];
+    v4i vals[MAXCH];
     if (LN) {
-        // Both moments in one pass and one reduction.  The squares of fp16 values are exact in fp64 and the sums
-        // carry 1e-16 of relative error, so the variance as "mean of squares minus squared mean" is as good as
-        // the two-pass form unless the mean dwarfs the spread by a factor of 1e6, which a hidden state never does.
-        // the row, the gain and the bias are requested together and stay in registers
 #pragma unroll
         for (int i = 0; i < MAXCH; i++) {
             const int c = threadIdx.x + GEMV_THREADS * i;
@@ -138,6 +139,58 @@ __global__ void __launch_bounds__(GEMV_GROUP * NG) k_gemv_row(LinearW w, RowIn i
                 br[i] = *(const v8h *)(in.ln_b + c * 8);
             }
         }
+    } else {
+#pragma unroll
+        for (int i = 0; i < MAXCH; i++) {
+            const int c = threadIdx.x + GEMV_THREADS * i;
+            if (c < nch8) vals[i] = *(const v4i *)(in.x + c * 8);
+        }
+    }
+    // A compute unit keeps only about 64 KB of loads in flight (16 waves x 4 KB; a wave that asks for more stalls at
+    // the request until earlier data has arrived), and it serves its waves' requests in order.  So: wait until the
+    // row has ARRIVED, request one chunk of weights per wave into registers - that alone fills the unit's share -
+    // and request the next chunks (into this wave's private LDS staging area, with asynchronous copies) one at a
+    // time at later points of the row preparation, when the chunk before has landed.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+    v4i wv[U];
+    // (an LDS object of its own: the compiler then knows that the prologue's other LDS traffic cannot touch it and
+    // does not wait for the copies in front of every LDS access)
+    __shared__ __align__(16) unsigned char stage_buf[NPF > 0 ? 8 * NG * NPF * U * 1024 : 16];
+    unsigned char *stage = stage_buf + (size_t)wave * NPF * (U * 1024);
+    const int8_t *panel0 = w.wt + (size_t)(p0 + min(grp, np - 1)) * KT * 1024;
+    {
+        const v4i *wp = (const v4i *)panel0 + lane;
+#pragma unroll
+        for (int u = 0; u < U; u++) wv[u] = __builtin_nontemporal_load(wp + (size_t)(min(tw, nchunks - 1) * U + u) * 64);
+    }
+    // buffer form of the copy (descriptor = this wave's first panel, bounds-checked by the hardware): the flat form
+    // makes the compiler wait for ALL loads at the next wait of any kind
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)panel0, 0, KT * 1024, 0x00020000);
+    // Request point k = 1, 2, 3 (in program order) asks for chunk tw + 8 k of the first panel: into staging slot
+    // k - 1 while k <= NPF, into the second register set at k = NPF + 1; the host chooses NPF so that the chunks exist.
+    v4i wv2[NPF > 0 ? U : 1];
+    auto request_point = [&](auto kc) {
+        constexpr int k = decltype(kc)::value;
+        if constexpr (NPF > 0 && k <= NPF) {
+#pragma unroll
+            for (int u = 0; u < U; u++)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void *)(stage + (size_t)((k - 1) * U + u) * 1024),
+                                                         16, lane * 16, ((tw + 8 * k) * U + u) * 1024, 0, 2 /* non-temporal */);
+        } else if constexpr (NPF > 0 && k == NPF + 1) {
+            const v4i *wp = (const v4i *)panel0 + lane;
+#pragma unroll
+            for (int u = 0; u < U; u++) wv2[u] = __builtin_nontemporal_load(wp + (size_t)((tw + 8 * k) * U + u) * 64);
+        }
+    };
+    __builtin_amdgcn_sched_barrier(0);
+
+    for (int i = threadIdx.x; i < K / 32; i += GEMV_THREADS) ((uint32_t *)m8)[i] = 0u;
+    double mean = 0.0, inv = 0.0;
+    if (LN) {
+        // Both moments in one pass and one reduction.  The squares of fp16 values are exact in fp64 and the sums
+        // carry 1e-16 of relative error, so the variance as "mean of squares minus squared mean" is as good as
+        // the two-pass form unless the mean dwarfs the spread by a factor of 1e6, which a hidden state never does.
         double s = 0.0, q = 0.0;
 #pragma unroll
         for (int i = 0; i < MAXCH; i++) {
@@ -149,18 +202,18 @@ __global__ void __launch_bounds__(GEMV_GROUP * NG) k_gemv_row(LinearW w, RowIn i
         s = wave_sum(s);
         q = wave_sum(q);
         if (lane == 0) { smd[wave] = s; smq[wave] = q; }
-        __syncthreads();
+        lds_barrier();
+        request_point(std::integral_constant<int, 1>());   // (the first chunk has landed by now)
         s = q = 0.0;
 #pragma unroll
         for (int i = 0; i < NWV; i++) { s += smd[i]; q += smq[i]; }
         mean = s / (double)K;
         inv = 1.0 / sqrt(fmax(q / (double)K - mean * mean, 0.0) + (double)in.eps);
     } else {
-        __syncthreads();      // mask bytes cleared before anybody sets one
+        lds_barrier();        // mask bytes cleared before anybody sets one
     }
 
     // detect + absolute maximum over regular columns, 8 columns per register quad
-    v4i vals[MAXCH];
     uint32_t mreg = 0;
 #pragma unroll
     for (int i = 0; i < MAXCH; i++) {
@@ -174,8 +227,6 @@ __global__ void __launch_bounds__(GEMV_GROUP * NG) k_gemv_row(LinearW w, RowIn i
                     out[e] = d2h_rn(((double)(float)v[e] - mean) * inv * (double)(float)gg[e] + (double)(float)bb[e]);
                 vals[i] = *(const v4i *)out;
                 if (first && in.a_out) *(v4i *)(in.a_out + c * 8) = vals[i];
-            } else {
-                vals[i] = *(const v4i *)(in.x + c * 8);
             }
             const uint32_t a0 = vals[i][0] & 0x7fff7fffu, a1 = vals[i][1] & 0x7fff7fffu;
             const uint32_t a2 = vals[i][2] & 0x7fff7fffu, a3 = vals[i][3] & 0x7fff7fffu;
@@ -193,11 +244,13 @@ __global__ void __launch_bounds__(GEMV_GROUP * NG) k_gemv_row(LinearW w, RowIn i
                 mreg = max(mreg, cmax);
             }
         }
+        if (LN && i == (MAXCH - 1) / 2) request_point(std::integral_constant<int, 2>());   // halfway through the arithmetic
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) mreg = max(mreg, (uint32_t)__shfl_xor((int)mreg, off));
     if (lane == 0) smi[wave] = (int)mreg;
-    __syncthreads();
+    lds_barrier();
+    request_point(std::integral_constant<int, LN ? 3 : 1>());
 #pragma unroll
     for (int i = 0; i < NWV; i++) mreg = max(mreg, (uint32_t)smi[i]);
     const unsigned short sb = (unsigned short)mreg;
@@ -217,8 +270,9 @@ __global__ void __launch_bounds__(GEMV_GROUP * NG) k_gemv_row(LinearW w, RowIn i
             v2i o2 = {pack4(q[0], q[1], q[2], q[3]), pack4(q[4], q[5], q[6], q[7])};
             *(v2i *)(xs + c * 8) = o2;
         }
+        if (!LN && i == (MAXCH - 1) / 2) request_point(std::integral_constant<int, 2>());  // halfway through the quantization
     }
-    __syncthreads();
+    lds_barrier();
     if (first) {
         if (in.sx_out && threadIdx.x == 0) *in.sx_out = s_x;
         if (in.xq_out) for (int i = threadIdx.x; i < K / 16; i += GEMV_THREADS) ((v4i *)in.xq_out)[i] = ((const v4i *)xs)[i];
@@ -234,10 +288,22 @@ __global__ void __launch_bounds__(GEMV_GROUP * NG) k_gemv_row(LinearW w, RowIn i
         int acc = 0;
         double outl = 0.0;
         if (active) {
-            for (int c = tw; c < nchunks; c += 8) {
-                if (it > 0 || c > tw) {                // the very first chunk was loaded before the prologue
+            for (int c = tw, j = 0; c < nchunks; c += 8, j++) {
+                // the first panel's first chunks were requested during the row preparation: registers, staging area, registers
+                // chunks requested ahead besides the first: the staged ones, then the second register set
+                constexpr int NPOINTS = LN ? 3 : 2, NSTAGED = NPF < NPOINTS ? NPF : NPOINTS;
+                constexpr bool REG2 = NPF > 0 && NPF + 1 <= NPOINTS;
+                constexpr int NAHEAD = NSTAGED + (REG2 ? 1 : 0);
+                if (it > 0 || j > NAHEAD) {
 #pragma unroll
                     for (int u = 0; u < U; u++) wv[u] = __builtin_nontemporal_load(wp + (size_t)(c * U + u) * 64);
+                } else if (REG2 && j == NAHEAD) {
+#pragma unroll
+                    for (int u = 0; u < U; u++) wv[u] = wv2[u];
+                } else if (j > 0) {
+                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's own copies have landed
+#pragma unroll
+                    for (int u = 0; u < U; u++) wv[u] = *(const v4i *)(stage + (size_t)((j - 1) * U + u) * 1024 + lane * 16);
                 }
 #pragma unroll
                 for (int u = 0; u < U; u++) {
@@ -280,9 +346,36 @@ __global__ void __launch_bounds__(GEMV_GROUP * NG) k_gemv_row(LinearW w, RowIn i
     }
 }
 
+template <int U, int MAXCH, int NG, int NPF>
+hipError_t launch4(bool ln, const LinearW &w, const RowIn &in, const OutDesc &o, const SessTable *sess, int G, int per,
+                   int extra, size_t base, size_t lds, size_t budget, hipStream_t st) {
+    auto kern = ln ? k_gemv_row<U, MAXCH, true, NG, NPF> : k_gemv_row<U, MAXCH, false, NG, NPF>;
+    if (base > 64 * 1024) {
+        static std::mutex attr_lock;
+        static bool attr_set[2] = {false, false};
+        std::lock_guard<std::mutex> hold(attr_lock);
+        if (!attr_set[ln]) {
+            hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(budget - (lds - base)));
+            if (e != hipSuccess) return e;
+            attr_set[ln] = true;
+        }
+    }
+    kern<<<G, GEMV_GROUP * NG, base, st>>>(w, in, o, sess, per, extra);
+    return hipGetLastError();
+}
+
 template <int U, int MAXCH, int NG>
 hipError_t launch3(bool ln, const LinearW &w, const RowIn &in, const OutDesc &o, const SessTable *sess, hipStream_t st) {
-    const size_t lds = (size_t)w.K + w.K / 8 + 256 * 12 * NG;
+    const size_t base = ((size_t)w.K + w.K / 8 + 256 * 12 * NG + 15) & ~(size_t)15;
+    // staging for the weight chunks requested before the row is prepared: up to two chunks per wave, as far as every
+    // wave has such chunks in its first panel and the compute unit's 160 KB of LDS allow (one 16-wave workgroup
+    // per unit, or two of 8 waves)
+    const size_t budget = (NG == 2 ? 160 : 80) * 1024 - 1024, per_chunk = (size_t)8 * NG * U * 1024;
+    const int nchunks = w.K / 64 / U;
+    int npf = base + per_chunk <= budget ? (int)min((size_t)2, (budget - base) / per_chunk) : 0;
+    if (!ln) npf = min(npf, 1);                         // without LayerNorm there are two request points, with it three
+    npf = max(0, min(npf, nchunks / 8 - 2));            // every wave's chunks tw + 8 k, k <= npf + 1, must exist
+    const size_t lds = base + npf * per_chunk;
     // one resident round: at most 1024 threads' worth of workgroups per compute unit twice over (512 groups of
     // 8 waves); prefer a split of the panels without remainder
     const int panels = w.N / 16, units = panels / NG, max_wg = 512 / NG;
@@ -290,20 +383,10 @@ hipError_t launch3(bool ln, const LinearW &w, const RowIn &in, const OutDesc &o,
     for (int cand = G; cand >= max(1, (G * 3) / 4); cand--)
         if (units % cand == 0) { G = cand; break; }
     const int per = panels / G, extra = panels % G;
-    auto kern = ln ? k_gemv_row<U, MAXCH, true, NG> : k_gemv_row<U, MAXCH, false, NG>;
-    if (lds > 96 * 1024) return hipErrorInvalidValue;   // K <= 65536: at most 86 KB
-    if (lds > 64 * 1024) {
-        static std::mutex attr_lock;
-        static bool attr_set[2] = {false, false};
-        std::lock_guard<std::mutex> hold(attr_lock);
-        if (!attr_set[ln]) {
-            hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
-            if (e != hipSuccess) return e;
-            attr_set[ln] = true;
-        }
-    }
-    kern<<<G, GEMV_GROUP * NG, lds, st>>>(w, in, o, sess, per, extra);
-    return hipGetLastError();
+    if (lds > budget) return hipErrorInvalidValue;      // K <= 65536 (base at most 86 KB) always fits
+    if (npf == 2) return launch4<U, MAXCH, NG, 2>(ln, w, in, o, sess, G, per, extra, base, lds, budget, st);
+    if (npf == 1) return launch4<U, MAXCH, NG, 1>(ln, w, in, o, sess, G, per, extra, base, lds, budget, st);
+    return launch4<U, MAXCH, NG, 0>(ln, w, in, o, sess, G, per, extra, base, lds, budget, st);
 }
 
 template <int U, int MAXCH>
