@@ -89,9 +89,9 @@ __device__ __forceinline__ void lds_barrier() {
 // would keep HBM busy, so the waves request weights of their first panel ahead: one chunk into registers as soon
 // as the row has arrived, then one more chunk at each of up to three later points of the preparation - NPF of them
 // into a private LDS staging area (asynchronous copies), and, if NPF > 0, a last one into registers again.  One
-// chunk per wave at a time, because a compute unit keeps only about 64 KB of loads in flight (16 waves x 4 KB): a
-// wave that asks for more stalls at the request until earlier data has arrived, and the preparation would wait
-// with it (all chunks requested at once: the preparation takes 2.5 to 5 us longer, nothing gained).
+// chunk per wave at a time: HBM delivers 16 waves x 4 KB per compute unit in about 2 us, and a wave that asks for
+// more than the memory pipeline takes on stalls at the request until earlier data has arrived - the preparation
+// then waits with it (all chunks requested at once: the preparation takes 2.5 to 5 us longer, nothing gained).
 template <int U, int MAXCH, bool LN, int NG, int NPF>
 __global__ void __launch_bounds__(GEMV_GROUP * NG) k_gemv_row(LinearW w, RowIn in, OutDesc o,
                                                              const SessTable *__restrict__ sess, int panels_per_wg,
@@ -146,11 +146,10 @@ __global__ void __launch_bounds__(GEMV_GROUP * NG) k_gemv_row(LinearW w, RowIn i
             if (c < nch8) vals[i] = *(const v4i *)(in.x + c * 8);
         }
     }
-    // A compute unit keeps only about 64 KB of loads in flight (16 waves x 4 KB; a wave that asks for more stalls at
-    // the request until earlier data has arrived), and it serves its waves' requests in order.  So: wait until the
-    // row has ARRIVED, request one chunk of weights per wave into registers - that alone fills the unit's share -
-    // and request the next chunks (into this wave's private LDS staging area, with asynchronous copies) one at a
-    // time at later points of the row preparation, when the chunk before has landed.
+    // A compute unit serves its waves' requests in order and takes on only so many ahead of the data (a wave that
+    // asks for more stalls at the request).  So: wait until the row has ARRIVED, request one chunk of weights per
+    // wave into registers, and request the next chunks one at a time at later points of the row preparation, when
+    // the chunk before has landed.
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);
     v4i wv[U];
