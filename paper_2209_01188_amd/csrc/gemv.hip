@@ -260,13 +260,26 @@ __global__ void __launch_bounds__(GEMV_GROUP * NG) k_gemv_row(LinearW w, RowIn i
         const int c = threadIdx.x + GEMV_THREADS * i;
         if (c < nch8) {
             const uint32_t byte = m8[c];          // set above by this same thread (0 from the initial clear)
+            // all 8 codes first, straight-line; the codes of outlier columns are then cleared byte by byte in the
+            // packed words (a test per element compiles to a branch per element, and a chunk with outlier
+            // columns is rare)
             int q[8];
 #pragma unroll
             for (int e = 0; e < 8; e++) {
                 const unsigned short hb = (unsigned short)((uint32_t)vals[i][e >> 1] >> ((e & 1) * 16));
-                q[e] = ((byte >> e) & 1u) ? 0 : q8(__half2float(*(const __half *)&hb), r);
+                q[e] = q8(__half2float(*(const __half *)&hb), r);
             }
             v2i o2 = {pack4(q[0], q[1], q[2], q[3]), pack4(q[4], q[5], q[6], q[7])};
+            if (byte) {
+                uint32_t keep0 = 0xffffffffu, keep1 = 0xffffffffu;
+#pragma unroll
+                for (int e = 0; e < 4; e++) {
+                    keep0 &= ~(((byte >> e) & 1u) * (0xffu << (8 * e)));
+                    keep1 &= ~(((byte >> (4 + e)) & 1u) * (0xffu << (8 * e)));
+                }
+                o2[0] &= (int)keep0;
+                o2[1] &= (int)keep1;
+            }
             *(v2i *)(xs + c * 8) = o2;
         }
         if (!LN && i == (MAXCH - 1) / 2) request_point(std::integral_constant<int, 2>());  // halfway through the quantization
