@@ -494,6 +494,36 @@ def _c4_block_pair(theta=6.0, rows=1, n_blocks=1):
     return cfg, osp, gsp, host      # host: the parameters of the last block
 
 
+@pytest.mark.parametrize("hidden,n_heads,ffn", [(16384, 128, 4096), (8192, 64, 32768), (8192, 64, 2048)])
+def test_one_row_decode_at_widths_that_take_the_other_request_ahead_forms(hidden, n_heads, ffn):
+    """The one-row linear requests weights ahead while it prepares the row: how many chunks go through its LDS
+    staging area depends on the row length and on the workgroup shape.  Widths chosen so that the forms the named
+    configurations do not reach run too - one or two staged chunks behind a LayerNorm in 8-wave workgroups (matrices
+    with few output rows), a 32768-column row without LayerNorm.  One block, batch
+    1, two decode steps on a short cache; every output against the oracle."""
+    cfg = synth.scaled(synth.CONFIGS["C4"], name="wide-%d" % hidden, n_blocks=1, hidden=hidden, n_heads=n_heads, ffn=ffn)
+    gsp = binding.Span(1, hidden, n_heads, ffn, 1, 1e-5, 6.0, DEV)
+    osp = oracle.Span(1, hidden, n_heads, ffn, 1e-5, 6.0)
+    p = synth.block_params_device(cfg, 0, DEV)
+    gsp.load_block(0, p)
+    osp.load_block(0, {k: v.cpu().numpy() for k, v in p.items()})
+    del p
+    try:
+        L = 70
+        kv = synth.kv_prefix_device(cfg, 0, 0, L, 2.4, DEV)
+        ose, gse = osp.open_session(L + 3), gsp.open_session(L + 3)
+        ose.import_kv(0, kv.cpu().numpy()); gse.import_kv(0, kv)
+        for i in (1, 2):
+            x = synth.hidden_states(cfg, i, 1, 1)
+            yo = osp.step([ose], x)
+            yg = to_np(gsp.decode_step([gse], to_dev(x[:, 0])))[:, None]
+            hidden_close(yg, yo, "width %d step %d" % (hidden, i))
+            assert (yg.view(np.uint16) == yo.view(np.uint16)).mean() > 0.999
+        hidden_close(to_np(gse.export_kv(0))[:, :, L:], ose.export_kv(0)[:, :, L:], "appended kv")
+    finally:
+        gsp.close(); osp.destroy()
+
+
 def test_c4_full_size_block_decode_at_the_benchmark_prefixes():
     """The benchmark's launch configuration (batch 1, H = 14336, F = 57344) on one block, every output checked."""
     cfg, osp, gsp, host = _c4_block_pair()
