@@ -97,6 +97,19 @@ def test_host_side_checks_need_no_device(b):
     assert L.petals_hidden_quantize(fake, C.c_size_t(10), 100, fake, fake, None) == -1        # block % 64
 
 
+def test_measurement_aids_reject_bad_arguments_before_any_launch(b):
+    L = b.lib()
+    fake = C.c_void_p(0x10000)
+    ops = C.c_double()
+    assert L.petals_bench_mfma(2, 0, 10, 4, fake, C.byref(ops), None) == -1                  # kind
+    assert L.petals_bench_mfma(0, 0, 0, 4, fake, C.byref(ops), None) == -1                   # iterations
+    assert L.petals_bench_stage(0, 8, 1, 4, fake, C.c_size_t(1 << 20), fake, None) == -1     # no piece selected
+    assert L.petals_bench_stage(7, 3, 1, 4, fake, C.c_size_t(1 << 20), fake, None) == -1     # fewer stages than ring slots
+    assert L.petals_bench_stage(7, 8, 1, 4, None, C.c_size_t(1 << 20), fake, None) == -1     # null source
+    assert L.petals_bench_stage(7, 8, 5, 4, fake, C.c_size_t(1 << 20), fake, None) == -2     # 5 regions x 8 stages x 32 KiB > 1 MiB
+    assert b"32 KiB" in L.petals_last_error()
+
+
 def test_code_table_bits_equal_the_oracle_table(b):
     import numpy as np
     import oracle
